@@ -1,0 +1,129 @@
+/*
+ * ks.h — C ABI of the MI355X (gfx950) CKKS hybrid key-switching library.
+ *
+ * The operations are the ones the paper builds its encrypted-inference kernels from
+ * (Background: "RNS and Limbs", "NTT", "Evaluation Keys"; Motivation: hoisting; Kernel Code
+ * Generation: the NTT, Base Conversion and Elementwise kernel classes).  The paper gives no
+ * formulas; the arithmetic follows the textbook algorithms it cites and is stated with each entry
+ * point below.
+ *
+ * General conventions
+ * -------------------
+ *  - Ring: Z[X]/(X^N + 1), N = 2^logN.  RNS basis: ciphertext primes q_0..q_{L-1} followed by special
+ *    primes p_0..p_{K-1}; "modulus id" m in [0, L+K) indexes that concatenated list.  Every modulus is
+ *    an odd prime below 2^36 with m = 1 (mod 2N).
+ *  - A limb is N residues in 64-bit words, N contiguous.  All residues handed to the library must be
+ *    canonical (in [0, modulus)); every output is canonical.
+ *  - Evaluation domain order is bit-reversed: slot k of a limb holds a(psi^(2*brv(k)+1)), brv = bit
+ *    reversal on logN bits, psi = the primitive 2N-th root of unity of that modulus.
+ *  - Digits for hybrid key-switching are contiguous groups of alpha = ceil(L/dnum) ciphertext limbs;
+ *    at level ell <= L the digits cover limbs 0..ell-1 and the last one may be short.
+ *  - All data pointers ("device" below) are GPU global memory owned by the caller, 16-byte aligned.
+ *    Inputs are never modified; outputs must not overlap inputs unless a call says "in place".
+ *    Pointers marked "host" are ordinary host memory read before the call returns.
+ *  - Every compute call is asynchronous on the given HIP stream (`stream` is a hipStream_t passed as
+ *    void*; NULL = default stream), performs no device-wide synchronisation and allocates no device
+ *    memory (ks_ctx_create and the first bconv call with a new pair of id lists are the exceptions).
+ *  - Return value: KS_OK (0) or a negative KS_E* code; ks_strerror() describes it.  On error nothing
+ *    has been launched.
+ */
+#ifndef KS_MI355X_H
+#define KS_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ks_ctx ks_ctx; /* opaque; owns only device tables (twiddles, conversion constants) */
+
+enum {
+    KS_OK = 0,
+    KS_EINVAL = -1,     /* bad argument: null / misaligned pointer, unsupported size, bad modulus ... */
+    KS_EWORKSPACE = -2, /* workspace pointer null or ws_bytes too small                               */
+    KS_EHIP = -3,       /* a HIP runtime call failed; see ks_last_hip_error()                          */
+    KS_ENOMEM = -4      /* host or device allocation failed while building a context                   */
+};
+
+enum { /* operations for ks_workspace_bytes */
+    KS_OP_KEYSWITCH = 1,
+    KS_OP_ROTATE_HOISTED = 2,
+    KS_OP_HMULT_RELIN_RESCALE = 3
+};
+
+/* Build the tables for one parameter set on GPU `device`.
+ *   logN  : 12 or 16 (ring degree 4096 or 65536).
+ *   q [L] : host, ciphertext primes.   p [K] : host, special primes (NULL iff K == 0).
+ *   psi   : host [L+K] primitive 2N-th roots, or NULL = the smallest positive one for each modulus.
+ *   dnum  : number of digits at full level (1 <= dnum <= L); dnum is ignored by the transform and
+ *           base-conversion primitives.
+ * Fails with KS_EINVAL if a modulus is not a prime < 2^36 with m = 1 (mod 2N), moduli repeat, a psi is
+ * not a primitive 2N-th root, L + K > 255, alpha > 16 or K > 16.  The context is immutable afterwards and
+ * may be used from several host threads. */
+int ks_ctx_create(ks_ctx** out, uint32_t logN, uint32_t L, uint32_t K, uint32_t dnum,
+                  const uint64_t* q, const uint64_t* p, const uint64_t* psi, int device);
+int ks_ctx_destroy(ks_ctx* ctx);
+
+/* Bytes of device workspace the given operation needs for `batch` ciphertexts at level `ell`
+ * (n_rot is only read for KS_OP_ROTATE_HOISTED).  Returns 0 for invalid arguments.  Large batches are
+ * processed in internal chunks, so the result stops growing beyond a chunk. */
+size_t ks_workspace_bytes(const ks_ctx* ctx, int op, uint32_t ell, uint32_t batch, uint32_t n_rot);
+
+const char* ks_strerror(int code);
+const char* ks_last_hip_error(void); /* text of the last HIP error seen by the calling thread */
+
+/* Negacyclic number-theoretic transform (Background, "NTT"), in place.
+ *   data    : device [batch][nlimbs][N].
+ *   mod_ids : host [nlimbs], modulus id of each limb (the same for every batch item), nlimbs <= 192.
+ * ntt_fwd: coefficient order in, bit-reversed evaluation order out:
+ *          out[k] = sum_i a_i psi^((2 brv(k) + 1) i) mod m.   ntt_inv is its exact inverse. */
+int ntt_fwd(const ks_ctx* ctx, uint64_t* data, const uint32_t* mod_ids, uint32_t nlimbs, uint32_t batch, void* stream);
+int ntt_inv(const ks_ctx* ctx, uint64_t* data, const uint32_t* mod_ids, uint32_t nlimbs, uint32_t batch, void* stream);
+
+/* Fast RNS base conversion (Kernel Code Generation, "Base Conversion" kernel class), coefficient-wise:
+ *   y_i = [x_i (D/s_i)^-1]_{s_i},   out_t = (sum_i y_i (D/s_i)) mod t,   D = product of the source moduli,
+ * i.e. the value x + u D (0 <= u < n_src) reduced modulo every target t; no correction of u.
+ *   in  : device [batch][n_src][N], limb i modulo src_ids[i] (host, n_src <= 16, distinct).
+ *   out : device [batch][n_dst][N], limb t modulo dst_ids[t] (host, n_dst <= 255).
+ * The first call with a new (src_ids, dst_ids) pair builds and caches its constant table in the context
+ * (one small device allocation and a synchronous copy); later calls with that pair allocate nothing. */
+int bconv(const ks_ctx* ctx, const uint64_t* in, const uint32_t* src_ids, uint32_t n_src,
+          uint64_t* out, const uint32_t* dst_ids, uint32_t n_dst, uint32_t batch, void* stream);
+
+/* Hybrid key-switching of one polynomial per batch item (Background, "Evaluation Keys"):
+ *   INTT -> per-digit base conversion to all other moduli -> NTT -> inner product with the key over the
+ *   digits -> INTT of the special limbs -> base conversion P -> q -> NTT -> (acc - conv) P^-1.
+ *   d   : device [batch][ell][N], evaluation domain, limb i modulo q_i.
+ *   evk : device [dnum][2][L+K][N], evaluation domain; component 0 pairs with out component 0.  The
+ *         gadget factor is part of the key; only limbs q_0..q_{ell-1} and p_* of it are read.
+ *   out : device [batch][2][ell][N], evaluation domain.
+ *   ws  : device workspace of at least ks_workspace_bytes(ctx, KS_OP_KEYSWITCH, ell, batch, 0) bytes;
+ *         contents undefined afterwards.  1 <= ell <= L. */
+int ks_keyswitch(const ks_ctx* ctx, const uint64_t* d, uint32_t ell, const uint64_t* evk, uint64_t* out,
+                 uint32_t batch, void* ws, size_t ws_bytes, void* stream);
+
+/* Hoisted rotations (Motivation: hoisting): for every ciphertext the decompose-and-raise of c1 is done once
+ * and shared by all n_rot Galois elements.  For each g: sigma_g (X -> X^g) is applied to the raised digits,
+ * then inner product with that rotation's key, division by P, and sigma_g(c0) is added to component 0.
+ *   ct       : device [batch][2][ell][N] (component 0 = c0, 1 = c1), evaluation domain.
+ *   galois   : host [n_rot], odd, 0 < g < 2N.
+ *   rot_keys : host array [n_rot] of device pointers, each laid out like evk above.
+ *   out      : device [batch][n_rot][2][ell][N]. */
+int ks_rotate_hoisted(const ks_ctx* ctx, const uint64_t* ct, uint32_t ell, const uint32_t* galois,
+                      const uint64_t* const* rot_keys, uint32_t n_rot, uint64_t* out, uint32_t batch,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/* Homomorphic multiplication with relinearisation and rescale: tensor product
+ * (d0, d1, d2) = (b1 b2, a1 b2 + a2 b1, a1 a2), key-switch d2 with rlk, add to (d0, d1), then drop limb
+ * q_{ell-1} from both components with rounding to nearest (subtract the centred remainder, divide).
+ *   cta, ctb : device [batch][2][ell][N] (component 0 = b, 1 = a), evaluation domain.  2 <= ell <= L.
+ *   rlk      : device, laid out like evk.      out : device [batch][2][ell-1][N]. */
+int hmult_relin_rescale(const ks_ctx* ctx, const uint64_t* cta, const uint64_t* ctb, uint32_t ell,
+                        const uint64_t* rlk, uint64_t* out, uint32_t batch, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KS_MI355X_H */

@@ -1,0 +1,18 @@
+"""MI355X-native CKKS hybrid key-switching: thin Python binding over the C-ABI library."""
+
+from .binding import (  # noqa: F401
+    KS_OP_HMULT_RELIN_RESCALE,
+    KS_OP_KEYSWITCH,
+    KS_OP_ROTATE_HOISTED,
+    Context,
+    KsError,
+    bconv,
+    hmult_relin_rescale,
+    ks_keyswitch,
+    ks_rotate_hoisted,
+    ks_workspace_bytes,
+    library_path,
+    load_library,
+    ntt_fwd,
+    ntt_inv,
+)

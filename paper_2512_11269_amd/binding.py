@@ -1,0 +1,158 @@
+"""ctypes binding of libks_mi355x.so: argument marshalling only.
+
+Functions carry the names of the C entry points (see include/ks.h) and take torch int64 CUDA tensors
+laid out exactly as the header documents; torch provides device memory and the current HIP stream and
+nothing else.  There is no fallback: if the shared object is missing or a call fails, an exception is
+raised.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libks_mi355x.so")
+_lib = None
+
+KS_OP_KEYSWITCH, KS_OP_ROTATE_HOISTED, KS_OP_HMULT_RELIN_RESCALE = 1, 2, 3
+
+_u64p = ctypes.POINTER(ctypes.c_uint64)
+_u32p = ctypes.POINTER(ctypes.c_uint32)
+_vp = ctypes.c_void_p
+
+
+class KsError(RuntimeError):
+    pass
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load the built shared object (building it first only if none exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(_LIB_PATH)
+    lib.ks_ctx_create.argtypes = [ctypes.POINTER(_vp), ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32,
+                                  _u64p, _u64p, _u64p, ctypes.c_int]
+    lib.ks_ctx_destroy.argtypes = [_vp]
+    lib.ks_workspace_bytes.restype = ctypes.c_size_t
+    lib.ks_workspace_bytes.argtypes = [_vp, ctypes.c_int, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32]
+    lib.ks_strerror.restype = ctypes.c_char_p
+    lib.ks_strerror.argtypes = [ctypes.c_int]
+    lib.ks_last_hip_error.restype = ctypes.c_char_p
+    lib.ntt_fwd.argtypes = [_vp, _vp, _u32p, ctypes.c_uint32, ctypes.c_uint32, _vp]
+    lib.ntt_inv.argtypes = [_vp, _vp, _u32p, ctypes.c_uint32, ctypes.c_uint32, _vp]
+    lib.bconv.argtypes = [_vp, _vp, _u32p, ctypes.c_uint32, _vp, _u32p, ctypes.c_uint32, ctypes.c_uint32, _vp]
+    lib.ks_keyswitch.argtypes = [_vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
+    lib.ks_rotate_hoisted.argtypes = [_vp, _vp, ctypes.c_uint32, _u32p, ctypes.POINTER(_vp), ctypes.c_uint32, _vp,
+                                      ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
+    lib.hmult_relin_rescale.argtypes = [_vp, _vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        lib = load_library()
+        msg = lib.ks_strerror(rc).decode()
+        if rc == -3:
+            msg += ": " + lib.ks_last_hip_error().decode()
+        raise KsError(f"{what} failed ({rc}): {msg}")
+
+
+def _u64_array(values):
+    return (ctypes.c_uint64 * len(values))(*[int(v) for v in values])
+
+
+def _u32_array(values):
+    return (ctypes.c_uint32 * len(values))(*[int(v) for v in values])
+
+
+def _dev_ptr(t: torch.Tensor) -> int:
+    if not (t.is_cuda and t.dtype == torch.int64 and t.is_contiguous()):
+        raise KsError("expected a contiguous int64 CUDA tensor")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+class Context:
+    """Owns a ks_ctx handle (device tables for one parameter set)."""
+
+    def __init__(self, logN: int, q, p, dnum: int, psi=None, device: int = 0):
+        lib = load_library()
+        self.logN, self.N = logN, 1 << logN
+        self.q, self.p = [int(x) for x in q], [int(x) for x in p]
+        self.L, self.K, self.dnum = len(self.q), len(self.p), dnum
+        self.device = device
+        h = _vp()
+        qa = _u64_array(self.q)
+        pa = _u64_array(self.p) if self.K else None
+        sa = _u64_array(psi) if psi is not None else None
+        _check(lib.ks_ctx_create(ctypes.byref(h), logN, self.L, self.K, dnum, qa, pa, sa, device), "ks_ctx_create")
+        self.handle = h
+
+    def close(self):
+        if getattr(self, "handle", None):
+            load_library().ks_ctx_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def ks_workspace_bytes(ctx: Context, op: int, ell: int, batch: int, n_rot: int = 0) -> int:
+    return int(load_library().ks_workspace_bytes(ctx.handle, op, ell, batch, n_rot))
+
+
+def ntt_fwd(ctx: Context, data: torch.Tensor, mod_ids) -> None:
+    """In place on data [batch][nlimbs][N]."""
+    nl = len(mod_ids)
+    batch = data.numel() // (nl * ctx.N)
+    _check(load_library().ntt_fwd(ctx.handle, _dev_ptr(data), _u32_array(mod_ids), nl, batch, _stream()), "ntt_fwd")
+
+
+def ntt_inv(ctx: Context, data: torch.Tensor, mod_ids) -> None:
+    nl = len(mod_ids)
+    batch = data.numel() // (nl * ctx.N)
+    _check(load_library().ntt_inv(ctx.handle, _dev_ptr(data), _u32_array(mod_ids), nl, batch, _stream()), "ntt_inv")
+
+
+def bconv(ctx: Context, x: torch.Tensor, src_ids, out: torch.Tensor, dst_ids) -> None:
+    batch = x.numel() // (len(src_ids) * ctx.N)
+    _check(load_library().bconv(ctx.handle, _dev_ptr(x), _u32_array(src_ids), len(src_ids), _dev_ptr(out),
+                                _u32_array(dst_ids), len(dst_ids), batch, _stream()), "bconv")
+
+
+def ks_keyswitch(ctx: Context, d: torch.Tensor, ell: int, evk: torch.Tensor, out: torch.Tensor, ws: torch.Tensor) -> None:
+    batch = d.numel() // (ell * ctx.N)
+    _check(load_library().ks_keyswitch(ctx.handle, _dev_ptr(d), ell, _dev_ptr(evk), _dev_ptr(out), batch, _dev_ptr(ws),
+                                       ws.numel() * 8, _stream()), "ks_keyswitch")
+
+
+def ks_rotate_hoisted(ctx: Context, ct: torch.Tensor, ell: int, galois, rot_keys, out: torch.Tensor, ws: torch.Tensor) -> None:
+    batch = ct.numel() // (2 * ell * ctx.N)
+    ptrs = (_vp * len(rot_keys))(*[_dev_ptr(k) for k in rot_keys])
+    _check(load_library().ks_rotate_hoisted(ctx.handle, _dev_ptr(ct), ell, _u32_array(galois), ptrs, len(rot_keys),
+                                            _dev_ptr(out), batch, _dev_ptr(ws), ws.numel() * 8, _stream()), "ks_rotate_hoisted")
+
+
+def hmult_relin_rescale(ctx: Context, cta: torch.Tensor, ctb: torch.Tensor, ell: int, rlk: torch.Tensor, out: torch.Tensor,
+                        ws: torch.Tensor) -> None:
+    batch = cta.numel() // (2 * ell * ctx.N)
+    _check(load_library().hmult_relin_rescale(ctx.handle, _dev_ptr(cta), _dev_ptr(ctb), ell, _dev_ptr(rlk), _dev_ptr(out),
+                                              batch, _dev_ptr(ws), ws.numel() * 8, _stream()), "hmult_relin_rescale")

@@ -1,0 +1,267 @@
+// The extern "C" entry points: argument checks, workspace carving and the kernel chains.
+#include <algorithm>
+
+#include "ks_internal.hpp"
+
+using namespace ks;
+
+namespace {
+
+constexpr uint32_t kChunk = 16;  // ciphertexts processed per pass of a pipeline; bounds the workspace
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int finish(const char* where) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_hip_error(e, where);
+        return KS_EHIP;
+    }
+    return KS_OK;
+}
+
+struct KsWorkspace {  // element counts (uint64 words) for a chunk of `bc` ciphertexts
+    uint64_t coeff, lifted, acc, conv;
+    uint64_t total() const { return coeff + lifted + acc + conv; }
+};
+
+KsWorkspace ks_ws_words(const ks_ctx* c, const Level& lv, uint32_t bc) {
+    const uint64_t N = c->N;
+    KsWorkspace w;
+    w.coeff = (uint64_t)bc * lv.ell * N;
+    w.lifted = (uint64_t)bc * lv.ndig * lv.E * N;
+    w.acc = (uint64_t)bc * 2 * lv.E * N;
+    w.conv = (uint64_t)bc * 2 * lv.ell * N;
+    return w;
+}
+
+// Decompose and raise: d (evaluation domain, `bc` polynomials d_ps words apart) -> lifted [bc][ndig][E][N]
+void mod_up(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, uint64_t* coeff, uint64_t* lifted, uint32_t bc,
+            hipStream_t s) {
+    const uint64_t N = c->N;
+    launch_ntt_inv(c, lv.q_map, XformIO{d, coeff, d_ps, (uint64_t)lv.ell * N, bc}, s);
+    launch_bconv(c, lv.d_modup, nullptr, lv.ndig, coeff, (uint64_t)lv.ell * N, lifted, (uint64_t)lv.ndig * lv.E * N, bc, c->alpha, s);
+    launch_ntt_fwd(c, lv.lifted_map, XformIO{lifted, lifted, (uint64_t)lv.ndig * lv.E * N, (uint64_t)lv.ndig * lv.E * N, bc}, s);
+}
+
+// Inner product with a key, division by P, optional addend.
+void key_mult_mod_down(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, const uint64_t* lifted, const uint64_t* evk,
+                       uint64_t* acc, uint64_t* conv, uint64_t* out, uint64_t out_bs, const uint64_t* addend, uint64_t addend_bs,
+                       uint32_t addend_comps, uint32_t galois, uint32_t bc, hipStream_t s) {
+    const uint64_t N = c->N;
+    launch_inner_product(c, lv, d, d_ps, lifted, evk, acc, bc, galois, s);
+    launch_ntt_inv(c, lv.special_map, XformIO{acc, acc, (uint64_t)lv.E * N, (uint64_t)lv.E * N, 2 * bc}, s);
+    launch_bconv(c, lv.d_moddown, nullptr, 1, acc, (uint64_t)lv.E * N, conv, (uint64_t)lv.ell * N, 2 * bc, c->K, s);
+    launch_ntt_fwd(c, lv.q_map, XformIO{conv, conv, (uint64_t)lv.ell * N, (uint64_t)lv.ell * N, 2 * bc}, s);
+    launch_moddown_finish(c, lv, acc, conv, out, out_bs, addend, addend_bs, addend_comps, galois, bc, s);
+}
+
+}  // namespace
+
+extern "C" size_t ks_workspace_bytes(const ks_ctx* c, int op, uint32_t ell, uint32_t batch, uint32_t n_rot) {
+    if (!c || c->K == 0 || ell < 1 || ell > c->L || batch == 0) return 0;
+    const Level& lv = c->levels[ell - 1];
+    const uint32_t bc = std::min(batch, kChunk);
+    const uint64_t N = c->N;
+    uint64_t words = ks_ws_words(c, lv, bc).total();
+    switch (op) {
+        case KS_OP_KEYSWITCH: break;
+        case KS_OP_ROTATE_HOISTED:
+            if (n_rot == 0) return 0;
+            break;
+        case KS_OP_HMULT_RELIN_RESCALE:
+            if (ell < 2) return 0;
+            // tensor product [bc][3][ell], sum [bc][2][ell], last limb [2 bc], spread [2 bc][ell-1]
+            words += (uint64_t)bc * (3 * ell + 2 * ell + 2 + 2 * (ell - 1)) * N;
+            break;
+        default: return 0;
+    }
+    return (size_t)words * sizeof(uint64_t);
+}
+
+static int check_map_args(const ks_ctx* c, const void* data, const uint32_t* mod_ids, uint32_t nlimbs, LimbMap* map) {
+    if (!c || !data || !mod_ids || nlimbs == 0 || nlimbs > (uint32_t)kMaxLimbs || !aligned16(data)) return KS_EINVAL;
+    map->n = nlimbs;
+    for (uint32_t i = 0; i < nlimbs; ++i) {
+        if (mod_ids[i] >= c->M) return KS_EINVAL;
+        map->off[i] = (uint16_t)i;
+        map->mod[i] = (uint8_t)mod_ids[i];
+    }
+    return KS_OK;
+}
+
+extern "C" int ntt_fwd(const ks_ctx* c, uint64_t* data, const uint32_t* mod_ids, uint32_t nlimbs, uint32_t batch, void* stream) {
+    LimbMap map;
+    int rc = check_map_args(c, data, mod_ids, nlimbs, &map);
+    if (rc != KS_OK) return rc;
+    if (batch == 0) return KS_OK;
+    if ((uint64_t)batch * nlimbs > (1u << 26)) return KS_EINVAL;
+    const uint64_t ps = (uint64_t)nlimbs * c->N;
+    launch_ntt_fwd(c, map, XformIO{data, data, ps, ps, batch}, static_cast<hipStream_t>(stream));
+    return finish("ntt_fwd");
+}
+
+extern "C" int ntt_inv(const ks_ctx* c, uint64_t* data, const uint32_t* mod_ids, uint32_t nlimbs, uint32_t batch, void* stream) {
+    LimbMap map;
+    int rc = check_map_args(c, data, mod_ids, nlimbs, &map);
+    if (rc != KS_OK) return rc;
+    if (batch == 0) return KS_OK;
+    if ((uint64_t)batch * nlimbs > (1u << 26)) return KS_EINVAL;
+    const uint64_t ps = (uint64_t)nlimbs * c->N;
+    launch_ntt_inv(c, map, XformIO{data, data, ps, ps, batch}, static_cast<hipStream_t>(stream));
+    return finish("ntt_inv");
+}
+
+extern "C" int bconv(const ks_ctx* c, const uint64_t* in, const uint32_t* src_ids, uint32_t n_src, uint64_t* out,
+                     const uint32_t* dst_ids, uint32_t n_dst, uint32_t batch, void* stream) {
+    if (!c || !in || !out || !src_ids || !dst_ids || !aligned16(in) || !aligned16(out)) return KS_EINVAL;
+    if (n_src == 0 || n_src > (uint32_t)kMaxSrc || n_dst == 0 || n_dst > 255) return KS_EINVAL;
+    std::vector<uint32_t> key;
+    key.push_back(n_src);
+    for (uint32_t i = 0; i < n_src; ++i) {
+        if (src_ids[i] >= c->M) return KS_EINVAL;
+        for (uint32_t k = 0; k < i; ++k)
+            if (src_ids[k] == src_ids[i]) return KS_EINVAL;
+        key.push_back(src_ids[i]);
+    }
+    for (uint32_t t = 0; t < n_dst; ++t) {
+        if (dst_ids[t] >= c->M) return KS_EINVAL;
+        key.push_back(dst_ids[t]);
+    }
+    if (batch == 0) return KS_OK;
+    BConvPlan* d_plan = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(c->mu);
+        auto it = c->bconv_cache.find(key);
+        if (it != c->bconv_cache.end()) {
+            d_plan = it->second;
+        } else {
+            std::vector<BConvPlan> plan(1);
+            uint16_t src_limb[kMaxSrc];
+            std::vector<uint16_t> dst_limb(n_dst);
+            for (uint32_t i = 0; i < n_src; ++i) src_limb[i] = (uint16_t)i;
+            for (uint32_t t = 0; t < n_dst; ++t) dst_limb[t] = (uint16_t)t;
+            fill_bconv_plan(c, plan.data(), src_ids, src_limb, n_src, dst_ids, dst_limb.data(), n_dst);
+            hipError_t e = hipMalloc(&d_plan, sizeof(BConvPlan));
+            if (e == hipSuccess) e = hipMemcpy(d_plan, plan.data(), sizeof(BConvPlan), hipMemcpyHostToDevice);
+            if (e != hipSuccess) {
+                set_hip_error(e, "bconv plan upload");
+                if (d_plan) (void)hipFree(d_plan);
+                return KS_EHIP;
+            }
+            c->bconv_cache[key] = d_plan;
+        }
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint64_t N = c->N;
+    for (uint32_t b0 = 0; b0 < batch; b0 += 32768) {
+        const uint32_t nb = std::min(batch - b0, 32768u);
+        launch_bconv(c, d_plan, nullptr, 1, in + (uint64_t)b0 * n_src * N, (uint64_t)n_src * N, out + (uint64_t)b0 * n_dst * N,
+                     (uint64_t)n_dst * N, nb, n_src, s);
+    }
+    return finish("bconv");
+}
+
+static int check_pipeline_args(const ks_ctx* c, uint32_t ell, uint32_t min_ell, const void* a, const void* b, const void* o,
+                               const void* ws) {
+    if (!c || c->K == 0 || !a || !b || !o || !aligned16(a) || !aligned16(b) || !aligned16(o)) return KS_EINVAL;
+    if (ell < min_ell || ell > c->L) return KS_EINVAL;
+    if (!ws || !aligned16(ws)) return KS_EWORKSPACE;
+    return KS_OK;
+}
+
+extern "C" int ks_keyswitch(const ks_ctx* c, const uint64_t* d, uint32_t ell, const uint64_t* evk, uint64_t* out, uint32_t batch,
+                            void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_pipeline_args(c, ell, 1, d, evk, out, ws);
+    if (rc != KS_OK) return rc;
+    if (batch == 0) return KS_OK;
+    if (ws_bytes < ks_workspace_bytes(c, KS_OP_KEYSWITCH, ell, batch, 0)) return KS_EWORKSPACE;
+    const Level& lv = c->levels[ell - 1];
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint64_t N = c->N, d_ps = (uint64_t)ell * N, out_bs = 2ull * ell * N;
+    for (uint32_t b0 = 0; b0 < batch; b0 += kChunk) {
+        const uint32_t bc = std::min(batch - b0, kChunk);
+        const KsWorkspace w = ks_ws_words(c, lv, bc);
+        uint64_t* coeff = static_cast<uint64_t*>(ws);
+        uint64_t* lifted = coeff + w.coeff;
+        uint64_t* acc = lifted + w.lifted;
+        uint64_t* conv = acc + w.acc;
+        const uint64_t* dc = d + (uint64_t)b0 * d_ps;
+        mod_up(c, lv, dc, d_ps, coeff, lifted, bc, s);
+        key_mult_mod_down(c, lv, dc, d_ps, lifted, evk, acc, conv, out + (uint64_t)b0 * out_bs, out_bs, nullptr, 0, 0, 1, bc, s);
+    }
+    return finish("ks_keyswitch");
+}
+
+extern "C" int ks_rotate_hoisted(const ks_ctx* c, const uint64_t* ct, uint32_t ell, const uint32_t* galois,
+                                 const uint64_t* const* rot_keys, uint32_t n_rot, uint64_t* out, uint32_t batch, void* ws,
+                                 size_t ws_bytes, void* stream) {
+    int rc = check_pipeline_args(c, ell, 1, ct, ct, out, ws);
+    if (rc != KS_OK) return rc;
+    if (!galois || !rot_keys || n_rot == 0) return KS_EINVAL;
+    for (uint32_t r = 0; r < n_rot; ++r) {
+        if ((galois[r] & 1u) == 0 || galois[r] >= 2u * c->N) return KS_EINVAL;
+        if (!rot_keys[r] || !aligned16(rot_keys[r])) return KS_EINVAL;
+    }
+    if (batch == 0) return KS_OK;
+    if (ws_bytes < ks_workspace_bytes(c, KS_OP_ROTATE_HOISTED, ell, batch, n_rot)) return KS_EWORKSPACE;
+    const Level& lv = c->levels[ell - 1];
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint64_t N = c->N, ct_bs = 2ull * ell * N, out_bs = (uint64_t)n_rot * 2 * ell * N;
+    for (uint32_t b0 = 0; b0 < batch; b0 += kChunk) {
+        const uint32_t bc = std::min(batch - b0, kChunk);
+        const KsWorkspace w = ks_ws_words(c, lv, bc);
+        uint64_t* coeff = static_cast<uint64_t*>(ws);
+        uint64_t* lifted = coeff + w.coeff;
+        uint64_t* acc = lifted + w.lifted;
+        uint64_t* conv = acc + w.acc;
+        const uint64_t* c0 = ct + (uint64_t)b0 * ct_bs;
+        const uint64_t* c1 = c0 + (uint64_t)ell * N;
+        mod_up(c, lv, c1, ct_bs, coeff, lifted, bc, s);
+        for (uint32_t r = 0; r < n_rot; ++r) {
+            uint64_t* o = out + (uint64_t)b0 * out_bs + (uint64_t)r * 2 * ell * N;
+            key_mult_mod_down(c, lv, c1, ct_bs, lifted, rot_keys[r], acc, conv, o, out_bs, c0, ct_bs, 1, galois[r], bc, s);
+        }
+    }
+    return finish("ks_rotate_hoisted");
+}
+
+extern "C" int hmult_relin_rescale(const ks_ctx* c, const uint64_t* cta, const uint64_t* ctb, uint32_t ell, const uint64_t* rlk,
+                                   uint64_t* out, uint32_t batch, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_pipeline_args(c, ell, 2, cta, ctb, out, ws);
+    if (rc != KS_OK) return rc;
+    if (!rlk || !aligned16(rlk)) return KS_EINVAL;
+    if (batch == 0) return KS_OK;
+    if (ws_bytes < ks_workspace_bytes(c, KS_OP_HMULT_RELIN_RESCALE, ell, batch, 0)) return KS_EWORKSPACE;
+    const Level& lv = c->levels[ell - 1];
+    const Level& lv_out = c->levels[ell - 2];
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint64_t N = c->N, ct_bs = 2ull * ell * N, td_bs = 3ull * ell * N, out_bs = 2ull * (ell - 1) * N;
+    LimbMap one;
+    one.n = 1;
+    one.off[0] = 0;
+    one.mod[0] = (uint8_t)(ell - 1);
+    for (uint32_t b0 = 0; b0 < batch; b0 += kChunk) {
+        const uint32_t bc = std::min(batch - b0, kChunk);
+        const KsWorkspace w = ks_ws_words(c, lv, bc);
+        uint64_t* coeff = static_cast<uint64_t*>(ws);
+        uint64_t* lifted = coeff + w.coeff;
+        uint64_t* acc = lifted + w.lifted;
+        uint64_t* conv = acc + w.acc;
+        uint64_t* td = conv + w.conv;                           // [bc][3][ell][N]
+        uint64_t* sum = td + (uint64_t)bc * td_bs;              // [bc][2][ell][N]
+        uint64_t* last = sum + (uint64_t)bc * ct_bs;            // [2 bc][N]
+        uint64_t* spread = last + (uint64_t)bc * 2 * N;         // [2 bc][ell-1][N]
+        launch_tensor_product(c, cta + (uint64_t)b0 * ct_bs, ctb + (uint64_t)b0 * ct_bs, td, ell, bc, s);
+        const uint64_t* d2 = td + 2ull * ell * N;
+        mod_up(c, lv, d2, td_bs, coeff, lifted, bc, s);
+        key_mult_mod_down(c, lv, d2, td_bs, lifted, rlk, acc, conv, sum, ct_bs, td, td_bs, 2, 1, bc, s);
+        // rescale both components: inverse transform of the last limb, centred remainder to every q_i, forward
+        // transform, subtract and divide
+        launch_ntt_inv(c, one, XformIO{sum + (uint64_t)(ell - 1) * N, last, (uint64_t)ell * N, N, 2 * bc}, s);
+        launch_rescale_spread(c, last, spread, ell, 2 * bc, s);
+        launch_ntt_fwd(c, lv_out.q_map, XformIO{spread, spread, (uint64_t)(ell - 1) * N, (uint64_t)(ell - 1) * N, 2 * bc}, s);
+        launch_rescale_finish(c, lv, sum, spread, out + (uint64_t)b0 * out_bs, 2 * bc, s);
+    }
+    return finish("hmult_relin_rescale");
+}

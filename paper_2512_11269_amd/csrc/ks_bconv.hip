@@ -1,0 +1,55 @@
+// Fast RNS base conversion (Kernel Code Generation, "Base Conversion" kernel class).
+//
+// One thread owns one coefficient position: it reads the n_src source residues, forms
+// y_i = [x_i (D/s_i)^-1]_{s_i} (canonical, so that the implicit lift is x + u D with 0 <= u < n_src) and then,
+// for every target modulus t, accumulates y_i * (D/s_i mod t) as lazy representatives and reduces once
+// (Kernel Code Generation: lazy modular reduction).  All constants are uniform per workgroup and arrive
+// through scalar loads; every global access is a contiguous 512-byte segment per wavefront.
+#include "ks_internal.hpp"
+
+namespace ks {
+
+template <int NSRC>
+__global__ __launch_bounds__(256) void bconv_kernel(const BConvPlan* __restrict__ plans, const uint64_t* __restrict__ in,
+                                                    uint64_t in_ps, uint64_t* __restrict__ out, uint64_t out_ps, uint32_t N) {
+    const BConvPlan& P = plans[blockIdx.y];
+    const uint32_t n = blockIdx.x * 256 + threadIdx.x;
+    const uint64_t* ip = in + (uint64_t)blockIdx.z * in_ps + n;
+    uint64_t* op = out + (uint64_t)blockIdx.z * out_ps + n;
+    const int n_src = (int)P.n_src;
+    double y[NSRC];
+#pragma unroll
+    for (int i = 0; i < NSRC; ++i) {
+        y[i] = 0.0;
+        if (i < n_src) {
+            const Mod mi = P.src_mod[i];
+            const double x = u64_to_f64(ip[(uint64_t)P.src_limb[i] * N]);
+            y[i] = canon(mulmod_lazy(x, P.src_inv[i], mi), mi);
+        }
+    }
+    const int n_dst = (int)P.n_dst;
+    for (int t = 0; t < n_dst; ++t) {
+        const Mod mt = P.dst_mod[t];
+        double acc = 0.0;
+#pragma unroll
+        for (int i = 0; i < NSRC; ++i)
+            if (i < n_src) acc += mulmod_lazy(y[i], P.hat[i][t], mt);
+        op[(uint64_t)P.dst_limb[t] * N] = f64_to_u64(canon(reduce_lazy(acc, mt), mt));
+    }
+}
+
+void launch_bconv(const ks_ctx* c, const BConvPlan* d_plans, const BConvPlan*, uint32_t n_plans, const uint64_t* in,
+                  uint64_t in_ps, uint64_t* out, uint64_t out_ps, uint32_t n_polys, uint32_t n_src_max, hipStream_t s) {
+    if (n_polys == 0 || n_plans == 0) return;
+    const dim3 grid(c->N / 256, n_plans, n_polys), block(256);
+    if (n_src_max <= 4)
+        hipLaunchKernelGGL(bconv_kernel<4>, grid, block, 0, s, d_plans, in, in_ps, out, out_ps, c->N);
+    else if (n_src_max <= 8)
+        hipLaunchKernelGGL(bconv_kernel<8>, grid, block, 0, s, d_plans, in, in_ps, out, out_ps, c->N);
+    else if (n_src_max <= 12)
+        hipLaunchKernelGGL(bconv_kernel<12>, grid, block, 0, s, d_plans, in, in_ps, out, out_ps, c->N);
+    else
+        hipLaunchKernelGGL(bconv_kernel<16>, grid, block, 0, s, d_plans, in, in_ps, out, out_ps, c->N);
+}
+
+}  // namespace ks

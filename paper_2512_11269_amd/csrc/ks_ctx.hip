@@ -1,0 +1,295 @@
+// Context construction: parameter validation, twiddle tables, base-conversion constants.
+// Host-side number theory here is the library's own (128-bit products); it shares nothing with
+// the CPU reference used by the tests.
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+#include <string>
+
+#include "ks_internal.hpp"
+
+namespace ks {
+
+typedef unsigned __int128 u128;
+
+uint64_t h_mulmod(uint64_t a, uint64_t b, uint64_t m) { return (uint64_t)((u128)a * b % m); }
+
+uint64_t h_powmod(uint64_t a, uint64_t e, uint64_t m) {
+    uint64_t r = 1 % m;
+    a %= m;
+    for (; e; e >>= 1) {
+        if (e & 1) r = h_mulmod(r, a, m);
+        a = h_mulmod(a, a, m);
+    }
+    return r;
+}
+
+uint64_t h_invmod(uint64_t a, uint64_t m) { return h_powmod(a % m, m - 2, m); }  // m prime
+
+static bool h_is_prime(uint64_t n) {
+    if (n < 2) return false;
+    static const uint64_t bases[] = {2, 3, 5, 7, 11, 13, 17, 19, 23, 29, 31, 37};
+    for (uint64_t b : bases) {
+        if (n % b == 0) return n == b;
+    }
+    uint64_t d = n - 1;
+    int s = 0;
+    while ((d & 1) == 0) { d >>= 1; ++s; }
+    for (uint64_t b : bases) {
+        uint64_t x = h_powmod(b, d, n);
+        if (x == 1 || x == n - 1) continue;
+        bool comp = true;
+        for (int i = 1; i < s; ++i) {
+            x = h_mulmod(x, x, n);
+            if (x == n - 1) { comp = false; break; }
+        }
+        if (comp) return false;
+    }
+    return true;
+}
+
+// Smallest primitive 2N-th root of unity modulo the prime m (m = 1 mod 2N): the N candidates are the odd
+// powers of any one of them.
+static uint64_t h_minimal_psi(uint64_t m, uint32_t N) {
+    uint64_t root = 0;
+    for (uint64_t x = 2;; ++x) {
+        root = h_powmod(x, (m - 1) / (2ull * N), m);
+        if (h_powmod(root, N, m) == m - 1) break;
+    }
+    const uint64_t sq = h_mulmod(root, root, m);
+    uint64_t best = root, cur = root;
+    for (uint32_t i = 1; i < N; ++i) {
+        cur = h_mulmod(cur, sq, m);
+        best = std::min(best, cur);
+    }
+    return best;
+}
+
+static uint32_t h_brv(uint32_t k, uint32_t bits) {
+    uint32_t r = 0;
+    for (uint32_t i = 0; i < bits; ++i) { r = (r << 1) | (k & 1); k >>= 1; }
+    return r;
+}
+
+static Mod make_mod(uint64_t m) { return Mod{(double)m, 1.0 / (double)m}; }
+
+void fill_bconv_plan(const ks_ctx* c, BConvPlan* plan, const uint32_t* src_ids, const uint16_t* src_limb, uint32_t n_src,
+                     const uint32_t* dst_ids, const uint16_t* dst_limb, uint32_t n_dst) {
+    memset(plan, 0, sizeof(BConvPlan));
+    plan->n_src = n_src;
+    plan->n_dst = n_dst;
+    for (uint32_t i = 0; i < n_src; ++i) {
+        const uint64_t si = c->mod[src_ids[i]];
+        uint64_t prod = 1;
+        for (uint32_t k = 0; k < n_src; ++k)
+            if (k != i) prod = h_mulmod(prod, c->mod[src_ids[k]] % si, si);
+        plan->src_limb[i] = src_limb[i];
+        plan->src_mod[i] = make_mod(si);
+        plan->src_inv[i] = (double)h_invmod(prod, si);
+    }
+    for (uint32_t t = 0; t < n_dst; ++t) {
+        const uint64_t mt = c->mod[dst_ids[t]];
+        plan->dst_limb[t] = dst_limb[t];
+        plan->dst_mod[t] = make_mod(mt);
+        for (uint32_t i = 0; i < n_src; ++i) {
+            uint64_t prod = 1 % mt;
+            for (uint32_t k = 0; k < n_src; ++k)
+                if (k != i) prod = h_mulmod(prod, c->mod[src_ids[k]] % mt, mt);
+            plan->hat[i][t] = (double)prod;
+        }
+    }
+}
+
+static thread_local std::string g_hip_error;
+void set_hip_error(hipError_t e, const char* where) {
+    g_hip_error = std::string(where) + ": " + hipGetErrorString(e);
+}
+
+}  // namespace ks
+
+using namespace ks;
+
+#define CK(call)                                   \
+    do {                                           \
+        hipError_t e_ = (call);                    \
+        if (e_ != hipSuccess) {                    \
+            set_hip_error(e_, #call);              \
+            rc = KS_EHIP;                          \
+            goto fail;                             \
+        }                                          \
+    } while (0)
+
+extern "C" const char* ks_last_hip_error(void) { return ks::g_hip_error.c_str(); }
+
+extern "C" const char* ks_strerror(int code) {
+    switch (code) {
+        case KS_OK: return "ok";
+        case KS_EINVAL: return "invalid argument";
+        case KS_EWORKSPACE: return "workspace missing or too small";
+        case KS_EHIP: return "HIP runtime error (see ks_last_hip_error)";
+        case KS_ENOMEM: return "out of memory";
+        default: return "unknown error code";
+    }
+}
+
+extern "C" int ks_ctx_destroy(ks_ctx* c) {
+    if (!c) return KS_EINVAL;
+    (void)hipSetDevice(c->device);
+    (void)hipFree(c->d_mod);
+    (void)hipFree(c->d_ninv);
+    (void)hipFree(c->d_Pinv);
+    (void)hipFree(c->d_tw_fwd);
+    (void)hipFree(c->d_tw_inv);
+    for (auto& lv : c->levels) {
+        (void)hipFree(lv.d_modup);
+        (void)hipFree(lv.d_moddown);
+        (void)hipFree(lv.d_qlinv);
+    }
+    for (auto& kv : c->bconv_cache) (void)hipFree(kv.second);
+    delete c;
+    return KS_OK;
+}
+
+extern "C" int ks_ctx_create(ks_ctx** out, uint32_t logN, uint32_t L, uint32_t K, uint32_t dnum,
+                             const uint64_t* q, const uint64_t* p, const uint64_t* psi, int device) {
+    if (!out) return KS_EINVAL;
+    *out = nullptr;
+    if (logN != 12 && logN != 16) return KS_EINVAL;
+    if (L == 0 || !q || (K > 0 && !p) || L + K > 255 || dnum == 0 || dnum > L) return KS_EINVAL;
+    const uint32_t N = 1u << logN, M = L + K;
+    const uint32_t alpha = (L + dnum - 1) / dnum;
+    if (K > (uint32_t)kMaxSrc) return KS_EINVAL;
+    if (K > 0 && alpha > (uint32_t)kMaxSrc) return KS_EINVAL;
+    if ((L + alpha - 1) / alpha > (uint32_t)kMaxDigits) return KS_EINVAL;
+    if (K > 0 && ((L + alpha - 1) / alpha) * M > (uint32_t)kMaxLimbs) return KS_EINVAL;
+
+    ks_ctx* c = new (std::nothrow) ks_ctx;
+    if (!c) return KS_ENOMEM;
+    int rc = KS_OK;
+    c->device = device;
+    c->logN = logN; c->N = N; c->L = L; c->K = K; c->dnum = dnum; c->alpha = alpha; c->M = M;
+    c->mod.resize(M);
+    c->psi.resize(M);
+    for (uint32_t m = 0; m < M; ++m) {
+        const uint64_t v = m < L ? q[m] : p[m - L];
+        if (v >= (1ull << 36) || v % (2ull * N) != 1 || !h_is_prime(v)) { rc = KS_EINVAL; goto fail; }
+        for (uint32_t k = 0; k < m; ++k)
+            if (c->mod[k] == v) { rc = KS_EINVAL; goto fail; }
+        c->mod[m] = v;
+        if (psi) {
+            if (psi[m] == 0 || psi[m] >= v || h_powmod(psi[m], N, v) != v - 1) { rc = KS_EINVAL; goto fail; }
+            c->psi[m] = psi[m];
+        } else {
+            c->psi[m] = h_minimal_psi(v, N);
+        }
+    }
+    {
+        CK(hipSetDevice(device));
+        // per-modulus constants
+        std::vector<Mod> hm(M);
+        std::vector<double> hn(M), hP(L);
+        for (uint32_t m = 0; m < M; ++m) {
+            hm[m] = Mod{(double)c->mod[m], 1.0 / (double)c->mod[m]};
+            hn[m] = (double)h_invmod(N % c->mod[m], c->mod[m]);
+        }
+        for (uint32_t i = 0; i < L; ++i) {
+            uint64_t P = 1;
+            for (uint32_t k = 0; k < K; ++k) P = h_mulmod(P, c->mod[L + k] % c->mod[i], c->mod[i]);
+            hP[i] = (double)h_invmod(P, c->mod[i]);
+        }
+        CK(hipMalloc(&c->d_mod, sizeof(Mod) * M));
+        CK(hipMalloc(&c->d_ninv, sizeof(double) * M));
+        CK(hipMalloc(&c->d_Pinv, sizeof(double) * L));
+        CK(hipMemcpy(c->d_mod, hm.data(), sizeof(Mod) * M, hipMemcpyHostToDevice));
+        CK(hipMemcpy(c->d_ninv, hn.data(), sizeof(double) * M, hipMemcpyHostToDevice));
+        CK(hipMemcpy(c->d_Pinv, hP.data(), sizeof(double) * L, hipMemcpyHostToDevice));
+
+        // twiddle tables: W[k] = psi^brv(k), Winv[k] = psi^-brv(k)
+        CK(hipMalloc(&c->d_tw_fwd, sizeof(double) * (size_t)M * N));
+        CK(hipMalloc(&c->d_tw_inv, sizeof(double) * (size_t)M * N));
+        std::vector<uint64_t> pw(N);
+        std::vector<double> tab(N);
+        for (uint32_t m = 0; m < M; ++m) {
+            const uint64_t mod = c->mod[m];
+            for (int dir = 0; dir < 2; ++dir) {
+                const uint64_t base = dir == 0 ? c->psi[m] : h_invmod(c->psi[m], mod);
+                pw[0] = 1;
+                for (uint32_t i = 1; i < N; ++i) pw[i] = h_mulmod(pw[i - 1], base, mod);
+                for (uint32_t k = 0; k < N; ++k) tab[k] = (double)pw[h_brv(k, logN)];
+                double* dst = (dir == 0 ? c->d_tw_fwd : c->d_tw_inv) + (size_t)m * N;
+                CK(hipMemcpy(dst, tab.data(), sizeof(double) * N, hipMemcpyHostToDevice));
+            }
+        }
+
+        // per-level pipeline tables (only meaningful with special primes)
+        c->levels.resize(L);
+        for (uint32_t ell = 1; ell <= L && K > 0; ++ell) {
+            Level& lv = c->levels[ell - 1];
+            lv.ell = ell;
+            lv.E = ell + K;
+            lv.ndig = (ell + alpha - 1) / alpha;
+            auto ext_id = [&](uint32_t pos) { return pos < ell ? pos : L + (pos - ell); };
+            std::vector<BConvPlan> plans(lv.ndig);
+            lv.lifted_map.n = 0;
+            for (uint32_t j = 0; j < lv.ndig; ++j) {
+                const uint32_t lo = j * alpha, hi = std::min(lo + alpha, ell);
+                lv.digit_lo[j] = lo;
+                lv.digit_hi[j] = hi;
+                uint32_t src_ids[kMaxSrc];
+                uint16_t src_limb[kMaxSrc];
+                std::vector<uint32_t> dst_ids;
+                std::vector<uint16_t> dst_limb;
+                for (uint32_t i = lo; i < hi; ++i) { src_ids[i - lo] = i; src_limb[i - lo] = (uint16_t)i; }
+                for (uint32_t pos = 0; pos < lv.E; ++pos) {
+                    if (pos >= lo && pos < hi) continue;
+                    dst_ids.push_back(ext_id(pos));
+                    dst_limb.push_back((uint16_t)(j * lv.E + pos));
+                    lv.lifted_map.off[lv.lifted_map.n] = (uint16_t)(j * lv.E + pos);
+                    lv.lifted_map.mod[lv.lifted_map.n] = (uint8_t)ext_id(pos);
+                    lv.lifted_map.n++;
+                }
+                fill_bconv_plan(c, &plans[j], src_ids, src_limb, hi - lo, dst_ids.data(), dst_limb.data(),
+                                (uint32_t)dst_ids.size());
+            }
+            lv.n_new = lv.lifted_map.n;
+            CK(hipMalloc(&lv.d_modup, sizeof(BConvPlan) * lv.ndig));
+            CK(hipMemcpy(lv.d_modup, plans.data(), sizeof(BConvPlan) * lv.ndig, hipMemcpyHostToDevice));
+
+            BConvPlan down;
+            uint32_t src_ids[kMaxSrc];
+            uint16_t src_limb[kMaxSrc];
+            std::vector<uint32_t> dst_ids(ell);
+            std::vector<uint16_t> dst_limb(ell);
+            lv.special_map.n = K;
+            for (uint32_t k = 0; k < K; ++k) {
+                src_ids[k] = L + k;
+                src_limb[k] = (uint16_t)(ell + k);
+                lv.special_map.off[k] = (uint16_t)(ell + k);
+                lv.special_map.mod[k] = (uint8_t)(L + k);
+            }
+            lv.q_map.n = ell;
+            for (uint32_t i = 0; i < ell; ++i) {
+                dst_ids[i] = i;
+                dst_limb[i] = (uint16_t)i;
+                lv.q_map.off[i] = (uint16_t)i;
+                lv.q_map.mod[i] = (uint8_t)i;
+            }
+            fill_bconv_plan(c, &down, src_ids, src_limb, K, dst_ids.data(), dst_limb.data(), ell);
+            CK(hipMalloc(&lv.d_moddown, sizeof(BConvPlan)));
+            CK(hipMemcpy(lv.d_moddown, &down, sizeof(BConvPlan), hipMemcpyHostToDevice));
+
+            if (ell >= 2) {
+                std::vector<double> ql(ell - 1);
+                for (uint32_t i = 0; i + 1 < ell; ++i) ql[i] = (double)h_invmod(c->mod[ell - 1] % c->mod[i], c->mod[i]);
+                CK(hipMalloc(&lv.d_qlinv, sizeof(double) * (ell - 1)));
+                CK(hipMemcpy(lv.d_qlinv, ql.data(), sizeof(double) * (ell - 1), hipMemcpyHostToDevice));
+            }
+        }
+    }
+    *out = c;
+    return KS_OK;
+fail:
+    ks_ctx_destroy(c);
+    return rc;
+}

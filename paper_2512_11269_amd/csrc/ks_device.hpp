@@ -1,0 +1,96 @@
+// Device-side modular arithmetic for primes below 2^36, carried in IEEE double precision.
+//
+// gfx950 issues double-precision FMA at full rate while 32-bit integer multiplies run at quarter
+// rate, so a 36x36 -> 72-bit modular product is an order of magnitude cheaper as a Barrett reduction
+// with an FMA-based exact product than as integer multiply chains.  Every quantity below is an
+// integer-valued double of magnitude < 2^53, hence exact; only the quotient estimate is approximate,
+// and its error merely moves the result to another small representative of the same residue class.
+//
+// "Lazy" values: a residue may be held as any integer r with |r| <= 16 p congruent to the true
+// value (Kernel Code Generation: lazy modular reduction); `canon` produces the canonical one.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ks {
+
+struct Mod {
+    double p;     // the modulus
+    double pinv;  // 1/p rounded to nearest
+};
+
+constexpr double kTwo52 = 4503599627370496.0;
+
+// Exact for x < 2^52: plant x in the mantissa of 2^52 and subtract 2^52.
+__device__ __forceinline__ double u64_to_f64(uint64_t x) {
+    return __longlong_as_double((long long)(x | 0x4330000000000000ull)) - kTwo52;
+}
+// Exact for integer-valued 0 <= r < 2^52.
+__device__ __forceinline__ uint64_t f64_to_u64(double r) {
+    return (uint64_t)__double_as_longlong(r + kTwo52) & 0x000FFFFFFFFFFFFFull;
+}
+
+// a * b mod p as a small signed representative.
+// Requires integer-valued |a| <= 2^40, |b| <= 2^36.  Returns r = a b (mod p) with |r| <= 0.501 p.
+//   h + l = a b exactly (l is the rounding error of the product, recovered by one FMA);
+//   q ~ a b / p; h - q p is an integer below 2^36 in magnitude, so the second FMA is exact too.
+__device__ __forceinline__ double mulmod_lazy(double a, double b, Mod m) {
+    double h = a * b;
+    double l = __builtin_fma(a, b, -h);
+    double q = __builtin_rint(h * m.pinv);
+    double r = __builtin_fma(-q, m.p, h);
+    return r + l;
+}
+
+// Any integer-valued |x| < 2^50 -> representative with |r| <= 0.501 p.
+__device__ __forceinline__ double reduce_lazy(double x, Mod m) {
+    double q = __builtin_rint(x * m.pinv);
+    return __builtin_fma(-q, m.p, x);
+}
+
+// Representative in (-p, p) -> canonical [0, p).
+__device__ __forceinline__ double canon(double r, Mod m) { return r < 0.0 ? r + m.p : r; }
+
+// Sixteen points, four decimation-in-time stages, in registers.  v[k] are 16 points whose mutual
+// distances are 8, 4, 2, 1 times a common stride; the twiddle of local stage u (pair distance 8>>u),
+// group g is W[(base << u) + g], i.e. the sub-tree below heap node `base` of the per-modulus table
+// W[k] = psi^brv(k).  Growth: every stage adds at most 0.501 p to the magnitude.
+__device__ __forceinline__ void radix16_fwd(double (&v)[16], const double* __restrict__ W, uint32_t base, Mod m) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int half = 8 >> u;
+#pragma unroll
+        for (int g = 0; g < (1 << u); ++g) {
+            const double w = W[(base << u) + g];
+#pragma unroll
+            for (int i = 0; i < half; ++i) {
+                const int k = g * 2 * half + i;
+                const double t = mulmod_lazy(v[k + half], w, m);
+                v[k + half] = v[k] - t;
+                v[k] = v[k] + t;
+            }
+        }
+    }
+}
+
+// Inverse of radix16_fwd up to the factor 16 (decimation in frequency), Winv[k] = psi^-brv(k).
+// Inputs must satisfy |v| <= p; sums double per stage, so outputs are bounded by 16 p.
+__device__ __forceinline__ void radix16_inv(double (&v)[16], const double* __restrict__ Winv, uint32_t base, Mod m) {
+#pragma unroll
+    for (int u = 3; u >= 0; --u) {
+        const int half = 8 >> u;
+#pragma unroll
+        for (int g = 0; g < (1 << u); ++g) {
+            const double w = Winv[(base << u) + g];
+#pragma unroll
+            for (int i = 0; i < half; ++i) {
+                const int k = g * 2 * half + i;
+                const double x = v[k], y = v[k + half];
+                v[k] = x + y;
+                v[k + half] = mulmod_lazy(x - y, w, m);
+            }
+        }
+    }
+}
+
+}  // namespace ks

@@ -1,0 +1,174 @@
+// Slot-wise kernels (Kernel Code Generation, "Elementwise" kernel class): inner product with the
+// evaluation key, the final subtract-and-scale of ModDown, tensor product, rescale pieces and the
+// evaluation-domain automorphism (a gather).  These are bandwidth-bound: one thread per slot, contiguous
+// 512-byte segments per wavefront, operands shared by both key components are read once ("load reuse").
+#include "ks_internal.hpp"
+
+namespace ks {
+
+struct DigitRanges {
+    uint32_t ndig;
+    uint32_t lo[kMaxDigits], hi[kMaxDigits];
+};
+
+// Slot permutation of sigma_g on a bit-reversed evaluation vector: slot n holds the point
+// psi^(2 brv(n) + 1); sigma_g(a) evaluated there is a evaluated at that point raised to g.
+__device__ __forceinline__ uint32_t galois_source_slot(uint32_t n, uint32_t g, uint32_t logN) {
+    const uint32_t e = (g * (2u * (__brev(n) >> (32 - logN)) + 1u)) & ((2u << logN) - 1u);
+    return __brev((e - 1u) >> 1) >> (32 - logN);
+}
+
+constexpr int kBatchGroup = 8;  // batch items sharing one read of the key slots
+
+template <bool GATHER>
+__global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restrict__ mods, DigitRanges dg, uint32_t ell, uint32_t E,
+                                                            uint32_t L, uint32_t M, uint32_t logN, const uint64_t* __restrict__ d,
+                                                            uint64_t d_ps, const uint64_t* __restrict__ lifted,
+                                                            const uint64_t* __restrict__ evk, uint64_t* __restrict__ acc,
+                                                            uint32_t batch, uint32_t galois) {
+    const uint32_t N = 1u << logN;
+    const uint32_t pos = blockIdx.y;
+    const uint32_t mid = pos < ell ? pos : L + (pos - ell);
+    const Mod m = mods[mid];
+    const uint32_t n = blockIdx.x * 256 + threadIdx.x;
+    const uint32_t sn = GATHER ? galois_source_slot(n, galois, logN) : n;
+    double k0[kMaxDigits], k1[kMaxDigits];
+#pragma unroll
+    for (int j = 0; j < kMaxDigits; ++j) {
+        k0[j] = k1[j] = 0.0;
+        if (j < (int)dg.ndig) {
+            k0[j] = u64_to_f64(evk[((uint64_t)(j * 2 + 0) * M + mid) * N + n]);
+            k1[j] = u64_to_f64(evk[((uint64_t)(j * 2 + 1) * M + mid) * N + n]);
+        }
+    }
+    const uint32_t b_lo = blockIdx.z * kBatchGroup;
+    const uint32_t b_hi = min(b_lo + kBatchGroup, batch);
+    for (uint32_t b = b_lo; b < b_hi; ++b) {
+        double a0 = 0.0, a1 = 0.0;
+#pragma unroll
+        for (int j = 0; j < kMaxDigits; ++j) {
+            if (j < (int)dg.ndig) {
+                const bool own = pos >= dg.lo[j] && pos < dg.hi[j];
+                const uint64_t* src = own ? d + (uint64_t)b * d_ps + (uint64_t)pos * N
+                                          : lifted + (((uint64_t)b * dg.ndig + j) * E + pos) * N;
+                const double x = u64_to_f64(src[sn]);
+                a0 += mulmod_lazy(x, k0[j], m);
+                a1 += mulmod_lazy(x, k1[j], m);
+            }
+        }
+        acc[(((uint64_t)b * 2 + 0) * E + pos) * N + n] = f64_to_u64(canon(reduce_lazy(a0, m), m));
+        acc[(((uint64_t)b * 2 + 1) * E + pos) * N + n] = f64_to_u64(canon(reduce_lazy(a1, m), m));
+    }
+}
+
+void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, const uint64_t* lifted,
+                          const uint64_t* evk, uint64_t* acc, uint32_t batch, uint32_t galois, hipStream_t s) {
+    if (batch == 0) return;
+    DigitRanges dg;
+    dg.ndig = lv.ndig;
+    for (uint32_t j = 0; j < kMaxDigits; ++j) {
+        dg.lo[j] = j < lv.ndig ? lv.digit_lo[j] : 0;
+        dg.hi[j] = j < lv.ndig ? lv.digit_hi[j] : 0;
+    }
+    const dim3 grid(c->N / 256, lv.E, (batch + kBatchGroup - 1) / kBatchGroup), block(256);
+    if (galois == 1)
+        hipLaunchKernelGGL(inner_product_kernel<false>, grid, block, 0, s, c->d_mod, dg, lv.ell, lv.E, c->L, c->M, c->logN, d,
+                           d_ps, lifted, evk, acc, batch, galois);
+    else
+        hipLaunchKernelGGL(inner_product_kernel<true>, grid, block, 0, s, c->d_mod, dg, lv.ell, lv.E, c->L, c->M, c->logN, d,
+                           d_ps, lifted, evk, acc, batch, galois);
+}
+
+// out = (acc - conv) * P^-1 (+ addend)
+template <bool GATHER>
+__global__ __launch_bounds__(256) void moddown_finish_kernel(const Mod* __restrict__ mods, const double* __restrict__ Pinv,
+                                                             uint32_t ell, uint32_t E, uint32_t logN,
+                                                             const uint64_t* __restrict__ acc, const uint64_t* __restrict__ conv,
+                                                             uint64_t* __restrict__ out, uint64_t out_bs,
+                                                             const uint64_t* __restrict__ addend, uint64_t addend_bs,
+                                                             uint32_t addend_comps, uint32_t galois) {
+    const uint32_t N = 1u << logN;
+    const uint32_t i = blockIdx.y, b = blockIdx.z >> 1, comp = blockIdx.z & 1;
+    const Mod m = mods[i];
+    const uint32_t n = blockIdx.x * 256 + threadIdx.x;
+    const double a = u64_to_f64(acc[(((uint64_t)b * 2 + comp) * E + i) * N + n]);
+    const double w = u64_to_f64(conv[(((uint64_t)b * 2 + comp) * ell + i) * N + n]);
+    double r = mulmod_lazy(a - w, Pinv[i], m);
+    if (addend != nullptr && comp < addend_comps) {
+        const uint32_t sn = GATHER ? galois_source_slot(n, galois, logN) : n;
+        r = reduce_lazy(r + u64_to_f64(addend[(uint64_t)b * addend_bs + ((uint64_t)comp * ell + i) * N + sn]), m);
+    }
+    out[(uint64_t)b * out_bs + ((uint64_t)comp * ell + i) * N + n] = f64_to_u64(canon(r, m));
+}
+
+void launch_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t* acc, const uint64_t* conv, uint64_t* out,
+                           uint64_t out_bs, const uint64_t* addend, uint64_t addend_bs, uint32_t addend_comps, uint32_t galois,
+                           uint32_t batch, hipStream_t s) {
+    if (batch == 0) return;
+    const dim3 grid(c->N / 256, lv.ell, batch * 2), block(256);
+    if (galois == 1)
+        hipLaunchKernelGGL(moddown_finish_kernel<false>, grid, block, 0, s, c->d_mod, c->d_Pinv, lv.ell, lv.E, c->logN, acc, conv,
+                           out, out_bs, addend, addend_bs, addend_comps, galois);
+    else
+        hipLaunchKernelGGL(moddown_finish_kernel<true>, grid, block, 0, s, c->d_mod, c->d_Pinv, lv.ell, lv.E, c->logN, acc, conv,
+                           out, out_bs, addend, addend_bs, addend_comps, galois);
+}
+
+// (b1, a1) x (b2, a2) -> d0 = b1 b2, d1 = a1 b2 + a2 b1, d2 = a1 a2
+__global__ __launch_bounds__(256) void tensor_product_kernel(const Mod* __restrict__ mods, uint32_t ell, uint32_t N,
+                                                             const uint64_t* __restrict__ cta, const uint64_t* __restrict__ ctb,
+                                                             uint64_t* __restrict__ td) {
+    const uint32_t i = blockIdx.y, b = blockIdx.z;
+    const Mod m = mods[i];
+    const uint64_t n = blockIdx.x * 256 + threadIdx.x;
+    const uint64_t ct_off = ((uint64_t)b * 2 * ell + i) * N + n, comp = (uint64_t)ell * N;
+    const double b1 = u64_to_f64(cta[ct_off]), a1 = u64_to_f64(cta[ct_off + comp]);
+    const double b2 = u64_to_f64(ctb[ct_off]), a2 = u64_to_f64(ctb[ct_off + comp]);
+    const uint64_t o = ((uint64_t)b * 3 * ell + i) * N + n;
+    td[o] = f64_to_u64(canon(mulmod_lazy(b1, b2, m), m));
+    td[o + comp] = f64_to_u64(canon(reduce_lazy(mulmod_lazy(a1, b2, m) + mulmod_lazy(a2, b1, m), m), m));
+    td[o + 2 * comp] = f64_to_u64(canon(mulmod_lazy(a1, a2, m), m));
+}
+
+void launch_tensor_product(const ks_ctx* c, const uint64_t* cta, const uint64_t* ctb, uint64_t* td, uint32_t ell,
+                           uint32_t batch, hipStream_t s) {
+    if (batch == 0) return;
+    hipLaunchKernelGGL(tensor_product_kernel, dim3(c->N / 256, ell, batch), dim3(256), 0, s, c->d_mod, ell, c->N, cta, ctb, td);
+}
+
+// spread[p][i] = centred remainder of last[p] (mod q_{ell-1}) reduced modulo q_i
+__global__ __launch_bounds__(256) void rescale_spread_kernel(const Mod* __restrict__ mods, uint32_t ell, uint32_t N,
+                                                             const uint64_t* __restrict__ last, uint64_t* __restrict__ spread) {
+    const uint32_t i = blockIdx.y, p = blockIdx.z;
+    const Mod m = mods[i];
+    const double ql = mods[ell - 1].p;
+    const uint64_t n = blockIdx.x * 256 + threadIdx.x;
+    double r = u64_to_f64(last[(uint64_t)p * N + n]);
+    if (r > (ql - 1.0) * 0.5) r -= ql;
+    spread[((uint64_t)p * (ell - 1) + i) * N + n] = f64_to_u64(canon(reduce_lazy(r, m), m));
+}
+
+void launch_rescale_spread(const ks_ctx* c, const uint64_t* last, uint64_t* spread, uint32_t ell, uint32_t n_polys, hipStream_t s) {
+    if (n_polys == 0 || ell < 2) return;
+    hipLaunchKernelGGL(rescale_spread_kernel, dim3(c->N / 256, ell - 1, n_polys), dim3(256), 0, s, c->d_mod, ell, c->N, last, spread);
+}
+
+__global__ __launch_bounds__(256) void rescale_finish_kernel(const Mod* __restrict__ mods, const double* __restrict__ qlinv,
+                                                             uint32_t ell, uint32_t N, const uint64_t* __restrict__ x,
+                                                             const uint64_t* __restrict__ spread, uint64_t* __restrict__ out) {
+    const uint32_t i = blockIdx.y, p = blockIdx.z;
+    const Mod m = mods[i];
+    const uint64_t n = blockIdx.x * 256 + threadIdx.x;
+    const double a = u64_to_f64(x[((uint64_t)p * ell + i) * N + n]);
+    const double w = u64_to_f64(spread[((uint64_t)p * (ell - 1) + i) * N + n]);
+    out[((uint64_t)p * (ell - 1) + i) * N + n] = f64_to_u64(canon(mulmod_lazy(a - w, qlinv[i], m), m));
+}
+
+void launch_rescale_finish(const ks_ctx* c, const Level& lv, const uint64_t* x, const uint64_t* spread, uint64_t* out,
+                           uint32_t n_polys, hipStream_t s) {
+    if (n_polys == 0 || lv.ell < 2) return;
+    hipLaunchKernelGGL(rescale_finish_kernel, dim3(c->N / 256, lv.ell - 1, n_polys), dim3(256), 0, s, c->d_mod, lv.d_qlinv,
+                       lv.ell, c->N, x, spread, out);
+}
+
+}  // namespace ks

@@ -1,0 +1,123 @@
+// Internal declarations shared by the translation units of the library (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <map>
+#include <mutex>
+#include <vector>
+
+#include "../../include/ks.h"
+#include "ks_device.hpp"
+
+namespace ks {
+
+constexpr int kMaxSrc = 16;     // source limbs of one base conversion (alpha or K)
+constexpr int kMaxDst = 256;    // target limbs of one base conversion
+constexpr int kMaxLimbs = 192;  // limbs of one polynomial bundle addressed by a LimbMap
+constexpr int kMaxDigits = 8;
+
+// Which limbs of a polynomial bundle a transform launch touches: limb `idx` lives at element offset
+// off[idx] * N from the bundle's base and is taken modulo moduli[mod[idx]].  Passed by value.
+struct LimbMap {
+    uint16_t off[kMaxLimbs];
+    uint8_t mod[kMaxLimbs];
+    uint32_t n;
+};
+
+// Constants of one fast base conversion, read by the kernel through uniform (scalar) loads.
+struct BConvPlan {
+    uint32_t n_src, n_dst;
+    uint16_t src_limb[kMaxSrc];  // limb index inside the input bundle
+    uint16_t dst_limb[kMaxDst];  // limb index inside the output bundle
+    Mod src_mod[kMaxSrc];
+    double src_inv[kMaxSrc];     // (D / s_i)^-1 mod s_i
+    Mod dst_mod[kMaxDst];
+    double hat[kMaxSrc][kMaxDst];  // (D / s_i) mod t
+};
+
+// Everything the key-switching pipeline needs at one level ell.
+struct Level {
+    uint32_t ell = 0, ndig = 0, E = 0;     // E = ell + K extended limb count
+    uint32_t n_new = 0;                    // sum over digits of (E - alpha_j): limbs produced by ModUp
+    BConvPlan* d_modup = nullptr;          // [ndig] device
+    BConvPlan* d_moddown = nullptr;        // [1] device
+    LimbMap lifted_map;                    // new limbs inside the [ndig][E][N] lifted bundle
+    LimbMap special_map;                   // the K special limbs inside an [E][N] accumulator
+    LimbMap q_map;                         // limbs 0..ell-1, modulus id = limb index
+    uint32_t digit_lo[kMaxDigits], digit_hi[kMaxDigits];
+    double* d_qlinv = nullptr;             // [ell-1] device: q_{ell-1}^-1 mod q_i (rescale)
+};
+
+}  // namespace ks
+
+struct ks_ctx {
+    int device = 0;
+    uint32_t logN = 0, N = 0, L = 0, K = 0, dnum = 0, alpha = 0, M = 0;
+    std::vector<uint64_t> mod, psi;       // host copies, index = modulus id
+    ks::Mod* d_mod = nullptr;             // [M]
+    double* d_ninv = nullptr;             // [M]  N^-1 mod m
+    double* d_Pinv = nullptr;             // [L]  P^-1 mod q_i
+    double* d_tw_fwd = nullptr;           // [M][N] psi^brv(k)
+    double* d_tw_inv = nullptr;           // [M][N] psi^-brv(k)
+    std::vector<ks::Level> levels;        // index ell-1
+    mutable std::mutex mu;
+    mutable std::map<std::vector<uint32_t>, ks::BConvPlan*> bconv_cache;  // key: n_src, src ids, dst ids
+};
+
+namespace ks {
+
+// ---- host number theory (ks_ctx.hip) ----
+uint64_t h_mulmod(uint64_t a, uint64_t b, uint64_t m);
+uint64_t h_powmod(uint64_t a, uint64_t e, uint64_t m);
+uint64_t h_invmod(uint64_t a, uint64_t m);
+void fill_bconv_plan(const ks_ctx* c, BConvPlan* plan, const uint32_t* src_ids, const uint16_t* src_limb, uint32_t n_src,
+                     const uint32_t* dst_ids, const uint16_t* dst_limb, uint32_t n_dst);
+
+// thread-local HIP error text
+void set_hip_error(hipError_t e, const char* where);
+
+// ---- launchers: all asynchronous on `s`, no allocation ----
+// In/out element formats of the two-phase transform.  Intermediate results between the two phases are
+// stored as raw doubles (lazy representatives) in the same 8-byte slots.
+struct XformIO {
+    const void* in;
+    void* out;
+    uint64_t in_poly_stride, out_poly_stride;  // elements between consecutive bundles
+    uint32_t n_polys;
+};
+// forward: coefficient (canonical u64) -> evaluation (canonical u64)
+void launch_ntt_fwd(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipStream_t s);
+// inverse: evaluation (canonical u64) -> coefficient (canonical u64)
+void launch_ntt_inv(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipStream_t s);
+
+void launch_bconv(const ks_ctx* c, const BConvPlan* d_plans, const BConvPlan* h_plan0_shape, uint32_t n_plans,
+                  const uint64_t* in, uint64_t in_poly_stride, uint64_t* out, uint64_t out_poly_stride,
+                  uint32_t n_polys, uint32_t n_src_max, hipStream_t s);
+
+// acc[b][c][pos] = sum_j src_j[pos] * key[j][c][ext_id(pos)];  src_j[pos] = d[b][pos] when pos lies in digit j,
+// otherwise lifted[b][j][pos].  With galois != 1 the source slot is permuted by sigma_g.
+void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_poly_stride,
+                          const uint64_t* lifted, const uint64_t* evk, uint64_t* acc, uint32_t batch,
+                          uint32_t galois, hipStream_t s);
+
+// out[b][c][i] = (acc[b][c][i] - conv[b][c][i]) * P^-1 (+ addend) mod q_i
+//   addend: nullptr, or a [b][*][ell][N] tensor whose component `c` is added (addend_comps = how many
+//   components it has per batch item: 1 means only component 0 receives it); with galois != 1 the addend
+//   is read through the sigma_g slot permutation.
+void launch_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t* acc, const uint64_t* conv, uint64_t* out,
+                           uint64_t out_batch_stride, const uint64_t* addend, uint64_t addend_batch_stride,
+                           uint32_t addend_comps, uint32_t galois, uint32_t batch, hipStream_t s);
+
+// d0 = b1 b2, d1 = a1 b2 + a2 b1, d2 = a1 a2 ; td: [batch][3][ell][N]
+void launch_tensor_product(const ks_ctx* c, const uint64_t* cta, const uint64_t* ctb, uint64_t* td, uint32_t ell,
+                           uint32_t batch, hipStream_t s);
+
+// rescale helpers: r = centred remainder of the (coefficient-domain) last limb, spread to every q_i, i < ell-1
+void launch_rescale_spread(const ks_ctx* c, const uint64_t* last_coeff /*[polys][N]*/, uint64_t* spread /*[polys][ell-1][N]*/,
+                           uint32_t ell, uint32_t n_polys, hipStream_t s);
+// out[p][i] = (x[p][i] - spread[p][i]) * q_{ell-1}^-1 mod q_i ; x has ell limbs per poly, out ell-1
+void launch_rescale_finish(const ks_ctx* c, const Level& lv, const uint64_t* x, const uint64_t* spread, uint64_t* out,
+                           uint32_t n_polys, hipStream_t s);
+
+}  // namespace ks

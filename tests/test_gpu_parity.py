@@ -1,0 +1,176 @@
+"""GPU parity: every entry point of the C-ABI library against the plain-C reference, bit-exact on every
+residue, on seeded inputs spanning several tiles, ragged digits, lower levels and batch chunks."""
+
+import numpy as np
+import pytest
+import torch
+
+import ks_inputs
+import paper_2512_11269_amd as K
+from gpu_util import Setup, assert_equal, host, workspace
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def small():      # configuration 1: N = 2^12, L = 4, K = 2, dnum = 2
+    return Setup(12, 4, 2, 2)
+
+
+@pytest.fixture(scope="module")
+def boot():       # configuration 2: N = 2^16, L = 24, K = 8, dnum = 3
+    return Setup(16, 24, 8, 3)
+
+
+@pytest.mark.parametrize("which,ids,batch", [("small", [0, 1, 2, 3, 4, 5, 0], 3), ("boot", [0, 31, 7, 24, 23], 2)])
+def test_ntt_matches_reference_and_round_trips(which, ids, batch, request):
+    st = request.getfixturevalue(which)
+    x = st.uniform(7, 1, (batch,), ids)
+    y = x.clone()
+    K.ntt_fwd(st.ctx, y, ids)
+    assert_equal(y, st.ref.ntt_fwd(host(x), ids))
+    z = y.clone()
+    K.ntt_inv(st.ctx, z, ids)
+    assert torch.equal(z, x)
+    w = x.clone()
+    K.ntt_inv(st.ctx, w, ids)
+    assert_equal(w, st.ref.ntt_inv(host(x), ids))
+
+
+def test_ntt_edge_values(boot):
+    """All-zero, all (m-1) and a single one: exercises the extremes of the lazy ranges."""
+    ids = [0, 24, 31]
+    N = boot.N
+    x = torch.zeros((3, len(ids), N), dtype=torch.int64, device="cuda")
+    for i, m in enumerate(ids):
+        x[1, i, :] = boot.moduli[m] - 1
+    x[2, :, 1] = 1
+    y = x.clone()
+    K.ntt_fwd(boot.ctx, y, ids)
+    assert_equal(y, boot.ref.ntt_fwd(host(x), ids))
+    assert int(y[0].abs().max()) == 0
+    K.ntt_inv(boot.ctx, y, ids)
+    assert torch.equal(y, x)
+
+
+@pytest.mark.parametrize("which,src,dst,batch", [
+    ("small", [0, 1], [2, 3, 4, 5], 2),
+    ("small", [4, 5], [0, 1, 2, 3], 1),
+    ("boot", list(range(8)), list(range(8, 32)), 2),
+    ("boot", [16, 17, 18], [0, 1, 30, 31], 1),
+    ("boot", [5], [0, 31], 1),
+])
+def test_bconv_matches_reference(which, src, dst, batch, request):
+    st = request.getfixturevalue(which)
+    x = st.uniform(8, 2, (batch,), src)
+    out = torch.empty((batch, len(dst), st.N), dtype=torch.int64, device="cuda")
+    K.bconv(st.ctx, x, src, out, dst)
+    assert_equal(out, st.ref.bconv(host(x), src, dst))
+    out2 = torch.empty_like(out)
+    K.bconv(st.ctx, x, src, out2, dst)          # second call takes the cached-table path
+    assert torch.equal(out, out2)
+
+
+def _run_keyswitch(st, seed, ell, batch):
+    d = st.uniform(seed, 1, (batch,), list(range(ell)))
+    evk = st.uniform(seed, 2, (st.ctx.dnum, 2), list(range(st.L + st.K)))
+    out = torch.empty((batch, 2, ell, st.N), dtype=torch.int64, device="cuda")
+    ws = workspace(st.ctx, K.KS_OP_KEYSWITCH, ell, batch)
+    K.ks_keyswitch(st.ctx, d, ell, evk, out, ws)
+    return d, evk, out
+
+
+@pytest.mark.parametrize("ell,batch", [(4, 1), (3, 2), (1, 1), (4, 19)])
+def test_keyswitch_small(small, ell, batch):
+    d, evk, out = _run_keyswitch(small, ks_inputs.CONFIGS[1]["seed"], ell, batch)
+    assert_equal(out, small.ref.keyswitch(host(d), host(evk), ell))
+
+
+@pytest.mark.parametrize("ell,batch", [(24, 1), (17, 2)])
+def test_keyswitch_bootstrap_shape(boot, ell, batch):
+    d, evk, out = _run_keyswitch(boot, ks_inputs.CONFIGS[2]["seed"], ell, batch)
+    assert_equal(out, boot.ref.keyswitch(host(d), host(evk), ell))
+
+
+def test_keyswitch_zero_key_gives_zero(boot):
+    d = boot.uniform(3, 1, (1,), list(range(24)))
+    evk = torch.zeros((3, 2, 32, boot.N), dtype=torch.int64, device="cuda")
+    out = torch.full((1, 2, 24, boot.N), -1, dtype=torch.int64, device="cuda")
+    K.ks_keyswitch(boot.ctx, d, 24, evk, out, workspace(boot.ctx, K.KS_OP_KEYSWITCH, 24, 1))
+    assert int(out.abs().max()) == 0
+
+
+def _run_rotate(st, seed, ell, batch, n_rot):
+    ct = st.uniform(seed, 1, (batch, 2), list(range(ell)))
+    keys = [st.uniform(seed, 10 + r, (st.ctx.dnum, 2), list(range(st.L + st.K))) for r in range(n_rot)]
+    galois = ks_inputs.galois_elements(st.logN, n_rot)
+    out = torch.empty((batch, n_rot, 2, ell, st.N), dtype=torch.int64, device="cuda")
+    ws = workspace(st.ctx, K.KS_OP_ROTATE_HOISTED, ell, batch, n_rot)
+    K.ks_rotate_hoisted(st.ctx, ct, ell, galois, keys, out, ws)
+    return ct, keys, galois, out
+
+
+@pytest.mark.parametrize("ell,batch,n_rot", [(4, 2, 3), (3, 1, 2)])
+def test_rotate_hoisted_small(small, ell, batch, n_rot):
+    ct, keys, galois, out = _run_rotate(small, 1003, ell, batch, n_rot)
+    assert_equal(out, small.ref.rotate_hoisted(host(ct), galois, [host(k) for k in keys], ell))
+
+
+def test_rotate_hoisted_bootstrap_shape(boot):
+    ct, keys, galois, out = _run_rotate(boot, 1003, 24, 2, 2)
+    assert_equal(out, boot.ref.rotate_hoisted(host(ct), galois, [host(k) for k in keys], 24))
+
+
+def test_rotate_by_identity_equals_keyswitch_plus_c0(small):
+    ell = 4
+    ct = small.uniform(5, 1, (1, 2), list(range(ell)))
+    key = small.uniform(5, 2, (2, 2), list(range(6)))
+    out = torch.empty((1, 1, 2, ell, small.N), dtype=torch.int64, device="cuda")
+    K.ks_rotate_hoisted(small.ctx, ct, ell, [1], [key], out, workspace(small.ctx, K.KS_OP_ROTATE_HOISTED, ell, 1, 1))
+    ks = torch.empty((1, 2, ell, small.N), dtype=torch.int64, device="cuda")
+    K.ks_keyswitch(small.ctx, ct[:, 1].contiguous(), ell, key, ks, workspace(small.ctx, K.KS_OP_KEYSWITCH, ell, 1))
+    q = torch.tensor(small.q, dtype=torch.int64, device="cuda").view(ell, 1)
+    assert torch.equal(out[0, 0, 1], ks[0, 1])
+    assert torch.equal(out[0, 0, 0], (ks[0, 0] + ct[0, 0]) % q)
+
+
+def _run_hmult(st, seed, ell, batch):
+    cta = st.uniform(seed, 1, (batch, 2), list(range(ell)))
+    ctb = st.uniform(seed, 2, (batch, 2), list(range(ell)))
+    rlk = st.uniform(seed, 3, (st.ctx.dnum, 2), list(range(st.L + st.K)))
+    out = torch.empty((batch, 2, ell - 1, st.N), dtype=torch.int64, device="cuda")
+    ws = workspace(st.ctx, K.KS_OP_HMULT_RELIN_RESCALE, ell, batch)
+    K.hmult_relin_rescale(st.ctx, cta, ctb, ell, rlk, out, ws)
+    return cta, ctb, rlk, out
+
+
+@pytest.mark.parametrize("ell,batch", [(4, 2), (2, 1), (4, 17)])
+def test_hmult_small(small, ell, batch):
+    cta, ctb, rlk, out = _run_hmult(small, 1005, ell, batch)
+    assert_equal(out, small.ref.hmult_relin_rescale(host(cta), host(ctb), host(rlk), ell))
+
+
+def test_hmult_llm_shape():
+    st = Setup(16, 35, 12, 3)            # configuration 5 shape: digits 12 / 12 / 11
+    cta, ctb, rlk, out = _run_hmult(st, 1005, 35, 2)
+    assert_equal(out, st.ref.hmult_relin_rescale(host(cta), host(ctb), host(rlk), 35))
+
+
+def test_error_paths_return_codes(small):
+    lib = K.load_library()
+    ell = 4
+    d = small.uniform(1, 1, (1,), list(range(ell)))
+    evk = small.uniform(1, 2, (2, 2), list(range(6)))
+    out = torch.empty((1, 2, ell, small.N), dtype=torch.int64, device="cuda")
+    ws = workspace(small.ctx, K.KS_OP_KEYSWITCH, ell, 1)
+    h = small.ctx.handle
+    assert lib.ks_keyswitch(h, d.data_ptr(), 5, evk.data_ptr(), out.data_ptr(), 1, ws.data_ptr(), ws.numel() * 8, None) == -1
+    assert lib.ks_keyswitch(h, d.data_ptr(), ell, evk.data_ptr(), out.data_ptr(), 1, ws.data_ptr(), 16, None) == -2
+    assert lib.ks_keyswitch(h, d.data_ptr() + 8, ell, evk.data_ptr(), out.data_ptr(), 1, ws.data_ptr(), ws.numel() * 8, None) == -1
+    assert lib.ks_keyswitch(h, d.data_ptr(), ell, evk.data_ptr(), out.data_ptr(), 1, None, 0, None) == -2
+    with pytest.raises(K.KsError):
+        K.ks_rotate_hoisted(small.ctx, torch.zeros((1, 2, ell, small.N), dtype=torch.int64, device="cuda"), ell, [4], [evk],
+                            torch.empty((1, 1, 2, ell, small.N), dtype=torch.int64, device="cuda"), ws)
+    with pytest.raises(K.KsError):
+        K.ntt_fwd(small.ctx, d, [99])
+    torch.cuda.synchronize()
