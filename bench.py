@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the hybrid key-switching hot path on one MI355X.
+
+Default workload: the bootstrapping-level key-switch (N = 2^16, L = 24 ciphertext primes, K = 8 special
+primes, dnum = 3, one ciphertext per call).  A "step" is one ks_keyswitch call, i.e. the whole chain INTT,
+ModUp base conversion, NTT, inner product with the evaluation key, INTT, ModDown base conversion, NTT and
+the final subtract-and-scale.  All inputs are resident in HBM before the timed region.  To keep the 256 MB
+last-level cache from flattering the number, steps rotate over several disjoint sets of (d, evk, out,
+workspace); `hot_value` reports the single-set figure next to it.
+
+Prints ONE JSON line.  `roofline` describes the kernel with the largest share of the step time: its
+algorithmic bytes (what one launch must read plus write) divided by its average duration, measured with
+HIP events on the launch stream in a separate instrumented pass over the same workload.
+`cpu_baseline` is the plain-C reference timed on this machine's host cores on a bounded sample.
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MIB = 1024.0 * 1024.0
+
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/), keyed by
+# workload and kernel; None where no counter run has been taken yet.
+MEASURED_TRAFFIC_BYTES: dict = {}
+
+
+def _keyswitch_bytes(L, K, dnum, N):
+    """Algorithmic traffic of one key-switch in bytes: compulsory (read d and the key, write out) and the
+    fused-plan model (every transform = two passes over its limbs, base conversion and products fused)."""
+    limb = N * 8
+    alpha = -(-L // dnum)
+    E = L + K
+    new_limbs = sum(E - (min((j + 1) * alpha, L) - j * alpha) for j in range(dnum))
+    compulsory = (L + dnum * 2 * E + 2 * L) * limb
+    fused = (2 * L                                       # INTT rows
+             + L + new_limbs                             # INTT cols + conversion + NTT cols
+             + new_limbs + L + dnum * 2 * E + 2 * E      # NTT rows + inner product
+             + 2 * 2 * K                                 # INTT rows of special limbs
+             + 2 * K + 2 * L                             # INTT cols + conversion + NTT cols
+             + 2 * L + 2 * L + 2 * L) * limb             # NTT rows + subtract-scale
+    return compulsory, fused
+
+
+def bench_keyswitch(args, torch, K, ks_inputs):
+    cfg = ks_inputs.CONFIGS[2]
+    q, p = ks_inputs.moduli(cfg)
+    logN, L, Kk, dnum = cfg["logN"], cfg["L"], cfg["K"], cfg["dnum"]
+    N = 1 << logN
+    ctx = K.Context(logN, q, p, dnum)
+    ws_words = K.ks_workspace_bytes(ctx, K.KS_OP_KEYSWITCH, L, 1) // 8
+    sets = []
+    for s in range(args.sets):
+        d = ks_inputs.uniform_residues(cfg["seed"], 100 * s + 1, (1,), q, N, device="cuda")
+        evk = ks_inputs.uniform_residues(cfg["seed"], 100 * s + 2, (dnum, 2), q + p, N, device="cuda")
+        out = torch.empty((1, 2, L, N), dtype=torch.int64, device="cuda")
+        ws = torch.empty(ws_words, dtype=torch.int64, device="cuda")
+        sets.append((d, evk, out, ws))
+
+    def run(n, rotate=True):
+        for i in range(n):
+            d, evk, out, ws = sets[i % len(sets)] if rotate else sets[0]
+            K.ks_keyswitch(ctx, d, L, evk, out, ws)
+
+    def timed(n, rotate):
+        torch.cuda.synchronize()
+        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0.record()
+        run(n, rotate)
+        t1.record()
+        torch.cuda.synchronize()
+        return t0.elapsed_time(t1) / n
+
+    run(args.warmup)
+    ms = timed(args.steps, True)
+    run(args.warmup, False)
+    ms_hot = timed(args.steps, False)
+
+    # instrumented pass: per-kernel durations from HIP events recorded by the library on the launch stream
+    K.ks_profile_enable(True)
+    prof_steps = min(args.steps, 24)
+    run(prof_steps)
+    torch.cuda.synchronize()
+    kernels = K.ks_profile_report()
+    K.ks_profile_enable(False)
+    for k in kernels:
+        k["avg_us"] = 1000.0 * k["total_ms"] / k["launches"]
+        k["ms_per_step"] = k["total_ms"] / prof_steps
+        k["achieved_GBs"] = k["total_bytes"] / (k["total_ms"] * 1e-3) / 1e9
+        k["bytes_per_launch"] = k["total_bytes"] / k["launches"]
+    dom = max(kernels, key=lambda k: k["total_ms"])
+    traffic = MEASURED_TRAFFIC_BYTES.get(("keyswitch", dom["kernel"]))
+    roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": round(dom["achieved_GBs"], 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(dom["achieved_GBs"] / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "algorithmic_bytes_per_launch": dom["bytes_per_launch"], "avg_launch_us": round(dom["avg_us"], 2),
+                "launches_per_step": dom["launches"] / prof_steps}
+    compulsory, fused = _keyswitch_bytes(L, Kk, dnum, N)
+    path = {"fused_plan_MiB": fused / MIB, "compulsory_MiB": compulsory / MIB,
+            "fused_plan_GBs": round(fused / (ms * 1e-3) / 1e9, 1), "fused_plan_frac_of_peak": round(fused / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "compulsory_GBs": round(compulsory / (ms * 1e-3) / 1e9, 1),
+            "sum_kernel_ms_per_step": round(sum(k["ms_per_step"] for k in kernels), 4)}
+    result = {
+        "metric": "key_switches_per_sec", "value": round(1000.0 / ms, 2), "unit": "key-switch/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": "bootstrap-keyswitch N=2^16 L=24 K=8 dnum=3 batch=1 (36-bit primes in 64-bit words)",
+                   "buffer_sets_rotated": args.sets},
+        "hot_value": round(1000.0 / ms_hot, 2), "roofline": roofline, "path": path,
+        "kernels": [{"kernel": k["kernel"], "launches_per_step": k["launches"] / prof_steps, "avg_us": round(k["avg_us"], 2),
+                     "ms_per_step": round(k["ms_per_step"], 4), "achieved_GBs": round(k["achieved_GBs"], 1)} for k in kernels],
+        "paper_context": "paper reports only end-to-end times on NVIDIA GPUs (bootstrapping 7.5 ms on 8xB200, BERT-Base 8.8 s, "
+                         "Llama3-8B 134 s); no per-key-switch figure exists to compare with",
+    }
+    return result, (cfg, q, p, sets[0])
+
+
+def cpu_baseline_keyswitch(cfg, q, p, first_set, ks_inputs, budget_s=15.0):
+    from oracle import c_tier
+    from oracle import ckks_ref as R
+    logN, dnum = cfg["logN"], cfg["dnum"]
+    ref = c_tier.COracle(logN, q, p, dnum, [R.minimal_psi(m, logN) for m in q + p])
+    d = ks_inputs.as_u64(first_set[0])
+    evk = ks_inputs.as_u64(first_set[1])
+    ref.keyswitch(d, evk)                       # warm the tables / page in
+    n, t0 = 0, time.time()
+    while n < 4 or (time.time() - t0 < budget_s and n < 200):
+        ref.keyswitch(d, evk)
+        n += 1
+    dt = time.time() - t0
+    return {"value": round(n / dt, 3), "unit": "key-switch/s", "cores": c_tier.max_threads(), "kind": "oracle",
+            "sample": f"{n} key-switches of the same workload (same seeded d and evk), {dt:.1f} s wall"}
+
+
+def bench_ntt(args, torch, K, ks_inputs):
+    cfg = ks_inputs.CONFIGS[4]
+    q, p = ks_inputs.moduli(cfg)
+    logN, L, batch = cfg["logN"], cfg["L"], cfg["batch"]
+    N = 1 << logN
+    ctx = K.Context(logN, q, p, 1)
+    ids = list(range(L))
+    data = ks_inputs.uniform_residues(cfg["seed"], 1, (batch,), q, N, device="cuda")
+    K.ntt_fwd(ctx, data, ids)
+    K.ntt_inv(ctx, data, ids)
+    torch.cuda.synchronize()
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    steps = max(2, args.steps // 10)
+    t0.record()
+    for _ in range(steps):
+        K.ntt_fwd(ctx, data, ids)
+        K.ntt_inv(ctx, data, ids)
+    t1.record()
+    torch.cuda.synchronize()
+    ms = t0.elapsed_time(t1) / steps
+    limbs = 2 * L * batch
+    bytes_one_pass = limbs * N * 8 * 2.0
+    return {"metric": "limb_ntts_per_sec", "value": round(limbs / (ms * 1e-3), 1), "unit": "limb-NTT/s (2^16 points)", "n_gpus": 1,
+            "steps": steps, "warmup": 1, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+            "config": {"workload": "batched-ntt N=2^16 60 limbs x 32 polynomials, forward then inverse"},
+            "roofline": {"bound": "hbm", "kernel": "ntt_fwd+ntt_inv (two passes each)", "achieved": round(2 * bytes_one_pass / (ms * 1e-3) / 1e9, 1),
+                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(2 * bytes_one_pass / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                         "traffic": None}}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--sets", type=int, default=6, help="disjoint buffer sets rotated through (cold-cache figure)")
+    ap.add_argument("--workload", default="keyswitch", choices=["keyswitch", "ntt"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (one key-switch stream on one MI355X); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import ks_inputs
+    import paper_2512_11269_amd as K
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP library has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    if args.workload == "ntt":
+        result = bench_ntt(args, torch, K, ks_inputs)
+    else:
+        result, (cfg, q, p, first_set) = bench_keyswitch(args, torch, K, ks_inputs)
+        if not args.no_cpu_baseline:
+            result["cpu_baseline"] = cpu_baseline_keyswitch(cfg, q, p, first_set, ks_inputs)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -123,6 +123,16 @@ int ks_rotate_hoisted(const ks_ctx* ctx, const uint64_t* ct, uint32_t ell, const
 int hmult_relin_rescale(const ks_ctx* ctx, const uint64_t* cta, const uint64_t* ctb, uint32_t ell,
                         const uint64_t* rlk, uint64_t* out, uint32_t batch, void* ws, size_t ws_bytes, void* stream);
 
+/* Per-kernel timing for benchmarks (the paper's evaluation characterises its NTT, base-conversion and
+ * elementwise kernel classes separately; this exposes the same breakdown).  While enabled, every kernel the
+ * library launches is bracketed by a pair of HIP events on its stream (this creates events, i.e. it is not
+ * allocation-free, and adds small gaps between kernels: never enable it inside a timed throughput run).
+ * ks_profile_enable(on) clears earlier records.  ks_profile_report waits for the recorded events and writes a
+ * JSON array [{"kernel", "launches", "total_ms", "total_bytes"}...] into buf (host); total_bytes is the
+ * algorithmic traffic (bytes each launch must read plus write).  KS_EINVAL if buf is too small. */
+int ks_profile_enable(int on);
+int ks_profile_report(char* buf, size_t buflen);
+
 #ifdef __cplusplus
 }
 #endif

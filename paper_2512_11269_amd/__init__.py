@@ -9,6 +9,8 @@ from .binding import (  # noqa: F401
     bconv,
     hmult_relin_rescale,
     ks_keyswitch,
+    ks_profile_enable,
+    ks_profile_report,
     ks_rotate_hoisted,
     ks_workspace_bytes,
     library_path,

@@ -56,8 +56,22 @@ def load_library():
     lib.ks_rotate_hoisted.argtypes = [_vp, _vp, ctypes.c_uint32, _u32p, ctypes.POINTER(_vp), ctypes.c_uint32, _vp,
                                       ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
     lib.hmult_relin_rescale.argtypes = [_vp, _vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
+    lib.ks_profile_enable.argtypes = [ctypes.c_int]
+    lib.ks_profile_report.argtypes = [ctypes.c_char_p, ctypes.c_size_t]
     _lib = lib
     return lib
+
+
+def ks_profile_enable(on: bool) -> None:
+    _check(load_library().ks_profile_enable(1 if on else 0), "ks_profile_enable")
+
+
+def ks_profile_report() -> list:
+    """Per-kernel records [{kernel, launches, total_ms, total_bytes}] gathered since ks_profile_enable(True)."""
+    import json
+    buf = ctypes.create_string_buffer(1 << 16)
+    _check(load_library().ks_profile_report(buf, len(buf)), "ks_profile_report")
+    return json.loads(buf.value.decode())
 
 
 def _check(rc: int, what: str):

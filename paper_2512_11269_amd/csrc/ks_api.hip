@@ -40,7 +40,7 @@ void mod_up(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, 
             hipStream_t s) {
     const uint64_t N = c->N;
     launch_ntt_inv(c, lv.q_map, XformIO{d, coeff, d_ps, (uint64_t)lv.ell * N, bc}, s);
-    launch_bconv(c, lv.d_modup, nullptr, lv.ndig, coeff, (uint64_t)lv.ell * N, lifted, (uint64_t)lv.ndig * lv.E * N, bc, c->alpha, s);
+    launch_bconv(c, lv.d_modup, lv.ell + lv.n_new, lv.ndig, coeff, (uint64_t)lv.ell * N, lifted, (uint64_t)lv.ndig * lv.E * N, bc, c->alpha, s);
     launch_ntt_fwd(c, lv.lifted_map, XformIO{lifted, lifted, (uint64_t)lv.ndig * lv.E * N, (uint64_t)lv.ndig * lv.E * N, bc}, s);
 }
 
@@ -51,7 +51,7 @@ void key_mult_mod_down(const ks_ctx* c, const Level& lv, const uint64_t* d, uint
     const uint64_t N = c->N;
     launch_inner_product(c, lv, d, d_ps, lifted, evk, acc, bc, galois, s);
     launch_ntt_inv(c, lv.special_map, XformIO{acc, acc, (uint64_t)lv.E * N, (uint64_t)lv.E * N, 2 * bc}, s);
-    launch_bconv(c, lv.d_moddown, nullptr, 1, acc, (uint64_t)lv.E * N, conv, (uint64_t)lv.ell * N, 2 * bc, c->K, s);
+    launch_bconv(c, lv.d_moddown, c->K + lv.ell, 1, acc, (uint64_t)lv.E * N, conv, (uint64_t)lv.ell * N, 2 * bc, c->K, s);
     launch_ntt_fwd(c, lv.q_map, XformIO{conv, conv, (uint64_t)lv.ell * N, (uint64_t)lv.ell * N, 2 * bc}, s);
     launch_moddown_finish(c, lv, acc, conv, out, out_bs, addend, addend_bs, addend_comps, galois, bc, s);
 }
@@ -156,7 +156,7 @@ extern "C" int bconv(const ks_ctx* c, const uint64_t* in, const uint32_t* src_id
     const uint64_t N = c->N;
     for (uint32_t b0 = 0; b0 < batch; b0 += 32768) {
         const uint32_t nb = std::min(batch - b0, 32768u);
-        launch_bconv(c, d_plan, nullptr, 1, in + (uint64_t)b0 * n_src * N, (uint64_t)n_src * N, out + (uint64_t)b0 * n_dst * N,
+        launch_bconv(c, d_plan, n_src + n_dst, 1, in + (uint64_t)b0 * n_src * N, (uint64_t)n_src * N, out + (uint64_t)b0 * n_dst * N,
                      (uint64_t)n_dst * N, nb, n_src, s);
     }
     return finish("bconv");

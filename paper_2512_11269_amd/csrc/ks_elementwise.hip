@@ -71,6 +71,8 @@ void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, u
         dg.hi[j] = j < lv.ndig ? lv.digit_hi[j] : 0;
     }
     const dim3 grid(c->N / 256, lv.E, (batch + kBatchGroup - 1) / kBatchGroup), block(256);
+    // reads: every raised digit limb per ciphertext, the key once; writes: both accumulators
+    ProfScope ps("inner_product", ((double)batch * (lv.ndig + 2) * lv.E + 2.0 * lv.ndig * lv.E) * c->N * 8.0, s);
     if (galois == 1)
         hipLaunchKernelGGL(inner_product_kernel<false>, grid, block, 0, s, c->d_mod, dg, lv.ell, lv.E, c->L, c->M, c->logN, d,
                            d_ps, lifted, evk, acc, batch, galois);
@@ -106,6 +108,7 @@ void launch_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t* acc
                            uint32_t batch, hipStream_t s) {
     if (batch == 0) return;
     const dim3 grid(c->N / 256, lv.ell, batch * 2), block(256);
+    ProfScope ps("moddown_finish", (double)batch * lv.ell * (6 + (addend ? addend_comps : 0)) * c->N * 8.0, s);
     if (galois == 1)
         hipLaunchKernelGGL(moddown_finish_kernel<false>, grid, block, 0, s, c->d_mod, c->d_Pinv, lv.ell, lv.E, c->logN, acc, conv,
                            out, out_bs, addend, addend_bs, addend_comps, galois);
@@ -133,6 +136,7 @@ __global__ __launch_bounds__(256) void tensor_product_kernel(const Mod* __restri
 void launch_tensor_product(const ks_ctx* c, const uint64_t* cta, const uint64_t* ctb, uint64_t* td, uint32_t ell,
                            uint32_t batch, hipStream_t s) {
     if (batch == 0) return;
+    ProfScope ps("tensor_product", (double)batch * ell * 7 * c->N * 8.0, s);
     hipLaunchKernelGGL(tensor_product_kernel, dim3(c->N / 256, ell, batch), dim3(256), 0, s, c->d_mod, ell, c->N, cta, ctb, td);
 }
 
@@ -150,6 +154,7 @@ __global__ __launch_bounds__(256) void rescale_spread_kernel(const Mod* __restri
 
 void launch_rescale_spread(const ks_ctx* c, const uint64_t* last, uint64_t* spread, uint32_t ell, uint32_t n_polys, hipStream_t s) {
     if (n_polys == 0 || ell < 2) return;
+    ProfScope ps("rescale_spread", (double)n_polys * ell * c->N * 8.0, s);
     hipLaunchKernelGGL(rescale_spread_kernel, dim3(c->N / 256, ell - 1, n_polys), dim3(256), 0, s, c->d_mod, ell, c->N, last, spread);
 }
 
@@ -167,6 +172,7 @@ __global__ __launch_bounds__(256) void rescale_finish_kernel(const Mod* __restri
 void launch_rescale_finish(const ks_ctx* c, const Level& lv, const uint64_t* x, const uint64_t* spread, uint64_t* out,
                            uint32_t n_polys, hipStream_t s) {
     if (n_polys == 0 || lv.ell < 2) return;
+    ProfScope ps("rescale_finish", (double)n_polys * (lv.ell - 1) * 3 * c->N * 8.0, s);
     hipLaunchKernelGGL(rescale_finish_kernel, dim3(c->N / 256, lv.ell - 1, n_polys), dim3(256), 0, s, c->d_mod, lv.d_qlinv,
                        lv.ell, c->N, x, spread, out);
 }

@@ -77,6 +77,15 @@ void fill_bconv_plan(const ks_ctx* c, BConvPlan* plan, const uint32_t* src_ids, 
 // thread-local HIP error text
 void set_hip_error(hipError_t e, const char* where);
 
+// Optional per-kernel timing (ks_profile_enable): when on, every launcher brackets its kernel with a pair of
+// HIP events on the launch stream and books the kernel's algorithmic bytes (what it must read plus write).
+struct ProfScope {
+    ProfScope(const char* name, double bytes, hipStream_t s);
+    ~ProfScope();
+    int slot;
+    hipStream_t stream;
+};
+
 // ---- launchers: all asynchronous on `s`, no allocation ----
 // In/out element formats of the two-phase transform.  Intermediate results between the two phases are
 // stored as raw doubles (lazy representatives) in the same 8-byte slots.
@@ -91,7 +100,7 @@ void launch_ntt_fwd(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipS
 // inverse: evaluation (canonical u64) -> coefficient (canonical u64)
 void launch_ntt_inv(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipStream_t s);
 
-void launch_bconv(const ks_ctx* c, const BConvPlan* d_plans, const BConvPlan* h_plan0_shape, uint32_t n_plans,
+void launch_bconv(const ks_ctx* c, const BConvPlan* d_plans, uint32_t limbs_moved_per_poly, uint32_t n_plans,
                   const uint64_t* in, uint64_t in_poly_stride, uint64_t* out, uint64_t out_poly_stride,
                   uint32_t n_polys, uint32_t n_src_max, hipStream_t s);
 

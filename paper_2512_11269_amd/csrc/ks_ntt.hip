@@ -186,16 +186,21 @@ void launch_ntt_fwd(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipS
     if (limbs == 0) return;
     const uint64_t* in = static_cast<const uint64_t*>(io.in);
     uint64_t* out = static_cast<uint64_t*>(io.out);
+    const double bytes = 2.0 * limbs * c->N * 8.0;
     if (c->logN == 16) {
+        { ProfScope ps("ntt_fwd_cols", bytes, s);
         hipLaunchKernelGGL(ntt_fwd_cols<8>, dim3(limbs * 16), dim3(256), 0, s, c->d_tw_fwd, c->d_mod, map, in, out,
-                           io.in_poly_stride, io.out_poly_stride);
+                           io.in_poly_stride, io.out_poly_stride); }
+        { ProfScope ps("ntt_fwd_rows", bytes, s);
         hipLaunchKernelGGL(ntt_fwd_rows<8>, dim3(limbs * 16), dim3(256), 0, s, c->d_tw_fwd, c->d_mod, map, out,
-                           io.out_poly_stride);
+                           io.out_poly_stride); }
     } else {
+        { ProfScope ps("ntt_fwd_cols", bytes, s);
         hipLaunchKernelGGL(ntt_fwd_cols<4>, dim3(limbs), dim3(256), 0, s, c->d_tw_fwd, c->d_mod, map, in, out,
-                           io.in_poly_stride, io.out_poly_stride);
+                           io.in_poly_stride, io.out_poly_stride); }
+        { ProfScope ps("ntt_fwd_rows", bytes, s);
         hipLaunchKernelGGL(ntt_fwd_rows<4>, dim3(limbs), dim3(256), 0, s, c->d_tw_fwd, c->d_mod, map, out,
-                           io.out_poly_stride);
+                           io.out_poly_stride); }
     }
 }
 
@@ -204,16 +209,21 @@ void launch_ntt_inv(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipS
     if (limbs == 0) return;
     const uint64_t* in = static_cast<const uint64_t*>(io.in);
     uint64_t* out = static_cast<uint64_t*>(io.out);
+    const double bytes = 2.0 * limbs * c->N * 8.0;
     if (c->logN == 16) {
+        { ProfScope ps("ntt_inv_rows", bytes, s);
         hipLaunchKernelGGL(ntt_inv_rows<8>, dim3(limbs * 16), dim3(256), 0, s, c->d_tw_inv, c->d_mod, map, in, out,
-                           io.in_poly_stride, io.out_poly_stride);
+                           io.in_poly_stride, io.out_poly_stride); }
+        { ProfScope ps("ntt_inv_cols", bytes, s);
         hipLaunchKernelGGL(ntt_inv_cols<8>, dim3(limbs * 16), dim3(256), 0, s, c->d_tw_inv, c->d_mod, c->d_ninv, map, out,
-                           io.out_poly_stride);
+                           io.out_poly_stride); }
     } else {
+        { ProfScope ps("ntt_inv_rows", bytes, s);
         hipLaunchKernelGGL(ntt_inv_rows<4>, dim3(limbs), dim3(256), 0, s, c->d_tw_inv, c->d_mod, map, in, out,
-                           io.in_poly_stride, io.out_poly_stride);
+                           io.in_poly_stride, io.out_poly_stride); }
+        { ProfScope ps("ntt_inv_cols", bytes, s);
         hipLaunchKernelGGL(ntt_inv_cols<4>, dim3(limbs), dim3(256), 0, s, c->d_tw_inv, c->d_mod, c->d_ninv, map, out,
-                           io.out_poly_stride);
+                           io.out_poly_stride); }
     }
 }
 
