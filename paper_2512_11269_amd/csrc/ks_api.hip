@@ -35,25 +35,28 @@ KsWorkspace ks_ws_words(const ks_ctx* c, const Level& lv, uint32_t bc) {
     return w;
 }
 
-// Decompose and raise: d (evaluation domain, `bc` polynomials d_ps words apart) -> lifted [bc][ndig][E][N]
+// Decompose and raise: d (evaluation domain, `bc` polynomials d_ps words apart) -> lifted [bc][ndig][E][N].
+// With finish_rows the raised limbs end as canonical evaluation-domain residues; without it they stop after the
+// column half of the forward transform (raw doubles) and the row half is left to the fused inner product.
 void mod_up(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, uint64_t* coeff, uint64_t* lifted, uint32_t bc,
-            hipStream_t s) {
-    const uint64_t N = c->N;
-    launch_ntt_inv(c, lv.q_map, XformIO{d, coeff, d_ps, (uint64_t)lv.ell * N, bc}, s);
-    launch_bconv(c, lv.d_modup, lv.ell + lv.n_new, lv.ndig, coeff, (uint64_t)lv.ell * N, lifted, (uint64_t)lv.ndig * lv.E * N, bc, c->alpha, s);
-    launch_ntt_fwd(c, lv.lifted_map, XformIO{lifted, lifted, (uint64_t)lv.ndig * lv.E * N, (uint64_t)lv.ndig * lv.E * N, bc}, s);
+            bool finish_rows, hipStream_t s) {
+    const uint64_t N = c->N, coeff_ps = (uint64_t)lv.ell * N, lifted_ps = (uint64_t)lv.ndig * lv.E * N;
+    launch_ntt_inv_rows(c, lv.q_map, XformIO{d, coeff, d_ps, coeff_ps, bc}, s);
+    // the column half also multiplies by N^-1 (D_j/q_i)^-1 and leaves canonical doubles for the conversion
+    launch_ntt_inv_cols(c, lv.q_map, coeff, coeff_ps, bc, lv.d_modup_scale, true, true, s);
+    launch_bconv_ntt_cols(c, lv.d_modup, lv.ndig, lv.max_targets, lv.ell + lv.n_new, coeff, coeff_ps, lifted, lifted_ps, bc, s);
+    if (finish_rows) launch_ntt_fwd_rows(c, lv.lifted_map, lifted, lifted_ps, bc, s);
 }
 
-// Inner product with a key, division by P, optional addend.
-void key_mult_mod_down(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, const uint64_t* lifted, const uint64_t* evk,
-                       uint64_t* acc, uint64_t* conv, uint64_t* out, uint64_t out_bs, const uint64_t* addend, uint64_t addend_bs,
-                       uint32_t addend_comps, uint32_t galois, uint32_t bc, hipStream_t s) {
-    const uint64_t N = c->N;
-    launch_inner_product(c, lv, d, d_ps, lifted, evk, acc, bc, galois, s);
-    launch_ntt_inv(c, lv.special_map, XformIO{acc, acc, (uint64_t)lv.E * N, (uint64_t)lv.E * N, 2 * bc}, s);
-    launch_bconv(c, lv.d_moddown, c->K + lv.ell, 1, acc, (uint64_t)lv.E * N, conv, (uint64_t)lv.ell * N, 2 * bc, c->K, s);
-    launch_ntt_fwd(c, lv.q_map, XformIO{conv, conv, (uint64_t)lv.ell * N, (uint64_t)lv.ell * N, 2 * bc}, s);
-    launch_moddown_finish(c, lv, acc, conv, out, out_bs, addend, addend_bs, addend_comps, galois, bc, s);
+// Division by P of both accumulators, optional addend: INTT of the special limbs (in place), fused base
+// conversion + column half, fused row half + (acc - conv) P^-1.
+void mod_down(const ks_ctx* c, const Level& lv, uint64_t* acc, uint64_t* conv, uint64_t* out, uint64_t out_bs,
+              const uint64_t* addend, uint64_t addend_bs, uint32_t addend_comps, uint32_t galois, uint32_t bc, hipStream_t s) {
+    const uint64_t N = c->N, acc_ps = (uint64_t)lv.E * N, conv_ps = (uint64_t)lv.ell * N;
+    launch_ntt_inv_rows(c, lv.special_map, XformIO{acc, acc, acc_ps, acc_ps, 2 * bc}, s);
+    launch_ntt_inv_cols(c, lv.special_map, acc, acc_ps, 2 * bc, c->d_moddown_scale, true, true, s);
+    launch_bconv_ntt_cols(c, lv.d_moddown, 1, lv.ell, c->K + lv.ell, acc, acc_ps, conv, conv_ps, 2 * bc, s);
+    launch_rows_moddown_finish(c, lv, acc, conv, out, out_bs, addend, addend_bs, addend_comps, galois, bc, s);
 }
 
 }  // namespace
@@ -187,8 +190,9 @@ extern "C" int ks_keyswitch(const ks_ctx* c, const uint64_t* d, uint32_t ell, co
         uint64_t* acc = lifted + w.lifted;
         uint64_t* conv = acc + w.acc;
         const uint64_t* dc = d + (uint64_t)b0 * d_ps;
-        mod_up(c, lv, dc, d_ps, coeff, lifted, bc, s);
-        key_mult_mod_down(c, lv, dc, d_ps, lifted, evk, acc, conv, out + (uint64_t)b0 * out_bs, out_bs, nullptr, 0, 0, 1, bc, s);
+        mod_up(c, lv, dc, d_ps, coeff, lifted, bc, false, s);
+        launch_rows_inner_product(c, lv, dc, d_ps, lifted, evk, acc, bc, s);
+        mod_down(c, lv, acc, conv, out + (uint64_t)b0 * out_bs, out_bs, nullptr, 0, 0, 1, bc, s);
     }
     return finish("ks_keyswitch");
 }
@@ -217,10 +221,11 @@ extern "C" int ks_rotate_hoisted(const ks_ctx* c, const uint64_t* ct, uint32_t e
         uint64_t* conv = acc + w.acc;
         const uint64_t* c0 = ct + (uint64_t)b0 * ct_bs;
         const uint64_t* c1 = c0 + (uint64_t)ell * N;
-        mod_up(c, lv, c1, ct_bs, coeff, lifted, bc, s);
+        mod_up(c, lv, c1, ct_bs, coeff, lifted, bc, true, s);   // finished once, shared by every rotation
         for (uint32_t r = 0; r < n_rot; ++r) {
             uint64_t* o = out + (uint64_t)b0 * out_bs + (uint64_t)r * 2 * ell * N;
-            key_mult_mod_down(c, lv, c1, ct_bs, lifted, rot_keys[r], acc, conv, o, out_bs, c0, ct_bs, 1, galois[r], bc, s);
+            launch_inner_product(c, lv, c1, ct_bs, lifted, rot_keys[r], acc, bc, galois[r], s);
+            mod_down(c, lv, acc, conv, o, out_bs, c0, ct_bs, 1, galois[r], bc, s);
         }
     }
     return finish("ks_rotate_hoisted");
@@ -254,8 +259,9 @@ extern "C" int hmult_relin_rescale(const ks_ctx* c, const uint64_t* cta, const u
         uint64_t* spread = last + (uint64_t)bc * 2 * N;         // [2 bc][ell-1][N]
         launch_tensor_product(c, cta + (uint64_t)b0 * ct_bs, ctb + (uint64_t)b0 * ct_bs, td, ell, bc, s);
         const uint64_t* d2 = td + 2ull * ell * N;
-        mod_up(c, lv, d2, td_bs, coeff, lifted, bc, s);
-        key_mult_mod_down(c, lv, d2, td_bs, lifted, rlk, acc, conv, sum, ct_bs, td, td_bs, 2, 1, bc, s);
+        mod_up(c, lv, d2, td_bs, coeff, lifted, bc, false, s);
+        launch_rows_inner_product(c, lv, d2, td_bs, lifted, rlk, acc, bc, s);
+        mod_down(c, lv, acc, conv, sum, ct_bs, td, td_bs, 2, 1, bc, s);
         // rescale both components: inverse transform of the last limb, centred remainder to every q_i, forward
         // transform, subtract and divide
         launch_ntt_inv(c, one, XformIO{sum + (uint64_t)(ell - 1) * N, last, (uint64_t)ell * N, N, 2 * bc}, s);

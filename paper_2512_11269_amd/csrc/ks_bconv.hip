@@ -33,7 +33,7 @@ __global__ __launch_bounds__(256) void bconv_kernel(const BConvPlan* __restrict_
         double acc = 0.0;
 #pragma unroll
         for (int i = 0; i < NSRC; ++i)
-            if (i < n_src) acc += mulmod_lazy(y[i], P.hat[i][t], mt);
+            if (i < n_src) acc += mulmod_lazy(y[i], P.hat[t][i], mt);
         op[(uint64_t)P.dst_limb[t] * N] = f64_to_u64(canon(reduce_lazy(acc, mt), mt));
     }
 }

@@ -92,11 +92,12 @@ void fill_bconv_plan(const ks_ctx* c, BConvPlan* plan, const uint32_t* src_ids, 
         const uint64_t mt = c->mod[dst_ids[t]];
         plan->dst_limb[t] = dst_limb[t];
         plan->dst_mod[t] = make_mod(mt);
+        plan->dst_mod_id[t] = (uint8_t)dst_ids[t];
         for (uint32_t i = 0; i < n_src; ++i) {
             uint64_t prod = 1 % mt;
             for (uint32_t k = 0; k < n_src; ++k)
                 if (k != i) prod = h_mulmod(prod, c->mod[src_ids[k]] % mt, mt);
-            plan->hat[i][t] = (double)prod;
+            plan->hat[t][i] = (double)prod;
         }
     }
 }
@@ -139,12 +140,14 @@ extern "C" int ks_ctx_destroy(ks_ctx* c) {
     (void)hipFree(c->d_mod);
     (void)hipFree(c->d_ninv);
     (void)hipFree(c->d_Pinv);
+    (void)hipFree(c->d_moddown_scale);
     (void)hipFree(c->d_tw_fwd);
     (void)hipFree(c->d_tw_inv);
     for (auto& lv : c->levels) {
         (void)hipFree(lv.d_modup);
         (void)hipFree(lv.d_moddown);
         (void)hipFree(lv.d_qlinv);
+        (void)hipFree(lv.d_modup_scale);
     }
     for (auto& kv : c->bconv_cache) (void)hipFree(kv.second);
     delete c;
@@ -204,6 +207,18 @@ extern "C" int ks_ctx_create(ks_ctx** out, uint32_t logN, uint32_t L, uint32_t K
         CK(hipMemcpy(c->d_mod, hm.data(), sizeof(Mod) * M, hipMemcpyHostToDevice));
         CK(hipMemcpy(c->d_ninv, hn.data(), sizeof(double) * M, hipMemcpyHostToDevice));
         CK(hipMemcpy(c->d_Pinv, hP.data(), sizeof(double) * L, hipMemcpyHostToDevice));
+        if (K > 0) {
+            std::vector<double> sc(K);
+            for (uint32_t k = 0; k < K; ++k) {
+                const uint64_t pk = c->mod[L + k];
+                uint64_t prod = 1;
+                for (uint32_t k2 = 0; k2 < K; ++k2)
+                    if (k2 != k) prod = h_mulmod(prod, c->mod[L + k2] % pk, pk);
+                sc[k] = (double)h_mulmod(h_invmod(prod, pk), h_invmod(N % pk, pk), pk);
+            }
+            CK(hipMalloc(&c->d_moddown_scale, sizeof(double) * K));
+            CK(hipMemcpy(c->d_moddown_scale, sc.data(), sizeof(double) * K, hipMemcpyHostToDevice));
+        }
 
         // twiddle tables: W[k] = psi^brv(k), Winv[k] = psi^-brv(k)
         CK(hipMalloc(&c->d_tw_fwd, sizeof(double) * (size_t)M * N));
@@ -253,6 +268,20 @@ extern "C" int ks_ctx_create(ks_ctx** out, uint32_t logN, uint32_t L, uint32_t K
                                 (uint32_t)dst_ids.size());
             }
             lv.n_new = lv.lifted_map.n;
+            {
+                std::vector<double> sc(ell);
+                lv.max_targets = 0;
+                for (uint32_t j = 0; j < lv.ndig; ++j) {
+                    lv.max_targets = std::max(lv.max_targets, plans[j].n_dst);
+                    for (uint32_t i = lv.digit_lo[j]; i < lv.digit_hi[j]; ++i) {
+                        const uint64_t qi = c->mod[i];
+                        const uint64_t dinv = (uint64_t)plans[j].src_inv[i - lv.digit_lo[j]];
+                        sc[i] = (double)h_mulmod(dinv, h_invmod(N % qi, qi), qi);
+                    }
+                }
+                CK(hipMalloc(&lv.d_modup_scale, sizeof(double) * ell));
+                CK(hipMemcpy(lv.d_modup_scale, sc.data(), sizeof(double) * ell, hipMemcpyHostToDevice));
+            }
             CK(hipMalloc(&lv.d_modup, sizeof(BConvPlan) * lv.ndig));
             CK(hipMemcpy(lv.d_modup, plans.data(), sizeof(BConvPlan) * lv.ndig, hipMemcpyHostToDevice));
 

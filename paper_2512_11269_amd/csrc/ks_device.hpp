@@ -31,7 +31,7 @@ __device__ __forceinline__ uint64_t f64_to_u64(double r) {
 }
 
 // a * b mod p as a small signed representative.
-// Requires integer-valued |a| <= 2^40, |b| <= 2^36.  Returns r = a b (mod p) with |r| <= 0.501 p.
+// Requires integer-valued |a| <= 2^43, |b| <= 2^36.  Returns r = a b (mod p) with |r| <= 0.51 p.
 //   h + l = a b exactly (l is the rounding error of the product, recovered by one FMA);
 //   q ~ a b / p; h - q p is an integer below 2^36 in magnitude, so the second FMA is exact too.
 __device__ __forceinline__ double mulmod_lazy(double a, double b, Mod m) {
@@ -42,7 +42,7 @@ __device__ __forceinline__ double mulmod_lazy(double a, double b, Mod m) {
     return r + l;
 }
 
-// Any integer-valued |x| < 2^50 -> representative with |r| <= 0.501 p.
+// Any integer-valued |x| < 2^50 -> representative with |r| <= 0.51 p.
 __device__ __forceinline__ double reduce_lazy(double x, Mod m) {
     double q = __builtin_rint(x * m.pinv);
     return __builtin_fma(-q, m.p, x);
@@ -51,37 +51,46 @@ __device__ __forceinline__ double reduce_lazy(double x, Mod m) {
 // Representative in (-p, p) -> canonical [0, p).
 __device__ __forceinline__ double canon(double r, Mod m) { return r < 0.0 ? r + m.p : r; }
 
-// Sixteen points, four decimation-in-time stages, in registers.  v[k] are 16 points whose mutual
-// distances are 8, 4, 2, 1 times a common stride; the twiddle of local stage u (pair distance 8>>u),
-// group g is W[(base << u) + g], i.e. the sub-tree below heap node `base` of the per-modulus table
-// W[k] = psi^brv(k).  Growth: every stage adds at most 0.501 p to the magnitude.
-__device__ __forceinline__ void radix16_fwd(double (&v)[16], const double* __restrict__ W, uint32_t base, Mod m) {
+// The 15 twiddles of a 16-point register pass: t[2^u + g] = W[(base << u) + g] for local stage u = 0..3 and
+// group g < 2^u, i.e. the sub-tree below heap node `base` of the per-modulus table W[k] = psi^brv(k).
+// Loading them ahead of the butterflies lets their latency overlap the data loads.
+__device__ __forceinline__ void load_twiddles16(double (&t)[16], const double* __restrict__ W, uint32_t base) {
+    t[0] = 0.0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int g = 0; g < (1 << u); ++g) t[(1 << u) + g] = W[(base << u) + g];
+}
+
+// Sixteen points, four decimation-in-time stages, in registers.  v[k] are 16 points whose mutual distances
+// are 8, 4, 2, 1 times a common stride.  Growth: every stage adds at most 0.51 p to the magnitude.
+__device__ __forceinline__ void radix16_fwd(double (&v)[16], const double (&t)[16], Mod m) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int half = 8 >> u;
 #pragma unroll
         for (int g = 0; g < (1 << u); ++g) {
-            const double w = W[(base << u) + g];
+            const double w = t[(1 << u) + g];
 #pragma unroll
             for (int i = 0; i < half; ++i) {
                 const int k = g * 2 * half + i;
-                const double t = mulmod_lazy(v[k + half], w, m);
-                v[k + half] = v[k] - t;
-                v[k] = v[k] + t;
+                const double x = mulmod_lazy(v[k + half], w, m);
+                v[k + half] = v[k] - x;
+                v[k] = v[k] + x;
             }
         }
     }
 }
 
-// Inverse of radix16_fwd up to the factor 16 (decimation in frequency), Winv[k] = psi^-brv(k).
+// Inverse of radix16_fwd up to the factor 16 (decimation in frequency) with t built from Winv[k] = psi^-brv(k).
 // Inputs must satisfy |v| <= p; sums double per stage, so outputs are bounded by 16 p.
-__device__ __forceinline__ void radix16_inv(double (&v)[16], const double* __restrict__ Winv, uint32_t base, Mod m) {
+__device__ __forceinline__ void radix16_inv(double (&v)[16], const double (&t)[16], Mod m) {
 #pragma unroll
     for (int u = 3; u >= 0; --u) {
         const int half = 8 >> u;
 #pragma unroll
         for (int g = 0; g < (1 << u); ++g) {
-            const double w = Winv[(base << u) + g];
+            const double w = t[(1 << u) + g];
 #pragma unroll
             for (int i = 0; i < half; ++i) {
                 const int k = g * 2 * half + i;

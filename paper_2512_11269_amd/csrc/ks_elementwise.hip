@@ -3,20 +3,9 @@
 // evaluation-domain automorphism (a gather).  These are bandwidth-bound: one thread per slot, contiguous
 // 512-byte segments per wavefront, operands shared by both key components are read once ("load reuse").
 #include "ks_internal.hpp"
+#include "ks_tiles.hpp"
 
 namespace ks {
-
-struct DigitRanges {
-    uint32_t ndig;
-    uint32_t lo[kMaxDigits], hi[kMaxDigits];
-};
-
-// Slot permutation of sigma_g on a bit-reversed evaluation vector: slot n holds the point
-// psi^(2 brv(n) + 1); sigma_g(a) evaluated there is a evaluated at that point raised to g.
-__device__ __forceinline__ uint32_t galois_source_slot(uint32_t n, uint32_t g, uint32_t logN) {
-    const uint32_t e = (g * (2u * (__brev(n) >> (32 - logN)) + 1u)) & ((2u << logN) - 1u);
-    return __brev((e - 1u) >> 1) >> (32 - logN);
-}
 
 constexpr int kBatchGroup = 8;  // batch items sharing one read of the key slots
 

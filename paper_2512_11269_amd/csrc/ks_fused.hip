@@ -1,0 +1,265 @@
+// Vertically fused kernels of the key-switching chain (the paper's vertical fusion: dependent limb
+// operations on the same positions stay in registers instead of making a round trip through memory).
+//
+//  * bconv_ntt_cols       base conversion of a digit feeding the column half of the forward transform of
+//                         each target limb: the converted limb never exists in memory in coefficient form.
+//  * rows_inner_product   row half of the forward transform of every raised limb feeding the inner product
+//                         with the key: the raised limb never exists in memory in evaluation form.
+//  * rows_moddown_finish  row half of the forward transform of the converted special part feeding
+//                         (acc - conv) * P^-1 (+ addend).
+//
+// Base conversion is coefficient-wise and the column half touches a fixed set of coefficient positions per
+// tile, so the first fusion is legal; the inner product and the final scale are slot-wise and the row half
+// produces complete slots, so the other two are.
+#include "ks_internal.hpp"
+#include "ks_tiles.hpp"
+
+namespace ks {
+
+// ------------------------------------------------------------------------------------------------
+// y: [poly][..][N] canonical doubles y_i = [x_i N^-1 (D/s_i)^-1]_{s_i} (written by ntt_inv_cols with its
+// scale table).  Each workgroup owns one column tile (4096 positions) and TS targets of one digit: it
+// accumulates sum_i y_i * (D/s_i mod t) lazily for its 16 positions per thread, then runs the column stages
+// of the forward transform modulo t and stores raw doubles.  The sources are re-read by the workgroups of
+// the other target subsets; those reads are served by L2 / the last-level cache.
+// ------------------------------------------------------------------------------------------------
+template <int LOG_R, int TS>
+__global__ __launch_bounds__(256) void bconv_ntt_cols(const double* __restrict__ tw, const BConvPlan* __restrict__ plans,
+                                                      const uint64_t* __restrict__ y, uint64_t y_ps, uint64_t* __restrict__ out,
+                                                      uint64_t out_ps, uint32_t n_subsets) {
+    constexpr uint32_t N = 256u << LOG_R, TILES = LOG_R == 8 ? 16 : 1, TC = 256 / TILES;
+    __shared__ double lds[LOG_R == 8 ? 4096 : 1];
+    const uint32_t tid = threadIdx.x, tile = blockIdx.x;
+    const uint32_t plan_id = blockIdx.y / n_subsets, subset = blockIdx.y - plan_id * n_subsets;
+    const BConvPlan& P = plans[plan_id];
+    const int n_dst = (int)P.n_dst, n_src = (int)P.n_src;
+    const int t0 = (int)subset * TS;
+    if (t0 >= n_dst) return;  // uniform for the whole workgroup
+    const uint64_t* yp = y + (uint64_t)blockIdx.z * y_ps;
+    uint64_t* op = out + (uint64_t)blockIdx.z * out_ps;
+    const uint32_t c = tid & (TC - 1), r0 = tid / TC, col = tile * TC + c;
+
+    double acc[TS][16];
+#pragma unroll
+    for (int tt = 0; tt < TS; ++tt)
+#pragma unroll
+        for (int k = 0; k < 16; ++k) acc[tt][k] = 0.0;
+
+    // software pipeline over the sources: the next source's 16 points are in flight while this one is used
+    double ynext[16];
+    {
+        const uint64_t* src = yp + (uint64_t)P.src_limb[0] * N;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) ynext[k] = load_f64(src + col_row_strided<LOG_R>(r0, k) * 256 + col);
+    }
+#pragma unroll 1
+    for (int i = 0; i < n_src; ++i) {
+        double yv[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) yv[k] = ynext[k];
+        if (i + 1 < n_src) {
+            const uint64_t* src = yp + (uint64_t)P.src_limb[i + 1] * N;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) ynext[k] = load_f64(src + col_row_strided<LOG_R>(r0, k) * 256 + col);
+        }
+#pragma unroll
+        for (int tt = 0; tt < TS; ++tt) {
+            const int t = min(t0 + tt, n_dst - 1);  // a ragged last subset recomputes its last target (stored once)
+            const Mod mt = P.dst_mod[t];
+            const double h = P.hat[t][i];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) acc[tt][k] += mulmod_lazy(yv[k], h, mt);
+        }
+    }
+
+#pragma unroll
+    for (int tt = 0; tt < TS; ++tt) {
+        const int t = t0 + tt;
+        if (t < n_dst) {  // uniform
+            const Mod mt = P.dst_mod[t];
+            const double* W = tw + (size_t)P.dst_mod_id[t] * N;
+            PassTwiddles tws;
+            load_col_twiddles<LOG_R>(tws, W, r0);
+#pragma unroll
+            for (int k = 0; k < 16; ++k) acc[tt][k] = reduce_lazy(acc[tt][k], mt);
+            col_fwd_core<LOG_R>(acc[tt], tws, c, r0, lds, mt);
+            uint64_t* dst = op + (uint64_t)P.dst_limb[t] * N;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) store_f64(dst + col_row_grouped<LOG_R>(r0, k) * 256 + col, acc[tt][k]);
+            if constexpr (LOG_R == 8) __syncthreads();  // the exchange buffer is reused by the next target
+        }
+    }
+}
+
+void launch_bconv_ntt_cols(const ks_ctx* c, const BConvPlan* d_plans, uint32_t n_plans, uint32_t max_targets,
+                           uint32_t limbs_moved_per_poly, const uint64_t* y, uint64_t y_ps, uint64_t* out, uint64_t out_ps,
+                           uint32_t n_polys, hipStream_t s) {
+    if (n_polys == 0 || n_plans == 0) return;
+    constexpr int TS = 4;
+    const uint32_t n_subsets = (max_targets + TS - 1) / TS;
+    ProfScope ps("bconv_ntt_cols", (double)limbs_moved_per_poly * n_polys * c->N * 8.0, s);
+    if (c->logN == 16)
+        hipLaunchKernelGGL((bconv_ntt_cols<8, TS>), dim3(16, n_plans * n_subsets, n_polys), dim3(256), 0, s, c->d_tw_fwd, d_plans, y,
+                           y_ps, out, out_ps, n_subsets);
+    else
+        hipLaunchKernelGGL((bconv_ntt_cols<4, TS>), dim3(1, n_plans * n_subsets, n_polys), dim3(256), 0, s, c->d_tw_fwd, d_plans, y,
+                           y_ps, out, out_ps, n_subsets);
+}
+
+// ------------------------------------------------------------------------------------------------
+// acc[b][c][pos] = sum_j d~_j[pos] * key[j][c][m(pos)].  For pos inside digit j, d~_j[pos] is the input limb
+// itself; otherwise it is the raised limb, whose row half of the forward transform is done here.
+// One wavefront = four rows of one limb position; it walks the digits, so d~ is read once and feeds both key
+// components (load reuse), and the accumulators are reduced and written once.
+// ------------------------------------------------------------------------------------------------
+template <int LOG_R>
+__global__ __launch_bounds__(64) void rows_inner_product(const double* __restrict__ tw, const Mod* __restrict__ mods, DigitRanges dg,
+                                                         uint32_t ell, uint32_t E, uint32_t L, uint32_t M,
+                                                         const uint64_t* __restrict__ d, uint64_t d_ps,
+                                                         const uint64_t* __restrict__ lifted, const uint64_t* __restrict__ evk,
+                                                         uint64_t* __restrict__ acc) {
+    constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R;
+    __shared__ double lds[4 * kRowPitch];
+    const uint32_t tid = threadIdx.x, rg = blockIdx.x, pos = blockIdx.y, b = blockIdx.z;
+    const uint32_t mid = pos < ell ? pos : L + (pos - ell);
+    const Mod m = mods[mid];
+    const double* W = tw + (size_t)mid * N;
+    const uint32_t j0 = tid & 15, rr = tid >> 4, row = rg * 4 + rr;
+    const uint32_t off = row * 256 + j0;
+    double a0[16], a1[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) a0[k] = a1[k] = 0.0;
+    PassTwiddles t;
+    load_row_twiddles(t, W, R + row, j0);
+
+#pragma unroll 1
+    for (uint32_t j = 0; j < dg.ndig; ++j) {
+        const bool own = pos >= dg.lo[j] && pos < dg.hi[j];  // uniform
+        const uint64_t* key0 = evk + ((uint64_t)(j * 2 + 0) * M + mid) * N + off;
+        const uint64_t* key1 = evk + ((uint64_t)(j * 2 + 1) * M + mid) * N + off;
+        // issue every load of this digit up front (the key slots are independent of the transform below)
+        double x[16], k0[16], k1[16];
+        const uint64_t* src = own ? d + (uint64_t)b * d_ps + (uint64_t)pos * N + off
+                                  : lifted + (((uint64_t)b * dg.ndig + j) * E + pos) * N + off;
+        uint64_t raw[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) raw[k] = src[16 * k];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) k0[k] = u64_to_f64(key0[16 * k]);
+#pragma unroll
+        for (int k = 0; k < 16; ++k) k1[k] = u64_to_f64(key1[16 * k]);
+        if (own) {
+#pragma unroll
+            for (int k = 0; k < 16; ++k) x[k] = u64_to_f64(raw[k]);
+        } else {
+#pragma unroll
+            for (int k = 0; k < 16; ++k) x[k] = __longlong_as_double((long long)raw[k]);
+            row_fwd_core(x, t, j0, lds + rr * kRowPitch, m);
+        }
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            a0[k] += mulmod_lazy(x[k], k0[k], m);
+            a1[k] += mulmod_lazy(x[k], k1[k], m);
+        }
+    }
+    uint64_t* o0 = acc + (((uint64_t)b * 2 + 0) * E + pos) * N + off;
+    uint64_t* o1 = acc + (((uint64_t)b * 2 + 1) * E + pos) * N + off;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        o0[16 * k] = f64_to_u64(canon(reduce_lazy(a0[k], m), m));
+        o1[16 * k] = f64_to_u64(canon(reduce_lazy(a1[k], m), m));
+    }
+}
+
+void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, const uint64_t* lifted,
+                               const uint64_t* evk, uint64_t* acc, uint32_t batch, hipStream_t s) {
+    if (batch == 0) return;
+    DigitRanges dg;
+    dg.ndig = lv.ndig;
+    for (uint32_t j = 0; j < kMaxDigits; ++j) {
+        dg.lo[j] = j < lv.ndig ? lv.digit_lo[j] : 0;
+        dg.hi[j] = j < lv.ndig ? lv.digit_hi[j] : 0;
+    }
+    // reads: every raised digit limb per ciphertext and the key (once per call); writes: both accumulators
+    ProfScope ps("rows_inner_product", ((double)batch * (lv.ndig + 2) * lv.E + 2.0 * lv.ndig * lv.E) * c->N * 8.0, s);
+    if (c->logN == 16)
+        hipLaunchKernelGGL(rows_inner_product<8>, dim3(64, lv.E, batch), dim3(64), 0, s, c->d_tw_fwd, c->d_mod, dg, lv.ell, lv.E,
+                           c->L, c->M, d, d_ps, lifted, evk, acc);
+    else
+        hipLaunchKernelGGL(rows_inner_product<4>, dim3(4, lv.E, batch), dim3(64), 0, s, c->d_tw_fwd, c->d_mod, dg, lv.ell, lv.E,
+                           c->L, c->M, d, d_ps, lifted, evk, acc);
+}
+
+// ------------------------------------------------------------------------------------------------
+// out[b][comp][i] = (acc[b][comp][i] - NTT_rows(conv[b][comp][i])) * P^-1 (+ addend), canonical.
+// ------------------------------------------------------------------------------------------------
+template <int LOG_R, bool GATHER>
+__global__ __launch_bounds__(64) void rows_moddown_finish(const double* __restrict__ tw, const Mod* __restrict__ mods,
+                                                          const double* __restrict__ Pinv, uint32_t ell, uint32_t E,
+                                                          const uint64_t* __restrict__ acc, const uint64_t* __restrict__ conv,
+                                                          uint64_t* __restrict__ out, uint64_t out_bs,
+                                                          const uint64_t* __restrict__ addend, uint64_t addend_bs,
+                                                          uint32_t addend_comps, uint32_t galois) {
+    constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R, LOGN = LOG_R + 8;
+    __shared__ double lds[4 * kRowPitch];
+    const uint32_t tid = threadIdx.x, rg = blockIdx.x, i = blockIdx.y, b = blockIdx.z >> 1, comp = blockIdx.z & 1;
+    const Mod m = mods[i];
+    const double* W = tw + (size_t)i * N;
+    const double pinv = Pinv[i];
+    const uint32_t j0 = tid & 15, rr = tid >> 4, row = rg * 4 + rr;
+    const uint32_t off = row * 256 + j0;
+    const uint64_t* src = conv + (((uint64_t)b * 2 + comp) * ell + i) * N + off;
+    const uint64_t* ap = acc + (((uint64_t)b * 2 + comp) * E + i) * N + off;
+    uint64_t* op = out + (uint64_t)b * out_bs + ((uint64_t)comp * ell + i) * N + off;
+    const bool add = addend != nullptr && comp < addend_comps;
+    const uint64_t* adp = add ? addend + (uint64_t)b * addend_bs + ((uint64_t)comp * ell + i) * N : nullptr;
+    // issue every load up front: the accumulator (and addend) slots do not depend on the transform
+    double w[16], a[16], ad[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) w[k] = load_f64(src + 16 * k);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) a[k] = u64_to_f64(ap[16 * k]);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        ad[k] = 0.0;
+        if (add) {
+            const uint32_t n = off + 16 * k;
+            ad[k] = u64_to_f64(adp[GATHER ? galois_source_slot(n, galois, LOGN) : n]);
+        }
+    }
+    PassTwiddles t;
+    load_row_twiddles(t, W, R + row, j0);
+    row_fwd_core(w, t, j0, lds + rr * kRowPitch, m);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const double r = reduce_lazy(mulmod_lazy(a[k] - w[k], pinv, m) + ad[k], m);
+        op[16 * k] = f64_to_u64(canon(r, m));
+    }
+}
+
+void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t* acc, const uint64_t* conv, uint64_t* out,
+                                uint64_t out_bs, const uint64_t* addend, uint64_t addend_bs, uint32_t addend_comps,
+                                uint32_t galois, uint32_t batch, hipStream_t s) {
+    if (batch == 0) return;
+    ProfScope ps("rows_moddown_finish", (double)batch * lv.ell * (6 + (addend ? addend_comps : 0)) * c->N * 8.0, s);
+    const dim3 block(64);
+    if (c->logN == 16) {
+        const dim3 grid(64, lv.ell, batch * 2);
+        if (galois == 1)
+            hipLaunchKernelGGL((rows_moddown_finish<8, false>), grid, block, 0, s, c->d_tw_fwd, c->d_mod, c->d_Pinv, lv.ell, lv.E, acc,
+                               conv, out, out_bs, addend, addend_bs, addend_comps, galois);
+        else
+            hipLaunchKernelGGL((rows_moddown_finish<8, true>), grid, block, 0, s, c->d_tw_fwd, c->d_mod, c->d_Pinv, lv.ell, lv.E, acc,
+                               conv, out, out_bs, addend, addend_bs, addend_comps, galois);
+    } else {
+        const dim3 grid(4, lv.ell, batch * 2);
+        if (galois == 1)
+            hipLaunchKernelGGL((rows_moddown_finish<4, false>), grid, block, 0, s, c->d_tw_fwd, c->d_mod, c->d_Pinv, lv.ell, lv.E, acc,
+                               conv, out, out_bs, addend, addend_bs, addend_comps, galois);
+        else
+            hipLaunchKernelGGL((rows_moddown_finish<4, true>), grid, block, 0, s, c->d_tw_fwd, c->d_mod, c->d_Pinv, lv.ell, lv.E, acc,
+                               conv, out, out_bs, addend, addend_bs, addend_comps, galois);
+    }
+}
+
+}  // namespace ks

@@ -28,12 +28,13 @@ struct LimbMap {
 // Constants of one fast base conversion, read by the kernel through uniform (scalar) loads.
 struct BConvPlan {
     uint32_t n_src, n_dst;
-    uint16_t src_limb[kMaxSrc];  // limb index inside the input bundle
-    uint16_t dst_limb[kMaxDst];  // limb index inside the output bundle
+    uint32_t src_limb[kMaxSrc];  // limb index inside the input bundle (32-bit fields: scalar loads)
+    uint32_t dst_limb[kMaxDst];  // limb index inside the output bundle
     Mod src_mod[kMaxSrc];
     double src_inv[kMaxSrc];     // (D / s_i)^-1 mod s_i
     Mod dst_mod[kMaxDst];
-    double hat[kMaxSrc][kMaxDst];  // (D / s_i) mod t
+    uint32_t dst_mod_id[kMaxDst];  // modulus id of each target (selects its twiddle table)
+    double hat[kMaxDst][kMaxSrc];  // hat[t][i] = (D / s_i) mod t; the sources of one target are contiguous
 };
 
 // Everything the key-switching pipeline needs at one level ell.
@@ -47,6 +48,8 @@ struct Level {
     LimbMap q_map;                         // limbs 0..ell-1, modulus id = limb index
     uint32_t digit_lo[kMaxDigits], digit_hi[kMaxDigits];
     double* d_qlinv = nullptr;             // [ell-1] device: q_{ell-1}^-1 mod q_i (rescale)
+    double* d_modup_scale = nullptr;       // [ell] device: N^-1 (D_j / q_i)^-1 mod q_i, j = digit of limb i
+    uint32_t max_targets = 0;              // largest target count of a ModUp digit
 };
 
 }  // namespace ks
@@ -58,6 +61,7 @@ struct ks_ctx {
     ks::Mod* d_mod = nullptr;             // [M]
     double* d_ninv = nullptr;             // [M]  N^-1 mod m
     double* d_Pinv = nullptr;             // [L]  P^-1 mod q_i
+    double* d_moddown_scale = nullptr;    // [K]  N^-1 (P / p_k)^-1 mod p_k
     double* d_tw_fwd = nullptr;           // [M][N] psi^brv(k)
     double* d_tw_inv = nullptr;           // [M][N] psi^-brv(k)
     std::vector<ks::Level> levels;        // index ell-1
@@ -99,6 +103,27 @@ struct XformIO {
 void launch_ntt_fwd(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipStream_t s);
 // inverse: evaluation (canonical u64) -> coefficient (canonical u64)
 void launch_ntt_inv(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipStream_t s);
+// The two halves of each transform on their own (the fused pipeline replaces some halves by fused kernels).
+void launch_ntt_fwd_cols(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipStream_t s);
+void launch_ntt_fwd_rows(const ks_ctx* c, const LimbMap& map, uint64_t* data, uint64_t ps_words, uint32_t n_polys, hipStream_t s);
+void launch_ntt_inv_rows(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipStream_t s);
+// scale_tab: multiplier applied with the final reduction, indexed by the limb's position in `map` (scale_by_idx)
+// or by its modulus id; out_f64: leave the canonical result as a double for a following fused kernel.
+void launch_ntt_inv_cols(const ks_ctx* c, const LimbMap& map, uint64_t* data, uint64_t ps_words, uint32_t n_polys,
+                         const double* scale_tab, bool scale_by_idx, bool out_f64, hipStream_t s);
+
+// Fused base conversion + column half of the forward transform.  y: pre-scaled canonical doubles
+// y_i = [x_i N^-1 (D/s_i)^-1]; out: raw doubles ready for the row half.  One plan per blockIdx.y group.
+void launch_bconv_ntt_cols(const ks_ctx* c, const BConvPlan* d_plans, uint32_t n_plans, uint32_t max_targets,
+                           uint32_t limbs_moved_per_poly, const uint64_t* y, uint64_t y_ps, uint64_t* out, uint64_t out_ps,
+                           uint32_t n_polys, hipStream_t s);
+// Fused row half of the forward transform of the raised digits + inner product with the key.
+void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, const uint64_t* lifted,
+                               const uint64_t* evk, uint64_t* acc, uint32_t batch, hipStream_t s);
+// Fused row half of the forward transform of the converted limbs + (acc - conv) P^-1 (+ addend).
+void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t* acc, const uint64_t* conv, uint64_t* out,
+                                uint64_t out_batch_stride, const uint64_t* addend, uint64_t addend_batch_stride,
+                                uint32_t addend_comps, uint32_t galois, uint32_t batch, hipStream_t s);
 
 void launch_bconv(const ks_ctx* c, const BConvPlan* d_plans, uint32_t limbs_moved_per_poly, uint32_t n_plans,
                   const uint64_t* in, uint64_t in_poly_stride, uint64_t* out, uint64_t out_poly_stride,

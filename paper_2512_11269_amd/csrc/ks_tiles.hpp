@@ -1,0 +1,121 @@
+// Tile-level pieces of the two-phase transform, shared by the plain NTT kernels and the fused ones.
+//
+// A limb is an R x 256 matrix (R = N / 256).  "Row" pieces work on contiguous 256-point rows, one
+// wavefront owning four rows (16 lanes per row, 16 points per lane); "column" pieces work on a tile of 16
+// columns x 256 rows owned by a 256-thread workgroup.  Twiddles come from the per-modulus heap-ordered
+// table W[k] = psi^brv(k): the forward stage with 2^s blocks uses W[2^s + block].
+#pragma once
+#include "ks_device.hpp"
+
+namespace ks {
+
+// Digit partition handed to kernels by value.
+struct DigitRanges {
+    uint32_t ndig;
+    uint32_t lo[8], hi[8];
+};
+
+// Slot permutation of sigma_g (X -> X^g) on a bit-reversed evaluation vector: slot n holds the point
+// psi^(2 brv(n) + 1); sigma_g(a) evaluated there is a evaluated at that point raised to g.
+__device__ __forceinline__ uint32_t galois_source_slot(uint32_t n, uint32_t g, uint32_t logN) {
+    const uint32_t e = (g * (2u * (__brev(n) >> (32 - logN)) + 1u)) & ((2u << logN) - 1u);
+    return __brev((e - 1u) >> 1) >> (32 - logN);
+}
+
+constexpr int kRowPitch = 272;  // 256 points + 1 pad per 16: the transposed LDS accesses hit distinct banks
+
+__device__ __forceinline__ double load_f64(const uint64_t* p) { return *reinterpret_cast<const double*>(p); }
+__device__ __forceinline__ void store_f64(uint64_t* p, double v) { *reinterpret_cast<double*>(p) = v; }
+
+// Twiddles of the two register passes of a tile core, loaded ahead of the butterflies.
+struct PassTwiddles {
+    double a[16], b[16];
+};
+// rows: node = R + row; lane j0 owns points 16 j0 .. 16 j0 + 15 in the second pass
+__device__ __forceinline__ void load_row_twiddles(PassTwiddles& t, const double* __restrict__ W, uint32_t node, uint32_t j0) {
+    load_twiddles16(t.a, W, node);
+    load_twiddles16(t.b, W, node * 16 + j0);
+}
+// columns: heap node 1 for the first pass, 16 + r0 for the second (LOG_R = 8 only)
+template <int LOG_R>
+__device__ __forceinline__ void load_col_twiddles(PassTwiddles& t, const double* __restrict__ W, uint32_t r0) {
+    load_twiddles16(t.a, W, 1);
+    if constexpr (LOG_R == 8) load_twiddles16(t.b, W, 16 + r0);
+}
+
+// Last 8 forward stages of one row.  in: v[k] = point j0 + 16 k of the row, lazy with |v| <= 8 p.
+// out: v[k] = transformed point j0 + 16 k, lazy with |v| <= |in| + 4.1 p.
+// lrow: this row's kRowPitch doubles of LDS, shared by the row's 16 lanes (all in one wavefront).
+__device__ __forceinline__ void row_fwd_core(double (&v)[16], const PassTwiddles& t, uint32_t j0, double* lrow, Mod m) {
+    radix16_fwd(v, t.a, m);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) lrow[j0 + 17 * k] = v[k];
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = lrow[17 * j0 + k];
+    radix16_fwd(v, t.b, m);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) lrow[17 * j0 + k] = v[k];
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = lrow[j0 + 17 * k];
+}
+
+// First 8 inverse stages of one row (t built from the inverse table).  in: v[k] = point j0 + 16 k, |v| <= p.
+// out: same layout, |v| <= 0.51 p.
+__device__ __forceinline__ void row_inv_core(double (&v)[16], const PassTwiddles& t, uint32_t j0, double* lrow, Mod m) {
+#pragma unroll
+    for (int k = 0; k < 16; ++k) lrow[j0 + 17 * k] = v[k];
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = lrow[17 * j0 + k];
+    radix16_inv(v, t.b, m);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) lrow[17 * j0 + k] = reduce_lazy(v[k], m);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = lrow[j0 + 17 * k];
+    radix16_inv(v, t.a, m);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = reduce_lazy(v[k], m);
+}
+
+// First log2(R) forward stages on a column tile.
+//   LOG_R = 8: 256 threads, thread (c = tid & 15, r0 = tid >> 4); in: v[k] = row r0 + 16 k, out: v[k] = row 16 r0 + k;
+//              lds: 4096 doubles.  LOG_R = 4: one register pass, rows k in and out, lds unused.
+// Growth: at most 0.51 p per stage.
+template <int LOG_R>
+__device__ __forceinline__ void col_fwd_core(double (&v)[16], const PassTwiddles& t, uint32_t c, uint32_t r0, double* lds, Mod m) {
+    radix16_fwd(v, t.a, m);
+    if constexpr (LOG_R == 8) {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) lds[(r0 + 16 * k) * 16 + c] = v[k];
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 16; ++k) v[k] = lds[(16 * r0 + k) * 16 + c];
+        radix16_fwd(v, t.b, m);
+    }
+}
+
+// Last log2(R) inverse stages on a column tile (no N^-1 factor).  LOG_R = 8: in rows 16 r0 + k, out rows r0 + 16 k.
+// in: |v| <= p.  out: |v| <= 16 p.
+template <int LOG_R>
+__device__ __forceinline__ void col_inv_core(double (&v)[16], const PassTwiddles& t, uint32_t c, uint32_t r0, double* lds, Mod m) {
+    if constexpr (LOG_R == 8) {
+        radix16_inv(v, t.b, m);
+#pragma unroll
+        for (int k = 0; k < 16; ++k) lds[(16 * r0 + k) * 16 + c] = reduce_lazy(v[k], m);
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 16; ++k) v[k] = lds[(r0 + 16 * k) * 16 + c];
+    }
+    radix16_inv(v, t.a, m);
+}
+
+// Row index of v[k] before / after the column cores, and the first column of the tile.
+template <int LOG_R>
+__device__ __forceinline__ uint32_t col_row_strided(uint32_t r0, int k) { return LOG_R == 8 ? r0 + 16 * k : (uint32_t)k; }
+template <int LOG_R>
+__device__ __forceinline__ uint32_t col_row_grouped(uint32_t r0, int k) { return LOG_R == 8 ? 16 * r0 + k : (uint32_t)k; }
+
+}  // namespace ks
