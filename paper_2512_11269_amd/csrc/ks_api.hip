@@ -51,9 +51,11 @@ void mod_up(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, 
 // Division by P of both accumulators, optional addend: INTT of the special limbs (in place), fused base
 // conversion + column half, fused row half + (acc - conv) P^-1.
 void mod_down(const ks_ctx* c, const Level& lv, uint64_t* acc, uint64_t* conv, uint64_t* out, uint64_t out_bs,
-              const uint64_t* addend, uint64_t addend_bs, uint32_t addend_comps, uint32_t galois, uint32_t bc, hipStream_t s) {
+              const uint64_t* addend, uint64_t addend_bs, uint32_t addend_comps, uint32_t galois, uint32_t bc,
+              bool special_rows_done, hipStream_t s) {
     const uint64_t N = c->N, acc_ps = (uint64_t)lv.E * N, conv_ps = (uint64_t)lv.ell * N;
-    launch_ntt_inv_rows(c, lv.special_map, XformIO{acc, acc, acc_ps, acc_ps, 2 * bc}, s);
+    // the fused inner product already ran the row half of the inverse transform on the special limbs
+    if (!special_rows_done) launch_ntt_inv_rows(c, lv.special_map, XformIO{acc, acc, acc_ps, acc_ps, 2 * bc}, s);
     launch_ntt_inv_cols(c, lv.special_map, acc, acc_ps, 2 * bc, c->d_moddown_scale, true, true, s);
     launch_bconv_ntt_cols(c, lv.d_moddown, 1, lv.ell, c->K + lv.ell, acc, acc_ps, conv, conv_ps, 2 * bc, s);
     launch_rows_moddown_finish(c, lv, acc, conv, out, out_bs, addend, addend_bs, addend_comps, galois, bc, s);
@@ -192,7 +194,7 @@ extern "C" int ks_keyswitch(const ks_ctx* c, const uint64_t* d, uint32_t ell, co
         const uint64_t* dc = d + (uint64_t)b0 * d_ps;
         mod_up(c, lv, dc, d_ps, coeff, lifted, bc, false, s);
         launch_rows_inner_product(c, lv, dc, d_ps, lifted, evk, acc, bc, s);
-        mod_down(c, lv, acc, conv, out + (uint64_t)b0 * out_bs, out_bs, nullptr, 0, 0, 1, bc, s);
+        mod_down(c, lv, acc, conv, out + (uint64_t)b0 * out_bs, out_bs, nullptr, 0, 0, 1, bc, true, s);
     }
     return finish("ks_keyswitch");
 }
@@ -225,7 +227,7 @@ extern "C" int ks_rotate_hoisted(const ks_ctx* c, const uint64_t* ct, uint32_t e
         for (uint32_t r = 0; r < n_rot; ++r) {
             uint64_t* o = out + (uint64_t)b0 * out_bs + (uint64_t)r * 2 * ell * N;
             launch_inner_product(c, lv, c1, ct_bs, lifted, rot_keys[r], acc, bc, galois[r], s);
-            mod_down(c, lv, acc, conv, o, out_bs, c0, ct_bs, 1, galois[r], bc, s);
+            mod_down(c, lv, acc, conv, o, out_bs, c0, ct_bs, 1, galois[r], bc, false, s);
         }
     }
     return finish("ks_rotate_hoisted");
@@ -261,7 +263,7 @@ extern "C" int hmult_relin_rescale(const ks_ctx* c, const uint64_t* cta, const u
         const uint64_t* d2 = td + 2ull * ell * N;
         mod_up(c, lv, d2, td_bs, coeff, lifted, bc, false, s);
         launch_rows_inner_product(c, lv, d2, td_bs, lifted, rlk, acc, bc, s);
-        mod_down(c, lv, acc, conv, sum, ct_bs, td, td_bs, 2, 1, bc, s);
+        mod_down(c, lv, acc, conv, sum, ct_bs, td, td_bs, 2, 1, bc, true, s);
         // rescale both components: inverse transform of the last limb, centred remainder to every q_i, forward
         // transform, subtract and divide
         launch_ntt_inv(c, one, XformIO{sum + (uint64_t)(ell - 1) * N, last, (uint64_t)ell * N, N, 2 * bc}, s);

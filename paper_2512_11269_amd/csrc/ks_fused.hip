@@ -11,6 +11,8 @@
 // Base conversion is coefficient-wise and the column half touches a fixed set of coefficient positions per
 // tile, so the first fusion is legal; the inner product and the final scale are slot-wise and the row half
 // produces complete slots, so the other two are.
+#include <stdlib.h>
+
 #include "ks_internal.hpp"
 #include "ks_tiles.hpp"
 
@@ -45,44 +47,63 @@ __global__ __launch_bounds__(256) void bconv_ntt_cols(const double* __restrict__
 #pragma unroll
         for (int k = 0; k < 16; ++k) acc[tt][k] = 0.0;
 
-    // software pipeline over the sources: the next source's 16 points are in flight while this one is used
-    double ynext[16];
+    // Per-target constants.  The conversion factors are fetched with per-lane (vector) loads on purpose: they
+    // then ride the same wait counter as the prefetched source points instead of stalling on scalar-load
+    // latency once per source and target.  `lane0` is zero but opaque to the compiler.
+    const uint32_t lane0 = tid >> 10;
+    Mod mt[TS];
+    const double* hat_row[TS];
+#pragma unroll
+    for (int tt = 0; tt < TS; ++tt) {
+        const int t = min(t0 + tt, n_dst - 1);  // a ragged last subset recomputes its last target (stored once)
+        mt[tt] = P.dst_mod[t];
+        hat_row[tt] = &P.hat[t][0] + lane0;
+    }
+
+    // software pipeline over the sources: the next source's 16 points and factors are in flight while this
+    // one's are used
+    double ynext[16], hnext[TS];
     {
         const uint64_t* src = yp + (uint64_t)P.src_limb[0] * N;
 #pragma unroll
         for (int k = 0; k < 16; ++k) ynext[k] = load_f64(src + col_row_strided<LOG_R>(r0, k) * 256 + col);
+#pragma unroll
+        for (int tt = 0; tt < TS; ++tt) hnext[tt] = hat_row[tt][0];
     }
+    // twiddles of the first target's column transform, also ahead of time
+    PassTwiddles tws;
+    load_col_twiddles<LOG_R>(tws, tw + (size_t)P.dst_mod_id[t0] * N + lane0, r0);
+
 #pragma unroll 1
     for (int i = 0; i < n_src; ++i) {
-        double yv[16];
+        double yv[16], hv[TS];
 #pragma unroll
         for (int k = 0; k < 16; ++k) yv[k] = ynext[k];
+#pragma unroll
+        for (int tt = 0; tt < TS; ++tt) hv[tt] = hnext[tt];
         if (i + 1 < n_src) {
             const uint64_t* src = yp + (uint64_t)P.src_limb[i + 1] * N;
 #pragma unroll
             for (int k = 0; k < 16; ++k) ynext[k] = load_f64(src + col_row_strided<LOG_R>(r0, k) * 256 + col);
+#pragma unroll
+            for (int tt = 0; tt < TS; ++tt) hnext[tt] = hat_row[tt][i + 1];
         }
 #pragma unroll
-        for (int tt = 0; tt < TS; ++tt) {
-            const int t = min(t0 + tt, n_dst - 1);  // a ragged last subset recomputes its last target (stored once)
-            const Mod mt = P.dst_mod[t];
-            const double h = P.hat[t][i];
+        for (int tt = 0; tt < TS; ++tt)
 #pragma unroll
-            for (int k = 0; k < 16; ++k) acc[tt][k] += mulmod_lazy(yv[k], h, mt);
-        }
+            for (int k = 0; k < 16; ++k) acc[tt][k] += mulmod_lazy(yv[k], hv[tt], mt[tt]);
     }
 
 #pragma unroll
     for (int tt = 0; tt < TS; ++tt) {
         const int t = t0 + tt;
         if (t < n_dst) {  // uniform
-            const Mod mt = P.dst_mod[t];
-            const double* W = tw + (size_t)P.dst_mod_id[t] * N;
-            PassTwiddles tws;
-            load_col_twiddles<LOG_R>(tws, W, r0);
+            PassTwiddles cur = tws;
+            if (tt + 1 < TS && t + 1 < n_dst)  // next target's twiddles travel while this target is transformed
+                load_col_twiddles<LOG_R>(tws, tw + (size_t)P.dst_mod_id[t + 1] * N + lane0, r0);
 #pragma unroll
-            for (int k = 0; k < 16; ++k) acc[tt][k] = reduce_lazy(acc[tt][k], mt);
-            col_fwd_core<LOG_R>(acc[tt], tws, c, r0, lds, mt);
+            for (int k = 0; k < 16; ++k) acc[tt][k] = reduce_lazy(acc[tt][k], mt[tt]);
+            col_fwd_core<LOG_R>(acc[tt], cur, c, r0, lds, mt[tt]);
             uint64_t* dst = op + (uint64_t)P.dst_limb[t] * N;
 #pragma unroll
             for (int k = 0; k < 16; ++k) store_f64(dst + col_row_grouped<LOG_R>(r0, k) * 256 + col, acc[tt][k]);
@@ -95,15 +116,31 @@ void launch_bconv_ntt_cols(const ks_ctx* c, const BConvPlan* d_plans, uint32_t n
                            uint32_t limbs_moved_per_poly, const uint64_t* y, uint64_t y_ps, uint64_t* out, uint64_t out_ps,
                            uint32_t n_polys, hipStream_t s) {
     if (n_polys == 0 || n_plans == 0) return;
-    constexpr int TS = 4;
-    const uint32_t n_subsets = (max_targets + TS - 1) / TS;
+    // Targets per workgroup: fewer targets = more workgroups (small launches need them to fill 256 compute units)
+    // but more re-reads of the sources from cache.  Pick the largest TS that still gives every compute unit about
+    // four workgroups; KS_BCONV_TS overrides it for experiments.
+    const uint32_t tiles = c->logN == 16 ? 16 : 1;
+    int ts = 4;
+    while (ts > 1 && (uint64_t)tiles * n_plans * ((max_targets + ts - 1) / ts) * n_polys < 1024) ts >>= 1;
+    if (const char* e = getenv("KS_BCONV_TS")) {
+        const int v = atoi(e);
+        if (v == 1 || v == 2 || v == 4) ts = v;
+    }
+    const uint32_t n_subsets = (max_targets + ts - 1) / ts;
+    const dim3 grid(tiles, n_plans * n_subsets, n_polys), block(256);
     ProfScope ps("bconv_ntt_cols", (double)limbs_moved_per_poly * n_polys * c->N * 8.0, s);
-    if (c->logN == 16)
-        hipLaunchKernelGGL((bconv_ntt_cols<8, TS>), dim3(16, n_plans * n_subsets, n_polys), dim3(256), 0, s, c->d_tw_fwd, d_plans, y,
-                           y_ps, out, out_ps, n_subsets);
-    else
-        hipLaunchKernelGGL((bconv_ntt_cols<4, TS>), dim3(1, n_plans * n_subsets, n_polys), dim3(256), 0, s, c->d_tw_fwd, d_plans, y,
-                           y_ps, out, out_ps, n_subsets);
+#define KS_LAUNCH_BCONV(LOGR, TSV) \
+    hipLaunchKernelGGL((bconv_ntt_cols<LOGR, TSV>), grid, block, 0, s, c->d_tw_fwd, d_plans, y, y_ps, out, out_ps, n_subsets)
+    if (c->logN == 16) {
+        if (ts == 4) KS_LAUNCH_BCONV(8, 4);
+        else if (ts == 2) KS_LAUNCH_BCONV(8, 2);
+        else KS_LAUNCH_BCONV(8, 1);
+    } else {
+        if (ts == 4) KS_LAUNCH_BCONV(4, 4);
+        else if (ts == 2) KS_LAUNCH_BCONV(4, 2);
+        else KS_LAUNCH_BCONV(4, 1);
+    }
+#undef KS_LAUNCH_BCONV
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -113,7 +150,8 @@ void launch_bconv_ntt_cols(const ks_ctx* c, const BConvPlan* d_plans, uint32_t n
 // components (load reuse), and the accumulators are reduced and written once.
 // ------------------------------------------------------------------------------------------------
 template <int LOG_R>
-__global__ __launch_bounds__(64) void rows_inner_product(const double* __restrict__ tw, const Mod* __restrict__ mods, DigitRanges dg,
+__global__ __launch_bounds__(64) void rows_inner_product(const double* __restrict__ tw, const double* __restrict__ twi,
+                                                         const Mod* __restrict__ mods, DigitRanges dg,
                                                          uint32_t ell, uint32_t E, uint32_t L, uint32_t M,
                                                          const uint64_t* __restrict__ d, uint64_t d_ps,
                                                          const uint64_t* __restrict__ lifted, const uint64_t* __restrict__ evk,
@@ -166,8 +204,27 @@ __global__ __launch_bounds__(64) void rows_inner_product(const double* __restric
     uint64_t* o1 = acc + (((uint64_t)b * 2 + 1) * E + pos) * N + off;
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
-        o0[16 * k] = f64_to_u64(canon(reduce_lazy(a0[k], m), m));
-        o1[16 * k] = f64_to_u64(canon(reduce_lazy(a1[k], m), m));
+        a0[k] = reduce_lazy(a0[k], m);
+        a1[k] = reduce_lazy(a1[k], m);
+    }
+    if (pos < ell) {  // uniform: ciphertext limbs are kept in evaluation domain for the final subtract-and-scale
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            o0[16 * k] = f64_to_u64(canon(a0[k], m));
+            o1[16 * k] = f64_to_u64(canon(a1[k], m));
+        }
+    } else {
+        // Special limbs go straight into ModDown: the row half of their inverse transform works on the very
+        // rows this wavefront holds, so it is done here and raw doubles are handed to the column half.
+        PassTwiddles ti;
+        load_row_twiddles(ti, twi + (size_t)mid * N, R + row, j0);
+        row_inv_core(a0, ti, j0, lds + rr * kRowPitch, m);
+        row_inv_core(a1, ti, j0, lds + rr * kRowPitch, m);
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            store_f64(o0 + 16 * k, a0[k]);
+            store_f64(o1 + 16 * k, a1[k]);
+        }
     }
 }
 
@@ -183,10 +240,10 @@ void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const uint64_t*
     // reads: every raised digit limb per ciphertext and the key (once per call); writes: both accumulators
     ProfScope ps("rows_inner_product", ((double)batch * (lv.ndig + 2) * lv.E + 2.0 * lv.ndig * lv.E) * c->N * 8.0, s);
     if (c->logN == 16)
-        hipLaunchKernelGGL(rows_inner_product<8>, dim3(64, lv.E, batch), dim3(64), 0, s, c->d_tw_fwd, c->d_mod, dg, lv.ell, lv.E,
+        hipLaunchKernelGGL(rows_inner_product<8>, dim3(64, lv.E, batch), dim3(64), 0, s, c->d_tw_fwd, c->d_tw_inv, c->d_mod, dg, lv.ell, lv.E,
                            c->L, c->M, d, d_ps, lifted, evk, acc);
     else
-        hipLaunchKernelGGL(rows_inner_product<4>, dim3(4, lv.E, batch), dim3(64), 0, s, c->d_tw_fwd, c->d_mod, dg, lv.ell, lv.E,
+        hipLaunchKernelGGL(rows_inner_product<4>, dim3(4, lv.E, batch), dim3(64), 0, s, c->d_tw_fwd, c->d_tw_inv, c->d_mod, dg, lv.ell, lv.E,
                            c->L, c->M, d, d_ps, lifted, evk, acc);
 }
 
