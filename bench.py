@@ -31,7 +31,15 @@ MIB = 1024.0 * 1024.0
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/), keyed by
 # workload and kernel; None where no counter run has been taken yet.
-MEASURED_TRAFFIC_BYTES: dict = {}
+MEASURED_TRAFFIC_BYTES: dict = {
+    # profiles/keyswitch_cfg2_hbm_traffic.txt: FETCH_SIZE scaled by 2.0 and WRITE_SIZE by 1.0 (what the same counters
+    # read for a 1 GiB device copy), summed, per launch.  The excess over the algorithmic bytes is twiddle-table reads.
+    ("keyswitch", "rows_inner_product"): 206214385,
+    ("keyswitch", "rows_moddown_finish"): 93516420,
+    ("keyswitch", "bconv_ntt_cols"): 43110608,      # mean of the ModUp (52.1 MB) and ModDown (34.2 MB) launches
+    ("keyswitch", "ntt_inv_rows"): 38068632,
+    ("keyswitch", "ntt_inv_cols"): 21377947,
+}
 
 
 def _keyswitch_bytes(L, K, dnum, N):
@@ -192,13 +200,32 @@ def bench_ntt(args, torch, K, ks_inputs):
                          "traffic": None}}
 
 
+def bench_copy(args, torch):
+    """A plain device copy of known size: the yardstick the HBM counters of the profiling runs are scaled by."""
+    n = 1 << 27  # 1 GiB of int64
+    a = torch.ones(n, dtype=torch.int64, device="cuda")
+    b = torch.empty_like(a)
+    b.copy_(a)
+    torch.cuda.synchronize()
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0.record()
+    for _ in range(10):
+        b.copy_(a)
+    t1.record()
+    torch.cuda.synchronize()
+    ms = t0.elapsed_time(t1) / 10
+    return {"metric": "copy_GBps", "value": round(2 * n * 8 / (ms * 1e-3) / 1e9, 1), "unit": "GB/s", "n_gpus": 1, "steps": 10,
+            "warmup": 1, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "int64", "data": "synthetic", "config": {"workload": "device copy, 1 GiB read + 1 GiB written per launch"}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--sets", type=int, default=6, help="disjoint buffer sets rotated through (cold-cache figure)")
-    ap.add_argument("--workload", default="keyswitch", choices=["keyswitch", "ntt"])
+    ap.add_argument("--workload", default="keyswitch", choices=["keyswitch", "ntt", "copy"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -213,7 +240,9 @@ def main():
         print("bench.py: no GPU visible; the HIP library has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
-    if args.workload == "ntt":
+    if args.workload == "copy":
+        result = bench_copy(args, torch)
+    elif args.workload == "ntt":
         result = bench_ntt(args, torch, K, ks_inputs)
     else:
         result, (cfg, q, p, first_set) = bench_keyswitch(args, torch, K, ks_inputs)

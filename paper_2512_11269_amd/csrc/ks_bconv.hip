@@ -30,11 +30,16 @@ __global__ __launch_bounds__(256) void bconv_kernel(const BConvPlan* __restrict_
     const int n_dst = (int)P.n_dst;
     for (int t = 0; t < n_dst; ++t) {
         const Mod mt = P.dst_mod[t];
-        double acc = 0.0;
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0;  // exact partial sums against the 12-bit pieces of the factors
 #pragma unroll
-        for (int i = 0; i < NSRC; ++i)
-            if (i < n_src) acc += mulmod_lazy(y[i], P.hat[t][i], mt);
-        op[(uint64_t)P.dst_limb[t] * N] = f64_to_u64(canon(reduce_lazy(acc, mt), mt));
+        for (int i = 0; i < NSRC; ++i) {
+            if (i < n_src) {
+                s0 = __builtin_fma(y[i], P.hat3[t][i][0], s0);
+                s1 = __builtin_fma(y[i], P.hat3[t][i][1], s1);
+                s2 = __builtin_fma(y[i], P.hat3[t][i][2], s2);
+            }
+        }
+        op[(uint64_t)P.dst_limb[t] * N] = f64_to_u64(canon(combine3_lazy(s0, s1, s2, mt), mt));
     }
 }
 

@@ -88,6 +88,9 @@ void fill_bconv_plan(const ks_ctx* c, BConvPlan* plan, const uint32_t* src_ids, 
         plan->src_mod[i] = make_mod(si);
         plan->src_inv[i] = (double)h_invmod(prod, si);
     }
+    // padding sources: factor 0 (from the memset) and the first real source's limb, so that kernels may run their
+    // source loop past n_src without branching and still read valid numbers
+    for (uint32_t i = n_src; i < (uint32_t)kMaxSrc; ++i) plan->src_limb[i] = src_limb[0];
     for (uint32_t t = 0; t < n_dst; ++t) {
         const uint64_t mt = c->mod[dst_ids[t]];
         plan->dst_limb[t] = dst_limb[t];
@@ -98,6 +101,9 @@ void fill_bconv_plan(const ks_ctx* c, BConvPlan* plan, const uint32_t* src_ids, 
             for (uint32_t k = 0; k < n_src; ++k)
                 if (k != i) prod = h_mulmod(prod, c->mod[src_ids[k]] % mt, mt);
             plan->hat[t][i] = (double)prod;
+            plan->hat3[t][i][0] = (double)(prod & 0xFFFu);
+            plan->hat3[t][i][1] = (double)((prod >> 12) & 0xFFFu);
+            plan->hat3[t][i][2] = (double)(prod >> 24);
         }
     }
 }

@@ -12,6 +12,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+// The arithmetic is plain IEEE double arithmetic, so it is callable from host code as well; the CPU-only test
+// suite uses that to check every bound stated below against 128-bit integer arithmetic.
+#define KS_HD __host__ __device__ __forceinline__
+
 namespace ks {
 
 struct Mod {
@@ -22,19 +26,19 @@ struct Mod {
 constexpr double kTwo52 = 4503599627370496.0;
 
 // Exact for x < 2^52: plant x in the mantissa of 2^52 and subtract 2^52.
-__device__ __forceinline__ double u64_to_f64(uint64_t x) {
-    return __longlong_as_double((long long)(x | 0x4330000000000000ull)) - kTwo52;
+KS_HD double u64_to_f64(uint64_t x) {
+    return __builtin_bit_cast(double, x | 0x4330000000000000ull) - kTwo52;
 }
 // Exact for integer-valued 0 <= r < 2^52.
-__device__ __forceinline__ uint64_t f64_to_u64(double r) {
-    return (uint64_t)__double_as_longlong(r + kTwo52) & 0x000FFFFFFFFFFFFFull;
+KS_HD uint64_t f64_to_u64(double r) {
+    return __builtin_bit_cast(uint64_t, r + kTwo52) & 0x000FFFFFFFFFFFFFull;
 }
 
 // a * b mod p as a small signed representative.
 // Requires integer-valued |a| <= 2^43, |b| <= 2^36.  Returns r = a b (mod p) with |r| <= 0.51 p.
 //   h + l = a b exactly (l is the rounding error of the product, recovered by one FMA);
 //   q ~ a b / p; h - q p is an integer below 2^36 in magnitude, so the second FMA is exact too.
-__device__ __forceinline__ double mulmod_lazy(double a, double b, Mod m) {
+KS_HD double mulmod_lazy(double a, double b, Mod m) {
     double h = a * b;
     double l = __builtin_fma(a, b, -h);
     double q = __builtin_rint(h * m.pinv);
@@ -43,18 +47,26 @@ __device__ __forceinline__ double mulmod_lazy(double a, double b, Mod m) {
 }
 
 // Any integer-valued |x| < 2^50 -> representative with |r| <= 0.51 p.
-__device__ __forceinline__ double reduce_lazy(double x, Mod m) {
+KS_HD double reduce_lazy(double x, Mod m) {
     double q = __builtin_rint(x * m.pinv);
     return __builtin_fma(-q, m.p, x);
 }
 
+// (s2 * 2^24 + s1 * 2^12 + s0) mod p as a lazy representative, for exact non-negative integer sums s_k < 2^52
+// (the three partial sums of a base conversion whose factors were split into 12-bit pieces).
+KS_HD double combine3_lazy(double s0, double s1, double s2, Mod m) {
+    double r = reduce_lazy(s2, m);
+    r = reduce_lazy(__builtin_fma(r, 4096.0, s1), m);
+    return reduce_lazy(__builtin_fma(r, 4096.0, s0), m);
+}
+
 // Representative in (-p, p) -> canonical [0, p).
-__device__ __forceinline__ double canon(double r, Mod m) { return r < 0.0 ? r + m.p : r; }
+KS_HD double canon(double r, Mod m) { return r < 0.0 ? r + m.p : r; }
 
 // The 15 twiddles of a 16-point register pass: t[2^u + g] = W[(base << u) + g] for local stage u = 0..3 and
 // group g < 2^u, i.e. the sub-tree below heap node `base` of the per-modulus table W[k] = psi^brv(k).
 // Loading them ahead of the butterflies lets their latency overlap the data loads.
-__device__ __forceinline__ void load_twiddles16(double (&t)[16], const double* __restrict__ W, uint32_t base) {
+KS_HD void load_twiddles16(double (&t)[16], const double* __restrict__ W, uint32_t base) {
     t[0] = 0.0;
 #pragma unroll
     for (int u = 0; u < 4; ++u)
@@ -64,7 +76,7 @@ __device__ __forceinline__ void load_twiddles16(double (&t)[16], const double* _
 
 // Sixteen points, four decimation-in-time stages, in registers.  v[k] are 16 points whose mutual distances
 // are 8, 4, 2, 1 times a common stride.  Growth: every stage adds at most 0.51 p to the magnitude.
-__device__ __forceinline__ void radix16_fwd(double (&v)[16], const double (&t)[16], Mod m) {
+KS_HD void radix16_fwd(double (&v)[16], const double (&t)[16], Mod m) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int half = 8 >> u;
@@ -84,7 +96,7 @@ __device__ __forceinline__ void radix16_fwd(double (&v)[16], const double (&t)[1
 
 // Inverse of radix16_fwd up to the factor 16 (decimation in frequency) with t built from Winv[k] = psi^-brv(k).
 // Inputs must satisfy |v| <= p; sums double per stage, so outputs are bounded by 16 p.
-__device__ __forceinline__ void radix16_inv(double (&v)[16], const double (&t)[16], Mod m) {
+KS_HD void radix16_inv(double (&v)[16], const double (&t)[16], Mod m) {
 #pragma unroll
     for (int u = 3; u >= 0; --u) {
         const int half = 8 >> u;

@@ -81,13 +81,18 @@ __global__ __launch_bounds__(256) void bconv_ntt_cols(const double* __restrict__
         for (int k = 0; k < 16; ++k) yv[k] = ynext[k];
 #pragma unroll
         for (int tt = 0; tt < TS; ++tt) hv[tt] = hnext[tt];
-        if (i + 1 < n_src) {
-            const uint64_t* src = yp + (uint64_t)P.src_limb[i + 1] * N;
+        {
+            // Unconditional prefetch: sources past the end are zero-padded in the plan (factor 0, a valid limb), so
+            // the extra fetch is harmless, while a conditional one would make the wait-count bookkeeping assume the
+            // worst at the join and stall every use on the newest loads.
+            const int inext = min(i + 1, kMaxSrc - 1);
+            const uint64_t* src = yp + (uint64_t)P.src_limb[inext] * N;
 #pragma unroll
             for (int k = 0; k < 16; ++k) ynext[k] = load_f64(src + col_row_strided<LOG_R>(r0, k) * 256 + col);
 #pragma unroll
-            for (int tt = 0; tt < TS; ++tt) hnext[tt] = hat_row[tt][i + 1];
+            for (int tt = 0; tt < TS; ++tt) hnext[tt] = hat_row[tt][inext];
         }
+        __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of the arithmetic below
 #pragma unroll
         for (int tt = 0; tt < TS; ++tt)
 #pragma unroll
@@ -118,10 +123,10 @@ void launch_bconv_ntt_cols(const ks_ctx* c, const BConvPlan* d_plans, uint32_t n
     if (n_polys == 0 || n_plans == 0) return;
     // Targets per workgroup: fewer targets = more workgroups (small launches need them to fill 256 compute units)
     // but more re-reads of the sources from cache.  Pick the largest TS that still gives every compute unit about
-    // four workgroups; KS_BCONV_TS overrides it for experiments.
+    // two workgroups (measured best on the single-ciphertext launches); KS_BCONV_TS overrides it for experiments.
     const uint32_t tiles = c->logN == 16 ? 16 : 1;
     int ts = 4;
-    while (ts > 1 && (uint64_t)tiles * n_plans * ((max_targets + ts - 1) / ts) * n_polys < 1024) ts >>= 1;
+    while (ts > 1 && (uint64_t)tiles * n_plans * ((max_targets + ts - 1) / ts) * n_polys < 512) ts >>= 1;
     if (const char* e = getenv("KS_BCONV_TS")) {
         const int v = atoi(e);
         if (v == 1 || v == 2 || v == 4) ts = v;

@@ -34,7 +34,11 @@ struct BConvPlan {
     double src_inv[kMaxSrc];     // (D / s_i)^-1 mod s_i
     Mod dst_mod[kMaxDst];
     uint32_t dst_mod_id[kMaxDst];  // modulus id of each target (selects its twiddle table)
-    double hat[kMaxDst][kMaxSrc];  // hat[t][i] = (D / s_i) mod t; the sources of one target are contiguous
+    // hat3[t][i][k], k = 0..2: the three 12-bit pieces (low to high) of (D / s_i) mod t.  A 36-bit residue times a
+    // 12-bit piece is below 2^48, so up to 16 such products add up exactly in a double: the conversion sum costs
+    // three FMAs per source and target plus one short recombination per target instead of a full modular product.
+    double hat3[kMaxDst][kMaxSrc][3];
+    double hat[kMaxDst][kMaxSrc];  // the same factors whole, for kernels that use a full modular product
 };
 
 // Everything the key-switching pipeline needs at one level ell.
