@@ -119,7 +119,7 @@ __global__ __launch_bounds__(256) void bconv_ntt_cols(const double* __restrict__
 
 void launch_bconv_ntt_cols(const ks_ctx* c, const BConvPlan* d_plans, uint32_t n_plans, uint32_t max_targets,
                            uint32_t limbs_moved_per_poly, const uint64_t* y, uint64_t y_ps, uint64_t* out, uint64_t out_ps,
-                           uint32_t n_polys, hipStream_t s) {
+                           uint32_t n_polys, hipStream_t s, double ops_per_coeff) {
     if (n_polys == 0 || n_plans == 0) return;
     // Targets per workgroup: fewer targets = more workgroups (small launches need them to fill 256 compute units)
     // but more re-reads of the sources from cache.  Pick the largest TS that still gives every compute unit about
@@ -133,7 +133,7 @@ void launch_bconv_ntt_cols(const ks_ctx* c, const BConvPlan* d_plans, uint32_t n
     }
     const uint32_t n_subsets = (max_targets + ts - 1) / ts;
     const dim3 grid(tiles, n_plans * n_subsets, n_polys), block(256);
-    ProfScope ps("bconv_ntt_cols", (double)limbs_moved_per_poly * n_polys * c->N * 8.0, s);
+    ProfScope ps("bconv_ntt_cols", (double)limbs_moved_per_poly * n_polys * c->N * 8.0, s, ops_per_coeff * n_polys * c->N);
 #define KS_LAUNCH_BCONV(LOGR, TSV) \
     hipLaunchKernelGGL((bconv_ntt_cols<LOGR, TSV>), grid, block, 0, s, c->d_tw_fwd, d_plans, y, y_ps, out, out_ps, n_subsets)
     if (c->logN == 16) {

@@ -88,7 +88,8 @@ void set_hip_error(hipError_t e, const char* where);
 // Optional per-kernel timing (ks_profile_enable): when on, every launcher brackets its kernel with a pair of
 // HIP events on the launch stream and books the kernel's algorithmic bytes (what it must read plus write).
 struct ProfScope {
-    ProfScope(const char* name, double bytes, hipStream_t s);
+    // ops: algorithmic fp64 vector instructions per lane (FMA, MUL, ADD and RNDNE each count one)
+    ProfScope(const char* name, double bytes, hipStream_t s, double ops = 0.0);
     ~ProfScope();
     int slot;
     hipStream_t stream;
@@ -120,7 +121,7 @@ void launch_ntt_inv_cols(const ks_ctx* c, const LimbMap& map, uint64_t* data, ui
 // y_i = [x_i N^-1 (D/s_i)^-1]; out: raw doubles ready for the row half.  One plan per blockIdx.y group.
 void launch_bconv_ntt_cols(const ks_ctx* c, const BConvPlan* d_plans, uint32_t n_plans, uint32_t max_targets,
                            uint32_t limbs_moved_per_poly, const uint64_t* y, uint64_t y_ps, uint64_t* out, uint64_t out_ps,
-                           uint32_t n_polys, hipStream_t s);
+                           uint32_t n_polys, hipStream_t s, double ops_per_coeff = 0.0);
 // Fused row half of the forward transform of the raised digits + inner product with the key.
 void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, const uint64_t* lifted,
                                const uint64_t* evk, uint64_t* acc, uint32_t batch, hipStream_t s);

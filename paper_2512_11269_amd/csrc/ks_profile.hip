@@ -1,5 +1,6 @@
 // Per-kernel timing with HIP events, off by default.  Used by the benchmark to report each kernel's achieved
-// bandwidth next to its algorithmic traffic; event pairs are recorded on the stream the kernel runs on.
+// bandwidth and arithmetic rate next to its algorithmic traffic and work; event pairs are recorded on the
+// stream the kernel runs on.
 #include <stdio.h>
 #include <string.h>
 
@@ -16,7 +17,7 @@ namespace ks {
 namespace {
 struct Record {
     const char* name;
-    double bytes;
+    double bytes, ops;
     hipEvent_t start, stop;
 };
 std::atomic<int> g_enabled{0};
@@ -24,9 +25,9 @@ std::mutex g_mu;
 std::vector<Record> g_records;
 }  // namespace
 
-ProfScope::ProfScope(const char* name, double bytes, hipStream_t s) : slot(-1), stream(s) {
+ProfScope::ProfScope(const char* name, double bytes, hipStream_t s, double ops) : slot(-1), stream(s) {
     if (!g_enabled.load(std::memory_order_relaxed)) return;
-    Record r{name, bytes, nullptr, nullptr};
+    Record r{name, bytes, ops, nullptr, nullptr};
     if (hipEventCreate(&r.start) != hipSuccess) return;
     if (hipEventCreate(&r.stop) != hipSuccess) {
         (void)hipEventDestroy(r.start);
@@ -62,7 +63,7 @@ extern "C" int ks_profile_enable(int on) {
 extern "C" int ks_profile_report(char* buf, size_t buflen) {
     if (!buf || buflen == 0) return KS_EINVAL;
     std::lock_guard<std::mutex> lock(g_mu);
-    struct Agg { double ms = 0, bytes = 0; long count = 0; };
+    struct Agg { double ms = 0, bytes = 0, ops = 0; long count = 0; };
     std::map<std::string, Agg> agg;
     std::vector<std::string> order;
     for (auto& r : g_records) {
@@ -73,14 +74,16 @@ extern "C" int ks_profile_report(char* buf, size_t buflen) {
         Agg& a = agg[r.name];
         a.ms += ms;
         a.bytes += r.bytes;
+        a.ops += r.ops;
         a.count += 1;
     }
     std::string out = "[";
     for (size_t i = 0; i < order.size(); ++i) {
         const Agg& a = agg[order[i]];
-        char line[256];
-        snprintf(line, sizeof(line), "%s{\"kernel\": \"%s\", \"launches\": %ld, \"total_ms\": %.6f, \"total_bytes\": %.0f}",
-                 i ? ", " : "", order[i].c_str(), a.count, a.ms, a.bytes);
+        char line[320];
+        snprintf(line, sizeof(line),
+                 "%s{\"kernel\": \"%s\", \"launches\": %ld, \"total_ms\": %.6f, \"total_bytes\": %.0f, \"total_ops\": %.0f}",
+                 i ? ", " : "", order[i].c_str(), a.count, a.ms, a.bytes, a.ops);
         out += line;
     }
     out += "]";
