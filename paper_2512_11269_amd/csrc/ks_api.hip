@@ -250,7 +250,6 @@ extern "C" int hmult_relin_rescale(const ks_ctx* c, const uint64_t* cta, const u
     if (batch == 0) return KS_OK;
     if (ws_bytes < ks_workspace_bytes(c, KS_OP_HMULT_RELIN_RESCALE, ell, batch, 0)) return KS_EWORKSPACE;
     const Level& lv = c->levels[ell - 1];
-    const Level& lv_out = c->levels[ell - 2];
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint64_t N = c->N, ct_bs = 2ull * ell * N, td_bs = 3ull * ell * N, out_bs = 2ull * (ell - 1) * N;
     LimbMap one;
@@ -275,10 +274,9 @@ extern "C" int hmult_relin_rescale(const ks_ctx* c, const uint64_t* cta, const u
         mod_down(c, lv, acc, conv, sum, ct_bs, td, td_bs, 2, 1, bc, true, s);
         // rescale both components: inverse transform of the last limb, centred remainder to every q_i, forward
         // transform, subtract and divide
-        launch_ntt_inv(c, one, XformIO{sum + (uint64_t)(ell - 1) * N, last, (uint64_t)ell * N, N, 2 * bc}, s);
-        launch_rescale_spread(c, last, spread, ell, 2 * bc, s);
-        launch_ntt_fwd(c, lv_out.q_map, XformIO{spread, spread, (uint64_t)(ell - 1) * N, (uint64_t)(ell - 1) * N, 2 * bc}, s);
-        launch_rescale_finish(c, lv, sum, spread, out + (uint64_t)b0 * out_bs, 2 * bc, s);
+        launch_ntt_inv_rows(c, one, XformIO{sum + (uint64_t)(ell - 1) * N, last, (uint64_t)ell * N, N, 2 * bc}, s);
+        launch_ntt_inv_cols(c, one, last, N, 2 * bc, c->d_ninv, false, true, s);   // canonical doubles
+        launch_rescale_fused(c, lv, sum, last, spread, out + (uint64_t)b0 * out_bs, 2 * bc, s);
     }
     return finish("hmult_relin_rescale");
 }

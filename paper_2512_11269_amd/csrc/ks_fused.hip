@@ -160,10 +160,17 @@ __global__ __launch_bounds__(64) void rows_inner_product(const double* __restric
                                                          uint32_t ell, uint32_t E, uint32_t L, uint32_t M,
                                                          const uint64_t* __restrict__ d, uint64_t d_ps,
                                                          const uint64_t* __restrict__ lifted, const uint64_t* __restrict__ evk,
-                                                         uint64_t* __restrict__ acc) {
+                                                         uint64_t* __restrict__ acc, uint32_t batch) {
     constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R;
     __shared__ double lds[4 * kRowPitch];
-    const uint32_t tid = threadIdx.x, rg = blockIdx.x, pos = blockIdx.y, b = blockIdx.z;
+    // Workgroup -> (row group, limb position, batch item).  Consecutive workgroup ids go to the eight XCDs in
+    // turn, each with its own L2; the ids that land on one XCD walk through all batch items of one
+    // (row group, position) tile before moving to the next tile, so the key slots and twiddles of a tile are
+    // fetched into that L2 once and reused by the whole batch.
+    const uint32_t tid = threadIdx.x;
+    const uint32_t slot = blockIdx.x >> 3, b = slot % batch, tile = (slot / batch) * 8 + (blockIdx.x & 7);
+    if (tile >= (R / 4) * E) return;  // uniform: padding workgroups when the tile count is not a multiple of 8
+    const uint32_t rg = tile % (R / 4), pos = tile / (R / 4);
     const uint32_t mid = pos < ell ? pos : L + (pos - ell);
     const Mod m = mods[mid];
     const double* W = tw + (size_t)mid * N;
@@ -244,12 +251,14 @@ void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const uint64_t*
     }
     // reads: every raised digit limb per ciphertext and the key (once per call); writes: both accumulators
     ProfScope ps("rows_inner_product", ((double)batch * (lv.ndig + 2) * lv.E + 2.0 * lv.ndig * lv.E) * c->N * 8.0, s);
+    const uint32_t tiles = (c->N / 1024) * lv.E;
+    const dim3 grid(((tiles + 7) / 8) * 8 * batch), block(64);
     if (c->logN == 16)
-        hipLaunchKernelGGL(rows_inner_product<8>, dim3(64, lv.E, batch), dim3(64), 0, s, c->d_tw_fwd, c->d_tw_inv, c->d_mod, dg, lv.ell, lv.E,
-                           c->L, c->M, d, d_ps, lifted, evk, acc);
+        hipLaunchKernelGGL(rows_inner_product<8>, grid, block, 0, s, c->d_tw_fwd, c->d_tw_inv, c->d_mod, dg, lv.ell, lv.E,
+                           c->L, c->M, d, d_ps, lifted, evk, acc, batch);
     else
-        hipLaunchKernelGGL(rows_inner_product<4>, dim3(4, lv.E, batch), dim3(64), 0, s, c->d_tw_fwd, c->d_tw_inv, c->d_mod, dg, lv.ell, lv.E,
-                           c->L, c->M, d, d_ps, lifted, evk, acc);
+        hipLaunchKernelGGL(rows_inner_product<4>, grid, block, 0, s, c->d_tw_fwd, c->d_tw_inv, c->d_mod, dg, lv.ell, lv.E,
+                           c->L, c->M, d, d_ps, lifted, evk, acc, batch);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -321,6 +330,85 @@ void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t
         else
             hipLaunchKernelGGL((rows_moddown_finish<4, true>), grid, block, 0, s, c->d_tw_fwd, c->d_mod, c->d_Pinv, lv.ell, lv.E, acc,
                                conv, out, out_bs, addend, addend_bs, addend_comps, galois);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Rescale, first half: the centred remainder of the dropped limb (coefficient domain, canonical doubles) is
+// reduced modulo q_i and sent straight through the column half of NTT_{q_i}; the "spread" limbs never exist
+// in coefficient form.  last: [polys][N]; out: [polys][ell-1][N] raw doubles.
+// ------------------------------------------------------------------------------------------------
+template <int LOG_R>
+__global__ __launch_bounds__(256) void rescale_cols(const double* __restrict__ tw, const Mod* __restrict__ mods, uint32_t ell,
+                                                    const uint64_t* __restrict__ last, uint64_t* __restrict__ out) {
+    constexpr uint32_t N = 256u << LOG_R, TILES = LOG_R == 8 ? 16 : 1, TC = 256 / TILES;
+    __shared__ double lds[LOG_R == 8 ? 4096 : 1];
+    const uint32_t tid = threadIdx.x, tile = blockIdx.x, i = blockIdx.y, p = blockIdx.z;
+    const Mod m = mods[i];
+    const double ql = mods[ell - 1].p, half = (ql - 1.0) * 0.5;
+    const uint32_t c = tid & (TC - 1), r0 = tid / TC, col = tile * TC + c;
+    const uint64_t* src = last + (uint64_t)p * N;
+    double v[16];
+    PassTwiddles t;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = load_f64(src + col_row_strided<LOG_R>(r0, k) * 256 + col);
+    load_col_twiddles<LOG_R>(t, tw + (size_t)i * N, r0);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = reduce_lazy(v[k] > half ? v[k] - ql : v[k], m);
+    col_fwd_core<LOG_R>(v, t, c, r0, lds, m);
+    uint64_t* dst = out + ((uint64_t)p * (ell - 1) + i) * N;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) store_f64(dst + col_row_grouped<LOG_R>(r0, k) * 256 + col, v[k]);
+}
+
+// Rescale, second half: row half of the forward transform, then out = (x - w) * q_{ell-1}^-1 mod q_i.
+// x: [polys][ell][N] canonical; spread: [polys][ell-1][N] raw doubles; out: [polys][ell-1][N] canonical.
+template <int LOG_R>
+__global__ __launch_bounds__(64) void rows_rescale_finish(const double* __restrict__ tw, const Mod* __restrict__ mods,
+                                                          const double* __restrict__ qlinv, uint32_t ell,
+                                                          const uint64_t* __restrict__ x, const uint64_t* __restrict__ spread,
+                                                          uint64_t* __restrict__ out) {
+    constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R;
+    __shared__ double lds[4 * kRowPitch];
+    const uint32_t tid = threadIdx.x, rg = blockIdx.x, i = blockIdx.y, p = blockIdx.z;
+    const Mod m = mods[i];
+    const double scale = qlinv[i];
+    const uint32_t j0 = tid & 15, rr = tid >> 4, row = rg * 4 + rr;
+    const uint32_t off = row * 256 + j0;
+    const uint64_t* src = spread + ((uint64_t)p * (ell - 1) + i) * N + off;
+    const uint64_t* xp = x + ((uint64_t)p * ell + i) * N + off;
+    uint64_t* op = out + ((uint64_t)p * (ell - 1) + i) * N + off;
+    double w[16], a[16];
+    PassTwiddles t;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) w[k] = load_f64(src + 16 * k);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) a[k] = u64_to_f64(xp[16 * k]);
+    load_row_twiddles(t, tw + (size_t)i * N, R + row, j0);
+    row_fwd_core(w, t, j0, lds + rr * kRowPitch, m);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) op[16 * k] = f64_to_u64(canon(mulmod_lazy(a[k] - w[k], scale, m), m));
+}
+
+void launch_rescale_fused(const ks_ctx* c, const Level& lv, const uint64_t* x, const uint64_t* last, uint64_t* spread,
+                          uint64_t* out, uint32_t n_polys, hipStream_t s) {
+    if (n_polys == 0 || lv.ell < 2) return;
+    const uint32_t nl = lv.ell - 1;
+    {
+        ProfScope ps("rescale_cols", ((double)n_polys * (1 + nl)) * c->N * 8.0, s);
+        if (c->logN == 16)
+            hipLaunchKernelGGL(rescale_cols<8>, dim3(16, nl, n_polys), dim3(256), 0, s, c->d_tw_fwd, c->d_mod, lv.ell, last, spread);
+        else
+            hipLaunchKernelGGL(rescale_cols<4>, dim3(1, nl, n_polys), dim3(256), 0, s, c->d_tw_fwd, c->d_mod, lv.ell, last, spread);
+    }
+    {
+        ProfScope ps("rows_rescale_finish", (double)n_polys * nl * 3 * c->N * 8.0, s);
+        if (c->logN == 16)
+            hipLaunchKernelGGL(rows_rescale_finish<8>, dim3(64, nl, n_polys), dim3(64), 0, s, c->d_tw_fwd, c->d_mod, lv.d_qlinv,
+                               lv.ell, x, spread, out);
+        else
+            hipLaunchKernelGGL(rows_rescale_finish<4>, dim3(4, nl, n_polys), dim3(64), 0, s, c->d_tw_fwd, c->d_mod, lv.d_qlinv,
+                               lv.ell, x, spread, out);
     }
 }
 

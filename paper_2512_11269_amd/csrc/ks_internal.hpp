@@ -130,6 +130,11 @@ void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t
                                 uint64_t out_batch_stride, const uint64_t* addend, uint64_t addend_batch_stride,
                                 uint32_t addend_comps, uint32_t galois, uint32_t batch, hipStream_t s);
 
+// Fused rescale: last = coefficient-domain dropped limb as canonical doubles [polys][N]; spread = scratch
+// [polys][ell-1][N]; out[p][i] = (x[p][i] - NTT(centred last mod q_i)) * q_{ell-1}^-1.
+void launch_rescale_fused(const ks_ctx* c, const Level& lv, const uint64_t* x, const uint64_t* last, uint64_t* spread,
+                          uint64_t* out, uint32_t n_polys, hipStream_t s);
+
 void launch_bconv(const ks_ctx* c, const BConvPlan* d_plans, uint32_t limbs_moved_per_poly, uint32_t n_plans,
                   const uint64_t* in, uint64_t in_poly_stride, uint64_t* out, uint64_t out_poly_stride,
                   uint32_t n_polys, uint32_t n_src_max, hipStream_t s);
