@@ -149,6 +149,8 @@ extern "C" int ks_ctx_destroy(ks_ctx* c) {
     (void)hipFree(c->d_moddown_scale);
     (void)hipFree(c->d_tw_fwd);
     (void)hipFree(c->d_tw_inv);
+    (void)hipFree(c->d_trow);
+    (void)hipFree(c->d_w16);
     for (auto& lv : c->levels) {
         (void)hipFree(lv.d_modup);
         (void)hipFree(lv.d_moddown);
@@ -229,8 +231,12 @@ extern "C" int ks_ctx_create(ks_ctx** out, uint32_t logN, uint32_t L, uint32_t K
         // twiddle tables: W[k] = psi^brv(k), Winv[k] = psi^-brv(k)
         CK(hipMalloc(&c->d_tw_fwd, sizeof(double) * (size_t)M * N));
         CK(hipMalloc(&c->d_tw_inv, sizeof(double) * (size_t)M * N));
+        CK(hipMalloc(&c->d_trow, sizeof(double) * 2 * (size_t)M * (N / 16)));
+        CK(hipMalloc(&c->d_w16, sizeof(double) * 2 * (size_t)M * 8));
+        c->tw_fwd = TwTables{c->d_tw_fwd, c->d_trow, c->d_w16};
+        c->tw_inv = TwTables{c->d_tw_inv, c->d_trow + (size_t)M * (N / 16), c->d_w16 + (size_t)M * 8};
         std::vector<uint64_t> pw(N);
-        std::vector<double> tab(N);
+        std::vector<double> tab(N), trow(N / 16), w16(8);
         for (uint32_t m = 0; m < M; ++m) {
             const uint64_t mod = c->mod[m];
             for (int dir = 0; dir < 2; ++dir) {
@@ -240,6 +246,13 @@ extern "C" int ks_ctx_create(ks_ctx** out, uint32_t logN, uint32_t L, uint32_t K
                 for (uint32_t k = 0; k < N; ++k) tab[k] = (double)pw[h_brv(k, logN)];
                 double* dst = (dir == 0 ? c->d_tw_fwd : c->d_tw_inv) + (size_t)m * N;
                 CK(hipMemcpy(dst, tab.data(), sizeof(double) * N, hipMemcpyHostToDevice));
+                // compact tables for the row kernels: last-pass generators and the powers of the 16th root of unity
+                for (uint32_t i = 0; i < N / 16; ++i) trow[i] = tab[8 * (N / 16 + i)];
+                for (uint32_t e = 0; e < 8; ++e) w16[e] = (double)pw[(size_t)(N / 8) * e];
+                const TwTables& tt = dir == 0 ? c->tw_fwd : c->tw_inv;
+                CK(hipMemcpy(const_cast<double*>(tt.trow) + (size_t)m * (N / 16), trow.data(), sizeof(double) * (N / 16),
+                             hipMemcpyHostToDevice));
+                CK(hipMemcpy(const_cast<double*>(tt.w16) + (size_t)m * 8, w16.data(), sizeof(double) * 8, hipMemcpyHostToDevice));
             }
         }
 

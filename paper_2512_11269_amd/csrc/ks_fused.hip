@@ -155,7 +155,7 @@ void launch_bconv_ntt_cols(const ks_ctx* c, const BConvPlan* d_plans, uint32_t n
 // components (load reuse), and the accumulators are reduced and written once.
 // ------------------------------------------------------------------------------------------------
 template <int LOG_R>
-__global__ __launch_bounds__(64) void rows_inner_product(const double* __restrict__ tw, const double* __restrict__ twi,
+__global__ __launch_bounds__(64) void rows_inner_product(TwTables tw, TwTables twi,
                                                          const Mod* __restrict__ mods, DigitRanges dg,
                                                          uint32_t ell, uint32_t E, uint32_t L, uint32_t M,
                                                          const uint64_t* __restrict__ d, uint64_t d_ps,
@@ -173,14 +173,13 @@ __global__ __launch_bounds__(64) void rows_inner_product(const double* __restric
     const uint32_t rg = tile % (R / 4), pos = tile / (R / 4);
     const uint32_t mid = pos < ell ? pos : L + (pos - ell);
     const Mod m = mods[mid];
-    const double* W = tw + (size_t)mid * N;
     const uint32_t j0 = tid & 15, rr = tid >> 4, row = rg * 4 + rr;
     const uint32_t off = row * 256 + j0;
     double a0[16], a1[16];
 #pragma unroll
     for (int k = 0; k < 16; ++k) a0[k] = a1[k] = 0.0;
     PassTwiddles t;
-    load_row_twiddles(t, W, R + row, j0);
+    load_row_twiddles(t, tw, mid, N, R + row, j0, m);
 
 #pragma unroll 1
     for (uint32_t j = 0; j < dg.ndig; ++j) {
@@ -229,7 +228,7 @@ __global__ __launch_bounds__(64) void rows_inner_product(const double* __restric
         // Special limbs go straight into ModDown: the row half of their inverse transform works on the very
         // rows this wavefront holds, so it is done here and raw doubles are handed to the column half.
         PassTwiddles ti;
-        load_row_twiddles(ti, twi + (size_t)mid * N, R + row, j0);
+        load_row_twiddles(ti, twi, mid, N, R + row, j0, m);
         row_inv_core(a0, ti, j0, lds + rr * kRowPitch, m);
         row_inv_core(a1, ti, j0, lds + rr * kRowPitch, m);
 #pragma unroll
@@ -254,10 +253,10 @@ void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const uint64_t*
     const uint32_t tiles = (c->N / 1024) * lv.E;
     const dim3 grid(((tiles + 7) / 8) * 8 * batch), block(64);
     if (c->logN == 16)
-        hipLaunchKernelGGL(rows_inner_product<8>, grid, block, 0, s, c->d_tw_fwd, c->d_tw_inv, c->d_mod, dg, lv.ell, lv.E,
+        hipLaunchKernelGGL(rows_inner_product<8>, grid, block, 0, s, c->tw_fwd, c->tw_inv, c->d_mod, dg, lv.ell, lv.E,
                            c->L, c->M, d, d_ps, lifted, evk, acc, batch);
     else
-        hipLaunchKernelGGL(rows_inner_product<4>, grid, block, 0, s, c->d_tw_fwd, c->d_tw_inv, c->d_mod, dg, lv.ell, lv.E,
+        hipLaunchKernelGGL(rows_inner_product<4>, grid, block, 0, s, c->tw_fwd, c->tw_inv, c->d_mod, dg, lv.ell, lv.E,
                            c->L, c->M, d, d_ps, lifted, evk, acc, batch);
 }
 
@@ -265,7 +264,7 @@ void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const uint64_t*
 // out[b][comp][i] = (acc[b][comp][i] - NTT_rows(conv[b][comp][i])) * P^-1 (+ addend), canonical.
 // ------------------------------------------------------------------------------------------------
 template <int LOG_R, bool GATHER>
-__global__ __launch_bounds__(64) void rows_moddown_finish(const double* __restrict__ tw, const Mod* __restrict__ mods,
+__global__ __launch_bounds__(64) void rows_moddown_finish(TwTables tw, const Mod* __restrict__ mods,
                                                           const double* __restrict__ Pinv, uint32_t ell, uint32_t E,
                                                           const uint64_t* __restrict__ acc, const uint64_t* __restrict__ conv,
                                                           uint64_t* __restrict__ out, uint64_t out_bs,
@@ -275,7 +274,6 @@ __global__ __launch_bounds__(64) void rows_moddown_finish(const double* __restri
     __shared__ double lds[4 * kRowPitch];
     const uint32_t tid = threadIdx.x, rg = blockIdx.x, i = blockIdx.y, b = blockIdx.z >> 1, comp = blockIdx.z & 1;
     const Mod m = mods[i];
-    const double* W = tw + (size_t)i * N;
     const double pinv = Pinv[i];
     const uint32_t j0 = tid & 15, rr = tid >> 4, row = rg * 4 + rr;
     const uint32_t off = row * 256 + j0;
@@ -299,7 +297,7 @@ __global__ __launch_bounds__(64) void rows_moddown_finish(const double* __restri
         }
     }
     PassTwiddles t;
-    load_row_twiddles(t, W, R + row, j0);
+    load_row_twiddles(t, tw, i, N, R + row, j0, m);
     row_fwd_core(w, t, j0, lds + rr * kRowPitch, m);
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
@@ -317,18 +315,18 @@ void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t
     if (c->logN == 16) {
         const dim3 grid(64, lv.ell, batch * 2);
         if (galois == 1)
-            hipLaunchKernelGGL((rows_moddown_finish<8, false>), grid, block, 0, s, c->d_tw_fwd, c->d_mod, c->d_Pinv, lv.ell, lv.E, acc,
+            hipLaunchKernelGGL((rows_moddown_finish<8, false>), grid, block, 0, s, c->tw_fwd, c->d_mod, c->d_Pinv, lv.ell, lv.E, acc,
                                conv, out, out_bs, addend, addend_bs, addend_comps, galois);
         else
-            hipLaunchKernelGGL((rows_moddown_finish<8, true>), grid, block, 0, s, c->d_tw_fwd, c->d_mod, c->d_Pinv, lv.ell, lv.E, acc,
+            hipLaunchKernelGGL((rows_moddown_finish<8, true>), grid, block, 0, s, c->tw_fwd, c->d_mod, c->d_Pinv, lv.ell, lv.E, acc,
                                conv, out, out_bs, addend, addend_bs, addend_comps, galois);
     } else {
         const dim3 grid(4, lv.ell, batch * 2);
         if (galois == 1)
-            hipLaunchKernelGGL((rows_moddown_finish<4, false>), grid, block, 0, s, c->d_tw_fwd, c->d_mod, c->d_Pinv, lv.ell, lv.E, acc,
+            hipLaunchKernelGGL((rows_moddown_finish<4, false>), grid, block, 0, s, c->tw_fwd, c->d_mod, c->d_Pinv, lv.ell, lv.E, acc,
                                conv, out, out_bs, addend, addend_bs, addend_comps, galois);
         else
-            hipLaunchKernelGGL((rows_moddown_finish<4, true>), grid, block, 0, s, c->d_tw_fwd, c->d_mod, c->d_Pinv, lv.ell, lv.E, acc,
+            hipLaunchKernelGGL((rows_moddown_finish<4, true>), grid, block, 0, s, c->tw_fwd, c->d_mod, c->d_Pinv, lv.ell, lv.E, acc,
                                conv, out, out_bs, addend, addend_bs, addend_comps, galois);
     }
 }
@@ -364,7 +362,7 @@ __global__ __launch_bounds__(256) void rescale_cols(const double* __restrict__ t
 // Rescale, second half: row half of the forward transform, then out = (x - w) * q_{ell-1}^-1 mod q_i.
 // x: [polys][ell][N] canonical; spread: [polys][ell-1][N] raw doubles; out: [polys][ell-1][N] canonical.
 template <int LOG_R>
-__global__ __launch_bounds__(64) void rows_rescale_finish(const double* __restrict__ tw, const Mod* __restrict__ mods,
+__global__ __launch_bounds__(64) void rows_rescale_finish(TwTables tw, const Mod* __restrict__ mods,
                                                           const double* __restrict__ qlinv, uint32_t ell,
                                                           const uint64_t* __restrict__ x, const uint64_t* __restrict__ spread,
                                                           uint64_t* __restrict__ out) {
@@ -384,7 +382,7 @@ __global__ __launch_bounds__(64) void rows_rescale_finish(const double* __restri
     for (int k = 0; k < 16; ++k) w[k] = load_f64(src + 16 * k);
 #pragma unroll
     for (int k = 0; k < 16; ++k) a[k] = u64_to_f64(xp[16 * k]);
-    load_row_twiddles(t, tw + (size_t)i * N, R + row, j0);
+    load_row_twiddles(t, tw, i, N, R + row, j0, m);
     row_fwd_core(w, t, j0, lds + rr * kRowPitch, m);
 #pragma unroll
     for (int k = 0; k < 16; ++k) op[16 * k] = f64_to_u64(canon(mulmod_lazy(a[k] - w[k], scale, m), m));
@@ -404,10 +402,10 @@ void launch_rescale_fused(const ks_ctx* c, const Level& lv, const uint64_t* x, c
     {
         ProfScope ps("rows_rescale_finish", (double)n_polys * nl * 3 * c->N * 8.0, s);
         if (c->logN == 16)
-            hipLaunchKernelGGL(rows_rescale_finish<8>, dim3(64, nl, n_polys), dim3(64), 0, s, c->d_tw_fwd, c->d_mod, lv.d_qlinv,
+            hipLaunchKernelGGL(rows_rescale_finish<8>, dim3(64, nl, n_polys), dim3(64), 0, s, c->tw_fwd, c->d_mod, lv.d_qlinv,
                                lv.ell, x, spread, out);
         else
-            hipLaunchKernelGGL(rows_rescale_finish<4>, dim3(4, nl, n_polys), dim3(64), 0, s, c->d_tw_fwd, c->d_mod, lv.d_qlinv,
+            hipLaunchKernelGGL(rows_rescale_finish<4>, dim3(4, nl, n_polys), dim3(64), 0, s, c->tw_fwd, c->d_mod, lv.d_qlinv,
                                lv.ell, x, spread, out);
     }
 }

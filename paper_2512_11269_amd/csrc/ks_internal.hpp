@@ -9,6 +9,7 @@
 
 #include "../../include/ks.h"
 #include "ks_device.hpp"
+#include "ks_tiles.hpp"
 
 namespace ks {
 
@@ -68,6 +69,9 @@ struct ks_ctx {
     double* d_moddown_scale = nullptr;    // [K]  N^-1 (P / p_k)^-1 mod p_k
     double* d_tw_fwd = nullptr;           // [M][N] psi^brv(k)
     double* d_tw_inv = nullptr;           // [M][N] psi^-brv(k)
+    double* d_trow = nullptr;             // [2][M][N/16] compact last-pass generators, forward then inverse
+    double* d_w16 = nullptr;              // [2][M][8] powers of the primitive 16th root, forward then inverse
+    ks::TwTables tw_fwd{}, tw_inv{};      // the three tables of each direction bundled for the row kernels
     std::vector<ks::Level> levels;        // index ell-1
     mutable std::mutex mu;
     mutable std::map<std::vector<uint32_t>, ks::BConvPlan*> bconv_cache;  // key: n_src, src ids, dst ids

@@ -48,7 +48,7 @@ __global__ __launch_bounds__(256) void ntt_fwd_cols(const double* __restrict__ t
 
 // forward, rows: raw doubles in, canonical u64 out, in place.  One wavefront = four rows.
 template <int LOG_R>
-__global__ __launch_bounds__(64) void ntt_fwd_rows(const double* __restrict__ tw, const Mod* __restrict__ mods, LimbMap map,
+__global__ __launch_bounds__(64) void ntt_fwd_rows(TwTables tw, const Mod* __restrict__ mods, LimbMap map,
                                                    uint64_t* data, uint64_t ps) {
     constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R, GROUPS = R / 4;
     __shared__ double lds[4 * kRowPitch];
@@ -56,14 +56,13 @@ __global__ __launch_bounds__(64) void ntt_fwd_rows(const double* __restrict__ tw
     const uint32_t li = blockIdx.x / GROUPS, rg = blockIdx.x - li * GROUPS;
     const LimbRef L = locate(map, li, data, data, ps, ps, N);
     const Mod m = mods[L.mod_id];
-    const double* W = tw + (size_t)L.mod_id * N;
     const uint32_t j0 = tid & 15, rr = tid >> 4, row = rg * 4 + rr;
     uint64_t* p = L.out + row * 256;
     double v[16];
     PassTwiddles t;
 #pragma unroll
     for (int k = 0; k < 16; ++k) v[k] = load_f64(p + j0 + 16 * k);
-    load_row_twiddles(t, W, R + row, j0);
+    load_row_twiddles(t, tw, L.mod_id, N, R + row, j0, m);
     row_fwd_core(v, t, j0, lds + rr * kRowPitch, m);
 #pragma unroll
     for (int k = 0; k < 16; ++k) p[j0 + 16 * k] = f64_to_u64(canon(reduce_lazy(v[k], m), m));
@@ -71,7 +70,7 @@ __global__ __launch_bounds__(64) void ntt_fwd_rows(const double* __restrict__ tw
 
 // inverse, rows first: canonical u64 in, raw doubles out (|x| <= 0.501 p).
 template <int LOG_R>
-__global__ __launch_bounds__(64) void ntt_inv_rows(const double* __restrict__ twi, const Mod* __restrict__ mods, LimbMap map,
+__global__ __launch_bounds__(64) void ntt_inv_rows(TwTables twi, const Mod* __restrict__ mods, LimbMap map,
                                                    const uint64_t* in, uint64_t* out, uint64_t in_ps, uint64_t out_ps) {
     constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R, GROUPS = R / 4;
     __shared__ double lds[4 * kRowPitch];
@@ -79,13 +78,12 @@ __global__ __launch_bounds__(64) void ntt_inv_rows(const double* __restrict__ tw
     const uint32_t li = blockIdx.x / GROUPS, rg = blockIdx.x - li * GROUPS;
     const LimbRef L = locate(map, li, in, out, in_ps, out_ps, N);
     const Mod m = mods[L.mod_id];
-    const double* Wi = twi + (size_t)L.mod_id * N;
     const uint32_t j0 = tid & 15, rr = tid >> 4, row = rg * 4 + rr;
     double v[16];
     PassTwiddles t;
 #pragma unroll
     for (int k = 0; k < 16; ++k) v[k] = u64_to_f64(L.in[row * 256 + j0 + 16 * k]);
-    load_row_twiddles(t, Wi, R + row, j0);
+    load_row_twiddles(t, twi, L.mod_id, N, R + row, j0, m);
     row_inv_core(v, t, j0, lds + rr * kRowPitch, m);
 #pragma unroll
     for (int k = 0; k < 16; ++k) store_f64(L.out + row * 256 + j0 + 16 * k, v[k]);
@@ -142,9 +140,9 @@ void launch_ntt_fwd_rows(const ks_ctx* c, const LimbMap& map, uint64_t* data, ui
     if (limbs == 0) return;
     ProfScope ps("ntt_fwd_rows", 2.0 * limbs * c->N * 8.0, s);
     if (c->logN == 16)
-        hipLaunchKernelGGL(ntt_fwd_rows<8>, dim3(limbs * 64), dim3(64), 0, s, c->d_tw_fwd, c->d_mod, map, data, ps_words);
+        hipLaunchKernelGGL(ntt_fwd_rows<8>, dim3(limbs * 64), dim3(64), 0, s, c->tw_fwd, c->d_mod, map, data, ps_words);
     else
-        hipLaunchKernelGGL(ntt_fwd_rows<4>, dim3(limbs * 4), dim3(64), 0, s, c->d_tw_fwd, c->d_mod, map, data, ps_words);
+        hipLaunchKernelGGL(ntt_fwd_rows<4>, dim3(limbs * 4), dim3(64), 0, s, c->tw_fwd, c->d_mod, map, data, ps_words);
 }
 
 void launch_ntt_fwd(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipStream_t s) {
@@ -159,10 +157,10 @@ void launch_ntt_inv_rows(const ks_ctx* c, const LimbMap& map, const XformIO& io,
     uint64_t* out = static_cast<uint64_t*>(io.out);
     ProfScope ps("ntt_inv_rows", 2.0 * limbs * c->N * 8.0, s);
     if (c->logN == 16)
-        hipLaunchKernelGGL(ntt_inv_rows<8>, dim3(limbs * 64), dim3(64), 0, s, c->d_tw_inv, c->d_mod, map, in, out,
+        hipLaunchKernelGGL(ntt_inv_rows<8>, dim3(limbs * 64), dim3(64), 0, s, c->tw_inv, c->d_mod, map, in, out,
                            io.in_poly_stride, io.out_poly_stride);
     else
-        hipLaunchKernelGGL(ntt_inv_rows<4>, dim3(limbs * 4), dim3(64), 0, s, c->d_tw_inv, c->d_mod, map, in, out,
+        hipLaunchKernelGGL(ntt_inv_rows<4>, dim3(limbs * 4), dim3(64), 0, s, c->tw_inv, c->d_mod, map, in, out,
                            io.in_poly_stride, io.out_poly_stride);
 }
 

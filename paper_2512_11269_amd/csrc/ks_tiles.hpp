@@ -31,10 +31,34 @@ __device__ __forceinline__ void store_f64(uint64_t* p, double v) { *reinterpret_
 struct PassTwiddles {
     double a[16], b[16];
 };
-// rows: node = R + row; lane j0 owns points 16 j0 .. 16 j0 + 15 in the second pass
-__device__ __forceinline__ void load_row_twiddles(PassTwiddles& t, const double* __restrict__ W, uint32_t node, uint32_t j0) {
-    load_twiddles16(t.a, W, node);
-    load_twiddles16(t.b, W, node * 16 + j0);
+// One direction's twiddle tables (device pointers, every table indexed [modulus id][...]):
+//   W    [N]     W[k] = psi^brv(k) (or psi^-brv(k)), heap order
+//   trow [N/16]  trow[i] = W[8 (N/16 + i)] = psi^(1 + 2 brv(i)): the generator of the last register pass of row-pass lane i
+//   w16  [8]     w16[e] = omega^e, omega = psi^(N/8) a primitive 16th root of unity
+struct TwTables {
+    const double* W;
+    const double* trow;
+    const double* w16;
+};
+
+// rows: node = R + row; lane j0 owns points 16 j0 .. 16 j0 + 15 in the second pass.
+// The second pass needs the 15 table entries below heap node n = 16 node + j0 -- one twiddle per point of the row,
+// as much data as the row itself.  They factor as W[n 2^u + g] = T^(2^(3-u)) * omega^(2^(3-u) brv_u(g)) with
+// T = W[8 n], so one load, three squarings and eleven products replace fifteen loads (row kernels are
+// bandwidth-bound and have arithmetic to spare).
+__device__ __forceinline__ void load_row_twiddles(PassTwiddles& t, const TwTables& tb, uint32_t mod_id, uint32_t N, uint32_t node,
+                                                  uint32_t j0, Mod m) {
+    load_twiddles16(t.a, tb.W + (size_t)mod_id * N, node);
+    const double* w = tb.w16 + mod_id * 8;
+    const double T1 = tb.trow[(size_t)mod_id * (N / 16) + (node * 16 + j0 - N / 16)];
+    const double T2 = mulmod_lazy(T1, T1, m), T4 = mulmod_lazy(T2, T2, m), T8 = mulmod_lazy(T4, T4, m);
+    t.b[0] = 0.0;
+    t.b[1] = T8;
+    t.b[2] = T4;  t.b[3] = mulmod_lazy(T4, w[4], m);
+    t.b[4] = T2;  t.b[5] = mulmod_lazy(T2, w[4], m);  t.b[6] = mulmod_lazy(T2, w[2], m);  t.b[7] = mulmod_lazy(T2, w[6], m);
+    t.b[8] = T1;  t.b[9] = mulmod_lazy(T1, w[4], m);  t.b[10] = mulmod_lazy(T1, w[2], m); t.b[11] = mulmod_lazy(T1, w[6], m);
+    t.b[12] = mulmod_lazy(T1, w[1], m);  t.b[13] = mulmod_lazy(T1, w[5], m);
+    t.b[14] = mulmod_lazy(T1, w[3], m);  t.b[15] = mulmod_lazy(T1, w[7], m);
 }
 // columns: heap node 1 for the first pass, 16 + r0 for the second (LOG_R = 8 only)
 template <int LOG_R>
