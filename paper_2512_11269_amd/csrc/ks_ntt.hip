@@ -25,11 +25,11 @@ __device__ __forceinline__ LimbRef locate(const LimbMap& map, uint32_t li, const
 }
 
 // forward, columns: canonical u64 in, raw doubles out (|x| <= (1 + 0.501 log2 R) p).
-template <int LOG_R>
-__global__ __launch_bounds__(256) void ntt_fwd_cols(const double* __restrict__ tw, const Mod* __restrict__ mods, LimbMap map,
-                                                    const uint64_t* in, uint64_t* out, uint64_t in_ps, uint64_t out_ps) {
-    constexpr uint32_t N = 256u << LOG_R, TILES = LOG_R == 8 ? 16 : 1, TC = 256 / TILES;
-    __shared__ double lds[LOG_R == 8 ? 4096 : 1];
+template <int LOG_R, int TC>
+__global__ __launch_bounds__(LOG_R == 8 ? TC * 16 : 256) void ntt_fwd_cols(const double* __restrict__ tw, const Mod* __restrict__ mods, LimbMap map,
+                                                        const uint64_t* in, uint64_t* out, uint64_t in_ps, uint64_t out_ps) {
+    constexpr uint32_t N = 256u << LOG_R, TILES = 256 / TC;
+    __shared__ double lds[LOG_R == 8 ? 256 * TC : 1];
     const uint32_t tid = threadIdx.x;
     const uint32_t li = blockIdx.x / TILES, tile = blockIdx.x - li * TILES;
     const LimbRef L = locate(map, li, in, out, in_ps, out_ps, N);
@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void ntt_fwd_cols(const double* __restrict__ t
 #pragma unroll
     for (int k = 0; k < 16; ++k) v[k] = u64_to_f64(L.in[col_row_strided<LOG_R>(r0, k) * 256 + col]);
     load_col_twiddles<LOG_R>(t, W, r0);
-    col_fwd_core<LOG_R>(v, t, c, r0, lds, m);
+    col_fwd_core<LOG_R, TC>(v, t, c, r0, lds, m);
 #pragma unroll
     for (int k = 0; k < 16; ++k) store_f64(L.out + col_row_grouped<LOG_R>(r0, k) * 256 + col, v[k]);
 }
@@ -92,12 +92,12 @@ __global__ __launch_bounds__(64) void ntt_inv_rows(TwTables twi, const Mod* __re
 // inverse, columns last, in place: raw doubles in; out = canonical [x * scale]_m where scale is N^-1,
 // optionally pre-multiplied by a per-limb constant (base conversion folds its (D/s_i)^-1 in here).
 // OUT_F64: store the canonical result as a double instead of a 64-bit integer.
-template <int LOG_R, bool OUT_F64>
-__global__ __launch_bounds__(256) void ntt_inv_cols(const double* __restrict__ twi, const Mod* __restrict__ mods,
-                                                    const double* __restrict__ scale_tab, int scale_by_idx, LimbMap map,
-                                                    uint64_t* data, uint64_t ps) {
-    constexpr uint32_t N = 256u << LOG_R, TILES = LOG_R == 8 ? 16 : 1, TC = 256 / TILES;
-    __shared__ double lds[LOG_R == 8 ? 4096 : 1];
+template <int LOG_R, int TC, bool OUT_F64>
+__global__ __launch_bounds__(LOG_R == 8 ? TC * 16 : 256) void ntt_inv_cols(const double* __restrict__ twi, const Mod* __restrict__ mods,
+                                                        const double* __restrict__ scale_tab, int scale_by_idx, LimbMap map,
+                                                        uint64_t* data, uint64_t ps) {
+    constexpr uint32_t N = 256u << LOG_R, TILES = 256 / TC;
+    __shared__ double lds[LOG_R == 8 ? 256 * TC : 1];
     const uint32_t tid = threadIdx.x;
     const uint32_t li = blockIdx.x / TILES, tile = blockIdx.x - li * TILES;
     const LimbRef L = locate(map, li, data, data, ps, ps, N);
@@ -110,7 +110,7 @@ __global__ __launch_bounds__(256) void ntt_inv_cols(const double* __restrict__ t
 #pragma unroll
     for (int k = 0; k < 16; ++k) v[k] = load_f64(L.in + col_row_grouped<LOG_R>(r0, k) * 256 + col);
     load_col_twiddles<LOG_R>(t, Wi, r0);
-    col_inv_core<LOG_R>(v, t, c, r0, lds, m);
+    col_inv_core<LOG_R, TC>(v, t, c, r0, lds, m);
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
         const double r = canon(mulmod_lazy(v[k], scale, m), m);
@@ -121,18 +121,27 @@ __global__ __launch_bounds__(256) void ntt_inv_cols(const double* __restrict__ t
 }
 
 // ------------------------------------------------------------------------------------------------
+// Wide tiles (32 columns, 256-byte segments) move more bytes per second but give half as many workgroups;
+// small launches keep the 16-column tiles.
+static bool wide_tiles(uint32_t limbs) { return limbs >= 256; }
+
 void launch_ntt_fwd_cols(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipStream_t s) {
     const uint32_t limbs = map.n * io.n_polys;
     if (limbs == 0) return;
     const uint64_t* in = static_cast<const uint64_t*>(io.in);
     uint64_t* out = static_cast<uint64_t*>(io.out);
     ProfScope ps("ntt_fwd_cols", 2.0 * limbs * c->N * 8.0, s);
-    if (c->logN == 16)
-        hipLaunchKernelGGL(ntt_fwd_cols<8>, dim3(limbs * 16), dim3(256), 0, s, c->d_tw_fwd, c->d_mod, map, in, out,
+    if (c->logN == 16) {
+        if (wide_tiles(limbs))
+            hipLaunchKernelGGL((ntt_fwd_cols<8, 32>), dim3(limbs * 8), dim3(512), 0, s, c->d_tw_fwd, c->d_mod, map, in, out,
+                               io.in_poly_stride, io.out_poly_stride);
+        else
+            hipLaunchKernelGGL((ntt_fwd_cols<8, 16>), dim3(limbs * 16), dim3(256), 0, s, c->d_tw_fwd, c->d_mod, map, in, out,
+                               io.in_poly_stride, io.out_poly_stride);
+    } else {
+        hipLaunchKernelGGL((ntt_fwd_cols<4, 256>), dim3(limbs), dim3(256), 0, s, c->d_tw_fwd, c->d_mod, map, in, out,
                            io.in_poly_stride, io.out_poly_stride);
-    else
-        hipLaunchKernelGGL(ntt_fwd_cols<4>, dim3(limbs), dim3(256), 0, s, c->d_tw_fwd, c->d_mod, map, in, out,
-                           io.in_poly_stride, io.out_poly_stride);
+    }
 }
 
 void launch_ntt_fwd_rows(const ks_ctx* c, const LimbMap& map, uint64_t* data, uint64_t ps_words, uint32_t n_polys, hipStream_t s) {
@@ -170,21 +179,22 @@ void launch_ntt_inv_cols(const ks_ctx* c, const LimbMap& map, uint64_t* data, ui
     if (limbs == 0) return;
     ProfScope ps("ntt_inv_cols", 2.0 * limbs * c->N * 8.0, s);
     const int by_idx = scale_by_idx ? 1 : 0;
+#define KS_LAUNCH_INV_COLS(LOGR, TCV, GRID, F64) \
+    hipLaunchKernelGGL((ntt_inv_cols<LOGR, TCV, F64>), dim3(GRID), dim3(LOGR == 8 ? TCV * 16 : 256), 0, s, c->d_tw_inv, c->d_mod, \
+                       scale_tab, by_idx, map, data, ps_words)
     if (c->logN == 16) {
-        if (out_f64)
-            hipLaunchKernelGGL((ntt_inv_cols<8, true>), dim3(limbs * 16), dim3(256), 0, s, c->d_tw_inv, c->d_mod, scale_tab, by_idx,
-                               map, data, ps_words);
-        else
-            hipLaunchKernelGGL((ntt_inv_cols<8, false>), dim3(limbs * 16), dim3(256), 0, s, c->d_tw_inv, c->d_mod, scale_tab, by_idx,
-                               map, data, ps_words);
+        if (wide_tiles(limbs)) {
+            if (out_f64) KS_LAUNCH_INV_COLS(8, 32, limbs * 8, true);
+            else KS_LAUNCH_INV_COLS(8, 32, limbs * 8, false);
+        } else {
+            if (out_f64) KS_LAUNCH_INV_COLS(8, 16, limbs * 16, true);
+            else KS_LAUNCH_INV_COLS(8, 16, limbs * 16, false);
+        }
     } else {
-        if (out_f64)
-            hipLaunchKernelGGL((ntt_inv_cols<4, true>), dim3(limbs), dim3(256), 0, s, c->d_tw_inv, c->d_mod, scale_tab, by_idx, map,
-                               data, ps_words);
-        else
-            hipLaunchKernelGGL((ntt_inv_cols<4, false>), dim3(limbs), dim3(256), 0, s, c->d_tw_inv, c->d_mod, scale_tab, by_idx, map,
-                               data, ps_words);
+        if (out_f64) KS_LAUNCH_INV_COLS(4, 256, limbs, true);
+        else KS_LAUNCH_INV_COLS(4, 256, limbs, false);
     }
+#undef KS_LAUNCH_INV_COLS
 }
 
 void launch_ntt_inv(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipStream_t s) {

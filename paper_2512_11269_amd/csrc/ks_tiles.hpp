@@ -105,33 +105,33 @@ __device__ __forceinline__ void row_inv_core(double (&v)[16], const PassTwiddles
 }
 
 // First log2(R) forward stages on a column tile.
-//   LOG_R = 8: 256 threads, thread (c = tid & 15, r0 = tid >> 4); in: v[k] = row r0 + 16 k, out: v[k] = row 16 r0 + k;
-//              lds: 4096 doubles.  LOG_R = 4: one register pass, rows k in and out, lds unused.
+//   LOG_R = 8: tile of TC columns x 256 rows, 16 TC threads, thread (c = tid % TC, r0 = tid / TC);
+//              in: v[k] = row r0 + 16 k, out: v[k] = row 16 r0 + k; lds: 256 TC doubles.  LOG_R = 4: one register pass, rows k in and out, lds unused.
 // Growth: at most 0.51 p per stage.
-template <int LOG_R>
+template <int LOG_R, int TC = 16>
 __device__ __forceinline__ void col_fwd_core(double (&v)[16], const PassTwiddles& t, uint32_t c, uint32_t r0, double* lds, Mod m) {
     radix16_fwd(v, t.a, m);
     if constexpr (LOG_R == 8) {
 #pragma unroll
-        for (int k = 0; k < 16; ++k) lds[(r0 + 16 * k) * 16 + c] = v[k];
+        for (int k = 0; k < 16; ++k) lds[(r0 + 16 * k) * TC + c] = v[k];
         __syncthreads();
 #pragma unroll
-        for (int k = 0; k < 16; ++k) v[k] = lds[(16 * r0 + k) * 16 + c];
+        for (int k = 0; k < 16; ++k) v[k] = lds[(16 * r0 + k) * TC + c];
         radix16_fwd(v, t.b, m);
     }
 }
 
 // Last log2(R) inverse stages on a column tile (no N^-1 factor).  LOG_R = 8: in rows 16 r0 + k, out rows r0 + 16 k.
 // in: |v| <= p.  out: |v| <= 16 p.
-template <int LOG_R>
+template <int LOG_R, int TC = 16>
 __device__ __forceinline__ void col_inv_core(double (&v)[16], const PassTwiddles& t, uint32_t c, uint32_t r0, double* lds, Mod m) {
     if constexpr (LOG_R == 8) {
         radix16_inv(v, t.b, m);
 #pragma unroll
-        for (int k = 0; k < 16; ++k) lds[(16 * r0 + k) * 16 + c] = reduce_lazy(v[k], m);
+        for (int k = 0; k < 16; ++k) lds[(16 * r0 + k) * TC + c] = reduce_lazy(v[k], m);
         __syncthreads();
 #pragma unroll
-        for (int k = 0; k < 16; ++k) v[k] = lds[(r0 + 16 * k) * 16 + c];
+        for (int k = 0; k < 16; ++k) v[k] = lds[(r0 + 16 * k) * TC + c];
     }
     radix16_inv(v, t.a, m);
 }
