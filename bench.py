@@ -180,6 +180,94 @@ def cpu_baseline_keyswitch(cfg, q, p, first_set, ks_inputs, budget_s=15.0):
             "sample": f"{n} key-switches of the same workload (same seeded d and evk), {dt:.1f} s wall"}
 
 
+def _kernel_breakdown(K, torch, fn, units):
+    """Run fn once with the library's event instrumentation on; per-kernel time per unit of work and rooflines."""
+    K.ks_profile_enable(True)
+    fn()
+    torch.cuda.synchronize()
+    kernels = K.ks_profile_report()
+    K.ks_profile_enable(False)
+    out = []
+    for k in kernels:
+        gbs = k["total_bytes"] / (k["total_ms"] * 1e-3) / 1e9
+        tfl = 2.0 * k.get("total_ops", 0.0) / (k["total_ms"] * 1e-3) / 1e12
+        out.append({"kernel": k["kernel"], "launches": k["launches"], "us_per_unit": round(k["total_ms"] * 1e3 / units, 3),
+                    "achieved_GBs": round(gbs, 1), "hbm_frac": round(gbs / HBM_PEAK_GBS, 3),
+                    "alu_frac": round(tfl / FP64_VECTOR_PEAK_TFLOPS, 3), "total_ms": k["total_ms"]})
+    return out
+
+
+def _dominant_roofline(kernels):
+    dom = max(kernels, key=lambda k: k["total_ms"])
+    if dom["alu_frac"] > dom["hbm_frac"]:
+        rl = {"bound": "alu", "kernel": dom["kernel"], "achieved": round(dom["alu_frac"] * FP64_VECTOR_PEAK_TFLOPS, 2),
+              "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": dom["alu_frac"], "traffic": None}
+    else:
+        rl = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["achieved_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+              "frac": dom["hbm_frac"], "traffic": None}
+    for k in kernels:
+        k.pop("total_ms", None)
+    return rl
+
+
+def _time_calls(torch, fn, reps):
+    fn()
+    torch.cuda.synchronize()
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0.record()
+    for _ in range(reps):
+        fn()
+    t1.record()
+    torch.cuda.synchronize()
+    return t0.elapsed_time(t1) / reps
+
+
+def bench_rotate(args, torch, K, ks_inputs):
+    """Configuration 3: 64 ciphertexts x 16 hoisted rotations per call (one ModUp per ciphertext, 16 rotation keys)."""
+    cfg = ks_inputs.CONFIGS[3]
+    q, p = ks_inputs.moduli(cfg)
+    logN, L, B, R, dnum = cfg["logN"], cfg["L"], cfg["batch"], cfg["n_rot"], cfg["dnum"]
+    N = 1 << logN
+    ctx = K.Context(logN, q, p, dnum)
+    ct = ks_inputs.uniform_residues(cfg["seed"], 1, (B, 2), q, N, device="cuda")
+    keys = [ks_inputs.uniform_residues(cfg["seed"], 10 + r, (dnum, 2), q + p, N, device="cuda") for r in range(R)]
+    gal = ks_inputs.galois_elements(logN, R)
+    out = torch.empty((B, R, 2, L, N), dtype=torch.int64, device="cuda")
+    ws = torch.empty(K.ks_workspace_bytes(ctx, K.KS_OP_ROTATE_HOISTED, L, B, R) // 8, dtype=torch.int64, device="cuda")
+    fn = lambda: K.ks_rotate_hoisted(ctx, ct, L, gal, keys, out, ws)
+    reps = max(2, args.steps // 60)
+    ms = _time_calls(torch, fn, reps)
+    kernels = _kernel_breakdown(K, torch, fn, B * R)
+    return {"metric": "rotations_per_sec", "value": round(B * R / (ms * 1e-3), 1), "unit": "rotation/s", "n_gpus": 1, "steps": reps,
+            "warmup": 1, "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "f64", "data": "synthetic",
+            "config": {"workload": "hoisted-rotations N=2^16 L=24 K=8 dnum=3, 64 ciphertexts x 16 Galois elements per call"},
+            "roofline": _dominant_roofline(kernels), "kernels": kernels}
+
+
+def bench_hmult(args, torch, K, ks_inputs):
+    """Configuration 5: 256 ciphertext pairs per call: tensor product, relinearisation, rescale."""
+    cfg = ks_inputs.CONFIGS[5]
+    q, p = ks_inputs.moduli(cfg)
+    logN, L, B, dnum = cfg["logN"], cfg["L"], cfg["batch"], cfg["dnum"]
+    N = 1 << logN
+    ctx = K.Context(logN, q, p, dnum)
+    cta = ks_inputs.uniform_residues(cfg["seed"], 1, (B, 2), q, N, device="cuda")
+    ctb = ks_inputs.uniform_residues(cfg["seed"], 2, (B, 2), q, N, device="cuda")
+    rlk = ks_inputs.uniform_residues(cfg["seed"], 3, (dnum, 2), q + p, N, device="cuda")
+    out = torch.empty((B, 2, L - 1, N), dtype=torch.int64, device="cuda")
+    ws = torch.empty(K.ks_workspace_bytes(ctx, K.KS_OP_HMULT_RELIN_RESCALE, L, B) // 8, dtype=torch.int64, device="cuda")
+    fn = lambda: K.hmult_relin_rescale(ctx, cta, ctb, L, rlk, out, ws)
+    reps = max(2, args.steps // 60)
+    ms = _time_calls(torch, fn, reps)
+    kernels = _kernel_breakdown(K, torch, fn, B)
+    return {"metric": "hmults_per_sec", "value": round(B / (ms * 1e-3), 1), "unit": "HMult+relin+rescale/s", "n_gpus": 1, "steps": reps,
+            "warmup": 1, "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "f64", "data": "synthetic",
+            "config": {"workload": "hmult-relin-rescale N=2^16 L=35 K=12 dnum=3, 256 ciphertext pairs per call"},
+            "roofline": _dominant_roofline(kernels), "kernels": kernels}
+
+
 def bench_ntt(args, torch, K, ks_inputs):
     cfg = ks_inputs.CONFIGS[4]
     q, p = ks_inputs.moduli(cfg)
@@ -202,7 +290,9 @@ def bench_ntt(args, torch, K, ks_inputs):
     ms = t0.elapsed_time(t1) / steps
     limbs = 2 * L * batch
     bytes_one_pass = limbs * N * 8 * 2.0
-    return {"metric": "limb_ntts_per_sec", "value": round(limbs / (ms * 1e-3), 1), "unit": "limb-NTT/s (2^16 points)", "n_gpus": 1,
+    kernels = _kernel_breakdown(K, torch, lambda: (K.ntt_fwd(ctx, data, ids), K.ntt_inv(ctx, data, ids)), limbs)
+    _dominant_roofline(kernels)
+    return {"metric": "limb_ntts_per_sec", "kernels": kernels, "value": round(limbs / (ms * 1e-3), 1), "unit": "limb-NTT/s (2^16 points)", "n_gpus": 1,
             "steps": steps, "warmup": 1, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
             "vs_baseline": None, "dtype": "f64", "data": "synthetic",
             "config": {"workload": "batched-ntt N=2^16 60 limbs x 32 polynomials, forward then inverse"},
@@ -236,7 +326,7 @@ def main():
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--sets", type=int, default=6, help="disjoint buffer sets rotated through (cold-cache figure)")
-    ap.add_argument("--workload", default="keyswitch", choices=["keyswitch", "ntt", "copy"])
+    ap.add_argument("--workload", default="keyswitch", choices=["keyswitch", "ntt", "rotate", "hmult", "copy"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -255,6 +345,10 @@ def main():
         result = bench_copy(args, torch)
     elif args.workload == "ntt":
         result = bench_ntt(args, torch, K, ks_inputs)
+    elif args.workload == "rotate":
+        result = bench_rotate(args, torch, K, ks_inputs)
+    elif args.workload == "hmult":
+        result = bench_hmult(args, torch, K, ks_inputs)
     else:
         result, (cfg, q, p, first_set) = bench_keyswitch(args, torch, K, ks_inputs)
         if not args.no_cpu_baseline:
