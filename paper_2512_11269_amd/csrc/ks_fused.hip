@@ -121,15 +121,15 @@ void launch_bconv_ntt_cols(const ks_ctx* c, const BConvPlan* d_plans, uint32_t n
                            uint32_t limbs_moved_per_poly, const uint64_t* y, uint64_t y_ps, uint64_t* out, uint64_t out_ps,
                            uint32_t n_polys, hipStream_t s, double ops_per_coeff) {
     if (n_polys == 0 || n_plans == 0) return;
-    // Targets per workgroup: fewer targets = more workgroups (small launches need them to fill 256 compute units)
-    // but more re-reads of the sources from cache.  Pick the largest TS that still gives every compute unit about
-    // two workgroups (measured best on the single-ciphertext launches); KS_BCONV_TS overrides it for experiments.
+    // Targets per workgroup: fewer targets = more workgroups but more re-reads of the sources from cache.  Four is
+    // best once the launch has a few workgroups per compute unit; for the single-ciphertext launches three measured
+    // best (384 and 256 workgroups: every one resident at once, none waiting for a second round).
+    // KS_BCONV_TS overrides the choice for experiments.
     const uint32_t tiles = c->logN == 16 ? 16 : 1;
-    int ts = 4;
-    while (ts > 1 && (uint64_t)tiles * n_plans * ((max_targets + ts - 1) / ts) * n_polys < 512) ts >>= 1;
+    int ts = (uint64_t)tiles * n_plans * ((max_targets + 3) / 4) * n_polys >= 512 ? 4 : 3;
     if (const char* e = getenv("KS_BCONV_TS")) {
         const int v = atoi(e);
-        if (v == 1 || v == 2 || v == 4) ts = v;
+        if (v >= 1 && v <= 4) ts = v;
     }
     const uint32_t n_subsets = (max_targets + ts - 1) / ts;
     const dim3 grid(tiles, n_plans * n_subsets, n_polys), block(256);
@@ -138,10 +138,12 @@ void launch_bconv_ntt_cols(const ks_ctx* c, const BConvPlan* d_plans, uint32_t n
     hipLaunchKernelGGL((bconv_ntt_cols<LOGR, TSV>), grid, block, 0, s, c->d_tw_fwd, d_plans, y, y_ps, out, out_ps, n_subsets)
     if (c->logN == 16) {
         if (ts == 4) KS_LAUNCH_BCONV(8, 4);
+        else if (ts == 3) KS_LAUNCH_BCONV(8, 3);
         else if (ts == 2) KS_LAUNCH_BCONV(8, 2);
         else KS_LAUNCH_BCONV(8, 1);
     } else {
         if (ts == 4) KS_LAUNCH_BCONV(4, 4);
+        else if (ts == 3) KS_LAUNCH_BCONV(4, 3);
         else if (ts == 2) KS_LAUNCH_BCONV(4, 2);
         else KS_LAUNCH_BCONV(4, 1);
     }
