@@ -34,12 +34,12 @@ MIB = 1024.0 * 1024.0
 # workload and kernel; None where no counter run has been taken yet.
 MEASURED_TRAFFIC_BYTES: dict = {
     # profiles/keyswitch_cfg2_hbm_traffic.txt: FETCH_SIZE scaled by 2.0 and WRITE_SIZE by 1.0 (what the same counters
-    # read for a 1 GiB device copy), summed, per launch.  The excess over the algorithmic bytes is twiddle-table reads.
-    ("keyswitch", "rows_inner_product"): 206214385,
-    ("keyswitch", "rows_moddown_finish"): 93516420,
-    ("keyswitch", "bconv_ntt_cols"): 43110608,      # mean of the ModUp (52.1 MB) and ModDown (34.2 MB) launches
-    ("keyswitch", "ntt_inv_rows"): 38068632,
-    ("keyswitch", "ntt_inv_cols"): 21377947,
+    # read for a 1 GiB device copy), summed, per launch.  The excess over the algorithmic bytes (2-8 %) is twiddle reads.
+    ("keyswitch", "rows_inner_product"): 187909334,
+    ("keyswitch", "rows_moddown_finish"): 77838647,
+    ("keyswitch", "bconv_ntt_cols"): 43172065,      # mean of the ModUp and the ModDown launch
+    ("keyswitch", "ntt_inv_rows"): 27093640,
+    ("keyswitch", "ntt_inv_cols"): 21384217,        # mean of the 24-limb and the 16-limb launch
 }
 
 
