@@ -44,12 +44,13 @@ void mod_up(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, 
     launch_ntt_inv_rows(c, lv.q_map, XformIO{d, coeff, d_ps, coeff_ps, bc}, s);
     // the column half also multiplies by N^-1 (D_j/q_i)^-1 and leaves canonical doubles for the conversion
     launch_ntt_inv_cols(c, lv.q_map, coeff, coeff_ps, bc, lv.d_modup_scale, true, true, s);
-    // algorithmic fp64 work per coefficient: 7 per source x target product-accumulate, then per target one reduction
-    // and the column stages (8 per butterfly, half a butterfly per point and stage)
+    // algorithmic fp64 work per coefficient: 3 FMAs per source x target plus the 6-addition split of the source shared
+    // by four targets (4.5 in all), then per target one reduction and the column stages (8 per butterfly, half a
+    // butterfly per point and stage)
     double ops = 0.0;
     for (uint32_t j = 0; j < lv.ndig; ++j) {
         const double a = lv.digit_hi[j] - lv.digit_lo[j];
-        ops += a * (lv.E - a) * 7.0;
+        ops += a * (lv.E - a) * 4.5;
     }
     ops += lv.n_new * (3.0 + 4.0 * (c->logN - 8));
     launch_bconv_ntt_cols(c, lv.d_modup, lv.ndig, lv.max_targets, lv.ell + lv.n_new, coeff, coeff_ps, lifted, lifted_ps, bc, s, ops);
@@ -65,7 +66,7 @@ void mod_down(const ks_ctx* c, const Level& lv, uint64_t* acc, uint64_t* conv, u
     // the fused inner product already ran the row half of the inverse transform on the special limbs
     if (!special_rows_done) launch_ntt_inv_rows(c, lv.special_map, XformIO{acc, acc, acc_ps, acc_ps, 2 * bc}, s);
     launch_ntt_inv_cols(c, lv.special_map, acc, acc_ps, 2 * bc, c->d_moddown_scale, true, true, s);
-    const double ops = (double)c->K * lv.ell * 7.0 + lv.ell * (3.0 + 4.0 * (c->logN - 8));
+    const double ops = (double)c->K * lv.ell * 4.5 + lv.ell * (3.0 + 4.0 * (c->logN - 8));
     launch_bconv_ntt_cols(c, lv.d_moddown, 1, lv.ell, c->K + lv.ell, acc, acc_ps, conv, conv_ps, 2 * bc, s, ops);
     launch_rows_moddown_finish(c, lv, acc, conv, out, out_bs, addend, addend_bs, addend_comps, galois, bc, s);
 }

@@ -1,6 +1,7 @@
 // Context construction: parameter validation, twiddle tables, base-conversion constants.
 // Host-side number theory here is the library's own (128-bit products); it shares nothing with
 // the CPU reference used by the tests.
+#include <math.h>
 #include <string.h>
 
 #include <algorithm>
@@ -100,7 +101,11 @@ void fill_bconv_plan(const ks_ctx* c, BConvPlan* plan, const uint32_t* src_ids, 
             uint64_t prod = 1 % mt;
             for (uint32_t k = 0; k < n_src; ++k)
                 if (k != i) prod = h_mulmod(prod, c->mod[src_ids[k]] % mt, mt);
-            plan->hat[t][i] = (double)prod;
+            for (int k = 0; k < 3; ++k) {
+                const uint64_t f = h_mulmod(prod, (1ull << (12 * k)) % mt, mt);
+                const double centred = f > mt / 2 ? -(double)(mt - f) : (double)f;
+                plan->hats[t][i][k] = ldexp(centred, -12 * k);
+            }
             plan->hat3[t][i][0] = (double)(prod & 0xFFFu);
             plan->hat3[t][i][1] = (double)((prod >> 12) & 0xFFFu);
             plan->hat3[t][i][2] = (double)(prod >> 24);

@@ -46,10 +46,26 @@ KS_HD double mulmod_lazy(double a, double b, Mod m) {
     return r + l;
 }
 
-// Any integer-valued |x| < 2^50 -> representative with |r| <= 0.51 p.
+// Any integer-valued |x| < 2^53 -> representative with |r| <= 0.51 p (the quotient estimate is off by at most one
+// part in 2^51, the FMA is exact because its result is).
 KS_HD double reduce_lazy(double x, Mod m) {
     double q = __builtin_rint(x * m.pinv);
     return __builtin_fma(-q, m.p, x);
+}
+
+// Split an integer-valued 0 <= y < 2^36 into y = y2 + y1 + y0 with y2 a multiple of 2^24 (0 <= y2 <= 2^36), y1 a
+// multiple of 2^12 (|y1| <= 2^23) and |y0| <= 2^11, by rounding to nearest at the two granularities (adding and
+// subtracting 1.5 * 2^(52 + g) rounds to a multiple of 2^g).  Six additions, no products.
+// Use: with factors f_k = centred([f * 2^(12 k)]_t) * 2^(-12 k), |f_k| * 2^(12 k) <= 2^35, the sum
+// y2 f_2 + y1 f_1 + y0 f_0 is an integer congruent to y f modulo t and at most 2^48 in magnitude, so up to sixteen
+// such triples accumulate exactly in one double: a conversion costs three FMAs per source and target, the split is
+// shared by all targets of the source, and one reduction per target finishes it.
+KS_HD void split3(double y, double& y2, double& y1, double& y0) {
+    constexpr double kRound24 = 0x1.8p76, kRound12 = 0x1.8p64;
+    y2 = (y + kRound24) - kRound24;
+    const double rem = y - y2;
+    y1 = (rem + kRound12) - kRound12;
+    y0 = rem - y1;
 }
 
 // (s2 * 2^24 + s1 * 2^12 + s0) mod p as a lazy representative, for exact non-negative integer sums s_k < 2^52

@@ -18,14 +18,55 @@
 
 namespace ks {
 
+// One source of a conversion: acc[t][k] += y[k] * f[t] as exact integers -- each source point is split once (split3),
+// every target adds three products against its shifted, centred factors.
+// REFILL: once y[k] has been consumed, the same registers receive point k of the next source (byte offset next_off in
+// the buffer), which then has a whole source's worth of arithmetic to arrive.
+// The factors of the next source (fnext: uniform, scalar loads) are requested after the first point, together with
+// the limb index of the source after next: scalar loads complete out of order, so the first use of f waits for every
+// scalar load in flight, and at that moment only f's own, requested a source ago, should be.
+template <int LOG_R, int TS, bool REFILL>
+__device__ __forceinline__ void bconv_accumulate(double (&acc)[TS][16], double (&y)[16], const double (&f)[TS][3],
+                                                 double (&fnext)[TS][3], const double* const (&hat_row)[TS], int inext,
+                                                 uint32_t& limb_after, const uint32_t* src_limb, int iafter, BufferRsrc rsrc,
+                                                 uint32_t lane_off, uint32_t next_off) {
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        double y2, y1, y0;
+        split3(y[k], y2, y1, y0);
+        if (REFILL) y[k] = load_strided_point<LOG_R>(rsrc, lane_off, next_off, k);
+#pragma unroll
+        for (int tt = 0; tt < TS; ++tt)
+            acc[tt][k] = __builtin_fma(y2, f[tt][2], __builtin_fma(y1, f[tt][1], __builtin_fma(y0, f[tt][0], acc[tt][k])));
+        if (k == 0) {
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int tt = 0; tt < TS; ++tt)
+#pragma unroll
+                for (int p = 0; p < 3; ++p) fnext[tt][p] = hat_row[tt][inext * 4 + p];
+            limb_after = src_limb[iafter];
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    // one refill per point, in order, each after a point's worth of arithmetic: the wait before point k then leaves 15
+    // loads in flight, while the arithmetic of neighbouring points may still interleave
+    if (REFILL) {
+#pragma unroll
+        for (int k = 1; k < 16; ++k) {
+            __builtin_amdgcn_sched_group_barrier(0x002, 6 + 3 * TS, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
 // y: [poly][..][N] canonical doubles y_i = [x_i N^-1 (D/s_i)^-1]_{s_i} (written by ntt_inv_cols with its
 // scale table).  Each workgroup owns one column tile (4096 positions) and TS targets of one digit: it
-// accumulates sum_i y_i * (D/s_i mod t) lazily for its 16 positions per thread, then runs the column stages
-// of the forward transform modulo t and stores raw doubles.  The sources are re-read by the workgroups of
+// accumulates sum_i y_i * (D/s_i mod t) as an exact integer (split3) for its 16 positions per thread, then runs the
+// column stages of the forward transform modulo t and stores raw doubles.  The sources are re-read by the workgroups of
 // the other target subsets; those reads are served by L2 / the last-level cache.
 // ------------------------------------------------------------------------------------------------
-template <int LOG_R, int TS>
+template <int LOG_R, int TS, bool TWO_SETS>
 __global__ __launch_bounds__(256) void bconv_ntt_cols(const double* __restrict__ tw, const BConvPlan* __restrict__ plans,
                                                       const uint64_t* __restrict__ y, uint64_t y_ps, uint64_t* __restrict__ out,
                                                       uint64_t out_ps, uint32_t n_subsets) {
@@ -47,65 +88,85 @@ __global__ __launch_bounds__(256) void bconv_ntt_cols(const double* __restrict__
 #pragma unroll
         for (int k = 0; k < 16; ++k) acc[tt][k] = 0.0;
 
-    // Per-target constants.  The conversion factors are fetched with per-lane (vector) loads on purpose: they
-    // then ride the same wait counter as the prefetched source points instead of stalling on scalar-load
-    // latency once per source and target.  `lane0` is zero but opaque to the compiler.
-    const uint32_t lane0 = tid >> 10;
+    // Per-target constants.  They are uniform across the workgroup and travel through scalar loads.
     Mod mt[TS];
     const double* hat_row[TS];
 #pragma unroll
     for (int tt = 0; tt < TS; ++tt) {
         const int t = min(t0 + tt, n_dst - 1);  // a ragged last subset recomputes its last target (stored once)
         mt[tt] = P.dst_mod[t];
-        hat_row[tt] = &P.hat[t][0] + lane0;
+        hat_row[tt] = &P.hats[t][0][0];
     }
 
-    // software pipeline over the sources: the next source's 16 points and factors are in flight while this
-    // one's are used
-    double ynext[16], hnext[TS];
-    {
-        const uint64_t* src = yp + (uint64_t)P.src_limb[0] * N;
+    // Software pipeline over the sources, two per trip so that the uniform factors can alternate between two scalar
+    // register sets, with the limb index of the source after next fetched ahead as well: nothing is waited for right
+    // after it was requested.  The 16 points of a source are either held in ONE register set that is refilled point by
+    // point with the next source while it is consumed (fewer registers; best for the few-workgroup launches of a single
+    // ciphertext), or in TWO sets, the idle one filled by a burst of 16 loads (measured 6 % faster on full-chip launches).
+    // Sources past the end are zero-padded in the plan (factor 0, a valid limb): prefetches are unconditional -- a
+    // conditional one would make the wait-count bookkeeping assume the worst at the join and stall every use on the
+    // newest loads -- and an odd source count simply runs one padding source.  Loads are fenced into use order, before
+    // the loop as inside it, so that every wait leaves exactly the younger loads in flight.  The points are read through a
+    // buffer descriptor of this polynomial's bundle: per-lane offset in a vector register, limb and row offset in a
+    // scalar one, so switching limb costs no vector instructions.
+    const BufferRsrc ysrd = make_buffer_rsrc(yp, y_ps * 8);
+    const uint32_t lane_off = (r0 * 256 + col) * 8;
+    double yv[16], ha[TS][3], hb[TS][3];
 #pragma unroll
-        for (int k = 0; k < 16; ++k) ynext[k] = load_f64(src + col_row_strided<LOG_R>(r0, k) * 256 + col);
-#pragma unroll
-        for (int tt = 0; tt < TS; ++tt) hnext[tt] = hat_row[tt][0];
+    for (int k = 0; k < 16; ++k) {
+        yv[k] = load_strided_point<LOG_R>(ysrd, lane_off, P.src_limb[0] * (N * 8), k);
+        __builtin_amdgcn_sched_barrier(0);
     }
-    // twiddles of the first target's column transform, also ahead of time
-    PassTwiddles tws;
-    load_col_twiddles<LOG_R>(tws, tw + (size_t)P.dst_mod_id[t0] * N + lane0, r0);
+#pragma unroll
+    for (int tt = 0; tt < TS; ++tt)
+#pragma unroll
+        for (int p = 0; p < 3; ++p) ha[tt][p] = hat_row[tt][p];
+    uint32_t limb_next = P.src_limb[1];
 
+    if constexpr (!TWO_SETS) {
 #pragma unroll 1
-    for (int i = 0; i < n_src; ++i) {
-        double yv[16], hv[TS];
-#pragma unroll
-        for (int k = 0; k < 16; ++k) yv[k] = ynext[k];
-#pragma unroll
-        for (int tt = 0; tt < TS; ++tt) hv[tt] = hnext[tt];
-        {
-            // Unconditional prefetch: sources past the end are zero-padded in the plan (factor 0, a valid limb), so
-            // the extra fetch is harmless, while a conditional one would make the wait-count bookkeeping assume the
-            // worst at the join and stall every use on the newest loads.
-            const int inext = min(i + 1, kMaxSrc - 1);
-            const uint64_t* src = yp + (uint64_t)P.src_limb[inext] * N;
-#pragma unroll
-            for (int k = 0; k < 16; ++k) ynext[k] = load_f64(src + col_row_strided<LOG_R>(r0, k) * 256 + col);
-#pragma unroll
-            for (int tt = 0; tt < TS; ++tt) hnext[tt] = hat_row[tt][inext];
+        for (int i = 0; i < n_src; i += 2) {
+            uint32_t limb_after;
+            bconv_accumulate<LOG_R, TS, true>(acc, yv, ha, hb, hat_row, min(i + 1, kMaxSrc - 1), limb_after, P.src_limb,
+                                              min(i + 2, kMaxSrc - 1), ysrd, lane_off, limb_next * (N * 8));
+            bconv_accumulate<LOG_R, TS, true>(acc, yv, hb, ha, hat_row, min(i + 2, kMaxSrc - 1), limb_next, P.src_limb,
+                                              min(i + 3, kMaxSrc - 1), ysrd, lane_off, limb_after * (N * 8));
         }
-        __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of the arithmetic below
+    } else {
+        double yw[16];
+#pragma unroll 1
+        for (int i = 0; i < n_src; i += 2) {
+            uint32_t limb_after;
 #pragma unroll
-        for (int tt = 0; tt < TS; ++tt)
+            for (int k = 0; k < 16; ++k) {
+                yw[k] = load_strided_point<LOG_R>(ysrd, lane_off, limb_next * (N * 8), k);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            bconv_accumulate<LOG_R, TS, false>(acc, yv, ha, hb, hat_row, min(i + 1, kMaxSrc - 1), limb_after, P.src_limb,
+                                               min(i + 2, kMaxSrc - 1), ysrd, lane_off, 0);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int k = 0; k < 16; ++k) acc[tt][k] += mulmod_lazy(yv[k], hv[tt], mt[tt]);
+            for (int k = 0; k < 16; ++k) {
+                yv[k] = load_strided_point<LOG_R>(ysrd, lane_off, limb_after * (N * 8), k);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            bconv_accumulate<LOG_R, TS, false>(acc, yw, hb, ha, hat_row, min(i + 2, kMaxSrc - 1), limb_next, P.src_limb,
+                                               min(i + 3, kMaxSrc - 1), ysrd, lane_off, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 
+    // Twiddles are requested one target ahead and always before the previous target's stores are issued: loads and
+    // stores share one in-order counter, so a wait for a load issued after a store would also wait for the store to be
+    // acknowledged by memory.
+    PassTwiddles tws;
+    load_col_twiddles<LOG_R>(tws, tw + (size_t)P.dst_mod_id[t0] * N, r0);
 #pragma unroll
     for (int tt = 0; tt < TS; ++tt) {
         const int t = t0 + tt;
         if (t < n_dst) {  // uniform
             PassTwiddles cur = tws;
-            if (tt + 1 < TS && t + 1 < n_dst)  // next target's twiddles travel while this target is transformed
-                load_col_twiddles<LOG_R>(tws, tw + (size_t)P.dst_mod_id[t + 1] * N + lane0, r0);
+            if (tt + 1 < TS && t + 1 < n_dst) load_col_twiddles<LOG_R>(tws, tw + (size_t)P.dst_mod_id[t + 1] * N, r0);
 #pragma unroll
             for (int k = 0; k < 16; ++k) acc[tt][k] = reduce_lazy(acc[tt][k], mt[tt]);
             col_fwd_core<LOG_R>(acc[tt], cur, c, r0, lds, mt[tt]);
@@ -121,9 +182,10 @@ void launch_bconv_ntt_cols(const ks_ctx* c, const BConvPlan* d_plans, uint32_t n
                            uint32_t limbs_moved_per_poly, const uint64_t* y, uint64_t y_ps, uint64_t* out, uint64_t out_ps,
                            uint32_t n_polys, hipStream_t s, double ops_per_coeff) {
     if (n_polys == 0 || n_plans == 0) return;
-    // Targets per workgroup: fewer targets = more workgroups but more re-reads of the sources from cache.  Four is
-    // best once the launch has a few workgroups per compute unit; for the single-ciphertext launches three measured
-    // best (384 and 256 workgroups: every one resident at once, none waiting for a second round).
+    // Targets per workgroup: fewer targets = more workgroups but more re-reads and re-splits of the sources.  Four (with
+    // the two-set source pipeline) is best once the launch has a few workgroups per compute unit; for the
+    // single-ciphertext launches three (one-set pipeline) measured best (384 and 256 workgroups: every one resident at
+    // once, none waiting for a second round).
     // KS_BCONV_TS overrides the choice for experiments.
     const uint32_t tiles = c->logN == 16 ? 16 : 1;
     int ts = (uint64_t)tiles * n_plans * ((max_targets + 3) / 4) * n_polys >= 512 ? 4 : 3;
@@ -135,7 +197,7 @@ void launch_bconv_ntt_cols(const ks_ctx* c, const BConvPlan* d_plans, uint32_t n
     const dim3 grid(tiles, n_plans * n_subsets, n_polys), block(256);
     ProfScope ps("bconv_ntt_cols", (double)limbs_moved_per_poly * n_polys * c->N * 8.0, s, ops_per_coeff * n_polys * c->N);
 #define KS_LAUNCH_BCONV(LOGR, TSV) \
-    hipLaunchKernelGGL((bconv_ntt_cols<LOGR, TSV>), grid, block, 0, s, c->d_tw_fwd, d_plans, y, y_ps, out, out_ps, n_subsets)
+    hipLaunchKernelGGL((bconv_ntt_cols<LOGR, TSV, (TSV == 4)>), grid, block, 0, s, c->d_tw_fwd, d_plans, y, y_ps, out, out_ps, n_subsets)
     if (c->logN == 16) {
         if (ts == 4) KS_LAUNCH_BCONV(8, 4);
         else if (ts == 3) KS_LAUNCH_BCONV(8, 3);
@@ -180,8 +242,13 @@ __global__ __launch_bounds__(64) void rows_inner_product(TwTables tw, TwTables t
     double a0[16], a1[16];
 #pragma unroll
     for (int k = 0; k < 16; ++k) a0[k] = a1[k] = 0.0;
-    PassTwiddles t;
-    load_row_twiddles(t, tw, mid, N, R + row, j0, m);
+    // every digit's transform uses the same twiddles; the first-pass ones live in LDS to leave registers for a second
+    // wavefront per SIMD
+    __shared__ double lds_ta[4 * 16];
+    double tb[16];
+    row_twiddles_to_lds(lds_ta + rr * 16, tw.W + (size_t)mid * N, R + row, j0);
+    load_row_twiddles_b(tb, tw, mid, N, R + row, j0, m);
+    __syncthreads();
 
 #pragma unroll 1
     for (uint32_t j = 0; j < dg.ndig; ++j) {
@@ -205,7 +272,7 @@ __global__ __launch_bounds__(64) void rows_inner_product(TwTables tw, TwTables t
         } else {
 #pragma unroll
             for (int k = 0; k < 16; ++k) x[k] = __longlong_as_double((long long)raw[k]);
-            row_fwd_core(x, t, j0, lds + rr * kRowPitch, m);
+            row_fwd_core_lds(x, lds_ta + rr * 16, tb, j0, lds + rr * kRowPitch, m);
         }
 #pragma unroll
         for (int k = 0; k < 16; ++k) {

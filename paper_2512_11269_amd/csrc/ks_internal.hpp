@@ -39,7 +39,9 @@ struct BConvPlan {
     // 12-bit piece is below 2^48, so up to 16 such products add up exactly in a double: the conversion sum costs
     // three FMAs per source and target plus one short recombination per target instead of a full modular product.
     double hat3[kMaxDst][kMaxSrc][3];
-    double hat[kMaxDst][kMaxSrc];  // the same factors whole, for kernels that use a full modular product
+    // hats[t][i][k], k = 0..2: centred([(D / s_i) 2^(12 k)]_t) * 2^(-12 k), the factors that go with the three pieces
+    // of a split source residue (split3); [3] pads the row to 32 bytes.  Zero for padding sources.
+    double hats[kMaxDst][kMaxSrc][4];
 };
 
 // Everything the key-switching pipeline needs at one level ell.

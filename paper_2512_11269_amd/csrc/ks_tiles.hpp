@@ -60,6 +60,28 @@ __device__ __forceinline__ void load_row_twiddles(PassTwiddles& t, const TwTable
     t.b[12] = mulmod_lazy(T1, w[1], m);  t.b[13] = mulmod_lazy(T1, w[5], m);
     t.b[14] = mulmod_lazy(T1, w[3], m);  t.b[15] = mulmod_lazy(T1, w[7], m);
 }
+// The same with the first-pass twiddles left out (for kernels that keep them in LDS, see row_twiddles_to_lds).
+__device__ __forceinline__ void load_row_twiddles_b(double (&tb)[16], const TwTables& tbl, uint32_t mod_id, uint32_t N, uint32_t node,
+                                                    uint32_t j0, Mod m) {
+    const double* w = tbl.w16 + mod_id * 8;
+    const double T1 = tbl.trow[(size_t)mod_id * (N / 16) + (node * 16 + j0 - N / 16)];
+    const double T2 = mulmod_lazy(T1, T1, m), T4 = mulmod_lazy(T2, T2, m), T8 = mulmod_lazy(T4, T4, m);
+    tb[0] = 0.0;
+    tb[1] = T8;
+    tb[2] = T4;  tb[3] = mulmod_lazy(T4, w[4], m);
+    tb[4] = T2;  tb[5] = mulmod_lazy(T2, w[4], m);  tb[6] = mulmod_lazy(T2, w[2], m);  tb[7] = mulmod_lazy(T2, w[6], m);
+    tb[8] = T1;  tb[9] = mulmod_lazy(T1, w[4], m);  tb[10] = mulmod_lazy(T1, w[2], m); tb[11] = mulmod_lazy(T1, w[6], m);
+    tb[12] = mulmod_lazy(T1, w[1], m);  tb[13] = mulmod_lazy(T1, w[5], m);
+    tb[14] = mulmod_lazy(T1, w[3], m);  tb[15] = mulmod_lazy(T1, w[7], m);
+}
+// First-pass twiddles of a row (the 15 table entries below heap node `node`, the same for the row's 16 lanes) placed in
+// 16 doubles of LDS: lane j0 fetches entry j0.  Frees 30 registers per lane where a kernel is short of them; the
+// butterflies then read them as LDS broadcasts.  The caller synchronises before use.
+__device__ __forceinline__ void row_twiddles_to_lds(double* ta_row, const double* __restrict__ W, uint32_t node, uint32_t j0) {
+    const uint32_t u = 31u - __clz(j0 | 1u), g = j0 - (1u << u);
+    ta_row[j0] = j0 ? W[(node << u) + g] : 0.0;
+}
+
 // columns: heap node 1 for the first pass, 16 + r0 for the second (LOG_R = 8 only)
 template <int LOG_R>
 __device__ __forceinline__ void load_col_twiddles(PassTwiddles& t, const double* __restrict__ W, uint32_t r0) {
@@ -78,6 +100,23 @@ __device__ __forceinline__ void row_fwd_core(double (&v)[16], const PassTwiddles
 #pragma unroll
     for (int k = 0; k < 16; ++k) v[k] = lrow[17 * j0 + k];
     radix16_fwd(v, t.b, m);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) lrow[17 * j0 + k] = v[k];
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = lrow[j0 + 17 * k];
+}
+
+// The same with the first-pass twiddles read from LDS (ta: 16 doubles of this row) and the second-pass ones in registers.
+__device__ __forceinline__ void row_fwd_core_lds(double (&v)[16], const double* ta, const double (&tb)[16], uint32_t j0, double* lrow,
+                                                 Mod m) {
+    radix16_fwd(v, *reinterpret_cast<const double(*)[16]>(ta), m);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) lrow[j0 + 17 * k] = v[k];
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = lrow[17 * j0 + k];
+    radix16_fwd(v, tb, m);
 #pragma unroll
     for (int k = 0; k < 16; ++k) lrow[17 * j0 + k] = v[k];
     __syncthreads();
@@ -134,6 +173,21 @@ __device__ __forceinline__ void col_inv_core(double (&v)[16], const PassTwiddles
         for (int k = 0; k < 16; ++k) v[k] = lds[(r0 + 16 * k) * TC + c];
     }
     radix16_inv(v, t.a, m);
+}
+
+// Buffer descriptor of a tensor slice (raw, unstrided; gfx9 data-format word): loads through it take a per-lane byte
+// offset in a vector register plus a uniform byte offset in a scalar register, and reads beyond `bytes` return zero.
+using BufferRsrc = __amdgpu_buffer_rsrc_t;
+__device__ __forceinline__ BufferRsrc make_buffer_rsrc(const void* base, uint64_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)(uint32_t)bytes, 0x00020000);
+}
+
+// Point k of the 16 strided points of a column-pass thread (rows r0 + 16 k, or k when a limb has only 16 rows): the
+// double at byte offset limb_off + k * (4096 | 256) * 8 + lane_off of the buffer, lane_off = 8 (256 r0 + column).
+template <int LOG_R>
+__device__ __forceinline__ double load_strided_point(BufferRsrc rsrc, uint32_t lane_off, uint32_t limb_off, int k) {
+    constexpr uint32_t kStrideBytes = (LOG_R == 8 ? 4096u : 256u) * 8u;
+    return __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)lane_off, (int)(limb_off + k * kStrideBytes), 0));
 }
 
 // Row index of v[k] before / after the column cores, and the first column of the tile.

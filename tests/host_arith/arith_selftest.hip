@@ -69,6 +69,34 @@ static void check_prime(uint64_t p) {
         const i128 exact = ((i128)s2 << 24) + ((i128)s1 << 12) + s0;
         CHECK(fabs(r) <= lim && mod_i128((i128)(int64_t)r, p) == mod_i128(exact, p), "combine3");
     }
+    // split3: the pieces add up, have the stated granularity and magnitude; with the centred shifted factors, sixteen
+    // sources accumulate exactly and reduce to sum y_i f_i mod p
+    for (int rep = 0; rep < 20000; ++rep) {
+        double acc = 0.0;
+        i128 exact = 0;
+        for (int i = 0; i < 16; ++i) {
+            uint64_t y = rnd() >> 28;  // below 2^36
+            if (rep % 9 == 0) y = (uint64_t[]){0, (1ull << 36) - 1, (1ull << 24) - 1, 1ull << 23, (1ull << 23) + (1ull << 11), p - 1, 0xFFF800800ull, 0x800800ull}[(rep / 9 + i) % 8];
+            uint64_t f = rnd() % p;
+            if (rep % 5 == 0) f = (i & 1) ? p / 2 : p / 2 + 1;  // largest centred magnitudes
+            double y2, y1, y0;
+            split3((double)y, y2, y1, y0);
+            CHECK(y2 + y1 + y0 == (double)y, "split3 sum %llu", (unsigned long long)y);
+            CHECK(fmod(y2, 16777216.0) == 0 && y2 >= 0 && y2 <= 68719476736.0, "split3 y2 %llu", (unsigned long long)y);
+            CHECK(fmod(y1, 4096.0) == 0 && fabs(y1) <= 8388608.0, "split3 y1 %llu", (unsigned long long)y);
+            CHECK(fabs(y0) <= 2048.0 && y0 == floor(y0), "split3 y0 %llu", (unsigned long long)y);
+            double fk[3];
+            for (int k = 0; k < 3; ++k) {
+                const uint64_t s = (uint64_t)(((i128)f << (12 * k)) % p);
+                fk[k] = ldexp(s > p / 2 ? -(double)(p - s) : (double)s, -12 * k);
+            }
+            acc = __builtin_fma(y2, fk[2], __builtin_fma(y1, fk[1], __builtin_fma(y0, fk[0], acc)));
+            CHECK(acc == floor(acc) && fabs(acc) < 9007199254740992.0, "split3 accumulator not an exact integer");
+            exact += (i128)y * f;
+        }
+        const double r = reduce_lazy(acc, m);
+        CHECK(fabs(r) <= lim && mod_i128((i128)(int64_t)r, p) == mod_i128(exact, p), "split3 conversion sum");
+    }
     // sixteen-point passes against exact butterflies; growth bounds
     for (int rep = 0; rep < 2000; ++rep) {
         double t[16], v[16], w[16];
