@@ -42,6 +42,7 @@ def _load():
         lib.orc_rotate_hoisted.argtypes = [ctypes.c_void_p, _u64p, ctypes.c_int, _u32p,
                                            ctypes.POINTER(_u64p), ctypes.c_int, _u64p, ctypes.c_int]
         lib.orc_hmult_relin_rescale.argtypes = [ctypes.c_void_p, _u64p, _u64p, ctypes.c_int, _u64p, _u64p, ctypes.c_int]
+        lib.orc_hmult_relin_rescale_merged.argtypes = [ctypes.c_void_p, _u64p, _u64p, ctypes.c_int, _u64p, _u64p, ctypes.c_int]
         lib.orc_max_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -135,4 +136,15 @@ class COracle:
         batch = cta.size // (2 * ell * self.N)
         out = np.zeros((batch, 2, ell - 1, self.N), dtype=np.uint64)
         _load().orc_hmult_relin_rescale(self._h, _p64(cta), _p64(ctb), ell, _p64(rlk), _p64(out), batch)
+        return out
+
+    def hmult_relin_rescale_merged(self, cta: np.ndarray, ctb: np.ndarray, rlk: np.ndarray, ell: int | None = None) -> np.ndarray:
+        """As hmult_relin_rescale, with ModDown and rescale merged into one division by P q_{ell-1}."""
+        ell = self.L if ell is None else ell
+        cta = np.ascontiguousarray(cta, dtype=np.uint64)
+        ctb = np.ascontiguousarray(ctb, dtype=np.uint64)
+        rlk = np.ascontiguousarray(rlk, dtype=np.uint64)
+        batch = cta.size // (2 * ell * self.N)
+        out = np.zeros((batch, 2, ell - 1, self.N), dtype=np.uint64)
+        _load().orc_hmult_relin_rescale_merged(self._h, _p64(cta), _p64(ctb), ell, _p64(rlk), _p64(out), batch)
         return out

@@ -429,6 +429,45 @@ def hmult_relin_rescale(pr: Params, cta, ctb, rlk, ell: int | None = None):
     return rescale(pr, c0, ell), rescale(pr, c1, ell)
 
 
+def mod_down_merged(pr: Params, acc_c: list[list[int]], addend: list[list[int]], ell: int) -> list[list[int]]:
+    """ModDown merged with the rescale that follows it (Compiler, polynomial-level optimisations:
+    "mod down merging"): instead of dividing by P and then by q_{ell-1}, add P * addend on the
+    ciphertext limbs (the addend is what the division by P would have been added to: d0 or d1 of a
+    multiplication) and divide once by D = P * q_{ell-1}, with one base conversion from the basis
+    {p_0..p_{K-1}, q_{ell-1}} to q_0..q_{ell-2}:
+
+        acc'[i]   = acc[i] + [P]_{q_i} * addend[i]            i < ell   (special limbs unchanged: P = 0 there)
+        out[i]    = (acc'[i] - NTT(BConv_{S -> q_i}(INTT(acc' on S)))) * D^-1 mod q_i,   i < ell - 1.
+
+    The fast conversion lifts [acc']_D to [acc']_D + u D with 0 <= u <= K, so every coefficient of
+    the result is floor(acc' / D) - u: floor-type rounding throughout, where the unmerged chain
+    floors the division by P and rounds the division by q_{ell-1} to nearest."""
+    ql = pr.q[ell - 1]
+    accp = [[(a + (pr.P % pr.q[i]) * d) % pr.q[i] for a, d in zip(acc_c[i], addend[i])] for i in range(ell)]
+    src = list(pr.p) + [ql]
+    src_limbs = [intt(acc_c[ell + k], pr.p[k], pr.psi[pr.L + k]) for k in range(pr.K)]
+    src_limbs.append(intt(accp[ell - 1], ql, pr.psi[ell - 1]))
+    conv = bconv_fast(src_limbs, src, pr.q[:ell - 1])
+    D = pr.P * ql
+    out = []
+    for i in range(ell - 1):
+        qi = pr.q[i]
+        w = ntt(conv[i], qi, pr.psi[i])
+        dinv = pow(D % qi, -1, qi)
+        out.append([(a - b) * dinv % qi for a, b in zip(accp[i], w)])
+    return out
+
+
+def hmult_relin_rescale_merged(pr: Params, cta, ctb, rlk, ell: int | None = None):
+    """Homomorphic multiply with the relinearisation's ModDown and the rescale merged into one
+    division by P * q_{ell-1} (mod_down_merged).  Returns (out_0, out_1) on ell-1 limbs."""
+    ell = pr.L if ell is None else ell
+    d0, d1, d2 = tensor_product(pr, cta, ctb, ell)
+    lifted = mod_up(pr, d2, ell)
+    acc0, acc1 = inner_product(pr, lifted, rlk, ell)
+    return mod_down_merged(pr, acc0, d0, ell), mod_down_merged(pr, acc1, d1, ell)
+
+
 # --------------------------------------------------------------------------------------
 # textbook key generation, encryption, decryption (host side only)
 # --------------------------------------------------------------------------------------

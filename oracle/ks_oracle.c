@@ -396,6 +396,72 @@ void orc_hmult_relin_rescale(const orc_ctx *c, const u64 *cta, const u64 *ctb, i
     free(d0); free(d1); free(d2); free(ks);
 }
 
+/* ModDown merged with the rescale that follows (Compiler: "mod down merging"): acc' = acc + P * addend on the
+ * ciphertext limbs, then one division by D = P * q_{ell-1} through a fast conversion from the basis
+ * {p_0..p_{K-1}, q_{ell-1}} to q_0..q_{ell-2}.  Floor-type: every coefficient is floor(acc' / D) - u, 0 <= u <= K. */
+static void mod_down_merged(const orc_ctx *c, const u64 *acc_c, const u64 *addend, int ell, u64 *out) {
+    u64 N = c->N;
+    int K = c->K, S = K + 1;
+    u64 *accp = (u64 *)malloc(sizeof(u64) * ell * N);
+    for (int i = 0; i < ell; i++) {
+        u64 qi = c->mod[i], Pmod = 1;
+        for (int k = 0; k < K; k++) Pmod = mulmod(Pmod, c->mod[c->L + k] % qi, qi);
+        for (u64 n = (u64)i * N; n < (u64)(i + 1) * N; n++) accp[n] = addmod(acc_c[n], mulmod(Pmod, addend[n], qi), qi);
+    }
+    u64 *srcl = (u64 *)malloc(sizeof(u64) * S * N);
+    memcpy(srcl, acc_c + (u64)ell * N, sizeof(u64) * K * N);
+    memcpy(srcl + (u64)K * N, accp + (u64)(ell - 1) * N, sizeof(u64) * N);
+    uint32_t *src = (uint32_t *)malloc(sizeof(uint32_t) * S);
+    uint32_t *dst = (uint32_t *)malloc(sizeof(uint32_t) * ell);
+    for (int k = 0; k < K; k++) src[k] = c->L + k;
+    src[K] = ell - 1;
+    for (int i = 0; i < ell - 1; i++) dst[i] = i;
+#pragma omp parallel for schedule(dynamic)
+    for (int k = 0; k < S; k++) intt_limb(c, src[k], srcl + (u64)k * N);
+    u64 *conv = (u64 *)malloc(sizeof(u64) * ell * N);
+    bconv_poly(c, srcl, src, S, conv, dst, ell - 1);
+#pragma omp parallel for schedule(dynamic)
+    for (int i = 0; i < ell - 1; i++) {
+        u64 qi = c->mod[i];
+        ntt_limb(c, i, conv + (u64)i * N);
+        u64 Dmod = c->mod[ell - 1] % qi;
+        for (int k = 0; k < K; k++) Dmod = mulmod(Dmod, c->mod[c->L + k] % qi, qi);
+        u64 dinv = invmod(Dmod, qi);
+        for (u64 n = (u64)i * N; n < (u64)(i + 1) * N; n++) out[n] = mulmod(submod(accp[n], conv[n], qi), dinv, qi);
+    }
+    free(accp); free(srcl); free(conv); free(src); free(dst);
+}
+
+void orc_hmult_relin_rescale_merged(const orc_ctx *c, const u64 *cta, const u64 *ctb, int ell,
+                                    const u64 *rlk, u64 *out, int batch) {
+    u64 N = c->N;
+    u64 sz = (u64)ell * N;
+    int E = ell + c->K;
+    int ndig_max = (ell + c->alpha - 1) / c->alpha;
+    u64 *d0 = (u64 *)malloc(sizeof(u64) * sz), *d1 = (u64 *)malloc(sizeof(u64) * sz), *d2 = (u64 *)malloc(sizeof(u64) * sz);
+    u64 *lifted = (u64 *)malloc(sizeof(u64) * ndig_max * E * N);
+    u64 *acc = (u64 *)malloc(sizeof(u64) * 2 * E * N);
+    for (int b = 0; b < batch; b++) {
+        const u64 *b1 = cta + (u64)b * 2 * sz, *a1 = b1 + sz;
+        const u64 *b2 = ctb + (u64)b * 2 * sz, *a2 = b2 + sz;
+#pragma omp parallel for schedule(dynamic)
+        for (int i = 0; i < ell; i++) {
+            u64 qi = c->mod[i];
+            for (u64 n = (u64)i * N; n < (u64)(i + 1) * N; n++) {
+                d0[n] = mulmod(b1[n], b2[n], qi);
+                d1[n] = addmod(mulmod(a1[n], b2[n], qi), mulmod(a2[n], b1[n], qi), qi);
+                d2[n] = mulmod(a1[n], a2[n], qi);
+            }
+        }
+        int ndig = mod_up(c, d2, ell, lifted);
+        inner_product(c, lifted, ndig, ell, rlk, acc);
+        u64 *o = out + (u64)b * 2 * (ell - 1) * N;
+        mod_down_merged(c, acc, d0, ell, o);
+        mod_down_merged(c, acc + (u64)E * N, d1, ell, o + (u64)(ell - 1) * N);
+    }
+    free(d0); free(d1); free(d2); free(lifted); free(acc);
+}
+
 int orc_max_threads(void) {
 #ifdef _OPENMP
     extern int omp_get_max_threads(void);

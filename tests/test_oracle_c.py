@@ -106,6 +106,18 @@ def test_c_hmult_matches_python(c_oracle_lib, logN, L, K, dnum):
     assert got[0].tolist() == o0 and got[1].tolist() == o1
 
 
+@pytest.mark.parametrize("logN,L,K,dnum,ell", [(5, 4, 2, 2, 4), (7, 35, 12, 3, 35), (6, 6, 2, 3, 4)])
+def test_c_hmult_merged_matches_python(c_oracle_lib, logN, L, K, dnum, ell):
+    pr, co = _setup(c_oracle_lib, logN, L, K, dnum)
+    rng = random.Random(6)
+    rlk = _rand_key(rng, pr)
+    cta = (_rand(rng, pr, range(ell)), _rand(rng, pr, range(ell)))
+    ctb = (_rand(rng, pr, range(ell)), _rand(rng, pr, range(ell)))
+    got = co.hmult_relin_rescale_merged(_np([list(cta)]), _np([list(ctb)]), _np(rlk), ell)[0]
+    o0, o1 = R.hmult_relin_rescale_merged(pr, cta, ctb, rlk, ell)
+    assert got[0].tolist() == o0 and got[1].tolist() == o1
+
+
 def test_input_generator_is_counter_based():
     """Any slab regenerated alone equals the same slab of the whole tensor; residues are in range."""
     mods = R.ntt_primes(12, 3)
