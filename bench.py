@@ -267,8 +267,9 @@ def bench_rotate(args, torch, K, ks_inputs):
             "roofline": _dominant_roofline(kernels), "kernels": kernels}
 
 
-def bench_hmult(args, torch, K, ks_inputs):
-    """Configuration 5: 256 ciphertext pairs per call: tensor product, relinearisation, rescale."""
+def bench_hmult(args, torch, K, ks_inputs, merged=False):
+    """Configuration 5: 256 ciphertext pairs per call: tensor product, relinearisation, rescale (merged: the division
+    by P and the rescale done as one division by P q_last)."""
     cfg = ks_inputs.CONFIGS[5]
     q, p = ks_inputs.moduli(cfg)
     logN, L, B, dnum = cfg["logN"], cfg["L"], cfg["batch"], cfg["dnum"]
@@ -279,14 +280,16 @@ def bench_hmult(args, torch, K, ks_inputs):
     rlk = ks_inputs.uniform_residues(cfg["seed"], 3, (dnum, 2), q + p, N, device="cuda")
     out = torch.empty((B, 2, L - 1, N), dtype=torch.int64, device="cuda")
     ws = torch.empty(K.ks_workspace_bytes(ctx, K.KS_OP_HMULT_RELIN_RESCALE, L, B) // 8, dtype=torch.int64, device="cuda")
-    fn = lambda: K.hmult_relin_rescale(ctx, cta, ctb, L, rlk, out, ws)
+    entry = K.hmult_relin_rescale_merged if merged else K.hmult_relin_rescale
+    fn = lambda: entry(ctx, cta, ctb, L, rlk, out, ws)
     reps = max(2, args.steps // 60)
     ms = _time_calls(torch, fn, reps)
     kernels = _kernel_breakdown(K, torch, fn, B)
     return {"metric": "hmults_per_sec", "value": round(B / (ms * 1e-3), 1), "unit": "HMult+relin+rescale/s", "n_gpus": 1, "steps": reps,
             "warmup": 1, "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
             "dtype": "f64", "data": "synthetic",
-            "config": {"workload": "hmult-relin-rescale N=2^16 L=35 K=12 dnum=3, 256 ciphertext pairs per call"},
+            "config": {"workload": "hmult-relin-rescale N=2^16 L=35 K=12 dnum=3, 256 ciphertext pairs per call"
+                                   + (", ModDown merged with rescale" if merged else "")},
             "roofline": _dominant_roofline(kernels), "kernels": kernels}
 
 
@@ -348,7 +351,7 @@ def main():
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--sets", type=int, default=6, help="disjoint buffer sets rotated through (cold-cache figure)")
-    ap.add_argument("--workload", default="keyswitch", choices=["keyswitch", "ntt", "rotate", "hmult", "copy"])
+    ap.add_argument("--workload", default="keyswitch", choices=["keyswitch", "ntt", "rotate", "hmult", "hmult_merged", "copy"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -369,8 +372,8 @@ def main():
         result = bench_ntt(args, torch, K, ks_inputs)
     elif args.workload == "rotate":
         result = bench_rotate(args, torch, K, ks_inputs)
-    elif args.workload == "hmult":
-        result = bench_hmult(args, torch, K, ks_inputs)
+    elif args.workload in ("hmult", "hmult_merged"):
+        result = bench_hmult(args, torch, K, ks_inputs, merged=args.workload == "hmult_merged")
     else:
         result, (cfg, q, p, first_set) = bench_keyswitch(args, torch, K, ks_inputs)
         if not args.no_cpu_baseline:

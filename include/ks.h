@@ -123,6 +123,19 @@ int ks_rotate_hoisted(const ks_ctx* ctx, const uint64_t* ct, uint32_t ell, const
 int hmult_relin_rescale(const ks_ctx* ctx, const uint64_t* cta, const uint64_t* ctb, uint32_t ell,
                         const uint64_t* rlk, uint64_t* out, uint32_t batch, void* ws, size_t ws_bytes, void* stream);
 
+/* The same multiplication with the key-switch's division by P and the rescale merged into one division by
+ * P q_{ell-1} (Compiler, polynomial-level optimisations: "mod down merging"): P (d0, d1) is added to the
+ * accumulated inner products on the ciphertext limbs, limb ell-1 joins the K special limbs as a source of one base
+ * conversion to q_0..q_{ell-2}, and the result is multiplied by (P q_{ell-1})^-1.  It saves the rescale's own
+ * transforms; every coefficient of the result is floor(x / (P q_{ell-1})) - u with 0 <= u <= K where
+ * hmult_relin_rescale floors the first division and rounds the second, so the two differ in the low bits (same
+ * noise order) and each has its own reference result.
+ *   Arguments, layouts, workspace (KS_OP_HMULT_RELIN_RESCALE) and errors as hmult_relin_rescale; additionally
+ *   KS_EINVAL when K + 1 exceeds the 16 sources one conversion takes. */
+int hmult_relin_rescale_merged(const ks_ctx* ctx, const uint64_t* cta, const uint64_t* ctb, uint32_t ell,
+                               const uint64_t* rlk, uint64_t* out, uint32_t batch, void* ws, size_t ws_bytes,
+                               void* stream);
+
 /* Per-kernel timing for benchmarks (the paper's evaluation characterises its NTT, base-conversion and
  * elementwise kernel classes separately; this exposes the same breakdown).  While enabled, every kernel the
  * library launches is bracketed by a pair of HIP events on its stream (this creates events, i.e. it is not

@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     KsError,
     bconv,
     hmult_relin_rescale,
+    hmult_relin_rescale_merged,
     ks_keyswitch,
     ks_profile_enable,
     ks_profile_report,

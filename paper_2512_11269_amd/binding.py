@@ -56,6 +56,7 @@ def load_library():
     lib.ks_rotate_hoisted.argtypes = [_vp, _vp, ctypes.c_uint32, _u32p, ctypes.POINTER(_vp), ctypes.c_uint32, _vp,
                                       ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
     lib.hmult_relin_rescale.argtypes = [_vp, _vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
+    lib.hmult_relin_rescale_merged.argtypes = [_vp, _vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
     lib.ks_profile_enable.argtypes = [ctypes.c_int]
     lib.ks_profile_report.argtypes = [ctypes.c_char_p, ctypes.c_size_t]
     _lib = lib
@@ -170,3 +171,10 @@ def hmult_relin_rescale(ctx: Context, cta: torch.Tensor, ctb: torch.Tensor, ell:
     batch = cta.numel() // (2 * ell * ctx.N)
     _check(load_library().hmult_relin_rescale(ctx.handle, _dev_ptr(cta), _dev_ptr(ctb), ell, _dev_ptr(rlk), _dev_ptr(out),
                                               batch, _dev_ptr(ws), ws.numel() * 8, _stream()), "hmult_relin_rescale")
+
+
+def hmult_relin_rescale_merged(ctx: Context, cta: torch.Tensor, ctb: torch.Tensor, ell: int, rlk: torch.Tensor, out: torch.Tensor,
+                               ws: torch.Tensor) -> None:
+    batch = cta.numel() // (2 * ell * ctx.N)
+    _check(load_library().hmult_relin_rescale_merged(ctx.handle, _dev_ptr(cta), _dev_ptr(ctb), ell, _dev_ptr(rlk), _dev_ptr(out),
+                                                     batch, _dev_ptr(ws), ws.numel() * 8, _stream()), "hmult_relin_rescale_merged")

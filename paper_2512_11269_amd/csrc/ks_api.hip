@@ -243,6 +243,50 @@ extern "C" int ks_rotate_hoisted(const ks_ctx* c, const uint64_t* ct, uint32_t e
     return finish("ks_rotate_hoisted");
 }
 
+// Division by P q_{ell-1} of acc + P addend in one conversion (ModDown merged with the rescale that would follow):
+// limb ell-1 joins the special limbs as a source, the targets are q_0..q_{ell-2}.  The fused inner product has already
+// run the row half of the inverse transform on the special limbs.
+static void mod_down_merged(const ks_ctx* c, const Level& lv, uint64_t* acc, uint64_t* conv, uint64_t* out, uint64_t out_bs,
+                            const uint64_t* addend, uint64_t addend_bs, uint32_t bc, hipStream_t s) {
+    const uint64_t N = c->N, acc_ps = (uint64_t)lv.E * N, conv_ps = (uint64_t)lv.ell * N;
+    launch_add_scaled_limb(c, acc, acc_ps, addend, addend_bs, (uint64_t)lv.ell * N, lv.ell - 1, lv.Pmod_last, bc, s);
+    launch_ntt_inv_rows(c, lv.last_map, XformIO{acc, acc, acc_ps, acc_ps, 2 * bc}, s);
+    launch_ntt_inv_cols(c, lv.merged_map, acc, acc_ps, 2 * bc, lv.d_merged_scale, true, true, s);
+    const uint32_t n_src = c->K + 1, n_dst = lv.ell - 1;
+    const double ops = (double)n_src * n_dst * 4.5 + n_dst * (3.0 + 4.0 * (c->logN - 8));
+    launch_bconv_ntt_cols(c, lv.d_merged, 1, n_dst, n_src + n_dst, acc, acc_ps, conv, conv_ps, 2 * bc, s, ops);
+    const FinishScale fs{lv.d_Dinv, lv.d_qlinv, n_dst};
+    launch_rows_moddown_finish(c, lv, acc, conv, out, out_bs, addend, addend_bs, 2, 1, bc, s, &fs);
+}
+
+extern "C" int hmult_relin_rescale_merged(const ks_ctx* c, const uint64_t* cta, const uint64_t* ctb, uint32_t ell, const uint64_t* rlk,
+                                          uint64_t* out, uint32_t batch, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_pipeline_args(c, ell, 2, cta, ctb, out, ws);
+    if (rc != KS_OK) return rc;
+    if (!rlk || !aligned16(rlk)) return KS_EINVAL;
+    if (batch == 0) return KS_OK;
+    if (ws_bytes < ks_workspace_bytes(c, KS_OP_HMULT_RELIN_RESCALE, ell, batch, 0)) return KS_EWORKSPACE;
+    const Level& lv = c->levels[ell - 1];
+    if (!lv.d_merged) return KS_EINVAL;  // K + 1 sources exceed what one conversion takes
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint64_t N = c->N, ct_bs = 2ull * ell * N, td_bs = 3ull * ell * N, out_bs = 2ull * (ell - 1) * N;
+    for (uint32_t b0 = 0; b0 < batch; b0 += kChunk) {
+        const uint32_t bc = std::min(batch - b0, kChunk);
+        const KsWorkspace w = ks_ws_words(c, lv, bc);
+        uint64_t* coeff = static_cast<uint64_t*>(ws);
+        uint64_t* lifted = coeff + w.coeff;
+        uint64_t* acc = lifted + w.lifted;
+        uint64_t* conv = acc + w.acc;
+        uint64_t* td = conv + w.conv;  // [bc][3][ell][N]
+        launch_tensor_product(c, cta + (uint64_t)b0 * ct_bs, ctb + (uint64_t)b0 * ct_bs, td, ell, bc, s);
+        const uint64_t* d2 = td + 2ull * ell * N;
+        mod_up(c, lv, d2, td_bs, coeff, lifted, bc, false, s);
+        launch_rows_inner_product(c, lv, d2, td_bs, lifted, rlk, acc, bc, s);
+        mod_down_merged(c, lv, acc, conv, out + (uint64_t)b0 * out_bs, out_bs, td, td_bs, bc, s);
+    }
+    return finish("hmult_relin_rescale_merged");
+}
+
 extern "C" int hmult_relin_rescale(const ks_ctx* c, const uint64_t* cta, const uint64_t* ctb, uint32_t ell, const uint64_t* rlk,
                                    uint64_t* out, uint32_t batch, void* ws, size_t ws_bytes, void* stream) {
     int rc = check_pipeline_args(c, ell, 2, cta, ctb, out, ws);

@@ -161,6 +161,9 @@ extern "C" int ks_ctx_destroy(ks_ctx* c) {
         (void)hipFree(lv.d_moddown);
         (void)hipFree(lv.d_qlinv);
         (void)hipFree(lv.d_modup_scale);
+        (void)hipFree(lv.d_merged);
+        (void)hipFree(lv.d_merged_scale);
+        (void)hipFree(lv.d_Dinv);
     }
     for (auto& kv : c->bconv_cache) (void)hipFree(kv.second);
     delete c;
@@ -332,6 +335,43 @@ extern "C" int ks_ctx_create(ks_ctx** out, uint32_t logN, uint32_t L, uint32_t K
             CK(hipMalloc(&lv.d_moddown, sizeof(BConvPlan)));
             CK(hipMemcpy(lv.d_moddown, &down, sizeof(BConvPlan), hipMemcpyHostToDevice));
 
+            if (ell >= 2 && K + 1 <= (uint32_t)kMaxSrc) {
+                BConvPlan merged;
+                uint32_t m_ids[kMaxSrc];
+                uint16_t m_limb[kMaxSrc];
+                lv.merged_map.n = K + 1;
+                for (uint32_t k = 0; k <= K; ++k) {
+                    m_ids[k] = k < K ? L + k : ell - 1;
+                    m_limb[k] = (uint16_t)(k < K ? ell + k : ell - 1);
+                    lv.merged_map.off[k] = m_limb[k];
+                    lv.merged_map.mod[k] = (uint8_t)m_ids[k];
+                }
+                lv.last_map.n = 1;
+                lv.last_map.off[0] = (uint16_t)(ell - 1);
+                lv.last_map.mod[0] = (uint8_t)(ell - 1);
+                fill_bconv_plan(c, &merged, m_ids, m_limb, K + 1, dst_ids.data(), dst_limb.data(), ell - 1);
+                CK(hipMalloc(&lv.d_merged, sizeof(BConvPlan)));
+                CK(hipMemcpy(lv.d_merged, &merged, sizeof(BConvPlan), hipMemcpyHostToDevice));
+                std::vector<double> sc(K + 1), dinv(ell - 1);
+                for (uint32_t k = 0; k <= K; ++k) {
+                    const uint64_t sk = c->mod[m_ids[k]];
+                    sc[k] = (double)h_mulmod((uint64_t)merged.src_inv[k], h_invmod(N % sk, sk), sk);
+                }
+                const uint64_t qlast = c->mod[ell - 1];
+                uint64_t pl = 1;
+                for (uint32_t k = 0; k < K; ++k) pl = h_mulmod(pl, c->mod[L + k] % qlast, qlast);
+                lv.Pmod_last = (double)pl;
+                for (uint32_t i = 0; i + 1 < ell; ++i) {
+                    const uint64_t qi = c->mod[i];
+                    uint64_t D = qlast % qi;
+                    for (uint32_t k = 0; k < K; ++k) D = h_mulmod(D, c->mod[L + k] % qi, qi);
+                    dinv[i] = (double)h_invmod(D, qi);
+                }
+                CK(hipMalloc(&lv.d_merged_scale, sizeof(double) * (K + 1)));
+                CK(hipMemcpy(lv.d_merged_scale, sc.data(), sizeof(double) * (K + 1), hipMemcpyHostToDevice));
+                CK(hipMalloc(&lv.d_Dinv, sizeof(double) * (ell - 1)));
+                CK(hipMemcpy(lv.d_Dinv, dinv.data(), sizeof(double) * (ell - 1), hipMemcpyHostToDevice));
+            }
             if (ell >= 2) {
                 std::vector<double> ql(ell - 1);
                 for (uint32_t i = 0; i + 1 < ell; ++i) ql[i] = (double)h_invmod(c->mod[ell - 1] % c->mod[i], c->mod[i]);

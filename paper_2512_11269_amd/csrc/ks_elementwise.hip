@@ -129,6 +129,28 @@ void launch_tensor_product(const ks_ctx* c, const uint64_t* cta, const uint64_t*
     hipLaunchKernelGGL(tensor_product_kernel, dim3(c->N / 256, ell, batch), dim3(256), 0, s, c->d_mod, ell, c->N, cta, ctb, td);
 }
 
+// acc[b][comp][limb] = (acc + mul * addend[b][comp][limb]) mod q_limb, canonical: the one ciphertext limb that joins the
+// special limbs as a conversion source when ModDown and rescale are merged.
+__global__ __launch_bounds__(256) void add_scaled_limb_kernel(const Mod* __restrict__ mods, uint32_t limb, double mul, uint32_t N,
+                                                              uint64_t* __restrict__ acc, uint64_t acc_ps,
+                                                              const uint64_t* __restrict__ addend, uint64_t addend_bs,
+                                                              uint64_t addend_cs) {
+    const Mod m = mods[limb];
+    const uint32_t b = blockIdx.z >> 1, comp = blockIdx.z & 1;
+    const uint64_t n = blockIdx.x * 256 + threadIdx.x;
+    uint64_t* a = acc + (uint64_t)blockIdx.z * acc_ps + (uint64_t)limb * N + n;
+    const double d = u64_to_f64(addend[(uint64_t)b * addend_bs + comp * addend_cs + (uint64_t)limb * N + n]);
+    *a = f64_to_u64(canon(reduce_lazy(u64_to_f64(*a) + mulmod_lazy(d, mul, m), m), m));
+}
+
+void launch_add_scaled_limb(const ks_ctx* c, uint64_t* acc, uint64_t acc_ps, const uint64_t* addend, uint64_t addend_bs,
+                            uint64_t addend_comp_stride, uint32_t limb, double mul, uint32_t batch, hipStream_t s) {
+    if (batch == 0) return;
+    ProfScope ps("add_scaled_limb", (double)batch * 2 * 3 * c->N * 8.0, s);
+    hipLaunchKernelGGL(add_scaled_limb_kernel, dim3(c->N / 256, 1, batch * 2), dim3(256), 0, s, c->d_mod, limb, mul, c->N, acc, acc_ps,
+                       addend, addend_bs, addend_comp_stride);
+}
+
 // spread[p][i] = centred remainder of last[p] (mod q_{ell-1}) reduced modulo q_i
 __global__ __launch_bounds__(256) void rescale_spread_kernel(const Mod* __restrict__ mods, uint32_t ell, uint32_t N,
                                                              const uint64_t* __restrict__ last, uint64_t* __restrict__ spread) {

@@ -334,7 +334,8 @@ void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const uint64_t*
 // ------------------------------------------------------------------------------------------------
 template <int LOG_R, bool GATHER>
 __global__ __launch_bounds__(64) void rows_moddown_finish(TwTables tw, const Mod* __restrict__ mods,
-                                                          const double* __restrict__ Pinv, uint32_t ell, uint32_t E,
+                                                          const double* __restrict__ Pinv, const double* __restrict__ addend_mul,
+                                                          uint32_t ell, uint32_t E, uint32_t out_limbs,
                                                           const uint64_t* __restrict__ acc, const uint64_t* __restrict__ conv,
                                                           uint64_t* __restrict__ out, uint64_t out_bs,
                                                           const uint64_t* __restrict__ addend, uint64_t addend_bs,
@@ -344,11 +345,12 @@ __global__ __launch_bounds__(64) void rows_moddown_finish(TwTables tw, const Mod
     const uint32_t tid = threadIdx.x, rg = blockIdx.x, i = blockIdx.y, b = blockIdx.z >> 1, comp = blockIdx.z & 1;
     const Mod m = mods[i];
     const double pinv = Pinv[i];
+    const double admul = addend_mul ? addend_mul[i] : 0.0;  // uniform; 0 = the addend enters unscaled
     const uint32_t j0 = tid & 15, rr = tid >> 4, row = rg * 4 + rr;
     const uint32_t off = row * 256 + j0;
     const uint64_t* src = conv + (((uint64_t)b * 2 + comp) * ell + i) * N + off;
     const uint64_t* ap = acc + (((uint64_t)b * 2 + comp) * E + i) * N + off;
-    uint64_t* op = out + (uint64_t)b * out_bs + ((uint64_t)comp * ell + i) * N + off;
+    uint64_t* op = out + (uint64_t)b * out_bs + ((uint64_t)comp * out_limbs + i) * N + off;
     const bool add = addend != nullptr && comp < addend_comps;
     const uint64_t* adp = add ? addend + (uint64_t)b * addend_bs + ((uint64_t)comp * ell + i) * N : nullptr;
     // issue every load up front: the accumulator (and addend) slots do not depend on the transform
@@ -370,34 +372,32 @@ __global__ __launch_bounds__(64) void rows_moddown_finish(TwTables tw, const Mod
     row_fwd_core(w, t, j0, lds + rr * kRowPitch, m);
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
-        const double r = reduce_lazy(mulmod_lazy(a[k] - w[k], pinv, m) + ad[k], m);
+        const double r = reduce_lazy(mulmod_lazy(a[k] - w[k], pinv, m) + (admul != 0.0 ? mulmod_lazy(ad[k], admul, m) : ad[k]), m);
         op[16 * k] = f64_to_u64(canon(r, m));
     }
 }
 
 void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t* acc, const uint64_t* conv, uint64_t* out,
                                 uint64_t out_bs, const uint64_t* addend, uint64_t addend_bs, uint32_t addend_comps,
-                                uint32_t galois, uint32_t batch, hipStream_t s) {
+                                uint32_t galois, uint32_t batch, hipStream_t s, const FinishScale* fs) {
     if (batch == 0) return;
-    ProfScope ps("rows_moddown_finish", (double)batch * lv.ell * (6 + (addend ? addend_comps : 0)) * c->N * 8.0, s);
+    const double* mul = fs ? fs->mul : c->d_Pinv;
+    const double* admul = fs ? fs->addend_mul : nullptr;
+    const uint32_t out_limbs = fs ? fs->out_limbs : lv.ell;
+    if (out_limbs == 0) return;
+    ProfScope ps("rows_moddown_finish", (double)batch * out_limbs * (6 + (addend ? addend_comps : 0)) * c->N * 8.0, s);
     const dim3 block(64);
+#define KS_LAUNCH_FINISH(LOGR, GATHER, ROWGROUPS)                                                                              \
+    hipLaunchKernelGGL((rows_moddown_finish<LOGR, GATHER>), dim3(ROWGROUPS, out_limbs, batch * 2), block, 0, s, c->tw_fwd, c->d_mod, \
+                       mul, admul, lv.ell, lv.E, out_limbs, acc, conv, out, out_bs, addend, addend_bs, addend_comps, galois)
     if (c->logN == 16) {
-        const dim3 grid(64, lv.ell, batch * 2);
-        if (galois == 1)
-            hipLaunchKernelGGL((rows_moddown_finish<8, false>), grid, block, 0, s, c->tw_fwd, c->d_mod, c->d_Pinv, lv.ell, lv.E, acc,
-                               conv, out, out_bs, addend, addend_bs, addend_comps, galois);
-        else
-            hipLaunchKernelGGL((rows_moddown_finish<8, true>), grid, block, 0, s, c->tw_fwd, c->d_mod, c->d_Pinv, lv.ell, lv.E, acc,
-                               conv, out, out_bs, addend, addend_bs, addend_comps, galois);
+        if (galois == 1) KS_LAUNCH_FINISH(8, false, 64);
+        else KS_LAUNCH_FINISH(8, true, 64);
     } else {
-        const dim3 grid(4, lv.ell, batch * 2);
-        if (galois == 1)
-            hipLaunchKernelGGL((rows_moddown_finish<4, false>), grid, block, 0, s, c->tw_fwd, c->d_mod, c->d_Pinv, lv.ell, lv.E, acc,
-                               conv, out, out_bs, addend, addend_bs, addend_comps, galois);
-        else
-            hipLaunchKernelGGL((rows_moddown_finish<4, true>), grid, block, 0, s, c->tw_fwd, c->d_mod, c->d_Pinv, lv.ell, lv.E, acc,
-                               conv, out, out_bs, addend, addend_bs, addend_comps, galois);
+        if (galois == 1) KS_LAUNCH_FINISH(4, false, 4);
+        else KS_LAUNCH_FINISH(4, true, 4);
     }
+#undef KS_LAUNCH_FINISH
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -56,6 +56,13 @@ struct Level {
     uint32_t digit_lo[kMaxDigits], digit_hi[kMaxDigits];
     double* d_qlinv = nullptr;             // [ell-1] device: q_{ell-1}^-1 mod q_i (rescale)
     double* d_modup_scale = nullptr;       // [ell] device: N^-1 (D_j / q_i)^-1 mod q_i, j = digit of limb i
+    // ModDown merged with rescale: one conversion from {p_0..p_{K-1}, q_{ell-1}} (product D) to q_0..q_{ell-2}
+    BConvPlan* d_merged = nullptr;         // [1] device (ell >= 2)
+    LimbMap merged_map;                    // the K special limbs and limb ell-1 inside an [E][N] accumulator
+    LimbMap last_map;                      // limb ell-1 alone
+    double* d_merged_scale = nullptr;      // [K+1] device: N^-1 (D / s)^-1 mod s, s in merged_map order
+    double* d_Dinv = nullptr;              // [ell-1] device: D^-1 mod q_i
+    double Pmod_last = 0.0;                // P mod q_{ell-1}
     uint32_t max_targets = 0;              // largest target count of a ModUp digit
 };
 
@@ -132,9 +139,20 @@ void launch_bconv_ntt_cols(const ks_ctx* c, const BConvPlan* d_plans, uint32_t n
 void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, const uint64_t* lifted,
                                const uint64_t* evk, uint64_t* acc, uint32_t batch, hipStream_t s);
 // Fused row half of the forward transform of the converted limbs + (acc - conv) P^-1 (+ addend).
+// fs == nullptr: multiply by P^-1, addend unscaled, ell output limbs.  Otherwise (merged ModDown + rescale): multiply by
+// fs->mul[i], scale the addend by fs->addend_mul[i], and write only the first fs->out_limbs limbs per component.
+struct FinishScale {
+    const double* mul;
+    const double* addend_mul;
+    uint32_t out_limbs;
+};
 void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t* acc, const uint64_t* conv, uint64_t* out,
                                 uint64_t out_batch_stride, const uint64_t* addend, uint64_t addend_batch_stride,
-                                uint32_t addend_comps, uint32_t galois, uint32_t batch, hipStream_t s);
+                                uint32_t addend_comps, uint32_t galois, uint32_t batch, hipStream_t s,
+                                const FinishScale* fs = nullptr);
+// acc[b][comp][limb] += mul * addend[b][comp][limb] for one ciphertext limb of both components (canonical in, canonical out)
+void launch_add_scaled_limb(const ks_ctx* c, uint64_t* acc, uint64_t acc_ps, const uint64_t* addend, uint64_t addend_bs,
+                            uint64_t addend_comp_stride, uint32_t limb, double mul, uint32_t batch, hipStream_t s);
 
 // Fused rescale: last = coefficient-domain dropped limb as canonical doubles [polys][N]; spread = scratch
 // [polys][ell-1][N]; out[p][i] = (x[p][i] - NTT(centred last mod q_i)) * q_{ell-1}^-1.

@@ -69,3 +69,19 @@ def test_cfg5_hmult_full_size():
         want = st.ref.hmult_relin_rescale(host(cta[b])[None], host(ctb[b])[None], host(rlk), ell)
         assert_equal(out[b], want[0])
     assert _in_range(out[100].reshape(-1, ell - 1, st.N), st.q[:ell - 1])
+
+
+def test_cfg5_hmult_merged_full_size():
+    cfg = ks_inputs.CONFIGS[5]
+    st = Setup(cfg["logN"], cfg["L"], cfg["K"], cfg["dnum"])
+    ell, B, seed = cfg["L"], cfg["batch"], cfg["seed"]
+    cta = st.uniform(seed, 1, (B, 2), list(range(ell)))
+    ctb = st.uniform(seed, 2, (B, 2), list(range(ell)))
+    rlk = st.uniform(seed, 3, (cfg["dnum"], 2), list(range(ell + cfg["K"])))
+    out = torch.empty((B, 2, ell - 1, st.N), dtype=torch.int64, device="cuda")
+    K.hmult_relin_rescale_merged(st.ctx, cta, ctb, ell, rlk, out, workspace(st.ctx, K.KS_OP_HMULT_RELIN_RESCALE, ell, B))
+    torch.cuda.synchronize()
+    for b in (0, 16, 255):
+        want = st.ref.hmult_relin_rescale_merged(host(cta[b])[None], host(ctb[b])[None], host(rlk), ell)
+        assert_equal(out[b], want[0])
+    assert _in_range(out[77].reshape(-1, ell - 1, st.N), st.q[:ell - 1])

@@ -134,13 +134,13 @@ def test_rotate_by_identity_equals_keyswitch_plus_c0(small):
     assert torch.equal(out[0, 0, 0], (ks[0, 0] + ct[0, 0]) % q)
 
 
-def _run_hmult(st, seed, ell, batch):
+def _run_hmult(st, seed, ell, batch, merged=False):
     cta = st.uniform(seed, 1, (batch, 2), list(range(ell)))
     ctb = st.uniform(seed, 2, (batch, 2), list(range(ell)))
     rlk = st.uniform(seed, 3, (st.ctx.dnum, 2), list(range(st.L + st.K)))
     out = torch.empty((batch, 2, ell - 1, st.N), dtype=torch.int64, device="cuda")
     ws = workspace(st.ctx, K.KS_OP_HMULT_RELIN_RESCALE, ell, batch)
-    K.hmult_relin_rescale(st.ctx, cta, ctb, ell, rlk, out, ws)
+    (K.hmult_relin_rescale_merged if merged else K.hmult_relin_rescale)(st.ctx, cta, ctb, ell, rlk, out, ws)
     return cta, ctb, rlk, out
 
 
@@ -148,6 +148,20 @@ def _run_hmult(st, seed, ell, batch):
 def test_hmult_small(small, ell, batch):
     cta, ctb, rlk, out = _run_hmult(small, 1005, ell, batch)
     assert_equal(out, small.ref.hmult_relin_rescale(host(cta), host(ctb), host(rlk), ell))
+
+
+@pytest.mark.parametrize("ell,batch", [(4, 2), (2, 1), (3, 17)])
+def test_hmult_merged_small(small, ell, batch):
+    cta, ctb, rlk, out = _run_hmult(small, 1006, ell, batch, merged=True)
+    assert_equal(out, small.ref.hmult_relin_rescale_merged(host(cta), host(ctb), host(rlk), ell))
+
+
+def test_hmult_merged_llm_shape():
+    st = Setup(16, 35, 12, 3)            # configuration 5 shape: 13 sources in the merged conversion
+    cta, ctb, rlk, out = _run_hmult(st, 1006, 35, 2, merged=True)
+    assert_equal(out, st.ref.hmult_relin_rescale_merged(host(cta), host(ctb), host(rlk), 35))
+    cta, ctb, rlk, out = _run_hmult(st, 1007, 24, 1, merged=True)   # lower level: digits 12 / 12, short last source set
+    assert_equal(out, st.ref.hmult_relin_rescale_merged(host(cta), host(ctb), host(rlk), 24))
 
 
 def test_hmult_llm_shape():
