@@ -1,6 +1,5 @@
 // Slot-wise kernels (Kernel Code Generation, "Elementwise" kernel class): inner product with the
-// evaluation key, the final subtract-and-scale of ModDown, tensor product, rescale pieces and the
-// evaluation-domain automorphism (a gather).  These are bandwidth-bound: one thread per slot, contiguous
+// evaluation key through the evaluation-domain automorphism (a gather), tensor product, and a scaled add.  These are bandwidth-bound: one thread per slot, contiguous
 // 512-byte segments per wavefront, operands shared by both key components are read once ("load reuse").
 #include "ks_internal.hpp"
 #include "ks_tiles.hpp"
@@ -70,42 +69,6 @@ void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, u
                            d_ps, lifted, evk, acc, batch, galois);
 }
 
-// out = (acc - conv) * P^-1 (+ addend)
-template <bool GATHER>
-__global__ __launch_bounds__(256) void moddown_finish_kernel(const Mod* __restrict__ mods, const double* __restrict__ Pinv,
-                                                             uint32_t ell, uint32_t E, uint32_t logN,
-                                                             const uint64_t* __restrict__ acc, const uint64_t* __restrict__ conv,
-                                                             uint64_t* __restrict__ out, uint64_t out_bs,
-                                                             const uint64_t* __restrict__ addend, uint64_t addend_bs,
-                                                             uint32_t addend_comps, uint32_t galois) {
-    const uint32_t N = 1u << logN;
-    const uint32_t i = blockIdx.y, b = blockIdx.z >> 1, comp = blockIdx.z & 1;
-    const Mod m = mods[i];
-    const uint32_t n = blockIdx.x * 256 + threadIdx.x;
-    const double a = u64_to_f64(acc[(((uint64_t)b * 2 + comp) * E + i) * N + n]);
-    const double w = u64_to_f64(conv[(((uint64_t)b * 2 + comp) * ell + i) * N + n]);
-    double r = mulmod_lazy(a - w, Pinv[i], m);
-    if (addend != nullptr && comp < addend_comps) {
-        const uint32_t sn = GATHER ? galois_source_slot(n, galois, logN) : n;
-        r = reduce_lazy(r + u64_to_f64(addend[(uint64_t)b * addend_bs + ((uint64_t)comp * ell + i) * N + sn]), m);
-    }
-    out[(uint64_t)b * out_bs + ((uint64_t)comp * ell + i) * N + n] = f64_to_u64(canon(r, m));
-}
-
-void launch_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t* acc, const uint64_t* conv, uint64_t* out,
-                           uint64_t out_bs, const uint64_t* addend, uint64_t addend_bs, uint32_t addend_comps, uint32_t galois,
-                           uint32_t batch, hipStream_t s) {
-    if (batch == 0) return;
-    const dim3 grid(c->N / 256, lv.ell, batch * 2), block(256);
-    ProfScope ps("moddown_finish", (double)batch * lv.ell * (6 + (addend ? addend_comps : 0)) * c->N * 8.0, s);
-    if (galois == 1)
-        hipLaunchKernelGGL(moddown_finish_kernel<false>, grid, block, 0, s, c->d_mod, c->d_Pinv, lv.ell, lv.E, c->logN, acc, conv,
-                           out, out_bs, addend, addend_bs, addend_comps, galois);
-    else
-        hipLaunchKernelGGL(moddown_finish_kernel<true>, grid, block, 0, s, c->d_mod, c->d_Pinv, lv.ell, lv.E, c->logN, acc, conv,
-                           out, out_bs, addend, addend_bs, addend_comps, galois);
-}
-
 // (b1, a1) x (b2, a2) -> d0 = b1 b2, d1 = a1 b2 + a2 b1, d2 = a1 a2
 __global__ __launch_bounds__(256) void tensor_product_kernel(const Mod* __restrict__ mods, uint32_t ell, uint32_t N,
                                                              const uint64_t* __restrict__ cta, const uint64_t* __restrict__ ctb,
@@ -149,43 +112,6 @@ void launch_add_scaled_limb(const ks_ctx* c, uint64_t* acc, uint64_t acc_ps, con
     ProfScope ps("add_scaled_limb", (double)batch * 2 * 3 * c->N * 8.0, s);
     hipLaunchKernelGGL(add_scaled_limb_kernel, dim3(c->N / 256, 1, batch * 2), dim3(256), 0, s, c->d_mod, limb, mul, c->N, acc, acc_ps,
                        addend, addend_bs, addend_comp_stride);
-}
-
-// spread[p][i] = centred remainder of last[p] (mod q_{ell-1}) reduced modulo q_i
-__global__ __launch_bounds__(256) void rescale_spread_kernel(const Mod* __restrict__ mods, uint32_t ell, uint32_t N,
-                                                             const uint64_t* __restrict__ last, uint64_t* __restrict__ spread) {
-    const uint32_t i = blockIdx.y, p = blockIdx.z;
-    const Mod m = mods[i];
-    const double ql = mods[ell - 1].p;
-    const uint64_t n = blockIdx.x * 256 + threadIdx.x;
-    double r = u64_to_f64(last[(uint64_t)p * N + n]);
-    if (r > (ql - 1.0) * 0.5) r -= ql;
-    spread[((uint64_t)p * (ell - 1) + i) * N + n] = f64_to_u64(canon(reduce_lazy(r, m), m));
-}
-
-void launch_rescale_spread(const ks_ctx* c, const uint64_t* last, uint64_t* spread, uint32_t ell, uint32_t n_polys, hipStream_t s) {
-    if (n_polys == 0 || ell < 2) return;
-    ProfScope ps("rescale_spread", (double)n_polys * ell * c->N * 8.0, s);
-    hipLaunchKernelGGL(rescale_spread_kernel, dim3(c->N / 256, ell - 1, n_polys), dim3(256), 0, s, c->d_mod, ell, c->N, last, spread);
-}
-
-__global__ __launch_bounds__(256) void rescale_finish_kernel(const Mod* __restrict__ mods, const double* __restrict__ qlinv,
-                                                             uint32_t ell, uint32_t N, const uint64_t* __restrict__ x,
-                                                             const uint64_t* __restrict__ spread, uint64_t* __restrict__ out) {
-    const uint32_t i = blockIdx.y, p = blockIdx.z;
-    const Mod m = mods[i];
-    const uint64_t n = blockIdx.x * 256 + threadIdx.x;
-    const double a = u64_to_f64(x[((uint64_t)p * ell + i) * N + n]);
-    const double w = u64_to_f64(spread[((uint64_t)p * (ell - 1) + i) * N + n]);
-    out[((uint64_t)p * (ell - 1) + i) * N + n] = f64_to_u64(canon(mulmod_lazy(a - w, qlinv[i], m), m));
-}
-
-void launch_rescale_finish(const ks_ctx* c, const Level& lv, const uint64_t* x, const uint64_t* spread, uint64_t* out,
-                           uint32_t n_polys, hipStream_t s) {
-    if (n_polys == 0 || lv.ell < 2) return;
-    ProfScope ps("rescale_finish", (double)n_polys * (lv.ell - 1) * 3 * c->N * 8.0, s);
-    hipLaunchKernelGGL(rescale_finish_kernel, dim3(c->N / 256, lv.ell - 1, n_polys), dim3(256), 0, s, c->d_mod, lv.d_qlinv,
-                       lv.ell, c->N, x, spread, out);
 }
 
 }  // namespace ks

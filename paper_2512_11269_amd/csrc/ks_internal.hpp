@@ -169,23 +169,8 @@ void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, u
                           const uint64_t* lifted, const uint64_t* evk, uint64_t* acc, uint32_t batch,
                           uint32_t galois, hipStream_t s);
 
-// out[b][c][i] = (acc[b][c][i] - conv[b][c][i]) * P^-1 (+ addend) mod q_i
-//   addend: nullptr, or a [b][*][ell][N] tensor whose component `c` is added (addend_comps = how many
-//   components it has per batch item: 1 means only component 0 receives it); with galois != 1 the addend
-//   is read through the sigma_g slot permutation.
-void launch_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t* acc, const uint64_t* conv, uint64_t* out,
-                           uint64_t out_batch_stride, const uint64_t* addend, uint64_t addend_batch_stride,
-                           uint32_t addend_comps, uint32_t galois, uint32_t batch, hipStream_t s);
-
 // d0 = b1 b2, d1 = a1 b2 + a2 b1, d2 = a1 a2 ; td: [batch][3][ell][N]
 void launch_tensor_product(const ks_ctx* c, const uint64_t* cta, const uint64_t* ctb, uint64_t* td, uint32_t ell,
                            uint32_t batch, hipStream_t s);
-
-// rescale helpers: r = centred remainder of the (coefficient-domain) last limb, spread to every q_i, i < ell-1
-void launch_rescale_spread(const ks_ctx* c, const uint64_t* last_coeff /*[polys][N]*/, uint64_t* spread /*[polys][ell-1][N]*/,
-                           uint32_t ell, uint32_t n_polys, hipStream_t s);
-// out[p][i] = (x[p][i] - spread[p][i]) * q_{ell-1}^-1 mod q_i ; x has ell limbs per poly, out ell-1
-void launch_rescale_finish(const ks_ctx* c, const Level& lv, const uint64_t* x, const uint64_t* spread, uint64_t* out,
-                           uint32_t n_polys, hipStream_t s);
 
 }  // namespace ks
