@@ -41,6 +41,8 @@ def _load():
         lib.orc_keyswitch.argtypes = [ctypes.c_void_p, _u64p, ctypes.c_int, _u64p, _u64p, ctypes.c_int]
         lib.orc_rotate_hoisted.argtypes = [ctypes.c_void_p, _u64p, ctypes.c_int, _u32p,
                                            ctypes.POINTER(_u64p), ctypes.c_int, _u64p, ctypes.c_int]
+        lib.orc_rotate_mac_hoisted.argtypes = [ctypes.c_void_p, _u64p, ctypes.c_int, _u32p, ctypes.POINTER(_u64p),
+                                               ctypes.POINTER(_u64p), ctypes.c_int, _u64p, ctypes.c_int]
         lib.orc_hmult_relin_rescale.argtypes = [ctypes.c_void_p, _u64p, _u64p, ctypes.c_int, _u64p, _u64p, ctypes.c_int]
         lib.orc_hmult_relin_rescale_merged.argtypes = [ctypes.c_void_p, _u64p, _u64p, ctypes.c_int, _u64p, _u64p, ctypes.c_int]
         lib.orc_max_threads.restype = ctypes.c_int
@@ -125,6 +127,20 @@ class COracle:
         out = np.zeros((batch, len(g), 2, ell, self.N), dtype=np.uint64)
         ptrs = (_u64p * len(keys))(*[_p64(k) for k in keys])
         _load().orc_rotate_hoisted(self._h, _p64(ct), ell, _p32(g), ptrs, len(g), _p64(out), batch)
+        return out
+
+    def rotate_mac_hoisted(self, ct: np.ndarray, galois, rot_keys, pts, ell: int | None = None) -> np.ndarray:
+        """ct [batch][2][ell][N]; rot_keys: list of [dnum][2][L+K][N]; pts: list of [L+K][N] -> [batch][2][ell][N]."""
+        ell = self.L if ell is None else ell
+        ct = np.ascontiguousarray(ct, dtype=np.uint64)
+        keys = [np.ascontiguousarray(k, dtype=np.uint64) for k in rot_keys]
+        pls = [np.ascontiguousarray(w, dtype=np.uint64) for w in pts]
+        g = np.asarray(galois, dtype=np.uint32)
+        batch = ct.size // (2 * ell * self.N)
+        out = np.zeros((batch, 2, ell, self.N), dtype=np.uint64)
+        kp = (_u64p * len(keys))(*[_p64(k) for k in keys])
+        pp = (_u64p * len(pls))(*[_p64(w) for w in pls])
+        _load().orc_rotate_mac_hoisted(self._h, _p64(ct), ell, _p32(g), kp, pp, len(g), _p64(out), batch)
         return out
 
     def hmult_relin_rescale(self, cta: np.ndarray, ctb: np.ndarray, rlk: np.ndarray, ell: int | None = None) -> np.ndarray:

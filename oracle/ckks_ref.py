@@ -390,6 +390,47 @@ def rotate_hoisted(pr: Params, ct, galois: list[int], rot_keys, ell: int | None 
     return outs
 
 
+def rotate_mac_hoisted(pr: Params, ct, galois: list[int], rot_keys, pts, ell: int | None = None):
+    """Inner sum of a baby-step giant-step linear transform with the rotations kept in the extended
+    basis ("double hoisting", the form in which the DSL's BSGS matrix products consume hoisted
+    rotations): sum_r pt_r * rot_{g_r}(ct) with ONE division by P for the whole sum instead of one per
+    rotation.
+
+    For every Galois element g_r: the raised digits of c1 (one decompose-and-raise, shared) are
+    permuted by sigma_{g_r} and multiplied with that rotation's key, which gives both accumulators on
+    the extended basis; sigma_{g_r}(c0) joins component 0 lifted to that basis as P * sigma(c0)
+    (P * x is x * [P]_{q_i} on the ciphertext limbs and 0 on the special limbs).  Each rotation's pair
+    is multiplied slot-wise by the plaintext pt_r (evaluation domain, all L + K limbs, like a key) and
+    the products are summed; the sum is divided by P once:
+
+        u_c[m]  = sum_r pt_r[m] * (acc_{r,c}[m] + [c = 0][m < ell] [P]_{q_m} sigma_{g_r}(c0)[m])   mod m
+        out_c   = mod_down(u_c).
+
+    With one rotation and pt = 1 this is rotate_hoisted bit for bit."""
+    ell = pr.L if ell is None else ell
+    c0, c1 = ct
+    lifted = mod_up(pr, c1, ell)
+    ext_ids = list(range(ell)) + [pr.L + k for k in range(pr.K)]
+
+    def sigma_eval(limb, m, g):
+        mod, psi = pr.moduli[m], pr.psi[m]
+        return ntt(automorphism_coeff(intt(limb, mod, psi), g, mod), mod, psi)
+
+    u = [[[0] * pr.N for _ in ext_ids] for _ in range(2)]
+    for g, key, pt in zip(galois, rot_keys, pts):
+        rotated = [[sigma_eval(dj[pos], m, g) for pos, m in enumerate(ext_ids)] for dj in lifted]
+        acc = inner_product(pr, rotated, key, ell)
+        for pos, m in enumerate(ext_ids):
+            mod = pr.moduli[m]
+            t0 = acc[0][pos]
+            if pos < ell:
+                pm = pr.P % mod
+                t0 = [(a + pm * b) % mod for a, b in zip(t0, sigma_eval(c0[pos], m, g))]
+            u[0][pos] = [(x + w * a) % mod for x, w, a in zip(u[0][pos], pt[m], t0)]
+            u[1][pos] = [(x + w * a) % mod for x, w, a in zip(u[1][pos], pt[m], acc[1][pos])]
+    return mod_down(pr, u[0], ell), mod_down(pr, u[1], ell)
+
+
 def tensor_product(pr: Params, cta, ctb, ell: int):
     """(b1,a1) x (b2,a2) -> d0 = b1 b2, d1 = a1 b2 + a2 b1, d2 = a1 a2, slot-wise per limb."""
     (b1, a1), (b2, a2) = cta, ctb

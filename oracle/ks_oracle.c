@@ -339,6 +339,56 @@ void orc_rotate_hoisted(const orc_ctx *c, const u64 *ct, int ell, const uint32_t
 }
 
 /* Drop limb ell-1 of poly [ell][N] with rounding to nearest: out [ell-1][N] */
+/* Inner sum of a baby-step giant-step transform with the rotations kept on the extended basis (double hoisting):
+ * u_c[m] = sum_r pt_r[m] * (acc_{r,c}[m] + [c = 0][m < ell] [P]_{q_m} sigma_{g_r}(c0)[m]); out_c = mod_down(u_c).
+ * pts[r] holds all L + K limbs in evaluation domain, like a key component. */
+void orc_rotate_mac_hoisted(const orc_ctx *c, const u64 *ct, int ell, const uint32_t *galois,
+                            const u64 *const *rot_keys, const u64 *const *pts, int n_rot, u64 *out, int batch) {
+    u64 N = c->N;
+    int E = ell + c->K;
+    int ndig_max = (ell + c->alpha - 1) / c->alpha;
+    u64 *lifted = (u64 *)malloc(sizeof(u64) * ndig_max * E * N);
+    u64 *rotated = (u64 *)malloc(sizeof(u64) * ndig_max * E * N);
+    u64 *acc = (u64 *)malloc(sizeof(u64) * 2 * E * N);
+    u64 *u = (u64 *)malloc(sizeof(u64) * 2 * E * N);
+    u64 *s0 = (u64 *)malloc(sizeof(u64) * ell * N);
+    for (int b = 0; b < batch; b++) {
+        const u64 *c0 = ct + (u64)b * 2 * ell * N, *c1 = c0 + (u64)ell * N;
+        int ndig = mod_up(c, c1, ell, lifted);
+        memset(u, 0, sizeof(u64) * 2 * E * N);
+        for (int r = 0; r < n_rot; r++) {
+            u64 g = galois[r];
+#pragma omp parallel for schedule(dynamic)
+            for (int idx = 0; idx < ndig * E; idx++) {
+                int pos = idx % E;
+                sigma_eval(c, ext_id(c, ell, pos), lifted + (u64)idx * N, rotated + (u64)idx * N, g);
+            }
+            inner_product(c, rotated, ndig, ell, rot_keys[r], acc);
+#pragma omp parallel for schedule(dynamic)
+            for (int pos = 0; pos < E; pos++) {
+                int m = ext_id(c, ell, pos);
+                u64 mod = c->mod[m];
+                const u64 *pt = pts[r] + (u64)m * N;
+                u64 *a0 = acc + (u64)pos * N, *a1 = acc + (u64)(E + pos) * N;
+                u64 *u0 = u + (u64)pos * N, *u1 = u + (u64)(E + pos) * N;
+                if (pos < ell) {
+                    u64 Pmod = 1;
+                    for (int k = 0; k < c->K; k++) Pmod = mulmod(Pmod, c->mod[c->L + k] % mod, mod);
+                    sigma_eval(c, m, c0 + (u64)pos * N, s0 + (u64)pos * N, g);
+                    for (u64 n = 0; n < N; n++) a0[n] = addmod(a0[n], mulmod(Pmod, s0[(u64)pos * N + n], mod), mod);
+                }
+                for (u64 n = 0; n < N; n++) {
+                    u0[n] = addmod(u0[n], mulmod(pt[n], a0[n], mod), mod);
+                    u1[n] = addmod(u1[n], mulmod(pt[n], a1[n], mod), mod);
+                }
+            }
+        }
+        u64 *o = out + (u64)b * 2 * ell * N;
+        for (int comp = 0; comp < 2; comp++) mod_down(c, u + (u64)comp * E * N, ell, o + (u64)comp * ell * N);
+    }
+    free(lifted); free(rotated); free(acc); free(u); free(s0);
+}
+
 static void rescale_poly(const orc_ctx *c, const u64 *poly, int ell, u64 *out) {
     u64 N = c->N;
     u64 ql = c->mod[ell - 1], half = (ql - 1) / 2;

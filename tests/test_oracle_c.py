@@ -94,6 +94,20 @@ def test_c_rotate_hoisted_matches_python(c_oracle_lib, logN, L, K, dnum):
             assert got[b, r, 0].tolist() == o0 and got[b, r, 1].tolist() == o1
 
 
+@pytest.mark.parametrize("logN,L,K,dnum,ell", [(5, 4, 2, 2, 4), (6, 24, 8, 3, 24), (6, 6, 2, 3, 5)])
+def test_c_rotate_mac_matches_python(c_oracle_lib, logN, L, K, dnum, ell):
+    pr, co = _setup(c_oracle_lib, logN, L, K, dnum)
+    rng = random.Random(7)
+    galois = ks_inputs.galois_elements(logN, 3)
+    keys = [_rand_key(rng, pr) for _ in galois]
+    pts = [_rand(rng, pr, range(L + K)) for _ in galois]
+    cts = [(_rand(rng, pr, range(ell)), _rand(rng, pr, range(ell))) for _ in range(2)]
+    got = co.rotate_mac_hoisted(_np([[c0, c1] for c0, c1 in cts]), galois, [_np(k) for k in keys], [_np(w) for w in pts], ell)
+    for b, ct in enumerate(cts):
+        o0, o1 = R.rotate_mac_hoisted(pr, ct, galois, keys, pts, ell)
+        assert got[b, 0].tolist() == o0 and got[b, 1].tolist() == o1
+
+
 @pytest.mark.parametrize("logN,L,K,dnum", [(5, 4, 2, 2), (7, 35, 12, 3)])
 def test_c_hmult_matches_python(c_oracle_lib, logN, L, K, dnum):
     pr, co = _setup(c_oracle_lib, logN, L, K, dnum)

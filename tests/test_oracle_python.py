@@ -294,6 +294,50 @@ def test_rotate_hoisted_decrypts_to_rotated_phase(g):
 
 # ------------------------------------------------------------------ multiply, relinearise, rescale
 
+def test_rotate_mac_with_unit_plaintext_is_rotate_hoisted():
+    """Double-hoisted form, special case fixed by the single-hoisted one: one rotation, pt = 1."""
+    pr = _small_params(5, 4, 2, 2)
+    rng = random.Random(31)
+    ids, all_ids = list(range(pr.L)), list(range(pr.L + pr.K))
+    ct = (_uniform_poly(rng, pr, ids), _uniform_poly(rng, pr, ids))
+    key = [[_uniform_poly(rng, pr, all_ids) for _ in range(2)] for _ in range(len(pr.digits(pr.L)))]
+    one = [[1] * pr.N for _ in all_ids]
+    for g in (5, 25):
+        assert R.rotate_mac_hoisted(pr, ct, [g], [key], [one]) == R.rotate_hoisted(pr, ct, [g], [key])[0]
+    zero = [[0] * pr.N for _ in all_ids]
+    z0, z1 = R.rotate_mac_hoisted(pr, ct, [5], [key], [zero])
+    assert all(v == 0 for limb in z0 + z1 for v in limb)
+
+
+@pytest.mark.parametrize("ell", [4, 3])
+def test_rotate_mac_decrypts_to_sum_of_plaintext_times_rotations(ell):
+    """phase(out) = sum_r pt_r * sigma_{g_r}(phase(ct)) up to the key-switch noise of each rotation times its
+    plaintext's 1-norm, plus one ModDown rounding."""
+    pr = _small_params(5, 4, 2, 2)
+    rng = random.Random(32)
+    ids, all_ids = list(range(ell)), list(range(pr.L + pr.K))
+    s = ks_inputs.ternary_secret(3, pr.N)
+    s_eval = R.to_eval(pr, s, all_ids)
+    galois = [5, 25, 125 % (2 * pr.N)]
+    keys = [_keys(pr, 50 + r, R.automorphism_signed(s, g), s) for r, g in enumerate(galois)]
+    pts_signed = [[rng.choice([-2, -1, 0, 0, 0, 1, 3]) for _ in range(pr.N)] for _ in galois]
+    pts = [R.to_eval(pr, w, all_ids) for w in pts_signed]
+    msg = [rng.randrange(-10**12, 10**12) for _ in range(pr.N)]   # every term of the sum dwarfs the noise bound
+    a = _uniform_poly(rng, pr, ids)
+    mu = R.to_eval(pr, msg, ids)
+    b = [[(mm - x * sv) % pr.q[i] for mm, x, sv in zip(mu[i], a[i], s_eval[i])] for i in ids]
+    o0, o1 = R.rotate_mac_hoisted(pr, (b, a), galois, keys, pts, ell)
+    got = R.phase(pr, o0, o1, s_eval[:ell], ell)
+    want = [0] * pr.N
+    for g, w in zip(galois, pts_signed):
+        term = R.poly_mul_signed(w, R.automorphism_signed(msg, g))
+        want = [x + y for x, y in zip(want, term)]
+    l1 = sum(sum(abs(x) for x in w) for w in pts_signed)
+    # before the division, phase(u) = P sum_r pt_r sigma_r(phase) + sum_r pt_r sum_j sigma_r(d~_j) e_{r,j} with d~_j < alpha_j D_j < alpha_j P
+    bound = l1 * pr.N * 19 * pr.L + pr.K * (pr.N + 1)
+    assert max(abs(x - y) for x, y in zip(got, want)) <= bound
+
+
 def test_rescale_is_rounded_division():
     pr = _small_params(5, 4, 2, 2)
     rng = random.Random(11)
