@@ -267,6 +267,32 @@ def bench_rotate(args, torch, K, ks_inputs):
             "roofline": _dominant_roofline(kernels), "kernels": kernels}
 
 
+def bench_rotate_mac(args, torch, K, ks_inputs):
+    """Configuration 3's shape through the double-hoisted entry point: per ciphertext the 16 rotations are multiplied by
+    plaintext diagonals and summed on the extended basis, with one division by P for the sum."""
+    cfg = ks_inputs.CONFIGS[3]
+    q, p = ks_inputs.moduli(cfg)
+    logN, L, B, R, dnum = cfg["logN"], cfg["L"], cfg["batch"], cfg["n_rot"], cfg["dnum"]
+    N = 1 << logN
+    ctx = K.Context(logN, q, p, dnum)
+    ct = ks_inputs.uniform_residues(cfg["seed"], 1, (B, 2), q, N, device="cuda")
+    keys = [ks_inputs.uniform_residues(cfg["seed"], 10 + r, (dnum, 2), q + p, N, device="cuda") for r in range(R)]
+    pts = [ks_inputs.uniform_residues(cfg["seed"], 100 + r, (), q + p, N, device="cuda") for r in range(R)]
+    gal = ks_inputs.galois_elements(logN, R)
+    out = torch.empty((B, 2, L, N), dtype=torch.int64, device="cuda")
+    ws = torch.empty(K.ks_workspace_bytes(ctx, K.KS_OP_ROTATE_HOISTED, L, B, R) // 8, dtype=torch.int64, device="cuda")
+    fn = lambda: K.ks_rotate_mac_hoisted(ctx, ct, L, gal, keys, pts, out, ws)
+    reps = max(2, args.steps // 30)
+    ms = _time_calls(torch, fn, reps)
+    kernels = _kernel_breakdown(K, torch, fn, B * R)
+    return {"metric": "rotations_per_sec", "value": round(B * R / (ms * 1e-3), 1), "unit": "rotation/s", "n_gpus": 1, "steps": reps,
+            "warmup": 1, "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "f64", "data": "synthetic",
+            "config": {"workload": "double-hoisted rotate-multiply-accumulate N=2^16 L=24 K=8 dnum=3, 64 ciphertexts x 16 Galois "
+                                   "elements per call, one ModDown per ciphertext"},
+            "roofline": _dominant_roofline(kernels), "kernels": kernels}
+
+
 def bench_hmult(args, torch, K, ks_inputs, merged=False):
     """Configuration 5: 256 ciphertext pairs per call: tensor product, relinearisation, rescale (merged: the division
     by P and the rescale done as one division by P q_last)."""
@@ -351,7 +377,7 @@ def main():
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--sets", type=int, default=6, help="disjoint buffer sets rotated through (cold-cache figure)")
-    ap.add_argument("--workload", default="keyswitch", choices=["keyswitch", "ntt", "rotate", "hmult", "hmult_merged", "copy"])
+    ap.add_argument("--workload", default="keyswitch", choices=["keyswitch", "ntt", "rotate", "rotate_mac", "hmult", "hmult_merged", "copy"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -372,6 +398,8 @@ def main():
         result = bench_ntt(args, torch, K, ks_inputs)
     elif args.workload == "rotate":
         result = bench_rotate(args, torch, K, ks_inputs)
+    elif args.workload == "rotate_mac":
+        result = bench_rotate_mac(args, torch, K, ks_inputs)
     elif args.workload in ("hmult", "hmult_merged"):
         result = bench_hmult(args, torch, K, ks_inputs, merged=args.workload == "hmult_merged")
     else:

@@ -115,6 +115,22 @@ int ks_rotate_hoisted(const ks_ctx* ctx, const uint64_t* ct, uint32_t ell, const
                       const uint64_t* const* rot_keys, uint32_t n_rot, uint64_t* out, uint32_t batch,
                       void* ws, size_t ws_bytes, void* stream);
 
+/* Inner sum of a baby-step giant-step linear transform with the rotations kept on the extended basis ("double
+ * hoisting"; DSL, matrix multiplication example: the form in which BSGS products consume hoisted rotations):
+ *     out = sum_r pt_r * rot_{g_r}(ct),   one decompose-and-raise for all rotations and ONE division by P for the sum.
+ * Per rotation the permuted raised digits of c1 are multiplied with that rotation's key (both accumulators, all
+ * ell + K limbs), P sigma_{g_r}(c0) joins component 0, the pair is multiplied slot-wise by the plaintext pt_r and
+ * added to the running sum; the sum is divided by P like a key-switch result.  With one rotation and pt = 1 the
+ * result equals ks_rotate_hoisted's bit for bit.
+ *   ct       : device [batch][2][ell][N], evaluation domain.
+ *   galois   : host [n_rot], odd, 0 < g < 2N.       rot_keys : host [n_rot] device pointers, laid out like evk.
+ *   pts      : host [n_rot] device pointers, each [L+K][N]: the plaintext reduced modulo every q_i and p_k,
+ *              evaluation domain (only limbs i < ell and the special ones are read).
+ *   out      : device [batch][2][ell][N].           Workspace: KS_OP_ROTATE_HOISTED.  Errors as ks_rotate_hoisted. */
+int ks_rotate_mac_hoisted(const ks_ctx* ctx, const uint64_t* ct, uint32_t ell, const uint32_t* galois,
+                          const uint64_t* const* rot_keys, const uint64_t* const* pts, uint32_t n_rot, uint64_t* out,
+                          uint32_t batch, void* ws, size_t ws_bytes, void* stream);
+
 /* Homomorphic multiplication with relinearisation and rescale: tensor product
  * (d0, d1, d2) = (b1 b2, a1 b2 + a2 b1, a1 a2), key-switch d2 with rlk, add to (d0, d1), then drop limb
  * q_{ell-1} from both components with rounding to nearest (subtract the centred remainder, divide).

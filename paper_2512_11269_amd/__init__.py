@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     ks_profile_enable,
     ks_profile_report,
     ks_rotate_hoisted,
+    ks_rotate_mac_hoisted,
     ks_workspace_bytes,
     library_path,
     load_library,

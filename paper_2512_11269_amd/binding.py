@@ -55,6 +55,8 @@ def load_library():
     lib.ks_keyswitch.argtypes = [_vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
     lib.ks_rotate_hoisted.argtypes = [_vp, _vp, ctypes.c_uint32, _u32p, ctypes.POINTER(_vp), ctypes.c_uint32, _vp,
                                       ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
+    lib.ks_rotate_mac_hoisted.argtypes = [_vp, _vp, ctypes.c_uint32, _u32p, ctypes.POINTER(_vp), ctypes.POINTER(_vp),
+                                          ctypes.c_uint32, _vp, ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
     lib.hmult_relin_rescale.argtypes = [_vp, _vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
     lib.hmult_relin_rescale_merged.argtypes = [_vp, _vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
     lib.ks_profile_enable.argtypes = [ctypes.c_int]
@@ -178,3 +180,11 @@ def hmult_relin_rescale_merged(ctx: Context, cta: torch.Tensor, ctb: torch.Tenso
     batch = cta.numel() // (2 * ell * ctx.N)
     _check(load_library().hmult_relin_rescale_merged(ctx.handle, _dev_ptr(cta), _dev_ptr(ctb), ell, _dev_ptr(rlk), _dev_ptr(out),
                                                      batch, _dev_ptr(ws), ws.numel() * 8, _stream()), "hmult_relin_rescale_merged")
+
+
+def ks_rotate_mac_hoisted(ctx: Context, ct: torch.Tensor, ell: int, galois, rot_keys, pts, out: torch.Tensor, ws: torch.Tensor) -> None:
+    batch = ct.numel() // (2 * ell * ctx.N)
+    kp = (_vp * len(rot_keys))(*[_dev_ptr(k) for k in rot_keys])
+    pp = (_vp * len(pts))(*[_dev_ptr(w) for w in pts])
+    _check(load_library().ks_rotate_mac_hoisted(ctx.handle, _dev_ptr(ct), ell, _u32_array(galois), kp, pp, len(rot_keys),
+                                                _dev_ptr(out), batch, _dev_ptr(ws), ws.numel() * 8, _stream()), "ks_rotate_mac_hoisted")

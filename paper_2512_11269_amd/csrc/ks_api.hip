@@ -243,6 +243,45 @@ extern "C" int ks_rotate_hoisted(const ks_ctx* c, const uint64_t* ct, uint32_t e
     return finish("ks_rotate_hoisted");
 }
 
+extern "C" int ks_rotate_mac_hoisted(const ks_ctx* c, const uint64_t* ct, uint32_t ell, const uint32_t* galois,
+                                     const uint64_t* const* rot_keys, const uint64_t* const* pts, uint32_t n_rot, uint64_t* out,
+                                     uint32_t batch, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_pipeline_args(c, ell, 1, ct, ct, out, ws);
+    if (rc != KS_OK) return rc;
+    if (!galois || !rot_keys || !pts || n_rot == 0) return KS_EINVAL;
+    for (uint32_t r = 0; r < n_rot; ++r) {
+        if ((galois[r] & 1u) == 0 || galois[r] >= 2u * c->N) return KS_EINVAL;
+        if (!rot_keys[r] || !aligned16(rot_keys[r]) || !pts[r] || !aligned16(pts[r])) return KS_EINVAL;
+    }
+    if (batch == 0) return KS_OK;
+    if (ws_bytes < ks_workspace_bytes(c, KS_OP_ROTATE_HOISTED, ell, batch, n_rot)) return KS_EWORKSPACE;
+    const Level& lv = c->levels[ell - 1];
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint64_t N = c->N, ct_bs = 2ull * ell * N;
+    for (uint32_t b0 = 0; b0 < batch; b0 += kChunk) {
+        const uint32_t bc = std::min(batch - b0, kChunk);
+        const KsWorkspace w = ks_ws_words(c, lv, bc);
+        uint64_t* coeff = static_cast<uint64_t*>(ws);
+        uint64_t* lifted = coeff + w.coeff;
+        uint64_t* acc = lifted + w.lifted;
+        uint64_t* conv = acc + w.acc;
+        const uint64_t* c0 = ct + (uint64_t)b0 * ct_bs;
+        mod_up(c, lv, c0 + (uint64_t)ell * N, ct_bs, coeff, lifted, bc, true, s);   // finished once, shared by every rotation
+        for (uint32_t r0 = 0; r0 < n_rot; r0 += kMacRotations) {
+            MacRotations rot;
+            rot.n = std::min<uint32_t>(n_rot - r0, kMacRotations);
+            for (uint32_t r = 0; r < rot.n; ++r) {
+                rot.galois[r] = galois[r0 + r];
+                rot.key[r] = rot_keys[r0 + r];
+                rot.pt[r] = pts[r0 + r];
+            }
+            launch_rotate_mac(c, lv, c0, ct_bs, lifted, rot, acc, bc, r0 != 0, s);
+        }
+        mod_down(c, lv, acc, conv, out + (uint64_t)b0 * ct_bs, ct_bs, nullptr, 0, 0, 1, bc, false, s);
+    }
+    return finish("ks_rotate_mac_hoisted");
+}
+
 // Division by P q_{ell-1} of acc + P addend in one conversion (ModDown merged with the rescale that would follow):
 // limb ell-1 joins the special limbs as a source, the targets are q_0..q_{ell-2}.  The fused inner product has already
 // run the row half of the inverse transform on the special limbs.

@@ -151,6 +151,7 @@ extern "C" int ks_ctx_destroy(ks_ctx* c) {
     (void)hipFree(c->d_mod);
     (void)hipFree(c->d_ninv);
     (void)hipFree(c->d_Pinv);
+    (void)hipFree(c->d_Pmod);
     (void)hipFree(c->d_moddown_scale);
     (void)hipFree(c->d_tw_fwd);
     (void)hipFree(c->d_tw_inv);
@@ -207,7 +208,7 @@ extern "C" int ks_ctx_create(ks_ctx** out, uint32_t logN, uint32_t L, uint32_t K
         CK(hipSetDevice(device));
         // per-modulus constants
         std::vector<Mod> hm(M);
-        std::vector<double> hn(M), hP(L);
+        std::vector<double> hn(M), hP(L), hPm(L);
         for (uint32_t m = 0; m < M; ++m) {
             hm[m] = Mod{(double)c->mod[m], 1.0 / (double)c->mod[m]};
             hn[m] = (double)h_invmod(N % c->mod[m], c->mod[m]);
@@ -216,6 +217,7 @@ extern "C" int ks_ctx_create(ks_ctx** out, uint32_t logN, uint32_t L, uint32_t K
             uint64_t P = 1;
             for (uint32_t k = 0; k < K; ++k) P = h_mulmod(P, c->mod[L + k] % c->mod[i], c->mod[i]);
             hP[i] = (double)h_invmod(P, c->mod[i]);
+            hPm[i] = (double)P;
         }
         CK(hipMalloc(&c->d_mod, sizeof(Mod) * M));
         CK(hipMalloc(&c->d_ninv, sizeof(double) * M));
@@ -223,6 +225,8 @@ extern "C" int ks_ctx_create(ks_ctx** out, uint32_t logN, uint32_t L, uint32_t K
         CK(hipMemcpy(c->d_mod, hm.data(), sizeof(Mod) * M, hipMemcpyHostToDevice));
         CK(hipMemcpy(c->d_ninv, hn.data(), sizeof(double) * M, hipMemcpyHostToDevice));
         CK(hipMemcpy(c->d_Pinv, hP.data(), sizeof(double) * L, hipMemcpyHostToDevice));
+        CK(hipMalloc(&c->d_Pmod, sizeof(double) * L));
+        CK(hipMemcpy(c->d_Pmod, hPm.data(), sizeof(double) * L, hipMemcpyHostToDevice));
         if (K > 0) {
             std::vector<double> sc(K);
             for (uint32_t k = 0; k < K; ++k) {

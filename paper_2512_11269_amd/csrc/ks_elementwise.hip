@@ -69,6 +69,96 @@ void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, u
                            d_ps, lifted, evk, acc, batch, galois);
 }
 
+// Rotate-multiply-accumulate on the extended basis (inner sum of a baby-step giant-step transform with the division by P
+// deferred to the whole sum).  One thread owns one slot of one limb position for a group of ciphertexts and walks the
+// rotations: key slots and the plaintext slot of a rotation are read once per group, the raised digits and c0 come
+// through the sigma_g gather, and the two running sums stay in registers until every rotation of the launch is in.
+__global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__ mods, const double* __restrict__ Pmod, DigitRanges dg,
+                                                         uint32_t ell, uint32_t E, uint32_t L, uint32_t M, uint32_t logN,
+                                                         const uint64_t* __restrict__ ct, uint64_t ct_bs,
+                                                         const uint64_t* __restrict__ lifted, MacRotations rot,
+                                                         uint64_t* __restrict__ u, uint32_t batch, int accumulate) {
+    const uint32_t N = 1u << logN;
+    const uint32_t pos = blockIdx.y;
+    const uint32_t mid = pos < ell ? pos : L + (pos - ell);
+    const Mod m = mods[mid];
+    const double pm = pos < ell ? Pmod[pos] : 0.0;
+    const uint32_t n = blockIdx.x * 256 + threadIdx.x;
+    const uint32_t b_lo = blockIdx.z * kBatchGroup;
+    const uint32_t nb = min((uint32_t)kBatchGroup, batch - b_lo);
+    double u0[kBatchGroup], u1[kBatchGroup];
+#pragma unroll
+    for (int bi = 0; bi < kBatchGroup; ++bi) {
+        u0[bi] = u1[bi] = 0.0;
+        if (accumulate && bi < (int)nb) {
+            u0[bi] = u64_to_f64(u[(((uint64_t)(b_lo + bi) * 2 + 0) * E + pos) * N + n]);
+            u1[bi] = u64_to_f64(u[(((uint64_t)(b_lo + bi) * 2 + 1) * E + pos) * N + n]);
+        }
+    }
+#pragma unroll 1
+    for (uint32_t r = 0; r < rot.n; ++r) {
+        const uint32_t sn = galois_source_slot(n, rot.galois[r], logN);
+        const uint64_t* key = rot.key[r];
+        double k0[kMaxDigits], k1[kMaxDigits];
+#pragma unroll
+        for (int j = 0; j < kMaxDigits; ++j) {
+            k0[j] = k1[j] = 0.0;
+            if (j < (int)dg.ndig) {
+                k0[j] = u64_to_f64(key[((uint64_t)(j * 2 + 0) * M + mid) * N + n]);
+                k1[j] = u64_to_f64(key[((uint64_t)(j * 2 + 1) * M + mid) * N + n]);
+            }
+        }
+        const double w = u64_to_f64(rot.pt[r][(uint64_t)mid * N + n]);
+#pragma unroll
+        for (int bi = 0; bi < kBatchGroup; ++bi) {
+            if (bi < (int)nb) {
+                const uint64_t* cb = ct + (uint64_t)(b_lo + bi) * ct_bs;
+                double t0 = 0.0, t1 = 0.0;
+#pragma unroll
+                for (int j = 0; j < kMaxDigits; ++j) {
+                    if (j < (int)dg.ndig) {
+                        const bool own = pos >= dg.lo[j] && pos < dg.hi[j];
+                        const uint64_t* src = own ? cb + ((uint64_t)ell + pos) * N
+                                                  : lifted + (((uint64_t)(b_lo + bi) * dg.ndig + j) * E + pos) * N;
+                        const double x = u64_to_f64(src[sn]);
+                        t0 += mulmod_lazy(x, k0[j], m);
+                        t1 += mulmod_lazy(x, k1[j], m);
+                    }
+                }
+                if (pos < ell) t0 += mulmod_lazy(u64_to_f64(cb[(uint64_t)pos * N + sn]), pm, m);
+                // |t| <= (digits + 1) * 0.51 p, far inside the range of a lazy product; the sums grow by 0.51 p a rotation
+                u0[bi] += mulmod_lazy(t0, w, m);
+                u1[bi] += mulmod_lazy(t1, w, m);
+            }
+        }
+    }
+#pragma unroll
+    for (int bi = 0; bi < kBatchGroup; ++bi) {
+        if (bi < (int)nb) {
+            u[(((uint64_t)(b_lo + bi) * 2 + 0) * E + pos) * N + n] = f64_to_u64(canon(reduce_lazy(u0[bi], m), m));
+            u[(((uint64_t)(b_lo + bi) * 2 + 1) * E + pos) * N + n] = f64_to_u64(canon(reduce_lazy(u1[bi], m), m));
+        }
+    }
+}
+
+void launch_rotate_mac(const ks_ctx* c, const Level& lv, const uint64_t* ct, uint64_t ct_bs, const uint64_t* lifted,
+                       const MacRotations& rot, uint64_t* u, uint32_t batch, bool accumulate, hipStream_t s) {
+    if (batch == 0 || rot.n == 0) return;
+    DigitRanges dg;
+    dg.ndig = lv.ndig;
+    for (uint32_t j = 0; j < kMaxDigits; ++j) {
+        dg.lo[j] = j < lv.ndig ? lv.digit_lo[j] : 0;
+        dg.hi[j] = j < lv.ndig ? lv.digit_hi[j] : 0;
+    }
+    const uint32_t groups = (batch + kBatchGroup - 1) / kBatchGroup;
+    const dim3 grid(c->N / 256, lv.E, groups), block(256);
+    // per rotation: every raised digit limb and c0 per ciphertext, key and plaintext once per group; both sums written once
+    const double reads = (double)rot.n * ((double)batch * (lv.ndig * lv.E + lv.ell) + (double)groups * (2.0 * lv.ndig + 1.0) * lv.E);
+    ProfScope ps("rotate_mac", (reads + (double)batch * 2 * lv.E * (accumulate ? 2 : 1)) * c->N * 8.0, s);
+    hipLaunchKernelGGL(rotate_mac_kernel, grid, block, 0, s, c->d_mod, c->d_Pmod, dg, lv.ell, lv.E, c->L, c->M, c->logN, ct, ct_bs, lifted,
+                       rot, u, batch, accumulate ? 1 : 0);
+}
+
 // (b1, a1) x (b2, a2) -> d0 = b1 b2, d1 = a1 b2 + a2 b1, d2 = a1 a2
 __global__ __launch_bounds__(256) void tensor_product_kernel(const Mod* __restrict__ mods, uint32_t ell, uint32_t N,
                                                              const uint64_t* __restrict__ cta, const uint64_t* __restrict__ ctb,

@@ -75,6 +75,7 @@ struct ks_ctx {
     ks::Mod* d_mod = nullptr;             // [M]
     double* d_ninv = nullptr;             // [M]  N^-1 mod m
     double* d_Pinv = nullptr;             // [L]  P^-1 mod q_i
+    double* d_Pmod = nullptr;             // [L]  P mod q_i
     double* d_moddown_scale = nullptr;    // [K]  N^-1 (P / p_k)^-1 mod p_k
     double* d_tw_fwd = nullptr;           // [M][N] psi^brv(k)
     double* d_tw_inv = nullptr;           // [M][N] psi^-brv(k)
@@ -168,6 +169,19 @@ void launch_bconv(const ks_ctx* c, const BConvPlan* d_plans, uint32_t limbs_move
 void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_poly_stride,
                           const uint64_t* lifted, const uint64_t* evk, uint64_t* acc, uint32_t batch,
                           uint32_t galois, hipStream_t s);
+
+// Rotations handled by one launch of the rotate-multiply-accumulate kernel (more are chained, accumulating).
+constexpr int kMacRotations = 16;
+struct MacRotations {
+    uint32_t n;
+    uint32_t galois[kMacRotations];
+    const uint64_t* key[kMacRotations];  // [dnum][2][L+K][N]
+    const uint64_t* pt[kMacRotations];   // [L+K][N]
+};
+// u[b][c][pos] (+)= sum_r pt_r[pos] * (sum_j sigma_r(src_j)[pos] key_r[j][c][pos] + [c = 0][pos < ell] P sigma_r(c0)[pos]);
+// ct: [b][2][ell][N] (c0, c1), lifted: finished raised digits of c1.  accumulate: add to what u already holds.
+void launch_rotate_mac(const ks_ctx* c, const Level& lv, const uint64_t* ct, uint64_t ct_bs, const uint64_t* lifted,
+                       const MacRotations& rot, uint64_t* u, uint32_t batch, bool accumulate, hipStream_t s);
 
 // d0 = b1 b2, d1 = a1 b2 + a2 b1, d2 = a1 a2 ; td: [batch][3][ell][N]
 void launch_tensor_product(const ks_ctx* c, const uint64_t* cta, const uint64_t* ctb, uint64_t* td, uint32_t ell,

@@ -85,3 +85,22 @@ def test_cfg5_hmult_merged_full_size():
         want = st.ref.hmult_relin_rescale_merged(host(cta[b])[None], host(ctb[b])[None], host(rlk), ell)
         assert_equal(out[b], want[0])
     assert _in_range(out[77].reshape(-1, ell - 1, st.N), st.q[:ell - 1])
+
+
+def test_cfg3_rotate_mac_full_size():
+    """Configuration 3's shape through the double-hoisted entry point: 64 ciphertexts, 16 rotations summed."""
+    cfg = ks_inputs.CONFIGS[3]
+    st = Setup(cfg["logN"], cfg["L"], cfg["K"], cfg["dnum"])
+    ell, B, n_rot, seed = cfg["L"], cfg["batch"], cfg["n_rot"], cfg["seed"]
+    ct = st.uniform(seed, 1, (B, 2), list(range(ell)))
+    keys = [st.uniform(seed, 10 + r, (cfg["dnum"], 2), list(range(ell + cfg["K"]))) for r in range(n_rot)]
+    pts = [st.uniform(seed, 100 + r, (), list(range(ell + cfg["K"]))) for r in range(n_rot)]
+    galois = ks_inputs.galois_elements(cfg["logN"], n_rot)
+    out = torch.empty((B, 2, ell, st.N), dtype=torch.int64, device="cuda")
+    K.ks_rotate_mac_hoisted(st.ctx, ct, ell, galois, keys, pts, out, workspace(st.ctx, K.KS_OP_ROTATE_HOISTED, ell, B, n_rot))
+    torch.cuda.synchronize()
+    hk, hp = [host(k) for k in keys], [host(w) for w in pts]
+    for b in (0, 17, 63):      # first chunk, chunk boundary + 1, last
+        want = st.ref.rotate_mac_hoisted(host(ct[b])[None], galois, hk, hp, ell)
+        assert_equal(out[b], want[0])
+    assert _in_range(out[40].reshape(-1, ell, st.N), st.q)

@@ -121,6 +121,41 @@ def test_rotate_hoisted_bootstrap_shape(boot):
     assert_equal(out, boot.ref.rotate_hoisted(host(ct), galois, [host(k) for k in keys], 24))
 
 
+def _run_rotate_mac(st, seed, ell, batch, n_rot):
+    ct = st.uniform(seed, 1, (batch, 2), list(range(ell)))
+    keys = [st.uniform(seed, 10 + r, (st.ctx.dnum, 2), list(range(st.L + st.K))) for r in range(n_rot)]
+    pts = [st.uniform(seed, 100 + r, (), list(range(st.L + st.K))) for r in range(n_rot)]
+    galois = ks_inputs.galois_elements(st.logN, n_rot)
+    out = torch.empty((batch, 2, ell, st.N), dtype=torch.int64, device="cuda")
+    ws = workspace(st.ctx, K.KS_OP_ROTATE_HOISTED, ell, batch, n_rot)
+    K.ks_rotate_mac_hoisted(st.ctx, ct, ell, galois, keys, pts, out, ws)
+    return ct, keys, pts, galois, out
+
+
+@pytest.mark.parametrize("ell,batch,n_rot", [(4, 2, 3), (3, 1, 2), (4, 19, 1), (4, 3, 18)])   # 18 rotations: two chained launches
+def test_rotate_mac_small(small, ell, batch, n_rot):
+    ct, keys, pts, galois, out = _run_rotate_mac(small, 1008, ell, batch, n_rot)
+    assert_equal(out, small.ref.rotate_mac_hoisted(host(ct), galois, [host(k) for k in keys], [host(w) for w in pts], ell))
+
+
+def test_rotate_mac_bootstrap_shape(boot):
+    ct, keys, pts, galois, out = _run_rotate_mac(boot, 1008, 24, 2, 3)
+    assert_equal(out, boot.ref.rotate_mac_hoisted(host(ct), galois, [host(k) for k in keys], [host(w) for w in pts], 24))
+
+
+def test_rotate_mac_unit_plaintext_equals_rotate_hoisted(small):
+    ell, g = 4, ks_inputs.galois_elements(small.logN, 2)[1]
+    ct = small.uniform(6, 1, (2, 2), list(range(ell)))
+    key = small.uniform(6, 2, (2, 2), list(range(6)))
+    one = torch.ones((6, small.N), dtype=torch.int64, device="cuda")
+    ws = workspace(small.ctx, K.KS_OP_ROTATE_HOISTED, ell, 2, 1)
+    mac = torch.empty((2, 2, ell, small.N), dtype=torch.int64, device="cuda")
+    K.ks_rotate_mac_hoisted(small.ctx, ct, ell, [g], [key], [one], mac, ws)
+    rot = torch.empty((2, 1, 2, ell, small.N), dtype=torch.int64, device="cuda")
+    K.ks_rotate_hoisted(small.ctx, ct, ell, [g], [key], rot, ws)
+    assert torch.equal(mac, rot[:, 0])
+
+
 def test_rotate_by_identity_equals_keyswitch_plus_c0(small):
     ell = 4
     ct = small.uniform(5, 1, (1, 2), list(range(ell)))
