@@ -73,6 +73,9 @@ void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, u
 // deferred to the whole sum).  One thread owns one slot of one limb position for a group of ciphertexts and walks the
 // rotations: key slots and the plaintext slot of a rotation are read once per group, the raised digits and c0 come
 // through the sigma_g gather, and the two running sums stay in registers until every rotation of the launch is in.
+// Branch-free on purpose (digit count as a template parameter, a short last group recomputes its last ciphertext, special
+// limbs read a c0 limb they multiply by zero): every load of a rotation is then issued before the first product.
+template <int NDIG>
 __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__ mods, const double* __restrict__ Pmod, DigitRanges dg,
                                                          uint32_t ell, uint32_t E, uint32_t L, uint32_t M, uint32_t logN,
                                                          const uint64_t* __restrict__ ct, uint64_t ct_bs,
@@ -82,62 +85,68 @@ __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__
     const uint32_t pos = blockIdx.y;
     const uint32_t mid = pos < ell ? pos : L + (pos - ell);
     const Mod m = mods[mid];
-    const double pm = pos < ell ? Pmod[pos] : 0.0;
+    const uint32_t c0_limb = min(pos, ell - 1);
+    const double pm = pos < ell ? Pmod[c0_limb] : 0.0;
     const uint32_t n = blockIdx.x * 256 + threadIdx.x;
     const uint32_t b_lo = blockIdx.z * kBatchGroup;
-    const uint32_t nb = min((uint32_t)kBatchGroup, batch - b_lo);
+    // per ciphertext of the group: where its c0 limb and its NDIG source limbs of this position start
+    const uint64_t* c0p[kBatchGroup];
+    const uint64_t* srcp[kBatchGroup][NDIG];
+    uint64_t* up[kBatchGroup];
+#pragma unroll
+    for (int bi = 0; bi < kBatchGroup; ++bi) {
+        const uint32_t b = min(b_lo + bi, batch - 1);
+        const uint64_t* cb = ct + (uint64_t)b * ct_bs;
+        c0p[bi] = cb + (uint64_t)c0_limb * N;
+#pragma unroll
+        for (int j = 0; j < NDIG; ++j) {
+            const bool own = pos >= dg.lo[j] && pos < dg.hi[j];  // uniform
+            srcp[bi][j] = own ? cb + ((uint64_t)ell + pos) * N : lifted + (((uint64_t)b * NDIG + j) * E + pos) * N;
+        }
+        up[bi] = u + (((uint64_t)b * 2) * E + pos) * N + n;
+    }
     double u0[kBatchGroup], u1[kBatchGroup];
 #pragma unroll
     for (int bi = 0; bi < kBatchGroup; ++bi) {
-        u0[bi] = u1[bi] = 0.0;
-        if (accumulate && bi < (int)nb) {
-            u0[bi] = u64_to_f64(u[(((uint64_t)(b_lo + bi) * 2 + 0) * E + pos) * N + n]);
-            u1[bi] = u64_to_f64(u[(((uint64_t)(b_lo + bi) * 2 + 1) * E + pos) * N + n]);
-        }
+        u0[bi] = accumulate ? u64_to_f64(up[bi][0]) : 0.0;
+        u1[bi] = accumulate ? u64_to_f64(up[bi][(uint64_t)E * N]) : 0.0;
     }
 #pragma unroll 1
     for (uint32_t r = 0; r < rot.n; ++r) {
         const uint32_t sn = galois_source_slot(n, rot.galois[r], logN);
-        const uint64_t* key = rot.key[r];
-        double k0[kMaxDigits], k1[kMaxDigits];
+        const uint64_t* key = rot.key[r] + (uint64_t)mid * N + n;
+        uint64_t kraw[NDIG][2], xraw[kBatchGroup][NDIG], craw[kBatchGroup];
 #pragma unroll
-        for (int j = 0; j < kMaxDigits; ++j) {
-            k0[j] = k1[j] = 0.0;
-            if (j < (int)dg.ndig) {
-                k0[j] = u64_to_f64(key[((uint64_t)(j * 2 + 0) * M + mid) * N + n]);
-                k1[j] = u64_to_f64(key[((uint64_t)(j * 2 + 1) * M + mid) * N + n]);
-            }
+        for (int j = 0; j < NDIG; ++j) {
+            kraw[j][0] = key[(uint64_t)(j * 2 + 0) * M * N];
+            kraw[j][1] = key[(uint64_t)(j * 2 + 1) * M * N];
         }
-        const double w = u64_to_f64(rot.pt[r][(uint64_t)mid * N + n]);
+        const uint64_t wraw = rot.pt[r][(uint64_t)mid * N + n];
 #pragma unroll
         for (int bi = 0; bi < kBatchGroup; ++bi) {
-            if (bi < (int)nb) {
-                const uint64_t* cb = ct + (uint64_t)(b_lo + bi) * ct_bs;
-                double t0 = 0.0, t1 = 0.0;
 #pragma unroll
-                for (int j = 0; j < kMaxDigits; ++j) {
-                    if (j < (int)dg.ndig) {
-                        const bool own = pos >= dg.lo[j] && pos < dg.hi[j];
-                        const uint64_t* src = own ? cb + ((uint64_t)ell + pos) * N
-                                                  : lifted + (((uint64_t)(b_lo + bi) * dg.ndig + j) * E + pos) * N;
-                        const double x = u64_to_f64(src[sn]);
-                        t0 += mulmod_lazy(x, k0[j], m);
-                        t1 += mulmod_lazy(x, k1[j], m);
-                    }
-                }
-                if (pos < ell) t0 += mulmod_lazy(u64_to_f64(cb[(uint64_t)pos * N + sn]), pm, m);
-                // |t| <= (digits + 1) * 0.51 p, far inside the range of a lazy product; the sums grow by 0.51 p a rotation
-                u0[bi] += mulmod_lazy(t0, w, m);
-                u1[bi] += mulmod_lazy(t1, w, m);
+            for (int j = 0; j < NDIG; ++j) xraw[bi][j] = srcp[bi][j][sn];
+            craw[bi] = c0p[bi][sn];
+        }
+        const double w = u64_to_f64(wraw);
+#pragma unroll
+        for (int bi = 0; bi < kBatchGroup; ++bi) {
+            double t0 = mulmod_lazy(u64_to_f64(craw[bi]), pm, m), t1 = 0.0;
+#pragma unroll
+            for (int j = 0; j < NDIG; ++j) {
+                const double x = u64_to_f64(xraw[bi][j]);
+                t0 += mulmod_lazy(x, u64_to_f64(kraw[j][0]), m);
+                t1 += mulmod_lazy(x, u64_to_f64(kraw[j][1]), m);
             }
+            // |t| <= (digits + 1) * 0.51 p, far inside the range of a lazy product; the sums grow by 0.51 p a rotation
+            u0[bi] += mulmod_lazy(t0, w, m);
+            u1[bi] += mulmod_lazy(t1, w, m);
         }
     }
 #pragma unroll
     for (int bi = 0; bi < kBatchGroup; ++bi) {
-        if (bi < (int)nb) {
-            u[(((uint64_t)(b_lo + bi) * 2 + 0) * E + pos) * N + n] = f64_to_u64(canon(reduce_lazy(u0[bi], m), m));
-            u[(((uint64_t)(b_lo + bi) * 2 + 1) * E + pos) * N + n] = f64_to_u64(canon(reduce_lazy(u1[bi], m), m));
-        }
+        up[bi][0] = f64_to_u64(canon(reduce_lazy(u0[bi], m), m));
+        up[bi][(uint64_t)E * N] = f64_to_u64(canon(reduce_lazy(u1[bi], m), m));
     }
 }
 
@@ -152,11 +161,26 @@ void launch_rotate_mac(const ks_ctx* c, const Level& lv, const uint64_t* ct, uin
     }
     const uint32_t groups = (batch + kBatchGroup - 1) / kBatchGroup;
     const dim3 grid(c->N / 256, lv.E, groups), block(256);
-    // per rotation: every raised digit limb and c0 per ciphertext, key and plaintext once per group; both sums written once
-    const double reads = (double)rot.n * ((double)batch * (lv.ndig * lv.E + lv.ell) + (double)groups * (2.0 * lv.ndig + 1.0) * lv.E);
-    ProfScope ps("rotate_mac", (reads + (double)batch * 2 * lv.E * (accumulate ? 2 : 1)) * c->N * 8.0, s);
-    hipLaunchKernelGGL(rotate_mac_kernel, grid, block, 0, s, c->d_mod, c->d_Pmod, dg, lv.ell, lv.E, c->L, c->M, c->logN, ct, ct_bs, lifted,
-                       rot, u, batch, accumulate ? 1 : 0);
+    // Algorithmic traffic: the raised digits and c0 of a ciphertext once (the rotations of a launch re-read them through
+    // the gather; those re-reads are meant to come from cache), key and plaintext of every rotation once per group, both
+    // sums written once.  Algorithmic work per slot, ciphertext and rotation: 2 NDIG + 3 modular products.
+    const double reads = (double)batch * (lv.ndig * lv.E + lv.ell) + (double)rot.n * groups * (2.0 * lv.ndig + 1.0) * lv.E;
+    ProfScope ps("rotate_mac", (reads + (double)batch * 2 * lv.E * (accumulate ? 2 : 1)) * c->N * 8.0, s,
+                 (double)rot.n * batch * lv.E * c->N * (7.0 * (2 * lv.ndig + 3)));
+#define KS_LAUNCH_MAC(ND)                                                                                                          \
+    hipLaunchKernelGGL(rotate_mac_kernel<ND>, grid, block, 0, s, c->d_mod, c->d_Pmod, dg, lv.ell, lv.E, c->L, c->M, c->logN, ct, ct_bs, \
+                       lifted, rot, u, batch, accumulate ? 1 : 0)
+    switch (lv.ndig) {
+        case 1: KS_LAUNCH_MAC(1); break;
+        case 2: KS_LAUNCH_MAC(2); break;
+        case 3: KS_LAUNCH_MAC(3); break;
+        case 4: KS_LAUNCH_MAC(4); break;
+        case 5: KS_LAUNCH_MAC(5); break;
+        case 6: KS_LAUNCH_MAC(6); break;
+        case 7: KS_LAUNCH_MAC(7); break;
+        default: KS_LAUNCH_MAC(8); break;
+    }
+#undef KS_LAUNCH_MAC
 }
 
 // (b1, a1) x (b2, a2) -> d0 = b1 b2, d1 = a1 b2 + a2 b1, d2 = a1 a2
