@@ -1,6 +1,8 @@
 // The extern "C" entry points: argument checks, workspace carving and the kernel chains.
 #include <algorithm>
 
+#include <stdlib.h>
+
 #include "ks_internal.hpp"
 
 using namespace ks;
@@ -8,6 +10,7 @@ using namespace ks;
 namespace {
 
 constexpr uint32_t kChunk = 16;  // ciphertexts processed per pass of a pipeline; bounds the workspace
+constexpr uint32_t kRotGroup = 4;  // hoisted rotations whose accumulators are formed by one launch (more gain nothing); bounds the workspace
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -57,6 +60,11 @@ void mod_up(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, 
     if (finish_rows) launch_ntt_fwd_rows(c, lv.lifted_map, lifted, lifted_ps, bc, s);
 }
 
+// algorithmic fp64 work per coefficient of the ModDown conversion + column half (see mod_up)
+static double moddown_ops(const ks_ctx* c, const Level& lv) {
+    return (double)c->K * lv.ell * 4.5 + lv.ell * (3.0 + 4.0 * (c->logN - 8));
+}
+
 // Division by P of both accumulators, optional addend: INTT of the special limbs (in place), fused base
 // conversion + column half, fused row half + (acc - conv) P^-1.
 void mod_down(const ks_ctx* c, const Level& lv, uint64_t* acc, uint64_t* conv, uint64_t* out, uint64_t out_bs,
@@ -66,8 +74,7 @@ void mod_down(const ks_ctx* c, const Level& lv, uint64_t* acc, uint64_t* conv, u
     // the fused inner product already ran the row half of the inverse transform on the special limbs
     if (!special_rows_done) launch_ntt_inv_rows(c, lv.special_map, XformIO{acc, acc, acc_ps, acc_ps, 2 * bc}, s);
     launch_ntt_inv_cols(c, lv.special_map, acc, acc_ps, 2 * bc, c->d_moddown_scale, true, true, s);
-    const double ops = (double)c->K * lv.ell * 4.5 + lv.ell * (3.0 + 4.0 * (c->logN - 8));
-    launch_bconv_ntt_cols(c, lv.d_moddown, 1, lv.ell, c->K + lv.ell, acc, acc_ps, conv, conv_ps, 2 * bc, s, ops);
+    launch_bconv_ntt_cols(c, lv.d_moddown, 1, lv.ell, c->K + lv.ell, acc, acc_ps, conv, conv_ps, 2 * bc, s, moddown_ops(c, lv));
     launch_rows_moddown_finish(c, lv, acc, conv, out, out_bs, addend, addend_bs, addend_comps, galois, bc, s);
 }
 
@@ -83,6 +90,8 @@ extern "C" size_t ks_workspace_bytes(const ks_ctx* c, int op, uint32_t ell, uint
         case KS_OP_KEYSWITCH: break;
         case KS_OP_ROTATE_HOISTED:
             if (n_rot == 0) return 0;
+            // accumulators and converted limbs for a whole group of rotations
+            words += (uint64_t)(std::min(n_rot, kRotGroup) - 1) * bc * (2 * lv.E + 2 * ell) * N;
             break;
         case KS_OP_HMULT_RELIN_RESCALE:
             if (ell < 2) return 0;
@@ -234,10 +243,29 @@ extern "C" int ks_rotate_hoisted(const ks_ctx* c, const uint64_t* ct, uint32_t e
         const uint64_t* c0 = ct + (uint64_t)b0 * ct_bs;
         const uint64_t* c1 = c0 + (uint64_t)ell * N;
         mod_up(c, lv, c1, ct_bs, coeff, lifted, bc, true, s);   // finished once, shared by every rotation
-        for (uint32_t r = 0; r < n_rot; ++r) {
-            uint64_t* o = out + (uint64_t)b0 * out_bs + (uint64_t)r * 2 * ell * N;
-            launch_inner_product(c, lv, c1, ct_bs, lifted, rot_keys[r], acc, bc, galois[r], s);
-            mod_down(c, lv, acc, conv, o, out_bs, c0, ct_bs, 1, galois[r], bc, false, s);
+        // Rotations go in groups: one gather launch forms the accumulators of the whole group (the raised digits then come
+        // from memory once per group), the inverse transform and the conversion run over the group as one batch, and only
+        // the last kernel, which adds sigma_g(c0) through a rotation's own permutation, runs per rotation.
+        const uint32_t group = std::min(n_rot, kRotGroup);
+        conv = acc + (uint64_t)group * w.acc;
+        const uint64_t acc_ps = (uint64_t)lv.E * N, conv_ps = (uint64_t)ell * N;
+        for (uint32_t r0 = 0; r0 < n_rot; r0 += group) {
+            MacRotations rot;
+            rot.n = std::min(n_rot - r0, group);
+            for (uint32_t r = 0; r < rot.n; ++r) {
+                rot.galois[r] = galois[r0 + r];
+                rot.key[r] = rot_keys[r0 + r];
+                rot.pt[r] = nullptr;
+            }
+            launch_inner_product(c, lv, c1, ct_bs, lifted, rot, acc, bc, s);
+            const uint32_t polys = 2 * rot.n * bc;
+            launch_ntt_inv_rows(c, lv.special_map, XformIO{acc, acc, acc_ps, acc_ps, polys}, s);
+            launch_ntt_inv_cols(c, lv.special_map, acc, acc_ps, polys, c->d_moddown_scale, true, true, s);
+            launch_bconv_ntt_cols(c, lv.d_moddown, 1, lv.ell, c->K + lv.ell, acc, acc_ps, conv, conv_ps, polys, s, moddown_ops(c, lv));
+            for (uint32_t r = 0; r < rot.n; ++r)
+                launch_rows_moddown_finish(c, lv, acc + (uint64_t)r * w.acc, conv + (uint64_t)r * w.conv,
+                                           out + (uint64_t)b0 * out_bs + (uint64_t)(r0 + r) * 2 * ell * N, out_bs, c0, ct_bs, 1,
+                                           galois[r0 + r], bc, s);
         }
     }
     return finish("ks_rotate_hoisted");

@@ -8,65 +8,92 @@ namespace ks {
 
 constexpr int kBatchGroup = 8;  // batch items sharing one read of the key slots
 
-template <bool GATHER>
+// Inner products through the sigma_g gather for a group of hoisted rotations: acc[r][b][c][pos] = sum_j sigma_{g_r}(src_j)[pos]
+// key_r[j][c][pos].  One thread owns one slot of one limb position for a group of ciphertexts and walks the rotations of
+// the launch, so the raised digits it gathers from are read from memory once per launch and from cache afterwards.
+// Branch-free like rotate_mac_kernel below: the digit count is a template parameter and a short last group recomputes
+// its last ciphertext, so every load of a rotation is issued before the first product.
+template <int NDIG>
 __global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restrict__ mods, DigitRanges dg, uint32_t ell, uint32_t E,
                                                             uint32_t L, uint32_t M, uint32_t logN, const uint64_t* __restrict__ d,
-                                                            uint64_t d_ps, const uint64_t* __restrict__ lifted,
-                                                            const uint64_t* __restrict__ evk, uint64_t* __restrict__ acc,
-                                                            uint32_t batch, uint32_t galois) {
+                                                            uint64_t d_ps, const uint64_t* __restrict__ lifted, MacRotations rot,
+                                                            uint64_t* __restrict__ acc, uint32_t batch) {
     const uint32_t N = 1u << logN;
     const uint32_t pos = blockIdx.y;
     const uint32_t mid = pos < ell ? pos : L + (pos - ell);
     const Mod m = mods[mid];
     const uint32_t n = blockIdx.x * 256 + threadIdx.x;
-    const uint32_t sn = GATHER ? galois_source_slot(n, galois, logN) : n;
-    double k0[kMaxDigits], k1[kMaxDigits];
+    const uint32_t b_lo = blockIdx.z * kBatchGroup;
+    const uint64_t* srcp[kBatchGroup][NDIG];
 #pragma unroll
-    for (int j = 0; j < kMaxDigits; ++j) {
-        k0[j] = k1[j] = 0.0;
-        if (j < (int)dg.ndig) {
-            k0[j] = u64_to_f64(evk[((uint64_t)(j * 2 + 0) * M + mid) * N + n]);
-            k1[j] = u64_to_f64(evk[((uint64_t)(j * 2 + 1) * M + mid) * N + n]);
+    for (int bi = 0; bi < kBatchGroup; ++bi) {
+        const uint32_t b = min(b_lo + bi, batch - 1);
+#pragma unroll
+        for (int j = 0; j < NDIG; ++j) {
+            const bool own = pos >= dg.lo[j] && pos < dg.hi[j];  // uniform
+            srcp[bi][j] = own ? d + (uint64_t)b * d_ps + (uint64_t)pos * N : lifted + (((uint64_t)b * NDIG + j) * E + pos) * N;
         }
     }
-    const uint32_t b_lo = blockIdx.z * kBatchGroup;
-    const uint32_t b_hi = min(b_lo + kBatchGroup, batch);
-    for (uint32_t b = b_lo; b < b_hi; ++b) {
-        double a0 = 0.0, a1 = 0.0;
+#pragma unroll 1
+    for (uint32_t r = 0; r < rot.n; ++r) {
+        const uint32_t sn = galois_source_slot(n, rot.galois[r], logN);
+        const uint64_t* key = rot.key[r] + (uint64_t)mid * N + n;
+        uint64_t kraw[NDIG][2], xraw[kBatchGroup][NDIG];
 #pragma unroll
-        for (int j = 0; j < kMaxDigits; ++j) {
-            if (j < (int)dg.ndig) {
-                const bool own = pos >= dg.lo[j] && pos < dg.hi[j];
-                const uint64_t* src = own ? d + (uint64_t)b * d_ps + (uint64_t)pos * N
-                                          : lifted + (((uint64_t)b * dg.ndig + j) * E + pos) * N;
-                const double x = u64_to_f64(src[sn]);
-                a0 += mulmod_lazy(x, k0[j], m);
-                a1 += mulmod_lazy(x, k1[j], m);
-            }
+        for (int j = 0; j < NDIG; ++j) {
+            kraw[j][0] = key[(uint64_t)(j * 2 + 0) * M * N];
+            kraw[j][1] = key[(uint64_t)(j * 2 + 1) * M * N];
         }
-        acc[(((uint64_t)b * 2 + 0) * E + pos) * N + n] = f64_to_u64(canon(reduce_lazy(a0, m), m));
-        acc[(((uint64_t)b * 2 + 1) * E + pos) * N + n] = f64_to_u64(canon(reduce_lazy(a1, m), m));
+#pragma unroll
+        for (int bi = 0; bi < kBatchGroup; ++bi)
+#pragma unroll
+            for (int j = 0; j < NDIG; ++j) xraw[bi][j] = srcp[bi][j][sn];
+        uint64_t* ar = acc + (uint64_t)r * batch * 2 * E * N;
+#pragma unroll
+        for (int bi = 0; bi < kBatchGroup; ++bi) {
+            const uint32_t b = min(b_lo + bi, batch - 1);
+            double a0 = 0.0, a1 = 0.0;
+#pragma unroll
+            for (int j = 0; j < NDIG; ++j) {
+                const double x = u64_to_f64(xraw[bi][j]);
+                a0 += mulmod_lazy(x, u64_to_f64(kraw[j][0]), m);
+                a1 += mulmod_lazy(x, u64_to_f64(kraw[j][1]), m);
+            }
+            ar[(((uint64_t)b * 2 + 0) * E + pos) * N + n] = f64_to_u64(canon(reduce_lazy(a0, m), m));
+            ar[(((uint64_t)b * 2 + 1) * E + pos) * N + n] = f64_to_u64(canon(reduce_lazy(a1, m), m));
+        }
     }
 }
 
 void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, const uint64_t* lifted,
-                          const uint64_t* evk, uint64_t* acc, uint32_t batch, uint32_t galois, hipStream_t s) {
-    if (batch == 0) return;
+                          const MacRotations& rot, uint64_t* acc, uint32_t batch, hipStream_t s) {
+    if (batch == 0 || rot.n == 0) return;
     DigitRanges dg;
     dg.ndig = lv.ndig;
     for (uint32_t j = 0; j < kMaxDigits; ++j) {
         dg.lo[j] = j < lv.ndig ? lv.digit_lo[j] : 0;
         dg.hi[j] = j < lv.ndig ? lv.digit_hi[j] : 0;
     }
-    const dim3 grid(c->N / 256, lv.E, (batch + kBatchGroup - 1) / kBatchGroup), block(256);
-    // reads: every raised digit limb per ciphertext, the key once; writes: both accumulators
-    ProfScope ps("inner_product", ((double)batch * (lv.ndig + 2) * lv.E + 2.0 * lv.ndig * lv.E) * c->N * 8.0, s);
-    if (galois == 1)
-        hipLaunchKernelGGL(inner_product_kernel<false>, grid, block, 0, s, c->d_mod, dg, lv.ell, lv.E, c->L, c->M, c->logN, d,
-                           d_ps, lifted, evk, acc, batch, galois);
-    else
-        hipLaunchKernelGGL(inner_product_kernel<true>, grid, block, 0, s, c->d_mod, dg, lv.ell, lv.E, c->L, c->M, c->logN, d,
-                           d_ps, lifted, evk, acc, batch, galois);
+    const uint32_t groups = (batch + kBatchGroup - 1) / kBatchGroup;
+    const dim3 grid(c->N / 256, lv.E, groups), block(256);
+    // reads: every raised digit limb per ciphertext once per launch, each rotation's key once per group; writes: both
+    // accumulators of every rotation
+    ProfScope ps("inner_product",
+                 ((double)batch * lv.ndig * lv.E + (double)rot.n * (2.0 * lv.ndig * lv.E * groups + 2.0 * lv.E * batch)) * c->N * 8.0, s);
+#define KS_LAUNCH_IP(ND)                                                                                                        \
+    hipLaunchKernelGGL(inner_product_kernel<ND>, grid, block, 0, s, c->d_mod, dg, lv.ell, lv.E, c->L, c->M, c->logN, d, d_ps, lifted, \
+                       rot, acc, batch)
+    switch (lv.ndig) {
+        case 1: KS_LAUNCH_IP(1); break;
+        case 2: KS_LAUNCH_IP(2); break;
+        case 3: KS_LAUNCH_IP(3); break;
+        case 4: KS_LAUNCH_IP(4); break;
+        case 5: KS_LAUNCH_IP(5); break;
+        case 6: KS_LAUNCH_IP(6); break;
+        case 7: KS_LAUNCH_IP(7); break;
+        default: KS_LAUNCH_IP(8); break;
+    }
+#undef KS_LAUNCH_IP
 }
 
 // Rotate-multiply-accumulate on the extended basis (inner sum of a baby-step giant-step transform with the division by P

@@ -164,13 +164,7 @@ void launch_bconv(const ks_ctx* c, const BConvPlan* d_plans, uint32_t limbs_move
                   const uint64_t* in, uint64_t in_poly_stride, uint64_t* out, uint64_t out_poly_stride,
                   uint32_t n_polys, uint32_t n_src_max, hipStream_t s);
 
-// acc[b][c][pos] = sum_j src_j[pos] * key[j][c][ext_id(pos)];  src_j[pos] = d[b][pos] when pos lies in digit j,
-// otherwise lifted[b][j][pos].  With galois != 1 the source slot is permuted by sigma_g.
-void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_poly_stride,
-                          const uint64_t* lifted, const uint64_t* evk, uint64_t* acc, uint32_t batch,
-                          uint32_t galois, hipStream_t s);
-
-// Rotations handled by one launch of the rotate-multiply-accumulate kernel (more are chained, accumulating).
+// Rotations handled by one launch of the gather kernels (more are chained).
 constexpr int kMacRotations = 16;
 struct MacRotations {
     uint32_t n;
@@ -178,6 +172,11 @@ struct MacRotations {
     const uint64_t* key[kMacRotations];  // [dnum][2][L+K][N]
     const uint64_t* pt[kMacRotations];   // [L+K][N]
 };
+// acc[r][b][c][pos] = sum_j sigma_{g_r}(src_j)[pos] * key_r[j][c][ext_id(pos)] for every rotation r of `rot` (pt unused);
+// src_j[pos] = d[b][pos] when pos lies in digit j, otherwise lifted[b][j][pos].
+void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_poly_stride, const uint64_t* lifted,
+                          const MacRotations& rot, uint64_t* acc, uint32_t batch, hipStream_t s);
+
 // u[b][c][pos] (+)= sum_r pt_r[pos] * (sum_j sigma_r(src_j)[pos] key_r[j][c][pos] + [c = 0][pos < ell] P sigma_r(c0)[pos]);
 // ct: [b][2][ell][N] (c0, c1), lifted: finished raised digits of c1.  accumulate: add to what u already holds.
 void launch_rotate_mac(const ks_ctx* c, const Level& lv, const uint64_t* ct, uint64_t ct_bs, const uint64_t* lifted,
