@@ -332,37 +332,38 @@ void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const uint64_t*
 // ------------------------------------------------------------------------------------------------
 // out[b][comp][i] = (acc[b][comp][i] - NTT_rows(conv[b][comp][i])) * P^-1 (+ addend), canonical.
 // ------------------------------------------------------------------------------------------------
-template <int LOG_R, bool GATHER>
+// ADDEND: 0 = none, 1 = added as it is, 2 = multiplied by addend_mul[i] first.  Compile-time so that the kernel has no
+// branch: behind a run-time test every addend load became its own load-wait-use round trip.  A launch covers the
+// components comp0 .. comp0 + n_comps - 1 of every batch item.
+template <int LOG_R, bool GATHER, int ADDEND>
 __global__ __launch_bounds__(64) void rows_moddown_finish(TwTables tw, const Mod* __restrict__ mods,
                                                           const double* __restrict__ Pinv, const double* __restrict__ addend_mul,
                                                           uint32_t ell, uint32_t E, uint32_t out_limbs,
                                                           const uint64_t* __restrict__ acc, const uint64_t* __restrict__ conv,
                                                           uint64_t* __restrict__ out, uint64_t out_bs,
                                                           const uint64_t* __restrict__ addend, uint64_t addend_bs,
-                                                          uint32_t addend_comps, uint32_t galois) {
+                                                          uint32_t comp0, uint32_t n_comps, uint32_t galois) {
     constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R, LOGN = LOG_R + 8;
     __shared__ double lds[4 * kRowPitch];
-    const uint32_t tid = threadIdx.x, rg = blockIdx.x, i = blockIdx.y, b = blockIdx.z >> 1, comp = blockIdx.z & 1;
+    const uint32_t tid = threadIdx.x, rg = blockIdx.x, i = blockIdx.y;
+    const uint32_t b = blockIdx.z / n_comps, comp = comp0 + (blockIdx.z - b * n_comps);
     const Mod m = mods[i];
     const double pinv = Pinv[i];
-    const double admul = addend_mul ? addend_mul[i] : 0.0;  // uniform; 0 = the addend enters unscaled
     const uint32_t j0 = tid & 15, rr = tid >> 4, row = rg * 4 + rr;
     const uint32_t off = row * 256 + j0;
     const uint64_t* src = conv + (((uint64_t)b * 2 + comp) * ell + i) * N + off;
     const uint64_t* ap = acc + (((uint64_t)b * 2 + comp) * E + i) * N + off;
     uint64_t* op = out + (uint64_t)b * out_bs + ((uint64_t)comp * out_limbs + i) * N + off;
-    const bool add = addend != nullptr && comp < addend_comps;
-    const uint64_t* adp = add ? addend + (uint64_t)b * addend_bs + ((uint64_t)comp * ell + i) * N : nullptr;
     // issue every load up front: the accumulator (and addend) slots do not depend on the transform
     double w[16], a[16], ad[16];
 #pragma unroll
     for (int k = 0; k < 16; ++k) w[k] = load_f64(src + 16 * k);
 #pragma unroll
     for (int k = 0; k < 16; ++k) a[k] = u64_to_f64(ap[16 * k]);
+    if constexpr (ADDEND != 0) {
+        const uint64_t* adp = addend + (uint64_t)b * addend_bs + ((uint64_t)comp * ell + i) * N;
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
-        ad[k] = 0.0;
-        if (add) {
+        for (int k = 0; k < 16; ++k) {
             const uint32_t n = off + 16 * k;
             ad[k] = u64_to_f64(adp[GATHER ? galois_source_slot(n, galois, LOGN) : n]);
         }
@@ -370,9 +371,13 @@ __global__ __launch_bounds__(64) void rows_moddown_finish(TwTables tw, const Mod
     PassTwiddles t;
     load_row_twiddles(t, tw, i, N, R + row, j0, m);
     row_fwd_core(w, t, j0, lds + rr * kRowPitch, m);
+    double admul = 0.0;
+    if constexpr (ADDEND == 2) admul = addend_mul[i];
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
-        const double r = reduce_lazy(mulmod_lazy(a[k] - w[k], pinv, m) + (admul != 0.0 ? mulmod_lazy(ad[k], admul, m) : ad[k]), m);
+        double r = mulmod_lazy(a[k] - w[k], pinv, m);
+        if constexpr (ADDEND == 1) r = reduce_lazy(r + ad[k], m);
+        if constexpr (ADDEND == 2) r = reduce_lazy(r + mulmod_lazy(ad[k], admul, m), m);
         op[16 * k] = f64_to_u64(canon(r, m));
     }
 }
@@ -385,19 +390,32 @@ void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t
     const double* admul = fs ? fs->addend_mul : nullptr;
     const uint32_t out_limbs = fs ? fs->out_limbs : lv.ell;
     if (out_limbs == 0) return;
-    ProfScope ps("rows_moddown_finish", (double)batch * out_limbs * (6 + (addend ? addend_comps : 0)) * c->N * 8.0, s);
+    if (!addend) addend_comps = 0;
+    ProfScope ps("rows_moddown_finish", (double)batch * out_limbs * (6 + addend_comps) * c->N * 8.0, s);
     const dim3 block(64);
-#define KS_LAUNCH_FINISH(LOGR, GATHER, ROWGROUPS)                                                                              \
-    hipLaunchKernelGGL((rows_moddown_finish<LOGR, GATHER>), dim3(ROWGROUPS, out_limbs, batch * 2), block, 0, s, c->tw_fwd, c->d_mod, \
-                       mul, admul, lv.ell, lv.E, out_limbs, acc, conv, out, out_bs, addend, addend_bs, addend_comps, galois)
-    if (c->logN == 16) {
-        if (galois == 1) KS_LAUNCH_FINISH(8, false, 64);
-        else KS_LAUNCH_FINISH(8, true, 64);
-    } else {
-        if (galois == 1) KS_LAUNCH_FINISH(4, false, 4);
-        else KS_LAUNCH_FINISH(4, true, 4);
-    }
+    const uint32_t row_groups = c->N / 1024;
+    // one launch for the components that take the addend, one for those that do not
+    for (int pass = 0; pass < 2; ++pass) {
+        const uint32_t comp0 = pass == 0 ? 0 : addend_comps, n_comps = pass == 0 ? addend_comps : 2 - addend_comps;
+        if (n_comps == 0) continue;
+        const int mode = pass == 1 ? 0 : (admul ? 2 : 1);
+        const dim3 grid(row_groups, out_limbs, batch * n_comps);
+#define KS_LAUNCH_FINISH(LOGR, GATHER, MODE)                                                                                   \
+    hipLaunchKernelGGL((rows_moddown_finish<LOGR, GATHER, MODE>), grid, block, 0, s, c->tw_fwd, c->d_mod, mul, admul, lv.ell, lv.E, \
+                       out_limbs, acc, conv, out, out_bs, addend, addend_bs, comp0, n_comps, galois)
+        if (c->logN == 16) {
+            if (mode == 0) KS_LAUNCH_FINISH(8, false, 0);
+            else if (mode == 2) KS_LAUNCH_FINISH(8, false, 2);
+            else if (galois == 1) KS_LAUNCH_FINISH(8, false, 1);
+            else KS_LAUNCH_FINISH(8, true, 1);
+        } else {
+            if (mode == 0) KS_LAUNCH_FINISH(4, false, 0);
+            else if (mode == 2) KS_LAUNCH_FINISH(4, false, 2);
+            else if (galois == 1) KS_LAUNCH_FINISH(4, false, 1);
+            else KS_LAUNCH_FINISH(4, true, 1);
+        }
 #undef KS_LAUNCH_FINISH
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
