@@ -222,4 +222,19 @@ def test_error_paths_return_codes(small):
                             torch.empty((1, 1, 2, ell, small.N), dtype=torch.int64, device="cuda"), ws)
     with pytest.raises(K.KsError):
         K.ntt_fwd(small.ctx, d, [99])
+    ct = torch.zeros((1, 2, ell, small.N), dtype=torch.int64, device="cuda")
+    pt = torch.ones((6, small.N), dtype=torch.int64, device="cuda")
+    with pytest.raises(K.KsError):          # even Galois element
+        K.ks_rotate_mac_hoisted(small.ctx, ct, ell, [6], [evk], [pt], out, ws)
+    with pytest.raises(K.KsError):          # nothing to drop at one limb
+        K.hmult_relin_rescale_merged(small.ctx, ct[:, :, :1].contiguous(), ct[:, :, :1].contiguous(), 1, evk,
+                                     torch.empty((1, 2, 1, small.N), dtype=torch.int64, device="cuda"),
+                                     workspace(small.ctx, K.KS_OP_HMULT_RELIN_RESCALE, 2, 1))
+    # an empty batch is a no-op that succeeds and leaves the output alone
+    out.fill_(-7)
+    assert lib.ks_keyswitch(h, d.data_ptr(), ell, evk.data_ptr(), out.data_ptr(), 0, ws.data_ptr(), ws.numel() * 8, None) == 0
+    assert lib.hmult_relin_rescale_merged(h, ct.data_ptr(), ct.data_ptr(), ell, evk.data_ptr(), out.data_ptr(), 0, ws.data_ptr(),
+                                          ws.numel() * 8, None) == 0
+    torch.cuda.synchronize()
+    assert int((out != -7).sum()) == 0
     torch.cuda.synchronize()
