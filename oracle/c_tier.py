@@ -43,6 +43,9 @@ def _load():
                                            ctypes.POINTER(_u64p), ctypes.c_int, _u64p, ctypes.c_int]
         lib.orc_rotate_mac_hoisted.argtypes = [ctypes.c_void_p, _u64p, ctypes.c_int, _u32p, ctypes.POINTER(_u64p),
                                                ctypes.POINTER(_u64p), ctypes.c_int, _u64p, ctypes.c_int]
+        lib.orc_bsgs_linear_transform.argtypes = [ctypes.c_void_p, _u64p, ctypes.c_int, _u32p, ctypes.POINTER(_u64p), ctypes.c_int,
+                                                  _u32p, ctypes.POINTER(_u64p), ctypes.c_int, ctypes.POINTER(_u64p), _u64p,
+                                                  ctypes.c_int]
         lib.orc_hmult_relin_rescale.argtypes = [ctypes.c_void_p, _u64p, _u64p, ctypes.c_int, _u64p, _u64p, ctypes.c_int]
         lib.orc_hmult_relin_rescale_merged.argtypes = [ctypes.c_void_p, _u64p, _u64p, ctypes.c_int, _u64p, _u64p, ctypes.c_int]
         lib.orc_max_threads.restype = ctypes.c_int
@@ -53,6 +56,11 @@ def _load():
 def _p64(a: np.ndarray):
     assert a.dtype == np.uint64 and a.flags["C_CONTIGUOUS"]
     return a.ctypes.data_as(_u64p)
+
+
+def _ptr_array(arrays):
+    """Array of limb pointers for a list of uint64 arrays; None entries become NULL."""
+    return (_u64p * len(arrays))(*[_u64p() if a is None else _p64(a) for a in arrays])
 
 
 def _p32(a: np.ndarray):
@@ -133,14 +141,30 @@ class COracle:
         """ct [batch][2][ell][N]; rot_keys: list of [dnum][2][L+K][N]; pts: list of [L+K][N] -> [batch][2][ell][N]."""
         ell = self.L if ell is None else ell
         ct = np.ascontiguousarray(ct, dtype=np.uint64)
-        keys = [np.ascontiguousarray(k, dtype=np.uint64) for k in rot_keys]
-        pls = [np.ascontiguousarray(w, dtype=np.uint64) for w in pts]
+        keys = [None if k is None else np.ascontiguousarray(k, dtype=np.uint64) for k in rot_keys]
+        pls = [None if w is None else np.ascontiguousarray(w, dtype=np.uint64) for w in pts]
         g = np.asarray(galois, dtype=np.uint32)
         batch = ct.size // (2 * ell * self.N)
         out = np.zeros((batch, 2, ell, self.N), dtype=np.uint64)
-        kp = (_u64p * len(keys))(*[_p64(k) for k in keys])
-        pp = (_u64p * len(pls))(*[_p64(w) for w in pls])
+        kp = _ptr_array(keys)
+        pp = _ptr_array(pls)
         _load().orc_rotate_mac_hoisted(self._h, _p64(ct), ell, _p32(g), kp, pp, len(g), _p64(out), batch)
+        return out
+
+    def bsgs_linear_transform(self, ct: np.ndarray, baby_galois, baby_keys, giant_galois, giant_keys, pts,
+                              ell: int | None = None) -> np.ndarray:
+        """ct [batch][2][ell][N]; keys: lists of [dnum][2][L+K][N] (None where the Galois element is 1);
+        pts[g][b]: [L+K][N] or None (= 1) -> [batch][2][ell][N]."""
+        ell = self.L if ell is None else ell
+        ct = np.ascontiguousarray(ct, dtype=np.uint64)
+        cont = lambda x: None if x is None else np.ascontiguousarray(x, dtype=np.uint64)
+        bk, gk = [cont(k) for k in baby_keys], [cont(k) for k in giant_keys]
+        flat = [cont(w) for row in pts for w in row]
+        bg, gg = np.asarray(baby_galois, dtype=np.uint32), np.asarray(giant_galois, dtype=np.uint32)
+        batch = ct.size // (2 * ell * self.N)
+        out = np.zeros((batch, 2, ell, self.N), dtype=np.uint64)
+        _load().orc_bsgs_linear_transform(self._h, _p64(ct), ell, _p32(bg), _ptr_array(bk), len(bg), _p32(gg), _ptr_array(gk),
+                                          len(gg), _ptr_array(flat), _p64(out), batch)
         return out
 
     def hmult_relin_rescale(self, cta: np.ndarray, ctb: np.ndarray, rlk: np.ndarray, ell: int | None = None) -> np.ndarray:

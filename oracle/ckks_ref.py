@@ -390,6 +390,33 @@ def rotate_hoisted(pr: Params, ct, galois: list[int], rot_keys, ell: int | None 
     return outs
 
 
+def _rotation_term(pr: Params, ct, lifted, g: int, key, ell: int):
+    """One rotated ciphertext on the extended basis, before any division by P: the pair
+    (acc_0 + P sigma_g(c0), acc_1) where acc is the inner product of the sigma_g-permuted raised digits
+    of c1 with the rotation key.  g = 1 stands for the unrotated ciphertext: no key is involved and
+    the pair is P (c0, c1).  (P x is x [P]_{q_i} on the ciphertext limbs and 0 on the special limbs.)"""
+    c0, c1 = ct
+    ext_ids = list(range(ell)) + [pr.L + k for k in range(pr.K)]
+
+    def sigma_eval(limb, m):
+        mod, psi = pr.moduli[m], pr.psi[m]
+        return ntt(automorphism_coeff(intt(limb, mod, psi), g, mod), mod, psi)
+
+    if g == 1:
+        t = [[[0] * pr.N for _ in ext_ids] for _ in range(2)]
+        for i in range(ell):
+            pm = pr.P % pr.q[i]
+            t[0][i] = [pm * x % pr.q[i] for x in c0[i]]
+            t[1][i] = [pm * x % pr.q[i] for x in c1[i]]
+        return t
+    rotated = [[sigma_eval(dj[pos], m) for pos, m in enumerate(ext_ids)] for dj in lifted]
+    acc = inner_product(pr, rotated, key, ell)
+    for i in range(ell):
+        pm = pr.P % pr.q[i]
+        acc[0][i] = [(a + pm * b) % pr.q[i] for a, b in zip(acc[0][i], sigma_eval(c0[i], i))]
+    return acc
+
+
 def rotate_mac_hoisted(pr: Params, ct, galois: list[int], rot_keys, pts, ell: int | None = None):
     """Inner sum of a baby-step giant-step linear transform with the rotations kept in the extended
     basis ("double hoisting", the form in which the DSL's BSGS matrix products consume hoisted
@@ -399,35 +426,47 @@ def rotate_mac_hoisted(pr: Params, ct, galois: list[int], rot_keys, pts, ell: in
     For every Galois element g_r: the raised digits of c1 (one decompose-and-raise, shared) are
     permuted by sigma_{g_r} and multiplied with that rotation's key, which gives both accumulators on
     the extended basis; sigma_{g_r}(c0) joins component 0 lifted to that basis as P * sigma(c0)
-    (P * x is x * [P]_{q_i} on the ciphertext limbs and 0 on the special limbs).  Each rotation's pair
-    is multiplied slot-wise by the plaintext pt_r (evaluation domain, all L + K limbs, like a key) and
-    the products are summed; the sum is divided by P once:
+    (_rotation_term; g_r = 1 is the unrotated ciphertext, P (c0, c1), and reads no key).  Each
+    rotation's pair is multiplied slot-wise by the plaintext pt_r (evaluation domain, all L + K limbs,
+    like a key; None = the constant 1) and the products are summed; the sum is divided by P once:
 
-        u_c[m]  = sum_r pt_r[m] * (acc_{r,c}[m] + [c = 0][m < ell] [P]_{q_m} sigma_{g_r}(c0)[m])   mod m
-        out_c   = mod_down(u_c).
+        u_c[m]  = sum_r pt_r[m] * term_{r,c}[m]   mod m,        out_c = mod_down(u_c).
 
-    With one rotation and pt = 1 this is rotate_hoisted bit for bit."""
+    With one rotation g != 1 and pt = 1 this is rotate_hoisted bit for bit."""
     ell = pr.L if ell is None else ell
-    c0, c1 = ct
-    lifted = mod_up(pr, c1, ell)
+    lifted = mod_up(pr, ct[1], ell)
     ext_ids = list(range(ell)) + [pr.L + k for k in range(pr.K)]
-
-    def sigma_eval(limb, m, g):
-        mod, psi = pr.moduli[m], pr.psi[m]
-        return ntt(automorphism_coeff(intt(limb, mod, psi), g, mod), mod, psi)
-
     u = [[[0] * pr.N for _ in ext_ids] for _ in range(2)]
     for g, key, pt in zip(galois, rot_keys, pts):
-        rotated = [[sigma_eval(dj[pos], m, g) for pos, m in enumerate(ext_ids)] for dj in lifted]
-        acc = inner_product(pr, rotated, key, ell)
-        for pos, m in enumerate(ext_ids):
-            mod = pr.moduli[m]
-            t0 = acc[0][pos]
-            if pos < ell:
-                pm = pr.P % mod
-                t0 = [(a + pm * b) % mod for a, b in zip(t0, sigma_eval(c0[pos], m, g))]
-            u[0][pos] = [(x + w * a) % mod for x, w, a in zip(u[0][pos], pt[m], t0)]
-            u[1][pos] = [(x + w * a) % mod for x, w, a in zip(u[1][pos], pt[m], acc[1][pos])]
+        term = _rotation_term(pr, ct, lifted, g, key, ell)
+        for c in range(2):
+            for pos, m in enumerate(ext_ids):
+                mod = pr.moduli[m]
+                w = pt[m] if pt is not None else [1] * pr.N
+                u[c][pos] = [(x + wv * a) % mod for x, wv, a in zip(u[c][pos], w, term[c][pos])]
+    return mod_down(pr, u[0], ell), mod_down(pr, u[1], ell)
+
+
+def bsgs_linear_transform(pr: Params, ct, baby_galois, baby_keys, giant_galois, giant_keys, pts, ell: int | None = None):
+    """Baby-step giant-step linear transform (DSL, matrix multiplication example), double-hoisted at
+    both levels:
+
+        out = sum_g rot_{G_g}( sum_b pts[g][b] * rot_{B_b}(ct) ).
+
+    Inner sums: rotate_mac_hoisted with the baby-step elements B_b (one decompose-and-raise of c1 for
+    all of them, one division by P per giant step) give v_g on the ciphertext basis.  Outer sum: every
+    v_g is rotated by its giant-step element G_g on the extended basis (_rotation_term: its own
+    decompose-and-raise, key G_g; G_g = 1 adds P v_g), the terms are added and divided by P once."""
+    ell = pr.L if ell is None else ell
+    ext_ids = list(range(ell)) + [pr.L + k for k in range(pr.K)]
+    u = [[[0] * pr.N for _ in ext_ids] for _ in range(2)]
+    for G, gkey, row in zip(giant_galois, giant_keys, pts):
+        v = rotate_mac_hoisted(pr, ct, baby_galois, baby_keys, row, ell)
+        term = _rotation_term(pr, v, mod_up(pr, v[1], ell) if G != 1 else None, G, gkey, ell)
+        for c in range(2):
+            for pos, m in enumerate(ext_ids):
+                mod = pr.moduli[m]
+                u[c][pos] = [(x + a) % mod for x, a in zip(u[c][pos], term[c][pos])]
     return mod_down(pr, u[0], ell), mod_down(pr, u[1], ell)
 
 

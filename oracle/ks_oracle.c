@@ -339,9 +339,64 @@ void orc_rotate_hoisted(const orc_ctx *c, const u64 *ct, int ell, const uint32_t
 }
 
 /* Drop limb ell-1 of poly [ell][N] with rounding to nearest: out [ell-1][N] */
-/* Inner sum of a baby-step giant-step transform with the rotations kept on the extended basis (double hoisting):
- * u_c[m] = sum_r pt_r[m] * (acc_{r,c}[m] + [c = 0][m < ell] [P]_{q_m} sigma_{g_r}(c0)[m]); out_c = mod_down(u_c).
- * pts[r] holds all L + K limbs in evaluation domain, like a key component. */
+/* One rotated ciphertext on the extended basis before any division by P: term = (acc_0 + P sigma_g(c0), acc_1), acc the
+ * inner product of the sigma_g-permuted raised digits of c1 with the rotation key.  g = 1 is the unrotated ciphertext:
+ * no key, term = P (c0, c1) on the ciphertext limbs and 0 on the special limbs.  `rotated`: scratch [ndig][E][N]. */
+static void rotation_term(const orc_ctx *c, const u64 *c0, const u64 *c1, const u64 *lifted, int ndig, int ell, u64 g,
+                          const u64 *key, u64 *rotated, u64 *term) {
+    u64 N = c->N;
+    int E = ell + c->K;
+    if (g == 1) {
+        memset(term, 0, sizeof(u64) * 2 * E * N);
+        for (int i = 0; i < ell; i++) {
+            u64 qi = c->mod[i], Pmod = 1;
+            for (int k = 0; k < c->K; k++) Pmod = mulmod(Pmod, c->mod[c->L + k] % qi, qi);
+            for (u64 n = (u64)i * N; n < (u64)(i + 1) * N; n++) {
+                term[n] = mulmod(Pmod, c0[n], qi);
+                term[(u64)E * N + n] = mulmod(Pmod, c1[n], qi);
+            }
+        }
+        return;
+    }
+#pragma omp parallel for schedule(dynamic)
+    for (int idx = 0; idx < ndig * E; idx++) {
+        int pos = idx % E;
+        sigma_eval(c, ext_id(c, ell, pos), lifted + (u64)idx * N, rotated + (u64)idx * N, g);
+    }
+    inner_product(c, rotated, ndig, ell, key, term);
+#pragma omp parallel for schedule(dynamic)
+    for (int i = 0; i < ell; i++) {
+        u64 qi = c->mod[i], Pmod = 1;
+        for (int k = 0; k < c->K; k++) Pmod = mulmod(Pmod, c->mod[c->L + k] % qi, qi);
+        u64 *s0 = (u64 *)malloc(sizeof(u64) * N);
+        sigma_eval(c, i, c0 + (u64)i * N, s0, g);
+        for (u64 n = 0; n < N; n++) term[(u64)i * N + n] = addmod(term[(u64)i * N + n], mulmod(Pmod, s0[n], qi), qi);
+        free(s0);
+    }
+}
+
+/* u (+)= sum_r pt_r * rotation_term(ct, g_r): the inner sum of a baby-step giant-step transform on the extended basis.
+ * pts[r] holds all L + K limbs in evaluation domain, like a key component; NULL = the constant 1. */
+static void rotate_mac_sum(const orc_ctx *c, const u64 *c0, const u64 *c1, int ell, const uint32_t *galois,
+                           const u64 *const *rot_keys, const u64 *const *pts, int n_rot, u64 *lifted, u64 *rotated, u64 *term,
+                           u64 *u) {
+    u64 N = c->N;
+    int E = ell + c->K;
+    int ndig = mod_up(c, c1, ell, lifted);
+    for (int r = 0; r < n_rot; r++) {
+        rotation_term(c, c0, c1, lifted, ndig, ell, galois[r], rot_keys[r], rotated, term);
+#pragma omp parallel for schedule(dynamic)
+        for (int idx = 0; idx < 2 * E; idx++) {
+            int pos = idx % E, m = ext_id(c, ell, pos);
+            u64 mod = c->mod[m];
+            const u64 *pt = pts[r] ? pts[r] + (u64)m * N : NULL;
+            u64 *t = term + (u64)idx * N, *ui = u + (u64)idx * N;
+            for (u64 n = 0; n < N; n++) ui[n] = addmod(ui[n], pt ? mulmod(pt[n], t[n], mod) : t[n], mod);
+        }
+    }
+}
+
+/* Double-hoisted rotate-multiply-accumulate: out = mod_down(sum_r pt_r * rotation_term(ct, g_r)). */
 void orc_rotate_mac_hoisted(const orc_ctx *c, const u64 *ct, int ell, const uint32_t *galois,
                             const u64 *const *rot_keys, const u64 *const *pts, int n_rot, u64 *out, int batch) {
     u64 N = c->N;
@@ -349,44 +404,46 @@ void orc_rotate_mac_hoisted(const orc_ctx *c, const u64 *ct, int ell, const uint
     int ndig_max = (ell + c->alpha - 1) / c->alpha;
     u64 *lifted = (u64 *)malloc(sizeof(u64) * ndig_max * E * N);
     u64 *rotated = (u64 *)malloc(sizeof(u64) * ndig_max * E * N);
-    u64 *acc = (u64 *)malloc(sizeof(u64) * 2 * E * N);
+    u64 *term = (u64 *)malloc(sizeof(u64) * 2 * E * N);
     u64 *u = (u64 *)malloc(sizeof(u64) * 2 * E * N);
-    u64 *s0 = (u64 *)malloc(sizeof(u64) * ell * N);
     for (int b = 0; b < batch; b++) {
         const u64 *c0 = ct + (u64)b * 2 * ell * N, *c1 = c0 + (u64)ell * N;
-        int ndig = mod_up(c, c1, ell, lifted);
         memset(u, 0, sizeof(u64) * 2 * E * N);
-        for (int r = 0; r < n_rot; r++) {
-            u64 g = galois[r];
-#pragma omp parallel for schedule(dynamic)
-            for (int idx = 0; idx < ndig * E; idx++) {
-                int pos = idx % E;
-                sigma_eval(c, ext_id(c, ell, pos), lifted + (u64)idx * N, rotated + (u64)idx * N, g);
-            }
-            inner_product(c, rotated, ndig, ell, rot_keys[r], acc);
-#pragma omp parallel for schedule(dynamic)
-            for (int pos = 0; pos < E; pos++) {
-                int m = ext_id(c, ell, pos);
-                u64 mod = c->mod[m];
-                const u64 *pt = pts[r] + (u64)m * N;
-                u64 *a0 = acc + (u64)pos * N, *a1 = acc + (u64)(E + pos) * N;
-                u64 *u0 = u + (u64)pos * N, *u1 = u + (u64)(E + pos) * N;
-                if (pos < ell) {
-                    u64 Pmod = 1;
-                    for (int k = 0; k < c->K; k++) Pmod = mulmod(Pmod, c->mod[c->L + k] % mod, mod);
-                    sigma_eval(c, m, c0 + (u64)pos * N, s0 + (u64)pos * N, g);
-                    for (u64 n = 0; n < N; n++) a0[n] = addmod(a0[n], mulmod(Pmod, s0[(u64)pos * N + n], mod), mod);
-                }
-                for (u64 n = 0; n < N; n++) {
-                    u0[n] = addmod(u0[n], mulmod(pt[n], a0[n], mod), mod);
-                    u1[n] = addmod(u1[n], mulmod(pt[n], a1[n], mod), mod);
-                }
-            }
-        }
+        rotate_mac_sum(c, c0, c1, ell, galois, rot_keys, pts, n_rot, lifted, rotated, term, u);
         u64 *o = out + (u64)b * 2 * ell * N;
         for (int comp = 0; comp < 2; comp++) mod_down(c, u + (u64)comp * E * N, ell, o + (u64)comp * ell * N);
     }
-    free(lifted); free(rotated); free(acc); free(u); free(s0);
+    free(lifted); free(rotated); free(term); free(u);
+}
+
+/* Baby-step giant-step linear transform, double-hoisted at both levels:
+ * out = mod_down(sum_g rotation_term(v_g, G_g)),  v_g = mod_down(sum_b pts[g * n1 + b] * rotation_term(ct, B_b)). */
+void orc_bsgs_linear_transform(const orc_ctx *c, const u64 *ct, int ell, const uint32_t *baby_galois,
+                               const u64 *const *baby_keys, int n1, const uint32_t *giant_galois,
+                               const u64 *const *giant_keys, int n2, const u64 *const *pts, u64 *out, int batch) {
+    u64 N = c->N;
+    int E = ell + c->K;
+    int ndig_max = (ell + c->alpha - 1) / c->alpha;
+    u64 *lifted = (u64 *)malloc(sizeof(u64) * ndig_max * E * N);
+    u64 *rotated = (u64 *)malloc(sizeof(u64) * ndig_max * E * N);
+    u64 *term = (u64 *)malloc(sizeof(u64) * 2 * E * N);
+    u64 *u = (u64 *)malloc(sizeof(u64) * 2 * E * N);
+    u64 *uo = (u64 *)malloc(sizeof(u64) * 2 * E * N);
+    u64 *v = (u64 *)malloc(sizeof(u64) * 2 * ell * N);
+    for (int b = 0; b < batch; b++) {
+        const u64 *c0 = ct + (u64)b * 2 * ell * N, *c1 = c0 + (u64)ell * N;
+        memset(uo, 0, sizeof(u64) * 2 * E * N);
+        for (int g = 0; g < n2; g++) {
+            memset(u, 0, sizeof(u64) * 2 * E * N);
+            rotate_mac_sum(c, c0, c1, ell, baby_galois, baby_keys, pts + (u64)g * n1, n1, lifted, rotated, term, u);
+            for (int comp = 0; comp < 2; comp++) mod_down(c, u + (u64)comp * E * N, ell, v + (u64)comp * ell * N);
+            const u64 *one_pt = NULL;
+            rotate_mac_sum(c, v, v + (u64)ell * N, ell, giant_galois + g, giant_keys + g, &one_pt, 1, lifted, rotated, term, uo);
+        }
+        u64 *o = out + (u64)b * 2 * ell * N;
+        for (int comp = 0; comp < 2; comp++) mod_down(c, uo + (u64)comp * E * N, ell, o + (u64)comp * ell * N);
+    }
+    free(lifted); free(rotated); free(term); free(u); free(uo); free(v);
 }
 
 static void rescale_poly(const orc_ctx *c, const u64 *poly, int ell, u64 *out) {

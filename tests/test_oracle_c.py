@@ -108,6 +108,29 @@ def test_c_rotate_mac_matches_python(c_oracle_lib, logN, L, K, dnum, ell):
         assert got[b, 0].tolist() == o0 and got[b, 1].tolist() == o1
 
 
+@pytest.mark.parametrize("logN,L,K,dnum,ell", [(5, 4, 2, 2, 4), (6, 6, 2, 3, 5)])
+def test_c_bsgs_matches_python(c_oracle_lib, logN, L, K, dnum, ell):
+    pr, co = _setup(c_oracle_lib, logN, L, K, dnum)
+    rng = random.Random(8)
+    gal = ks_inputs.galois_elements(logN, 3)
+    baby, giant = [1, gal[0], gal[1]], [1, gal[2]]
+    bkeys = [None] + [_rand_key(rng, pr) for _ in baby[1:]]
+    gkeys = [None] + [_rand_key(rng, pr) for _ in giant[1:]]
+    pts = [[_rand(rng, pr, range(L + K)) for _ in baby] for _ in giant]
+    pts[1][0] = None                                             # a unit plaintext
+    cts = [(_rand(rng, pr, range(ell)), _rand(rng, pr, range(ell))) for _ in range(2)]
+    npk = lambda k: None if k is None else _np(k)
+    got = co.bsgs_linear_transform(_np([[c0, c1] for c0, c1 in cts]), baby, [npk(k) for k in bkeys], giant, [npk(k) for k in gkeys],
+                                   [[npk(w) for w in row] for row in pts], ell)
+    for b, ct in enumerate(cts):
+        o0, o1 = R.bsgs_linear_transform(pr, ct, baby, bkeys, giant, gkeys, pts, ell)
+        assert got[b, 0].tolist() == o0 and got[b, 1].tolist() == o1
+    # the identity element and the unit plaintext in the single-level entry point
+    got = co.rotate_mac_hoisted(_np([list(cts[0])]), baby, [npk(k) for k in bkeys], [npk(w) for w in pts[1]], ell)[0]
+    o0, o1 = R.rotate_mac_hoisted(pr, cts[0], baby, bkeys, pts[1], ell)
+    assert got[0].tolist() == o0 and got[1].tolist() == o1
+
+
 @pytest.mark.parametrize("logN,L,K,dnum", [(5, 4, 2, 2), (7, 35, 12, 3)])
 def test_c_hmult_matches_python(c_oracle_lib, logN, L, K, dnum):
     pr, co = _setup(c_oracle_lib, logN, L, K, dnum)

@@ -338,6 +338,55 @@ def test_rotate_mac_decrypts_to_sum_of_plaintext_times_rotations(ell):
     assert max(abs(x - y) for x, y in zip(got, want)) <= bound
 
 
+def test_bsgs_special_cases_reduce_to_the_single_level_operations():
+    """One identity giant step: the outer level adds P v and divides by P again, exactly v.  One identity baby step with
+    pt = 1 and one giant step G: a plain hoisted rotation by G."""
+    pr = _small_params(5, 4, 2, 2)
+    rng = random.Random(33)
+    ids, all_ids = list(range(pr.L)), list(range(pr.L + pr.K))
+    ct = (_uniform_poly(rng, pr, ids), _uniform_poly(rng, pr, ids))
+    mk = lambda: [[_uniform_poly(rng, pr, all_ids) for _ in range(2)] for _ in range(len(pr.digits(pr.L)))]
+    keys = [None, mk(), mk()]
+    galois = [1, 5, 25]
+    pts = [_uniform_poly(rng, pr, all_ids) for _ in galois]
+    assert R.bsgs_linear_transform(pr, ct, galois, keys, [1], [None], [pts]) == R.rotate_mac_hoisted(pr, ct, galois, keys, pts)
+    gk = mk()
+    assert R.bsgs_linear_transform(pr, ct, [1], [None], [125 % (2 * pr.N)], [gk], [[None]]) == \
+        R.rotate_hoisted(pr, ct, [125 % (2 * pr.N)], [gk])[0]
+
+
+def test_bsgs_decrypts_to_the_double_sum():
+    """phase(out) = sum_g sigma_{G_g}( sum_b pt_{g,b} sigma_{B_b}(message) ) up to key-switch noise."""
+    pr = _small_params(5, 4, 2, 2)
+    rng = random.Random(34)
+    ell = pr.L
+    ids, all_ids = list(range(ell)), list(range(pr.L + pr.K))
+    s = ks_inputs.ternary_secret(4, pr.N)
+    s_eval = R.to_eval(pr, s, all_ids)
+    baby, giant = [1, 5, 25], [1, 125 % (2 * pr.N)]
+    key_for = lambda seed, g: None if g == 1 else _keys(pr, seed, R.automorphism_signed(s, g), s)
+    bkeys = [key_for(60 + i, g) for i, g in enumerate(baby)]
+    gkeys = [key_for(70 + i, g) for i, g in enumerate(giant)]
+    w_signed = [[[rng.choice([-2, -1, 0, 0, 1, 2]) for _ in range(pr.N)] for _ in baby] for _ in giant]
+    pts = [[R.to_eval(pr, w, all_ids) for w in row] for row in w_signed]
+    msg = [rng.randrange(-10**12, 10**12) for _ in range(pr.N)]
+    a = _uniform_poly(rng, pr, ids)
+    mu = R.to_eval(pr, msg, ids)
+    b = [[(mm - x * sv) % pr.q[i] for mm, x, sv in zip(mu[i], a[i], s_eval[i])] for i in ids]
+    o0, o1 = R.bsgs_linear_transform(pr, (b, a), baby, bkeys, giant, gkeys, pts, ell)
+    got = R.phase(pr, o0, o1, s_eval[:ell], ell)
+    want = [0] * pr.N
+    for G, row in zip(giant, w_signed):
+        inner = [0] * pr.N
+        for Bb, w in zip(baby, row):
+            inner = [x + y for x, y in zip(inner, R.poly_mul_signed(w, R.automorphism_signed(msg, Bb)))]
+        want = [x + y for x, y in zip(want, R.automorphism_signed(inner, G))]
+    l1 = max(sum(sum(abs(x) for x in w) for w in row) for row in w_signed)
+    ks_noise = pr.N * 19 * pr.L + pr.K * (pr.N + 1)
+    bound = len(giant) * (l1 * ks_noise + ks_noise)      # inner sums' noise passes through the outer rotations, which add their own
+    assert max(abs(x - y) for x, y in zip(got, want)) <= bound
+
+
 def test_rescale_is_rounded_division():
     pr = _small_params(5, 4, 2, 2)
     rng = random.Random(11)
