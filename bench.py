@@ -293,6 +293,35 @@ def bench_rotate_mac(args, torch, K, ks_inputs):
             "roofline": _dominant_roofline(kernels), "kernels": kernels}
 
 
+def bench_bsgs(args, torch, K, ks_inputs):
+    """Baby-step giant-step linear transform with configuration 3's parameters: 64 ciphertexts, 16 x 16 = 256 plaintext
+    diagonals per ciphertext (rotation 0 of either level is the identity and needs no key)."""
+    cfg = ks_inputs.CONFIGS[3]
+    q, p = ks_inputs.moduli(cfg)
+    logN, L, B, dnum = cfg["logN"], cfg["L"], cfg["batch"], cfg["dnum"]
+    n1 = n2 = 16
+    N = 1 << logN
+    ctx = K.Context(logN, q, p, dnum)
+    gal = ks_inputs.galois_elements(logN, n1 + n2)
+    baby, giant = [1] + gal[:n1 - 1], [1] + gal[n1:n1 + n2 - 1]
+    key = lambda tid, g: None if g == 1 else ks_inputs.uniform_residues(cfg["seed"], tid, (dnum, 2), q + p, N, device="cuda")
+    bkeys = [key(10 + i, g) for i, g in enumerate(baby)]
+    gkeys = [key(40 + i, g) for i, g in enumerate(giant)]
+    pts = [[ks_inputs.uniform_residues(cfg["seed"], 100 + g * n1 + b, (), q + p, N, device="cuda") for b in range(n1)] for g in range(n2)]
+    ct = ks_inputs.uniform_residues(cfg["seed"], 1, (B, 2), q, N, device="cuda")
+    out = torch.empty((B, 2, L, N), dtype=torch.int64, device="cuda")
+    ws = torch.empty(K.ks_workspace_bytes(ctx, K.KS_OP_BSGS, L, B) // 8, dtype=torch.int64, device="cuda")
+    fn = lambda: K.ks_bsgs_linear_transform(ctx, ct, L, baby, bkeys, giant, gkeys, pts, out, ws)
+    reps = max(2, args.steps // 100)
+    ms = _time_calls(torch, fn, reps)
+    kernels = _kernel_breakdown(K, torch, fn, B * n1 * n2)
+    return {"metric": "bsgs_diagonal_terms_per_sec", "value": round(B * n1 * n2 / (ms * 1e-3), 1), "unit": "rotated-and-multiplied term/s",
+            "n_gpus": 1, "steps": reps, "warmup": 1, "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "f64", "data": "synthetic", "transforms_per_sec": round(B / (ms * 1e-3), 1),
+            "config": {"workload": "bsgs linear transform N=2^16 L=24 K=8 dnum=3, 64 ciphertexts x (16 baby x 16 giant) diagonals per call"},
+            "roofline": _dominant_roofline(kernels), "kernels": kernels}
+
+
 def bench_hmult(args, torch, K, ks_inputs, merged=False):
     """Configuration 5: 256 ciphertext pairs per call: tensor product, relinearisation, rescale (merged: the division
     by P and the rescale done as one division by P q_last)."""
@@ -378,7 +407,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--sets", type=int, default=6, help="disjoint buffer sets rotated through (cold-cache figure)")
     ap.add_argument("--no-batched", action="store_true", help="skip the batched key-switch measurement (counter runs)")
-    ap.add_argument("--workload", default="keyswitch", choices=["keyswitch", "ntt", "rotate", "rotate_mac", "hmult", "hmult_merged", "copy"])
+    ap.add_argument("--workload", default="keyswitch", choices=["keyswitch", "ntt", "rotate", "rotate_mac", "bsgs", "hmult", "hmult_merged", "copy"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -401,6 +430,8 @@ def main():
         result = bench_rotate(args, torch, K, ks_inputs)
     elif args.workload == "rotate_mac":
         result = bench_rotate_mac(args, torch, K, ks_inputs)
+    elif args.workload == "bsgs":
+        result = bench_bsgs(args, torch, K, ks_inputs)
     elif args.workload in ("hmult", "hmult_merged"):
         result = bench_hmult(args, torch, K, ks_inputs, merged=args.workload == "hmult_merged")
     else:

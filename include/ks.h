@@ -50,7 +50,8 @@ enum {
 enum { /* operations for ks_workspace_bytes */
     KS_OP_KEYSWITCH = 1,
     KS_OP_ROTATE_HOISTED = 2,
-    KS_OP_HMULT_RELIN_RESCALE = 3
+    KS_OP_HMULT_RELIN_RESCALE = 3,
+    KS_OP_BSGS = 4
 };
 
 /* Build the tables for one parameter set on GPU `device`.
@@ -126,10 +127,29 @@ int ks_rotate_hoisted(const ks_ctx* ctx, const uint64_t* ct, uint32_t ell, const
  *   galois   : host [n_rot], odd, 0 < g < 2N.       rot_keys : host [n_rot] device pointers, laid out like evk.
  *   pts      : host [n_rot] device pointers, each [L+K][N]: the plaintext reduced modulo every q_i and p_k,
  *              evaluation domain (only limbs i < ell and the special ones are read).
- *   out      : device [batch][2][ell][N].           Workspace: KS_OP_ROTATE_HOISTED.  Errors as ks_rotate_hoisted. */
+ *   out      : device [batch][2][ell][N].           Workspace: KS_OP_ROTATE_HOISTED.  Errors as ks_rotate_hoisted.
+ * A Galois element 1 stands for the unrotated ciphertext: its term is P (c0, c1), no key is read (rot_keys[r] may be
+ * NULL) and no key-switching noise is added -- unlike ks_rotate_hoisted, where g = 1 is an ordinary key-switch.  A NULL
+ * plaintext pointer is the constant 1. */
 int ks_rotate_mac_hoisted(const ks_ctx* ctx, const uint64_t* ct, uint32_t ell, const uint32_t* galois,
                           const uint64_t* const* rot_keys, const uint64_t* const* pts, uint32_t n_rot, uint64_t* out,
                           uint32_t batch, void* ws, size_t ws_bytes, void* stream);
+
+/* Baby-step giant-step linear transform (DSL, matrix multiplication example), double-hoisted at both levels:
+ *     out = sum_g rot_{G_g}( sum_b pts[g * n1 + b] * rot_{B_b}(ct) ).
+ * Inner sums as ks_rotate_mac_hoisted with the n1 baby-step elements B_b (one decompose-and-raise of c1 serves every
+ * baby step of every giant step; one division by P per giant step).  Outer sum: each inner result is raised again,
+ * rotated by its giant-step element G_g on the extended basis and added to a running sum that is divided by P once.
+ * n1 n2 + n2 key-switch inner products, but only n2 + 1 divisions by P and n2 + 1 decompose-and-raise steps.
+ *   baby_galois [n1], giant_galois [n2] : host, odd, < 2N; 1 = no rotation (its key pointer may be NULL).
+ *   baby_keys [n1], giant_keys [n2]     : host arrays of device pointers, laid out like evk.
+ *   pts [n2 * n1]                       : host array of device pointers, each [L+K][N] as in ks_rotate_mac_hoisted, or
+ *                                         NULL for the constant 1.
+ *   ct, out : device [batch][2][ell][N].   Workspace: KS_OP_BSGS (n_rot ignored). */
+int ks_bsgs_linear_transform(const ks_ctx* ctx, const uint64_t* ct, uint32_t ell, const uint32_t* baby_galois,
+                             const uint64_t* const* baby_keys, uint32_t n1, const uint32_t* giant_galois,
+                             const uint64_t* const* giant_keys, uint32_t n2, const uint64_t* const* pts, uint64_t* out,
+                             uint32_t batch, void* ws, size_t ws_bytes, void* stream);
 
 /* Homomorphic multiplication with relinearisation and rescale: tensor product
  * (d0, d1, d2) = (b1 b2, a1 b2 + a2 b1, a1 a2), key-switch d2 with rlk, add to (d0, d1), then drop limb

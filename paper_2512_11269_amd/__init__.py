@@ -1,6 +1,7 @@
 """MI355X-native CKKS hybrid key-switching: thin Python binding over the C-ABI library."""
 
 from .binding import (  # noqa: F401
+    KS_OP_BSGS,
     KS_OP_HMULT_RELIN_RESCALE,
     KS_OP_KEYSWITCH,
     KS_OP_ROTATE_HOISTED,
@@ -9,6 +10,7 @@ from .binding import (  # noqa: F401
     bconv,
     hmult_relin_rescale,
     hmult_relin_rescale_merged,
+    ks_bsgs_linear_transform,
     ks_keyswitch,
     ks_profile_enable,
     ks_profile_report,

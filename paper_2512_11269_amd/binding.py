@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libks_mi355x.so")
 _lib = None
 
-KS_OP_KEYSWITCH, KS_OP_ROTATE_HOISTED, KS_OP_HMULT_RELIN_RESCALE = 1, 2, 3
+KS_OP_KEYSWITCH, KS_OP_ROTATE_HOISTED, KS_OP_HMULT_RELIN_RESCALE, KS_OP_BSGS = 1, 2, 3, 4
 
 _u64p = ctypes.POINTER(ctypes.c_uint64)
 _u32p = ctypes.POINTER(ctypes.c_uint32)
@@ -57,6 +57,9 @@ def load_library():
                                       ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
     lib.ks_rotate_mac_hoisted.argtypes = [_vp, _vp, ctypes.c_uint32, _u32p, ctypes.POINTER(_vp), ctypes.POINTER(_vp),
                                           ctypes.c_uint32, _vp, ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
+    lib.ks_bsgs_linear_transform.argtypes = [_vp, _vp, ctypes.c_uint32, _u32p, ctypes.POINTER(_vp), ctypes.c_uint32, _u32p,
+                                             ctypes.POINTER(_vp), ctypes.c_uint32, ctypes.POINTER(_vp), _vp, ctypes.c_uint32, _vp,
+                                             ctypes.c_size_t, _vp]
     lib.hmult_relin_rescale.argtypes = [_vp, _vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
     lib.hmult_relin_rescale_merged.argtypes = [_vp, _vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
     lib.ks_profile_enable.argtypes = [ctypes.c_int]
@@ -182,9 +185,24 @@ def hmult_relin_rescale_merged(ctx: Context, cta: torch.Tensor, ctb: torch.Tenso
                                                      batch, _dev_ptr(ws), ws.numel() * 8, _stream()), "hmult_relin_rescale_merged")
 
 
+def _ptr_array(tensors):
+    """Host array of device pointers; None entries become NULL."""
+    return (_vp * len(tensors))(*[None if t is None else _dev_ptr(t) for t in tensors])
+
+
 def ks_rotate_mac_hoisted(ctx: Context, ct: torch.Tensor, ell: int, galois, rot_keys, pts, out: torch.Tensor, ws: torch.Tensor) -> None:
     batch = ct.numel() // (2 * ell * ctx.N)
-    kp = (_vp * len(rot_keys))(*[_dev_ptr(k) for k in rot_keys])
-    pp = (_vp * len(pts))(*[_dev_ptr(w) for w in pts])
-    _check(load_library().ks_rotate_mac_hoisted(ctx.handle, _dev_ptr(ct), ell, _u32_array(galois), kp, pp, len(rot_keys),
-                                                _dev_ptr(out), batch, _dev_ptr(ws), ws.numel() * 8, _stream()), "ks_rotate_mac_hoisted")
+    _check(load_library().ks_rotate_mac_hoisted(ctx.handle, _dev_ptr(ct), ell, _u32_array(galois), _ptr_array(rot_keys), _ptr_array(pts),
+                                                len(rot_keys), _dev_ptr(out), batch, _dev_ptr(ws), ws.numel() * 8, _stream()),
+           "ks_rotate_mac_hoisted")
+
+
+def ks_bsgs_linear_transform(ctx: Context, ct: torch.Tensor, ell: int, baby_galois, baby_keys, giant_galois, giant_keys, pts,
+                             out: torch.Tensor, ws: torch.Tensor) -> None:
+    """pts: n2 rows of n1 plaintext tensors (or None)."""
+    batch = ct.numel() // (2 * ell * ctx.N)
+    flat = [w for row in pts for w in row]
+    _check(load_library().ks_bsgs_linear_transform(ctx.handle, _dev_ptr(ct), ell, _u32_array(baby_galois), _ptr_array(baby_keys),
+                                                   len(baby_keys), _u32_array(giant_galois), _ptr_array(giant_keys), len(giant_keys),
+                                                   _ptr_array(flat), _dev_ptr(out), batch, _dev_ptr(ws), ws.numel() * 8, _stream()),
+           "ks_bsgs_linear_transform")

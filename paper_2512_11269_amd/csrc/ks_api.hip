@@ -93,6 +93,12 @@ extern "C" size_t ks_workspace_bytes(const ks_ctx* c, int op, uint32_t ell, uint
             // accumulators and converted limbs for a whole group of rotations
             words += (uint64_t)(std::min(n_rot, kRotGroup) - 1) * bc * (2 * lv.E + 2 * ell) * N;
             break;
+        case KS_OP_BSGS: {
+            // second set of raised digits and accumulators (outer level), inner result [bc][2][ell]
+            const KsWorkspace w = ks_ws_words(c, lv, bc);
+            words += w.lifted + w.acc + (uint64_t)bc * 2 * ell * N;
+            break;
+        }
         case KS_OP_HMULT_RELIN_RESCALE:
             if (ell < 2) return 0;
             // tensor product [bc][3][ell], sum [bc][2][ell], last limb [2 bc], spread [2 bc][ell-1]
@@ -271,16 +277,40 @@ extern "C" int ks_rotate_hoisted(const ks_ctx* c, const uint64_t* ct, uint32_t e
     return finish("ks_rotate_hoisted");
 }
 
+// Galois elements, keys and plaintexts of a rotate-multiply-accumulate: g = 1 needs no key, a null plaintext is 1.
+static int check_mac_rotations(const ks_ctx* c, const uint32_t* galois, const uint64_t* const* keys, const uint64_t* const* pts,
+                               uint32_t n) {
+    if (!galois || !keys || n == 0) return KS_EINVAL;
+    for (uint32_t r = 0; r < n; ++r) {
+        if ((galois[r] & 1u) == 0 || galois[r] >= 2u * c->N) return KS_EINVAL;
+        if (galois[r] != 1 && (!keys[r] || !aligned16(keys[r]))) return KS_EINVAL;
+        if (pts && pts[r] && !aligned16(pts[r])) return KS_EINVAL;
+    }
+    return KS_OK;
+}
+
+// u (+)= sum_r pt_r * rot_{g_r}(ct) for all n rotations, in launches of kMacRotations
+static void rotate_mac_all(const ks_ctx* c, const Level& lv, const uint64_t* ct, uint64_t ct_bs, const uint64_t* lifted,
+                           const uint32_t* galois, const uint64_t* const* keys, const uint64_t* const* pts, uint32_t n, uint64_t* u,
+                           uint32_t bc, bool accumulate, hipStream_t s) {
+    for (uint32_t r0 = 0; r0 < n; r0 += kMacRotations) {
+        MacRotations rot;
+        rot.n = std::min<uint32_t>(n - r0, kMacRotations);
+        for (uint32_t r = 0; r < rot.n; ++r) {
+            rot.galois[r] = galois[r0 + r];
+            rot.key[r] = keys[r0 + r];
+            rot.pt[r] = pts ? pts[r0 + r] : nullptr;
+        }
+        launch_rotate_mac(c, lv, ct, ct_bs, lifted, rot, u, bc, accumulate || r0 != 0, s);
+    }
+}
+
 extern "C" int ks_rotate_mac_hoisted(const ks_ctx* c, const uint64_t* ct, uint32_t ell, const uint32_t* galois,
                                      const uint64_t* const* rot_keys, const uint64_t* const* pts, uint32_t n_rot, uint64_t* out,
                                      uint32_t batch, void* ws, size_t ws_bytes, void* stream) {
     int rc = check_pipeline_args(c, ell, 1, ct, ct, out, ws);
     if (rc != KS_OK) return rc;
-    if (!galois || !rot_keys || !pts || n_rot == 0) return KS_EINVAL;
-    for (uint32_t r = 0; r < n_rot; ++r) {
-        if ((galois[r] & 1u) == 0 || galois[r] >= 2u * c->N) return KS_EINVAL;
-        if (!rot_keys[r] || !aligned16(rot_keys[r]) || !pts[r] || !aligned16(pts[r])) return KS_EINVAL;
-    }
+    if (!pts || (rc = check_mac_rotations(c, galois, rot_keys, pts, n_rot)) != KS_OK) return KS_EINVAL;
     if (batch == 0) return KS_OK;
     if (ws_bytes < ks_workspace_bytes(c, KS_OP_ROTATE_HOISTED, ell, batch, n_rot)) return KS_EWORKSPACE;
     const Level& lv = c->levels[ell - 1];
@@ -295,19 +325,47 @@ extern "C" int ks_rotate_mac_hoisted(const ks_ctx* c, const uint64_t* ct, uint32
         uint64_t* conv = acc + w.acc;
         const uint64_t* c0 = ct + (uint64_t)b0 * ct_bs;
         mod_up(c, lv, c0 + (uint64_t)ell * N, ct_bs, coeff, lifted, bc, true, s);   // finished once, shared by every rotation
-        for (uint32_t r0 = 0; r0 < n_rot; r0 += kMacRotations) {
-            MacRotations rot;
-            rot.n = std::min<uint32_t>(n_rot - r0, kMacRotations);
-            for (uint32_t r = 0; r < rot.n; ++r) {
-                rot.galois[r] = galois[r0 + r];
-                rot.key[r] = rot_keys[r0 + r];
-                rot.pt[r] = pts[r0 + r];
-            }
-            launch_rotate_mac(c, lv, c0, ct_bs, lifted, rot, acc, bc, r0 != 0, s);
-        }
+        rotate_mac_all(c, lv, c0, ct_bs, lifted, galois, rot_keys, pts, n_rot, acc, bc, false, s);
         mod_down(c, lv, acc, conv, out + (uint64_t)b0 * ct_bs, ct_bs, nullptr, 0, 0, 1, bc, false, s);
     }
     return finish("ks_rotate_mac_hoisted");
+}
+
+extern "C" int ks_bsgs_linear_transform(const ks_ctx* c, const uint64_t* ct, uint32_t ell, const uint32_t* baby_galois,
+                                        const uint64_t* const* baby_keys, uint32_t n1, const uint32_t* giant_galois,
+                                        const uint64_t* const* giant_keys, uint32_t n2, const uint64_t* const* pts, uint64_t* out,
+                                        uint32_t batch, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_pipeline_args(c, ell, 1, ct, ct, out, ws);
+    if (rc != KS_OK) return rc;
+    if (!pts || check_mac_rotations(c, giant_galois, giant_keys, nullptr, n2) != KS_OK) return KS_EINVAL;
+    for (uint32_t g = 0; g < n2; ++g)
+        if (check_mac_rotations(c, baby_galois, baby_keys, pts + (size_t)g * n1, n1) != KS_OK) return KS_EINVAL;
+    if (batch == 0) return KS_OK;
+    if (ws_bytes < ks_workspace_bytes(c, KS_OP_BSGS, ell, batch, 0)) return KS_EWORKSPACE;
+    const Level& lv = c->levels[ell - 1];
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint64_t N = c->N, ct_bs = 2ull * ell * N;
+    for (uint32_t b0 = 0; b0 < batch; b0 += kChunk) {
+        const uint32_t bc = std::min(batch - b0, kChunk);
+        const KsWorkspace w = ks_ws_words(c, lv, bc);
+        uint64_t* coeff = static_cast<uint64_t*>(ws);
+        uint64_t* lifted = coeff + w.coeff;          // raised digits of c1, shared by every baby step of every giant step
+        uint64_t* acc = lifted + w.lifted;           // inner sum of the current giant step
+        uint64_t* conv = acc + w.acc;
+        uint64_t* lifted_v = conv + w.conv;          // raised digits of the current inner result
+        uint64_t* acc_outer = lifted_v + w.lifted;   // outer sum over the giant steps
+        uint64_t* v = acc_outer + w.acc;             // [bc][2][ell][N] inner result of the current giant step
+        const uint64_t* c0 = ct + (uint64_t)b0 * ct_bs;
+        mod_up(c, lv, c0 + (uint64_t)ell * N, ct_bs, coeff, lifted, bc, true, s);
+        for (uint32_t g = 0; g < n2; ++g) {
+            rotate_mac_all(c, lv, c0, ct_bs, lifted, baby_galois, baby_keys, pts + (size_t)g * n1, n1, acc, bc, false, s);
+            mod_down(c, lv, acc, conv, v, ct_bs, nullptr, 0, 0, 1, bc, false, s);
+            if (giant_galois[g] != 1) mod_up(c, lv, v + (uint64_t)ell * N, ct_bs, coeff, lifted_v, bc, true, s);
+            rotate_mac_all(c, lv, v, ct_bs, lifted_v, giant_galois + g, giant_keys + g, nullptr, 1, acc_outer, bc, g != 0, s);
+        }
+        mod_down(c, lv, acc_outer, conv, out + (uint64_t)b0 * ct_bs, ct_bs, nullptr, 0, 0, 1, bc, false, s);
+    }
+    return finish("ks_bsgs_linear_transform");
 }
 
 // Division by P q_{ell-1} of acc + P addend in one conversion (ModDown merged with the rescale that would follow):

@@ -152,6 +152,7 @@ extern "C" int ks_ctx_destroy(ks_ctx* c) {
     (void)hipFree(c->d_ninv);
     (void)hipFree(c->d_Pinv);
     (void)hipFree(c->d_Pmod);
+    (void)hipFree(c->d_one);
     (void)hipFree(c->d_moddown_scale);
     (void)hipFree(c->d_tw_fwd);
     (void)hipFree(c->d_tw_inv);
@@ -226,6 +227,11 @@ extern "C" int ks_ctx_create(ks_ctx** out, uint32_t logN, uint32_t L, uint32_t K
         CK(hipMemcpy(c->d_ninv, hn.data(), sizeof(double) * M, hipMemcpyHostToDevice));
         CK(hipMemcpy(c->d_Pinv, hP.data(), sizeof(double) * L, hipMemcpyHostToDevice));
         CK(hipMalloc(&c->d_Pmod, sizeof(double) * L));
+        {
+            const uint64_t ones[2] = {1, 1};
+            CK(hipMalloc(&c->d_one, sizeof(ones)));
+            CK(hipMemcpy(c->d_one, ones, sizeof(ones), hipMemcpyHostToDevice));
+        }
         CK(hipMemcpy(c->d_Pmod, hPm.data(), sizeof(double) * L, hipMemcpyHostToDevice));
         if (K > 0) {
             std::vector<double> sc(K);

@@ -100,14 +100,16 @@ void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, u
 // deferred to the whole sum).  One thread owns one slot of one limb position for a group of ciphertexts and walks the
 // rotations: key slots and the plaintext slot of a rotation are read once per group, the raised digits and c0 come
 // through the sigma_g gather, and the two running sums stay in registers until every rotation of the launch is in.
-// Branch-free on purpose (digit count as a template parameter, a short last group recomputes its last ciphertext, special
-// limbs read a c0 limb they multiply by zero): every load of a rotation is then issued before the first product.
+// Branch-free within a rotation on purpose (digit count as a template parameter, a short last group recomputes its last
+// ciphertext, special limbs read a c0 limb they multiply by zero): every load of a rotation is then issued before the
+// first product.  Galois element 1 is the unrotated ciphertext (P (c0, c1), no key read).
 template <int NDIG>
 __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__ mods, const double* __restrict__ Pmod, DigitRanges dg,
                                                          uint32_t ell, uint32_t E, uint32_t L, uint32_t M, uint32_t logN,
                                                          const uint64_t* __restrict__ ct, uint64_t ct_bs,
                                                          const uint64_t* __restrict__ lifted, MacRotations rot,
-                                                         uint64_t* __restrict__ u, uint32_t batch, int accumulate) {
+                                                         const uint64_t* __restrict__ one, uint64_t* __restrict__ u, uint32_t batch,
+                                                         int accumulate) {
     const uint32_t N = 1u << logN;
     const uint32_t pos = blockIdx.y;
     const uint32_t mid = pos < ell ? pos : L + (pos - ell);
@@ -140,6 +142,25 @@ __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__
     }
 #pragma unroll 1
     for (uint32_t r = 0; r < rot.n; ++r) {
+        // the plaintext slot; a null plaintext is the constant 1, read (by every lane) from a one-word table so that the
+        // load stays unconditional
+        const uint64_t* wp = rot.pt[r] ? rot.pt[r] + (uint64_t)mid * N + n : one;
+        if (rot.galois[r] == 1) {  // uniform: the unrotated ciphertext, P (c0, c1), no key
+            uint64_t c0raw[kBatchGroup], c1raw[kBatchGroup];
+            const uint64_t wraw = *wp;
+#pragma unroll
+            for (int bi = 0; bi < kBatchGroup; ++bi) {
+                c0raw[bi] = c0p[bi][n];
+                c1raw[bi] = c0p[bi][(uint64_t)ell * N + n];
+            }
+            const double w = u64_to_f64(wraw);
+#pragma unroll
+            for (int bi = 0; bi < kBatchGroup; ++bi) {
+                u0[bi] += mulmod_lazy(mulmod_lazy(u64_to_f64(c0raw[bi]), pm, m), w, m);
+                u1[bi] += mulmod_lazy(mulmod_lazy(u64_to_f64(c1raw[bi]), pm, m), w, m);
+            }
+            continue;
+        }
         const uint32_t sn = galois_source_slot(n, rot.galois[r], logN);
         const uint64_t* key = rot.key[r] + (uint64_t)mid * N + n;
         uint64_t kraw[NDIG][2], xraw[kBatchGroup][NDIG], craw[kBatchGroup];
@@ -148,7 +169,7 @@ __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__
             kraw[j][0] = key[(uint64_t)(j * 2 + 0) * M * N];
             kraw[j][1] = key[(uint64_t)(j * 2 + 1) * M * N];
         }
-        const uint64_t wraw = rot.pt[r][(uint64_t)mid * N + n];
+        const uint64_t wraw = *wp;
 #pragma unroll
         for (int bi = 0; bi < kBatchGroup; ++bi) {
 #pragma unroll
@@ -196,7 +217,7 @@ void launch_rotate_mac(const ks_ctx* c, const Level& lv, const uint64_t* ct, uin
                  (double)rot.n * batch * lv.E * c->N * (7.0 * (2 * lv.ndig + 3)));
 #define KS_LAUNCH_MAC(ND)                                                                                                          \
     hipLaunchKernelGGL(rotate_mac_kernel<ND>, grid, block, 0, s, c->d_mod, c->d_Pmod, dg, lv.ell, lv.E, c->L, c->M, c->logN, ct, ct_bs, \
-                       lifted, rot, u, batch, accumulate ? 1 : 0)
+                       lifted, rot, c->d_one, u, batch, accumulate ? 1 : 0)
     switch (lv.ndig) {
         case 1: KS_LAUNCH_MAC(1); break;
         case 2: KS_LAUNCH_MAC(2); break;

@@ -76,6 +76,7 @@ struct ks_ctx {
     double* d_ninv = nullptr;             // [M]  N^-1 mod m
     double* d_Pinv = nullptr;             // [L]  P^-1 mod q_i
     double* d_Pmod = nullptr;             // [L]  P mod q_i
+    uint64_t* d_one = nullptr;            // [2]  the residue 1 (unit plaintext slot)
     double* d_moddown_scale = nullptr;    // [K]  N^-1 (P / p_k)^-1 mod p_k
     double* d_tw_fwd = nullptr;           // [M][N] psi^brv(k)
     double* d_tw_inv = nullptr;           // [M][N] psi^-brv(k)
@@ -179,6 +180,7 @@ void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, u
 
 // u[b][c][pos] (+)= sum_r pt_r[pos] * (sum_j sigma_r(src_j)[pos] key_r[j][c][pos] + [c = 0][pos < ell] P sigma_r(c0)[pos]);
 // ct: [b][2][ell][N] (c0, c1), lifted: finished raised digits of c1.  accumulate: add to what u already holds.
+// galois[r] == 1: the term is P (c0, c1) and key[r] is not read; pt[r] == nullptr: the constant 1.
 void launch_rotate_mac(const ks_ctx* c, const Level& lv, const uint64_t* ct, uint64_t ct_bs, const uint64_t* lifted,
                        const MacRotations& rot, uint64_t* u, uint32_t batch, bool accumulate, hipStream_t s);
 

@@ -104,3 +104,27 @@ def test_cfg3_rotate_mac_full_size():
         want = st.ref.rotate_mac_hoisted(host(ct[b])[None], galois, hk, hp, ell)
         assert_equal(out[b], want[0])
     assert _in_range(out[40].reshape(-1, ell, st.N), st.q)
+
+
+def test_cfg3_bsgs_full_size():
+    """Configuration 3's parameters through the two-level transform: 64 ciphertexts, 16 baby steps x 4 giant steps."""
+    cfg = ks_inputs.CONFIGS[3]
+    st = Setup(cfg["logN"], cfg["L"], cfg["K"], cfg["dnum"])
+    ell, B, seed, n1, n2 = cfg["L"], cfg["batch"], cfg["seed"], 16, 4
+    all_ids = list(range(ell + cfg["K"]))
+    gal = ks_inputs.galois_elements(cfg["logN"], n1 + n2)
+    baby, giant = [1] + gal[:n1 - 1], [1] + gal[n1:n1 + n2 - 1]
+    key = lambda tid, g: None if g == 1 else st.uniform(seed, tid, (cfg["dnum"], 2), all_ids)
+    bkeys = [key(10 + i, g) for i, g in enumerate(baby)]
+    gkeys = [key(40 + i, g) for i, g in enumerate(giant)]
+    pts = [[st.uniform(seed, 100 + g * n1 + b, (), all_ids) for b in range(n1)] for g in range(n2)]
+    ct = st.uniform(seed, 1, (B, 2), list(range(ell)))
+    out = torch.empty((B, 2, ell, st.N), dtype=torch.int64, device="cuda")
+    K.ks_bsgs_linear_transform(st.ctx, ct, ell, baby, bkeys, giant, gkeys, pts, out, workspace(st.ctx, K.KS_OP_BSGS, ell, B))
+    torch.cuda.synchronize()
+    h = lambda x: None if x is None else host(x)
+    hb, hg, hp = [h(k) for k in bkeys], [h(k) for k in gkeys], [[h(w) for w in row] for row in pts]
+    for b in (0, 33):
+        want = st.ref.bsgs_linear_transform(host(ct[b])[None], baby, hb, giant, hg, hp, ell)
+        assert_equal(out[b], want[0])
+    assert _in_range(out[63].reshape(-1, ell, st.N), st.q)

@@ -156,6 +156,47 @@ def test_rotate_mac_unit_plaintext_equals_rotate_hoisted(small):
     assert torch.equal(mac, rot[:, 0])
 
 
+def _bsgs_inputs(st, seed, ell, batch, n1, n2, with_identity=True):
+    gal = ks_inputs.galois_elements(st.logN, n1 + n2)
+    baby = ([1] if with_identity else []) + gal[:n1 - (1 if with_identity else 0)]
+    giant = ([1] if with_identity else []) + gal[n1:n1 + n2 - (1 if with_identity else 0)]
+    all_ids = list(range(st.L + st.K))
+    key = lambda tid, g: None if g == 1 else st.uniform(seed, tid, (st.ctx.dnum, 2), all_ids)
+    bkeys = [key(10 + i, g) for i, g in enumerate(baby)]
+    gkeys = [key(40 + i, g) for i, g in enumerate(giant)]
+    pts = [[st.uniform(seed, 100 + g * n1 + b, (), all_ids) for b in range(n1)] for g in range(n2)]
+    pts[-1][0] = None                                        # a unit plaintext
+    ct = st.uniform(seed, 1, (batch, 2), list(range(ell)))
+    return ct, baby, bkeys, giant, gkeys, pts
+
+
+def _hostify(x):
+    return None if x is None else host(x)
+
+
+@pytest.mark.parametrize("ell,batch,n1,n2", [(4, 2, 3, 2), (3, 17, 2, 3), (4, 1, 1, 1)])
+def test_bsgs_small(small, ell, batch, n1, n2):
+    ct, baby, bkeys, giant, gkeys, pts = _bsgs_inputs(small, 1009, ell, batch, n1, n2)
+    out = torch.empty((batch, 2, ell, small.N), dtype=torch.int64, device="cuda")
+    K.ks_bsgs_linear_transform(small.ctx, ct, ell, baby, bkeys, giant, gkeys, pts, out, workspace(small.ctx, K.KS_OP_BSGS, ell, batch))
+    want = small.ref.bsgs_linear_transform(host(ct), baby, [_hostify(k) for k in bkeys], giant, [_hostify(k) for k in gkeys],
+                                           [[_hostify(w) for w in row] for row in pts], ell)
+    assert_equal(out, want)
+    # the identity element and the unit plaintext through the single-level entry point
+    mac = torch.empty_like(out)
+    K.ks_rotate_mac_hoisted(small.ctx, ct, ell, baby, bkeys, pts[-1], mac, workspace(small.ctx, K.KS_OP_ROTATE_HOISTED, ell, batch, n1))
+    assert_equal(mac, small.ref.rotate_mac_hoisted(host(ct), baby, [_hostify(k) for k in bkeys], [_hostify(w) for w in pts[-1]], ell))
+
+
+def test_bsgs_bootstrap_shape(boot):
+    ct, baby, bkeys, giant, gkeys, pts = _bsgs_inputs(boot, 1009, 24, 2, 3, 2)
+    out = torch.empty((2, 2, 24, boot.N), dtype=torch.int64, device="cuda")
+    K.ks_bsgs_linear_transform(boot.ctx, ct, 24, baby, bkeys, giant, gkeys, pts, out, workspace(boot.ctx, K.KS_OP_BSGS, 24, 2))
+    want = boot.ref.bsgs_linear_transform(host(ct), baby, [_hostify(k) for k in bkeys], giant, [_hostify(k) for k in gkeys],
+                                          [[_hostify(w) for w in row] for row in pts], 24)
+    assert_equal(out, want)
+
+
 def test_rotate_by_identity_equals_keyswitch_plus_c0(small):
     ell = 4
     ct = small.uniform(5, 1, (1, 2), list(range(ell)))
