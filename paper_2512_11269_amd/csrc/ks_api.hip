@@ -1,8 +1,6 @@
 // The extern "C" entry points: argument checks, workspace carving and the kernel chains.
 #include <algorithm>
 
-#include <stdlib.h>
-
 #include "ks_internal.hpp"
 
 using namespace ks;
@@ -10,7 +8,7 @@ using namespace ks;
 namespace {
 
 constexpr uint32_t kChunk = 16;  // ciphertexts processed per pass of a pipeline; bounds the workspace
-constexpr uint32_t kRotGroup = 4;  // hoisted rotations whose accumulators are formed by one launch (more gain nothing); bounds the workspace
+constexpr uint32_t kRotGroup = 4;  // hoisted rotations per gather launch (larger groups measured no faster); bounds the workspace
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
