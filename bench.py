@@ -161,11 +161,17 @@ def bench_keyswitch(args, torch, K, ks_inputs):
     roofline.update({"algorithmic_bytes_per_launch": dom["bytes_per_launch"], "avg_launch_us": round(dom["avg_us"], 2),
                      "launches_per_step": dom["launches"] / prof_steps})
     compulsory, fused = _keyswitch_bytes(L, Kk, dnum, N)
+    # what a plain device copy of 1 GiB reaches on this GPU: the practical ceiling beside the 8 TB/s data-sheet peak
+    copy_gbs = bench_copy(args, torch)["value"] if not args.no_batched else None
     path = {"fused_plan_MiB": fused / MIB, "compulsory_MiB": compulsory / MIB,
             "fused_plan_GBs": round(fused / (ms * 1e-3) / 1e9, 1), "fused_plan_frac_of_peak": round(fused / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "compulsory_GBs": round(compulsory / (ms * 1e-3) / 1e9, 1),
             "sum_kernel_ms_per_step": round(sum(k["ms_per_step"] for k in kernels), 4),
-            "batched_fused_plan_frac_of_peak": {str(nb): round(fused / (v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) for nb, v in batched.items()}}
+            "batched_fused_plan_frac_of_peak": {str(nb): round(fused / (v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) for nb, v in batched.items()},
+            "device_copy_GBs": copy_gbs,
+            "fused_plan_frac_of_device_copy": round(fused / (ms * 1e-3) / 1e9 / copy_gbs, 4) if copy_gbs else None,
+            "batched_fused_plan_frac_of_device_copy": {str(nb): round(fused / (v * 1e-3) / 1e9 / copy_gbs, 4)
+                                                       for nb, v in batched.items()} if copy_gbs else None}
     result = {
         "metric": "key_switches_per_sec", "value": round(1000.0 / ms, 2), "unit": "key-switch/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5), "higher_is_better": True,
