@@ -55,7 +55,7 @@ enum { /* operations for ks_workspace_bytes */
 };
 
 /* Build the tables for one parameter set on GPU `device`.
- *   logN  : 12 or 16 (ring degree 4096 or 65536).
+ *   logN  : 12 .. 16 (ring degree 4096 .. 65536).
  *   q [L] : host, ciphertext primes.   p [K] : host, special primes (NULL iff K == 0).
  *   psi   : host [L+K] primitive 2N-th roots, or NULL = the smallest positive one for each modulus.
  *   dnum  : number of digits at full level (1 <= dnum <= L); dnum is ignored by the transform and

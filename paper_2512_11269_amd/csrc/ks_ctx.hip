@@ -176,7 +176,7 @@ extern "C" int ks_ctx_create(ks_ctx** out, uint32_t logN, uint32_t L, uint32_t K
                              const uint64_t* q, const uint64_t* p, const uint64_t* psi, int device) {
     if (!out) return KS_EINVAL;
     *out = nullptr;
-    if (logN != 12 && logN != 16) return KS_EINVAL;
+    if (logN < 12 || logN > 16) return KS_EINVAL;
     if (L == 0 || !q || (K > 0 && !p) || L + K > 255 || dnum == 0 || dnum > L) return KS_EINVAL;
     const uint32_t N = 1u << logN, M = L + K;
     const uint32_t alpha = (L + dnum - 1) / dnum;

@@ -92,9 +92,12 @@ KS_HD void load_twiddles16(double (&t)[16], const double* __restrict__ W, uint32
 
 // Sixteen points, four decimation-in-time stages, in registers.  v[k] are 16 points whose mutual distances
 // are 8, 4, 2, 1 times a common stride.  Growth: every stage adds at most 0.51 p to the magnitude.
+// U0 > 0 runs only the local stages U0..3 (the last 4 - U0 stages: distances 8 >> U0 .. 1), for passes shorter than four
+// stages; the table layout is the same.
+template <int U0 = 0>
 KS_HD void radix16_fwd(double (&v)[16], const double (&t)[16], Mod m) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = U0; u < 4; ++u) {
         const int half = 8 >> u;
 #pragma unroll
         for (int g = 0; g < (1 << u); ++g) {
@@ -112,9 +115,10 @@ KS_HD void radix16_fwd(double (&v)[16], const double (&t)[16], Mod m) {
 
 // Inverse of radix16_fwd up to the factor 16 (decimation in frequency) with t built from Winv[k] = psi^-brv(k).
 // Inputs must satisfy |v| <= p; sums double per stage, so outputs are bounded by 16 p.
+template <int U0 = 0>
 KS_HD void radix16_inv(double (&v)[16], const double (&t)[16], Mod m) {
 #pragma unroll
-    for (int u = 3; u >= 0; --u) {
+    for (int u = 3; u >= U0; --u) {
         const int half = 8 >> u;
 #pragma unroll
         for (int g = 0; g < (1 << u); ++g) {

@@ -70,8 +70,8 @@ template <int LOG_R, int TS, bool TWO_SETS>
 __global__ __launch_bounds__(256) void bconv_ntt_cols(const double* __restrict__ tw, const BConvPlan* __restrict__ plans,
                                                       const uint64_t* __restrict__ y, uint64_t y_ps, uint64_t* __restrict__ out,
                                                       uint64_t out_ps, uint32_t n_subsets) {
-    constexpr uint32_t N = 256u << LOG_R, TILES = LOG_R == 8 ? 16 : 1, TC = 256 / TILES;
-    __shared__ double lds[LOG_R == 8 ? 4096 : 1];
+    constexpr uint32_t N = 256u << LOG_R, TILES = 1u << (LOG_R - 4), TC = 256 / TILES;
+    __shared__ double lds[LOG_R > 4 ? 4096 : 1];
     const uint32_t tid = threadIdx.x, tile = blockIdx.x;
     const uint32_t plan_id = blockIdx.y / n_subsets, subset = blockIdx.y - plan_id * n_subsets;
     const BConvPlan& P = plans[plan_id];
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(256) void bconv_ntt_cols(const double* __restrict__
             uint64_t* dst = op + (uint64_t)P.dst_limb[t] * N;
 #pragma unroll
             for (int k = 0; k < 16; ++k) store_f64(dst + col_row_grouped<LOG_R>(r0, k) * 256 + col, acc[tt][k]);
-            if constexpr (LOG_R == 8) __syncthreads();  // the exchange buffer is reused by the next target
+            if constexpr (LOG_R > 4) __syncthreads();  // the exchange buffer is reused by the next target
         }
     }
 }
@@ -187,12 +187,13 @@ void launch_bconv_ntt_cols(const ks_ctx* c, const BConvPlan* d_plans, uint32_t n
     // single-ciphertext launches three (one-set pipeline) measured best (384 and 256 workgroups: every one resident at
     // once, none waiting for a second round).
     // KS_BCONV_TS overrides the choice for experiments.
-    const uint32_t tiles = c->logN == 16 ? 16 : 1;
+    const uint32_t tiles = 1u << (c->logN - 12);
     int ts = (uint64_t)tiles * n_plans * ((max_targets + 3) / 4) * n_polys >= 512 ? 4 : 3;
     if (const char* e = getenv("KS_BCONV_TS")) {
         const int v = atoi(e);
         if (v >= 1 && v <= 4) ts = v;
     }
+    if (c->logN != 16 && ts < 3) ts = 3;  // the other ring degrees come with the two production shapes only
     const uint32_t n_subsets = (max_targets + ts - 1) / ts;
     const dim3 grid(tiles, n_plans * n_subsets, n_polys), block(256);
     ProfScope ps("bconv_ntt_cols", (double)limbs_moved_per_poly * n_polys * c->N * 8.0, s, ops_per_coeff * n_polys * c->N);
@@ -204,10 +205,11 @@ void launch_bconv_ntt_cols(const ks_ctx* c, const BConvPlan* d_plans, uint32_t n
         else if (ts == 2) KS_LAUNCH_BCONV(8, 2);
         else KS_LAUNCH_BCONV(8, 1);
     } else {
-        if (ts == 4) KS_LAUNCH_BCONV(4, 4);
-        else if (ts == 3) KS_LAUNCH_BCONV(4, 3);
-        else if (ts == 2) KS_LAUNCH_BCONV(4, 2);
-        else KS_LAUNCH_BCONV(4, 1);
+#define KS_LAUNCH(LOGR)      \
+    if (ts == 4) KS_LAUNCH_BCONV(LOGR, 4); \
+    else KS_LAUNCH_BCONV(LOGR, 3)
+        KS_FOR_LOG_R(c->logN, KS_LAUNCH)
+#undef KS_LAUNCH
     }
 #undef KS_LAUNCH_BCONV
 }
@@ -321,12 +323,11 @@ void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const uint64_t*
     ProfScope ps("rows_inner_product", ((double)batch * (lv.ndig + 2) * lv.E + 2.0 * lv.ndig * lv.E) * c->N * 8.0, s);
     const uint32_t tiles = (c->N / 1024) * lv.E;
     const dim3 grid(((tiles + 7) / 8) * 8 * batch), block(64);
-    if (c->logN == 16)
-        hipLaunchKernelGGL(rows_inner_product<8>, grid, block, 0, s, c->tw_fwd, c->tw_inv, c->d_mod, dg, lv.ell, lv.E,
-                           c->L, c->M, d, d_ps, lifted, evk, acc, batch);
-    else
-        hipLaunchKernelGGL(rows_inner_product<4>, grid, block, 0, s, c->tw_fwd, c->tw_inv, c->d_mod, dg, lv.ell, lv.E,
-                           c->L, c->M, d, d_ps, lifted, evk, acc, batch);
+#define KS_LAUNCH(LOGR)                                                                                                     \
+    hipLaunchKernelGGL(rows_inner_product<LOGR>, grid, block, 0, s, c->tw_fwd, c->tw_inv, c->d_mod, dg, lv.ell, lv.E, c->L, c->M, d, \
+                       d_ps, lifted, evk, acc, batch)
+    KS_FOR_LOG_R(c->logN, KS_LAUNCH)
+#undef KS_LAUNCH
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -403,17 +404,13 @@ void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t
 #define KS_LAUNCH_FINISH(LOGR, GATHER, MODE)                                                                                   \
     hipLaunchKernelGGL((rows_moddown_finish<LOGR, GATHER, MODE>), grid, block, 0, s, c->tw_fwd, c->d_mod, mul, admul, lv.ell, lv.E, \
                        out_limbs, acc, conv, out, out_bs, addend, addend_bs, comp0, n_comps, galois)
-        if (c->logN == 16) {
-            if (mode == 0) KS_LAUNCH_FINISH(8, false, 0);
-            else if (mode == 2) KS_LAUNCH_FINISH(8, false, 2);
-            else if (galois == 1) KS_LAUNCH_FINISH(8, false, 1);
-            else KS_LAUNCH_FINISH(8, true, 1);
-        } else {
-            if (mode == 0) KS_LAUNCH_FINISH(4, false, 0);
-            else if (mode == 2) KS_LAUNCH_FINISH(4, false, 2);
-            else if (galois == 1) KS_LAUNCH_FINISH(4, false, 1);
-            else KS_LAUNCH_FINISH(4, true, 1);
-        }
+#define KS_LAUNCH(LOGR)                                        \
+    if (mode == 0) KS_LAUNCH_FINISH(LOGR, false, 0);           \
+    else if (mode == 2) KS_LAUNCH_FINISH(LOGR, false, 2);      \
+    else if (galois == 1) KS_LAUNCH_FINISH(LOGR, false, 1);    \
+    else KS_LAUNCH_FINISH(LOGR, true, 1)
+        KS_FOR_LOG_R(c->logN, KS_LAUNCH)
+#undef KS_LAUNCH
 #undef KS_LAUNCH_FINISH
     }
 }
@@ -426,8 +423,8 @@ void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t
 template <int LOG_R>
 __global__ __launch_bounds__(256) void rescale_cols(const double* __restrict__ tw, const Mod* __restrict__ mods, uint32_t ell,
                                                     const uint64_t* __restrict__ last, uint64_t* __restrict__ out) {
-    constexpr uint32_t N = 256u << LOG_R, TILES = LOG_R == 8 ? 16 : 1, TC = 256 / TILES;
-    __shared__ double lds[LOG_R == 8 ? 4096 : 1];
+    constexpr uint32_t N = 256u << LOG_R, TILES = 1u << (LOG_R - 4), TC = 256 / TILES;
+    __shared__ double lds[LOG_R > 4 ? 4096 : 1];
     const uint32_t tid = threadIdx.x, tile = blockIdx.x, i = blockIdx.y, p = blockIdx.z;
     const Mod m = mods[i];
     const double ql = mods[ell - 1].p, half = (ql - 1.0) * 0.5;
@@ -481,19 +478,18 @@ void launch_rescale_fused(const ks_ctx* c, const Level& lv, const uint64_t* x, c
     const uint32_t nl = lv.ell - 1;
     {
         ProfScope ps("rescale_cols", ((double)n_polys * (1 + nl)) * c->N * 8.0, s);
-        if (c->logN == 16)
-            hipLaunchKernelGGL(rescale_cols<8>, dim3(16, nl, n_polys), dim3(256), 0, s, c->d_tw_fwd, c->d_mod, lv.ell, last, spread);
-        else
-            hipLaunchKernelGGL(rescale_cols<4>, dim3(1, nl, n_polys), dim3(256), 0, s, c->d_tw_fwd, c->d_mod, lv.ell, last, spread);
+#define KS_LAUNCH(LOGR) \
+    hipLaunchKernelGGL(rescale_cols<LOGR>, dim3(1u << (LOGR - 4), nl, n_polys), dim3(256), 0, s, c->d_tw_fwd, c->d_mod, lv.ell, last, spread)
+        KS_FOR_LOG_R(c->logN, KS_LAUNCH)
+#undef KS_LAUNCH
     }
     {
         ProfScope ps("rows_rescale_finish", (double)n_polys * nl * 3 * c->N * 8.0, s);
-        if (c->logN == 16)
-            hipLaunchKernelGGL(rows_rescale_finish<8>, dim3(64, nl, n_polys), dim3(64), 0, s, c->tw_fwd, c->d_mod, lv.d_qlinv,
-                               lv.ell, x, spread, out);
-        else
-            hipLaunchKernelGGL(rows_rescale_finish<4>, dim3(4, nl, n_polys), dim3(64), 0, s, c->tw_fwd, c->d_mod, lv.d_qlinv,
-                               lv.ell, x, spread, out);
+#define KS_LAUNCH(LOGR)                                                                                                       \
+    hipLaunchKernelGGL(rows_rescale_finish<LOGR>, dim3(1u << (LOGR - 2), nl, n_polys), dim3(64), 0, s, c->tw_fwd, c->d_mod, lv.d_qlinv, \
+                       lv.ell, x, spread, out)
+        KS_FOR_LOG_R(c->logN, KS_LAUNCH)
+#undef KS_LAUNCH
     }
 }
 

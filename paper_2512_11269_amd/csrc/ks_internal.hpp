@@ -110,6 +110,16 @@ struct ProfScope {
     hipStream_t stream;
 };
 
+// Dispatch on the ring degree: N = 2^12 .. 2^16 <-> R = N / 256 = 2^4 .. 2^8 rows.
+#define KS_FOR_LOG_R(logN, M) \
+    switch (logN) {           \
+        case 12: M(4); break; \
+        case 13: M(5); break; \
+        case 14: M(6); break; \
+        case 15: M(7); break; \
+        default: M(8); break; \
+    }
+
 // ---- launchers: all asynchronous on `s`, no allocation ----
 // In/out element formats of the two-phase transform.  Intermediate results between the two phases are
 // stored as raw doubles (lazy representatives) in the same 8-byte slots.

@@ -1,9 +1,9 @@
-// Negacyclic NTT / INTT for N = 2^12 and 2^16 (Background, "NTT"; Kernel Code Generation, NTT kernels).
+// Negacyclic NTT / INTT for N = 2^12 .. 2^16 (Background, "NTT"; Kernel Code Generation, NTT kernels).
 //
 // A limb is viewed as an R x 256 matrix (row-major, R = N / 256).  The forward transform runs its first
 // log2(R) decimation-in-time stages down the columns (butterfly partners R/2 ... 1 rows apart) and its last
 // 8 stages inside the contiguous 256-point rows; the inverse mirrors it.  Each thread owns 16 points: four
-// stages run in registers, then the tile is re-distributed through LDS for the next four.  Intermediate
+// stages run in registers, then the tile is re-distributed through LDS for the next (up to) four.  Intermediate
 // results between the two kernels of a transform are raw doubles (lazy representatives); only the last
 // kernel reduces to canonical residues.
 #include <algorithm>
@@ -28,10 +28,10 @@ __device__ __forceinline__ LimbRef locate(const LimbMap& map, uint32_t li, const
 
 // forward, columns: canonical u64 in, raw doubles out (|x| <= (1 + 0.501 log2 R) p).
 template <int LOG_R, int TC>
-__global__ __launch_bounds__(LOG_R == 8 ? TC * 16 : 256) void ntt_fwd_cols(const double* __restrict__ tw, const Mod* __restrict__ mods, LimbMap map,
+__global__ __launch_bounds__((TC << LOG_R) / 16) void ntt_fwd_cols(const double* __restrict__ tw, const Mod* __restrict__ mods, LimbMap map,
                                                         const uint64_t* in, uint64_t* out, uint64_t in_ps, uint64_t out_ps) {
     constexpr uint32_t N = 256u << LOG_R, TILES = 256 / TC;
-    __shared__ double lds[LOG_R == 8 ? 256 * TC : 1];
+    __shared__ double lds[LOG_R > 4 ? (TC << LOG_R) : 1];
     const uint32_t tid = threadIdx.x;
     const uint32_t li = blockIdx.x / TILES, tile = blockIdx.x - li * TILES;
     const LimbRef L = locate(map, li, in, out, in_ps, out_ps, N);
@@ -95,11 +95,11 @@ __global__ __launch_bounds__(64) void ntt_inv_rows(TwTables twi, const Mod* __re
 // optionally pre-multiplied by a per-limb constant (base conversion folds its (D/s_i)^-1 in here).
 // OUT_F64: store the canonical result as a double instead of a 64-bit integer.
 template <int LOG_R, int TC, bool OUT_F64>
-__global__ __launch_bounds__(LOG_R == 8 ? TC * 16 : 256) void ntt_inv_cols(const double* __restrict__ twi, const Mod* __restrict__ mods,
+__global__ __launch_bounds__((TC << LOG_R) / 16) void ntt_inv_cols(const double* __restrict__ twi, const Mod* __restrict__ mods,
                                                         const double* __restrict__ scale_tab, int scale_by_idx, LimbMap map,
                                                         uint64_t* data, uint64_t ps) {
     constexpr uint32_t N = 256u << LOG_R, TILES = 256 / TC;
-    __shared__ double lds[LOG_R == 8 ? 256 * TC : 1];
+    __shared__ double lds[LOG_R > 4 ? (TC << LOG_R) : 1];
     const uint32_t tid = threadIdx.x;
     const uint32_t li = blockIdx.x / TILES, tile = blockIdx.x - li * TILES;
     const LimbRef L = locate(map, li, data, data, ps, ps, N);
@@ -133,27 +133,26 @@ void launch_ntt_fwd_cols(const ks_ctx* c, const LimbMap& map, const XformIO& io,
     const uint64_t* in = static_cast<const uint64_t*>(io.in);
     uint64_t* out = static_cast<uint64_t*>(io.out);
     ProfScope ps("ntt_fwd_cols", 2.0 * limbs * c->N * 8.0, s);
-    if (c->logN == 16) {
-        if (wide_tiles(limbs))
-            hipLaunchKernelGGL((ntt_fwd_cols<8, 32>), dim3(limbs * 8), dim3(512), 0, s, c->d_tw_fwd, c->d_mod, map, in, out,
-                               io.in_poly_stride, io.out_poly_stride);
-        else
-            hipLaunchKernelGGL((ntt_fwd_cols<8, 16>), dim3(limbs * 16), dim3(256), 0, s, c->d_tw_fwd, c->d_mod, map, in, out,
-                               io.in_poly_stride, io.out_poly_stride);
-    } else {
-        hipLaunchKernelGGL((ntt_fwd_cols<4, 256>), dim3(limbs), dim3(256), 0, s, c->d_tw_fwd, c->d_mod, map, in, out,
+    if (c->logN == 16 && wide_tiles(limbs)) {
+        hipLaunchKernelGGL((ntt_fwd_cols<8, 32>), dim3(limbs * 8), dim3(512), 0, s, c->d_tw_fwd, c->d_mod, map, in, out,
                            io.in_poly_stride, io.out_poly_stride);
+        return;
     }
+#define KS_LAUNCH(LOGR)                                                                                                          \
+    hipLaunchKernelGGL((ntt_fwd_cols<LOGR, (4096 >> LOGR)>), dim3(limbs << (LOGR - 4)), dim3(256), 0, s, c->d_tw_fwd, c->d_mod, map, in, \
+                       out, io.in_poly_stride, io.out_poly_stride)
+    KS_FOR_LOG_R(c->logN, KS_LAUNCH)
+#undef KS_LAUNCH
 }
 
 void launch_ntt_fwd_rows(const ks_ctx* c, const LimbMap& map, uint64_t* data, uint64_t ps_words, uint32_t n_polys, hipStream_t s) {
     const uint32_t limbs = map.n * n_polys;
     if (limbs == 0) return;
     ProfScope ps("ntt_fwd_rows", 2.0 * limbs * c->N * 8.0, s);
-    if (c->logN == 16)
-        hipLaunchKernelGGL(ntt_fwd_rows<8>, dim3(limbs * 64), dim3(64), 0, s, c->tw_fwd, c->d_mod, map, data, ps_words);
-    else
-        hipLaunchKernelGGL(ntt_fwd_rows<4>, dim3(limbs * 4), dim3(64), 0, s, c->tw_fwd, c->d_mod, map, data, ps_words);
+#define KS_LAUNCH(LOGR) \
+    hipLaunchKernelGGL(ntt_fwd_rows<LOGR>, dim3(limbs << (LOGR - 2)), dim3(64), 0, s, c->tw_fwd, c->d_mod, map, data, ps_words)
+    KS_FOR_LOG_R(c->logN, KS_LAUNCH)
+#undef KS_LAUNCH
 }
 
 // Polynomials per launch pair of a two-pass transform: the second pass of a group should find what the first pass wrote
@@ -182,12 +181,11 @@ void launch_ntt_inv_rows(const ks_ctx* c, const LimbMap& map, const XformIO& io,
     const uint64_t* in = static_cast<const uint64_t*>(io.in);
     uint64_t* out = static_cast<uint64_t*>(io.out);
     ProfScope ps("ntt_inv_rows", 2.0 * limbs * c->N * 8.0, s);
-    if (c->logN == 16)
-        hipLaunchKernelGGL(ntt_inv_rows<8>, dim3(limbs * 64), dim3(64), 0, s, c->tw_inv, c->d_mod, map, in, out,
-                           io.in_poly_stride, io.out_poly_stride);
-    else
-        hipLaunchKernelGGL(ntt_inv_rows<4>, dim3(limbs * 4), dim3(64), 0, s, c->tw_inv, c->d_mod, map, in, out,
-                           io.in_poly_stride, io.out_poly_stride);
+#define KS_LAUNCH(LOGR)                                                                                                      \
+    hipLaunchKernelGGL(ntt_inv_rows<LOGR>, dim3(limbs << (LOGR - 2)), dim3(64), 0, s, c->tw_inv, c->d_mod, map, in, out, \
+                       io.in_poly_stride, io.out_poly_stride)
+    KS_FOR_LOG_R(c->logN, KS_LAUNCH)
+#undef KS_LAUNCH
 }
 
 void launch_ntt_inv_cols(const ks_ctx* c, const LimbMap& map, uint64_t* data, uint64_t ps_words, uint32_t n_polys,
@@ -196,21 +194,19 @@ void launch_ntt_inv_cols(const ks_ctx* c, const LimbMap& map, uint64_t* data, ui
     if (limbs == 0) return;
     ProfScope ps("ntt_inv_cols", 2.0 * limbs * c->N * 8.0, s);
     const int by_idx = scale_by_idx ? 1 : 0;
-#define KS_LAUNCH_INV_COLS(LOGR, TCV, GRID, F64) \
-    hipLaunchKernelGGL((ntt_inv_cols<LOGR, TCV, F64>), dim3(GRID), dim3(LOGR == 8 ? TCV * 16 : 256), 0, s, c->d_tw_inv, c->d_mod, \
-                       scale_tab, by_idx, map, data, ps_words)
-    if (c->logN == 16) {
-        if (wide_tiles(limbs)) {
-            if (out_f64) KS_LAUNCH_INV_COLS(8, 32, limbs * 8, true);
-            else KS_LAUNCH_INV_COLS(8, 32, limbs * 8, false);
-        } else {
-            if (out_f64) KS_LAUNCH_INV_COLS(8, 16, limbs * 16, true);
-            else KS_LAUNCH_INV_COLS(8, 16, limbs * 16, false);
-        }
-    } else {
-        if (out_f64) KS_LAUNCH_INV_COLS(4, 256, limbs, true);
-        else KS_LAUNCH_INV_COLS(4, 256, limbs, false);
+#define KS_LAUNCH_INV_COLS(LOGR, TCV, GRID, F64)                                                                               \
+    hipLaunchKernelGGL((ntt_inv_cols<LOGR, TCV, F64>), dim3(GRID), dim3((TCV << LOGR) / 16), 0, s, c->d_tw_inv, c->d_mod, scale_tab, \
+                       by_idx, map, data, ps_words)
+    if (c->logN == 16 && wide_tiles(limbs)) {
+        if (out_f64) KS_LAUNCH_INV_COLS(8, 32, limbs * 8, true);
+        else KS_LAUNCH_INV_COLS(8, 32, limbs * 8, false);
+        return;
     }
+#define KS_LAUNCH(LOGR)                                                                       \
+    if (out_f64) KS_LAUNCH_INV_COLS(LOGR, (4096 >> LOGR), limbs << (LOGR - 4), true); \
+    else KS_LAUNCH_INV_COLS(LOGR, (4096 >> LOGR), limbs << (LOGR - 4), false)
+    KS_FOR_LOG_R(c->logN, KS_LAUNCH)
+#undef KS_LAUNCH
 #undef KS_LAUNCH_INV_COLS
 }
 

@@ -1,8 +1,8 @@
 // Tile-level pieces of the two-phase transform, shared by the plain NTT kernels and the fused ones.
 //
-// A limb is an R x 256 matrix (R = N / 256).  "Row" pieces work on contiguous 256-point rows, one
-// wavefront owning four rows (16 lanes per row, 16 points per lane); "column" pieces work on a tile of 16
-// columns x 256 rows owned by a 256-thread workgroup.  Twiddles come from the per-modulus heap-ordered
+// A limb is an R x 256 matrix (R = N / 256 = 16 .. 256).  "Row" pieces work on contiguous 256-point rows, one
+// wavefront owning four rows (16 lanes per row, 16 points per lane); "column" pieces work on a tile of 4096 / R
+// columns x R rows (16 x 256 for N = 2^16) owned by a 256-thread workgroup.  Twiddles come from the per-modulus heap-ordered
 // table W[k] = psi^brv(k): the forward stage with 2^s blocks uses W[2^s + block].
 #pragma once
 #include "ks_device.hpp"
@@ -82,11 +82,21 @@ __device__ __forceinline__ void row_twiddles_to_lds(double* ta_row, const double
     ta_row[j0] = j0 ? W[(node << u) + g] : 0.0;
 }
 
-// columns: heap node 1 for the first pass, 16 + r0 for the second (LOG_R = 8 only)
+// Columns (R = 2^LOG_R rows, 4 <= LOG_R <= 8): the first register pass runs global stages 0..3 with the sub-tree below
+// heap node 1; the second one the remaining E = LOG_R - 4 stages on 16 consecutive rows 16 r0 + k, as the last E local
+// stages of a 16-point pass: local stage ul = 4 - E + u is global stage 4 + u, whose block of row 16 r0 + k is
+// r0 2^ul + (k >> (4 - ul)), so its table entry (1 << ul) + g holds W[2^(E + ul) + r0 2^ul + g].  For E = 4 that is
+// the sub-tree below node 16 + r0.
 template <int LOG_R>
 __device__ __forceinline__ void load_col_twiddles(PassTwiddles& t, const double* __restrict__ W, uint32_t r0) {
+    constexpr int E = LOG_R - 4;
     load_twiddles16(t.a, W, 1);
-    if constexpr (LOG_R == 8) load_twiddles16(t.b, W, 16 + r0);
+    if constexpr (E > 0) {
+#pragma unroll
+        for (int ul = 4 - E; ul < 4; ++ul)
+#pragma unroll
+            for (int g = 0; g < (1 << ul); ++g) t.b[(1 << ul) + g] = W[(1u << (E + ul)) + (r0 << ul) + g];
+    }
 }
 
 // Last 8 forward stages of one row.  in: v[k] = point j0 + 16 k of the row, lazy with |v| <= 8 p.
@@ -143,34 +153,35 @@ __device__ __forceinline__ void row_inv_core(double (&v)[16], const PassTwiddles
     for (int k = 0; k < 16; ++k) v[k] = reduce_lazy(v[k], m);
 }
 
-// First log2(R) forward stages on a column tile.
-//   LOG_R = 8: tile of TC columns x 256 rows, 16 TC threads, thread (c = tid % TC, r0 = tid / TC);
-//              in: v[k] = row r0 + 16 k, out: v[k] = row 16 r0 + k; lds: 256 TC doubles.  LOG_R = 4: one register pass, rows k in and out, lds unused.
-// Growth: at most 0.51 p per stage.
-template <int LOG_R, int TC = 16>
+// First log2(R) forward stages on a column tile of TC columns x R rows (R = 2^LOG_R), TC R / 16 threads, thread
+// (c = tid % TC, r0 = tid / TC).  in: v[k] = row r0 + (R / 16) k; out: v[k] = row 16 r0 + k; lds: R TC doubles (unused for
+// R = 16, where one register pass does everything and rows k go in and out).  Growth: at most 0.51 p per stage.
+template <int LOG_R, int TC = (4096 >> LOG_R)>
 __device__ __forceinline__ void col_fwd_core(double (&v)[16], const PassTwiddles& t, uint32_t c, uint32_t r0, double* lds, Mod m) {
+    constexpr int E = LOG_R - 4, S = 1 << E;
     radix16_fwd(v, t.a, m);
-    if constexpr (LOG_R == 8) {
+    if constexpr (E > 0) {
 #pragma unroll
-        for (int k = 0; k < 16; ++k) lds[(r0 + 16 * k) * TC + c] = v[k];
+        for (int k = 0; k < 16; ++k) lds[(r0 + S * k) * TC + c] = v[k];
         __syncthreads();
 #pragma unroll
         for (int k = 0; k < 16; ++k) v[k] = lds[(16 * r0 + k) * TC + c];
-        radix16_fwd(v, t.b, m);
+        radix16_fwd<4 - E>(v, t.b, m);
     }
 }
 
-// Last log2(R) inverse stages on a column tile (no N^-1 factor).  LOG_R = 8: in rows 16 r0 + k, out rows r0 + 16 k.
+// Last log2(R) inverse stages on a column tile (no N^-1 factor): in rows 16 r0 + k, out rows r0 + (R / 16) k.
 // in: |v| <= p.  out: |v| <= 16 p.
-template <int LOG_R, int TC = 16>
+template <int LOG_R, int TC = (4096 >> LOG_R)>
 __device__ __forceinline__ void col_inv_core(double (&v)[16], const PassTwiddles& t, uint32_t c, uint32_t r0, double* lds, Mod m) {
-    if constexpr (LOG_R == 8) {
-        radix16_inv(v, t.b, m);
+    constexpr int E = LOG_R - 4, S = 1 << E;
+    if constexpr (E > 0) {
+        radix16_inv<4 - E>(v, t.b, m);
 #pragma unroll
         for (int k = 0; k < 16; ++k) lds[(16 * r0 + k) * TC + c] = reduce_lazy(v[k], m);
         __syncthreads();
 #pragma unroll
-        for (int k = 0; k < 16; ++k) v[k] = lds[(r0 + 16 * k) * TC + c];
+        for (int k = 0; k < 16; ++k) v[k] = lds[(r0 + S * k) * TC + c];
     }
     radix16_inv(v, t.a, m);
 }
@@ -182,18 +193,18 @@ __device__ __forceinline__ BufferRsrc make_buffer_rsrc(const void* base, uint64_
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)(uint32_t)bytes, 0x00020000);
 }
 
-// Point k of the 16 strided points of a column-pass thread (rows r0 + 16 k, or k when a limb has only 16 rows): the
-// double at byte offset limb_off + k * (4096 | 256) * 8 + lane_off of the buffer, lane_off = 8 (256 r0 + column).
+// Point k of the 16 strided points of a column-pass thread (rows r0 + (R / 16) k): the double at byte offset
+// limb_off + k * 16 R * 8 + lane_off of the buffer, lane_off = 8 (256 r0 + column).
 template <int LOG_R>
 __device__ __forceinline__ double load_strided_point(BufferRsrc rsrc, uint32_t lane_off, uint32_t limb_off, int k) {
-    constexpr uint32_t kStrideBytes = (LOG_R == 8 ? 4096u : 256u) * 8u;
+    constexpr uint32_t kStrideBytes = (16u << LOG_R) * 8u;
     return __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)lane_off, (int)(limb_off + k * kStrideBytes), 0));
 }
 
 // Row index of v[k] before / after the column cores, and the first column of the tile.
 template <int LOG_R>
-__device__ __forceinline__ uint32_t col_row_strided(uint32_t r0, int k) { return LOG_R == 8 ? r0 + 16 * k : (uint32_t)k; }
+__device__ __forceinline__ uint32_t col_row_strided(uint32_t r0, int k) { return r0 + ((uint32_t)k << (LOG_R - 4)); }
 template <int LOG_R>
-__device__ __forceinline__ uint32_t col_row_grouped(uint32_t r0, int k) { return LOG_R == 8 ? 16 * r0 + k : (uint32_t)k; }
+__device__ __forceinline__ uint32_t col_row_grouped(uint32_t r0, int k) { return 16 * r0 + (uint32_t)k; }
 
 }  // namespace ks

@@ -114,6 +114,21 @@ static void check_prime(uint64_t p) {
             CHECK(mod_i128((i128)(int64_t)w[k], p) == x[k], "radix16_fwd value");
             CHECK(fabs(w[k]) <= in_max + 4 * lim, "radix16_fwd growth");
         }
+        // shortened passes (last 4 - U0 stages only) against the same exact butterflies
+        {
+            int64_t y[16];
+            double z[16];
+            for (int k = 0; k < 16; ++k) { y[k] = mod_i128(e[k], p); z[k] = v[k]; }
+            for (int u = 2; u < 4; ++u) { int half = 8 >> u; for (int g = 0; g < (1 << u); ++g) { int64_t tw = (int64_t)t[(1 << u) + g]; for (int i = 0; i < half; ++i) { int k = g * 2 * half + i; int64_t xx = mod_i128((i128)y[k + half] * tw, p); int64_t a = y[k]; y[k] = mod_i128((i128)a + xx, p); y[k + half] = mod_i128((i128)a - xx, p); } } }
+            radix16_fwd<2>(z, t, m);
+            for (int k = 0; k < 16; ++k) CHECK(mod_i128((i128)(int64_t)z[k], p) == y[k], "radix16_fwd<2> value");
+            for (int k = 0; k < 16; ++k) { y[k] = mod_i128(e[k], p); z[k] = v[k]; }
+            for (int u = 3; u >= 1; --u) { int half = 8 >> u; for (int g = 0; g < (1 << u); ++g) { int64_t tw = (int64_t)t[(1 << u) + g]; for (int i = 0; i < half; ++i) { int k = g * 2 * half + i; int64_t a = y[k], b = y[k + half]; y[k] = mod_i128((i128)a + b, p); y[k + half] = mod_i128((i128)mod_i128((i128)a - b, p) * tw, p); } } }
+            if (rep & 1) {   // canonical inputs: inside the inverse pass's input range
+                radix16_inv<1>(z, t, m);
+                for (int k = 0; k < 16; ++k) CHECK(mod_i128((i128)(int64_t)z[k], p) == y[k], "radix16_inv<1> value");
+            }
+        }
         // inverse pass needs |v| <= p
         for (int k = 0; k < 16; ++k) { e[k] = (int64_t)(rnd() % (2 * p)) - (int64_t)p; v[k] = (double)e[k]; x[k] = mod_i128(e[k], p); }
         for (int u = 3; u >= 0; --u) { int half = 8 >> u; for (int g = 0; g < (1 << u); ++g) { int64_t tw = (int64_t)t[(1 << u) + g]; for (int i = 0; i < half; ++i) { int k = g * 2 * half + i; int64_t a = x[k], b = x[k + half]; x[k] = mod_i128((i128)a + b, p); x[k + half] = mod_i128((i128)(a - b) * tw, p); } } }
