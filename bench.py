@@ -250,6 +250,46 @@ def _time_calls(torch, fn, reps):
     return t0.elapsed_time(t1) / reps
 
 
+def bench_keyswitch_u32(args, torch, K, ks_inputs):
+    """Configuration 2's shape with the paper's word size: 28-bit primes, d / key / result in 32-bit words."""
+    cfg = dict(ks_inputs.CONFIGS[2], bits=28)
+    q, p = ks_inputs.moduli(cfg)
+    logN, L, Kk, dnum = cfg["logN"], cfg["L"], cfg["K"], cfg["dnum"]
+    N = 1 << logN
+    ctx = K.Context(logN, q, p, dnum)
+    i32 = lambda t: t.to(torch.int32)
+    sets = []
+    for sidx in range(args.sets):
+        d = i32(ks_inputs.uniform_residues(cfg["seed"], 100 * sidx + 1, (1,), q, N, device="cuda"))
+        evk = i32(ks_inputs.uniform_residues(cfg["seed"], 100 * sidx + 2, (dnum, 2), q + p, N, device="cuda"))
+        out = torch.empty((1, 2, L, N), dtype=torch.int32, device="cuda")
+        ws = torch.empty(K.ks_workspace_bytes(ctx, K.KS_OP_KEYSWITCH, L, 1) // 8, dtype=torch.int64, device="cuda")
+        sets.append((d, evk, out, ws))
+    state = {"i": 0}
+
+    def one():
+        d, evk, out, ws = sets[state["i"] % len(sets)]
+        state["i"] += 1
+        K.ks_keyswitch_u32(ctx, d, L, evk, out, ws)
+
+    for _ in range(args.warmup):
+        one()
+    ms = _time_calls(torch, one, args.steps)
+    nb = 16
+    d_b = i32(ks_inputs.uniform_residues(cfg["seed"], 7001, (nb,), q, N, device="cuda"))
+    out_b = torch.empty((nb, 2, L, N), dtype=torch.int32, device="cuda")
+    ws_b = torch.empty(K.ks_workspace_bytes(ctx, K.KS_OP_KEYSWITCH, L, nb) // 8, dtype=torch.int64, device="cuda")
+    batched = lambda: K.ks_keyswitch_u32(ctx, d_b, L, sets[0][1], out_b, ws_b)
+    ms_b = _time_calls(torch, batched, max(2, min(20, args.steps // nb + 1))) / nb
+    kernels = _kernel_breakdown(K, torch, lambda: [one() for _ in range(24)], 24)
+    return {"metric": "key_switches_per_sec", "value": round(1000.0 / ms, 2), "unit": "key-switch/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "f64", "data": "synthetic", "batched_value": {str(nb): round(1000.0 / ms_b, 2)},
+            "config": {"workload": "bootstrap-keyswitch N=2^16 L=24 K=8 dnum=3 batch=1, 28-bit primes, d / key / result in 32-bit words",
+                       "buffer_sets_rotated": args.sets},
+            "roofline": _dominant_roofline(kernels), "kernels": kernels}
+
+
 def bench_rotate(args, torch, K, ks_inputs):
     """Configuration 3: 64 ciphertexts x 16 hoisted rotations per call (one ModUp per ciphertext, 16 rotation keys)."""
     cfg = ks_inputs.CONFIGS[3]
@@ -413,7 +453,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--sets", type=int, default=6, help="disjoint buffer sets rotated through (cold-cache figure)")
     ap.add_argument("--no-batched", action="store_true", help="skip the batched key-switch measurement (counter runs)")
-    ap.add_argument("--workload", default="keyswitch", choices=["keyswitch", "ntt", "rotate", "rotate_mac", "bsgs", "hmult", "hmult_merged", "copy"])
+    ap.add_argument("--workload", default="keyswitch", choices=["keyswitch", "keyswitch_u32", "ntt", "rotate", "rotate_mac", "bsgs", "hmult", "hmult_merged", "copy"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -432,6 +472,8 @@ def main():
         result = bench_copy(args, torch)
     elif args.workload == "ntt":
         result = bench_ntt(args, torch, K, ks_inputs)
+    elif args.workload == "keyswitch_u32":
+        result = bench_keyswitch_u32(args, torch, K, ks_inputs)
     elif args.workload == "rotate":
         result = bench_rotate(args, torch, K, ks_inputs)
     elif args.workload == "rotate_mac":

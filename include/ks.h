@@ -105,6 +105,14 @@ int bconv(const ks_ctx* ctx, const uint64_t* in, const uint32_t* src_ids, uint32
 int ks_keyswitch(const ks_ctx* ctx, const uint64_t* d, uint32_t ell, const uint64_t* evk, uint64_t* out,
                  uint32_t batch, void* ws, size_t ws_bytes, void* stream);
 
+/* ks_keyswitch with the boundary tensors in 32-bit words (the paper's word size: Evaluation, "Benchmarks", a 28-bit RNS basis in
+ * 32-bit words): d [batch][ell][N], evk [dnum][2][L+K][N] and out [batch][2][ell][N] hold one
+ * residue per uint32_t, which halves the traffic of the key, the largest tensor of the operation.  Arithmetic, workspace
+ * (KS_OP_KEYSWITCH, 8-byte elements inside) and results are those of ks_keyswitch.  KS_EINVAL unless every modulus
+ * of the context is below 2^32. */
+int ks_keyswitch_u32(const ks_ctx* ctx, const uint32_t* d, uint32_t ell, const uint32_t* evk, uint32_t* out,
+                     uint32_t batch, void* ws, size_t ws_bytes, void* stream);
+
 /* Hoisted rotations (Motivation: hoisting): for every ciphertext the decompose-and-raise of c1 is done once
  * and shared by all n_rot Galois elements.  For each g: sigma_g (X -> X^g) is applied to the raised digits,
  * then inner product with that rotation's key, division by P, and sigma_g(c0) is added to component 0.

@@ -60,7 +60,7 @@ def prime_list(logN: int, count: int, bits: int = 36) -> list[int]:
 
 def moduli(cfg: dict) -> tuple[list[int], list[int]]:
     """(q, p): special primes take the K largest primes, ciphertext primes the next L."""
-    pl = prime_list(cfg["logN"], cfg["L"] + cfg["K"])
+    pl = prime_list(cfg["logN"], cfg["L"] + cfg["K"], cfg.get("bits", 36))
     return pl[cfg["K"]:], pl[:cfg["K"]]
 
 

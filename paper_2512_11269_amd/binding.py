@@ -53,6 +53,7 @@ def load_library():
     lib.ntt_inv.argtypes = [_vp, _vp, _u32p, ctypes.c_uint32, ctypes.c_uint32, _vp]
     lib.bconv.argtypes = [_vp, _vp, _u32p, ctypes.c_uint32, _vp, _u32p, ctypes.c_uint32, ctypes.c_uint32, _vp]
     lib.ks_keyswitch.argtypes = [_vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
+    lib.ks_keyswitch_u32.argtypes = [_vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
     lib.ks_rotate_hoisted.argtypes = [_vp, _vp, ctypes.c_uint32, _u32p, ctypes.POINTER(_vp), ctypes.c_uint32, _vp,
                                       ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
     lib.ks_rotate_mac_hoisted.argtypes = [_vp, _vp, ctypes.c_uint32, _u32p, ctypes.POINTER(_vp), ctypes.POINTER(_vp),
@@ -97,9 +98,9 @@ def _u32_array(values):
     return (ctypes.c_uint32 * len(values))(*[int(v) for v in values])
 
 
-def _dev_ptr(t: torch.Tensor) -> int:
-    if not (t.is_cuda and t.dtype == torch.int64 and t.is_contiguous()):
-        raise KsError("expected a contiguous int64 CUDA tensor")
+def _dev_ptr(t: torch.Tensor, dtype=torch.int64) -> int:
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise KsError(f"expected a contiguous {dtype} CUDA tensor")
     return t.data_ptr()
 
 
@@ -206,3 +207,10 @@ def ks_bsgs_linear_transform(ctx: Context, ct: torch.Tensor, ell: int, baby_galo
                                                    len(baby_keys), _u32_array(giant_galois), _ptr_array(giant_keys), len(giant_keys),
                                                    _ptr_array(flat), _dev_ptr(out), batch, _dev_ptr(ws), ws.numel() * 8, _stream()),
            "ks_bsgs_linear_transform")
+
+
+def ks_keyswitch_u32(ctx: Context, d: torch.Tensor, ell: int, evk: torch.Tensor, out: torch.Tensor, ws: torch.Tensor) -> None:
+    """d, evk, out: int32 tensors holding one residue (< 2^32) per 32-bit word; ws as for ks_keyswitch (int64)."""
+    batch = d.numel() // (ell * ctx.N)
+    _check(load_library().ks_keyswitch_u32(ctx.handle, _dev_ptr(d, torch.int32), ell, _dev_ptr(evk, torch.int32),
+                                           _dev_ptr(out, torch.int32), batch, _dev_ptr(ws), ws.numel() * 8, _stream()), "ks_keyswitch_u32")

@@ -41,10 +41,10 @@ KsWorkspace ks_ws_words(const ks_ctx* c, const Level& lv, uint32_t bc) {
 // Decompose and raise: d (evaluation domain, `bc` polynomials d_ps words apart) -> lifted [bc][ndig][E][N].
 // With finish_rows the raised limbs end as canonical evaluation-domain residues; without it they stop after the
 // column half of the forward transform (raw doubles) and the row half is left to the fused inner product.
-void mod_up(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, uint64_t* coeff, uint64_t* lifted, uint32_t bc,
-            bool finish_rows, hipStream_t s) {
+void mod_up(const ks_ctx* c, const Level& lv, const void* d, uint64_t d_ps, uint64_t* coeff, uint64_t* lifted, uint32_t bc,
+            bool finish_rows, hipStream_t s, bool d_words32 = false) {
     const uint64_t N = c->N, coeff_ps = (uint64_t)lv.ell * N, lifted_ps = (uint64_t)lv.ndig * lv.E * N;
-    launch_ntt_inv_rows(c, lv.q_map, XformIO{d, coeff, d_ps, coeff_ps, bc}, s);
+    launch_ntt_inv_rows(c, lv.q_map, XformIO{d, coeff, d_ps, coeff_ps, bc}, s, d_words32);
     // the column half also multiplies by N^-1 (D_j/q_i)^-1 and leaves canonical doubles for the conversion
     launch_ntt_inv_cols(c, lv.q_map, coeff, coeff_ps, bc, lv.d_modup_scale, true, true, s);
     // algorithmic fp64 work per coefficient: 3 FMAs per source x target plus the 6-addition split of the source shared
@@ -67,15 +67,15 @@ static double moddown_ops(const ks_ctx* c, const Level& lv) {
 
 // Division by P of both accumulators, optional addend: INTT of the special limbs (in place), fused base
 // conversion + column half, fused row half + (acc - conv) P^-1.
-void mod_down(const ks_ctx* c, const Level& lv, uint64_t* acc, uint64_t* conv, uint64_t* out, uint64_t out_bs,
+void mod_down(const ks_ctx* c, const Level& lv, uint64_t* acc, uint64_t* conv, void* out, uint64_t out_bs,
               const uint64_t* addend, uint64_t addend_bs, uint32_t addend_comps, uint32_t galois, uint32_t bc,
-              bool special_rows_done, hipStream_t s) {
+              bool special_rows_done, hipStream_t s, bool out_words32 = false) {
     const uint64_t N = c->N, acc_ps = (uint64_t)lv.E * N, conv_ps = (uint64_t)lv.ell * N;
     // the fused inner product already ran the row half of the inverse transform on the special limbs
     if (!special_rows_done) launch_ntt_inv_rows(c, lv.special_map, XformIO{acc, acc, acc_ps, acc_ps, 2 * bc}, s);
     launch_ntt_inv_cols(c, lv.special_map, acc, acc_ps, 2 * bc, c->d_moddown_scale, true, true, s);
     launch_bconv_ntt_cols(c, lv.d_moddown, 1, lv.ell, c->K + lv.ell, acc, acc_ps, conv, conv_ps, 2 * bc, s, moddown_ops(c, lv));
-    launch_rows_moddown_finish(c, lv, acc, conv, out, out_bs, addend, addend_bs, addend_comps, galois, bc, s);
+    launch_rows_moddown_finish(c, lv, acc, conv, out, out_bs, addend, addend_bs, addend_comps, galois, bc, s, nullptr, out_words32);
 }
 
 }  // namespace
@@ -200,15 +200,19 @@ static int check_pipeline_args(const ks_ctx* c, uint32_t ell, uint32_t min_ell, 
     return KS_OK;
 }
 
-extern "C" int ks_keyswitch(const ks_ctx* c, const uint64_t* d, uint32_t ell, const uint64_t* evk, uint64_t* out, uint32_t batch,
-                            void* ws, size_t ws_bytes, void* stream) {
+// d, evk and out in 64-bit words, or all three in 32-bit words (words32; every modulus then below 2^32).
+static int keyswitch_impl(const ks_ctx* c, const void* d, uint32_t ell, const void* evk, void* out, uint32_t batch, void* ws,
+                          size_t ws_bytes, void* stream, bool words32) {
     int rc = check_pipeline_args(c, ell, 1, d, evk, out, ws);
     if (rc != KS_OK) return rc;
+    if (words32)
+        for (uint64_t m : c->mod)
+            if (m >> 32) return KS_EINVAL;
     if (batch == 0) return KS_OK;
     if (ws_bytes < ks_workspace_bytes(c, KS_OP_KEYSWITCH, ell, batch, 0)) return KS_EWORKSPACE;
     const Level& lv = c->levels[ell - 1];
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const uint64_t N = c->N, d_ps = (uint64_t)ell * N, out_bs = 2ull * ell * N;
+    const uint64_t N = c->N, d_ps = (uint64_t)ell * N, out_bs = 2ull * ell * N, word = words32 ? 4 : 8;
     for (uint32_t b0 = 0; b0 < batch; b0 += kChunk) {
         const uint32_t bc = std::min(batch - b0, kChunk);
         const KsWorkspace w = ks_ws_words(c, lv, bc);
@@ -216,12 +220,22 @@ extern "C" int ks_keyswitch(const ks_ctx* c, const uint64_t* d, uint32_t ell, co
         uint64_t* lifted = coeff + w.coeff;
         uint64_t* acc = lifted + w.lifted;
         uint64_t* conv = acc + w.acc;
-        const uint64_t* dc = d + (uint64_t)b0 * d_ps;
-        mod_up(c, lv, dc, d_ps, coeff, lifted, bc, false, s);
-        launch_rows_inner_product(c, lv, dc, d_ps, lifted, evk, acc, bc, s);
-        mod_down(c, lv, acc, conv, out + (uint64_t)b0 * out_bs, out_bs, nullptr, 0, 0, 1, bc, true, s);
+        const char* dc = static_cast<const char*>(d) + (uint64_t)b0 * d_ps * word;
+        mod_up(c, lv, dc, d_ps, coeff, lifted, bc, false, s, words32);
+        launch_rows_inner_product(c, lv, dc, d_ps, lifted, evk, acc, bc, s, words32);
+        mod_down(c, lv, acc, conv, static_cast<char*>(out) + (uint64_t)b0 * out_bs * word, out_bs, nullptr, 0, 0, 1, bc, true, s, words32);
     }
-    return finish("ks_keyswitch");
+    return finish(words32 ? "ks_keyswitch_u32" : "ks_keyswitch");
+}
+
+extern "C" int ks_keyswitch(const ks_ctx* c, const uint64_t* d, uint32_t ell, const uint64_t* evk, uint64_t* out, uint32_t batch,
+                            void* ws, size_t ws_bytes, void* stream) {
+    return keyswitch_impl(c, d, ell, evk, out, batch, ws, ws_bytes, stream, false);
+}
+
+extern "C" int ks_keyswitch_u32(const ks_ctx* c, const uint32_t* d, uint32_t ell, const uint32_t* evk, uint32_t* out, uint32_t batch,
+                                void* ws, size_t ws_bytes, void* stream) {
+    return keyswitch_impl(c, d, ell, evk, out, batch, ws, ws_bytes, stream, true);
 }
 
 extern "C" int ks_rotate_hoisted(const ks_ctx* c, const uint64_t* ct, uint32_t ell, const uint32_t* galois,

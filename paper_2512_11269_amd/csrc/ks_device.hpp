@@ -34,6 +34,20 @@ KS_HD uint64_t f64_to_u64(double r) {
     return __builtin_bit_cast(uint64_t, r + kTwo52) & 0x000FFFFFFFFFFFFFull;
 }
 
+// Residues at the library boundary are stored in 64-bit words or, for moduli below 2^32, in 32-bit words.
+template <typename W>
+KS_HD double word_to_f64(W x);
+template <>
+KS_HD double word_to_f64<uint64_t>(uint64_t x) { return u64_to_f64(x); }
+template <>
+KS_HD double word_to_f64<uint32_t>(uint32_t x) { return (double)x; }
+template <typename W>
+KS_HD W f64_to_word(double r);  // integer-valued canonical residue
+template <>
+KS_HD uint64_t f64_to_word<uint64_t>(double r) { return f64_to_u64(r); }
+template <>
+KS_HD uint32_t f64_to_word<uint32_t>(double r) { return (uint32_t)r; }
+
 // a * b mod p as a small signed representative.
 // Requires integer-valued |a| <= 2^43, |b| <= 2^36.  Returns r = a b (mod p) with |r| <= 0.51 p.
 //   h + l = a b exactly (l is the rounding error of the product, recovered by one FMA);

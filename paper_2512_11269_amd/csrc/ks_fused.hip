@@ -220,12 +220,13 @@ void launch_bconv_ntt_cols(const ks_ctx* c, const BConvPlan* d_plans, uint32_t n
 // One wavefront = four rows of one limb position; it walks the digits, so d~ is read once and feeds both key
 // components (load reuse), and the accumulators are reduced and written once.
 // ------------------------------------------------------------------------------------------------
-template <int LOG_R>
+// W: word type of the boundary tensors d and evk (64-bit, or 32-bit for moduli below 2^32).
+template <int LOG_R, typename W>
 __global__ __launch_bounds__(64) void rows_inner_product(TwTables tw, TwTables twi,
                                                          const Mod* __restrict__ mods, DigitRanges dg,
                                                          uint32_t ell, uint32_t E, uint32_t L, uint32_t M,
-                                                         const uint64_t* __restrict__ d, uint64_t d_ps,
-                                                         const uint64_t* __restrict__ lifted, const uint64_t* __restrict__ evk,
+                                                         const W* __restrict__ d, uint64_t d_ps,
+                                                         const uint64_t* __restrict__ lifted, const W* __restrict__ evk,
                                                          uint64_t* __restrict__ acc, uint32_t batch) {
     constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R;
     __shared__ double lds[4 * kRowPitch];
@@ -255,26 +256,50 @@ __global__ __launch_bounds__(64) void rows_inner_product(TwTables tw, TwTables t
 #pragma unroll 1
     for (uint32_t j = 0; j < dg.ndig; ++j) {
         const bool own = pos >= dg.lo[j] && pos < dg.hi[j];  // uniform
-        const uint64_t* key0 = evk + ((uint64_t)(j * 2 + 0) * M + mid) * N + off;
-        const uint64_t* key1 = evk + ((uint64_t)(j * 2 + 1) * M + mid) * N + off;
+        const W* key0 = evk + ((uint64_t)(j * 2 + 0) * M + mid) * N + off;
+        const W* key1 = evk + ((uint64_t)(j * 2 + 1) * M + mid) * N + off;
         // issue every load of this digit up front (the key slots are independent of the transform below)
         double x[16], k0[16], k1[16];
-        const uint64_t* src = own ? d + (uint64_t)b * d_ps + (uint64_t)pos * N + off
-                                  : lifted + (((uint64_t)b * dg.ndig + j) * E + pos) * N + off;
-        uint64_t raw[16];
+        if constexpr (sizeof(W) == 8) {
+            const uint64_t* src = own ? reinterpret_cast<const uint64_t*>(d) + (uint64_t)b * d_ps + (uint64_t)pos * N + off
+                                      : lifted + (((uint64_t)b * dg.ndig + j) * E + pos) * N + off;
+            uint64_t raw[16];
 #pragma unroll
-        for (int k = 0; k < 16; ++k) raw[k] = src[16 * k];
+            for (int k = 0; k < 16; ++k) raw[k] = src[16 * k];
 #pragma unroll
-        for (int k = 0; k < 16; ++k) k0[k] = u64_to_f64(key0[16 * k]);
+            for (int k = 0; k < 16; ++k) k0[k] = word_to_f64<W>(key0[16 * k]);
 #pragma unroll
-        for (int k = 0; k < 16; ++k) k1[k] = u64_to_f64(key1[16 * k]);
-        if (own) {
+            for (int k = 0; k < 16; ++k) k1[k] = word_to_f64<W>(key1[16 * k]);
+            if (own) {
 #pragma unroll
-            for (int k = 0; k < 16; ++k) x[k] = u64_to_f64(raw[k]);
+                for (int k = 0; k < 16; ++k) x[k] = u64_to_f64(raw[k]);
+            } else {
+#pragma unroll
+                for (int k = 0; k < 16; ++k) x[k] = __longlong_as_double((long long)raw[k]);
+                row_fwd_core_lds(x, lds_ta + rr * 16, tb, j0, lds + rr * kRowPitch, m);
+            }
         } else {
+            // the digit's own limbs come in boundary words, the raised ones as raw doubles: two load shapes, so the
+            // (uniform) choice is a branch; the key slots are requested before it and everything is awaited after it
+            W kr0[16], kr1[16];
 #pragma unroll
-            for (int k = 0; k < 16; ++k) x[k] = __longlong_as_double((long long)raw[k]);
-            row_fwd_core_lds(x, lds_ta + rr * 16, tb, j0, lds + rr * kRowPitch, m);
+            for (int k = 0; k < 16; ++k) kr0[k] = key0[16 * k];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) kr1[k] = key1[16 * k];
+            if (own) {
+                const W* src = d + (uint64_t)b * d_ps + (uint64_t)pos * N + off;
+#pragma unroll
+                for (int k = 0; k < 16; ++k) x[k] = word_to_f64<W>(src[16 * k]);
+            } else {
+                const uint64_t* src = lifted + (((uint64_t)b * dg.ndig + j) * E + pos) * N + off;
+#pragma unroll
+                for (int k = 0; k < 16; ++k) x[k] = load_f64(src + 16 * k);
+                row_fwd_core_lds(x, lds_ta + rr * 16, tb, j0, lds + rr * kRowPitch, m);
+            }
+#pragma unroll
+            for (int k = 0; k < 16; ++k) k0[k] = word_to_f64<W>(kr0[k]);
+#pragma unroll
+            for (int k = 0; k < 16; ++k) k1[k] = word_to_f64<W>(kr1[k]);
         }
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
@@ -310,8 +335,8 @@ __global__ __launch_bounds__(64) void rows_inner_product(TwTables tw, TwTables t
     }
 }
 
-void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, const uint64_t* lifted,
-                               const uint64_t* evk, uint64_t* acc, uint32_t batch, hipStream_t s) {
+void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const void* d, uint64_t d_ps, const uint64_t* lifted,
+                               const void* evk, uint64_t* acc, uint32_t batch, hipStream_t s, bool words32) {
     if (batch == 0) return;
     DigitRanges dg;
     dg.ndig = lv.ndig;
@@ -320,12 +345,19 @@ void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const uint64_t*
         dg.hi[j] = j < lv.ndig ? lv.digit_hi[j] : 0;
     }
     // reads: every raised digit limb per ciphertext and the key (once per call); writes: both accumulators
-    ProfScope ps("rows_inner_product", ((double)batch * (lv.ndig + 2) * lv.E + 2.0 * lv.ndig * lv.E) * c->N * 8.0, s);
+    // d (ell limbs per ciphertext) and the key arrive in boundary words, the raised limbs and the sums in 8 bytes
+    const double wb = words32 ? 0.5 : 1.0;
+    ProfScope ps("rows_inner_product",
+                 ((double)batch * ((lv.ndig * lv.E - lv.ell) + wb * lv.ell + 2.0 * lv.E) + wb * 2.0 * lv.ndig * lv.E) * c->N * 8.0, s);
     const uint32_t tiles = (c->N / 1024) * lv.E;
     const dim3 grid(((tiles + 7) / 8) * 8 * batch), block(64);
-#define KS_LAUNCH(LOGR)                                                                                                     \
-    hipLaunchKernelGGL(rows_inner_product<LOGR>, grid, block, 0, s, c->tw_fwd, c->tw_inv, c->d_mod, dg, lv.ell, lv.E, c->L, c->M, d, \
-                       d_ps, lifted, evk, acc, batch)
+#define KS_LAUNCH(LOGR)                                                                                                            \
+    if (words32)                                                                                                                   \
+        hipLaunchKernelGGL((rows_inner_product<LOGR, uint32_t>), grid, block, 0, s, c->tw_fwd, c->tw_inv, c->d_mod, dg, lv.ell, lv.E, c->L, \
+                           c->M, static_cast<const uint32_t*>(d), d_ps, lifted, static_cast<const uint32_t*>(evk), acc, batch);    \
+    else                                                                                                                           \
+        hipLaunchKernelGGL((rows_inner_product<LOGR, uint64_t>), grid, block, 0, s, c->tw_fwd, c->tw_inv, c->d_mod, dg, lv.ell, lv.E, c->L, \
+                           c->M, static_cast<const uint64_t*>(d), d_ps, lifted, static_cast<const uint64_t*>(evk), acc, batch)
     KS_FOR_LOG_R(c->logN, KS_LAUNCH)
 #undef KS_LAUNCH
 }
@@ -336,12 +368,12 @@ void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const uint64_t*
 // ADDEND: 0 = none, 1 = added as it is, 2 = multiplied by addend_mul[i] first.  Compile-time so that the kernel has no
 // branch: behind a run-time test every addend load became its own load-wait-use round trip.  A launch covers the
 // components comp0 .. comp0 + n_comps - 1 of every batch item.
-template <int LOG_R, bool GATHER, int ADDEND>
+template <int LOG_R, bool GATHER, int ADDEND, typename W = uint64_t>
 __global__ __launch_bounds__(64) void rows_moddown_finish(TwTables tw, const Mod* __restrict__ mods,
                                                           const double* __restrict__ Pinv, const double* __restrict__ addend_mul,
                                                           uint32_t ell, uint32_t E, uint32_t out_limbs,
                                                           const uint64_t* __restrict__ acc, const uint64_t* __restrict__ conv,
-                                                          uint64_t* __restrict__ out, uint64_t out_bs,
+                                                          W* __restrict__ out, uint64_t out_bs,
                                                           const uint64_t* __restrict__ addend, uint64_t addend_bs,
                                                           uint32_t comp0, uint32_t n_comps, uint32_t galois) {
     constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R, LOGN = LOG_R + 8;
@@ -354,7 +386,7 @@ __global__ __launch_bounds__(64) void rows_moddown_finish(TwTables tw, const Mod
     const uint32_t off = row * 256 + j0;
     const uint64_t* src = conv + (((uint64_t)b * 2 + comp) * ell + i) * N + off;
     const uint64_t* ap = acc + (((uint64_t)b * 2 + comp) * E + i) * N + off;
-    uint64_t* op = out + (uint64_t)b * out_bs + ((uint64_t)comp * out_limbs + i) * N + off;
+    W* op = out + (uint64_t)b * out_bs + ((uint64_t)comp * out_limbs + i) * N + off;
     // issue every load up front: the accumulator (and addend) slots do not depend on the transform
     double w[16], a[16], ad[16];
 #pragma unroll
@@ -379,14 +411,26 @@ __global__ __launch_bounds__(64) void rows_moddown_finish(TwTables tw, const Mod
         double r = mulmod_lazy(a[k] - w[k], pinv, m);
         if constexpr (ADDEND == 1) r = reduce_lazy(r + ad[k], m);
         if constexpr (ADDEND == 2) r = reduce_lazy(r + mulmod_lazy(ad[k], admul, m), m);
-        op[16 * k] = f64_to_u64(canon(r, m));
+        op[16 * k] = f64_to_word<W>(canon(r, m));
     }
 }
 
-void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t* acc, const uint64_t* conv, uint64_t* out,
+void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t* acc, const uint64_t* conv, void* out_words,
                                 uint64_t out_bs, const uint64_t* addend, uint64_t addend_bs, uint32_t addend_comps,
-                                uint32_t galois, uint32_t batch, hipStream_t s, const FinishScale* fs) {
+                                uint32_t galois, uint32_t batch, hipStream_t s, const FinishScale* fs, bool out_words32) {
     if (batch == 0) return;
+    uint64_t* out = static_cast<uint64_t*>(out_words);
+    if (out_words32) {  // plain key-switch result in 32-bit words: no addend, no rescaling
+        if (addend || fs) return;
+        ProfScope ps("rows_moddown_finish", (double)batch * lv.ell * 5 * c->N * 8.0, s);
+        const dim3 grid(c->N / 1024, lv.ell, batch * 2), block(64);
+#define KS_LAUNCH(LOGR)                                                                                                          \
+    hipLaunchKernelGGL((rows_moddown_finish<LOGR, false, 0, uint32_t>), grid, block, 0, s, c->tw_fwd, c->d_mod, c->d_Pinv, nullptr,      \
+                       lv.ell, lv.E, lv.ell, acc, conv, static_cast<uint32_t*>(out_words), out_bs, nullptr, 0, 0, 2, 1)
+        KS_FOR_LOG_R(c->logN, KS_LAUNCH)
+#undef KS_LAUNCH
+        return;
+    }
     const double* mul = fs ? fs->mul : c->d_Pinv;
     const double* admul = fs ? fs->addend_mul : nullptr;
     const uint32_t out_limbs = fs ? fs->out_limbs : lv.ell;

@@ -136,7 +136,8 @@ void launch_ntt_inv(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipS
 // The two halves of each transform on their own (the fused pipeline replaces some halves by fused kernels).
 void launch_ntt_fwd_cols(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipStream_t s);
 void launch_ntt_fwd_rows(const ks_ctx* c, const LimbMap& map, uint64_t* data, uint64_t ps_words, uint32_t n_polys, hipStream_t s);
-void launch_ntt_inv_rows(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipStream_t s);
+// in_words32: io.in holds 32-bit words (strides still count elements)
+void launch_ntt_inv_rows(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipStream_t s, bool in_words32 = false);
 // scale_tab: multiplier applied with the final reduction, indexed by the limb's position in `map` (scale_by_idx)
 // or by its modulus id; out_f64: leave the canonical result as a double for a following fused kernel.
 void launch_ntt_inv_cols(const ks_ctx* c, const LimbMap& map, uint64_t* data, uint64_t ps_words, uint32_t n_polys,
@@ -148,8 +149,8 @@ void launch_bconv_ntt_cols(const ks_ctx* c, const BConvPlan* d_plans, uint32_t n
                            uint32_t limbs_moved_per_poly, const uint64_t* y, uint64_t y_ps, uint64_t* out, uint64_t out_ps,
                            uint32_t n_polys, hipStream_t s, double ops_per_coeff = 0.0);
 // Fused row half of the forward transform of the raised digits + inner product with the key.
-void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, const uint64_t* lifted,
-                               const uint64_t* evk, uint64_t* acc, uint32_t batch, hipStream_t s);
+void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const void* d, uint64_t d_ps, const uint64_t* lifted,
+                               const void* evk, uint64_t* acc, uint32_t batch, hipStream_t s, bool words32 = false);
 // Fused row half of the forward transform of the converted limbs + (acc - conv) P^-1 (+ addend).
 // fs == nullptr: multiply by P^-1, addend unscaled, ell output limbs.  Otherwise (merged ModDown + rescale): multiply by
 // fs->mul[i], scale the addend by fs->addend_mul[i], and write only the first fs->out_limbs limbs per component.
@@ -158,10 +159,10 @@ struct FinishScale {
     const double* addend_mul;
     uint32_t out_limbs;
 };
-void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t* acc, const uint64_t* conv, uint64_t* out,
+void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t* acc, const uint64_t* conv, void* out,
                                 uint64_t out_batch_stride, const uint64_t* addend, uint64_t addend_batch_stride,
                                 uint32_t addend_comps, uint32_t galois, uint32_t batch, hipStream_t s,
-                                const FinishScale* fs = nullptr);
+                                const FinishScale* fs = nullptr, bool out_words32 = false);
 // acc[b][comp][limb] += mul * addend[b][comp][limb] for one ciphertext limb of both components (canonical in, canonical out)
 void launch_add_scaled_limb(const ks_ctx* c, uint64_t* acc, uint64_t acc_ps, const uint64_t* addend, uint64_t addend_bs,
                             uint64_t addend_comp_stride, uint32_t limb, double mul, uint32_t batch, hipStream_t s);

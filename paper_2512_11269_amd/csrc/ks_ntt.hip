@@ -70,25 +70,28 @@ __global__ __launch_bounds__(64) void ntt_fwd_rows(TwTables tw, const Mod* __res
     for (int k = 0; k < 16; ++k) p[j0 + 16 * k] = f64_to_u64(canon(reduce_lazy(v[k], m), m));
 }
 
-// inverse, rows first: canonical u64 in, raw doubles out (|x| <= 0.501 p).
-template <int LOG_R>
+// inverse, rows first: canonical residues in (64- or 32-bit words), raw doubles out (|x| <= 0.501 p).
+template <int LOG_R, typename W>
 __global__ __launch_bounds__(64) void ntt_inv_rows(TwTables twi, const Mod* __restrict__ mods, LimbMap map,
-                                                   const uint64_t* in, uint64_t* out, uint64_t in_ps, uint64_t out_ps) {
+                                                   const W* in, uint64_t* out, uint64_t in_ps, uint64_t out_ps) {
     constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R, GROUPS = R / 4;
     __shared__ double lds[4 * kRowPitch];
     const uint32_t tid = threadIdx.x;
     const uint32_t li = blockIdx.x / GROUPS, rg = blockIdx.x - li * GROUPS;
-    const LimbRef L = locate(map, li, in, out, in_ps, out_ps, N);
-    const Mod m = mods[L.mod_id];
+    const uint32_t poly = li / map.n, idx = li - poly * map.n, mod_id = map.mod[idx];
+    const uint64_t off = (uint64_t)map.off[idx] * N;
+    const W* ip = in + poly * in_ps + off;
+    uint64_t* op = out + poly * out_ps + off;
+    const Mod m = mods[mod_id];
     const uint32_t j0 = tid & 15, rr = tid >> 4, row = rg * 4 + rr;
     double v[16];
     PassTwiddles t;
 #pragma unroll
-    for (int k = 0; k < 16; ++k) v[k] = u64_to_f64(L.in[row * 256 + j0 + 16 * k]);
-    load_row_twiddles(t, twi, L.mod_id, N, R + row, j0, m);
+    for (int k = 0; k < 16; ++k) v[k] = word_to_f64<W>(ip[row * 256 + j0 + 16 * k]);
+    load_row_twiddles(t, twi, mod_id, N, R + row, j0, m);
     row_inv_core(v, t, j0, lds + rr * kRowPitch, m);
 #pragma unroll
-    for (int k = 0; k < 16; ++k) store_f64(L.out + row * 256 + j0 + 16 * k, v[k]);
+    for (int k = 0; k < 16; ++k) store_f64(op + row * 256 + j0 + 16 * k, v[k]);
 }
 
 // inverse, columns last, in place: raw doubles in; out = canonical [x * scale]_m where scale is N^-1,
@@ -175,15 +178,18 @@ void launch_ntt_fwd(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipS
     }
 }
 
-void launch_ntt_inv_rows(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipStream_t s) {
+void launch_ntt_inv_rows(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipStream_t s, bool in_words32) {
     const uint32_t limbs = map.n * io.n_polys;
     if (limbs == 0) return;
-    const uint64_t* in = static_cast<const uint64_t*>(io.in);
     uint64_t* out = static_cast<uint64_t*>(io.out);
-    ProfScope ps("ntt_inv_rows", 2.0 * limbs * c->N * 8.0, s);
-#define KS_LAUNCH(LOGR)                                                                                                      \
-    hipLaunchKernelGGL(ntt_inv_rows<LOGR>, dim3(limbs << (LOGR - 2)), dim3(64), 0, s, c->tw_inv, c->d_mod, map, in, out, \
-                       io.in_poly_stride, io.out_poly_stride)
+    ProfScope ps("ntt_inv_rows", (in_words32 ? 1.5 : 2.0) * limbs * c->N * 8.0, s);
+#define KS_LAUNCH(LOGR)                                                                                                          \
+    if (in_words32)                                                                                                              \
+        hipLaunchKernelGGL((ntt_inv_rows<LOGR, uint32_t>), dim3(limbs << (LOGR - 2)), dim3(64), 0, s, c->tw_inv, c->d_mod, map,          \
+                           static_cast<const uint32_t*>(io.in), out, io.in_poly_stride, io.out_poly_stride);                     \
+    else                                                                                                                         \
+        hipLaunchKernelGGL((ntt_inv_rows<LOGR, uint64_t>), dim3(limbs << (LOGR - 2)), dim3(64), 0, s, c->tw_inv, c->d_mod, map,          \
+                           static_cast<const uint64_t*>(io.in), out, io.in_poly_stride, io.out_poly_stride)
     KS_FOR_LOG_R(c->logN, KS_LAUNCH)
 #undef KS_LAUNCH
 }

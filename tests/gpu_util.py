@@ -11,8 +11,8 @@ from oracle import ckks_ref as R
 
 
 class Setup:
-    def __init__(self, logN, L, Kk, dnum):
-        cfg = dict(logN=logN, L=L, K=Kk)
+    def __init__(self, logN, L, Kk, dnum, bits=36):
+        cfg = dict(logN=logN, L=L, K=Kk, bits=bits)
         self.q, self.p = ks_inputs.moduli(cfg)
         self.logN, self.N, self.L, self.K, self.dnum = logN, 1 << logN, L, Kk, dnum
         self.moduli = self.q + self.p

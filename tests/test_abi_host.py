@@ -21,7 +21,7 @@ def test_library_exports_every_declared_symbol():
     lib = K.load_library()
     names = _declared_functions()
     assert {"ks_ctx_create", "ks_ctx_destroy", "ks_workspace_bytes", "ks_strerror", "ks_last_hip_error", "ntt_fwd",
-            "ntt_inv", "bconv", "ks_keyswitch", "ks_rotate_hoisted", "hmult_relin_rescale", "hmult_relin_rescale_merged", "ks_rotate_mac_hoisted", "ks_bsgs_linear_transform"} <= set(names)
+            "ntt_inv", "bconv", "ks_keyswitch", "ks_rotate_hoisted", "hmult_relin_rescale", "hmult_relin_rescale_merged", "ks_rotate_mac_hoisted", "ks_bsgs_linear_transform", "ks_keyswitch_u32"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 

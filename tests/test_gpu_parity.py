@@ -100,6 +100,31 @@ def test_keyswitch_zero_key_gives_zero(boot):
     assert int(out.abs().max()) == 0
 
 
+@pytest.mark.parametrize("logN,L,Kk,dnum,ell,batch", [(12, 4, 2, 2, 4, 3), (12, 5, 2, 3, 3, 9), (16, 24, 8, 3, 24, 2), (14, 6, 3, 2, 6, 1)])
+def test_keyswitch_32bit_words(logN, L, Kk, dnum, ell, batch):
+    """28-bit primes, boundary tensors in 32-bit words: same residues as the 64-bit entry point and as the reference."""
+    st = Setup(logN, L, Kk, dnum, bits=28)
+    assert max(st.moduli) < 1 << 28
+    d = st.uniform(1010, 1, (batch,), list(range(ell)))
+    evk = st.uniform(1010, 2, (dnum, 2), list(range(L + Kk)))
+    ws = workspace(st.ctx, K.KS_OP_KEYSWITCH, ell, batch)
+    out32 = torch.empty((batch, 2, ell, st.N), dtype=torch.int32, device="cuda")
+    K.ks_keyswitch_u32(st.ctx, d.to(torch.int32), ell, evk.to(torch.int32), out32, ws)
+    want = st.ref.keyswitch(host(d), host(evk), ell)
+    assert_equal(out32.to(torch.int64), want)
+    out64 = torch.empty((batch, 2, ell, st.N), dtype=torch.int64, device="cuda")
+    K.ks_keyswitch(st.ctx, d, ell, evk, out64, ws)
+    assert torch.equal(out64, out32.to(torch.int64))
+
+
+def test_keyswitch_32bit_words_needs_small_moduli(small):
+    d = torch.zeros((1, 4, small.N), dtype=torch.int32, device="cuda")
+    evk = torch.zeros((2, 2, 6, small.N), dtype=torch.int32, device="cuda")
+    with pytest.raises(K.KsError):       # 36-bit moduli do not fit
+        K.ks_keyswitch_u32(small.ctx, d, 4, evk, torch.empty((1, 2, 4, small.N), dtype=torch.int32, device="cuda"),
+                           workspace(small.ctx, K.KS_OP_KEYSWITCH, 4, 1))
+
+
 def _run_rotate(st, seed, ell, batch, n_rot):
     ct = st.uniform(seed, 1, (batch, 2), list(range(ell)))
     keys = [st.uniform(seed, 10 + r, (st.ctx.dnum, 2), list(range(st.L + st.K))) for r in range(n_rot)]
