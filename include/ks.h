@@ -12,8 +12,8 @@
  *  - Ring: Z[X]/(X^N + 1), N = 2^logN.  RNS basis: ciphertext primes q_0..q_{L-1} followed by special
  *    primes p_0..p_{K-1}; "modulus id" m in [0, L+K) indexes that concatenated list.  Every modulus is
  *    an odd prime below 2^36 with m = 1 (mod 2N).
- *  - A limb is N residues in 64-bit words, N contiguous.  All residues handed to the library must be
- *    canonical (in [0, modulus)); every output is canonical.
+ *  - A limb is N residues in 64-bit words, N contiguous (ks_keyswitch_u32 alone takes 32-bit words).  All
+ *    residues handed to the library must be canonical (in [0, modulus)); every output is canonical.
  *  - Evaluation domain order is bit-reversed: slot k of a limb holds a(psi^(2*brv(k)+1)), brv = bit
  *    reversal on logN bits, psi = the primitive 2N-th root of unity of that modulus.
  *  - Digits for hybrid key-switching are contiguous groups of alpha = ceil(L/dnum) ciphertext limbs;
@@ -68,8 +68,9 @@ int ks_ctx_create(ks_ctx** out, uint32_t logN, uint32_t L, uint32_t K, uint32_t 
 int ks_ctx_destroy(ks_ctx* ctx);
 
 /* Bytes of device workspace the given operation needs for `batch` ciphertexts at level `ell`
- * (n_rot is only read for KS_OP_ROTATE_HOISTED).  Returns 0 for invalid arguments.  Large batches are
- * processed in internal chunks, so the result stops growing beyond a chunk. */
+ * (n_rot is only read for KS_OP_ROTATE_HOISTED, which also serves ks_rotate_mac_hoisted; KS_OP_HMULT_RELIN_RESCALE
+ * serves both multiplication entry points).  Returns 0 for invalid arguments.  Large batches are processed in
+ * internal chunks, so the result stops growing beyond a chunk. */
 size_t ks_workspace_bytes(const ks_ctx* ctx, int op, uint32_t ell, uint32_t batch, uint32_t n_rot);
 
 const char* ks_strerror(int code);
