@@ -125,6 +125,35 @@ def test_keyswitch_32bit_words_needs_small_moduli(small):
                            workspace(small.ctx, K.KS_OP_KEYSWITCH, 4, 1))
 
 
+def test_keyswitch_is_capturable_in_a_graph(boot):
+    """The entry points allocate nothing and never synchronise, so a call can be recorded into a HIP graph.  The graph is
+    replayed several times with new inputs, eager calls and synchronisations in between; every replay must give what
+    the eager call gives."""
+    ell = 24
+    d = boot.uniform(1011, 1, (2,), list(range(ell)))
+    evk = boot.uniform(1011, 2, (3, 2), list(range(32)))
+    out = torch.empty((2, 2, ell, boot.N), dtype=torch.int64, device="cuda")
+    ws = workspace(boot.ctx, K.KS_OP_KEYSWITCH, ell, 2)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        K.ks_keyswitch(boot.ctx, d, ell, evk, out, ws)          # warm-up outside the capture
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            K.ks_keyswitch(boot.ctx, d, ell, evk, out, ws)
+    torch.cuda.synchronize()
+    eager_out, eager_ws = torch.empty_like(out), torch.empty_like(ws)
+    for rep in range(3):
+        d.copy_(boot.uniform(1011, 10 + rep, (2,), list(range(ell))))   # new input in the captured buffer
+        K.ks_keyswitch(boot.ctx, d, ell, evk, eager_out, eager_ws)
+        torch.cuda.synchronize()
+        out.fill_(-1)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager_out), rep
+    assert_equal(out, boot.ref.keyswitch(host(d), host(evk), ell))
+
+
 def _run_rotate(st, seed, ell, batch, n_rot):
     ct = st.uniform(seed, 1, (batch, 2), list(range(ell)))
     keys = [st.uniform(seed, 10 + r, (st.ctx.dnum, 2), list(range(st.L + st.K))) for r in range(n_rot)]
