@@ -5,15 +5,37 @@ multiplications at N = 2^16), so the reference recomputes sampled batch items / 
 those must match bit-exactly; properties that hold for the whole tensor (exact round trip, residues in
 range) are checked everywhere."""
 
+import os
+
 import numpy as np
 import pytest
 import torch
 
 import ks_inputs
 import paper_2512_11269_amd as K
+from checksum import checksum
 from gpu_util import Setup, assert_equal, host, workspace
 
 pytestmark = pytest.mark.gpu
+
+
+def _golden_checksums():
+    """(workload, item, sub-item) -> (c1, c2): checksums of the CPU reference's full-size outputs, computed ahead of time by
+    tests/golden/make_fullsize_checksums.py (reference and seeded inputs only)."""
+    table = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "fullsize_checksums.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            name, a, b, c1, c2 = line.split()
+            table[(name, int(a), int(b))] = (int(c1, 16), int(c2, 16))
+    return table
+
+
+def _assert_all_items_match(name, items, table):
+    """items: iterable of ((item, sub-item), tensor).  Every one must reproduce the reference's checksums."""
+    bad = [(key, got) for key, t in items if (got := checksum(t)) != table[(name,) + key]]
+    assert not bad, f"{len(bad)} outputs differ from the reference, first {bad[0][0]}"
 
 
 def _in_range(t, mods):
@@ -53,6 +75,8 @@ def test_cfg3_hoisted_rotations_full_size():
         assert_equal(out[b, r], want[0, 0])
     for b in (1, 40):
         assert _in_range(out[b].reshape(-1, ell, st.N), st.q)
+    # every one of the 1024 rotated ciphertexts (24 GiB) against the reference's checksums
+    _assert_all_items_match("cfg3_rotate", (((b, r), out[b, r]) for b in range(B) for r in range(n_rot)), _golden_checksums())
 
 
 def test_cfg5_hmult_full_size():
@@ -69,6 +93,7 @@ def test_cfg5_hmult_full_size():
         want = st.ref.hmult_relin_rescale(host(cta[b])[None], host(ctb[b])[None], host(rlk), ell)
         assert_equal(out[b], want[0])
     assert _in_range(out[100].reshape(-1, ell - 1, st.N), st.q[:ell - 1])
+    _assert_all_items_match("cfg5_hmult", (((b, 0), out[b]) for b in range(B)), _golden_checksums())
 
 
 def test_cfg5_hmult_merged_full_size():
@@ -85,6 +110,7 @@ def test_cfg5_hmult_merged_full_size():
         want = st.ref.hmult_relin_rescale_merged(host(cta[b])[None], host(ctb[b])[None], host(rlk), ell)
         assert_equal(out[b], want[0])
     assert _in_range(out[77].reshape(-1, ell - 1, st.N), st.q[:ell - 1])
+    _assert_all_items_match("cfg5_hmult_merged", (((b, 0), out[b]) for b in range(B)), _golden_checksums())
 
 
 def test_cfg3_rotate_mac_full_size():

@@ -171,3 +171,37 @@ def test_input_generator_is_counter_based():
     z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & mask
     z ^= z >> 31
     assert int(whole[0, 0, 0, 0]) == (z >> 28) % mods[0]
+
+
+def test_checksum_sees_value_and_position():
+    import torch
+    from checksum import checksum
+    x = torch.arange(1000, dtype=torch.int64) * 977 % 68718428161
+    base = checksum(x)
+    y = x.clone(); y[123] += 1
+    assert checksum(y) != base
+    z = x.clone(); z[[5, 900]] = z[[900, 5]]
+    assert checksum(z) != base
+    assert checksum(x.view(10, 100)) == base           # shape does not matter, order does
+
+
+def test_stored_fullsize_checksums_come_from_the_reference(c_oracle_lib):
+    """Spot check of tests/golden/fullsize_checksums.txt: one multiplication of configuration 5 recomputed here."""
+    import os
+    import torch
+    from checksum import checksum
+    path = os.path.join(os.path.dirname(__file__), "golden", "fullsize_checksums.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert sum(r[0] == "cfg3_rotate" for r in rows) == 64 * 16
+    assert sum(r[0] == "cfg5_hmult" for r in rows) == 256 and sum(r[0] == "cfg5_hmult_merged" for r in rows) == 256
+    table = {(r[0], int(r[1]), int(r[2])): (int(r[3], 16), int(r[4], 16)) for r in rows}
+    cfg = ks_inputs.CONFIGS[5]
+    q, p = ks_inputs.moduli(cfg)
+    N, L, seed, b = 1 << cfg["logN"], cfg["L"], cfg["seed"], 201
+    co = c_oracle_lib.COracle(cfg["logN"], q, p, cfg["dnum"], [R.minimal_psi(m, cfg["logN"]) for m in q + p])
+    u64 = lambda t: t.numpy().view(np.uint64)
+    rlk = u64(ks_inputs.uniform_residues(seed, 3, (cfg["dnum"], 2), q + p, N))
+    cta = np.stack([u64(ks_inputs.uniform_slab(seed, 1, 2 * b + c, q, N)) for c in range(2)])[None]
+    ctb = np.stack([u64(ks_inputs.uniform_slab(seed, 2, 2 * b + c, q, N)) for c in range(2)])[None]
+    out = co.hmult_relin_rescale_merged(cta, ctb, rlk, L)[0]
+    assert checksum(torch.from_numpy(np.ascontiguousarray(out).view(np.int64))) == table[("cfg5_hmult_merged", b, 0)]
