@@ -185,7 +185,7 @@ void launch_bconv_ntt_cols(const ks_ctx* c, const BConvPlan* d_plans, uint32_t n
     // Targets per workgroup: fewer targets = more workgroups but more re-reads and re-splits of the sources.  Four (with
     // the two-set source pipeline) is best once the launch has a few workgroups per compute unit; for the
     // single-ciphertext launches three (one-set pipeline) measured best (384 and 256 workgroups: every one resident at
-    // once, none waiting for a second round).
+    // once, none waiting for a slot to free up).
     // KS_BCONV_TS overrides the choice for experiments.
     const uint32_t tiles = 1u << (c->logN - 12);
     int ts = (uint64_t)tiles * n_plans * ((max_targets + 3) / 4) * n_polys >= 512 ? 4 : 3;
