@@ -379,7 +379,10 @@ __global__ __launch_bounds__(64) void rows_moddown_finish(TwTables tw, const Mod
     constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R, LOGN = LOG_R + 8;
     __shared__ double lds[4 * kRowPitch];
     const uint32_t tid = threadIdx.x, rg = blockIdx.x, i = blockIdx.y;
-    const uint32_t b = blockIdx.z / n_comps, comp = comp0 + (blockIdx.z - b * n_comps);
+    // batch items in descending order: the conversion kernel before this one wrote them in ascending order, so the most
+    // recently written ones, still in the last-level cache, are read first (4-5 % on this kernel in batched calls)
+    const uint32_t zz = gridDim.z - 1 - blockIdx.z;
+    const uint32_t b = zz / n_comps, comp = comp0 + (zz - b * n_comps);
     const Mod m = mods[i];
     const double pinv = Pinv[i];
     const uint32_t j0 = tid & 15, rr = tid >> 4, row = rg * 4 + rr;
