@@ -36,9 +36,9 @@ MEASURED_TRAFFIC_BYTES: dict = {
     # profiles/keyswitch_cfg2_hbm_traffic.txt: FETCH_SIZE scaled by 2.0 and WRITE_SIZE by 1.0 (what the same counters
     # read for a 1 GiB device copy), summed, per launch.  The excess over the algorithmic bytes (2-8 %) is twiddle reads.
     ("keyswitch", "rows_inner_product"): 187917623,
-    ("keyswitch", "rows_moddown_finish"): 77648785,
-    ("keyswitch", "bconv_ntt_cols"): 43275590,      # mean of the ModUp and the ModDown launch
-    ("keyswitch", "ntt_inv_rows"): 27089621,
+    ("keyswitch", "rows_moddown_finish"): 77525908,
+    ("keyswitch", "bconv_ntt_cols"): 43279686,      # mean of the ModUp and the ModDown launch
+    ("keyswitch", "ntt_inv_rows"): 27091669,
     ("keyswitch", "ntt_inv_cols"): 21380728,        # mean of the 24-limb and the 16-limb launch
 }
 
