@@ -114,6 +114,19 @@ int ks_keyswitch(const ks_ctx* ctx, const uint64_t* d, uint32_t ell, const uint6
 int ks_keyswitch_u32(const ks_ctx* ctx, const uint32_t* d, uint32_t ell, const uint32_t* evk, uint32_t* out,
                      uint32_t batch, void* ws, size_t ws_bytes, void* stream);
 
+/* ks_keyswitch for callers that cannot allocate device memory and have no workspace to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The workspace is a library-owned static device
+ * array of KS_STATIC_WORKSPACE_BYTES (sized for one ciphertext at N = 2^16, L = 24, K = 8, dnum = 3; every GPU a
+ * context has been created on holds it until the process ends).  Arguments, layouts and results as ks_keyswitch.
+ * KS_EWORKSPACE if ks_workspace_bytes(ctx, KS_OP_KEYSWITCH, ell, batch, 0) exceeds that size (nothing is launched).
+ * The call allocates nothing and does not synchronise.  All calls on one GPU share the one array: calls whose
+ * execution may overlap on a GPU (different streams, different host threads) race on it and must be serialised
+ * by the caller; calls on one stream are safe.  Nothing in the array needs clearing between calls. */
+#define KS_STATIC_WORKSPACE_BYTES ((size_t)232 * 65536 * 8)
+size_t ks_static_workspace_bytes(void);
+int ks_keyswitch_static(const ks_ctx* ctx, const uint64_t* d, uint32_t ell, const uint64_t* evk, uint64_t* out,
+                        uint32_t batch, void* stream);
+
 /* Hoisted rotations (Motivation: hoisting): for every ciphertext the decompose-and-raise of c1 is done once
  * and shared by all n_rot Galois elements.  For each g: sigma_g (X -> X^g) is applied to the raised digits,
  * then inner product with that rotation's key, division by P, and sigma_g(c0) is added to component 0.

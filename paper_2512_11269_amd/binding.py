@@ -54,6 +54,9 @@ def load_library():
     lib.bconv.argtypes = [_vp, _vp, _u32p, ctypes.c_uint32, _vp, _u32p, ctypes.c_uint32, ctypes.c_uint32, _vp]
     lib.ks_keyswitch.argtypes = [_vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
     lib.ks_keyswitch_u32.argtypes = [_vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
+    lib.ks_static_workspace_bytes.restype = ctypes.c_size_t
+    lib.ks_static_workspace_bytes.argtypes = []
+    lib.ks_keyswitch_static.argtypes = [_vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint32, _vp]
     lib.ks_rotate_hoisted.argtypes = [_vp, _vp, ctypes.c_uint32, _u32p, ctypes.POINTER(_vp), ctypes.c_uint32, _vp,
                                       ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
     lib.ks_rotate_mac_hoisted.argtypes = [_vp, _vp, ctypes.c_uint32, _u32p, ctypes.POINTER(_vp), ctypes.POINTER(_vp),
@@ -163,6 +166,17 @@ def ks_keyswitch(ctx: Context, d: torch.Tensor, ell: int, evk: torch.Tensor, out
     batch = d.numel() // (ell * ctx.N)
     _check(load_library().ks_keyswitch(ctx.handle, _dev_ptr(d), ell, _dev_ptr(evk), _dev_ptr(out), batch, _dev_ptr(ws),
                                        ws.numel() * 8, _stream()), "ks_keyswitch")
+
+
+def ks_static_workspace_bytes() -> int:
+    return int(load_library().ks_static_workspace_bytes())
+
+
+def ks_keyswitch_static(ctx: Context, d: torch.Tensor, ell: int, evk: torch.Tensor, out: torch.Tensor) -> None:
+    """ks_keyswitch on the library's own static scratch array: no workspace argument, no allocation."""
+    batch = d.numel() // (ell * ctx.N)
+    _check(load_library().ks_keyswitch_static(ctx.handle, _dev_ptr(d), ell, _dev_ptr(evk), _dev_ptr(out), batch, _stream()),
+           "ks_keyswitch_static")
 
 
 def ks_rotate_hoisted(ctx: Context, ct: torch.Tensor, ell: int, galois, rot_keys, out: torch.Tensor, ws: torch.Tensor) -> None:

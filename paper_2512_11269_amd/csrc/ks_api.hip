@@ -201,7 +201,7 @@ static int check_pipeline_args(const ks_ctx* c, uint32_t ell, uint32_t min_ell, 
 }
 
 // d, evk and out in 64-bit words, or all three in 32-bit words (words32; every modulus then below 2^32).
-static int keyswitch_impl(const ks_ctx* c, const void* d, uint32_t ell, const void* evk, void* out, uint32_t batch, void* ws,
+int ks::keyswitch_impl(const ks_ctx* c, const void* d, uint32_t ell, const void* evk, void* out, uint32_t batch, void* ws,
                           size_t ws_bytes, void* stream, bool words32) {
     int rc = check_pipeline_args(c, ell, 1, d, evk, out, ws);
     if (rc != KS_OK) return rc;

@@ -207,6 +207,7 @@ extern "C" int ks_ctx_create(ks_ctx** out, uint32_t logN, uint32_t L, uint32_t K
     }
     {
         CK(hipSetDevice(device));
+        CK(bind_static_scratch(device));
         // per-modulus constants
         std::vector<Mod> hm(M);
         std::vector<double> hn(M), hP(L), hPm(L);

@@ -195,6 +195,15 @@ void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, u
 void launch_rotate_mac(const ks_ctx* c, const Level& lv, const uint64_t* ct, uint64_t ct_bs, const uint64_t* lifted,
                        const MacRotations& rot, uint64_t* u, uint32_t batch, bool accumulate, hipStream_t s);
 
+// The key-switch chain behind ks_keyswitch / ks_keyswitch_u32 (argument checks included); ws is any device buffer of
+// at least ks_workspace_bytes(KS_OP_KEYSWITCH) bytes, whose contents need no initialisation.
+int keyswitch_impl(const ks_ctx* c, const void* d, uint32_t ell, const void* evk, void* out, uint32_t batch, void* ws,
+                   size_t ws_bytes, void* stream, bool words32);
+
+// Resolve this device's copy of the library-owned static scratch array (ks_static.hip); called by ks_ctx_create with
+// the device current.  Returns a HIP error code.
+hipError_t bind_static_scratch(int device);
+
 // d0 = b1 b2, d1 = a1 b2 + a2 b1, d2 = a1 a2 ; td: [batch][3][ell][N]
 void launch_tensor_product(const ks_ctx* c, const uint64_t* cta, const uint64_t* ctb, uint64_t* td, uint32_t ell,
                            uint32_t batch, hipStream_t s);
