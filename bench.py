@@ -60,12 +60,20 @@ def _keyswitch_bytes(L, K, dnum, N):
     return compulsory, fused
 
 
+def _apply_options(ctx, args):
+    """--opt ID=VALUE pairs: tuning options of the context (see ks_ctx_set_option)."""
+    for item in args.opt or []:
+        k, v = item.split("=")
+        ctx.set_option(int(k), int(v))
+
+
 def bench_keyswitch(args, torch, K, ks_inputs):
     cfg = ks_inputs.CONFIGS[2]
     q, p = ks_inputs.moduli(cfg)
     logN, L, Kk, dnum = cfg["logN"], cfg["L"], cfg["K"], cfg["dnum"]
     N = 1 << logN
     ctx = K.Context(logN, q, p, dnum)
+    _apply_options(ctx, args)
     ws_words = K.ks_workspace_bytes(ctx, K.KS_OP_KEYSWITCH, L, 1) // 8
     sets = []
     for s in range(args.sets):
@@ -257,6 +265,7 @@ def bench_keyswitch_u32(args, torch, K, ks_inputs):
     logN, L, Kk, dnum = cfg["logN"], cfg["L"], cfg["K"], cfg["dnum"]
     N = 1 << logN
     ctx = K.Context(logN, q, p, dnum)
+    _apply_options(ctx, args)
     i32 = lambda t: t.to(torch.int32)
     sets = []
     for sidx in range(args.sets):
@@ -297,6 +306,7 @@ def bench_rotate(args, torch, K, ks_inputs):
     logN, L, B, R, dnum = cfg["logN"], cfg["L"], cfg["batch"], cfg["n_rot"], cfg["dnum"]
     N = 1 << logN
     ctx = K.Context(logN, q, p, dnum)
+    _apply_options(ctx, args)
     ct = ks_inputs.uniform_residues(cfg["seed"], 1, (B, 2), q, N, device="cuda")
     keys = [ks_inputs.uniform_residues(cfg["seed"], 10 + r, (dnum, 2), q + p, N, device="cuda") for r in range(R)]
     gal = ks_inputs.galois_elements(logN, R)
@@ -321,6 +331,7 @@ def bench_rotate_mac(args, torch, K, ks_inputs):
     logN, L, B, R, dnum = cfg["logN"], cfg["L"], cfg["batch"], cfg["n_rot"], cfg["dnum"]
     N = 1 << logN
     ctx = K.Context(logN, q, p, dnum)
+    _apply_options(ctx, args)
     ct = ks_inputs.uniform_residues(cfg["seed"], 1, (B, 2), q, N, device="cuda")
     keys = [ks_inputs.uniform_residues(cfg["seed"], 10 + r, (dnum, 2), q + p, N, device="cuda") for r in range(R)]
     pts = [ks_inputs.uniform_residues(cfg["seed"], 100 + r, (), q + p, N, device="cuda") for r in range(R)]
@@ -348,6 +359,7 @@ def bench_bsgs(args, torch, K, ks_inputs):
     n1 = n2 = 16
     N = 1 << logN
     ctx = K.Context(logN, q, p, dnum)
+    _apply_options(ctx, args)
     gal = ks_inputs.galois_elements(logN, n1 + n2)
     baby, giant = [1] + gal[:n1 - 1], [1] + gal[n1:n1 + n2 - 1]
     key = lambda tid, g: None if g == 1 else ks_inputs.uniform_residues(cfg["seed"], tid, (dnum, 2), q + p, N, device="cuda")
@@ -376,6 +388,7 @@ def bench_hmult(args, torch, K, ks_inputs, merged=False):
     logN, L, B, dnum = cfg["logN"], cfg["L"], cfg["batch"], cfg["dnum"]
     N = 1 << logN
     ctx = K.Context(logN, q, p, dnum)
+    _apply_options(ctx, args)
     cta = ks_inputs.uniform_residues(cfg["seed"], 1, (B, 2), q, N, device="cuda")
     ctb = ks_inputs.uniform_residues(cfg["seed"], 2, (B, 2), q, N, device="cuda")
     rlk = ks_inputs.uniform_residues(cfg["seed"], 3, (dnum, 2), q + p, N, device="cuda")
@@ -400,6 +413,7 @@ def bench_ntt(args, torch, K, ks_inputs):
     logN, L, batch = cfg["logN"], cfg["L"], cfg["batch"]
     N = 1 << logN
     ctx = K.Context(logN, q, p, 1)
+    _apply_options(ctx, args)
     ids = list(range(L))
     data = ks_inputs.uniform_residues(cfg["seed"], 1, (batch,), q, N, device="cuda")
     K.ntt_fwd(ctx, data, ids)
@@ -455,6 +469,7 @@ def main():
     ap.add_argument("--no-batched", action="store_true", help="skip the batched key-switch measurement (counter runs)")
     ap.add_argument("--workload", default="keyswitch", choices=["keyswitch", "keyswitch_u32", "ntt", "rotate", "rotate_mac", "bsgs", "hmult", "hmult_merged", "copy"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--opt", action="append", help="context tuning option ID=VALUE (ks_ctx_set_option), repeatable")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one key-switch stream on one MI355X); run with --gpus 1", file=sys.stderr)

@@ -23,7 +23,7 @@
  *    Pointers marked "host" are ordinary host memory read before the call returns.
  *  - Every compute call is asynchronous on the given HIP stream (`stream` is a hipStream_t passed as
  *    void*; NULL = default stream), performs no device-wide synchronisation and allocates no device
- *    memory (ks_ctx_create and the first bconv call with a new pair of id lists are the exceptions).
+ *    memory (ks_ctx_create and bconv_prepare, the set-up calls, are the exceptions).
  *  - Return value: KS_OK (0) or a negative KS_E* code; ks_strerror() describes it.  On error nothing
  *    has been launched.
  */
@@ -44,7 +44,8 @@ enum {
     KS_EINVAL = -1,     /* bad argument: null / misaligned pointer, unsupported size, bad modulus ... */
     KS_EWORKSPACE = -2, /* workspace pointer null or ws_bytes too small                               */
     KS_EHIP = -3,       /* a HIP runtime call failed; see ks_last_hip_error()                          */
-    KS_ENOMEM = -4      /* host or device allocation failed while building a context                   */
+    KS_ENOMEM = -4,     /* host or device allocation failed while building a context                   */
+    KS_ENOTPREPARED = -5 /* bconv called for a (source, target) list pair that bconv_prepare has not registered */
 };
 
 enum { /* operations for ks_workspace_bytes */
@@ -66,6 +67,16 @@ enum { /* operations for ks_workspace_bytes */
 int ks_ctx_create(ks_ctx** out, uint32_t logN, uint32_t L, uint32_t K, uint32_t dnum,
                   const uint64_t* q, const uint64_t* p, const uint64_t* psi, int device);
 int ks_ctx_destroy(ks_ctx* ctx);
+
+/* Tuning options of a context (results never depend on them).
+ *   KS_OPT_BCONV_KERNEL   which fused base-conversion kernel the pipelines use: 1 = vector fp64 accumulation,
+ *                         2 = int8 matrix cores; 0 (default) = chosen from the launch size.
+ *   KS_OPT_BCONV_TARGETS  target limbs per workgroup (vector kernel, 1..4) or per lane half (matrix-core kernel, 1 or 3) of
+ *                         the fused conversion kernel; 0 (default) = chosen from the launch size.
+ * Not thread-safe against calls in flight on the same context from other host threads.  KS_EINVAL for an unknown
+ * option or a value out of range. */
+enum { KS_OPT_BCONV_TARGETS = 0, KS_OPT_BCONV_KERNEL = 1, KS_OPT_COUNT_ = 2 };
+int ks_ctx_set_option(ks_ctx* ctx, int option, int value);
 
 /* Bytes of device workspace the given operation needs for `batch` ciphertexts at level `ell`
  * (n_rot is only read for KS_OP_ROTATE_HOISTED, which also serves ks_rotate_mac_hoisted; KS_OP_HMULT_RELIN_RESCALE
@@ -89,8 +100,11 @@ int ntt_inv(const ks_ctx* ctx, uint64_t* data, const uint32_t* mod_ids, uint32_t
  * i.e. the value x + u D (0 <= u < n_src) reduced modulo every target t; no correction of u.
  *   in  : device [batch][n_src][N], limb i modulo src_ids[i] (host, n_src <= 16, distinct).
  *   out : device [batch][n_dst][N], limb t modulo dst_ids[t] (host, n_dst <= 255).
- * The first call with a new (src_ids, dst_ids) pair builds and caches its constant table in the context
- * (one small device allocation and a synchronous copy); later calls with that pair allocate nothing. */
+ * The constant table of a (src_ids, dst_ids) pair is built by bconv_prepare (set-up time: one device allocation and a
+ * synchronous copy, kept by the context); bconv itself allocates nothing, never synchronises and returns
+ * KS_ENOTPREPARED for a pair that was not registered.  bconv_prepare is idempotent; it must not run concurrently with
+ * other calls that use the same context. */
+int bconv_prepare(ks_ctx* ctx, const uint32_t* src_ids, uint32_t n_src, const uint32_t* dst_ids, uint32_t n_dst);
 int bconv(const ks_ctx* ctx, const uint64_t* in, const uint32_t* src_ids, uint32_t n_src,
           uint64_t* out, const uint32_t* dst_ids, uint32_t n_dst, uint32_t batch, void* stream);
 

@@ -14,10 +14,12 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libks_mi355x.so")
+# KS_MI355X_LIB selects another build of the same library (e.g. one compiled with different tuning macros)
+_LIB_PATH = os.environ.get("KS_MI355X_LIB") or os.path.join(_HERE, "libks_mi355x.so")
 _lib = None
 
 KS_OP_KEYSWITCH, KS_OP_ROTATE_HOISTED, KS_OP_HMULT_RELIN_RESCALE, KS_OP_BSGS = 1, 2, 3, 4
+KS_OPT_BCONV_TARGETS, KS_OPT_BCONV_KERNEL = 0, 1
 
 _u64p = ctypes.POINTER(ctypes.c_uint64)
 _u32p = ctypes.POINTER(ctypes.c_uint32)
@@ -44,6 +46,7 @@ def load_library():
     lib.ks_ctx_create.argtypes = [ctypes.POINTER(_vp), ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32,
                                   _u64p, _u64p, _u64p, ctypes.c_int]
     lib.ks_ctx_destroy.argtypes = [_vp]
+    lib.ks_ctx_set_option.argtypes = [_vp, ctypes.c_int, ctypes.c_int]
     lib.ks_workspace_bytes.restype = ctypes.c_size_t
     lib.ks_workspace_bytes.argtypes = [_vp, ctypes.c_int, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32]
     lib.ks_strerror.restype = ctypes.c_char_p
@@ -51,6 +54,7 @@ def load_library():
     lib.ks_last_hip_error.restype = ctypes.c_char_p
     lib.ntt_fwd.argtypes = [_vp, _vp, _u32p, ctypes.c_uint32, ctypes.c_uint32, _vp]
     lib.ntt_inv.argtypes = [_vp, _vp, _u32p, ctypes.c_uint32, ctypes.c_uint32, _vp]
+    lib.bconv_prepare.argtypes = [_vp, _u32p, ctypes.c_uint32, _u32p, ctypes.c_uint32]
     lib.bconv.argtypes = [_vp, _vp, _u32p, ctypes.c_uint32, _vp, _u32p, ctypes.c_uint32, ctypes.c_uint32, _vp]
     lib.ks_keyswitch.argtypes = [_vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
     lib.ks_keyswitch_u32.argtypes = [_vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
@@ -127,6 +131,9 @@ class Context:
         _check(lib.ks_ctx_create(ctypes.byref(h), logN, self.L, self.K, dnum, qa, pa, sa, device), "ks_ctx_create")
         self.handle = h
 
+    def set_option(self, option: int, value: int) -> None:
+        _check(load_library().ks_ctx_set_option(self.handle, option, value), "ks_ctx_set_option")
+
     def close(self):
         if getattr(self, "handle", None):
             load_library().ks_ctx_destroy(self.handle)
@@ -154,6 +161,12 @@ def ntt_inv(ctx: Context, data: torch.Tensor, mod_ids) -> None:
     nl = len(mod_ids)
     batch = data.numel() // (nl * ctx.N)
     _check(load_library().ntt_inv(ctx.handle, _dev_ptr(data), _u32_array(mod_ids), nl, batch, _stream()), "ntt_inv")
+
+
+def bconv_prepare(ctx: Context, src_ids, dst_ids) -> None:
+    """Set-up call: builds the constant table of this (source, target) list pair once; bconv needs it."""
+    _check(load_library().bconv_prepare(ctx.handle, _u32_array(src_ids), len(src_ids), _u32_array(dst_ids), len(dst_ids)),
+           "bconv_prepare")
 
 
 def bconv(ctx: Context, x: torch.Tensor, src_ids, out: torch.Tensor, dst_ids) -> None:

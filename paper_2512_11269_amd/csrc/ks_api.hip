@@ -56,7 +56,7 @@ void mod_up(const ks_ctx* c, const Level& lv, const void* d, uint64_t d_ps, uint
         ops += a * (lv.E - a) * 4.5;
     }
     ops += lv.n_new * (3.0 + 4.0 * (c->logN - 8));
-    launch_bconv_ntt_cols(c, lv.d_modup, lv.ndig, lv.max_targets, lv.ell + lv.n_new, coeff, coeff_ps, lifted, lifted_ps, bc, s, ops);
+    launch_bconv_ntt_cols(c, lv.modup, lv.ell + lv.n_new, coeff, coeff_ps, lifted, lifted_ps, bc, s, ops);
     if (finish_rows) launch_ntt_fwd_rows(c, lv.lifted_map, lifted, lifted_ps, bc, s);
 }
 
@@ -74,7 +74,7 @@ void mod_down(const ks_ctx* c, const Level& lv, uint64_t* acc, uint64_t* conv, v
     // the fused inner product already ran the row half of the inverse transform on the special limbs
     if (!special_rows_done) launch_ntt_inv_rows(c, lv.special_map, XformIO{acc, acc, acc_ps, acc_ps, 2 * bc}, s);
     launch_ntt_inv_cols(c, lv.special_map, acc, acc_ps, 2 * bc, c->d_moddown_scale, true, true, s);
-    launch_bconv_ntt_cols(c, lv.d_moddown, 1, lv.ell, c->K + lv.ell, acc, acc_ps, conv, conv_ps, 2 * bc, s, moddown_ops(c, lv));
+    launch_bconv_ntt_cols(c, lv.moddown, c->K + lv.ell, acc, acc_ps, conv, conv_ps, 2 * bc, s, moddown_ops(c, lv));
     launch_rows_moddown_finish(c, lv, acc, conv, out, out_bs, addend, addend_bs, addend_comps, galois, bc, s, nullptr, out_words32);
 }
 
@@ -142,52 +142,71 @@ extern "C" int ntt_inv(const ks_ctx* c, uint64_t* data, const uint32_t* mod_ids,
     return finish("ntt_inv");
 }
 
-extern "C" int bconv(const ks_ctx* c, const uint64_t* in, const uint32_t* src_ids, uint32_t n_src, uint64_t* out,
-                     const uint32_t* dst_ids, uint32_t n_dst, uint32_t batch, void* stream) {
-    if (!c || !in || !out || !src_ids || !dst_ids || !aligned16(in) || !aligned16(out)) return KS_EINVAL;
+// Key of a registered conversion: n_src, source ids, target ids.  Returns KS_OK or KS_EINVAL.
+static int bconv_key(const ks_ctx* c, const uint32_t* src_ids, uint32_t n_src, const uint32_t* dst_ids, uint32_t n_dst,
+                     std::vector<uint32_t>* key) {
+    if (!c || !src_ids || !dst_ids) return KS_EINVAL;
     if (n_src == 0 || n_src > (uint32_t)kMaxSrc || n_dst == 0 || n_dst > 255) return KS_EINVAL;
-    std::vector<uint32_t> key;
-    key.push_back(n_src);
+    key->push_back(n_src);
     for (uint32_t i = 0; i < n_src; ++i) {
         if (src_ids[i] >= c->M) return KS_EINVAL;
         for (uint32_t k = 0; k < i; ++k)
             if (src_ids[k] == src_ids[i]) return KS_EINVAL;
-        key.push_back(src_ids[i]);
+        key->push_back(src_ids[i]);
     }
     for (uint32_t t = 0; t < n_dst; ++t) {
         if (dst_ids[t] >= c->M) return KS_EINVAL;
-        key.push_back(dst_ids[t]);
+        key->push_back(dst_ids[t]);
     }
-    if (batch == 0) return KS_OK;
-    BConvPlan* d_plan = nullptr;
+    return KS_OK;
+}
+
+extern "C" int bconv_prepare(ks_ctx* c, const uint32_t* src_ids, uint32_t n_src, const uint32_t* dst_ids, uint32_t n_dst) {
+    std::vector<uint32_t> key;
+    int rc = bconv_key(c, src_ids, n_src, dst_ids, n_dst, &key);
+    if (rc != KS_OK) return rc;
+    std::lock_guard<std::mutex> lock(c->mu);
+    if (c->bconv_cache.count(key)) return KS_OK;
+    if (hipSetDevice(c->device) != hipSuccess) return KS_EHIP;
+    std::vector<BConvPlan> plan(1);
+    uint16_t src_limb[kMaxSrc];
+    std::vector<uint16_t> dst_limb(n_dst);
+    for (uint32_t i = 0; i < n_src; ++i) src_limb[i] = (uint16_t)i;
+    for (uint32_t t = 0; t < n_dst; ++t) dst_limb[t] = (uint16_t)t;
+    fill_bconv_plan(c, plan.data(), src_ids, src_limb, n_src, dst_ids, dst_limb.data(), n_dst);
+    PlanSet set;
+    hipError_t e = upload_plans(plan.data(), 1, n_src, &set);
+    if (e != hipSuccess) {
+        set_hip_error(e, "bconv_prepare: table upload");
+        return KS_EHIP;
+    }
+    c->bconv_cache[key] = set;
+    return KS_OK;
+}
+
+extern "C" int bconv(const ks_ctx* c, const uint64_t* in, const uint32_t* src_ids, uint32_t n_src, uint64_t* out,
+                     const uint32_t* dst_ids, uint32_t n_dst, uint32_t batch, void* stream) {
+    if (!in || !out || !aligned16(in) || !aligned16(out)) return KS_EINVAL;
+    std::vector<uint32_t> key;
+    int rc = bconv_key(c, src_ids, n_src, dst_ids, n_dst, &key);
+    if (rc != KS_OK) return rc;
+    PlanSet set;
     {
         std::lock_guard<std::mutex> lock(c->mu);
         auto it = c->bconv_cache.find(key);
-        if (it != c->bconv_cache.end()) {
-            d_plan = it->second;
-        } else {
-            std::vector<BConvPlan> plan(1);
-            uint16_t src_limb[kMaxSrc];
-            std::vector<uint16_t> dst_limb(n_dst);
-            for (uint32_t i = 0; i < n_src; ++i) src_limb[i] = (uint16_t)i;
-            for (uint32_t t = 0; t < n_dst; ++t) dst_limb[t] = (uint16_t)t;
-            fill_bconv_plan(c, plan.data(), src_ids, src_limb, n_src, dst_ids, dst_limb.data(), n_dst);
-            hipError_t e = hipMalloc(&d_plan, sizeof(BConvPlan));
-            if (e == hipSuccess) e = hipMemcpy(d_plan, plan.data(), sizeof(BConvPlan), hipMemcpyHostToDevice);
-            if (e != hipSuccess) {
-                set_hip_error(e, "bconv plan upload");
-                if (d_plan) (void)hipFree(d_plan);
-                return KS_EHIP;
-            }
-            c->bconv_cache[key] = d_plan;
-        }
+        if (it == c->bconv_cache.end()) return KS_ENOTPREPARED;  // compute calls never allocate: register with bconv_prepare
+        set = it->second;
     }
+    if (batch == 0) return KS_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint64_t N = c->N;
     for (uint32_t b0 = 0; b0 < batch; b0 += 32768) {
         const uint32_t nb = std::min(batch - b0, 32768u);
-        launch_bconv(c, d_plan, n_src + n_dst, 1, in + (uint64_t)b0 * n_src * N, (uint64_t)n_src * N, out + (uint64_t)b0 * n_dst * N,
-                     (uint64_t)n_dst * N, nb, n_src, s);
+        // the vector kernel unless the matrix-core one is asked for (it measured no faster: both move the same bytes
+        // and the conversion alone is bandwidth-bound)
+        auto launch = c->opt[KS_OPT_BCONV_KERNEL] == 2 ? launch_bconv_mfma : launch_bconv;
+        launch(c, set, n_src + n_dst, in + (uint64_t)b0 * n_src * N, (uint64_t)n_src * N, out + (uint64_t)b0 * n_dst * N,
+               (uint64_t)n_dst * N, nb, s);
     }
     return finish("bconv");
 }
@@ -281,7 +300,7 @@ extern "C" int ks_rotate_hoisted(const ks_ctx* c, const uint64_t* ct, uint32_t e
             const uint32_t polys = 2 * rot.n * bc;
             launch_ntt_inv_rows(c, lv.special_map, XformIO{acc, acc, acc_ps, acc_ps, polys}, s);
             launch_ntt_inv_cols(c, lv.special_map, acc, acc_ps, polys, c->d_moddown_scale, true, true, s);
-            launch_bconv_ntt_cols(c, lv.d_moddown, 1, lv.ell, c->K + lv.ell, acc, acc_ps, conv, conv_ps, polys, s, moddown_ops(c, lv));
+            launch_bconv_ntt_cols(c, lv.moddown, c->K + lv.ell, acc, acc_ps, conv, conv_ps, polys, s, moddown_ops(c, lv));
             for (uint32_t r = 0; r < rot.n; ++r)
                 launch_rows_moddown_finish(c, lv, acc + (uint64_t)r * w.acc, conv + (uint64_t)r * w.conv,
                                            out + (uint64_t)b0 * out_bs + (uint64_t)(r0 + r) * 2 * ell * N, out_bs, c0, ct_bs, 1,
@@ -393,7 +412,7 @@ static void mod_down_merged(const ks_ctx* c, const Level& lv, uint64_t* acc, uin
     launch_ntt_inv_cols(c, lv.merged_map, acc, acc_ps, 2 * bc, lv.d_merged_scale, true, true, s);
     const uint32_t n_src = c->K + 1, n_dst = lv.ell - 1;
     const double ops = (double)n_src * n_dst * 4.5 + n_dst * (3.0 + 4.0 * (c->logN - 8));
-    launch_bconv_ntt_cols(c, lv.d_merged, 1, n_dst, n_src + n_dst, acc, acc_ps, conv, conv_ps, 2 * bc, s, ops);
+    launch_bconv_ntt_cols(c, lv.merged, n_src + n_dst, acc, acc_ps, conv, conv_ps, 2 * bc, s, ops);
     const FinishScale fs{lv.d_Dinv, lv.d_qlinv, n_dst};
     launch_rows_moddown_finish(c, lv, acc, conv, out, out_bs, addend, addend_bs, 2, 1, bc, s, &fs);
 }
@@ -406,7 +425,7 @@ extern "C" int hmult_relin_rescale_merged(const ks_ctx* c, const uint64_t* cta, 
     if (batch == 0) return KS_OK;
     if (ws_bytes < ks_workspace_bytes(c, KS_OP_HMULT_RELIN_RESCALE, ell, batch, 0)) return KS_EWORKSPACE;
     const Level& lv = c->levels[ell - 1];
-    if (!lv.d_merged) return KS_EINVAL;  // K + 1 sources exceed what one conversion takes
+    if (!lv.merged.d_plans) return KS_EINVAL;  // K + 1 sources exceed what one conversion takes
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint64_t N = c->N, ct_bs = 2ull * ell * N, td_bs = 3ull * ell * N, out_bs = 2ull * (ell - 1) * N;
     for (uint32_t b0 = 0; b0 < batch; b0 += kChunk) {

@@ -43,16 +43,17 @@ __global__ __launch_bounds__(256) void bconv_kernel(const BConvPlan* __restrict_
     }
 }
 
-void launch_bconv(const ks_ctx* c, const BConvPlan* d_plans, uint32_t limbs_moved_per_poly, uint32_t n_plans, const uint64_t* in,
-                  uint64_t in_ps, uint64_t* out, uint64_t out_ps, uint32_t n_polys, uint32_t n_src_max, hipStream_t s) {
-    if (n_polys == 0 || n_plans == 0) return;
-    const dim3 grid(c->N / 256, n_plans, n_polys), block(256);
+void launch_bconv(const ks_ctx* c, const PlanSet& plans, uint32_t limbs_moved_per_poly, const uint64_t* in, uint64_t in_ps,
+                  uint64_t* out, uint64_t out_ps, uint32_t n_polys, hipStream_t s) {
+    if (n_polys == 0 || plans.n_plans == 0) return;
+    const dim3 grid(c->N / 256, plans.n_plans, n_polys), block(256);
+    const BConvPlan* d_plans = plans.d_plans;
     ProfScope ps("bconv", (double)limbs_moved_per_poly * n_polys * c->N * 8.0, s);
-    if (n_src_max <= 4)
+    if (plans.shape_src <= 4)
         hipLaunchKernelGGL(bconv_kernel<4>, grid, block, 0, s, d_plans, in, in_ps, out, out_ps, c->N);
-    else if (n_src_max <= 8)
+    else if (plans.shape_src <= 8)
         hipLaunchKernelGGL(bconv_kernel<8>, grid, block, 0, s, d_plans, in, in_ps, out, out_ps, c->N);
-    else if (n_src_max <= 12)
+    else if (plans.shape_src <= 12)
         hipLaunchKernelGGL(bconv_kernel<12>, grid, block, 0, s, d_plans, in, in_ps, out, out_ps, c->N);
     else
         hipLaunchKernelGGL(bconv_kernel<16>, grid, block, 0, s, d_plans, in, in_ps, out, out_ps, c->N);

@@ -76,10 +76,14 @@ static uint32_t h_brv(uint32_t k, uint32_t bits) {
 static Mod make_mod(uint64_t m) { return Mod{(double)m, 1.0 / (double)m}; }
 
 void fill_bconv_plan(const ks_ctx* c, BConvPlan* plan, const uint32_t* src_ids, const uint16_t* src_limb, uint32_t n_src,
-                     const uint32_t* dst_ids, const uint16_t* dst_limb, uint32_t n_dst) {
+                     const uint32_t* dst_ids, const uint16_t* dst_limb, uint32_t n_dst, uint32_t shape_src) {
     memset(plan, 0, sizeof(BConvPlan));
+    if (shape_src < n_src) shape_src = n_src;
     plan->n_src = n_src;
     plan->n_dst = n_dst;
+    plan->mfma_nm = (shape_src + 5) / 6;
+    plan->mfma_nps = (shape_src + 2 * plan->mfma_nm - 1) / (2 * plan->mfma_nm);
+    for (uint32_t k = 0; k < (uint32_t)kMfmaSlots * 3; ++k) plan->mfma_src_limb[k] = src_limb[k < n_src ? k : 0];
     for (uint32_t i = 0; i < n_src; ++i) {
         const uint64_t si = c->mod[src_ids[i]];
         uint64_t prod = 1;
@@ -97,6 +101,9 @@ void fill_bconv_plan(const ks_ctx* c, BConvPlan* plan, const uint32_t* src_ids, 
         plan->dst_limb[t] = dst_limb[t];
         plan->dst_mod[t] = make_mod(mt);
         plan->dst_mod_id[t] = (uint8_t)dst_ids[t];
+        plan->trec[t].m = plan->dst_mod[t];
+        plan->trec[t].mod_id = dst_ids[t];
+        plan->trec[t].limb = dst_limb[t];
         for (uint32_t i = 0; i < n_src; ++i) {
             uint64_t prod = 1 % mt;
             for (uint32_t k = 0; k < n_src; ++k)
@@ -109,8 +116,40 @@ void fill_bconv_plan(const ks_ctx* c, BConvPlan* plan, const uint32_t* src_ids, 
             plan->hat3[t][i][0] = (double)(prod & 0xFFFu);
             plan->hat3[t][i][1] = (double)((prod >> 12) & 0xFFFu);
             plan->hat3[t][i][2] = (double)(prod >> 24);
+            // matrix-core operand rows: digit b of centred([(D / s_i) 256^a]_t), at the byte that pairs with digit a of source i
+            const uint32_t slot = i / plan->mfma_nps, e = i % plan->mfma_nps;
+            for (int a = 0; a < kMfmaPlanes; ++a) {
+                const uint64_t f = h_mulmod(prod, (1ull << (8 * a)) % mt, mt);
+                int64_t v = f > mt / 2 ? -(int64_t)(mt - f) : (int64_t)f;
+                for (int b = 0; b < kMfmaPlanes; ++b) {
+                    int64_t digit = b + 1 < kMfmaPlanes ? ((v + 128) & 255) - 128 : v;   // the last digit takes what is left (|.| <= 9)
+                    v = (v - digit) / 256;
+                    plan->afac[t][b][slot][a < 4 ? 4 * e + a : 12 + e] = (int8_t)digit;
+                }
+            }
         }
     }
+}
+
+hipError_t upload_plans(const BConvPlan* host_plans, uint32_t n_plans, uint32_t shape_src, PlanSet* out) {
+    *out = PlanSet{};
+    if (n_plans == 0 || n_plans > (uint32_t)kMaxDigits) return hipErrorInvalidValue;
+    hipError_t e = hipMalloc(&out->d_plans, sizeof(BConvPlan) * n_plans);
+    if (e != hipSuccess) return e;
+    e = hipMemcpy(out->d_plans, host_plans, sizeof(BConvPlan) * n_plans, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        (void)hipFree(out->d_plans);
+        out->d_plans = nullptr;
+        return e;
+    }
+    out->n_plans = n_plans;
+    out->shape_src = shape_src;
+    for (uint32_t j = 0; j < n_plans; ++j) {
+        out->max_targets = std::max(out->max_targets, host_plans[j].n_dst);
+        out->meta.plan[j].n_dst = host_plans[j].n_dst;
+        for (int k = 0; k < kMfmaSlots * 3; ++k) out->meta.plan[j].src_limb[k] = host_plans[j].mfma_src_limb[k];
+    }
+    return hipSuccess;
 }
 
 static thread_local std::string g_hip_error;
@@ -141,8 +180,24 @@ extern "C" const char* ks_strerror(int code) {
         case KS_EWORKSPACE: return "workspace missing or too small";
         case KS_EHIP: return "HIP runtime error (see ks_last_hip_error)";
         case KS_ENOMEM: return "out of memory";
+        case KS_ENOTPREPARED: return "conversion not registered (call bconv_prepare first)";
         default: return "unknown error code";
     }
+}
+
+extern "C" int ks_ctx_set_option(ks_ctx* c, int option, int value) {
+    if (!c) return KS_EINVAL;
+    switch (option) {
+        case KS_OPT_BCONV_TARGETS:
+            if (value < 0 || value > 4) return KS_EINVAL;
+            break;
+        case KS_OPT_BCONV_KERNEL:
+            if (value < 0 || value > 2) return KS_EINVAL;
+            break;
+        default: return KS_EINVAL;
+    }
+    c->opt[option] = value;
+    return KS_OK;
 }
 
 extern "C" int ks_ctx_destroy(ks_ctx* c) {
@@ -159,15 +214,15 @@ extern "C" int ks_ctx_destroy(ks_ctx* c) {
     (void)hipFree(c->d_trow);
     (void)hipFree(c->d_w16);
     for (auto& lv : c->levels) {
-        (void)hipFree(lv.d_modup);
-        (void)hipFree(lv.d_moddown);
+        (void)hipFree(lv.modup.d_plans);
+        (void)hipFree(lv.moddown.d_plans);
         (void)hipFree(lv.d_qlinv);
         (void)hipFree(lv.d_modup_scale);
-        (void)hipFree(lv.d_merged);
+        (void)hipFree(lv.merged.d_plans);
         (void)hipFree(lv.d_merged_scale);
         (void)hipFree(lv.d_Dinv);
     }
-    for (auto& kv : c->bconv_cache) (void)hipFree(kv.second);
+    for (auto& kv : c->bconv_cache) (void)hipFree(kv.second.d_plans);
     delete c;
     return KS_OK;
 }
@@ -285,6 +340,7 @@ extern "C" int ks_ctx_create(ks_ctx** out, uint32_t logN, uint32_t L, uint32_t K
             auto ext_id = [&](uint32_t pos) { return pos < ell ? pos : L + (pos - ell); };
             std::vector<BConvPlan> plans(lv.ndig);
             lv.lifted_map.n = 0;
+            const uint32_t max_src = std::min(alpha, ell);
             for (uint32_t j = 0; j < lv.ndig; ++j) {
                 const uint32_t lo = j * alpha, hi = std::min(lo + alpha, ell);
                 lv.digit_lo[j] = lo;
@@ -303,14 +359,12 @@ extern "C" int ks_ctx_create(ks_ctx** out, uint32_t logN, uint32_t L, uint32_t K
                     lv.lifted_map.n++;
                 }
                 fill_bconv_plan(c, &plans[j], src_ids, src_limb, hi - lo, dst_ids.data(), dst_limb.data(),
-                                (uint32_t)dst_ids.size());
+                                (uint32_t)dst_ids.size(), max_src);
             }
             lv.n_new = lv.lifted_map.n;
             {
                 std::vector<double> sc(ell);
-                lv.max_targets = 0;
                 for (uint32_t j = 0; j < lv.ndig; ++j) {
-                    lv.max_targets = std::max(lv.max_targets, plans[j].n_dst);
                     for (uint32_t i = lv.digit_lo[j]; i < lv.digit_hi[j]; ++i) {
                         const uint64_t qi = c->mod[i];
                         const uint64_t dinv = (uint64_t)plans[j].src_inv[i - lv.digit_lo[j]];
@@ -320,8 +374,7 @@ extern "C" int ks_ctx_create(ks_ctx** out, uint32_t logN, uint32_t L, uint32_t K
                 CK(hipMalloc(&lv.d_modup_scale, sizeof(double) * ell));
                 CK(hipMemcpy(lv.d_modup_scale, sc.data(), sizeof(double) * ell, hipMemcpyHostToDevice));
             }
-            CK(hipMalloc(&lv.d_modup, sizeof(BConvPlan) * lv.ndig));
-            CK(hipMemcpy(lv.d_modup, plans.data(), sizeof(BConvPlan) * lv.ndig, hipMemcpyHostToDevice));
+            CK(upload_plans(plans.data(), lv.ndig, max_src, &lv.modup));
 
             BConvPlan down;
             uint32_t src_ids[kMaxSrc];
@@ -343,8 +396,7 @@ extern "C" int ks_ctx_create(ks_ctx** out, uint32_t logN, uint32_t L, uint32_t K
                 lv.q_map.mod[i] = (uint8_t)i;
             }
             fill_bconv_plan(c, &down, src_ids, src_limb, K, dst_ids.data(), dst_limb.data(), ell);
-            CK(hipMalloc(&lv.d_moddown, sizeof(BConvPlan)));
-            CK(hipMemcpy(lv.d_moddown, &down, sizeof(BConvPlan), hipMemcpyHostToDevice));
+            CK(upload_plans(&down, 1, K, &lv.moddown));
 
             if (ell >= 2 && K + 1 <= (uint32_t)kMaxSrc) {
                 BConvPlan merged;
@@ -361,8 +413,7 @@ extern "C" int ks_ctx_create(ks_ctx** out, uint32_t logN, uint32_t L, uint32_t K
                 lv.last_map.off[0] = (uint16_t)(ell - 1);
                 lv.last_map.mod[0] = (uint8_t)(ell - 1);
                 fill_bconv_plan(c, &merged, m_ids, m_limb, K + 1, dst_ids.data(), dst_limb.data(), ell - 1);
-                CK(hipMalloc(&lv.d_merged, sizeof(BConvPlan)));
-                CK(hipMemcpy(lv.d_merged, &merged, sizeof(BConvPlan), hipMemcpyHostToDevice));
+                CK(upload_plans(&merged, 1, K + 1, &lv.merged));
                 std::vector<double> sc(K + 1), dinv(ell - 1);
                 for (uint32_t k = 0; k <= K; ++k) {
                     const uint64_t sk = c->mod[m_ids[k]];

@@ -11,8 +11,6 @@
 // Base conversion is coefficient-wise and the column half touches a fixed set of coefficient positions per
 // tile, so the first fusion is legal; the inner product and the final scale are slot-wise and the row half
 // produces complete slots, so the other two are.
-#include <stdlib.h>
-
 #include "ks_internal.hpp"
 #include "ks_tiles.hpp"
 
@@ -178,21 +176,30 @@ __global__ __launch_bounds__(256) void bconv_ntt_cols(const double* __restrict__
     }
 }
 
-void launch_bconv_ntt_cols(const ks_ctx* c, const BConvPlan* d_plans, uint32_t n_plans, uint32_t max_targets,
-                           uint32_t limbs_moved_per_poly, const uint64_t* y, uint64_t y_ps, uint64_t* out, uint64_t out_ps,
-                           uint32_t n_polys, hipStream_t s, double ops_per_coeff) {
+void launch_bconv_ntt_cols(const ks_ctx* c, const PlanSet& plans, uint32_t limbs_moved_per_poly, const uint64_t* y, uint64_t y_ps,
+                           uint64_t* out, uint64_t out_ps, uint32_t n_polys, hipStream_t s, double ops_per_coeff) {
+    const uint32_t n_plans = plans.n_plans, max_targets = plans.max_targets;
+    const BConvPlan* d_plans = plans.d_plans;
     if (n_polys == 0 || n_plans == 0) return;
+    // Which kernel: on launches too small to fill the chip (a single ciphertext) the matrix-core kernel measured 4-5 %
+    // faster per key-switch; once a launch has a few workgroups per compute unit the vector kernel wins by 13-24 %.
+    const uint32_t tiles16 = 1u << (c->logN - 12);
+    const bool small_launch = (uint64_t)tiles16 * n_plans * ((max_targets + 3) / 4) * n_polys < 512;
+    const int kernel = c->opt[KS_OPT_BCONV_KERNEL] ? c->opt[KS_OPT_BCONV_KERNEL] : (small_launch && c->logN == 16 ? 2 : 1);
+    if (kernel == 2) {
+        ProfScope ps("bconv_mfma_ntt_cols", (double)limbs_moved_per_poly * n_polys * c->N * 8.0, s, ops_per_coeff * n_polys * c->N);
+        const int tl = c->opt[KS_OPT_BCONV_TARGETS] >= 1 && c->opt[KS_OPT_BCONV_TARGETS] <= 3 ? c->opt[KS_OPT_BCONV_TARGETS] : 3;
+        launch_bconv_mfma_ntt_cols(c, plans, y, y_ps, out, out_ps, n_polys, tl, s);
+        return;
+    }
     // Targets per workgroup: fewer targets = more workgroups but more re-reads and re-splits of the sources.  Four (with
     // the two-set source pipeline) is best once the launch has a few workgroups per compute unit; for the
     // single-ciphertext launches three (one-set pipeline) measured best (384 and 256 workgroups: every one resident at
     // once, none waiting for a slot to free up).
-    // KS_BCONV_TS overrides the choice for experiments.
+    // The context option KS_OPT_BCONV_TARGETS overrides the choice.
     const uint32_t tiles = 1u << (c->logN - 12);
     int ts = (uint64_t)tiles * n_plans * ((max_targets + 3) / 4) * n_polys >= 512 ? 4 : 3;
-    if (const char* e = getenv("KS_BCONV_TS")) {
-        const int v = atoi(e);
-        if (v >= 1 && v <= 4) ts = v;
-    }
+    if (c->opt[KS_OPT_BCONV_TARGETS] >= 1 && c->opt[KS_OPT_BCONV_TARGETS] <= 4) ts = c->opt[KS_OPT_BCONV_TARGETS];
     if (c->logN != 16 && ts < 3) ts = 3;  // the other ring degrees come with the two production shapes only
     const uint32_t n_subsets = (max_targets + ts - 1) / ts;
     const dim3 grid(tiles, n_plans * n_subsets, n_polys), block(256);

@@ -14,6 +14,8 @@
 namespace ks {
 
 constexpr int kMaxSrc = 16;     // source limbs of one base conversion (alpha or K)
+constexpr int kMfmaSlots = 6;   // 16-byte operand slots of the matrix-core conversion: 3 instructions x 2 lane halves, 3 sources each
+constexpr int kMfmaPlanes = 5;  // signed base-256 digits of a 36-bit residue or factor
 constexpr int kMaxDst = 256;    // target limbs of one base conversion
 constexpr int kMaxLimbs = 192;  // limbs of one polynomial bundle addressed by a LimbMap
 constexpr int kMaxDigits = 8;
@@ -42,14 +44,48 @@ struct BConvPlan {
     // hats[t][i][k], k = 0..2: centred([(D / s_i) 2^(12 k)]_t) * 2^(-12 k), the factors that go with the three pieces
     // of a split source residue (split3); [3] pads the row to 32 bytes.  Zero for padding sources.
     double hats[kMaxDst][kMaxSrc][4];
+    // Matrix-core form (int8 MFMA, see ks_bconv_mfma.hip).  A source residue y = sum_a d_a 256^a is cut into five signed
+    // digits; for every digit position a the factor F_a = centred([(D / s_i) 256^a]_t) is cut the same way into digits
+    // e_b, so that y (D / s_i) = sum_b 256^b sum_a d_a e_{a,b} (mod t): five small integer sums per target, each a dot
+    // product over (source, a) that the matrix cores accumulate exactly in 32 bits.
+    // The sources are dealt to operand slots of 16 bytes, mfma_nps (1..3) sources per slot, slot = 2 * instruction + lane
+    // half; inside a slot, bytes 4 e + a (a < 4) belong to digit a of the slot's e-th source and byte 12 + e to its digit 4.
+    // afac[t][b][slot] is the A-operand row of target t, digit plane b, in that byte order (zero where a slot has no source).
+    uint32_t mfma_nm, mfma_nps;                 // instructions per block (1..3), sources per slot
+    uint32_t mfma_src_limb[kMfmaSlots * 3];     // limb of slot-major source k (padding: the first source's limb)
+    alignas(16) int8_t afac[kMaxDst][kMfmaPlanes][kMfmaSlots][16];
+    // everything the matrix-core kernel needs to know about a target, in one 32-byte record (one load per lane)
+    struct alignas(32) TargetRec {
+        Mod m;
+        uint32_t mod_id, limb, pad[2];
+    } trec[kMaxDst];
+};
+
+// The part of a plan a kernel launch carries by value in its arguments (no dependent load before the first source
+// read): target count and source limbs in operand-slot order.
+struct PlanMeta {
+    uint32_t n_dst;
+    uint32_t src_limb[kMfmaSlots * 3];
+};
+struct LaunchMeta {
+    PlanMeta plan[kMaxDigits];
+};
+// The plans of one conversion launch (one per digit for ModUp, a single one otherwise): device copies plus the host
+// facts the launchers need.
+struct PlanSet {
+    BConvPlan* d_plans = nullptr;  // [n_plans] device
+    uint32_t n_plans = 0;
+    uint32_t max_targets = 0;      // largest target count of a plan
+    uint32_t shape_src = 0;        // source count the matrix-core operand slots were laid out for (the largest of the plans)
+    LaunchMeta meta{};
 };
 
 // Everything the key-switching pipeline needs at one level ell.
 struct Level {
     uint32_t ell = 0, ndig = 0, E = 0;     // E = ell + K extended limb count
     uint32_t n_new = 0;                    // sum over digits of (E - alpha_j): limbs produced by ModUp
-    BConvPlan* d_modup = nullptr;          // [ndig] device
-    BConvPlan* d_moddown = nullptr;        // [1] device
+    PlanSet modup;                         // one plan per digit
+    PlanSet moddown;
     LimbMap lifted_map;                    // new limbs inside the [ndig][E][N] lifted bundle
     LimbMap special_map;                   // the K special limbs inside an [E][N] accumulator
     LimbMap q_map;                         // limbs 0..ell-1, modulus id = limb index
@@ -57,13 +93,12 @@ struct Level {
     double* d_qlinv = nullptr;             // [ell-1] device: q_{ell-1}^-1 mod q_i (rescale)
     double* d_modup_scale = nullptr;       // [ell] device: N^-1 (D_j / q_i)^-1 mod q_i, j = digit of limb i
     // ModDown merged with rescale: one conversion from {p_0..p_{K-1}, q_{ell-1}} (product D) to q_0..q_{ell-2}
-    BConvPlan* d_merged = nullptr;         // [1] device (ell >= 2)
+    PlanSet merged;                        // d_plans == nullptr when unavailable (ell < 2 or K + 1 sources too many)
     LimbMap merged_map;                    // the K special limbs and limb ell-1 inside an [E][N] accumulator
     LimbMap last_map;                      // limb ell-1 alone
     double* d_merged_scale = nullptr;      // [K+1] device: N^-1 (D / s)^-1 mod s, s in merged_map order
     double* d_Dinv = nullptr;              // [ell-1] device: D^-1 mod q_i
     double Pmod_last = 0.0;                // P mod q_{ell-1}
-    uint32_t max_targets = 0;              // largest target count of a ModUp digit
 };
 
 }  // namespace ks
@@ -84,8 +119,9 @@ struct ks_ctx {
     double* d_w16 = nullptr;              // [2][M][8] powers of the primitive 16th root, forward then inverse
     ks::TwTables tw_fwd{}, tw_inv{};      // the three tables of each direction bundled for the row kernels
     std::vector<ks::Level> levels;        // index ell-1
+    int opt[KS_OPT_COUNT_] = {};          // ks_ctx_set_option values, index = option id
     mutable std::mutex mu;
-    mutable std::map<std::vector<uint32_t>, ks::BConvPlan*> bconv_cache;  // key: n_src, src ids, dst ids
+    mutable std::map<std::vector<uint32_t>, ks::PlanSet> bconv_cache;  // key: n_src, src ids, dst ids
 };
 
 namespace ks {
@@ -94,8 +130,10 @@ namespace ks {
 uint64_t h_mulmod(uint64_t a, uint64_t b, uint64_t m);
 uint64_t h_powmod(uint64_t a, uint64_t e, uint64_t m);
 uint64_t h_invmod(uint64_t a, uint64_t m);
+// shape_src: the source count that fixes the operand-slot layout of the matrix-core tables (all plans of one launch must
+// agree on it); 0 = n_src.
 void fill_bconv_plan(const ks_ctx* c, BConvPlan* plan, const uint32_t* src_ids, const uint16_t* src_limb, uint32_t n_src,
-                     const uint32_t* dst_ids, const uint16_t* dst_limb, uint32_t n_dst);
+                     const uint32_t* dst_ids, const uint16_t* dst_limb, uint32_t n_dst, uint32_t shape_src = 0);
 
 // thread-local HIP error text
 void set_hip_error(hipError_t e, const char* where);
@@ -145,9 +183,13 @@ void launch_ntt_inv_cols(const ks_ctx* c, const LimbMap& map, uint64_t* data, ui
 
 // Fused base conversion + column half of the forward transform.  y: pre-scaled canonical doubles
 // y_i = [x_i N^-1 (D/s_i)^-1]; out: raw doubles ready for the row half.  One plan per blockIdx.y group.
-void launch_bconv_ntt_cols(const ks_ctx* c, const BConvPlan* d_plans, uint32_t n_plans, uint32_t max_targets,
-                           uint32_t limbs_moved_per_poly, const uint64_t* y, uint64_t y_ps, uint64_t* out, uint64_t out_ps,
-                           uint32_t n_polys, hipStream_t s, double ops_per_coeff = 0.0);
+void launch_bconv_ntt_cols(const ks_ctx* c, const PlanSet& plans, uint32_t limbs_moved_per_poly, const uint64_t* y, uint64_t y_ps,
+                           uint64_t* out, uint64_t out_ps, uint32_t n_polys, hipStream_t s, double ops_per_coeff = 0.0);
+// The same conversion + column half on the matrix cores (ks_bconv_mfma.hip); tl = targets per lane half, 1..3.
+void launch_bconv_mfma_ntt_cols(const ks_ctx* c, const PlanSet& plans, const uint64_t* y, uint64_t y_ps, uint64_t* out,
+                                uint64_t out_ps, uint32_t n_polys, int tl, hipStream_t s);
+// Upload host plans as a PlanSet (allocates; ks_ctx_create and bconv plan registration only).  Returns a HIP error code.
+hipError_t upload_plans(const BConvPlan* host_plans, uint32_t n_plans, uint32_t shape_src, PlanSet* out);
 // Fused row half of the forward transform of the raised digits + inner product with the key.
 void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const void* d, uint64_t d_ps, const uint64_t* lifted,
                                const void* evk, uint64_t* acc, uint32_t batch, hipStream_t s, bool words32 = false);
@@ -172,9 +214,11 @@ void launch_add_scaled_limb(const ks_ctx* c, uint64_t* acc, uint64_t acc_ps, con
 void launch_rescale_fused(const ks_ctx* c, const Level& lv, const uint64_t* x, const uint64_t* last, uint64_t* spread,
                           uint64_t* out, uint32_t n_polys, hipStream_t s);
 
-void launch_bconv(const ks_ctx* c, const BConvPlan* d_plans, uint32_t limbs_moved_per_poly, uint32_t n_plans,
-                  const uint64_t* in, uint64_t in_poly_stride, uint64_t* out, uint64_t out_poly_stride,
-                  uint32_t n_polys, uint32_t n_src_max, hipStream_t s);
+void launch_bconv(const ks_ctx* c, const PlanSet& plans, uint32_t limbs_moved_per_poly, const uint64_t* in, uint64_t in_poly_stride,
+                  uint64_t* out, uint64_t out_poly_stride, uint32_t n_polys, hipStream_t s);
+// the same conversion on the matrix cores (ks_bconv_mfma.hip)
+void launch_bconv_mfma(const ks_ctx* c, const PlanSet& plans, uint32_t limbs_moved_per_poly, const uint64_t* in, uint64_t in_poly_stride,
+                       uint64_t* out, uint64_t out_poly_stride, uint32_t n_polys, hipStream_t s);
 
 // Rotations handled by one launch of the gather kernels (more are chained).
 constexpr int kMacRotations = 16;

@@ -64,11 +64,21 @@ def test_bconv_matches_reference(which, src, dst, batch, request):
     st = request.getfixturevalue(which)
     x = st.uniform(8, 2, (batch,), src)
     out = torch.empty((batch, len(dst), st.N), dtype=torch.int64, device="cuda")
+    K.bconv_prepare(st.ctx, src, dst)
     K.bconv(st.ctx, x, src, out, dst)
     assert_equal(out, st.ref.bconv(host(x), src, dst))
     out2 = torch.empty_like(out)
-    K.bconv(st.ctx, x, src, out2, dst)          # second call takes the cached-table path
+    K.bconv_prepare(st.ctx, src, dst)           # registering twice is harmless
+    K.bconv(st.ctx, x, src, out2, dst)
     assert torch.equal(out, out2)
+
+
+def test_bconv_needs_registration(small):
+    """Compute calls never allocate: a conversion whose table was not built by bconv_prepare is refused."""
+    x = small.uniform(8, 3, (1,), [1, 2])
+    out = torch.empty((1, 1, small.N), dtype=torch.int64, device="cuda")
+    with pytest.raises(K.KsError, match="not registered"):
+        K.bconv(small.ctx, x, [1, 2], out, [5])
 
 
 def _run_keyswitch(st, seed, ell, batch):

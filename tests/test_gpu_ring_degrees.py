@@ -31,6 +31,7 @@ def test_transforms_and_conversion(st):
     src, dst = [5, 6], [0, 1, 2, 3, 4]
     xin = st.uniform(3001, 2, (2,), src)
     out = torch.empty((2, len(dst), st.N), dtype=torch.int64, device="cuda")
+    K.bconv_prepare(st.ctx, src, dst)
     K.bconv(st.ctx, xin, src, out, dst)
     assert_equal(out, st.ref.bconv(host(xin), src, dst))
 
