@@ -19,46 +19,9 @@
 // thread (pair p = 32 wave + lane % 32, half h) walks the 16 positions (row r0 + 16 k, column c) of pair p, exactly the
 // points the column butterflies need in its registers afterwards.
 #include "ks_internal.hpp"
-#include "ks_tiles.hpp"
+#include "ks_tasks.hpp"
 
 namespace ks {
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-
-// Adding 2^52 + 0x80808080 to a canonical residue y < 2^36 (held as a double) leaves y + 0x80808080 in the mantissa:
-// its low four bytes, each with the top bit flipped, are the signed digits d_0..d_3 (digit = byte - 128), and bits
-// 32..39 are the non-negative digit d_4 <= 16.
-constexpr double kDigitBias = 4503599627370496.0 + 2155905152.0;
-
-#ifdef KS_EXP_TRACE
-// phase timestamps of every wavefront (tuning builds only)
-__device__ unsigned long long g_trace[1 << 15][8];
-#define KS_TRACE(phase)                                                                                               \
-    do {                                                                                                              \
-        if ((threadIdx.x & 63u) == 0) {                                                                               \
-            const uint32_t w_ = ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 4 + (threadIdx.x >> 6); \
-            if (w_ < (1u << 15)) g_trace[w_][phase] = __builtin_readcyclecounter();                                   \
-        }                                                                                                             \
-    } while (0)
-#else
-#define KS_TRACE(phase)
-#endif
-
-// Twiddles of the column butterflies, staged in LDS (both lane halves of a workgroup need different tables, so they
-// cannot ride in scalar registers, and 30 vector registers per target would cost a wavefront of occupancy):
-//   first pass : entries 1..15 = W[j], the sub-tree below heap node 1, the same for every thread of a half;
-//   second pass: for every row group r0, entries (1 << ul) + g = W[(1 << (E + ul)) + (r0 << ul) + g] for the last E local
-//                stages ul = 4 - E .. 3 (for E = 4 the sub-tree below node 16 + r0).
-// Layout per (half, target): [1 + S][16] doubles, S = R / 16 row groups.
-template <int LOG_R>
-__device__ __forceinline__ uint32_t col_twiddle_index(uint32_t slot, uint32_t j) {
-    constexpr int E = LOG_R - 4;
-    if (j == 0) return 0;
-    if (slot == 0) return j;
-    const uint32_t ul = 31u - __clz(j), g = j - (1u << ul), r0 = slot - 1;
-    return (int)ul >= 4 - E ? (1u << (E + ul)) + (r0 << ul) + g : 0u;
-}
 
 // Workgroups per compute unit the register allocation must leave room for: without a bound the scheduler hoists the
 // matrix instructions of all 16 positions (256 result registers) and the kernel drops to one wavefront per SIMD.
@@ -68,182 +31,19 @@ template <int LOG_R, int TL, int NM, int NPS>
 __global__ __launch_bounds__(256, mfma_min_blocks(TL)) void bconv_mfma_ntt_cols(const double* __restrict__ tw, const BConvPlan* __restrict__ plans,
                                                            LaunchMeta meta, const uint64_t* __restrict__ y, uint64_t y_ps,
                                                            uint64_t* __restrict__ out, uint64_t out_ps, uint32_t n_subsets) {
-    constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R, TC = 2048u >> LOG_R;  // tile: TC columns x R rows
-    constexpr int E = LOG_R - 4, S = 1 << E;
-    // exchange buffer of the column butterflies, one region per lane half; rows are padded so that the 16-row groups the
-    // second pass reads start in different banks
-    constexpr uint32_t PADW = TC <= 16 ? TC : 0, HALF_WORDS = R * TC + (R / 16) * PADW;
-    constexpr uint32_t TW_WORDS = (1 + S) * 16;  // per (half, target)
-    __shared__ double lds[LOG_R > 4 ? 2 * HALF_WORDS : 1];
-    __shared__ double lds_tw[2 * TL * TW_WORDS];
-    const uint32_t tid = threadIdx.x, lane = tid & 63u, h = lane >> 5, p = (tid >> 6) * 32u + (lane & 31u);
-    const uint32_t c = p & (TC - 1), r0 = p / TC, col = blockIdx.x * TC + c;
-    KS_TRACE(0);
+    using Shape = MfmaConvShape<LOG_R, TL>;
+    __shared__ double lds[Shape::LDS_WORDS];
+    __shared__ double lds_tw[Shape::LDS_TW_WORDS];
     const uint32_t plan_id = blockIdx.y / n_subsets, subset = blockIdx.y - plan_id * n_subsets;
     const PlanMeta& PM = meta.plan[plan_id];  // kernel arguments: scalar loads, nothing else to wait for
-    const BConvPlan& P = plans[plan_id];
-    const int n_dst = (int)PM.n_dst;
     const int t0 = (int)subset * 2 * TL;
-    if (t0 >= n_dst) return;  // uniform for the whole workgroup
-    const uint64_t* yp = y + (uint64_t)blockIdx.z * y_ps;
-    uint64_t* op = out + (uint64_t)blockIdx.z * out_ps;
-
-    // B operand: the sources of this lane's slots, read through a buffer descriptor (per-lane offset = position + limb).
-    // The first half of the positions is requested before anything else.
-    const BufferRsrc ysrd = make_buffer_rsrc(yp, y_ps * 8);
-    uint32_t voff[NM][NPS];
-#pragma unroll
-    for (int m = 0; m < NM; ++m)
-#pragma unroll
-        for (int e = 0; e < NPS; ++e) {
-            // both candidates through scalar registers (a select between two loads would become one per-lane load)
-            const uint32_t limb0 = __builtin_amdgcn_readfirstlane(PM.src_limb[(2 * m) * NPS + e]);
-            const uint32_t limb1 = __builtin_amdgcn_readfirstlane(PM.src_limb[(2 * m + 1) * NPS + e]);
-            const uint32_t limb = h ? limb1 : limb0;
-            voff[m][e] = (limb * N + r0 * 256 + col) * 8;
-        }
-    constexpr uint32_t kStrideBytes = (16u << LOG_R) * 8u;  // rows r0 + (R / 16) k
-    // positions whose loads are in flight together, and whether position k - 1 is recombined under the matrix instructions
-    // of position k (a second set of result registers) or right away: the single-target shape is kept within 128 registers
-    constexpr int kLoadBudget = TL == 1 ? 16 : 32;  // source values a lane keeps in flight
-    constexpr int KB = kLoadBudget / (NM * NPS) >= 16 ? 16 : kLoadBudget / (NM * NPS) >= 1 ? kLoadBudget / (NM * NPS) : 1;
-    constexpr bool OVERLAP = TL > 1;
-    double yv[KB][NM][NPS];
-#pragma unroll
-    for (int kk = 0; kk < KB; ++kk)
-#pragma unroll
-        for (int m = 0; m < NM; ++m)
-#pragma unroll
-            for (int e = 0; e < NPS; ++e)
-                yv[kk][m][e] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(ysrd, (int)voff[m][e], (int)(kk * kStrideBytes), 0));
-
-    // A operand: this lane's row of the factor matrix.  Result register j = 5 u + b sits in row 8 (j / 4) + 4 h' + j % 4,
-    // so row r belongs to lane half h' = (r / 4) % 2 and register j = 4 (r / 8) + r % 4.
-    v4i afac[NM];
-    {
-        const uint32_t r = lane & 31u, hp = (r >> 2) & 1u, j = 4 * (r >> 3) + (r & 3u), u = j / 5, b = j - 5 * u;
-        const int ta = min(t0 + (int)(hp * TL + u), n_dst - 1);  // a ragged last subset recomputes the last target
-        const bool used = u < (uint32_t)TL;
-#pragma unroll
-        for (int m = 0; m < NM; ++m) {
-            const v4i* row = reinterpret_cast<const v4i*>(&P.afac[ta][b][2 * m + h][0]);
-            afac[m] = used ? *row : v4i{0, 0, 0, 0};
-        }
-    }
-    // per-lane constants of the targets this lane half receives: one 32-byte record each
-    Mod mt[TL];
-    int tgt[TL];
-    uint32_t dst_limb[TL];
-#pragma unroll
-    for (int u = 0; u < TL; ++u) {
-        tgt[u] = t0 + (int)h * TL + u;
-        const BConvPlan::TargetRec rec = P.trec[min(tgt[u], n_dst - 1)];
-        mt[u] = rec.m;
-        dst_limb[u] = rec.limb;
-    }
-    // twiddles of all 2 TL targets -> LDS (requested now, written after the conversion, used after a barrier)
-    constexpr int TW_PER_THREAD = (2 * TL * TW_WORDS + 255) / 256;
-    double twv[TW_PER_THREAD];
-#pragma unroll
-    for (int i = 0; i < TW_PER_THREAD; ++i) {
-        const uint32_t w = min(tid + 256u * i, 2u * TL * TW_WORDS - 1), ht = w / TW_WORDS, rem = w - ht * TW_WORDS;
-        const int t = min(t0 + (int)ht, n_dst - 1);  // ht = half * TL + u, the order of the targets
-        twv[i] = tw[(size_t)P.trec[t].mod_id * N + col_twiddle_index<LOG_R>(rem >> 4, rem & 15u)];
-    }
-    KS_TRACE(1);
-
-    // Software pipeline over the 16 positions, fenced per position so that the schedule below is the one that runs
-    // (left alone, the scheduler hoists every matrix instruction and spills): cut position k into bytes, re-request its
-    // registers for position k + KB, issue its matrix instructions, then recombine position k - 1, whose results have had a
-    // whole position's worth of instructions to arrive.
-    double acc[TL][16];
-    v16i sums[OVERLAP ? 2 : 1];
-    auto recombine = [&](int k) {
-        const v16i& s = sums[OVERLAP ? (k & 1) : 0];
-#pragma unroll
-        for (int u = 0; u < TL; ++u) {
-            // sum_b 256^b S_b: the two low pairs fit 32-bit integers, the rest is exact in doubles
-            const int lo = s[5 * u] + (s[5 * u + 1] << 8), mid = s[5 * u + 2] + (s[5 * u + 3] << 8);
-            const double v = __builtin_fma((double)s[5 * u + 4], 4294967296.0, __builtin_fma((double)mid, 65536.0, (double)lo));
-            acc[u][k] = reduce_lazy(v, mt[u]);
-            // pin the recombined value here: otherwise the optimiser sinks these few instructions down to the butterflies
-            // and keeps the 16 raw sums of every position alive instead (spilling them)
-            asm volatile("" : "+v"(acc[u][k]));
-        }
-    };
-#pragma unroll
-    for (int k = 0; k < 16; ++k) {
-        const int kk = k % KB;
-        v16i s = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-        for (int m = 0; m < NM; ++m) {
-            v4i bq = {0, 0, 0, 0};
-            uint32_t top = 0;
-#pragma unroll
-            for (int e = 0; e < NPS; ++e) {
-                const uint64_t bits = __builtin_bit_cast(uint64_t, yv[kk][m][e] + kDigitBias);
-                bq[e] = (int)((uint32_t)bits ^ 0x80808080u);
-                top |= ((uint32_t)(bits >> 32) & 0xFFu) << (8 * e);
-                if (k + KB < 16)
-                    yv[kk][m][e] = __builtin_bit_cast(
-                        double, __builtin_amdgcn_raw_buffer_load_b64(ysrd, (int)voff[m][e], (int)((k + KB) * kStrideBytes), 0));
-            }
-            bq[3] = (int)top;
-            s = __builtin_amdgcn_mfma_i32_32x32x32_i8(afac[m], bq, s, 0, 0, 0);
-        }
-        sums[OVERLAP ? (k & 1) : 0] = s;
-        if (!OVERLAP) recombine(k);
-        else if (k > 0) recombine(k - 1);
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    if (OVERLAP) recombine(15);
-#pragma unroll
-    for (int i = 0; i < TW_PER_THREAD; ++i)
-        if (tid + 256u * i < 2u * TL * TW_WORDS) lds_tw[tid + 256u * i] = twv[i];
-    __syncthreads();
-    KS_TRACE(2);
-
-    // column half of the forward transform of each target, both lane halves at once (different moduli per half)
-    double* lh = lds + h * HALF_WORDS;
-#pragma unroll
-    for (int u = 0; u < TL; ++u) {
-        const double* ta = lds_tw + (h * TL + u) * TW_WORDS;
-        radix16_fwd(acc[u], *reinterpret_cast<const double(*)[16]>(ta), mt[u]);
-        if (u == 0) KS_TRACE(3);
-        if constexpr (E > 0) {
-            if (u > 0) __syncthreads();  // the previous target's reads of the exchange buffer are done
-#pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                const uint32_t row = r0 + S * k;
-                lh[row * TC + (row >> 4) * PADW + c] = acc[u][k];
-            }
-            __syncthreads();
-#pragma unroll
-            for (int k = 0; k < 16; ++k) acc[u][k] = lh[(16 * r0 + k) * TC + r0 * PADW + c];
-            radix16_fwd<4 - E>(acc[u], *reinterpret_cast<const double(*)[16]>(ta + 16 * (1 + r0)), mt[u]);
-        }
-        if (u == 0) KS_TRACE(4);
-        if (tgt[u] < n_dst) {
-            uint64_t* dst = op + (uint64_t)dst_limb[u] * N;
-#pragma unroll
-            for (int k = 0; k < 16; ++k) store_f64(dst + col_row_grouped<LOG_R>(r0, k) * 256 + col, acc[u][k]);
-        }
-    }
-    KS_TRACE(5);
-#ifdef KS_EXP_TRACE
-    __builtin_amdgcn_s_waitcnt(0);
-    KS_TRACE(6);
-#endif
+    if (t0 >= (int)PM.n_dst) return;  // uniform for the whole workgroup
+    task_bconv_mfma_cols<LOG_R, TL, NM, NPS>(tw, plans[plan_id], PM, y + (uint64_t)blockIdx.z * y_ps, y_ps * 8,
+                                             out + (uint64_t)blockIdx.z * out_ps, blockIdx.x, t0, threadIdx.x, lds, lds_tw);
 }
 
-#ifdef KS_EXP_TRACE
-extern "C" int ks_debug_trace_read(unsigned long long* host, size_t bytes) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), bytes);
-}
-#endif
-
-// Targets per lane half: one gives the most workgroups (single-ciphertext launches are latency-bound and want the chip
-// full of short workgroups), three shares the byte-cutting of the sources among the most targets.
+// Targets per lane half: one gives the most workgroups, three shares the byte-cutting of the sources among the most
+// targets (and keeps the stores of one target under the butterflies of the next).
 void launch_bconv_mfma_ntt_cols(const ks_ctx* c, const PlanSet& plans, const uint64_t* y, uint64_t y_ps, uint64_t* out,
                                 uint64_t out_ps, uint32_t n_polys, int tl, hipStream_t s) {
     const uint32_t n_src = plans.shape_src, n_plans = plans.n_plans, max_targets = plans.max_targets;
@@ -253,7 +53,7 @@ void launch_bconv_mfma_ntt_cols(const ks_ctx* c, const PlanSet& plans, const uin
     tl = (c->logN != 12 && c->logN != 16) || tl < 2 ? 1 : 3;  // built shapes: one or three targets per lane half
     const uint32_t n_subsets = (max_targets + 2 * tl - 1) / (2 * tl);
     const dim3 grid(tiles, n_plans * n_subsets, n_polys), block(256);
-#define KS_LAUNCH_MFMA(LOGR, TLV, NMV, NPSV)                                                                                    \
+#define KS_LAUNCH_MFMA(LOGR, TLV, NMV, NPSV)                                                                                        \
     hipLaunchKernelGGL((bconv_mfma_ntt_cols<LOGR, TLV, NMV, NPSV>), grid, block, 0, s, c->d_tw_fwd, d_plans, plans.meta, y, y_ps, \
                        out, out_ps, n_subsets)
 #define KS_MFMA_SHAPE(LOGR, TLV)                                      \
@@ -263,8 +63,8 @@ void launch_bconv_mfma_ntt_cols(const ks_ctx* c, const PlanSet& plans, const uin
     else if (nm == 2 && nps == 2) KS_LAUNCH_MFMA(LOGR, TLV, 2, 2);    \
     else if (nm == 2) KS_LAUNCH_MFMA(LOGR, TLV, 2, 3);                \
     else KS_LAUNCH_MFMA(LOGR, TLV, 3, 3)
-    // every TL for the benchmarked ring degree and for the smallest one (which the parity sweeps run on); the degrees
-    // in between take TL = 1
+    // every shape for the benchmarked ring degree and for the smallest one (which the parity sweeps run on); the degrees
+    // in between take one target per lane half
 #define KS_LAUNCH_TL(LOGR)                   \
     if (tl == 1) { KS_MFMA_SHAPE(LOGR, 1); } \
     else { KS_MFMA_SHAPE(LOGR, 3); }

@@ -12,7 +12,7 @@
 // tile, so the first fusion is legal; the inner product and the final scale are slot-wise and the row half
 // produces complete slots, so the other two are.
 #include "ks_internal.hpp"
-#include "ks_tiles.hpp"
+#include "ks_tasks.hpp"
 
 namespace ks {
 
@@ -237,109 +237,16 @@ __global__ __launch_bounds__(64) void rows_inner_product(TwTables tw, TwTables t
                                                          uint64_t* __restrict__ acc, uint32_t batch) {
     constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R;
     __shared__ double lds[4 * kRowPitch];
+    __shared__ double lds_ta[4 * 16];
     // Workgroup -> (row group, limb position, batch item).  Consecutive workgroup ids go to the eight XCDs in
     // turn, each with its own L2; the ids that land on one XCD walk through all batch items of one
     // (row group, position) tile before moving to the next tile, so the key slots and twiddles of a tile are
     // fetched into that L2 once and reused by the whole batch.
-    const uint32_t tid = threadIdx.x;
     const uint32_t slot = blockIdx.x >> 3, b = slot % batch, tile = (slot / batch) * 8 + (blockIdx.x & 7);
     if (tile >= (R / 4) * E) return;  // uniform: padding workgroups when the tile count is not a multiple of 8
     const uint32_t rg = tile % (R / 4), pos = tile / (R / 4);
-    const uint32_t mid = pos < ell ? pos : L + (pos - ell);
-    const Mod m = mods[mid];
-    const uint32_t j0 = tid & 15, rr = tid >> 4, row = rg * 4 + rr;
-    const uint32_t off = row * 256 + j0;
-    double a0[16], a1[16];
-#pragma unroll
-    for (int k = 0; k < 16; ++k) a0[k] = a1[k] = 0.0;
-    // every digit's transform uses the same twiddles; the first-pass ones live in LDS to leave registers for a second
-    // wavefront per SIMD
-    __shared__ double lds_ta[4 * 16];
-    double tb[16];
-    row_twiddles_to_lds(lds_ta + rr * 16, tw.W + (size_t)mid * N, R + row, j0);
-    load_row_twiddles_b(tb, tw, mid, N, R + row, j0, m);
-    __syncthreads();
-
-#pragma unroll 1
-    for (uint32_t j = 0; j < dg.ndig; ++j) {
-        const bool own = pos >= dg.lo[j] && pos < dg.hi[j];  // uniform
-        const W* key0 = evk + ((uint64_t)(j * 2 + 0) * M + mid) * N + off;
-        const W* key1 = evk + ((uint64_t)(j * 2 + 1) * M + mid) * N + off;
-        // issue every load of this digit up front (the key slots are independent of the transform below)
-        double x[16], k0[16], k1[16];
-        if constexpr (sizeof(W) == 8) {
-            const uint64_t* src = own ? reinterpret_cast<const uint64_t*>(d) + (uint64_t)b * d_ps + (uint64_t)pos * N + off
-                                      : lifted + (((uint64_t)b * dg.ndig + j) * E + pos) * N + off;
-            uint64_t raw[16];
-#pragma unroll
-            for (int k = 0; k < 16; ++k) raw[k] = src[16 * k];
-#pragma unroll
-            for (int k = 0; k < 16; ++k) k0[k] = word_to_f64<W>(key0[16 * k]);
-#pragma unroll
-            for (int k = 0; k < 16; ++k) k1[k] = word_to_f64<W>(key1[16 * k]);
-            if (own) {
-#pragma unroll
-                for (int k = 0; k < 16; ++k) x[k] = u64_to_f64(raw[k]);
-            } else {
-#pragma unroll
-                for (int k = 0; k < 16; ++k) x[k] = __longlong_as_double((long long)raw[k]);
-                row_fwd_core_lds(x, lds_ta + rr * 16, tb, j0, lds + rr * kRowPitch, m);
-            }
-        } else {
-            // the digit's own limbs come in boundary words, the raised ones as raw doubles: two load shapes, so the
-            // (uniform) choice is a branch; the key slots are requested before it and everything is awaited after it
-            W kr0[16], kr1[16];
-#pragma unroll
-            for (int k = 0; k < 16; ++k) kr0[k] = key0[16 * k];
-#pragma unroll
-            for (int k = 0; k < 16; ++k) kr1[k] = key1[16 * k];
-            if (own) {
-                const W* src = d + (uint64_t)b * d_ps + (uint64_t)pos * N + off;
-#pragma unroll
-                for (int k = 0; k < 16; ++k) x[k] = word_to_f64<W>(src[16 * k]);
-            } else {
-                const uint64_t* src = lifted + (((uint64_t)b * dg.ndig + j) * E + pos) * N + off;
-#pragma unroll
-                for (int k = 0; k < 16; ++k) x[k] = load_f64(src + 16 * k);
-                row_fwd_core_lds(x, lds_ta + rr * 16, tb, j0, lds + rr * kRowPitch, m);
-            }
-#pragma unroll
-            for (int k = 0; k < 16; ++k) k0[k] = word_to_f64<W>(kr0[k]);
-#pragma unroll
-            for (int k = 0; k < 16; ++k) k1[k] = word_to_f64<W>(kr1[k]);
-        }
-#pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            a0[k] += mulmod_lazy(x[k], k0[k], m);
-            a1[k] += mulmod_lazy(x[k], k1[k], m);
-        }
-    }
-    uint64_t* o0 = acc + (((uint64_t)b * 2 + 0) * E + pos) * N + off;
-    uint64_t* o1 = acc + (((uint64_t)b * 2 + 1) * E + pos) * N + off;
-#pragma unroll
-    for (int k = 0; k < 16; ++k) {
-        a0[k] = reduce_lazy(a0[k], m);
-        a1[k] = reduce_lazy(a1[k], m);
-    }
-    if (pos < ell) {  // uniform: ciphertext limbs are kept in evaluation domain for the final subtract-and-scale
-#pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            o0[16 * k] = f64_to_u64(canon(a0[k], m));
-            o1[16 * k] = f64_to_u64(canon(a1[k], m));
-        }
-    } else {
-        // Special limbs go straight into ModDown: the row half of their inverse transform works on the very
-        // rows this wavefront holds, so it is done here and raw doubles are handed to the column half.
-        PassTwiddles ti;
-        load_row_twiddles(ti, twi, mid, N, R + row, j0, m);
-        row_inv_core(a0, ti, j0, lds + rr * kRowPitch, m);
-        row_inv_core(a1, ti, j0, lds + rr * kRowPitch, m);
-#pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            store_f64(o0 + 16 * k, a0[k]);
-            store_f64(o1 + 16 * k, a1[k]);
-        }
-    }
+    task_rows_inner_product<LOG_R, W>(tw, twi, mods, dg, ell, E, L, M, d + (uint64_t)b * d_ps, lifted + (uint64_t)b * dg.ndig * E * N, evk,
+                                      acc + (uint64_t)b * 2 * E * N, pos, rg, threadIdx.x, lds, lds_ta);
 }
 
 void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const void* d, uint64_t d_ps, const uint64_t* lifted,
@@ -383,46 +290,21 @@ __global__ __launch_bounds__(64) void rows_moddown_finish(TwTables tw, const Mod
                                                           W* __restrict__ out, uint64_t out_bs,
                                                           const uint64_t* __restrict__ addend, uint64_t addend_bs,
                                                           uint32_t comp0, uint32_t n_comps, uint32_t galois) {
-    constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R, LOGN = LOG_R + 8;
+    constexpr uint32_t N = 256u << LOG_R;
     __shared__ double lds[4 * kRowPitch];
-    const uint32_t tid = threadIdx.x, rg = blockIdx.x, i = blockIdx.y;
+    const uint32_t rg = blockIdx.x, i = blockIdx.y;
     // batch items in descending order: the conversion kernel before this one wrote them in ascending order, so the most
     // recently written ones, still in the last-level cache, are read first (4-5 % on this kernel in batched calls)
     const uint32_t zz = gridDim.z - 1 - blockIdx.z;
     const uint32_t b = zz / n_comps, comp = comp0 + (zz - b * n_comps);
-    const Mod m = mods[i];
-    const double pinv = Pinv[i];
-    const uint32_t j0 = tid & 15, rr = tid >> 4, row = rg * 4 + rr;
-    const uint32_t off = row * 256 + j0;
-    const uint64_t* src = conv + (((uint64_t)b * 2 + comp) * ell + i) * N + off;
-    const uint64_t* ap = acc + (((uint64_t)b * 2 + comp) * E + i) * N + off;
-    W* op = out + (uint64_t)b * out_bs + ((uint64_t)comp * out_limbs + i) * N + off;
-    // issue every load up front: the accumulator (and addend) slots do not depend on the transform
-    double w[16], a[16], ad[16];
-#pragma unroll
-    for (int k = 0; k < 16; ++k) w[k] = load_f64(src + 16 * k);
-#pragma unroll
-    for (int k = 0; k < 16; ++k) a[k] = u64_to_f64(ap[16 * k]);
-    if constexpr (ADDEND != 0) {
-        const uint64_t* adp = addend + (uint64_t)b * addend_bs + ((uint64_t)comp * ell + i) * N;
-#pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            const uint32_t n = off + 16 * k;
-            ad[k] = u64_to_f64(adp[GATHER ? galois_source_slot(n, galois, LOGN) : n]);
-        }
-    }
-    PassTwiddles t;
-    load_row_twiddles(t, tw, i, N, R + row, j0, m);
-    row_fwd_core(w, t, j0, lds + rr * kRowPitch, m);
+    const uint64_t* adp = nullptr;
     double admul = 0.0;
+    if constexpr (ADDEND != 0) adp = addend + (uint64_t)b * addend_bs + ((uint64_t)comp * ell + i) * N;
     if constexpr (ADDEND == 2) admul = addend_mul[i];
-#pragma unroll
-    for (int k = 0; k < 16; ++k) {
-        double r = mulmod_lazy(a[k] - w[k], pinv, m);
-        if constexpr (ADDEND == 1) r = reduce_lazy(r + ad[k], m);
-        if constexpr (ADDEND == 2) r = reduce_lazy(r + mulmod_lazy(ad[k], admul, m), m);
-        op[16 * k] = f64_to_word<W>(canon(r, m));
-    }
+    task_rows_finish<LOG_R, GATHER, ADDEND, W>(tw, mods[i], i, Pinv[i], admul, conv + (((uint64_t)b * 2 + comp) * ell + i) * N,
+                                               acc + (((uint64_t)b * 2 + comp) * E + i) * N,
+                                               out + (uint64_t)b * out_bs + ((uint64_t)comp * out_limbs + i) * N, adp, galois, rg,
+                                               threadIdx.x, lds);
 }
 
 void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t* acc, const uint64_t* conv, void* out_words,

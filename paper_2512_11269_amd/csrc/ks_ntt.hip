@@ -9,7 +9,7 @@
 #include <algorithm>
 
 #include "ks_internal.hpp"
-#include "ks_tiles.hpp"
+#include "ks_tasks.hpp"
 
 namespace ks {
 
@@ -74,24 +74,12 @@ __global__ __launch_bounds__(64) void ntt_fwd_rows(TwTables tw, const Mod* __res
 template <int LOG_R, typename W>
 __global__ __launch_bounds__(64) void ntt_inv_rows(TwTables twi, const Mod* __restrict__ mods, LimbMap map,
                                                    const W* in, uint64_t* out, uint64_t in_ps, uint64_t out_ps) {
-    constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R, GROUPS = R / 4;
+    constexpr uint32_t N = 256u << LOG_R, GROUPS = (1u << LOG_R) / 4;
     __shared__ double lds[4 * kRowPitch];
-    const uint32_t tid = threadIdx.x;
     const uint32_t li = blockIdx.x / GROUPS, rg = blockIdx.x - li * GROUPS;
     const uint32_t poly = li / map.n, idx = li - poly * map.n, mod_id = map.mod[idx];
     const uint64_t off = (uint64_t)map.off[idx] * N;
-    const W* ip = in + poly * in_ps + off;
-    uint64_t* op = out + poly * out_ps + off;
-    const Mod m = mods[mod_id];
-    const uint32_t j0 = tid & 15, rr = tid >> 4, row = rg * 4 + rr;
-    double v[16];
-    PassTwiddles t;
-#pragma unroll
-    for (int k = 0; k < 16; ++k) v[k] = word_to_f64<W>(ip[row * 256 + j0 + 16 * k]);
-    load_row_twiddles(t, twi, mod_id, N, R + row, j0, m);
-    row_inv_core(v, t, j0, lds + rr * kRowPitch, m);
-#pragma unroll
-    for (int k = 0; k < 16; ++k) store_f64(op + row * 256 + j0 + 16 * k, v[k]);
+    task_inv_rows<LOG_R, W>(twi, mods[mod_id], mod_id, in + poly * in_ps + off, out + poly * out_ps + off, rg, threadIdx.x, lds);
 }
 
 // inverse, columns last, in place: raw doubles in; out = canonical [x * scale]_m where scale is N^-1,
@@ -103,26 +91,10 @@ __global__ __launch_bounds__((TC << LOG_R) / 16) void ntt_inv_cols(const double*
                                                         uint64_t* data, uint64_t ps) {
     constexpr uint32_t N = 256u << LOG_R, TILES = 256 / TC;
     __shared__ double lds[LOG_R > 4 ? (TC << LOG_R) : 1];
-    const uint32_t tid = threadIdx.x;
     const uint32_t li = blockIdx.x / TILES, tile = blockIdx.x - li * TILES;
     const LimbRef L = locate(map, li, data, data, ps, ps, N);
-    const Mod m = mods[L.mod_id];
-    const double* Wi = twi + (size_t)L.mod_id * N;
-    const double scale = scale_tab[scale_by_idx ? L.idx : L.mod_id];
-    const uint32_t c = tid & (TC - 1), r0 = tid / TC, col = tile * TC + c;
-    double v[16];
-    PassTwiddles t;
-#pragma unroll
-    for (int k = 0; k < 16; ++k) v[k] = load_f64(L.in + col_row_grouped<LOG_R>(r0, k) * 256 + col);
-    load_col_twiddles<LOG_R>(t, Wi, r0);
-    col_inv_core<LOG_R, TC>(v, t, c, r0, lds, m);
-#pragma unroll
-    for (int k = 0; k < 16; ++k) {
-        const double r = canon(mulmod_lazy(v[k], scale, m), m);
-        uint64_t* dst = L.out + col_row_strided<LOG_R>(r0, k) * 256 + col;
-        if constexpr (OUT_F64) store_f64(dst, r);
-        else *dst = f64_to_u64(r);
-    }
+    task_inv_cols<LOG_R, TC, OUT_F64>(twi + (size_t)L.mod_id * N, mods[L.mod_id], scale_tab[scale_by_idx ? L.idx : L.mod_id], L.in,
+                                      L.out, tile, threadIdx.x, lds);
 }
 
 // ------------------------------------------------------------------------------------------------
