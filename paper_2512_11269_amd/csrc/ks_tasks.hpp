@@ -1,6 +1,5 @@
-// The bodies of the pipeline kernels as device functions over explicit tile coordinates, so that the one-kernel-per-step
-// launches (ks_ntt.hip, ks_fused.hip, ks_bconv_mfma.hip) and the dependency-ordered single launches of ks_chain.hip run
-// the same code.  "Wave tasks" are executed by one wavefront (lane = threadIdx.x % 64) on four 256-point rows and need
+// The bodies of the pipeline kernels as device functions over explicit tile coordinates (the kernels in ks_ntt.hip,
+// ks_fused.hip and ks_bconv_mfma.hip map their block indices onto them).  "Wave tasks" are executed by one wavefront (lane = threadIdx.x % 64) on four 256-point rows and need
 // 4 * kRowPitch doubles of LDS of their own; "workgroup tasks" are executed by 256 threads on a column tile.
 // Every task contains the same number of workgroup barriers for all its threads.
 #pragma once
@@ -15,8 +14,8 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 // ---- inverse transform, row half: canonical residues in (64- or 32-bit words), raw doubles out (|x| <= 0.501 p) ----
 // ip / op: the limb's first element; rg: group of four rows; lds_wave: 4 * kRowPitch doubles.
 template <int LOG_R, typename W>
-__device__ __forceinline__ void task_inv_rows(const TwTables& twi, Mod m, uint32_t mod_id, const W* __restrict__ ip,
-                                              uint64_t* __restrict__ op, uint32_t rg, uint32_t lane, double* lds_wave) {
+__device__ __forceinline__ void task_inv_rows(const TwTables& twi, Mod m, uint32_t mod_id, const W* ip,
+                                              uint64_t* op, uint32_t rg, uint32_t lane, double* lds_wave) {
     constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R;
     const uint32_t j0 = lane & 15, rr = lane >> 4, row = rg * 4 + rr;
     double v[16];
