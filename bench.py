@@ -29,31 +29,40 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 FP64_VECTOR_PEAK_TFLOPS = 78.6   # 256 CU x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz
 MIB = 1024.0 * 1024.0
+GIB = 1024.0 * MIB
+CHUNK = 8                        # ciphertexts per internal pass of the batched pipelines (the key is read once per chunk)
 
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/), keyed by
-# workload and kernel; None where no counter run has been taken yet.
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/keyswitch_cfg2_hbm_traffic.txt,
+# "measured" column: FETCH_SIZE and WRITE_SIZE scaled by what the same counters read for a 1 GiB device copy, summed, per
+# launch), keyed by workload and kernel.  tests/test_profiles_consistent.py checks these against that file.
 MEASURED_TRAFFIC_BYTES: dict = {
-    # profiles/keyswitch_cfg2_hbm_traffic.txt: FETCH_SIZE scaled by 2.0 and WRITE_SIZE by 1.0 (what the same counters
-    # read for a 1 GiB device copy), summed, per launch.  The excess over the algorithmic bytes (2-8 %) is twiddle reads.
     ("keyswitch", "rows_inner_product"): 187917623,
     ("keyswitch", "rows_moddown_finish"): 77525908,
-    ("keyswitch", "bconv_ntt_cols"): 43279686,      # mean of the ModUp and the ModDown launch
+    ("keyswitch", "bconv_mfma_ntt_cols"): 43279686,  # mean of the ModUp and the ModDown launch
     ("keyswitch", "ntt_inv_rows"): 27091669,
-    ("keyswitch", "ntt_inv_cols"): 21380728,        # mean of the 24-limb and the 16-limb launch
+    ("keyswitch", "ntt_inv_cols"): 21380728,         # mean of the 24-limb and the 16-limb launch
 }
 
+# Algorithmic bytes of the other workloads (fused-plan accounting: every transform = two passes over its limbs, base
+# conversion and products fused into them, keys read once per chunk of ciphertexts), per unit of work.
+CFG3_BYTES_PER_CALL = 222.5 * GIB          # 64 ciphertexts x 16 hoisted rotations
+CFG4_BYTES_PER_DIRECTION = 2 * 2 * 1920 * 65536 * 8.0   # 1920 limb transforms, two passes, read + write
+CFG5_BYTES_PER_HMULT = 698.0 * MIB
 
-def _keyswitch_bytes(L, K, dnum, N):
+
+def _keyswitch_bytes(L, K, dnum, N, batch=1):
     """Algorithmic traffic of one key-switch in bytes: compulsory (read d and the key, write out) and the
-    fused-plan model (every transform = two passes over its limbs, base conversion and products fused)."""
+    fused-plan model (every transform = two passes over its limbs, base conversion and products fused).  In a batched
+    call the key is read once per chunk of min(batch, 8) ciphertexts, so each ciphertext is charged that share of it."""
     limb = N * 8
     alpha = -(-L // dnum)
     E = L + K
     new_limbs = sum(E - (min((j + 1) * alpha, L) - j * alpha) for j in range(dnum))
-    compulsory = (L + dnum * 2 * E + 2 * L) * limb
+    key_limbs = dnum * 2 * E / min(batch, CHUNK)
+    compulsory = (L + key_limbs + 2 * L) * limb
     fused = (2 * L                                       # INTT rows
              + L + new_limbs                             # INTT cols + conversion + NTT cols
-             + new_limbs + L + dnum * 2 * E + 2 * E      # NTT rows + inner product
+             + new_limbs + L + key_limbs + 2 * E         # NTT rows + inner product
              + 2 * 2 * K                                 # INTT rows of special limbs
              + 2 * K + 2 * L                             # INTT cols + conversion + NTT cols
              + 2 * L + 2 * L + 2 * L) * limb             # NTT rows + subtract-scale
@@ -65,6 +74,22 @@ def _apply_options(ctx, args):
     for item in args.opt or []:
         k, v = item.split("=")
         ctx.set_option(int(k), int(v))
+
+
+def _median(xs):
+    xs = sorted(xs)
+    return xs[len(xs) // 2] if len(xs) % 2 else 0.5 * (xs[len(xs) // 2 - 1] + xs[len(xs) // 2])
+
+
+def _event_timed(torch, issue, calls):
+    """Milliseconds per call of `calls` back-to-back calls on the current stream (HIP events around the lot)."""
+    torch.cuda.synchronize()
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0.record()
+    issue(calls)
+    t1.record()
+    torch.cuda.synchronize()
+    return t0.elapsed_time(t1) / calls
 
 
 def bench_keyswitch(args, torch, K, ks_inputs):
@@ -82,24 +107,27 @@ def bench_keyswitch(args, torch, K, ks_inputs):
         out = torch.empty((1, 2, L, N), dtype=torch.int64, device="cuda")
         ws = torch.empty(ws_words, dtype=torch.int64, device="cuda")
         sets.append((d, evk, out, ws))
+    state = {"i": 0}
 
     def run(n, rotate=True):
-        for i in range(n):
-            d, evk, out, ws = sets[i % len(sets)] if rotate else sets[0]
+        for _ in range(n):
+            d, evk, out, ws = sets[state["i"] % len(sets)] if rotate else sets[0]
+            state["i"] += 1
             K.ks_keyswitch(ctx, d, L, evk, out, ws)
 
-    def timed(n, rotate):
-        torch.cuda.synchronize()
-        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t0.record()
-        run(n, rotate)
-        t1.record()
-        torch.cuda.synchronize()
-        return t0.elapsed_time(t1) / n
+    # Timing protocol: W warm-up calls, then `repeats` runs of max(K, 200) calls each, HIP events around each run;
+    # the headline is the MEDIAN run.  The run of exactly K calls the command line asks for is reported beside it.
+    calls = max(args.steps, 200)
+    run(args.warmup)
+    exact_k = _event_timed(torch, run, args.steps)
+    runs = [_event_timed(torch, run, calls) for _ in range(args.repeats)]
+    ms = _median(runs)
+    run(args.warmup, False)
+    ms_hot = _median([_event_timed(torch, lambda n: run(n, False), calls) for _ in range(3)])
 
     def timed_streams(n, n_streams):
-        """Independent key-switches issued round-robin on several streams (default priority), wall-clocked
-        between device-wide synchronisations: a serving loop with several requests in flight."""
+        """Independent key-switches issued round-robin on several streams (default priority), wall-clocked between
+        device-wide synchronisations over at least 200 calls: a serving loop with several requests in flight."""
         streams = [torch.cuda.Stream() for _ in range(n_streams)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -110,16 +138,13 @@ def bench_keyswitch(args, torch, K, ks_inputs):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / n
 
-    run(args.warmup)
-    ms = timed(args.steps, True)
-    run(args.warmup, False)
-    ms_hot = timed(args.steps, False)
     ms_streams = {}
-    if args.sets >= 2:
+    if args.sets >= 2 and not args.no_batched:
         for ns in (2, 3):
             if ns <= args.sets:
-                timed_streams(args.warmup, ns)
-                ms_streams[ns] = timed_streams(args.steps, ns)
+                timed_streams(max(args.warmup, 30), ns)
+                trials = [timed_streams(calls, ns) for _ in range(3)]
+                ms_streams[ns] = {"median": _median(trials), "best": min(trials), "worst": max(trials)}
 
     # the same key-switch over a batch of independent ciphertexts in one call (one key): what a serving loop or an
     # encrypted matrix product issues; every launch then fills the chip
@@ -128,22 +153,15 @@ def bench_keyswitch(args, torch, K, ks_inputs):
         d_b = ks_inputs.uniform_residues(cfg["seed"], 7001, (nb,), q, N, device="cuda")
         out_b = torch.empty((nb, 2, L, N), dtype=torch.int64, device="cuda")
         ws_b = torch.empty(K.ks_workspace_bytes(ctx, K.KS_OP_KEYSWITCH, L, nb) // 8, dtype=torch.int64, device="cuda")
-        reps = max(2, min(20, args.steps // nb + 1))
-        for _ in range(2):
-            K.ks_keyswitch(ctx, d_b, L, sets[0][1], out_b, ws_b)
-        torch.cuda.synchronize()
-        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t0.record()
-        for _ in range(reps):
-            K.ks_keyswitch(ctx, d_b, L, sets[0][1], out_b, ws_b)
-        t1.record()
-        torch.cuda.synchronize()
-        batched[nb] = t0.elapsed_time(t1) / (reps * nb)
+        issue = lambda n: [K.ks_keyswitch(ctx, d_b, L, sets[0][1], out_b, ws_b) for _ in range(n)]
+        issue(2)
+        reps = max(13, calls // nb)                      # at least 200 key-switches per run
+        batched[nb] = _median([_event_timed(torch, issue, reps) for _ in range(3)]) / nb
         del d_b, out_b, ws_b
 
     # instrumented pass: per-kernel durations from HIP events recorded by the library on the launch stream
     K.ks_profile_enable(True)
-    prof_steps = min(args.steps, 24)
+    prof_steps = 24
     run(prof_steps)
     torch.cuda.synchronize()
     kernels = K.ks_profile_report()
@@ -171,23 +189,29 @@ def bench_keyswitch(args, torch, K, ks_inputs):
     compulsory, fused = _keyswitch_bytes(L, Kk, dnum, N)
     # what a plain device copy of 1 GiB reaches on this GPU: the practical ceiling beside the 8 TB/s data-sheet peak
     copy_gbs = bench_copy(args, torch)["value"] if not args.no_batched else None
+    frac = lambda nbytes, t_ms: round(nbytes / (t_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
     path = {"fused_plan_MiB": fused / MIB, "compulsory_MiB": compulsory / MIB,
-            "fused_plan_GBs": round(fused / (ms * 1e-3) / 1e9, 1), "fused_plan_frac_of_peak": round(fused / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "fused_plan_GBs": round(fused / (ms * 1e-3) / 1e9, 1), "fused_plan_frac_of_peak": frac(fused, ms),
+            "target_frac_of_peak": 0.60,
             "compulsory_GBs": round(compulsory / (ms * 1e-3) / 1e9, 1),
             "sum_kernel_ms_per_step": round(sum(k["ms_per_step"] for k in kernels), 4),
-            "batched_fused_plan_frac_of_peak": {str(nb): round(fused / (v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) for nb, v in batched.items()},
+            # algorithmic traffic per ciphertext of a batched call, the key charged once per chunk of 8 (part of this
+            # traffic is served by the last-level cache: one key and one workspace are reused by the whole batch)
+            "batched_fused_plan_MiB_per_keyswitch": {str(nb): round(_keyswitch_bytes(L, Kk, dnum, N, nb)[1] / MIB, 1) for nb in batched},
+            "batched_fused_plan_frac_of_peak": {str(nb): frac(_keyswitch_bytes(L, Kk, dnum, N, nb)[1], v) for nb, v in batched.items()},
             "device_copy_GBs": copy_gbs,
-            "fused_plan_frac_of_device_copy": round(fused / (ms * 1e-3) / 1e9 / copy_gbs, 4) if copy_gbs else None,
-            "batched_fused_plan_frac_of_device_copy": {str(nb): round(fused / (v * 1e-3) / 1e9 / copy_gbs, 4)
-                                                       for nb, v in batched.items()} if copy_gbs else None}
+            "fused_plan_frac_of_device_copy": round(fused / (ms * 1e-3) / 1e9 / copy_gbs, 4) if copy_gbs else None}
     result = {
         "metric": "key_switches_per_sec", "value": round(1000.0 / ms, 2), "unit": "key-switch/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": "bootstrap-keyswitch N=2^16 L=24 K=8 dnum=3 batch=1 (36-bit primes in 64-bit words)",
                    "buffer_sets_rotated": args.sets},
+        "timing": {"protocol": "median of repeats; each repeat = calls_per_repeat back-to-back calls between two HIP events",
+                   "repeats": args.repeats, "calls_per_repeat": calls, "ms_per_step_min": round(min(runs), 5),
+                   "ms_per_step_max": round(max(runs), 5), "ms_per_step_exactly_steps_calls": round(exact_k, 5)},
         "hot_value": round(1000.0 / ms_hot, 2),
-        "multi_stream_value": {str(ns): round(1000.0 / v, 2) for ns, v in ms_streams.items()},
+        "multi_stream_value": {str(ns): {k2: round(1000.0 / v2, 2) for k2, v2 in v.items()} for ns, v in ms_streams.items()},
         "batched_value": {str(nb): round(1000.0 / v, 2) for nb, v in batched.items()},
         "roofline": roofline, "path": path,
         "kernels": [{"kernel": k["kernel"], "launches_per_step": k["launches"] / prof_steps, "avg_us": round(k["avg_us"], 2),
@@ -196,10 +220,38 @@ def bench_keyswitch(args, torch, K, ks_inputs):
         "paper_context": "paper reports only end-to-end times on NVIDIA GPUs (bootstrapping 7.5 ms on 8xB200, BERT-Base 8.8 s, "
                          "Llama3-8B 134 s); no per-key-switch figure exists to compare with",
     }
-    return result, (cfg, q, p, sets[0])
+    first = sets[0]
+    del sets
+    return result, (cfg, q, p, first)
 
 
-def cpu_baseline_keyswitch(cfg, q, p, first_set, ks_inputs, budget_s=15.0):
+def other_workloads(args, torch, K, ks_inputs):
+    """Configurations 3, 4 and 5 in the same run, compactly: throughput and the fraction of the HBM peak their
+    algorithmic (fused-plan) bytes move at.  Few repetitions: the calls are tens of milliseconds long."""
+    import copy
+    import gc
+    a = copy.copy(args)
+    a.steps = 120
+    out = {}
+
+    def compact(r, nbytes_per_ms_step):
+        gbs = nbytes_per_ms_step / (r["ms_per_step"] * 1e-3) / 1e9
+        return {"value": r["value"], "unit": r["unit"], "ms_per_call": r["ms_per_step"], "workload": r["config"]["workload"],
+                "algorithmic_GBs": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+
+    for name, fn, nbytes in (("cfg3_hoisted_rotations", lambda: bench_rotate(a, torch, K, ks_inputs), CFG3_BYTES_PER_CALL),
+                             ("cfg4_batched_ntt", lambda: bench_ntt(a, torch, K, ks_inputs), 2 * CFG4_BYTES_PER_DIRECTION),
+                             ("cfg5_hmult", lambda: bench_hmult(a, torch, K, ks_inputs), 256 * CFG5_BYTES_PER_HMULT),
+                             ("cfg5_hmult_moddown_merged", lambda: bench_hmult(a, torch, K, ks_inputs, merged=True), 256 * CFG5_BYTES_PER_HMULT)):
+        out[name] = compact(fn(), nbytes)
+        gc.collect()
+        torch.cuda.empty_cache()
+    return out
+
+
+def cpu_baseline_keyswitch(cfg, q, p, first_set, ks_inputs, budget_s=12.0):
+    """The plain-C reference as it stands on this machine's host cores: all cores, then one thread."""
+    import ctypes
     from oracle import c_tier
     from oracle import ckks_ref as R
     logN, dnum = cfg["logN"], cfg["dnum"]
@@ -207,13 +259,26 @@ def cpu_baseline_keyswitch(cfg, q, p, first_set, ks_inputs, budget_s=15.0):
     d = ks_inputs.as_u64(first_set[0])
     evk = ks_inputs.as_u64(first_set[1])
     ref.keyswitch(d, evk)                       # warm the tables / page in
+    cores = c_tier.max_threads()
     n, t0 = 0, time.time()
     while n < 4 or (time.time() - t0 < budget_s and n < 200):
         ref.keyswitch(d, evk)
         n += 1
     dt = time.time() - t0
-    return {"value": round(n / dt, 3), "unit": "key-switch/s", "cores": c_tier.max_threads(), "kind": "oracle",
-            "sample": f"{n} key-switches of the same workload (same seeded d and evk), {dt:.1f} s wall"}
+    single = None
+    try:
+        gomp = ctypes.CDLL("libgomp.so.1")
+        gomp.omp_set_num_threads(1)
+        n1, t1 = 0, time.time()
+        while n1 < 2 or (time.time() - t1 < 6.0 and n1 < 20):
+            ref.keyswitch(d, evk)
+            n1 += 1
+        single = {"value": round(n1 / (time.time() - t1), 3), "cores": 1, "sample": f"{n1} key-switches"}
+        gomp.omp_set_num_threads(cores)
+    except OSError:
+        pass
+    return {"value": round(n / dt, 3), "unit": "key-switch/s", "cores": cores, "kind": "oracle",
+            "sample": f"{n} key-switches of the same workload (same seeded d and evk), {dt:.1f} s wall", "single_thread": single}
 
 
 def _kernel_breakdown(K, torch, fn, units):
@@ -469,6 +534,8 @@ def main():
     ap.add_argument("--no-batched", action="store_true", help="skip the batched key-switch measurement (counter runs)")
     ap.add_argument("--workload", default="keyswitch", choices=["keyswitch", "keyswitch_u32", "ntt", "rotate", "rotate_mac", "bsgs", "hmult", "hmult_merged", "copy"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--repeats", type=int, default=5, help="timed runs of the headline workload (the median is reported)")
+    ap.add_argument("--no-extras", action="store_true", help="skip configurations 3, 4 and 5 (profiling runs)")
     ap.add_argument("--opt", action="append", help="context tuning option ID=VALUE (ks_ctx_set_option), repeatable")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -501,6 +568,10 @@ def main():
         result, (cfg, q, p, first_set) = bench_keyswitch(args, torch, K, ks_inputs)
         if not args.no_cpu_baseline:
             result["cpu_baseline"] = cpu_baseline_keyswitch(cfg, q, p, first_set, ks_inputs)
+        del first_set
+        torch.cuda.empty_cache()
+        if not (args.no_extras or args.no_batched):
+            result["other_workloads"] = other_workloads(args, torch, K, ks_inputs)
     print(json.dumps(result))
 
 

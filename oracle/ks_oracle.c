@@ -338,7 +338,6 @@ void orc_rotate_hoisted(const orc_ctx *c, const u64 *ct, int ell, const uint32_t
     free(lifted); free(rotated); free(acc); free(s0);
 }
 
-/* Drop limb ell-1 of poly [ell][N] with rounding to nearest: out [ell-1][N] */
 /* One rotated ciphertext on the extended basis before any division by P: term = (acc_0 + P sigma_g(c0), acc_1), acc the
  * inner product of the sigma_g-permuted raised digits of c1 with the rotation key.  g = 1 is the unrotated ciphertext:
  * no key, term = P (c0, c1) on the ciphertext limbs and 0 on the special limbs.  `rotated`: scratch [ndig][E][N]. */

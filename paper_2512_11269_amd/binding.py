@@ -150,16 +150,51 @@ def ks_workspace_bytes(ctx: Context, op: int, ell: int, batch: int, n_rot: int =
     return int(load_library().ks_workspace_bytes(ctx.handle, op, ell, batch, n_rot))
 
 
+# ---- size checks ----------------------------------------------------------------------------------------------------
+# The C ABI takes bare pointers and cannot know how large the caller's tensors are; a tensor that is too small would
+# make a kernel read or write outside its allocation (a GPU memory fault).  Every wrapper therefore checks element
+# counts against what the header documents before anything is handed to the library.
+
+def _batch_of(t: torch.Tensor, per_item: int, what: str) -> int:
+    n = t.numel()
+    if per_item <= 0 or n == 0 or n % per_item:
+        raise KsError(f"{what}: {n} elements is not a positive multiple of {per_item} (one batch item)")
+    return n // per_item
+
+
+def _need(t: torch.Tensor, want: int, what: str, exact: bool = True) -> None:
+    n = t.numel()
+    if (n != want) if exact else (n < want):
+        raise KsError(f"{what}: expected {'' if exact else 'at least '}{want} elements, got {n}")
+
+
+def _level(ctx: Context, ell: int, lo: int = 1) -> None:
+    if not (lo <= ell <= ctx.L):
+        raise KsError(f"level {ell} outside {lo}..{ctx.L}")
+
+
+def _key_words(ctx: Context) -> int:
+    return ctx.dnum * 2 * (ctx.L + ctx.K) * ctx.N
+
+
+def _on_device(ctx: Context, *tensors) -> None:
+    for t in tensors:
+        if t is not None and not (t.is_cuda and t.device.index == ctx.device):
+            raise KsError(f"tensor on {t.device}, context on cuda:{ctx.device}")
+
+
 def ntt_fwd(ctx: Context, data: torch.Tensor, mod_ids) -> None:
     """In place on data [batch][nlimbs][N]."""
     nl = len(mod_ids)
-    batch = data.numel() // (nl * ctx.N)
+    batch = _batch_of(data, nl * ctx.N, "ntt_fwd data")
+    _on_device(ctx, data)
     _check(load_library().ntt_fwd(ctx.handle, _dev_ptr(data), _u32_array(mod_ids), nl, batch, _stream()), "ntt_fwd")
 
 
 def ntt_inv(ctx: Context, data: torch.Tensor, mod_ids) -> None:
     nl = len(mod_ids)
-    batch = data.numel() // (nl * ctx.N)
+    batch = _batch_of(data, nl * ctx.N, "ntt_inv data")
+    _on_device(ctx, data)
     _check(load_library().ntt_inv(ctx.handle, _dev_ptr(data), _u32_array(mod_ids), nl, batch, _stream()), "ntt_inv")
 
 
@@ -170,13 +205,25 @@ def bconv_prepare(ctx: Context, src_ids, dst_ids) -> None:
 
 
 def bconv(ctx: Context, x: torch.Tensor, src_ids, out: torch.Tensor, dst_ids) -> None:
-    batch = x.numel() // (len(src_ids) * ctx.N)
+    batch = _batch_of(x, len(src_ids) * ctx.N, "bconv input")
+    _need(out, batch * len(dst_ids) * ctx.N, "bconv output")
+    _on_device(ctx, x, out)
     _check(load_library().bconv(ctx.handle, _dev_ptr(x), _u32_array(src_ids), len(src_ids), _dev_ptr(out),
                                 _u32_array(dst_ids), len(dst_ids), batch, _stream()), "bconv")
 
 
+def _workspace_ok(ctx: Context, ws: torch.Tensor, op: int, ell: int, batch: int, n_rot: int = 0) -> None:
+    if getattr(ctx, "handle", None) is not None:
+        _need(ws, -(-ks_workspace_bytes(ctx, op, ell, batch, n_rot) // 8), "workspace", exact=False)
+
+
 def ks_keyswitch(ctx: Context, d: torch.Tensor, ell: int, evk: torch.Tensor, out: torch.Tensor, ws: torch.Tensor) -> None:
-    batch = d.numel() // (ell * ctx.N)
+    _level(ctx, ell)
+    batch = _batch_of(d, ell * ctx.N, "ks_keyswitch d")
+    _need(evk, _key_words(ctx), "evaluation key", exact=False)
+    _need(out, batch * 2 * ell * ctx.N, "ks_keyswitch out")
+    _workspace_ok(ctx, ws, KS_OP_KEYSWITCH, ell, batch)
+    _on_device(ctx, d, evk, out, ws)
     _check(load_library().ks_keyswitch(ctx.handle, _dev_ptr(d), ell, _dev_ptr(evk), _dev_ptr(out), batch, _dev_ptr(ws),
                                        ws.numel() * 8, _stream()), "ks_keyswitch")
 
@@ -187,28 +234,59 @@ def ks_static_workspace_bytes() -> int:
 
 def ks_keyswitch_static(ctx: Context, d: torch.Tensor, ell: int, evk: torch.Tensor, out: torch.Tensor) -> None:
     """ks_keyswitch on the library's own static scratch array: no workspace argument, no allocation."""
-    batch = d.numel() // (ell * ctx.N)
+    _level(ctx, ell)
+    batch = _batch_of(d, ell * ctx.N, "ks_keyswitch_static d")
+    _need(evk, _key_words(ctx), "evaluation key", exact=False)
+    _need(out, batch * 2 * ell * ctx.N, "ks_keyswitch_static out")
+    _on_device(ctx, d, evk, out)
     _check(load_library().ks_keyswitch_static(ctx.handle, _dev_ptr(d), ell, _dev_ptr(evk), _dev_ptr(out), batch, _stream()),
            "ks_keyswitch_static")
 
 
+def _rotation_args(ctx: Context, ct, ell, galois, rot_keys, what):
+    _level(ctx, ell)
+    batch = _batch_of(ct, 2 * ell * ctx.N, f"{what} ct")
+    if len(galois) != len(rot_keys) or not rot_keys:
+        raise KsError(f"{what}: {len(galois)} Galois elements for {len(rot_keys)} keys")
+    for k in rot_keys:
+        if k is not None:
+            _need(k, _key_words(ctx), "rotation key", exact=False)
+    return batch
+
+
 def ks_rotate_hoisted(ctx: Context, ct: torch.Tensor, ell: int, galois, rot_keys, out: torch.Tensor, ws: torch.Tensor) -> None:
-    batch = ct.numel() // (2 * ell * ctx.N)
+    batch = _rotation_args(ctx, ct, ell, galois, rot_keys, "ks_rotate_hoisted")
+    if any(k is None for k in rot_keys):
+        raise KsError("ks_rotate_hoisted: every rotation needs a key")
+    _need(out, batch * len(rot_keys) * 2 * ell * ctx.N, "ks_rotate_hoisted out")
+    _workspace_ok(ctx, ws, KS_OP_ROTATE_HOISTED, ell, batch, len(rot_keys))
+    _on_device(ctx, ct, out, ws, *rot_keys)
     ptrs = (_vp * len(rot_keys))(*[_dev_ptr(k) for k in rot_keys])
     _check(load_library().ks_rotate_hoisted(ctx.handle, _dev_ptr(ct), ell, _u32_array(galois), ptrs, len(rot_keys),
                                             _dev_ptr(out), batch, _dev_ptr(ws), ws.numel() * 8, _stream()), "ks_rotate_hoisted")
 
 
+def _hmult_args(ctx: Context, cta, ctb, ell, rlk, out, ws, what):
+    _level(ctx, ell, 2)
+    batch = _batch_of(cta, 2 * ell * ctx.N, f"{what} cta")
+    _need(ctb, cta.numel(), f"{what} ctb")
+    _need(rlk, _key_words(ctx), "relinearisation key", exact=False)
+    _need(out, batch * 2 * (ell - 1) * ctx.N, f"{what} out")
+    _workspace_ok(ctx, ws, KS_OP_HMULT_RELIN_RESCALE, ell, batch)
+    _on_device(ctx, cta, ctb, rlk, out, ws)
+    return batch
+
+
 def hmult_relin_rescale(ctx: Context, cta: torch.Tensor, ctb: torch.Tensor, ell: int, rlk: torch.Tensor, out: torch.Tensor,
                         ws: torch.Tensor) -> None:
-    batch = cta.numel() // (2 * ell * ctx.N)
+    batch = _hmult_args(ctx, cta, ctb, ell, rlk, out, ws, "hmult_relin_rescale")
     _check(load_library().hmult_relin_rescale(ctx.handle, _dev_ptr(cta), _dev_ptr(ctb), ell, _dev_ptr(rlk), _dev_ptr(out),
                                               batch, _dev_ptr(ws), ws.numel() * 8, _stream()), "hmult_relin_rescale")
 
 
 def hmult_relin_rescale_merged(ctx: Context, cta: torch.Tensor, ctb: torch.Tensor, ell: int, rlk: torch.Tensor, out: torch.Tensor,
                                ws: torch.Tensor) -> None:
-    batch = cta.numel() // (2 * ell * ctx.N)
+    batch = _hmult_args(ctx, cta, ctb, ell, rlk, out, ws, "hmult_relin_rescale_merged")
     _check(load_library().hmult_relin_rescale_merged(ctx.handle, _dev_ptr(cta), _dev_ptr(ctb), ell, _dev_ptr(rlk), _dev_ptr(out),
                                                      batch, _dev_ptr(ws), ws.numel() * 8, _stream()), "hmult_relin_rescale_merged")
 
@@ -218,8 +296,20 @@ def _ptr_array(tensors):
     return (_vp * len(tensors))(*[None if t is None else _dev_ptr(t) for t in tensors])
 
 
+def _plaintexts_ok(ctx: Context, pts) -> None:
+    for w in pts:
+        if w is not None:
+            _need(w, (ctx.L + ctx.K) * ctx.N, "plaintext", exact=False)
+
+
 def ks_rotate_mac_hoisted(ctx: Context, ct: torch.Tensor, ell: int, galois, rot_keys, pts, out: torch.Tensor, ws: torch.Tensor) -> None:
-    batch = ct.numel() // (2 * ell * ctx.N)
+    batch = _rotation_args(ctx, ct, ell, galois, rot_keys, "ks_rotate_mac_hoisted")
+    if len(pts) != len(rot_keys):
+        raise KsError(f"ks_rotate_mac_hoisted: {len(pts)} plaintexts for {len(rot_keys)} rotations")
+    _plaintexts_ok(ctx, pts)
+    _need(out, batch * 2 * ell * ctx.N, "ks_rotate_mac_hoisted out")
+    _workspace_ok(ctx, ws, KS_OP_ROTATE_HOISTED, ell, batch, len(rot_keys))
+    _on_device(ctx, ct, out, ws, *rot_keys, *pts)
     _check(load_library().ks_rotate_mac_hoisted(ctx.handle, _dev_ptr(ct), ell, _u32_array(galois), _ptr_array(rot_keys), _ptr_array(pts),
                                                 len(rot_keys), _dev_ptr(out), batch, _dev_ptr(ws), ws.numel() * 8, _stream()),
            "ks_rotate_mac_hoisted")
@@ -228,8 +318,15 @@ def ks_rotate_mac_hoisted(ctx: Context, ct: torch.Tensor, ell: int, galois, rot_
 def ks_bsgs_linear_transform(ctx: Context, ct: torch.Tensor, ell: int, baby_galois, baby_keys, giant_galois, giant_keys, pts,
                              out: torch.Tensor, ws: torch.Tensor) -> None:
     """pts: n2 rows of n1 plaintext tensors (or None)."""
-    batch = ct.numel() // (2 * ell * ctx.N)
+    batch = _rotation_args(ctx, ct, ell, baby_galois, baby_keys, "ks_bsgs_linear_transform (baby steps)")
+    _rotation_args(ctx, ct, ell, giant_galois, giant_keys, "ks_bsgs_linear_transform (giant steps)")
+    if len(pts) != len(giant_keys) or any(len(row) != len(baby_keys) for row in pts):
+        raise KsError("ks_bsgs_linear_transform: plaintexts must form n2 rows of n1 entries")
     flat = [w for row in pts for w in row]
+    _plaintexts_ok(ctx, flat)
+    _need(out, batch * 2 * ell * ctx.N, "ks_bsgs_linear_transform out")
+    _workspace_ok(ctx, ws, KS_OP_BSGS, ell, batch)
+    _on_device(ctx, ct, out, ws, *baby_keys, *giant_keys, *flat)
     _check(load_library().ks_bsgs_linear_transform(ctx.handle, _dev_ptr(ct), ell, _u32_array(baby_galois), _ptr_array(baby_keys),
                                                    len(baby_keys), _u32_array(giant_galois), _ptr_array(giant_keys), len(giant_keys),
                                                    _ptr_array(flat), _dev_ptr(out), batch, _dev_ptr(ws), ws.numel() * 8, _stream()),
@@ -238,6 +335,11 @@ def ks_bsgs_linear_transform(ctx: Context, ct: torch.Tensor, ell: int, baby_galo
 
 def ks_keyswitch_u32(ctx: Context, d: torch.Tensor, ell: int, evk: torch.Tensor, out: torch.Tensor, ws: torch.Tensor) -> None:
     """d, evk, out: int32 tensors holding one residue (< 2^32) per 32-bit word; ws as for ks_keyswitch (int64)."""
-    batch = d.numel() // (ell * ctx.N)
+    _level(ctx, ell)
+    batch = _batch_of(d, ell * ctx.N, "ks_keyswitch_u32 d")
+    _need(evk, _key_words(ctx), "evaluation key", exact=False)
+    _need(out, batch * 2 * ell * ctx.N, "ks_keyswitch_u32 out")
+    _workspace_ok(ctx, ws, KS_OP_KEYSWITCH, ell, batch)
+    _on_device(ctx, d, evk, out, ws)
     _check(load_library().ks_keyswitch_u32(ctx.handle, _dev_ptr(d, torch.int32), ell, _dev_ptr(evk, torch.int32),
                                            _dev_ptr(out, torch.int32), batch, _dev_ptr(ws), ws.numel() * 8, _stream()), "ks_keyswitch_u32")

@@ -187,7 +187,12 @@ void launch_bconv_ntt_cols(const ks_ctx* c, const PlanSet& plans, uint32_t limbs
     const bool small_launch = (uint64_t)tiles16 * n_plans * ((max_targets + 3) / 4) * n_polys < 512;
     const int kernel = c->opt[KS_OPT_BCONV_KERNEL] ? c->opt[KS_OPT_BCONV_KERNEL] : (small_launch && c->logN == 16 ? 2 : 1);
     if (kernel == 2) {
-        ProfScope ps("bconv_mfma_ntt_cols", (double)limbs_moved_per_poly * n_polys * c->N * 8.0, s, ops_per_coeff * n_polys * c->N);
+        // algorithmic fp64 / integer vector work per coefficient of this kernel: per target 9 to recombine and reduce the
+        // five sums and 35 for the column half; per source 2 to cut it into bytes (the contraction itself runs on the
+        // matrix cores: 25 int8 multiply-adds per source and target)
+        double vec_ops = 0.0;
+        for (uint32_t j = 0; j < n_plans; ++j) vec_ops += plans.meta.plan[j].n_dst * 44.0 + plans.shape_src * 2.0;
+        ProfScope ps("bconv_mfma_ntt_cols", (double)limbs_moved_per_poly * n_polys * c->N * 8.0, s, vec_ops * n_polys * c->N);
         const int tl = c->opt[KS_OPT_BCONV_TARGETS] >= 1 && c->opt[KS_OPT_BCONV_TARGETS] <= 3 ? c->opt[KS_OPT_BCONV_TARGETS] : 3;
         launch_bconv_mfma_ntt_cols(c, plans, y, y_ps, out, out_ps, n_polys, tl, s);
         return;

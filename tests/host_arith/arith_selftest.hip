@@ -142,7 +142,10 @@ static void check_prime(uint64_t p) {
 
 int main() {
     const uint64_t primes[] = {68718428161ull /* largest, N=2^16 */, 68617633793ull /* 60th, N=2^16 */, 68719403009ull /* largest, N=2^12 */,
-                               68718764033ull /* 6th, N=2^12 */, 34359754753ull /* a 35-bit prime = 1 mod 2^17 */};
+                               68718764033ull /* 6th, N=2^12 */, 34359754753ull /* a 35-bit prime = 1 mod 2^17 */,
+                               // the rest of the admitted range: the paper's word size, the top of the 32-bit range, a tiny modulus
+                               268042241ull /* largest 28-bit prime = 1 mod 2^17 */, 4293918721ull /* largest below 2^32, = 1 mod 2^17 */,
+                               40961ull /* = 1 mod 2^13 */};
     for (uint64_t p : primes) check_prime(p);
     if (fails) { printf("%d checks failed\n", fails); return 1; }
     printf("OK\n");

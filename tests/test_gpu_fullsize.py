@@ -51,11 +51,18 @@ def test_cfg4_batched_ntt_full_size():
     y = x.clone()
     K.ntt_fwd(st.ctx, y, ids)
     assert _in_range(y, st.q)
+    # two whole polynomials (every one of the 60 moduli, so a wrong root or table of any modulus shows) and a few more
+    # sampled limbs against the reference; the round trip covers the rest
+    for b in (0, cfg["batch"] - 1):
+        assert_equal(y[b], st.ref.ntt_fwd(host(x[b])[None], ids)[0])
     rng = np.random.RandomState(4)
     for _ in range(6):
         b, i = int(rng.randint(cfg["batch"])), int(rng.randint(cfg["L"]))
         want = st.ref.ntt_fwd(host(x[b, i])[None, None], [i])
         assert_equal(y[b, i], want[0, 0])
+    z = x[3].clone()
+    K.ntt_inv(st.ctx, z, ids)                       # the inverse alone on a whole polynomial, not only as a round trip
+    assert_equal(z, st.ref.ntt_inv(host(x[3])[None], ids)[0])
     K.ntt_inv(st.ctx, y, ids)
     assert torch.equal(y, x)
 

@@ -102,6 +102,31 @@ def test_keyswitch_bootstrap_shape(boot, ell, batch):
     assert_equal(out, boot.ref.keyswitch(host(d), host(evk), ell))
 
 
+def test_calls_are_deterministic(boot, small):
+    """The same call twice into fresh outputs (and a fresh workspace) gives identical residues: no result depends on
+    the order in which workgroups run or on what a buffer held before."""
+    for st, ell in ((boot, 24), (small, 4)):
+        d = st.uniform(91, 1, (2,), list(range(ell)))
+        evk = st.uniform(91, 2, (st.ctx.dnum, 2), list(range(st.L + st.K)))
+        outs = []
+        for fill in (0, -1):
+            out = torch.full((2, 2, ell, st.N), fill, dtype=torch.int64, device="cuda")
+            ws = workspace(st.ctx, K.KS_OP_KEYSWITCH, ell, 2)
+            ws.fill_(fill)
+            K.ks_keyswitch(st.ctx, d, ell, evk, out, ws)
+            outs.append(out)
+        assert torch.equal(outs[0], outs[1])
+        cta, ctb = st.uniform(92, 3, (2, 2), list(range(ell))), st.uniform(92, 4, (2, 2), list(range(ell)))
+        outs = []
+        for fill in (0, -1):
+            out = torch.full((2, 2, ell - 1, st.N), fill, dtype=torch.int64, device="cuda")
+            ws = workspace(st.ctx, K.KS_OP_HMULT_RELIN_RESCALE, ell, 2)
+            ws.fill_(fill)
+            K.hmult_relin_rescale(st.ctx, cta, ctb, ell, evk, out, ws)
+            outs.append(out)
+        assert torch.equal(outs[0], outs[1])
+
+
 def test_keyswitch_zero_key_gives_zero(boot):
     d = boot.uniform(3, 1, (1,), list(range(24)))
     evk = torch.zeros((3, 2, 32, boot.N), dtype=torch.int64, device="cuda")

@@ -460,6 +460,66 @@ def test_mod_down_merged_is_floor_division_by_P_qlast(L, K, dnum, ell):
     assert len(seen_u) > 1 or pr.K == 0     # the lift error really occurs: the test would notice a centred variant
 
 
+@pytest.mark.parametrize("L,K,dnum,ell", [(4, 2, 2, 4), (5, 3, 2, 4), (3, 1, 3, 3)])
+def test_mod_down_is_floor_division_by_P_with_lift_error(L, K, dnum, ell):
+    """Pin that tells the fast conversion from the exact one inside mod_down: with X the CRT reconstruction of the
+    accumulator modulo P Q_ell (computed here, not by the function under test), every output coefficient is
+    floor(X / P) - v with 0 <= v < K, and v > 0 really occurs -- an exact (corrected) conversion would give v = 0
+    everywhere, a centred one negative v."""
+    pr = _small_params(4, L, K, dnum)
+    rng = random.Random(50 + L)
+    ext_ids = list(range(ell)) + [pr.L + k for k in range(pr.K)]
+    ext_mods = [pr.moduli[m] for m in ext_ids]
+    acc = _uniform_poly(rng, pr, ext_ids)
+    out = R.mod_down(pr, acc, ell)
+    acc_coeff = [R.intt(acc[pos], pr.moduli[m], pr.psi[m]) for pos, m in enumerate(ext_ids)]
+    out_coeff = [R.intt(out[i], pr.q[i], pr.psi[i]) for i in range(ell)]
+    Q = pr.Q(ell)
+    seen = set()
+    for n in range(pr.N):
+        X = R.crt_reconstruct([limb[n] for limb in acc_coeff], ext_mods)
+        got = R.crt_reconstruct([limb[n] for limb in out_coeff], pr.q[:ell])
+        v = (X // pr.P - got) % Q
+        assert 0 <= v < max(pr.K, 1), (n, v)
+        seen.add(v)
+    assert pr.K == 1 or len(seen) > 1
+
+
+@pytest.mark.parametrize("L,K,dnum,ell", [(4, 2, 2, 4), (5, 3, 2, 5), (6, 2, 2, 5)])
+def test_mod_up_limbs_are_the_digit_value_plus_lift_error(L, K, dnum, ell):
+    """The same for mod_up: the raised limbs of digit j are congruent to x + u D_j, x the digit's value in [0, D_j)
+    (CRT of its limbs, computed here) and 0 <= u < alpha_j the same for every target modulus of a coefficient;
+    u > 0 occurs, which an exact conversion would never produce."""
+    pr = _small_params(4, L, K, dnum)
+    rng = random.Random(60 + L)
+    d = _uniform_poly(rng, pr, range(ell))
+    lifted = R.mod_up(pr, d, ell)
+    ext_ids = list(range(ell)) + [pr.L + k for k in range(pr.K)]
+    d_coeff = [R.intt(d[i], pr.q[i], pr.psi[i]) for i in range(ell)]
+    for j, dig in enumerate(pr.digits(ell)):
+        src = [pr.q[i] for i in dig]
+        Dj = 1
+        for q in src:
+            Dj *= q
+        lifted_coeff = [R.intt(lifted[j][pos], pr.moduli[m], pr.psi[m]) for pos, m in enumerate(ext_ids)]
+        seen = set()
+        for n in range(pr.N):
+            x = R.crt_reconstruct([d_coeff[i][n] for i in dig], src)
+            us = set()
+            for pos, m in enumerate(ext_ids):
+                t = pr.moduli[m]
+                if m in dig:
+                    assert lifted_coeff[pos][n] == x % t
+                    continue
+                # u from this target: (limb - x) / D_j modulo t
+                us.add((lifted_coeff[pos][n] - x) * pow(Dj % t, -1, t) % t)
+            assert len(us) == 1, (j, n, us)          # one lift error per coefficient, shared by all targets
+            u = us.pop()
+            assert 0 <= u < len(dig), (j, n, u)
+            seen.add(u)
+        assert len(dig) == 1 or len(seen) > 1
+
+
 def test_hmult_merged_decrypts_to_scaled_product():
     pr = _small_params(5, 4, 2, 2)
     rng = random.Random(12)
