@@ -323,6 +323,14 @@ def _time_calls(torch, fn, reps):
     return t0.elapsed_time(t1) / reps
 
 
+def _words(args, torch, cfg):
+    """(cfg, dtype, narrow, tag) for the word size asked for: 64-bit words with the configuration's own primes, or the
+    paper's word size (28-bit primes, one residue per 32-bit word) through the _u32 entry points."""
+    if args.word_size == 32:
+        return dict(cfg, bits=28), torch.int32, (lambda t: None if t is None else t.to(torch.int32)), ", 28-bit primes in 32-bit words"
+    return cfg, torch.int64, (lambda t: t), ""
+
+
 def bench_keyswitch_u32(args, torch, K, ks_inputs):
     """Configuration 2's shape with the paper's word size: 28-bit primes, d / key / result in 32-bit words."""
     cfg = dict(ks_inputs.CONFIGS[2], bits=28)
@@ -366,44 +374,50 @@ def bench_keyswitch_u32(args, torch, K, ks_inputs):
 
 def bench_rotate(args, torch, K, ks_inputs):
     """Configuration 3: 64 ciphertexts x 16 hoisted rotations per call (one ModUp per ciphertext, 16 rotation keys)."""
-    cfg = ks_inputs.CONFIGS[3]
+    cfg, dtype, narrow, tag = _words(args, torch, ks_inputs.CONFIGS[3])
+    w32 = args.word_size == 32
     q, p = ks_inputs.moduli(cfg)
     logN, L, B, R, dnum = cfg["logN"], cfg["L"], cfg["batch"], cfg["n_rot"], cfg["dnum"]
     N = 1 << logN
     ctx = K.Context(logN, q, p, dnum)
     _apply_options(ctx, args)
-    ct = ks_inputs.uniform_residues(cfg["seed"], 1, (B, 2), q, N, device="cuda")
-    keys = [ks_inputs.uniform_residues(cfg["seed"], 10 + r, (dnum, 2), q + p, N, device="cuda") for r in range(R)]
+    ct = narrow(ks_inputs.uniform_residues(cfg["seed"], 1, (B, 2), q, N, device="cuda"))
+    keys = [narrow(ks_inputs.uniform_residues(cfg["seed"], 10 + r, (dnum, 2), q + p, N, device="cuda")) for r in range(R)]
     gal = ks_inputs.galois_elements(logN, R)
-    out = torch.empty((B, R, 2, L, N), dtype=torch.int64, device="cuda")
-    ws = torch.empty(K.ks_workspace_bytes(ctx, K.KS_OP_ROTATE_HOISTED, L, B, R) // 8, dtype=torch.int64, device="cuda")
-    fn = lambda: K.ks_rotate_hoisted(ctx, ct, L, gal, keys, out, ws)
+    out = torch.empty((B, R, 2, L, N), dtype=dtype, device="cuda")
+    op = K.KS_OP_ROTATE_HOISTED_U32 if w32 else K.KS_OP_ROTATE_HOISTED
+    ws = torch.empty(K.ks_workspace_bytes(ctx, op, L, B, R) // 8, dtype=torch.int64, device="cuda")
+    entry = K.ks_rotate_hoisted_u32 if w32 else K.ks_rotate_hoisted
+    fn = lambda: entry(ctx, ct, L, gal, keys, out, ws)
     reps = max(2, args.steps // 60)
     ms = _time_calls(torch, fn, reps)
     kernels = _kernel_breakdown(K, torch, fn, B * R)
     return {"metric": "rotations_per_sec", "value": round(B * R / (ms * 1e-3), 1), "unit": "rotation/s", "n_gpus": 1, "steps": reps,
             "warmup": 1, "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
             "dtype": "f64", "data": "synthetic",
-            "config": {"workload": "hoisted-rotations N=2^16 L=24 K=8 dnum=3, 64 ciphertexts x 16 Galois elements per call"},
+            "config": {"workload": "hoisted-rotations N=2^16 L=24 K=8 dnum=3, 64 ciphertexts x 16 Galois elements per call" + tag},
             "roofline": _dominant_roofline(kernels), "kernels": kernels}
 
 
 def bench_rotate_mac(args, torch, K, ks_inputs):
     """Configuration 3's shape through the double-hoisted entry point: per ciphertext the 16 rotations are multiplied by
     plaintext diagonals and summed on the extended basis, with one division by P for the sum."""
-    cfg = ks_inputs.CONFIGS[3]
+    cfg, dtype, narrow, tag = _words(args, torch, ks_inputs.CONFIGS[3])
+    w32 = args.word_size == 32
     q, p = ks_inputs.moduli(cfg)
     logN, L, B, R, dnum = cfg["logN"], cfg["L"], cfg["batch"], cfg["n_rot"], cfg["dnum"]
     N = 1 << logN
     ctx = K.Context(logN, q, p, dnum)
     _apply_options(ctx, args)
-    ct = ks_inputs.uniform_residues(cfg["seed"], 1, (B, 2), q, N, device="cuda")
-    keys = [ks_inputs.uniform_residues(cfg["seed"], 10 + r, (dnum, 2), q + p, N, device="cuda") for r in range(R)]
-    pts = [ks_inputs.uniform_residues(cfg["seed"], 100 + r, (), q + p, N, device="cuda") for r in range(R)]
+    ct = narrow(ks_inputs.uniform_residues(cfg["seed"], 1, (B, 2), q, N, device="cuda"))
+    keys = [narrow(ks_inputs.uniform_residues(cfg["seed"], 10 + r, (dnum, 2), q + p, N, device="cuda")) for r in range(R)]
+    pts = [narrow(ks_inputs.uniform_residues(cfg["seed"], 100 + r, (), q + p, N, device="cuda")) for r in range(R)]
     gal = ks_inputs.galois_elements(logN, R)
-    out = torch.empty((B, 2, L, N), dtype=torch.int64, device="cuda")
-    ws = torch.empty(K.ks_workspace_bytes(ctx, K.KS_OP_ROTATE_HOISTED, L, B, R) // 8, dtype=torch.int64, device="cuda")
-    fn = lambda: K.ks_rotate_mac_hoisted(ctx, ct, L, gal, keys, pts, out, ws)
+    out = torch.empty((B, 2, L, N), dtype=dtype, device="cuda")
+    op = K.KS_OP_ROTATE_HOISTED_U32 if w32 else K.KS_OP_ROTATE_HOISTED
+    ws = torch.empty(K.ks_workspace_bytes(ctx, op, L, B, R) // 8, dtype=torch.int64, device="cuda")
+    entry = K.ks_rotate_mac_hoisted_u32 if w32 else K.ks_rotate_mac_hoisted
+    fn = lambda: entry(ctx, ct, L, gal, keys, pts, out, ws)
     reps = max(2, args.steps // 30)
     ms = _time_calls(torch, fn, reps)
     kernels = _kernel_breakdown(K, torch, fn, B * R)
@@ -411,7 +425,7 @@ def bench_rotate_mac(args, torch, K, ks_inputs):
             "warmup": 1, "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
             "dtype": "f64", "data": "synthetic",
             "config": {"workload": "double-hoisted rotate-multiply-accumulate N=2^16 L=24 K=8 dnum=3, 64 ciphertexts x 16 Galois "
-                                   "elements per call, one ModDown per ciphertext"},
+                                   "elements per call, one ModDown per ciphertext" + tag},
             "roofline": _dominant_roofline(kernels), "kernels": kernels}
 
 
@@ -448,18 +462,21 @@ def bench_bsgs(args, torch, K, ks_inputs):
 def bench_hmult(args, torch, K, ks_inputs, merged=False):
     """Configuration 5: 256 ciphertext pairs per call: tensor product, relinearisation, rescale (merged: the division
     by P and the rescale done as one division by P q_last)."""
-    cfg = ks_inputs.CONFIGS[5]
+    cfg, dtype, narrow, tag = _words(args, torch, ks_inputs.CONFIGS[5])
     q, p = ks_inputs.moduli(cfg)
     logN, L, B, dnum = cfg["logN"], cfg["L"], cfg["batch"], cfg["dnum"]
     N = 1 << logN
     ctx = K.Context(logN, q, p, dnum)
     _apply_options(ctx, args)
-    cta = ks_inputs.uniform_residues(cfg["seed"], 1, (B, 2), q, N, device="cuda")
-    ctb = ks_inputs.uniform_residues(cfg["seed"], 2, (B, 2), q, N, device="cuda")
-    rlk = ks_inputs.uniform_residues(cfg["seed"], 3, (dnum, 2), q + p, N, device="cuda")
-    out = torch.empty((B, 2, L - 1, N), dtype=torch.int64, device="cuda")
+    cta = narrow(ks_inputs.uniform_residues(cfg["seed"], 1, (B, 2), q, N, device="cuda"))
+    ctb = narrow(ks_inputs.uniform_residues(cfg["seed"], 2, (B, 2), q, N, device="cuda"))
+    rlk = narrow(ks_inputs.uniform_residues(cfg["seed"], 3, (dnum, 2), q + p, N, device="cuda"))
+    out = torch.empty((B, 2, L - 1, N), dtype=dtype, device="cuda")
     ws = torch.empty(K.ks_workspace_bytes(ctx, K.KS_OP_HMULT_RELIN_RESCALE, L, B) // 8, dtype=torch.int64, device="cuda")
-    entry = K.hmult_relin_rescale_merged if merged else K.hmult_relin_rescale
+    if args.word_size == 32:
+        entry = K.hmult_relin_rescale_merged_u32 if merged else K.hmult_relin_rescale_u32
+    else:
+        entry = K.hmult_relin_rescale_merged if merged else K.hmult_relin_rescale
     fn = lambda: entry(ctx, cta, ctb, L, rlk, out, ws)
     reps = max(2, args.steps // 60)
     ms = _time_calls(torch, fn, reps)
@@ -468,39 +485,40 @@ def bench_hmult(args, torch, K, ks_inputs, merged=False):
             "warmup": 1, "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
             "dtype": "f64", "data": "synthetic",
             "config": {"workload": "hmult-relin-rescale N=2^16 L=35 K=12 dnum=3, 256 ciphertext pairs per call"
-                                   + (", ModDown merged with rescale" if merged else "")},
+                                   + (", ModDown merged with rescale" if merged else "") + tag},
             "roofline": _dominant_roofline(kernels), "kernels": kernels}
 
 
 def bench_ntt(args, torch, K, ks_inputs):
-    cfg = ks_inputs.CONFIGS[4]
+    cfg, dtype, narrow, tag = _words(args, torch, ks_inputs.CONFIGS[4])
     q, p = ks_inputs.moduli(cfg)
     logN, L, batch = cfg["logN"], cfg["L"], cfg["batch"]
     N = 1 << logN
     ctx = K.Context(logN, q, p, 1)
     _apply_options(ctx, args)
     ids = list(range(L))
-    data = ks_inputs.uniform_residues(cfg["seed"], 1, (batch,), q, N, device="cuda")
-    K.ntt_fwd(ctx, data, ids)
-    K.ntt_inv(ctx, data, ids)
+    data = narrow(ks_inputs.uniform_residues(cfg["seed"], 1, (batch,), q, N, device="cuda"))
+    fwd, inv = (K.ntt_fwd_u32, K.ntt_inv_u32) if args.word_size == 32 else (K.ntt_fwd, K.ntt_inv)
+    fwd(ctx, data, ids)
+    inv(ctx, data, ids)
     torch.cuda.synchronize()
     t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     steps = max(2, args.steps // 10)
     t0.record()
     for _ in range(steps):
-        K.ntt_fwd(ctx, data, ids)
-        K.ntt_inv(ctx, data, ids)
+        fwd(ctx, data, ids)
+        inv(ctx, data, ids)
     t1.record()
     torch.cuda.synchronize()
     ms = t0.elapsed_time(t1) / steps
     limbs = 2 * L * batch
-    bytes_one_pass = limbs * N * 8 * 2.0
-    kernels = _kernel_breakdown(K, torch, lambda: (K.ntt_fwd(ctx, data, ids), K.ntt_inv(ctx, data, ids)), limbs)
+    bytes_one_pass = limbs * N * (args.word_size // 8) * 2.0
+    kernels = _kernel_breakdown(K, torch, lambda: (fwd(ctx, data, ids), inv(ctx, data, ids)), limbs)
     _dominant_roofline(kernels)
     return {"metric": "limb_ntts_per_sec", "kernels": kernels, "value": round(limbs / (ms * 1e-3), 1), "unit": "limb-NTT/s (2^16 points)", "n_gpus": 1,
             "steps": steps, "warmup": 1, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
             "vs_baseline": None, "dtype": "f64", "data": "synthetic",
-            "config": {"workload": "batched-ntt N=2^16 60 limbs x 32 polynomials, forward then inverse"},
+            "config": {"workload": "batched-ntt N=2^16 60 limbs x 32 polynomials, forward then inverse" + tag},
             "roofline": {"bound": "hbm", "kernel": "ntt_fwd+ntt_inv (two passes each)", "achieved": round(2 * bytes_one_pass / (ms * 1e-3) / 1e9, 1),
                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(2 * bytes_one_pass / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                          "traffic": None}}
@@ -533,6 +551,8 @@ def main():
     ap.add_argument("--sets", type=int, default=6, help="disjoint buffer sets rotated through (cold-cache figure)")
     ap.add_argument("--no-batched", action="store_true", help="skip the batched key-switch measurement (counter runs)")
     ap.add_argument("--workload", default="keyswitch", choices=["keyswitch", "keyswitch_u32", "ntt", "rotate", "rotate_mac", "bsgs", "hmult", "hmult_merged", "copy"])
+    ap.add_argument("--word-size", type=int, default=64, choices=[64, 32],
+                    help="32: the rotate / rotate_mac / hmult / hmult_merged / ntt workloads with 28-bit primes in 32-bit words")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--repeats", type=int, default=5, help="timed runs of the headline workload (the median is reported)")
     ap.add_argument("--no-extras", action="store_true", help="skip configurations 3, 4 and 5 (profiling runs)")

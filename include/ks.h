@@ -12,8 +12,9 @@
  *  - Ring: Z[X]/(X^N + 1), N = 2^logN.  RNS basis: ciphertext primes q_0..q_{L-1} followed by special
  *    primes p_0..p_{K-1}; "modulus id" m in [0, L+K) indexes that concatenated list.  Every modulus is
  *    an odd prime below 2^36 with m = 1 (mod 2N).
- *  - A limb is N residues in 64-bit words, N contiguous (ks_keyswitch_u32 alone takes 32-bit words).  All
- *    residues handed to the library must be canonical (in [0, modulus)); every output is canonical.
+ *  - A limb is N residues in 64-bit words, N contiguous.  The entry points whose names end in _u32 take the
+ *    same tensors with one residue per 32-bit word (see "32-bit words" below).  All residues handed to the
+ *    library must be canonical (in [0, modulus)); every output is canonical.
  *  - Evaluation domain order is bit-reversed: slot k of a limb holds a(psi^(2*brv(k)+1)), brv = bit
  *    reversal on logN bits, psi = the primitive 2N-th root of unity of that modulus.
  *  - Digits for hybrid key-switching are contiguous groups of alpha = ceil(L/dnum) ciphertext limbs;
@@ -52,7 +53,8 @@ enum { /* operations for ks_workspace_bytes */
     KS_OP_KEYSWITCH = 1,
     KS_OP_ROTATE_HOISTED = 2,
     KS_OP_HMULT_RELIN_RESCALE = 3,
-    KS_OP_BSGS = 4
+    KS_OP_BSGS = 4,
+    KS_OP_ROTATE_HOISTED_U32 = 5 /* ks_rotate_hoisted_u32 and ks_rotate_mac_hoisted_u32 */
 };
 
 /* Build the tables for one parameter set on GPU `device`.
@@ -207,6 +209,32 @@ int hmult_relin_rescale(const ks_ctx* ctx, const uint64_t* cta, const uint64_t* 
 int hmult_relin_rescale_merged(const ks_ctx* ctx, const uint64_t* cta, const uint64_t* ctb, uint32_t ell,
                                const uint64_t* rlk, uint64_t* out, uint32_t batch, void* ws, size_t ws_bytes,
                                void* stream);
+
+/* 32-bit words (Evaluation, "Benchmarks": the paper's parameter sets use a 28-bit RNS basis held in 32-bit words).
+ * Each call below is the entry point of the same name without the suffix with every DEVICE tensor of residues --
+ * ciphertexts, keys, plaintexts, results; for the transforms and the conversion the data itself -- holding one
+ * residue per uint32_t in the same layout.  Arithmetic and results are identical; the traffic of those tensors
+ * halves.  Intermediate values in the workspace stay 8 bytes wide.  Every call returns KS_EINVAL unless every modulus
+ * of the context is below 2^32.  Workspace: the operation code of the 64-bit call, except that the two rotation calls
+ * take KS_OP_ROTATE_HOISTED_U32 (the ciphertexts of a chunk are widened once into the workspace).
+ *   ntt_fwd_u32 / ntt_inv_u32 : in place on [batch][nlimbs][N] uint32_t.
+ *   bconv_u32                 : pairs registered with bconv_prepare serve both word sizes. */
+int ntt_fwd_u32(const ks_ctx* ctx, uint32_t* data, const uint32_t* mod_ids, uint32_t nlimbs, uint32_t batch, void* stream);
+int ntt_inv_u32(const ks_ctx* ctx, uint32_t* data, const uint32_t* mod_ids, uint32_t nlimbs, uint32_t batch, void* stream);
+int bconv_u32(const ks_ctx* ctx, const uint32_t* in, const uint32_t* src_ids, uint32_t n_src,
+              uint32_t* out, const uint32_t* dst_ids, uint32_t n_dst, uint32_t batch, void* stream);
+int ks_rotate_hoisted_u32(const ks_ctx* ctx, const uint32_t* ct, uint32_t ell, const uint32_t* galois,
+                          const uint32_t* const* rot_keys, uint32_t n_rot, uint32_t* out, uint32_t batch,
+                          void* ws, size_t ws_bytes, void* stream);
+int ks_rotate_mac_hoisted_u32(const ks_ctx* ctx, const uint32_t* ct, uint32_t ell, const uint32_t* galois,
+                              const uint32_t* const* rot_keys, const uint32_t* const* pts, uint32_t n_rot,
+                              uint32_t* out, uint32_t batch, void* ws, size_t ws_bytes, void* stream);
+int hmult_relin_rescale_u32(const ks_ctx* ctx, const uint32_t* cta, const uint32_t* ctb, uint32_t ell,
+                            const uint32_t* rlk, uint32_t* out, uint32_t batch, void* ws, size_t ws_bytes,
+                            void* stream);
+int hmult_relin_rescale_merged_u32(const ks_ctx* ctx, const uint32_t* cta, const uint32_t* ctb, uint32_t ell,
+                                   const uint32_t* rlk, uint32_t* out, uint32_t batch, void* ws, size_t ws_bytes,
+                                   void* stream);
 
 /* Per-kernel timing for benchmarks (the paper's evaluation characterises its NTT, base-conversion and
  * elementwise kernel classes separately; this exposes the same breakdown).  While enabled, every kernel the

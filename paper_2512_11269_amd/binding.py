@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("KS_MI355X_LIB") or os.path.join(_HERE, "libks_mi355x.so")
 _lib = None
 
-KS_OP_KEYSWITCH, KS_OP_ROTATE_HOISTED, KS_OP_HMULT_RELIN_RESCALE, KS_OP_BSGS = 1, 2, 3, 4
+KS_OP_KEYSWITCH, KS_OP_ROTATE_HOISTED, KS_OP_HMULT_RELIN_RESCALE, KS_OP_BSGS, KS_OP_ROTATE_HOISTED_U32 = 1, 2, 3, 4, 5
 KS_OPT_BCONV_TARGETS, KS_OPT_BCONV_KERNEL = 0, 1
 
 _u64p = ctypes.POINTER(ctypes.c_uint64)
@@ -70,6 +70,9 @@ def load_library():
                                              ctypes.c_size_t, _vp]
     lib.hmult_relin_rescale.argtypes = [_vp, _vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
     lib.hmult_relin_rescale_merged.argtypes = [_vp, _vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
+    for name in ("ntt_fwd", "ntt_inv", "bconv", "ks_rotate_hoisted", "ks_rotate_mac_hoisted", "hmult_relin_rescale",
+                 "hmult_relin_rescale_merged"):
+        getattr(lib, name + "_u32").argtypes = getattr(lib, name).argtypes
     lib.ks_profile_enable.argtypes = [ctypes.c_int]
     lib.ks_profile_report.argtypes = [ctypes.c_char_p, ctypes.c_size_t]
     _lib = lib
@@ -183,19 +186,29 @@ def _on_device(ctx: Context, *tensors) -> None:
             raise KsError(f"tensor on {t.device}, context on cuda:{ctx.device}")
 
 
+def _ntt(name: str, dtype, ctx: Context, data: torch.Tensor, mod_ids) -> None:
+    nl = len(mod_ids)
+    batch = _batch_of(data, nl * ctx.N, f"{name} data")
+    _on_device(ctx, data)
+    _check(getattr(load_library(), name)(ctx.handle, _dev_ptr(data, dtype), _u32_array(mod_ids), nl, batch, _stream()), name)
+
+
 def ntt_fwd(ctx: Context, data: torch.Tensor, mod_ids) -> None:
     """In place on data [batch][nlimbs][N]."""
-    nl = len(mod_ids)
-    batch = _batch_of(data, nl * ctx.N, "ntt_fwd data")
-    _on_device(ctx, data)
-    _check(load_library().ntt_fwd(ctx.handle, _dev_ptr(data), _u32_array(mod_ids), nl, batch, _stream()), "ntt_fwd")
+    _ntt("ntt_fwd", torch.int64, ctx, data, mod_ids)
 
 
 def ntt_inv(ctx: Context, data: torch.Tensor, mod_ids) -> None:
-    nl = len(mod_ids)
-    batch = _batch_of(data, nl * ctx.N, "ntt_inv data")
-    _on_device(ctx, data)
-    _check(load_library().ntt_inv(ctx.handle, _dev_ptr(data), _u32_array(mod_ids), nl, batch, _stream()), "ntt_inv")
+    _ntt("ntt_inv", torch.int64, ctx, data, mod_ids)
+
+
+def ntt_fwd_u32(ctx: Context, data: torch.Tensor, mod_ids) -> None:
+    """In place on an int32 tensor [batch][nlimbs][N] holding one residue (< 2^32) per 32-bit word."""
+    _ntt("ntt_fwd_u32", torch.int32, ctx, data, mod_ids)
+
+
+def ntt_inv_u32(ctx: Context, data: torch.Tensor, mod_ids) -> None:
+    _ntt("ntt_inv_u32", torch.int32, ctx, data, mod_ids)
 
 
 def bconv_prepare(ctx: Context, src_ids, dst_ids) -> None:
@@ -204,12 +217,21 @@ def bconv_prepare(ctx: Context, src_ids, dst_ids) -> None:
            "bconv_prepare")
 
 
-def bconv(ctx: Context, x: torch.Tensor, src_ids, out: torch.Tensor, dst_ids) -> None:
-    batch = _batch_of(x, len(src_ids) * ctx.N, "bconv input")
-    _need(out, batch * len(dst_ids) * ctx.N, "bconv output")
+def _bconv(name: str, dtype, ctx: Context, x: torch.Tensor, src_ids, out: torch.Tensor, dst_ids) -> None:
+    batch = _batch_of(x, len(src_ids) * ctx.N, f"{name} input")
+    _need(out, batch * len(dst_ids) * ctx.N, f"{name} output")
     _on_device(ctx, x, out)
-    _check(load_library().bconv(ctx.handle, _dev_ptr(x), _u32_array(src_ids), len(src_ids), _dev_ptr(out),
-                                _u32_array(dst_ids), len(dst_ids), batch, _stream()), "bconv")
+    _check(getattr(load_library(), name)(ctx.handle, _dev_ptr(x, dtype), _u32_array(src_ids), len(src_ids), _dev_ptr(out, dtype),
+                                         _u32_array(dst_ids), len(dst_ids), batch, _stream()), name)
+
+
+def bconv(ctx: Context, x: torch.Tensor, src_ids, out: torch.Tensor, dst_ids) -> None:
+    _bconv("bconv", torch.int64, ctx, x, src_ids, out, dst_ids)
+
+
+def bconv_u32(ctx: Context, x: torch.Tensor, src_ids, out: torch.Tensor, dst_ids) -> None:
+    """bconv on int32 tensors holding one residue (< 2^32) per 32-bit word."""
+    _bconv("bconv_u32", torch.int32, ctx, x, src_ids, out, dst_ids)
 
 
 def _workspace_ok(ctx: Context, ws: torch.Tensor, op: int, ell: int, batch: int, n_rot: int = 0) -> None:
@@ -254,16 +276,25 @@ def _rotation_args(ctx: Context, ct, ell, galois, rot_keys, what):
     return batch
 
 
-def ks_rotate_hoisted(ctx: Context, ct: torch.Tensor, ell: int, galois, rot_keys, out: torch.Tensor, ws: torch.Tensor) -> None:
-    batch = _rotation_args(ctx, ct, ell, galois, rot_keys, "ks_rotate_hoisted")
+def _rotate_hoisted(name, dtype, op, ctx, ct, ell, galois, rot_keys, out, ws) -> None:
+    batch = _rotation_args(ctx, ct, ell, galois, rot_keys, name)
     if any(k is None for k in rot_keys):
-        raise KsError("ks_rotate_hoisted: every rotation needs a key")
-    _need(out, batch * len(rot_keys) * 2 * ell * ctx.N, "ks_rotate_hoisted out")
-    _workspace_ok(ctx, ws, KS_OP_ROTATE_HOISTED, ell, batch, len(rot_keys))
+        raise KsError(f"{name}: every rotation needs a key")
+    _need(out, batch * len(rot_keys) * 2 * ell * ctx.N, f"{name} out")
+    _workspace_ok(ctx, ws, op, ell, batch, len(rot_keys))
     _on_device(ctx, ct, out, ws, *rot_keys)
-    ptrs = (_vp * len(rot_keys))(*[_dev_ptr(k) for k in rot_keys])
-    _check(load_library().ks_rotate_hoisted(ctx.handle, _dev_ptr(ct), ell, _u32_array(galois), ptrs, len(rot_keys),
-                                            _dev_ptr(out), batch, _dev_ptr(ws), ws.numel() * 8, _stream()), "ks_rotate_hoisted")
+    ptrs = (_vp * len(rot_keys))(*[_dev_ptr(k, dtype) for k in rot_keys])
+    _check(getattr(load_library(), name)(ctx.handle, _dev_ptr(ct, dtype), ell, _u32_array(galois), ptrs, len(rot_keys),
+                                         _dev_ptr(out, dtype), batch, _dev_ptr(ws), ws.numel() * 8, _stream()), name)
+
+
+def ks_rotate_hoisted(ctx: Context, ct: torch.Tensor, ell: int, galois, rot_keys, out: torch.Tensor, ws: torch.Tensor) -> None:
+    _rotate_hoisted("ks_rotate_hoisted", torch.int64, KS_OP_ROTATE_HOISTED, ctx, ct, ell, galois, rot_keys, out, ws)
+
+
+def ks_rotate_hoisted_u32(ctx: Context, ct: torch.Tensor, ell: int, galois, rot_keys, out: torch.Tensor, ws: torch.Tensor) -> None:
+    """ct, keys, out: int32 tensors, one residue (< 2^32) per word; ws: int64, sized for KS_OP_ROTATE_HOISTED_U32."""
+    _rotate_hoisted("ks_rotate_hoisted_u32", torch.int32, KS_OP_ROTATE_HOISTED_U32, ctx, ct, ell, galois, rot_keys, out, ws)
 
 
 def _hmult_args(ctx: Context, cta, ctb, ell, rlk, out, ws, what):
@@ -277,23 +308,36 @@ def _hmult_args(ctx: Context, cta, ctb, ell, rlk, out, ws, what):
     return batch
 
 
+def _hmult(name, dtype, ctx, cta, ctb, ell, rlk, out, ws) -> None:
+    batch = _hmult_args(ctx, cta, ctb, ell, rlk, out, ws, name)
+    _check(getattr(load_library(), name)(ctx.handle, _dev_ptr(cta, dtype), _dev_ptr(ctb, dtype), ell, _dev_ptr(rlk, dtype),
+                                         _dev_ptr(out, dtype), batch, _dev_ptr(ws), ws.numel() * 8, _stream()), name)
+
+
 def hmult_relin_rescale(ctx: Context, cta: torch.Tensor, ctb: torch.Tensor, ell: int, rlk: torch.Tensor, out: torch.Tensor,
                         ws: torch.Tensor) -> None:
-    batch = _hmult_args(ctx, cta, ctb, ell, rlk, out, ws, "hmult_relin_rescale")
-    _check(load_library().hmult_relin_rescale(ctx.handle, _dev_ptr(cta), _dev_ptr(ctb), ell, _dev_ptr(rlk), _dev_ptr(out),
-                                              batch, _dev_ptr(ws), ws.numel() * 8, _stream()), "hmult_relin_rescale")
+    _hmult("hmult_relin_rescale", torch.int64, ctx, cta, ctb, ell, rlk, out, ws)
 
 
 def hmult_relin_rescale_merged(ctx: Context, cta: torch.Tensor, ctb: torch.Tensor, ell: int, rlk: torch.Tensor, out: torch.Tensor,
                                ws: torch.Tensor) -> None:
-    batch = _hmult_args(ctx, cta, ctb, ell, rlk, out, ws, "hmult_relin_rescale_merged")
-    _check(load_library().hmult_relin_rescale_merged(ctx.handle, _dev_ptr(cta), _dev_ptr(ctb), ell, _dev_ptr(rlk), _dev_ptr(out),
-                                                     batch, _dev_ptr(ws), ws.numel() * 8, _stream()), "hmult_relin_rescale_merged")
+    _hmult("hmult_relin_rescale_merged", torch.int64, ctx, cta, ctb, ell, rlk, out, ws)
 
 
-def _ptr_array(tensors):
+def hmult_relin_rescale_u32(ctx: Context, cta: torch.Tensor, ctb: torch.Tensor, ell: int, rlk: torch.Tensor, out: torch.Tensor,
+                            ws: torch.Tensor) -> None:
+    """cta, ctb, rlk, out: int32 tensors, one residue (< 2^32) per word; ws: int64 as for hmult_relin_rescale."""
+    _hmult("hmult_relin_rescale_u32", torch.int32, ctx, cta, ctb, ell, rlk, out, ws)
+
+
+def hmult_relin_rescale_merged_u32(ctx: Context, cta: torch.Tensor, ctb: torch.Tensor, ell: int, rlk: torch.Tensor,
+                                   out: torch.Tensor, ws: torch.Tensor) -> None:
+    _hmult("hmult_relin_rescale_merged_u32", torch.int32, ctx, cta, ctb, ell, rlk, out, ws)
+
+
+def _ptr_array(tensors, dtype=torch.int64):
     """Host array of device pointers; None entries become NULL."""
-    return (_vp * len(tensors))(*[None if t is None else _dev_ptr(t) for t in tensors])
+    return (_vp * len(tensors))(*[None if t is None else _dev_ptr(t, dtype) for t in tensors])
 
 
 def _plaintexts_ok(ctx: Context, pts) -> None:
@@ -302,17 +346,27 @@ def _plaintexts_ok(ctx: Context, pts) -> None:
             _need(w, (ctx.L + ctx.K) * ctx.N, "plaintext", exact=False)
 
 
-def ks_rotate_mac_hoisted(ctx: Context, ct: torch.Tensor, ell: int, galois, rot_keys, pts, out: torch.Tensor, ws: torch.Tensor) -> None:
-    batch = _rotation_args(ctx, ct, ell, galois, rot_keys, "ks_rotate_mac_hoisted")
+def _rotate_mac(name, dtype, op, ctx, ct, ell, galois, rot_keys, pts, out, ws) -> None:
+    batch = _rotation_args(ctx, ct, ell, galois, rot_keys, name)
     if len(pts) != len(rot_keys):
-        raise KsError(f"ks_rotate_mac_hoisted: {len(pts)} plaintexts for {len(rot_keys)} rotations")
+        raise KsError(f"{name}: {len(pts)} plaintexts for {len(rot_keys)} rotations")
     _plaintexts_ok(ctx, pts)
-    _need(out, batch * 2 * ell * ctx.N, "ks_rotate_mac_hoisted out")
-    _workspace_ok(ctx, ws, KS_OP_ROTATE_HOISTED, ell, batch, len(rot_keys))
+    _need(out, batch * 2 * ell * ctx.N, f"{name} out")
+    _workspace_ok(ctx, ws, op, ell, batch, len(rot_keys))
     _on_device(ctx, ct, out, ws, *rot_keys, *pts)
-    _check(load_library().ks_rotate_mac_hoisted(ctx.handle, _dev_ptr(ct), ell, _u32_array(galois), _ptr_array(rot_keys), _ptr_array(pts),
-                                                len(rot_keys), _dev_ptr(out), batch, _dev_ptr(ws), ws.numel() * 8, _stream()),
-           "ks_rotate_mac_hoisted")
+    _check(getattr(load_library(), name)(ctx.handle, _dev_ptr(ct, dtype), ell, _u32_array(galois), _ptr_array(rot_keys, dtype),
+                                         _ptr_array(pts, dtype), len(rot_keys), _dev_ptr(out, dtype), batch, _dev_ptr(ws),
+                                         ws.numel() * 8, _stream()), name)
+
+
+def ks_rotate_mac_hoisted(ctx: Context, ct: torch.Tensor, ell: int, galois, rot_keys, pts, out: torch.Tensor, ws: torch.Tensor) -> None:
+    _rotate_mac("ks_rotate_mac_hoisted", torch.int64, KS_OP_ROTATE_HOISTED, ctx, ct, ell, galois, rot_keys, pts, out, ws)
+
+
+def ks_rotate_mac_hoisted_u32(ctx: Context, ct: torch.Tensor, ell: int, galois, rot_keys, pts, out: torch.Tensor,
+                              ws: torch.Tensor) -> None:
+    """ct, keys, plaintexts, out: int32 tensors, one residue (< 2^32) per word; ws: int64, KS_OP_ROTATE_HOISTED_U32."""
+    _rotate_mac("ks_rotate_mac_hoisted_u32", torch.int32, KS_OP_ROTATE_HOISTED_U32, ctx, ct, ell, galois, rot_keys, pts, out, ws)
 
 
 def ks_bsgs_linear_transform(ctx: Context, ct: torch.Tensor, ell: int, baby_galois, baby_keys, giant_galois, giant_keys, pts,

@@ -89,9 +89,12 @@ extern "C" size_t ks_workspace_bytes(const ks_ctx* c, int op, uint32_t ell, uint
     switch (op) {
         case KS_OP_KEYSWITCH: break;
         case KS_OP_ROTATE_HOISTED:
+        case KS_OP_ROTATE_HOISTED_U32:
             if (n_rot == 0) return 0;
             // accumulators and converted limbs for a whole group of rotations
             words += (uint64_t)(std::min(n_rot, kRotGroup) - 1) * bc * (2 * lv.E + 2 * ell) * N;
+            // the chunk's ciphertexts widened to 64-bit words
+            if (op == KS_OP_ROTATE_HOISTED_U32) words += (uint64_t)bc * 2 * ell * N;
             break;
         case KS_OP_BSGS: {
             // second set of raised digits and accumulators (outer level), inner result [bc][2][ell]
@@ -142,6 +145,32 @@ extern "C" int ntt_inv(const ks_ctx* c, uint64_t* data, const uint32_t* mod_ids,
     return finish("ntt_inv");
 }
 
+static bool moduli_fit_u32(const ks_ctx* c) {
+    for (uint64_t m : c->mod)
+        if (m >> 32) return false;
+    return true;
+}
+
+static int ntt_u32(const ks_ctx* c, uint32_t* data, const uint32_t* mod_ids, uint32_t nlimbs, uint32_t batch, void* stream,
+                   bool inverse) {
+    LimbMap map;
+    int rc = check_map_args(c, data, mod_ids, nlimbs, &map);
+    if (rc != KS_OK) return rc;
+    if (!moduli_fit_u32(c)) return KS_EINVAL;
+    if (batch == 0) return KS_OK;
+    if ((uint64_t)batch * nlimbs > (1u << 26)) return KS_EINVAL;
+    launch_ntt_u32(c, map, data, (uint64_t)nlimbs * c->N, batch, inverse, static_cast<hipStream_t>(stream));
+    return finish(inverse ? "ntt_inv_u32" : "ntt_fwd_u32");
+}
+
+extern "C" int ntt_fwd_u32(const ks_ctx* c, uint32_t* data, const uint32_t* mod_ids, uint32_t nlimbs, uint32_t batch, void* stream) {
+    return ntt_u32(c, data, mod_ids, nlimbs, batch, stream, false);
+}
+
+extern "C" int ntt_inv_u32(const ks_ctx* c, uint32_t* data, const uint32_t* mod_ids, uint32_t nlimbs, uint32_t batch, void* stream) {
+    return ntt_u32(c, data, mod_ids, nlimbs, batch, stream, true);
+}
+
 // Key of a registered conversion: n_src, source ids, target ids.  Returns KS_OK or KS_EINVAL.
 static int bconv_key(const ks_ctx* c, const uint32_t* src_ids, uint32_t n_src, const uint32_t* dst_ids, uint32_t n_dst,
                      std::vector<uint32_t>* key) {
@@ -184,12 +213,13 @@ extern "C" int bconv_prepare(ks_ctx* c, const uint32_t* src_ids, uint32_t n_src,
     return KS_OK;
 }
 
-extern "C" int bconv(const ks_ctx* c, const uint64_t* in, const uint32_t* src_ids, uint32_t n_src, uint64_t* out,
-                     const uint32_t* dst_ids, uint32_t n_dst, uint32_t batch, void* stream) {
+static int bconv_impl(const ks_ctx* c, const void* in, const uint32_t* src_ids, uint32_t n_src, void* out, const uint32_t* dst_ids,
+                      uint32_t n_dst, uint32_t batch, void* stream, bool words32) {
     if (!in || !out || !aligned16(in) || !aligned16(out)) return KS_EINVAL;
     std::vector<uint32_t> key;
     int rc = bconv_key(c, src_ids, n_src, dst_ids, n_dst, &key);
     if (rc != KS_OK) return rc;
+    if (words32 && !moduli_fit_u32(c)) return KS_EINVAL;
     PlanSet set;
     {
         std::lock_guard<std::mutex> lock(c->mu);
@@ -199,16 +229,30 @@ extern "C" int bconv(const ks_ctx* c, const uint64_t* in, const uint32_t* src_id
     }
     if (batch == 0) return KS_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const uint64_t N = c->N;
+    const uint64_t N = c->N, word = words32 ? 4 : 8;
     for (uint32_t b0 = 0; b0 < batch; b0 += 32768) {
         const uint32_t nb = std::min(batch - b0, 32768u);
+        const char* ip = static_cast<const char*>(in) + (uint64_t)b0 * n_src * N * word;
+        char* op = static_cast<char*>(out) + (uint64_t)b0 * n_dst * N * word;
         // the vector kernel unless the matrix-core one is asked for (it measured no faster: both move the same bytes
-        // and the conversion alone is bandwidth-bound)
-        auto launch = c->opt[KS_OPT_BCONV_KERNEL] == 2 ? launch_bconv_mfma : launch_bconv;
-        launch(c, set, n_src + n_dst, in + (uint64_t)b0 * n_src * N, (uint64_t)n_src * N, out + (uint64_t)b0 * n_dst * N,
-               (uint64_t)n_dst * N, nb, s);
+        // and the conversion alone is bandwidth-bound); 32-bit words always take the vector kernel
+        if (!words32 && c->opt[KS_OPT_BCONV_KERNEL] == 2)
+            launch_bconv_mfma(c, set, n_src + n_dst, reinterpret_cast<const uint64_t*>(ip), (uint64_t)n_src * N,
+                              reinterpret_cast<uint64_t*>(op), (uint64_t)n_dst * N, nb, s);
+        else
+            launch_bconv(c, set, n_src + n_dst, ip, (uint64_t)n_src * N, op, (uint64_t)n_dst * N, nb, s, words32);
     }
-    return finish("bconv");
+    return finish(words32 ? "bconv_u32" : "bconv");
+}
+
+extern "C" int bconv(const ks_ctx* c, const uint64_t* in, const uint32_t* src_ids, uint32_t n_src, uint64_t* out,
+                     const uint32_t* dst_ids, uint32_t n_dst, uint32_t batch, void* stream) {
+    return bconv_impl(c, in, src_ids, n_src, out, dst_ids, n_dst, batch, stream, false);
+}
+
+extern "C" int bconv_u32(const ks_ctx* c, const uint32_t* in, const uint32_t* src_ids, uint32_t n_src, uint32_t* out,
+                         const uint32_t* dst_ids, uint32_t n_dst, uint32_t batch, void* stream) {
+    return bconv_impl(c, in, src_ids, n_src, out, dst_ids, n_dst, batch, stream, true);
 }
 
 static int check_pipeline_args(const ks_ctx* c, uint32_t ell, uint32_t min_ell, const void* a, const void* b, const void* o,
@@ -224,9 +268,7 @@ int ks::keyswitch_impl(const ks_ctx* c, const void* d, uint32_t ell, const void*
                           size_t ws_bytes, void* stream, bool words32) {
     int rc = check_pipeline_args(c, ell, 1, d, evk, out, ws);
     if (rc != KS_OK) return rc;
-    if (words32)
-        for (uint64_t m : c->mod)
-            if (m >> 32) return KS_EINVAL;
+    if (words32 && !moduli_fit_u32(c)) return KS_EINVAL;
     if (batch == 0) return KS_OK;
     if (ws_bytes < ks_workspace_bytes(c, KS_OP_KEYSWITCH, ell, batch, 0)) return KS_EWORKSPACE;
     const Level& lv = c->levels[ell - 1];
@@ -241,7 +283,7 @@ int ks::keyswitch_impl(const ks_ctx* c, const void* d, uint32_t ell, const void*
         uint64_t* conv = acc + w.acc;
         const char* dc = static_cast<const char*>(d) + (uint64_t)b0 * d_ps * word;
         mod_up(c, lv, dc, d_ps, coeff, lifted, bc, false, s, words32);
-        launch_rows_inner_product(c, lv, dc, d_ps, lifted, evk, acc, bc, s, words32);
+        launch_rows_inner_product(c, lv, dc, d_ps, lifted, evk, acc, bc, s, words32, words32);
         mod_down(c, lv, acc, conv, static_cast<char*>(out) + (uint64_t)b0 * out_bs * word, out_bs, nullptr, 0, 0, 1, bc, true, s, words32);
     }
     return finish(words32 ? "ks_keyswitch_u32" : "ks_keyswitch");
@@ -257,9 +299,23 @@ extern "C" int ks_keyswitch_u32(const ks_ctx* c, const uint32_t* d, uint32_t ell
     return keyswitch_impl(c, d, ell, evk, out, batch, ws, ws_bytes, stream, true);
 }
 
-extern "C" int ks_rotate_hoisted(const ks_ctx* c, const uint64_t* ct, uint32_t ell, const uint32_t* galois,
-                                 const uint64_t* const* rot_keys, uint32_t n_rot, uint64_t* out, uint32_t batch, void* ws,
-                                 size_t ws_bytes, void* stream) {
+// Start of a chunk's ciphertexts as 64-bit words: the caller's own, or (words32) a widened copy at the head of the
+// workspace, whose remaining part starts at *rest.
+static const uint64_t* chunk_ct(const ks_ctx* c, const void* ct, uint32_t b0, uint32_t bc, uint64_t ct_bs, bool words32, void* ws,
+                                uint64_t** rest, hipStream_t s) {
+    if (!words32) {
+        *rest = static_cast<uint64_t*>(ws);
+        return static_cast<const uint64_t*>(ct) + (uint64_t)b0 * ct_bs;
+    }
+    uint64_t* wide = static_cast<uint64_t*>(ws);
+    launch_widen_u32(static_cast<const uint32_t*>(ct) + (uint64_t)b0 * ct_bs, wide, (uint64_t)bc * ct_bs, s);
+    *rest = wide + (uint64_t)bc * ct_bs;
+    return wide;
+}
+
+// ct, keys and out in 64-bit words, or all in 32-bit words (words32).
+static int rotate_hoisted_impl(const ks_ctx* c, const void* ct, uint32_t ell, const uint32_t* galois, const void* const* rot_keys,
+                               uint32_t n_rot, void* out, uint32_t batch, void* ws, size_t ws_bytes, void* stream, bool words32) {
     int rc = check_pipeline_args(c, ell, 1, ct, ct, out, ws);
     if (rc != KS_OK) return rc;
     if (!galois || !rot_keys || n_rot == 0) return KS_EINVAL;
@@ -267,26 +323,27 @@ extern "C" int ks_rotate_hoisted(const ks_ctx* c, const uint64_t* ct, uint32_t e
         if ((galois[r] & 1u) == 0 || galois[r] >= 2u * c->N) return KS_EINVAL;
         if (!rot_keys[r] || !aligned16(rot_keys[r])) return KS_EINVAL;
     }
+    if (words32 && !moduli_fit_u32(c)) return KS_EINVAL;
     if (batch == 0) return KS_OK;
-    if (ws_bytes < ks_workspace_bytes(c, KS_OP_ROTATE_HOISTED, ell, batch, n_rot)) return KS_EWORKSPACE;
+    if (ws_bytes < ks_workspace_bytes(c, words32 ? KS_OP_ROTATE_HOISTED_U32 : KS_OP_ROTATE_HOISTED, ell, batch, n_rot))
+        return KS_EWORKSPACE;
     const Level& lv = c->levels[ell - 1];
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const uint64_t N = c->N, ct_bs = 2ull * ell * N, out_bs = (uint64_t)n_rot * 2 * ell * N;
+    const uint64_t N = c->N, ct_bs = 2ull * ell * N, out_bs = (uint64_t)n_rot * 2 * ell * N, word = words32 ? 4 : 8;
     for (uint32_t b0 = 0; b0 < batch; b0 += kChunk) {
         const uint32_t bc = std::min(batch - b0, kChunk);
         const KsWorkspace w = ks_ws_words(c, lv, bc);
-        uint64_t* coeff = static_cast<uint64_t*>(ws);
+        uint64_t* coeff;
+        const uint64_t* c0 = chunk_ct(c, ct, b0, bc, ct_bs, words32, ws, &coeff, s);
         uint64_t* lifted = coeff + w.coeff;
         uint64_t* acc = lifted + w.lifted;
-        uint64_t* conv = acc + w.acc;
-        const uint64_t* c0 = ct + (uint64_t)b0 * ct_bs;
         const uint64_t* c1 = c0 + (uint64_t)ell * N;
         mod_up(c, lv, c1, ct_bs, coeff, lifted, bc, true, s);   // finished once, shared by every rotation
         // Rotations go in groups: one gather launch forms the accumulators of the whole group (the raised digits then come
         // from memory once per group), the inverse transform and the conversion run over the group as one batch, and only
         // the last kernel, which adds sigma_g(c0) through a rotation's own permutation, runs per rotation.
         const uint32_t group = std::min(n_rot, kRotGroup);
-        conv = acc + (uint64_t)group * w.acc;
+        uint64_t* conv = acc + (uint64_t)group * w.acc;
         const uint64_t acc_ps = (uint64_t)lv.E * N, conv_ps = (uint64_t)ell * N;
         for (uint32_t r0 = 0; r0 < n_rot; r0 += group) {
             MacRotations rot;
@@ -296,22 +353,36 @@ extern "C" int ks_rotate_hoisted(const ks_ctx* c, const uint64_t* ct, uint32_t e
                 rot.key[r] = rot_keys[r0 + r];
                 rot.pt[r] = nullptr;
             }
-            launch_inner_product(c, lv, c1, ct_bs, lifted, rot, acc, bc, s);
+            launch_inner_product(c, lv, c1, ct_bs, lifted, rot, acc, bc, s, words32);
             const uint32_t polys = 2 * rot.n * bc;
             launch_ntt_inv_rows(c, lv.special_map, XformIO{acc, acc, acc_ps, acc_ps, polys}, s);
             launch_ntt_inv_cols(c, lv.special_map, acc, acc_ps, polys, c->d_moddown_scale, true, true, s);
             launch_bconv_ntt_cols(c, lv.moddown, c->K + lv.ell, acc, acc_ps, conv, conv_ps, polys, s, moddown_ops(c, lv));
             for (uint32_t r = 0; r < rot.n; ++r)
                 launch_rows_moddown_finish(c, lv, acc + (uint64_t)r * w.acc, conv + (uint64_t)r * w.conv,
-                                           out + (uint64_t)b0 * out_bs + (uint64_t)(r0 + r) * 2 * ell * N, out_bs, c0, ct_bs, 1,
-                                           galois[r0 + r], bc, s);
+                                           static_cast<char*>(out) + ((uint64_t)b0 * out_bs + (uint64_t)(r0 + r) * 2 * ell * N) * word,
+                                           out_bs, c0, ct_bs, 1, galois[r0 + r], bc, s, nullptr, words32);
         }
     }
-    return finish("ks_rotate_hoisted");
+    return finish(words32 ? "ks_rotate_hoisted_u32" : "ks_rotate_hoisted");
+}
+
+extern "C" int ks_rotate_hoisted(const ks_ctx* c, const uint64_t* ct, uint32_t ell, const uint32_t* galois,
+                                 const uint64_t* const* rot_keys, uint32_t n_rot, uint64_t* out, uint32_t batch, void* ws,
+                                 size_t ws_bytes, void* stream) {
+    return rotate_hoisted_impl(c, ct, ell, galois, reinterpret_cast<const void* const*>(rot_keys), n_rot, out, batch, ws, ws_bytes,
+                               stream, false);
+}
+
+extern "C" int ks_rotate_hoisted_u32(const ks_ctx* c, const uint32_t* ct, uint32_t ell, const uint32_t* galois,
+                                     const uint32_t* const* rot_keys, uint32_t n_rot, uint32_t* out, uint32_t batch, void* ws,
+                                     size_t ws_bytes, void* stream) {
+    return rotate_hoisted_impl(c, ct, ell, galois, reinterpret_cast<const void* const*>(rot_keys), n_rot, out, batch, ws, ws_bytes,
+                               stream, true);
 }
 
 // Galois elements, keys and plaintexts of a rotate-multiply-accumulate: g = 1 needs no key, a null plaintext is 1.
-static int check_mac_rotations(const ks_ctx* c, const uint32_t* galois, const uint64_t* const* keys, const uint64_t* const* pts,
+static int check_mac_rotations(const ks_ctx* c, const uint32_t* galois, const void* const* keys, const void* const* pts,
                                uint32_t n) {
     if (!galois || !keys || n == 0) return KS_EINVAL;
     for (uint32_t r = 0; r < n; ++r) {
@@ -324,8 +395,8 @@ static int check_mac_rotations(const ks_ctx* c, const uint32_t* galois, const ui
 
 // u (+)= sum_r pt_r * rot_{g_r}(ct) for all n rotations, in launches of kMacRotations
 static void rotate_mac_all(const ks_ctx* c, const Level& lv, const uint64_t* ct, uint64_t ct_bs, const uint64_t* lifted,
-                           const uint32_t* galois, const uint64_t* const* keys, const uint64_t* const* pts, uint32_t n, uint64_t* u,
-                           uint32_t bc, bool accumulate, hipStream_t s) {
+                           const uint32_t* galois, const void* const* keys, const void* const* pts, uint32_t n, uint64_t* u,
+                           uint32_t bc, bool accumulate, hipStream_t s, bool key_words32 = false) {
     for (uint32_t r0 = 0; r0 < n; r0 += kMacRotations) {
         MacRotations rot;
         rot.n = std::min<uint32_t>(n - r0, kMacRotations);
@@ -334,34 +405,50 @@ static void rotate_mac_all(const ks_ctx* c, const Level& lv, const uint64_t* ct,
             rot.key[r] = keys[r0 + r];
             rot.pt[r] = pts ? pts[r0 + r] : nullptr;
         }
-        launch_rotate_mac(c, lv, ct, ct_bs, lifted, rot, u, bc, accumulate || r0 != 0, s);
+        launch_rotate_mac(c, lv, ct, ct_bs, lifted, rot, u, bc, accumulate || r0 != 0, s, key_words32);
     }
+}
+
+static int rotate_mac_impl(const ks_ctx* c, const void* ct, uint32_t ell, const uint32_t* galois, const void* const* rot_keys,
+                           const void* const* pts, uint32_t n_rot, void* out, uint32_t batch, void* ws, size_t ws_bytes, void* stream,
+                           bool words32) {
+    int rc = check_pipeline_args(c, ell, 1, ct, ct, out, ws);
+    if (rc != KS_OK) return rc;
+    if (!pts || (rc = check_mac_rotations(c, galois, rot_keys, pts, n_rot)) != KS_OK) return KS_EINVAL;
+    if (words32 && !moduli_fit_u32(c)) return KS_EINVAL;
+    if (batch == 0) return KS_OK;
+    if (ws_bytes < ks_workspace_bytes(c, words32 ? KS_OP_ROTATE_HOISTED_U32 : KS_OP_ROTATE_HOISTED, ell, batch, n_rot))
+        return KS_EWORKSPACE;
+    const Level& lv = c->levels[ell - 1];
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint64_t N = c->N, ct_bs = 2ull * ell * N, word = words32 ? 4 : 8;
+    for (uint32_t b0 = 0; b0 < batch; b0 += kChunk) {
+        const uint32_t bc = std::min(batch - b0, kChunk);
+        const KsWorkspace w = ks_ws_words(c, lv, bc);
+        uint64_t* coeff;
+        const uint64_t* c0 = chunk_ct(c, ct, b0, bc, ct_bs, words32, ws, &coeff, s);
+        uint64_t* lifted = coeff + w.coeff;
+        uint64_t* acc = lifted + w.lifted;
+        uint64_t* conv = acc + w.acc;
+        mod_up(c, lv, c0 + (uint64_t)ell * N, ct_bs, coeff, lifted, bc, true, s);   // finished once, shared by every rotation
+        rotate_mac_all(c, lv, c0, ct_bs, lifted, galois, rot_keys, pts, n_rot, acc, bc, false, s, words32);
+        mod_down(c, lv, acc, conv, static_cast<char*>(out) + (uint64_t)b0 * ct_bs * word, ct_bs, nullptr, 0, 0, 1, bc, false, s, words32);
+    }
+    return finish(words32 ? "ks_rotate_mac_hoisted_u32" : "ks_rotate_mac_hoisted");
 }
 
 extern "C" int ks_rotate_mac_hoisted(const ks_ctx* c, const uint64_t* ct, uint32_t ell, const uint32_t* galois,
                                      const uint64_t* const* rot_keys, const uint64_t* const* pts, uint32_t n_rot, uint64_t* out,
                                      uint32_t batch, void* ws, size_t ws_bytes, void* stream) {
-    int rc = check_pipeline_args(c, ell, 1, ct, ct, out, ws);
-    if (rc != KS_OK) return rc;
-    if (!pts || (rc = check_mac_rotations(c, galois, rot_keys, pts, n_rot)) != KS_OK) return KS_EINVAL;
-    if (batch == 0) return KS_OK;
-    if (ws_bytes < ks_workspace_bytes(c, KS_OP_ROTATE_HOISTED, ell, batch, n_rot)) return KS_EWORKSPACE;
-    const Level& lv = c->levels[ell - 1];
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const uint64_t N = c->N, ct_bs = 2ull * ell * N;
-    for (uint32_t b0 = 0; b0 < batch; b0 += kChunk) {
-        const uint32_t bc = std::min(batch - b0, kChunk);
-        const KsWorkspace w = ks_ws_words(c, lv, bc);
-        uint64_t* coeff = static_cast<uint64_t*>(ws);
-        uint64_t* lifted = coeff + w.coeff;
-        uint64_t* acc = lifted + w.lifted;
-        uint64_t* conv = acc + w.acc;
-        const uint64_t* c0 = ct + (uint64_t)b0 * ct_bs;
-        mod_up(c, lv, c0 + (uint64_t)ell * N, ct_bs, coeff, lifted, bc, true, s);   // finished once, shared by every rotation
-        rotate_mac_all(c, lv, c0, ct_bs, lifted, galois, rot_keys, pts, n_rot, acc, bc, false, s);
-        mod_down(c, lv, acc, conv, out + (uint64_t)b0 * ct_bs, ct_bs, nullptr, 0, 0, 1, bc, false, s);
-    }
-    return finish("ks_rotate_mac_hoisted");
+    return rotate_mac_impl(c, ct, ell, galois, reinterpret_cast<const void* const*>(rot_keys),
+                           reinterpret_cast<const void* const*>(pts), n_rot, out, batch, ws, ws_bytes, stream, false);
+}
+
+extern "C" int ks_rotate_mac_hoisted_u32(const ks_ctx* c, const uint32_t* ct, uint32_t ell, const uint32_t* galois,
+                                         const uint32_t* const* rot_keys, const uint32_t* const* pts, uint32_t n_rot, uint32_t* out,
+                                         uint32_t batch, void* ws, size_t ws_bytes, void* stream) {
+    return rotate_mac_impl(c, ct, ell, galois, reinterpret_cast<const void* const*>(rot_keys),
+                           reinterpret_cast<const void* const*>(pts), n_rot, out, batch, ws, ws_bytes, stream, true);
 }
 
 extern "C" int ks_bsgs_linear_transform(const ks_ctx* c, const uint64_t* ct, uint32_t ell, const uint32_t* baby_galois,
@@ -370,9 +457,12 @@ extern "C" int ks_bsgs_linear_transform(const ks_ctx* c, const uint64_t* ct, uin
                                         uint32_t batch, void* ws, size_t ws_bytes, void* stream) {
     int rc = check_pipeline_args(c, ell, 1, ct, ct, out, ws);
     if (rc != KS_OK) return rc;
-    if (!pts || check_mac_rotations(c, giant_galois, giant_keys, nullptr, n2) != KS_OK) return KS_EINVAL;
+    const void* const* bkeys = reinterpret_cast<const void* const*>(baby_keys);
+    const void* const* gkeys = reinterpret_cast<const void* const*>(giant_keys);
+    const void* const* ptv = reinterpret_cast<const void* const*>(pts);
+    if (!pts || check_mac_rotations(c, giant_galois, gkeys, nullptr, n2) != KS_OK) return KS_EINVAL;
     for (uint32_t g = 0; g < n2; ++g)
-        if (check_mac_rotations(c, baby_galois, baby_keys, pts + (size_t)g * n1, n1) != KS_OK) return KS_EINVAL;
+        if (check_mac_rotations(c, baby_galois, bkeys, ptv + (size_t)g * n1, n1) != KS_OK) return KS_EINVAL;
     if (batch == 0) return KS_OK;
     if (ws_bytes < ks_workspace_bytes(c, KS_OP_BSGS, ell, batch, 0)) return KS_EWORKSPACE;
     const Level& lv = c->levels[ell - 1];
@@ -391,10 +481,10 @@ extern "C" int ks_bsgs_linear_transform(const ks_ctx* c, const uint64_t* ct, uin
         const uint64_t* c0 = ct + (uint64_t)b0 * ct_bs;
         mod_up(c, lv, c0 + (uint64_t)ell * N, ct_bs, coeff, lifted, bc, true, s);
         for (uint32_t g = 0; g < n2; ++g) {
-            rotate_mac_all(c, lv, c0, ct_bs, lifted, baby_galois, baby_keys, pts + (size_t)g * n1, n1, acc, bc, false, s);
+            rotate_mac_all(c, lv, c0, ct_bs, lifted, baby_galois, bkeys, ptv + (size_t)g * n1, n1, acc, bc, false, s);
             mod_down(c, lv, acc, conv, v, ct_bs, nullptr, 0, 0, 1, bc, false, s);
             if (giant_galois[g] != 1) mod_up(c, lv, v + (uint64_t)ell * N, ct_bs, coeff, lifted_v, bc, true, s);
-            rotate_mac_all(c, lv, v, ct_bs, lifted_v, giant_galois + g, giant_keys + g, nullptr, 1, acc_outer, bc, g != 0, s);
+            rotate_mac_all(c, lv, v, ct_bs, lifted_v, giant_galois + g, gkeys + g, nullptr, 1, acc_outer, bc, g != 0, s);
         }
         mod_down(c, lv, acc_outer, conv, out + (uint64_t)b0 * ct_bs, ct_bs, nullptr, 0, 0, 1, bc, false, s);
     }
@@ -404,8 +494,8 @@ extern "C" int ks_bsgs_linear_transform(const ks_ctx* c, const uint64_t* ct, uin
 // Division by P q_{ell-1} of acc + P addend in one conversion (ModDown merged with the rescale that would follow):
 // limb ell-1 joins the special limbs as a source, the targets are q_0..q_{ell-2}.  The fused inner product has already
 // run the row half of the inverse transform on the special limbs.
-static void mod_down_merged(const ks_ctx* c, const Level& lv, uint64_t* acc, uint64_t* conv, uint64_t* out, uint64_t out_bs,
-                            const uint64_t* addend, uint64_t addend_bs, uint32_t bc, hipStream_t s) {
+static void mod_down_merged(const ks_ctx* c, const Level& lv, uint64_t* acc, uint64_t* conv, void* out, uint64_t out_bs,
+                            const uint64_t* addend, uint64_t addend_bs, uint32_t bc, hipStream_t s, bool out_words32) {
     const uint64_t N = c->N, acc_ps = (uint64_t)lv.E * N, conv_ps = (uint64_t)lv.ell * N;
     launch_add_scaled_limb(c, acc, acc_ps, addend, addend_bs, (uint64_t)lv.ell * N, lv.ell - 1, lv.Pmod_last, bc, s);
     launch_ntt_inv_rows(c, lv.last_map, XformIO{acc, acc, acc_ps, acc_ps, 2 * bc}, s);
@@ -414,47 +504,23 @@ static void mod_down_merged(const ks_ctx* c, const Level& lv, uint64_t* acc, uin
     const double ops = (double)n_src * n_dst * 4.5 + n_dst * (3.0 + 4.0 * (c->logN - 8));
     launch_bconv_ntt_cols(c, lv.merged, n_src + n_dst, acc, acc_ps, conv, conv_ps, 2 * bc, s, ops);
     const FinishScale fs{lv.d_Dinv, lv.d_qlinv, n_dst};
-    launch_rows_moddown_finish(c, lv, acc, conv, out, out_bs, addend, addend_bs, 2, 1, bc, s, &fs);
+    launch_rows_moddown_finish(c, lv, acc, conv, out, out_bs, addend, addend_bs, 2, 1, bc, s, &fs, out_words32);
 }
 
-extern "C" int hmult_relin_rescale_merged(const ks_ctx* c, const uint64_t* cta, const uint64_t* ctb, uint32_t ell, const uint64_t* rlk,
-                                          uint64_t* out, uint32_t batch, void* ws, size_t ws_bytes, void* stream) {
+// cta, ctb, rlk and out in 64-bit words, or all four in 32-bit words (words32); the tensor product and everything after it
+// in the workspace stay 64-bit.
+static int hmult_impl(const ks_ctx* c, const void* cta, const void* ctb, uint32_t ell, const void* rlk, void* out, uint32_t batch,
+                      void* ws, size_t ws_bytes, void* stream, bool merged, bool words32) {
     int rc = check_pipeline_args(c, ell, 2, cta, ctb, out, ws);
     if (rc != KS_OK) return rc;
     if (!rlk || !aligned16(rlk)) return KS_EINVAL;
+    if (words32 && !moduli_fit_u32(c)) return KS_EINVAL;
     if (batch == 0) return KS_OK;
     if (ws_bytes < ks_workspace_bytes(c, KS_OP_HMULT_RELIN_RESCALE, ell, batch, 0)) return KS_EWORKSPACE;
     const Level& lv = c->levels[ell - 1];
-    if (!lv.merged.d_plans) return KS_EINVAL;  // K + 1 sources exceed what one conversion takes
+    if (merged && !lv.merged.d_plans) return KS_EINVAL;  // K + 1 sources exceed what one conversion takes
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const uint64_t N = c->N, ct_bs = 2ull * ell * N, td_bs = 3ull * ell * N, out_bs = 2ull * (ell - 1) * N;
-    for (uint32_t b0 = 0; b0 < batch; b0 += kChunk) {
-        const uint32_t bc = std::min(batch - b0, kChunk);
-        const KsWorkspace w = ks_ws_words(c, lv, bc);
-        uint64_t* coeff = static_cast<uint64_t*>(ws);
-        uint64_t* lifted = coeff + w.coeff;
-        uint64_t* acc = lifted + w.lifted;
-        uint64_t* conv = acc + w.acc;
-        uint64_t* td = conv + w.conv;  // [bc][3][ell][N]
-        launch_tensor_product(c, cta + (uint64_t)b0 * ct_bs, ctb + (uint64_t)b0 * ct_bs, td, ell, bc, s);
-        const uint64_t* d2 = td + 2ull * ell * N;
-        mod_up(c, lv, d2, td_bs, coeff, lifted, bc, false, s);
-        launch_rows_inner_product(c, lv, d2, td_bs, lifted, rlk, acc, bc, s);
-        mod_down_merged(c, lv, acc, conv, out + (uint64_t)b0 * out_bs, out_bs, td, td_bs, bc, s);
-    }
-    return finish("hmult_relin_rescale_merged");
-}
-
-extern "C" int hmult_relin_rescale(const ks_ctx* c, const uint64_t* cta, const uint64_t* ctb, uint32_t ell, const uint64_t* rlk,
-                                   uint64_t* out, uint32_t batch, void* ws, size_t ws_bytes, void* stream) {
-    int rc = check_pipeline_args(c, ell, 2, cta, ctb, out, ws);
-    if (rc != KS_OK) return rc;
-    if (!rlk || !aligned16(rlk)) return KS_EINVAL;
-    if (batch == 0) return KS_OK;
-    if (ws_bytes < ks_workspace_bytes(c, KS_OP_HMULT_RELIN_RESCALE, ell, batch, 0)) return KS_EWORKSPACE;
-    const Level& lv = c->levels[ell - 1];
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const uint64_t N = c->N, ct_bs = 2ull * ell * N, td_bs = 3ull * ell * N, out_bs = 2ull * (ell - 1) * N;
+    const uint64_t N = c->N, ct_bs = 2ull * ell * N, td_bs = 3ull * ell * N, out_bs = 2ull * (ell - 1) * N, word = words32 ? 4 : 8;
     LimbMap one;
     one.n = 1;
     one.off[0] = 0;
@@ -470,16 +536,44 @@ extern "C" int hmult_relin_rescale(const ks_ctx* c, const uint64_t* cta, const u
         uint64_t* sum = td + (uint64_t)bc * td_bs;              // [bc][2][ell][N]
         uint64_t* last = sum + (uint64_t)bc * ct_bs;            // [2 bc][N]
         uint64_t* spread = last + (uint64_t)bc * 2 * N;         // [2 bc][ell-1][N]
-        launch_tensor_product(c, cta + (uint64_t)b0 * ct_bs, ctb + (uint64_t)b0 * ct_bs, td, ell, bc, s);
+        char* oc = static_cast<char*>(out) + (uint64_t)b0 * out_bs * word;
+        launch_tensor_product(c, static_cast<const char*>(cta) + (uint64_t)b0 * ct_bs * word,
+                              static_cast<const char*>(ctb) + (uint64_t)b0 * ct_bs * word, td, ell, bc, s, words32);
         const uint64_t* d2 = td + 2ull * ell * N;
         mod_up(c, lv, d2, td_bs, coeff, lifted, bc, false, s);
-        launch_rows_inner_product(c, lv, d2, td_bs, lifted, rlk, acc, bc, s);
+        launch_rows_inner_product(c, lv, d2, td_bs, lifted, rlk, acc, bc, s, false, words32);
+        if (merged) {
+            mod_down_merged(c, lv, acc, conv, oc, out_bs, td, td_bs, bc, s, words32);
+            continue;
+        }
         mod_down(c, lv, acc, conv, sum, ct_bs, td, td_bs, 2, 1, bc, true, s);
         // rescale both components: inverse transform of the last limb, centred remainder to every q_i, forward
         // transform, subtract and divide
         launch_ntt_inv_rows(c, one, XformIO{sum + (uint64_t)(ell - 1) * N, last, (uint64_t)ell * N, N, 2 * bc}, s);
         launch_ntt_inv_cols(c, one, last, N, 2 * bc, c->d_ninv, false, true, s);   // canonical doubles
-        launch_rescale_fused(c, lv, sum, last, spread, out + (uint64_t)b0 * out_bs, 2 * bc, s);
+        launch_rescale_fused(c, lv, sum, last, spread, oc, 2 * bc, s, words32);
     }
-    return finish("hmult_relin_rescale");
+    if (merged) return finish(words32 ? "hmult_relin_rescale_merged_u32" : "hmult_relin_rescale_merged");
+    return finish(words32 ? "hmult_relin_rescale_u32" : "hmult_relin_rescale");
+}
+
+extern "C" int hmult_relin_rescale_merged(const ks_ctx* c, const uint64_t* cta, const uint64_t* ctb, uint32_t ell, const uint64_t* rlk,
+                                          uint64_t* out, uint32_t batch, void* ws, size_t ws_bytes, void* stream) {
+    return hmult_impl(c, cta, ctb, ell, rlk, out, batch, ws, ws_bytes, stream, true, false);
+}
+
+extern "C" int hmult_relin_rescale(const ks_ctx* c, const uint64_t* cta, const uint64_t* ctb, uint32_t ell, const uint64_t* rlk,
+                                   uint64_t* out, uint32_t batch, void* ws, size_t ws_bytes, void* stream) {
+    return hmult_impl(c, cta, ctb, ell, rlk, out, batch, ws, ws_bytes, stream, false, false);
+}
+
+extern "C" int hmult_relin_rescale_merged_u32(const ks_ctx* c, const uint32_t* cta, const uint32_t* ctb, uint32_t ell,
+                                              const uint32_t* rlk, uint32_t* out, uint32_t batch, void* ws, size_t ws_bytes,
+                                              void* stream) {
+    return hmult_impl(c, cta, ctb, ell, rlk, out, batch, ws, ws_bytes, stream, true, true);
+}
+
+extern "C" int hmult_relin_rescale_u32(const ks_ctx* c, const uint32_t* cta, const uint32_t* ctb, uint32_t ell, const uint32_t* rlk,
+                                       uint32_t* out, uint32_t batch, void* ws, size_t ws_bytes, void* stream) {
+    return hmult_impl(c, cta, ctb, ell, rlk, out, batch, ws, ws_bytes, stream, false, true);
 }

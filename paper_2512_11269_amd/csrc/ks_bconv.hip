@@ -9,13 +9,14 @@
 
 namespace ks {
 
-template <int NSRC>
-__global__ __launch_bounds__(256) void bconv_kernel(const BConvPlan* __restrict__ plans, const uint64_t* __restrict__ in,
-                                                    uint64_t in_ps, uint64_t* __restrict__ out, uint64_t out_ps, uint32_t N) {
+// W: word type of in and out (64-bit, or 32-bit for moduli below 2^32; strides in words).
+template <int NSRC, typename W>
+__global__ __launch_bounds__(256) void bconv_kernel(const BConvPlan* __restrict__ plans, const W* __restrict__ in,
+                                                    uint64_t in_ps, W* __restrict__ out, uint64_t out_ps, uint32_t N) {
     const BConvPlan& P = plans[blockIdx.y];
     const uint32_t n = blockIdx.x * 256 + threadIdx.x;
-    const uint64_t* ip = in + (uint64_t)blockIdx.z * in_ps + n;
-    uint64_t* op = out + (uint64_t)blockIdx.z * out_ps + n;
+    const W* ip = in + (uint64_t)blockIdx.z * in_ps + n;
+    W* op = out + (uint64_t)blockIdx.z * out_ps + n;
     const int n_src = (int)P.n_src;
     double y[NSRC];
 #pragma unroll
@@ -23,7 +24,7 @@ __global__ __launch_bounds__(256) void bconv_kernel(const BConvPlan* __restrict_
         y[i] = 0.0;
         if (i < n_src) {
             const Mod mi = P.src_mod[i];
-            const double x = u64_to_f64(ip[(uint64_t)P.src_limb[i] * N]);
+            const double x = word_to_f64<W>(ip[(uint64_t)P.src_limb[i] * N]);
             y[i] = canon(mulmod_lazy(x, P.src_inv[i], mi), mi);
         }
     }
@@ -39,24 +40,28 @@ __global__ __launch_bounds__(256) void bconv_kernel(const BConvPlan* __restrict_
                 s2 = __builtin_fma(y[i], P.hat3[t][i][2], s2);
             }
         }
-        op[(uint64_t)P.dst_limb[t] * N] = f64_to_u64(canon(combine3_lazy(s0, s1, s2, mt), mt));
+        op[(uint64_t)P.dst_limb[t] * N] = f64_to_word<W>(canon(combine3_lazy(s0, s1, s2, mt), mt));
     }
 }
 
-void launch_bconv(const ks_ctx* c, const PlanSet& plans, uint32_t limbs_moved_per_poly, const uint64_t* in, uint64_t in_ps,
-                  uint64_t* out, uint64_t out_ps, uint32_t n_polys, hipStream_t s) {
+void launch_bconv(const ks_ctx* c, const PlanSet& plans, uint32_t limbs_moved_per_poly, const void* in, uint64_t in_ps,
+                  void* out, uint64_t out_ps, uint32_t n_polys, hipStream_t s, bool words32) {
     if (n_polys == 0 || plans.n_plans == 0) return;
     const dim3 grid(c->N / 256, plans.n_plans, n_polys), block(256);
     const BConvPlan* d_plans = plans.d_plans;
-    ProfScope ps("bconv", (double)limbs_moved_per_poly * n_polys * c->N * 8.0, s);
-    if (plans.shape_src <= 4)
-        hipLaunchKernelGGL(bconv_kernel<4>, grid, block, 0, s, d_plans, in, in_ps, out, out_ps, c->N);
-    else if (plans.shape_src <= 8)
-        hipLaunchKernelGGL(bconv_kernel<8>, grid, block, 0, s, d_plans, in, in_ps, out, out_ps, c->N);
-    else if (plans.shape_src <= 12)
-        hipLaunchKernelGGL(bconv_kernel<12>, grid, block, 0, s, d_plans, in, in_ps, out, out_ps, c->N);
-    else
-        hipLaunchKernelGGL(bconv_kernel<16>, grid, block, 0, s, d_plans, in, in_ps, out, out_ps, c->N);
+    ProfScope ps(words32 ? "bconv_u32" : "bconv", (double)limbs_moved_per_poly * n_polys * c->N * (words32 ? 4.0 : 8.0), s);
+#define KS_LAUNCH_BCONV(NS)                                                                                                    \
+    if (words32)                                                                                                               \
+        hipLaunchKernelGGL((bconv_kernel<NS, uint32_t>), grid, block, 0, s, d_plans, static_cast<const uint32_t*>(in), in_ps,  \
+                           static_cast<uint32_t*>(out), out_ps, c->N);                                                        \
+    else                                                                                                                       \
+        hipLaunchKernelGGL((bconv_kernel<NS, uint64_t>), grid, block, 0, s, d_plans, static_cast<const uint64_t*>(in), in_ps,  \
+                           static_cast<uint64_t*>(out), out_ps, c->N)
+    if (plans.shape_src <= 4) KS_LAUNCH_BCONV(4);
+    else if (plans.shape_src <= 8) KS_LAUNCH_BCONV(8);
+    else if (plans.shape_src <= 12) KS_LAUNCH_BCONV(12);
+    else KS_LAUNCH_BCONV(16);
+#undef KS_LAUNCH_BCONV
 }
 
 }  // namespace ks

@@ -82,6 +82,16 @@ KS_HD void split3(double y, double& y2, double& y1, double& y0) {
     y0 = rem - y1;
 }
 
+// The same for 0 <= y < 2^28 (contexts whose moduli are all below 2^28, the paper's word size): y = y1 + y0 with y1 a
+// multiple of 2^14 and |y0| <= 2^13.  With f_k = centred([f * 2^(14 k)]_t) * 2^(-14 k), |f_k| * 2^(14 k) <= 2^27, the sum
+// y1 f_1 + y0 f_0 is an integer congruent to y f modulo t and below 2^42 in magnitude: sixteen accumulate exactly, at
+// two FMAs per source and target and three additions per split.
+KS_HD void split2(double y, double& y1, double& y0) {
+    constexpr double kRound14 = 0x1.8p66;
+    y1 = (y + kRound14) - kRound14;
+    y0 = y - y1;
+}
+
 // (s2 * 2^24 + s1 * 2^12 + s0) mod p as a lazy representative, for exact non-negative integer sums s_k < 2^52
 // (the three partial sums of a base conversion whose factors were split into 12-bit pieces).
 KS_HD double combine3_lazy(double s0, double s1, double s2, Mod m) {

@@ -13,7 +13,7 @@ constexpr int kBatchGroup = 8;  // batch items sharing one read of the key slots
 // the launch, so the raised digits it gathers from are read from memory once per launch and from cache afterwards.
 // Branch-free like rotate_mac_kernel below: the digit count is a template parameter and a short last group recomputes
 // its last ciphertext, so every load of a rotation is issued before the first product.
-template <int NDIG>
+template <int NDIG, typename WK>
 __global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restrict__ mods, DigitRanges dg, uint32_t ell, uint32_t E,
                                                             uint32_t L, uint32_t M, uint32_t logN, const uint64_t* __restrict__ d,
                                                             uint64_t d_ps, const uint64_t* __restrict__ lifted, MacRotations rot,
@@ -37,8 +37,9 @@ __global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restric
 #pragma unroll 1
     for (uint32_t r = 0; r < rot.n; ++r) {
         const uint32_t sn = galois_source_slot(n, rot.galois[r], logN);
-        const uint64_t* key = rot.key[r] + (uint64_t)mid * N + n;
-        uint64_t kraw[NDIG][2], xraw[kBatchGroup][NDIG];
+        const WK* key = static_cast<const WK*>(rot.key[r]) + (uint64_t)mid * N + n;
+        WK kraw[NDIG][2];
+        uint64_t xraw[kBatchGroup][NDIG];
 #pragma unroll
         for (int j = 0; j < NDIG; ++j) {
             kraw[j][0] = key[(uint64_t)(j * 2 + 0) * M * N];
@@ -56,8 +57,8 @@ __global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restric
 #pragma unroll
             for (int j = 0; j < NDIG; ++j) {
                 const double x = u64_to_f64(xraw[bi][j]);
-                a0 += mulmod_lazy(x, u64_to_f64(kraw[j][0]), m);
-                a1 += mulmod_lazy(x, u64_to_f64(kraw[j][1]), m);
+                a0 += mulmod_lazy(x, word_to_f64<WK>(kraw[j][0]), m);
+                a1 += mulmod_lazy(x, word_to_f64<WK>(kraw[j][1]), m);
             }
             ar[(((uint64_t)b * 2 + 0) * E + pos) * N + n] = f64_to_u64(canon(reduce_lazy(a0, m), m));
             ar[(((uint64_t)b * 2 + 1) * E + pos) * N + n] = f64_to_u64(canon(reduce_lazy(a1, m), m));
@@ -66,7 +67,7 @@ __global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restric
 }
 
 void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, const uint64_t* lifted,
-                          const MacRotations& rot, uint64_t* acc, uint32_t batch, hipStream_t s) {
+                          const MacRotations& rot, uint64_t* acc, uint32_t batch, hipStream_t s, bool key_words32) {
     if (batch == 0 || rot.n == 0) return;
     DigitRanges dg;
     dg.ndig = lv.ndig;
@@ -78,11 +79,16 @@ void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, u
     const dim3 grid(c->N / 256, lv.E, groups), block(256);
     // reads: every raised digit limb per ciphertext once per launch, each rotation's key once per group; writes: both
     // accumulators of every rotation
+    const double wk = key_words32 ? 0.5 : 1.0;
     ProfScope ps("inner_product",
-                 ((double)batch * lv.ndig * lv.E + (double)rot.n * (2.0 * lv.ndig * lv.E * groups + 2.0 * lv.E * batch)) * c->N * 8.0, s);
-#define KS_LAUNCH_IP(ND)                                                                                                        \
-    hipLaunchKernelGGL(inner_product_kernel<ND>, grid, block, 0, s, c->d_mod, dg, lv.ell, lv.E, c->L, c->M, c->logN, d, d_ps, lifted, \
-                       rot, acc, batch)
+                 ((double)batch * lv.ndig * lv.E + (double)rot.n * (wk * 2.0 * lv.ndig * lv.E * groups + 2.0 * lv.E * batch)) * c->N * 8.0, s);
+#define KS_LAUNCH_IP(ND)                                                                                                                  \
+    if (key_words32)                                                                                                                      \
+        hipLaunchKernelGGL((inner_product_kernel<ND, uint32_t>), grid, block, 0, s, c->d_mod, dg, lv.ell, lv.E, c->L, c->M, c->logN, d, d_ps, \
+                           lifted, rot, acc, batch);                                                                                     \
+    else                                                                                                                                  \
+        hipLaunchKernelGGL((inner_product_kernel<ND, uint64_t>), grid, block, 0, s, c->d_mod, dg, lv.ell, lv.E, c->L, c->M, c->logN, d, d_ps, \
+                           lifted, rot, acc, batch)
     switch (lv.ndig) {
         case 1: KS_LAUNCH_IP(1); break;
         case 2: KS_LAUNCH_IP(2); break;
@@ -103,7 +109,7 @@ void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, u
 // Branch-free within a rotation on purpose (digit count as a template parameter, a short last group recomputes its last
 // ciphertext, special limbs read a c0 limb they multiply by zero): every load of a rotation is then issued before the
 // first product.  Galois element 1 is the unrotated ciphertext (P (c0, c1), no key read).
-template <int NDIG>
+template <int NDIG, typename WK>
 __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__ mods, const double* __restrict__ Pmod, DigitRanges dg,
                                                          uint32_t ell, uint32_t E, uint32_t L, uint32_t M, uint32_t logN,
                                                          const uint64_t* __restrict__ ct, uint64_t ct_bs,
@@ -144,16 +150,17 @@ __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__
     for (uint32_t r = 0; r < rot.n; ++r) {
         // the plaintext slot; a null plaintext is the constant 1, read (by every lane) from a one-word table so that the
         // load stays unconditional
-        const uint64_t* wp = rot.pt[r] ? rot.pt[r] + (uint64_t)mid * N + n : one;
+        // (the table holds the 64-bit word 1, whose low half is the 32-bit word 1)
+        const WK* wp = rot.pt[r] ? static_cast<const WK*>(rot.pt[r]) + (uint64_t)mid * N + n : reinterpret_cast<const WK*>(one);
         if (rot.galois[r] == 1) {  // uniform: the unrotated ciphertext, P (c0, c1), no key
             uint64_t c0raw[kBatchGroup], c1raw[kBatchGroup];
-            const uint64_t wraw = *wp;
+            const WK wraw = *wp;
 #pragma unroll
             for (int bi = 0; bi < kBatchGroup; ++bi) {
                 c0raw[bi] = c0p[bi][n];
                 c1raw[bi] = c0p[bi][(uint64_t)ell * N + n];
             }
-            const double w = u64_to_f64(wraw);
+            const double w = word_to_f64<WK>(wraw);
 #pragma unroll
             for (int bi = 0; bi < kBatchGroup; ++bi) {
                 u0[bi] += mulmod_lazy(mulmod_lazy(u64_to_f64(c0raw[bi]), pm, m), w, m);
@@ -162,29 +169,30 @@ __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__
             continue;
         }
         const uint32_t sn = galois_source_slot(n, rot.galois[r], logN);
-        const uint64_t* key = rot.key[r] + (uint64_t)mid * N + n;
-        uint64_t kraw[NDIG][2], xraw[kBatchGroup][NDIG], craw[kBatchGroup];
+        const WK* key = static_cast<const WK*>(rot.key[r]) + (uint64_t)mid * N + n;
+        WK kraw[NDIG][2];
+        uint64_t xraw[kBatchGroup][NDIG], craw[kBatchGroup];
 #pragma unroll
         for (int j = 0; j < NDIG; ++j) {
             kraw[j][0] = key[(uint64_t)(j * 2 + 0) * M * N];
             kraw[j][1] = key[(uint64_t)(j * 2 + 1) * M * N];
         }
-        const uint64_t wraw = *wp;
+        const WK wraw = *wp;
 #pragma unroll
         for (int bi = 0; bi < kBatchGroup; ++bi) {
 #pragma unroll
             for (int j = 0; j < NDIG; ++j) xraw[bi][j] = srcp[bi][j][sn];
             craw[bi] = c0p[bi][sn];
         }
-        const double w = u64_to_f64(wraw);
+        const double w = word_to_f64<WK>(wraw);
 #pragma unroll
         for (int bi = 0; bi < kBatchGroup; ++bi) {
             double t0 = mulmod_lazy(u64_to_f64(craw[bi]), pm, m), t1 = 0.0;
 #pragma unroll
             for (int j = 0; j < NDIG; ++j) {
                 const double x = u64_to_f64(xraw[bi][j]);
-                t0 += mulmod_lazy(x, u64_to_f64(kraw[j][0]), m);
-                t1 += mulmod_lazy(x, u64_to_f64(kraw[j][1]), m);
+                t0 += mulmod_lazy(x, word_to_f64<WK>(kraw[j][0]), m);
+                t1 += mulmod_lazy(x, word_to_f64<WK>(kraw[j][1]), m);
             }
             // |t| <= (digits + 1) * 0.51 p, far inside the range of a lazy product; the sums grow by 0.51 p a rotation
             u0[bi] += mulmod_lazy(t0, w, m);
@@ -199,7 +207,7 @@ __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__
 }
 
 void launch_rotate_mac(const ks_ctx* c, const Level& lv, const uint64_t* ct, uint64_t ct_bs, const uint64_t* lifted,
-                       const MacRotations& rot, uint64_t* u, uint32_t batch, bool accumulate, hipStream_t s) {
+                       const MacRotations& rot, uint64_t* u, uint32_t batch, bool accumulate, hipStream_t s, bool key_words32) {
     if (batch == 0 || rot.n == 0) return;
     DigitRanges dg;
     dg.ndig = lv.ndig;
@@ -212,12 +220,17 @@ void launch_rotate_mac(const ks_ctx* c, const Level& lv, const uint64_t* ct, uin
     // Algorithmic traffic: the raised digits and c0 of a ciphertext once (the rotations of a launch re-read them through
     // the gather; those re-reads are meant to come from cache), key and plaintext of every rotation once per group, both
     // sums written once.  Algorithmic work per slot, ciphertext and rotation: 2 NDIG + 3 modular products.
-    const double reads = (double)batch * (lv.ndig * lv.E + lv.ell) + (double)rot.n * groups * (2.0 * lv.ndig + 1.0) * lv.E;
+    const double reads = (double)batch * (lv.ndig * lv.E + lv.ell) +
+                         (key_words32 ? 0.5 : 1.0) * (double)rot.n * groups * (2.0 * lv.ndig + 1.0) * lv.E;
     ProfScope ps("rotate_mac", (reads + (double)batch * 2 * lv.E * (accumulate ? 2 : 1)) * c->N * 8.0, s,
                  (double)rot.n * batch * lv.E * c->N * (7.0 * (2 * lv.ndig + 3)));
-#define KS_LAUNCH_MAC(ND)                                                                                                          \
-    hipLaunchKernelGGL(rotate_mac_kernel<ND>, grid, block, 0, s, c->d_mod, c->d_Pmod, dg, lv.ell, lv.E, c->L, c->M, c->logN, ct, ct_bs, \
-                       lifted, rot, c->d_one, u, batch, accumulate ? 1 : 0)
+#define KS_LAUNCH_MAC(ND)                                                                                                                  \
+    if (key_words32)                                                                                                                       \
+        hipLaunchKernelGGL((rotate_mac_kernel<ND, uint32_t>), grid, block, 0, s, c->d_mod, c->d_Pmod, dg, lv.ell, lv.E, c->L, c->M, c->logN, ct, \
+                           ct_bs, lifted, rot, c->d_one, u, batch, accumulate ? 1 : 0);                                                   \
+    else                                                                                                                                   \
+        hipLaunchKernelGGL((rotate_mac_kernel<ND, uint64_t>), grid, block, 0, s, c->d_mod, c->d_Pmod, dg, lv.ell, lv.E, c->L, c->M, c->logN, ct, \
+                           ct_bs, lifted, rot, c->d_one, u, batch, accumulate ? 1 : 0)
     switch (lv.ndig) {
         case 1: KS_LAUNCH_MAC(1); break;
         case 2: KS_LAUNCH_MAC(2); break;
@@ -232,26 +245,43 @@ void launch_rotate_mac(const ks_ctx* c, const Level& lv, const uint64_t* ct, uin
 }
 
 // (b1, a1) x (b2, a2) -> d0 = b1 b2, d1 = a1 b2 + a2 b1, d2 = a1 a2
+template <typename W>
 __global__ __launch_bounds__(256) void tensor_product_kernel(const Mod* __restrict__ mods, uint32_t ell, uint32_t N,
-                                                             const uint64_t* __restrict__ cta, const uint64_t* __restrict__ ctb,
+                                                             const W* __restrict__ cta, const W* __restrict__ ctb,
                                                              uint64_t* __restrict__ td) {
     const uint32_t i = blockIdx.y, b = blockIdx.z;
     const Mod m = mods[i];
     const uint64_t n = blockIdx.x * 256 + threadIdx.x;
     const uint64_t ct_off = ((uint64_t)b * 2 * ell + i) * N + n, comp = (uint64_t)ell * N;
-    const double b1 = u64_to_f64(cta[ct_off]), a1 = u64_to_f64(cta[ct_off + comp]);
-    const double b2 = u64_to_f64(ctb[ct_off]), a2 = u64_to_f64(ctb[ct_off + comp]);
+    const double b1 = word_to_f64<W>(cta[ct_off]), a1 = word_to_f64<W>(cta[ct_off + comp]);
+    const double b2 = word_to_f64<W>(ctb[ct_off]), a2 = word_to_f64<W>(ctb[ct_off + comp]);
     const uint64_t o = ((uint64_t)b * 3 * ell + i) * N + n;
     td[o] = f64_to_u64(canon(mulmod_lazy(b1, b2, m), m));
     td[o + comp] = f64_to_u64(canon(reduce_lazy(mulmod_lazy(a1, b2, m) + mulmod_lazy(a2, b1, m), m), m));
     td[o + 2 * comp] = f64_to_u64(canon(mulmod_lazy(a1, a2, m), m));
 }
 
-void launch_tensor_product(const ks_ctx* c, const uint64_t* cta, const uint64_t* ctb, uint64_t* td, uint32_t ell,
-                           uint32_t batch, hipStream_t s) {
+void launch_tensor_product(const ks_ctx* c, const void* cta, const void* ctb, uint64_t* td, uint32_t ell, uint32_t batch,
+                           hipStream_t s, bool in_words32) {
     if (batch == 0) return;
-    ProfScope ps("tensor_product", (double)batch * ell * 7 * c->N * 8.0, s);
-    hipLaunchKernelGGL(tensor_product_kernel, dim3(c->N / 256, ell, batch), dim3(256), 0, s, c->d_mod, ell, c->N, cta, ctb, td);
+    ProfScope ps("tensor_product", (double)batch * ell * (in_words32 ? 5 : 7) * c->N * 8.0, s);
+    if (in_words32)
+        hipLaunchKernelGGL(tensor_product_kernel<uint32_t>, dim3(c->N / 256, ell, batch), dim3(256), 0, s, c->d_mod, ell, c->N,
+                           static_cast<const uint32_t*>(cta), static_cast<const uint32_t*>(ctb), td);
+    else
+        hipLaunchKernelGGL(tensor_product_kernel<uint64_t>, dim3(c->N / 256, ell, batch), dim3(256), 0, s, c->d_mod, ell, c->N,
+                           static_cast<const uint64_t*>(cta), static_cast<const uint64_t*>(ctb), td);
+}
+
+__global__ __launch_bounds__(256) void widen_u32_kernel(const uint32_t* __restrict__ in, uint64_t* __restrict__ out, uint64_t n) {
+    const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) out[i] = in[i];
+}
+
+void launch_widen_u32(const uint32_t* in, uint64_t* out, uint64_t n, hipStream_t s) {
+    if (n == 0) return;
+    ProfScope ps("widen_u32", (double)n * 12.0, s);
+    hipLaunchKernelGGL(widen_u32_kernel, dim3((uint32_t)((n + 255) / 256)), dim3(256), 0, s, in, out, n);
 }
 
 // acc[b][comp][limb] = (acc + mul * addend[b][comp][limb]) mod q_limb, canonical: the one ciphertext limb that joins the

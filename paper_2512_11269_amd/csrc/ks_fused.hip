@@ -16,32 +16,35 @@
 
 namespace ks {
 
-// One source of a conversion: acc[t][k] += y[k] * f[t] as exact integers -- each source point is split once (split3),
-// every target adds three products against its shifted, centred factors.
+// One source of a conversion: acc[t][k] += y[k] * f[t] as exact integers -- each source point is split once (split3, or
+// split2 when every modulus is below 2^28), every target adds PIECES products against its shifted, centred factors.
 // REFILL: once y[k] has been consumed, the same registers receive point k of the next source (byte offset next_off in
 // the buffer), which then has a whole source's worth of arithmetic to arrive.
 // The factors of the next source (fnext: uniform, scalar loads) are requested after the first point, together with
 // the limb index of the source after next: scalar loads complete out of order, so the first use of f waits for every
 // scalar load in flight, and at that moment only f's own, requested a source ago, should be.
-template <int LOG_R, int TS, bool REFILL>
+template <int LOG_R, int TS, bool REFILL, int PIECES>
 __device__ __forceinline__ void bconv_accumulate(double (&acc)[TS][16], double (&y)[16], const double (&f)[TS][3],
                                                  double (&fnext)[TS][3], const double* const (&hat_row)[TS], int inext,
                                                  uint32_t& limb_after, const uint32_t* src_limb, int iafter, BufferRsrc rsrc,
                                                  uint32_t lane_off, uint32_t next_off) {
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
-        double y2, y1, y0;
-        split3(y[k], y2, y1, y0);
+        double y2 = 0.0, y1, y0;
+        if constexpr (PIECES == 3) split3(y[k], y2, y1, y0);
+        else split2(y[k], y1, y0);
         if (REFILL) y[k] = load_strided_point<LOG_R>(rsrc, lane_off, next_off, k);
 #pragma unroll
-        for (int tt = 0; tt < TS; ++tt)
-            acc[tt][k] = __builtin_fma(y2, f[tt][2], __builtin_fma(y1, f[tt][1], __builtin_fma(y0, f[tt][0], acc[tt][k])));
+        for (int tt = 0; tt < TS; ++tt) {
+            acc[tt][k] = __builtin_fma(y1, f[tt][1], __builtin_fma(y0, f[tt][0], acc[tt][k]));
+            if constexpr (PIECES == 3) acc[tt][k] = __builtin_fma(y2, f[tt][2], acc[tt][k]);
+        }
         if (k == 0) {
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int tt = 0; tt < TS; ++tt)
 #pragma unroll
-                for (int p = 0; p < 3; ++p) fnext[tt][p] = hat_row[tt][inext * 4 + p];
+                for (int p = 0; p < PIECES; ++p) fnext[tt][p] = hat_row[tt][inext * 4 + p];
             limb_after = src_limb[iafter];
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -51,7 +54,7 @@ __device__ __forceinline__ void bconv_accumulate(double (&acc)[TS][16], double (
     if (REFILL) {
 #pragma unroll
         for (int k = 1; k < 16; ++k) {
-            __builtin_amdgcn_sched_group_barrier(0x002, 6 + 3 * TS, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, PIECES == 3 ? 6 + 3 * TS : 3 + 2 * TS, 0);
             __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
     }
@@ -64,7 +67,9 @@ __device__ __forceinline__ void bconv_accumulate(double (&acc)[TS][16], double (
 // column stages of the forward transform modulo t and stores raw doubles.  The sources are re-read by the workgroups of
 // the other target subsets; those reads are served by L2 / the last-level cache.
 // ------------------------------------------------------------------------------------------------
-template <int LOG_R, int TS, bool TWO_SETS>
+// PIECES: 3 in general (moduli below 2^36); 2 when every modulus of the context is below 2^28 (the plan's factors are
+// then cut at 14 bits: two products per source and target instead of three).
+template <int LOG_R, int TS, bool TWO_SETS, int PIECES>
 __global__ __launch_bounds__(256) void bconv_ntt_cols(const double* __restrict__ tw, const BConvPlan* __restrict__ plans,
                                                       const uint64_t* __restrict__ y, uint64_t y_ps, uint64_t* __restrict__ out,
                                                       uint64_t out_ps, uint32_t n_subsets) {
@@ -118,16 +123,16 @@ __global__ __launch_bounds__(256) void bconv_ntt_cols(const double* __restrict__
 #pragma unroll
     for (int tt = 0; tt < TS; ++tt)
 #pragma unroll
-        for (int p = 0; p < 3; ++p) ha[tt][p] = hat_row[tt][p];
+        for (int p = 0; p < PIECES; ++p) ha[tt][p] = hat_row[tt][p];
     uint32_t limb_next = P.src_limb[1];
 
     if constexpr (!TWO_SETS) {
 #pragma unroll 1
         for (int i = 0; i < n_src; i += 2) {
             uint32_t limb_after;
-            bconv_accumulate<LOG_R, TS, true>(acc, yv, ha, hb, hat_row, min(i + 1, kMaxSrc - 1), limb_after, P.src_limb,
+            bconv_accumulate<LOG_R, TS, true, PIECES>(acc, yv, ha, hb, hat_row, min(i + 1, kMaxSrc - 1), limb_after, P.src_limb,
                                               min(i + 2, kMaxSrc - 1), ysrd, lane_off, limb_next * (N * 8));
-            bconv_accumulate<LOG_R, TS, true>(acc, yv, hb, ha, hat_row, min(i + 2, kMaxSrc - 1), limb_next, P.src_limb,
+            bconv_accumulate<LOG_R, TS, true, PIECES>(acc, yv, hb, ha, hat_row, min(i + 2, kMaxSrc - 1), limb_next, P.src_limb,
                                               min(i + 3, kMaxSrc - 1), ysrd, lane_off, limb_after * (N * 8));
         }
     } else {
@@ -140,7 +145,7 @@ __global__ __launch_bounds__(256) void bconv_ntt_cols(const double* __restrict__
                 yw[k] = load_strided_point<LOG_R>(ysrd, lane_off, limb_next * (N * 8), k);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            bconv_accumulate<LOG_R, TS, false>(acc, yv, ha, hb, hat_row, min(i + 1, kMaxSrc - 1), limb_after, P.src_limb,
+            bconv_accumulate<LOG_R, TS, false, PIECES>(acc, yv, ha, hb, hat_row, min(i + 1, kMaxSrc - 1), limb_after, P.src_limb,
                                                min(i + 2, kMaxSrc - 1), ysrd, lane_off, 0);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -148,7 +153,7 @@ __global__ __launch_bounds__(256) void bconv_ntt_cols(const double* __restrict__
                 yv[k] = load_strided_point<LOG_R>(ysrd, lane_off, limb_after * (N * 8), k);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            bconv_accumulate<LOG_R, TS, false>(acc, yw, hb, ha, hat_row, min(i + 2, kMaxSrc - 1), limb_next, P.src_limb,
+            bconv_accumulate<LOG_R, TS, false, PIECES>(acc, yw, hb, ha, hat_row, min(i + 2, kMaxSrc - 1), limb_next, P.src_limb,
                                                min(i + 3, kMaxSrc - 1), ysrd, lane_off, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -209,17 +214,22 @@ void launch_bconv_ntt_cols(const ks_ctx* c, const PlanSet& plans, uint32_t limbs
     const uint32_t n_subsets = (max_targets + ts - 1) / ts;
     const dim3 grid(tiles, n_plans * n_subsets, n_polys), block(256);
     ProfScope ps("bconv_ntt_cols", (double)limbs_moved_per_poly * n_polys * c->N * 8.0, s, ops_per_coeff * n_polys * c->N);
-#define KS_LAUNCH_BCONV(LOGR, TSV) \
-    hipLaunchKernelGGL((bconv_ntt_cols<LOGR, TSV, (TSV == 4)>), grid, block, 0, s, c->d_tw_fwd, d_plans, y, y_ps, out, out_ps, n_subsets)
+#define KS_LAUNCH_BCONV(LOGR, TSV)                                                                                                      \
+    if (c->pieces == 2)                                                                                                                 \
+        hipLaunchKernelGGL((bconv_ntt_cols<LOGR, TSV, (TSV == 4), 2>), grid, block, 0, s, c->d_tw_fwd, d_plans, y, y_ps, out, out_ps,  \
+                           n_subsets);                                                                                                  \
+    else                                                                                                                                \
+        hipLaunchKernelGGL((bconv_ntt_cols<LOGR, TSV, (TSV == 4), 3>), grid, block, 0, s, c->d_tw_fwd, d_plans, y, y_ps, out, out_ps,  \
+                           n_subsets)
     if (c->logN == 16) {
-        if (ts == 4) KS_LAUNCH_BCONV(8, 4);
-        else if (ts == 3) KS_LAUNCH_BCONV(8, 3);
-        else if (ts == 2) KS_LAUNCH_BCONV(8, 2);
-        else KS_LAUNCH_BCONV(8, 1);
+        if (ts == 4) { KS_LAUNCH_BCONV(8, 4); }
+        else if (ts == 3) { KS_LAUNCH_BCONV(8, 3); }
+        else if (ts == 2) { KS_LAUNCH_BCONV(8, 2); }
+        else { KS_LAUNCH_BCONV(8, 1); }
     } else {
-#define KS_LAUNCH(LOGR)      \
-    if (ts == 4) KS_LAUNCH_BCONV(LOGR, 4); \
-    else KS_LAUNCH_BCONV(LOGR, 3)
+#define KS_LAUNCH(LOGR)                        \
+    if (ts == 4) { KS_LAUNCH_BCONV(LOGR, 4); } \
+    else { KS_LAUNCH_BCONV(LOGR, 3); }
         KS_FOR_LOG_R(c->logN, KS_LAUNCH)
 #undef KS_LAUNCH
     }
@@ -232,13 +242,13 @@ void launch_bconv_ntt_cols(const ks_ctx* c, const PlanSet& plans, uint32_t limbs
 // One wavefront = four rows of one limb position; it walks the digits, so d~ is read once and feeds both key
 // components (load reuse), and the accumulators are reduced and written once.
 // ------------------------------------------------------------------------------------------------
-// W: word type of the boundary tensors d and evk (64-bit, or 32-bit for moduli below 2^32).
-template <int LOG_R, typename W>
+// WD / WK: word types of d and of the key (64-bit, or 32-bit for moduli below 2^32).
+template <int LOG_R, typename WD, typename WK>
 __global__ __launch_bounds__(64) void rows_inner_product(TwTables tw, TwTables twi,
                                                          const Mod* __restrict__ mods, DigitRanges dg,
                                                          uint32_t ell, uint32_t E, uint32_t L, uint32_t M,
-                                                         const W* __restrict__ d, uint64_t d_ps,
-                                                         const uint64_t* __restrict__ lifted, const W* __restrict__ evk,
+                                                         const WD* __restrict__ d, uint64_t d_ps,
+                                                         const uint64_t* __restrict__ lifted, const WK* __restrict__ evk,
                                                          uint64_t* __restrict__ acc, uint32_t batch) {
     constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R;
     __shared__ double lds[4 * kRowPitch];
@@ -250,12 +260,12 @@ __global__ __launch_bounds__(64) void rows_inner_product(TwTables tw, TwTables t
     const uint32_t slot = blockIdx.x >> 3, b = slot % batch, tile = (slot / batch) * 8 + (blockIdx.x & 7);
     if (tile >= (R / 4) * E) return;  // uniform: padding workgroups when the tile count is not a multiple of 8
     const uint32_t rg = tile % (R / 4), pos = tile / (R / 4);
-    task_rows_inner_product<LOG_R, W>(tw, twi, mods, dg, ell, E, L, M, d + (uint64_t)b * d_ps, lifted + (uint64_t)b * dg.ndig * E * N, evk,
+    task_rows_inner_product<LOG_R, WD, WK>(tw, twi, mods, dg, ell, E, L, M, d + (uint64_t)b * d_ps, lifted + (uint64_t)b * dg.ndig * E * N, evk,
                                       acc + (uint64_t)b * 2 * E * N, pos, rg, threadIdx.x, lds, lds_ta);
 }
 
 void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const void* d, uint64_t d_ps, const uint64_t* lifted,
-                               const void* evk, uint64_t* acc, uint32_t batch, hipStream_t s, bool words32) {
+                               const void* evk, uint64_t* acc, uint32_t batch, hipStream_t s, bool d_words32, bool key_words32) {
     if (batch == 0) return;
     DigitRanges dg;
     dg.ndig = lv.ndig;
@@ -265,20 +275,21 @@ void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const void* d, 
     }
     // reads: every raised digit limb per ciphertext and the key (once per call); writes: both accumulators
     // d (ell limbs per ciphertext) and the key arrive in boundary words, the raised limbs and the sums in 8 bytes
-    const double wb = words32 ? 0.5 : 1.0;
+    const double wd = d_words32 ? 0.5 : 1.0, wk = key_words32 ? 0.5 : 1.0;
     ProfScope ps("rows_inner_product",
-                 ((double)batch * ((lv.ndig * lv.E - lv.ell) + wb * lv.ell + 2.0 * lv.E) + wb * 2.0 * lv.ndig * lv.E) * c->N * 8.0, s);
+                 ((double)batch * ((lv.ndig * lv.E - lv.ell) + wd * lv.ell + 2.0 * lv.E) + wk * 2.0 * lv.ndig * lv.E) * c->N * 8.0, s);
     const uint32_t tiles = (c->N / 1024) * lv.E;
     const dim3 grid(((tiles + 7) / 8) * 8 * batch), block(64);
-#define KS_LAUNCH(LOGR)                                                                                                            \
-    if (words32)                                                                                                                   \
-        hipLaunchKernelGGL((rows_inner_product<LOGR, uint32_t>), grid, block, 0, s, c->tw_fwd, c->tw_inv, c->d_mod, dg, lv.ell, lv.E, c->L, \
-                           c->M, static_cast<const uint32_t*>(d), d_ps, lifted, static_cast<const uint32_t*>(evk), acc, batch);    \
-    else                                                                                                                           \
-        hipLaunchKernelGGL((rows_inner_product<LOGR, uint64_t>), grid, block, 0, s, c->tw_fwd, c->tw_inv, c->d_mod, dg, lv.ell, lv.E, c->L, \
-                           c->M, static_cast<const uint64_t*>(d), d_ps, lifted, static_cast<const uint64_t*>(evk), acc, batch)
+#define KS_LAUNCH_IP(LOGR, WDT, WKT)                                                                                               \
+    hipLaunchKernelGGL((rows_inner_product<LOGR, WDT, WKT>), grid, block, 0, s, c->tw_fwd, c->tw_inv, c->d_mod, dg, lv.ell, lv.E, c->L, \
+                       c->M, static_cast<const WDT*>(d), d_ps, lifted, static_cast<const WKT*>(evk), acc, batch)
+#define KS_LAUNCH(LOGR)                                                          \
+    if (d_words32 && key_words32) KS_LAUNCH_IP(LOGR, uint32_t, uint32_t);        \
+    else if (key_words32) KS_LAUNCH_IP(LOGR, uint64_t, uint32_t);                \
+    else KS_LAUNCH_IP(LOGR, uint64_t, uint64_t)
     KS_FOR_LOG_R(c->logN, KS_LAUNCH)
 #undef KS_LAUNCH
+#undef KS_LAUNCH_IP
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -316,24 +327,12 @@ void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t
                                 uint64_t out_bs, const uint64_t* addend, uint64_t addend_bs, uint32_t addend_comps,
                                 uint32_t galois, uint32_t batch, hipStream_t s, const FinishScale* fs, bool out_words32) {
     if (batch == 0) return;
-    uint64_t* out = static_cast<uint64_t*>(out_words);
-    if (out_words32) {  // plain key-switch result in 32-bit words: no addend, no rescaling
-        if (addend || fs) return;
-        ProfScope ps("rows_moddown_finish", (double)batch * lv.ell * 5 * c->N * 8.0, s);
-        const dim3 grid(c->N / 1024, lv.ell, batch * 2), block(64);
-#define KS_LAUNCH(LOGR)                                                                                                          \
-    hipLaunchKernelGGL((rows_moddown_finish<LOGR, false, 0, uint32_t>), grid, block, 0, s, c->tw_fwd, c->d_mod, c->d_Pinv, nullptr,      \
-                       lv.ell, lv.E, lv.ell, acc, conv, static_cast<uint32_t*>(out_words), out_bs, nullptr, 0, 0, 2, 1)
-        KS_FOR_LOG_R(c->logN, KS_LAUNCH)
-#undef KS_LAUNCH
-        return;
-    }
     const double* mul = fs ? fs->mul : c->d_Pinv;
     const double* admul = fs ? fs->addend_mul : nullptr;
     const uint32_t out_limbs = fs ? fs->out_limbs : lv.ell;
     if (out_limbs == 0) return;
     if (!addend) addend_comps = 0;
-    ProfScope ps("rows_moddown_finish", (double)batch * out_limbs * (6 + addend_comps) * c->N * 8.0, s);
+    ProfScope ps("rows_moddown_finish", (double)batch * out_limbs * (4 + (out_words32 ? 1 : 2) + addend_comps) * c->N * 8.0, s);
     const dim3 block(64);
     const uint32_t row_groups = c->N / 1024;
     // one launch for the components that take the addend, one for those that do not
@@ -342,16 +341,20 @@ void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t
         if (n_comps == 0) continue;
         const int mode = pass == 1 ? 0 : (admul ? 2 : 1);
         const dim3 grid(row_groups, out_limbs, batch * n_comps);
-#define KS_LAUNCH_FINISH(LOGR, GATHER, MODE)                                                                                   \
-    hipLaunchKernelGGL((rows_moddown_finish<LOGR, GATHER, MODE>), grid, block, 0, s, c->tw_fwd, c->d_mod, mul, admul, lv.ell, lv.E, \
-                       out_limbs, acc, conv, out, out_bs, addend, addend_bs, comp0, n_comps, galois)
-#define KS_LAUNCH(LOGR)                                        \
-    if (mode == 0) KS_LAUNCH_FINISH(LOGR, false, 0);           \
-    else if (mode == 2) KS_LAUNCH_FINISH(LOGR, false, 2);      \
-    else if (galois == 1) KS_LAUNCH_FINISH(LOGR, false, 1);    \
-    else KS_LAUNCH_FINISH(LOGR, true, 1)
+#define KS_LAUNCH_FINISH(LOGR, GATHER, MODE, WT)                                                                                   \
+    hipLaunchKernelGGL((rows_moddown_finish<LOGR, GATHER, MODE, WT>), grid, block, 0, s, c->tw_fwd, c->d_mod, mul, admul, lv.ell, lv.E, \
+                       out_limbs, acc, conv, static_cast<WT*>(out_words), out_bs, addend, addend_bs, comp0, n_comps, galois)
+#define KS_LAUNCH_MODES(LOGR, WT)                                  \
+    if (mode == 0) KS_LAUNCH_FINISH(LOGR, false, 0, WT);           \
+    else if (mode == 2) KS_LAUNCH_FINISH(LOGR, false, 2, WT);      \
+    else if (galois == 1) KS_LAUNCH_FINISH(LOGR, false, 1, WT);    \
+    else KS_LAUNCH_FINISH(LOGR, true, 1, WT)
+#define KS_LAUNCH(LOGR)                                     \
+    if (out_words32) { KS_LAUNCH_MODES(LOGR, uint32_t); }   \
+    else { KS_LAUNCH_MODES(LOGR, uint64_t); }
         KS_FOR_LOG_R(c->logN, KS_LAUNCH)
 #undef KS_LAUNCH
+#undef KS_LAUNCH_MODES
 #undef KS_LAUNCH_FINISH
     }
 }
@@ -386,11 +389,11 @@ __global__ __launch_bounds__(256) void rescale_cols(const double* __restrict__ t
 
 // Rescale, second half: row half of the forward transform, then out = (x - w) * q_{ell-1}^-1 mod q_i.
 // x: [polys][ell][N] canonical; spread: [polys][ell-1][N] raw doubles; out: [polys][ell-1][N] canonical.
-template <int LOG_R>
+template <int LOG_R, typename W>
 __global__ __launch_bounds__(64) void rows_rescale_finish(TwTables tw, const Mod* __restrict__ mods,
                                                           const double* __restrict__ qlinv, uint32_t ell,
                                                           const uint64_t* __restrict__ x, const uint64_t* __restrict__ spread,
-                                                          uint64_t* __restrict__ out) {
+                                                          W* __restrict__ out) {
     constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R;
     __shared__ double lds[4 * kRowPitch];
     const uint32_t tid = threadIdx.x, rg = blockIdx.x, i = blockIdx.y, p = blockIdx.z;
@@ -400,7 +403,7 @@ __global__ __launch_bounds__(64) void rows_rescale_finish(TwTables tw, const Mod
     const uint32_t off = row * 256 + j0;
     const uint64_t* src = spread + ((uint64_t)p * (ell - 1) + i) * N + off;
     const uint64_t* xp = x + ((uint64_t)p * ell + i) * N + off;
-    uint64_t* op = out + ((uint64_t)p * (ell - 1) + i) * N + off;
+    W* op = out + ((uint64_t)p * (ell - 1) + i) * N + off;
     double w[16], a[16];
     PassTwiddles t;
 #pragma unroll
@@ -410,11 +413,11 @@ __global__ __launch_bounds__(64) void rows_rescale_finish(TwTables tw, const Mod
     load_row_twiddles(t, tw, i, N, R + row, j0, m);
     row_fwd_core(w, t, j0, lds + rr * kRowPitch, m);
 #pragma unroll
-    for (int k = 0; k < 16; ++k) op[16 * k] = f64_to_u64(canon(mulmod_lazy(a[k] - w[k], scale, m), m));
+    for (int k = 0; k < 16; ++k) op[16 * k] = f64_to_word<W>(canon(mulmod_lazy(a[k] - w[k], scale, m), m));
 }
 
 void launch_rescale_fused(const ks_ctx* c, const Level& lv, const uint64_t* x, const uint64_t* last, uint64_t* spread,
-                          uint64_t* out, uint32_t n_polys, hipStream_t s) {
+                          void* out, uint32_t n_polys, hipStream_t s, bool out_words32) {
     if (n_polys == 0 || lv.ell < 2) return;
     const uint32_t nl = lv.ell - 1;
     {
@@ -425,10 +428,14 @@ void launch_rescale_fused(const ks_ctx* c, const Level& lv, const uint64_t* x, c
 #undef KS_LAUNCH
     }
     {
-        ProfScope ps("rows_rescale_finish", (double)n_polys * nl * 3 * c->N * 8.0, s);
-#define KS_LAUNCH(LOGR)                                                                                                       \
-    hipLaunchKernelGGL(rows_rescale_finish<LOGR>, dim3(1u << (LOGR - 2), nl, n_polys), dim3(64), 0, s, c->tw_fwd, c->d_mod, lv.d_qlinv, \
-                       lv.ell, x, spread, out)
+        ProfScope ps("rows_rescale_finish", (double)n_polys * nl * (out_words32 ? 2.5 : 3.0) * c->N * 8.0, s);
+#define KS_LAUNCH(LOGR)                                                                                                                      \
+    if (out_words32)                                                                                                                         \
+        hipLaunchKernelGGL((rows_rescale_finish<LOGR, uint32_t>), dim3(1u << (LOGR - 2), nl, n_polys), dim3(64), 0, s, c->tw_fwd, c->d_mod,   \
+                           lv.d_qlinv, lv.ell, x, spread, static_cast<uint32_t*>(out));                                                      \
+    else                                                                                                                                     \
+        hipLaunchKernelGGL((rows_rescale_finish<LOGR, uint64_t>), dim3(1u << (LOGR - 2), nl, n_polys), dim3(64), 0, s, c->tw_fwd, c->d_mod,   \
+                           lv.d_qlinv, lv.ell, x, spread, static_cast<uint64_t*>(out))
         KS_FOR_LOG_R(c->logN, KS_LAUNCH)
 #undef KS_LAUNCH
     }

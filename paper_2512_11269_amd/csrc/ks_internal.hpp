@@ -120,6 +120,7 @@ struct ks_ctx {
     ks::TwTables tw_fwd{}, tw_inv{};      // the three tables of each direction bundled for the row kernels
     std::vector<ks::Level> levels;        // index ell-1
     int opt[KS_OPT_COUNT_] = {};          // ks_ctx_set_option values, index = option id
+    int pieces = 3;                       // pieces a source residue is cut into by the fused conversion: 2 iff every modulus < 2^28
     mutable std::mutex mu;
     mutable std::map<std::vector<uint32_t>, ks::PlanSet> bconv_cache;  // key: n_src, src ids, dst ids
 };
@@ -171,6 +172,9 @@ struct XformIO {
 void launch_ntt_fwd(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipStream_t s);
 // inverse: evaluation (canonical u64) -> coefficient (canonical u64)
 void launch_ntt_inv(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipStream_t s);
+// both directions on limbs in 32-bit words, in place (canonical residues between the two passes as well)
+void launch_ntt_u32(const ks_ctx* c, const LimbMap& map, uint32_t* data, uint64_t ps_words, uint32_t n_polys, bool inverse,
+                    hipStream_t s);
 // The two halves of each transform on their own (the fused pipeline replaces some halves by fused kernels).
 void launch_ntt_fwd_cols(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipStream_t s);
 void launch_ntt_fwd_rows(const ks_ctx* c, const LimbMap& map, uint64_t* data, uint64_t ps_words, uint32_t n_polys, hipStream_t s);
@@ -191,8 +195,10 @@ void launch_bconv_mfma_ntt_cols(const ks_ctx* c, const PlanSet& plans, const uin
 // Upload host plans as a PlanSet (allocates; ks_ctx_create and bconv plan registration only).  Returns a HIP error code.
 hipError_t upload_plans(const BConvPlan* host_plans, uint32_t n_plans, uint32_t shape_src, PlanSet* out);
 // Fused row half of the forward transform of the raised digits + inner product with the key.
+// d_words32 / key_words32: d / the key hold one residue per 32-bit word (d_words32 implies key_words32)
 void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const void* d, uint64_t d_ps, const uint64_t* lifted,
-                               const void* evk, uint64_t* acc, uint32_t batch, hipStream_t s, bool words32 = false);
+                               const void* evk, uint64_t* acc, uint32_t batch, hipStream_t s, bool d_words32 = false,
+                               bool key_words32 = false);
 // Fused row half of the forward transform of the converted limbs + (acc - conv) P^-1 (+ addend).
 // fs == nullptr: multiply by P^-1, addend unscaled, ell output limbs.  Otherwise (merged ModDown + rescale): multiply by
 // fs->mul[i], scale the addend by fs->addend_mul[i], and write only the first fs->out_limbs limbs per component.
@@ -212,10 +218,11 @@ void launch_add_scaled_limb(const ks_ctx* c, uint64_t* acc, uint64_t acc_ps, con
 // Fused rescale: last = coefficient-domain dropped limb as canonical doubles [polys][N]; spread = scratch
 // [polys][ell-1][N]; out[p][i] = (x[p][i] - NTT(centred last mod q_i)) * q_{ell-1}^-1.
 void launch_rescale_fused(const ks_ctx* c, const Level& lv, const uint64_t* x, const uint64_t* last, uint64_t* spread,
-                          uint64_t* out, uint32_t n_polys, hipStream_t s);
+                          void* out, uint32_t n_polys, hipStream_t s, bool out_words32 = false);
 
-void launch_bconv(const ks_ctx* c, const PlanSet& plans, uint32_t limbs_moved_per_poly, const uint64_t* in, uint64_t in_poly_stride,
-                  uint64_t* out, uint64_t out_poly_stride, uint32_t n_polys, hipStream_t s);
+// words32: in and out hold one residue per 32-bit word (strides in words either way)
+void launch_bconv(const ks_ctx* c, const PlanSet& plans, uint32_t limbs_moved_per_poly, const void* in, uint64_t in_poly_stride,
+                  void* out, uint64_t out_poly_stride, uint32_t n_polys, hipStream_t s, bool words32 = false);
 // the same conversion on the matrix cores (ks_bconv_mfma.hip)
 void launch_bconv_mfma(const ks_ctx* c, const PlanSet& plans, uint32_t limbs_moved_per_poly, const uint64_t* in, uint64_t in_poly_stride,
                        uint64_t* out, uint64_t out_poly_stride, uint32_t n_polys, hipStream_t s);
@@ -225,19 +232,20 @@ constexpr int kMacRotations = 16;
 struct MacRotations {
     uint32_t n;
     uint32_t galois[kMacRotations];
-    const uint64_t* key[kMacRotations];  // [dnum][2][L+K][N]
-    const uint64_t* pt[kMacRotations];   // [L+K][N]
+    const void* key[kMacRotations];  // [dnum][2][L+K][N], 64- or 32-bit words
+    const void* pt[kMacRotations];   // [L+K][N], same word size as the keys
 };
 // acc[r][b][c][pos] = sum_j sigma_{g_r}(src_j)[pos] * key_r[j][c][ext_id(pos)] for every rotation r of `rot` (pt unused);
 // src_j[pos] = d[b][pos] when pos lies in digit j, otherwise lifted[b][j][pos].
+// key_words32: keys (and plaintexts) hold one residue per 32-bit word; d, ct and the raised digits are always 64-bit.
 void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_poly_stride, const uint64_t* lifted,
-                          const MacRotations& rot, uint64_t* acc, uint32_t batch, hipStream_t s);
+                          const MacRotations& rot, uint64_t* acc, uint32_t batch, hipStream_t s, bool key_words32 = false);
 
 // u[b][c][pos] (+)= sum_r pt_r[pos] * (sum_j sigma_r(src_j)[pos] key_r[j][c][pos] + [c = 0][pos < ell] P sigma_r(c0)[pos]);
 // ct: [b][2][ell][N] (c0, c1), lifted: finished raised digits of c1.  accumulate: add to what u already holds.
 // galois[r] == 1: the term is P (c0, c1) and key[r] is not read; pt[r] == nullptr: the constant 1.
 void launch_rotate_mac(const ks_ctx* c, const Level& lv, const uint64_t* ct, uint64_t ct_bs, const uint64_t* lifted,
-                       const MacRotations& rot, uint64_t* u, uint32_t batch, bool accumulate, hipStream_t s);
+                       const MacRotations& rot, uint64_t* u, uint32_t batch, bool accumulate, hipStream_t s, bool key_words32 = false);
 
 // The key-switch chain behind ks_keyswitch / ks_keyswitch_u32 (argument checks included); ws is any device buffer of
 // at least ks_workspace_bytes(KS_OP_KEYSWITCH) bytes, whose contents need no initialisation.
@@ -249,7 +257,10 @@ int keyswitch_impl(const ks_ctx* c, const void* d, uint32_t ell, const void* evk
 hipError_t bind_static_scratch(int device);
 
 // d0 = b1 b2, d1 = a1 b2 + a2 b1, d2 = a1 a2 ; td: [batch][3][ell][N]
-void launch_tensor_product(const ks_ctx* c, const uint64_t* cta, const uint64_t* ctb, uint64_t* td, uint32_t ell,
-                           uint32_t batch, hipStream_t s);
+void launch_tensor_product(const ks_ctx* c, const void* cta, const void* ctb, uint64_t* td, uint32_t ell, uint32_t batch,
+                           hipStream_t s, bool in_words32 = false);
+// out[i] = in[i] for n 32-bit words -> 64-bit words (ciphertexts handed over in 32-bit words are widened once per chunk;
+// the large tensors of those calls -- keys, plaintexts, results -- are read and written in 32 bits by the kernels)
+void launch_widen_u32(const uint32_t* in, uint64_t* out, uint64_t n, hipStream_t s);
 
 }  // namespace ks

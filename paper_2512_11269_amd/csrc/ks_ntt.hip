@@ -98,6 +98,82 @@ __global__ __launch_bounds__((TC << LOG_R) / 16) void ntt_inv_cols(const double*
 }
 
 // ------------------------------------------------------------------------------------------------
+// Transforms of limbs held in 32-bit words (every modulus below 2^32), in place.  Both passes read and write canonical
+// residues, so the half-way values fit the same words and a transform moves half the bytes of the 64-bit one.
+// fwd_cols -> fwd_rows, inv_rows -> inv_cols as above.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t* locate_u32(const LimbMap& map, uint32_t li, uint32_t* data, uint64_t ps, uint32_t N,
+                                                uint32_t* mod_id) {
+    const uint32_t poly = li / map.n, idx = li - poly * map.n;
+    *mod_id = map.mod[idx];
+    return data + poly * ps + (uint64_t)map.off[idx] * N;
+}
+
+template <int LOG_R, int TC>
+__global__ __launch_bounds__((TC << LOG_R) / 16) void ntt_fwd_cols_u32(const double* __restrict__ tw, const Mod* __restrict__ mods,
+                                                                     LimbMap map, uint32_t* data, uint64_t ps) {
+    constexpr uint32_t N = 256u << LOG_R, TILES = 256 / TC;
+    __shared__ double lds[LOG_R > 4 ? (TC << LOG_R) : 1];
+    const uint32_t tid = threadIdx.x, li = blockIdx.x / TILES, tile = blockIdx.x - li * TILES;
+    uint32_t mod_id;
+    uint32_t* p = locate_u32(map, li, data, ps, N, &mod_id);
+    const Mod m = mods[mod_id];
+    const uint32_t c = tid & (TC - 1), r0 = tid / TC, col = tile * TC + c;
+    double v[16];
+    PassTwiddles t;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = (double)p[col_row_strided<LOG_R>(r0, k) * 256 + col];
+    load_col_twiddles<LOG_R>(t, tw + (size_t)mod_id * N, r0);
+    col_fwd_core<LOG_R, TC>(v, t, c, r0, lds, m);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) p[col_row_grouped<LOG_R>(r0, k) * 256 + col] = (uint32_t)canon(reduce_lazy(v[k], m), m);
+}
+
+template <int LOG_R, bool INVERSE>
+__global__ __launch_bounds__(64) void ntt_rows_u32(TwTables tw, const Mod* __restrict__ mods, LimbMap map, uint32_t* data,
+                                                   uint64_t ps) {
+    constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R, GROUPS = R / 4;
+    __shared__ double lds[4 * kRowPitch];
+    const uint32_t tid = threadIdx.x, li = blockIdx.x / GROUPS, rg = blockIdx.x - li * GROUPS;
+    uint32_t mod_id;
+    uint32_t* limb = locate_u32(map, li, data, ps, N, &mod_id);
+    const Mod m = mods[mod_id];
+    const uint32_t j0 = tid & 15, rr = tid >> 4, row = rg * 4 + rr;
+    uint32_t* p = limb + row * 256;
+    double v[16];
+    PassTwiddles t;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = (double)p[j0 + 16 * k];
+    load_row_twiddles(t, tw, mod_id, N, R + row, j0, m);
+    if constexpr (INVERSE) row_inv_core(v, t, j0, lds + rr * kRowPitch, m);
+    else row_fwd_core(v, t, j0, lds + rr * kRowPitch, m);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) p[j0 + 16 * k] = (uint32_t)canon(reduce_lazy(v[k], m), m);
+}
+
+template <int LOG_R, int TC>
+__global__ __launch_bounds__((TC << LOG_R) / 16) void ntt_inv_cols_u32(const double* __restrict__ twi, const Mod* __restrict__ mods,
+                                                                     const double* __restrict__ ninv, LimbMap map, uint32_t* data,
+                                                                     uint64_t ps) {
+    constexpr uint32_t N = 256u << LOG_R, TILES = 256 / TC;
+    __shared__ double lds[LOG_R > 4 ? (TC << LOG_R) : 1];
+    const uint32_t tid = threadIdx.x, li = blockIdx.x / TILES, tile = blockIdx.x - li * TILES;
+    uint32_t mod_id;
+    uint32_t* p = locate_u32(map, li, data, ps, N, &mod_id);
+    const Mod m = mods[mod_id];
+    const double scale = ninv[mod_id];
+    const uint32_t c = tid & (TC - 1), r0 = tid / TC, col = tile * TC + c;
+    double v[16];
+    PassTwiddles t;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = (double)p[col_row_grouped<LOG_R>(r0, k) * 256 + col];
+    load_col_twiddles<LOG_R>(t, twi + (size_t)mod_id * N, r0);
+    col_inv_core<LOG_R, TC>(v, t, c, r0, lds, m);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) p[col_row_strided<LOG_R>(r0, k) * 256 + col] = (uint32_t)canon(mulmod_lazy(v[k], scale, m), m);
+}
+
+// ------------------------------------------------------------------------------------------------
 // Wide tiles (32 columns, 256-byte segments) move more bytes per second but give half as many workgroups;
 // small launches keep the 16-column tiles.
 static bool wide_tiles(uint32_t limbs) { return limbs >= 256; }
@@ -196,6 +272,45 @@ void launch_ntt_inv(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipS
                      static_cast<uint64_t*>(io.out) + (uint64_t)p0 * io.out_poly_stride, io.in_poly_stride, io.out_poly_stride, np};
         launch_ntt_inv_rows(c, map, part, s);
         launch_ntt_inv_cols(c, map, static_cast<uint64_t*>(part.out), io.out_poly_stride, np, c->d_ninv, false, false, s);
+    }
+}
+
+void launch_ntt_u32(const ks_ctx* c, const LimbMap& map, uint32_t* data, uint64_t ps_words, uint32_t n_polys, bool inverse,
+                    hipStream_t s) {
+    // groups sized like the 64-bit transform's: the second pass should find the first pass's output in the last-level cache
+    const uint32_t g = 2 * polys_per_group(c, map);
+    for (uint32_t p0 = 0; p0 < n_polys; p0 += g) {
+        const uint32_t limbs = map.n * std::min(g, n_polys - p0);
+        uint32_t* part = data + (uint64_t)p0 * ps_words;
+        // column tiles: 32 columns at N = 2^16 (128-byte row segments of 32-bit words), 4096 / R otherwise
+#define KS_LAUNCH_TC(LOGR, TCV)                                                                                                     \
+    if (!inverse) {                                                                                                                 \
+        {                                                                                                                           \
+            ProfScope ps("ntt_fwd_cols_u32", 1.0 * limbs * c->N * 8.0, s);                                                          \
+            hipLaunchKernelGGL((ntt_fwd_cols_u32<LOGR, TCV>), dim3(limbs * (256 / TCV)), dim3((TCV << LOGR) / 16), 0, s,            \
+                               c->d_tw_fwd, c->d_mod, map, part, ps_words);                                                        \
+        }                                                                                                                           \
+        ProfScope ps("ntt_fwd_rows_u32", 1.0 * limbs * c->N * 8.0, s);                                                              \
+        hipLaunchKernelGGL((ntt_rows_u32<LOGR, false>), dim3(limbs << (LOGR - 2)), dim3(64), 0, s, c->tw_fwd, c->d_mod, map, part,  \
+                           ps_words);                                                                                              \
+    } else {                                                                                                                        \
+        {                                                                                                                           \
+            ProfScope ps("ntt_inv_rows_u32", 1.0 * limbs * c->N * 8.0, s);                                                          \
+            hipLaunchKernelGGL((ntt_rows_u32<LOGR, true>), dim3(limbs << (LOGR - 2)), dim3(64), 0, s, c->tw_inv, c->d_mod, map,     \
+                               part, ps_words);                                                                                    \
+        }                                                                                                                           \
+        ProfScope ps("ntt_inv_cols_u32", 1.0 * limbs * c->N * 8.0, s);                                                              \
+        hipLaunchKernelGGL((ntt_inv_cols_u32<LOGR, TCV>), dim3(limbs * (256 / TCV)), dim3((TCV << LOGR) / 16), 0, s, c->d_tw_inv,   \
+                           c->d_mod, c->d_ninv, map, part, ps_words);                                                              \
+    }
+        switch (c->logN) {
+            case 12: KS_LAUNCH_TC(4, 256) break;
+            case 13: KS_LAUNCH_TC(5, 128) break;
+            case 14: KS_LAUNCH_TC(6, 64) break;
+            case 15: KS_LAUNCH_TC(7, 32) break;
+            default: KS_LAUNCH_TC(8, 32) break;
+        }
+#undef KS_LAUNCH_TC
     }
 }
 

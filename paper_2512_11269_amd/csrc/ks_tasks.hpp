@@ -236,11 +236,12 @@ __device__ __forceinline__ void task_bconv_mfma_cols(const double* __restrict__ 
 // ---- row half of the forward transform of the raised limbs + inner product with the key (see ks_fused.hip) ----------
 // One wavefront: four rows (group rg) of limb position pos of one batch item.  d_b / lifted_b / acc_b: that batch item's
 // d [ell][N], raised digits [ndig][E][N] and accumulators [2][E][N].  lds_wave: 4 * kRowPitch doubles, lds_ta_wave: 64.
-template <int LOG_R, typename W>
+// WD / WK: word types of d and of the key (64-bit, or 32-bit for moduli below 2^32).
+template <int LOG_R, typename WD, typename WK>
 __device__ __forceinline__ void task_rows_inner_product(const TwTables& tw, const TwTables& twi, const Mod* __restrict__ mods,
                                                         const DigitRanges& dg, uint32_t ell, uint32_t E, uint32_t L, uint32_t M,
-                                                        const W* __restrict__ d_b, const uint64_t* __restrict__ lifted_b,
-                                                        const W* __restrict__ evk, uint64_t* __restrict__ acc_b, uint32_t pos,
+                                                        const WD* __restrict__ d_b, const uint64_t* __restrict__ lifted_b,
+                                                        const WK* __restrict__ evk, uint64_t* __restrict__ acc_b, uint32_t pos,
                                                         uint32_t rg, uint32_t lane, double* lds_wave, double* lds_ta_wave) {
     constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R;
     const uint32_t mid = pos < ell ? pos : L + (pos - ell);
@@ -260,20 +261,20 @@ __device__ __forceinline__ void task_rows_inner_product(const TwTables& tw, cons
 #pragma unroll 1
     for (uint32_t j = 0; j < dg.ndig; ++j) {
         const bool own = pos >= dg.lo[j] && pos < dg.hi[j];  // uniform
-        const W* key0 = evk + ((uint64_t)(j * 2 + 0) * M + mid) * N + off;
-        const W* key1 = evk + ((uint64_t)(j * 2 + 1) * M + mid) * N + off;
+        const WK* key0 = evk + ((uint64_t)(j * 2 + 0) * M + mid) * N + off;
+        const WK* key1 = evk + ((uint64_t)(j * 2 + 1) * M + mid) * N + off;
         // issue every load of this digit up front (the key slots are independent of the transform below)
         double x[16], k0[16], k1[16];
-        if constexpr (sizeof(W) == 8) {
+        if constexpr (sizeof(WD) == 8 && sizeof(WK) == 8) {
             const uint64_t* src = own ? reinterpret_cast<const uint64_t*>(d_b) + (uint64_t)pos * N + off
                                       : lifted_b + ((uint64_t)j * E + pos) * N + off;
             uint64_t raw[16];
 #pragma unroll
             for (int k = 0; k < 16; ++k) raw[k] = src[16 * k];
 #pragma unroll
-            for (int k = 0; k < 16; ++k) k0[k] = word_to_f64<W>(key0[16 * k]);
+            for (int k = 0; k < 16; ++k) k0[k] = word_to_f64<WK>(key0[16 * k]);
 #pragma unroll
-            for (int k = 0; k < 16; ++k) k1[k] = word_to_f64<W>(key1[16 * k]);
+            for (int k = 0; k < 16; ++k) k1[k] = word_to_f64<WK>(key1[16 * k]);
             if (own) {
 #pragma unroll
                 for (int k = 0; k < 16; ++k) x[k] = u64_to_f64(raw[k]);
@@ -285,15 +286,15 @@ __device__ __forceinline__ void task_rows_inner_product(const TwTables& tw, cons
         } else {
             // the digit's own limbs come in boundary words, the raised ones as raw doubles: two load shapes, so the
             // (uniform) choice is a branch; the key slots are requested before it and everything is awaited after it
-            W kr0[16], kr1[16];
+            WK kr0[16], kr1[16];
 #pragma unroll
             for (int k = 0; k < 16; ++k) kr0[k] = key0[16 * k];
 #pragma unroll
             for (int k = 0; k < 16; ++k) kr1[k] = key1[16 * k];
             if (own) {
-                const W* src = d_b + (uint64_t)pos * N + off;
+                const WD* src = d_b + (uint64_t)pos * N + off;
 #pragma unroll
-                for (int k = 0; k < 16; ++k) x[k] = word_to_f64<W>(src[16 * k]);
+                for (int k = 0; k < 16; ++k) x[k] = word_to_f64<WD>(src[16 * k]);
             } else {
                 const uint64_t* src = lifted_b + ((uint64_t)j * E + pos) * N + off;
 #pragma unroll
@@ -301,9 +302,9 @@ __device__ __forceinline__ void task_rows_inner_product(const TwTables& tw, cons
                 row_fwd_core_lds(x, lds_ta_wave + rr * 16, tb, j0, lds_wave + rr * kRowPitch, m);
             }
 #pragma unroll
-            for (int k = 0; k < 16; ++k) k0[k] = word_to_f64<W>(kr0[k]);
+            for (int k = 0; k < 16; ++k) k0[k] = word_to_f64<WK>(kr0[k]);
 #pragma unroll
-            for (int k = 0; k < 16; ++k) k1[k] = word_to_f64<W>(kr1[k]);
+            for (int k = 0; k < 16; ++k) k1[k] = word_to_f64<WK>(kr1[k]);
         }
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
