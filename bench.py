@@ -36,10 +36,10 @@ CHUNK = 8                        # ciphertexts per internal pass of the batched 
 # "measured" column: FETCH_SIZE and WRITE_SIZE scaled by what the same counters read for a 1 GiB device copy, summed, per
 # launch), keyed by workload and kernel.  tests/test_profiles_consistent.py checks these against that file.
 MEASURED_TRAFFIC_BYTES: dict = {
-    ("keyswitch", "rows_inner_product"): 187917623,
-    ("keyswitch", "rows_moddown_finish"): 77525908,
-    ("keyswitch", "bconv_mfma_ntt_cols"): 43279686,  # mean of the ModUp and the ModDown launch
-    ("keyswitch", "ntt_inv_rows"): 27091669,
+    ("keyswitch", "rows_inner_product"): 187897144,
+    ("keyswitch", "rows_moddown_finish"): 77505428,
+    ("keyswitch", "bconv_mfma_ntt_cols"): 53444702,  # mean of the ModUp and the ModDown launch
+    ("keyswitch", "ntt_inv_rows"): 27075285,
     ("keyswitch", "ntt_inv_cols"): 21380728,         # mean of the 24-limb and the 16-limb launch
 }
 
@@ -117,7 +117,7 @@ def bench_keyswitch(args, torch, K, ks_inputs):
 
     # Timing protocol: W warm-up calls, then `repeats` runs of max(K, 200) calls each, HIP events around each run;
     # the headline is the MEDIAN run.  The run of exactly K calls the command line asks for is reported beside it.
-    calls = max(args.steps, 200)
+    calls = max(args.steps, args.min_calls)
     run(args.warmup)
     exact_k = _event_timed(torch, run, args.steps)
     runs = [_event_timed(torch, run, calls) for _ in range(args.repeats)]
@@ -524,6 +524,52 @@ def bench_ntt(args, torch, K, ks_inputs):
                          "traffic": None}}
 
 
+def bench_bconv(args, torch, K, ks_inputs):
+    """The standalone base conversion at the two shapes the key-switch uses most (configuration 2's ModUp digit: 8 -> 24
+    moduli; configuration 5's: 12 -> 35), vector kernel against the int8 matrix-core kernel, one polynomial and 64."""
+    rows = []
+    for cfg_id, n_src, n_dst in ((2, 8, 24), (5, 12, 35)):
+        cfg = ks_inputs.CONFIGS[cfg_id]
+        q, p = ks_inputs.moduli(cfg)
+        logN = cfg["logN"]
+        N = 1 << logN
+        ctx = K.Context(logN, q, p, cfg["dnum"])
+        src, dst = list(range(n_src)), list(range(n_src, n_src + n_dst))
+        K.bconv_prepare(ctx, src, dst)
+        for batch in (1, 64):
+            x = ks_inputs.uniform_residues(cfg["seed"], 1, (batch,), [(q + p)[i] for i in src], N, device="cuda")
+            out = torch.empty((batch, n_dst, N), dtype=torch.int64, device="cuda")
+            row = {"shape": f"{n_src}->{n_dst} moduli, N=2^{logN}, {batch} polynomial(s)", "bytes": (n_src + n_dst) * batch * N * 8}
+            for name, kernel in (("vector", 1), ("int8_mfma", 2)):
+                ctx.set_option(K.KS_OPT_BCONV_KERNEL, kernel)
+                fn = lambda: K.bconv(ctx, x, src, out, dst)
+                fn()
+                # kernel durations from the library's own HIP events (a single-polynomial launch is shorter than the
+                # host-side cost of a call, so back-to-back wall time would measure the host)
+                reps, trials = (100 if batch == 1 else 20), []
+                for _ in range(3):
+                    torch.cuda.synchronize()
+                    K.ks_profile_enable(True)
+                    for _ in range(reps):
+                        fn()
+                    torch.cuda.synchronize()
+                    rec = K.ks_profile_report()
+                    K.ks_profile_enable(False)
+                    trials.append(sum(k["total_ms"] for k in rec) * 1e3 / reps)
+                us = sorted(trials)[1]
+                row[name + "_us"] = round(us, 2)
+                row[name + "_GBs"] = round(row["bytes"] / (us * 1e-6) / 1e9, 1)
+            ctx.set_option(K.KS_OPT_BCONV_KERNEL, 0)
+            rows.append(row)
+    big = rows[1]
+    return {"metric": "bconv_GBps", "value": big["vector_GBs"], "unit": "GB/s", "n_gpus": 1, "steps": 20, "warmup": 1,
+            "ms_per_step": round(big["vector_us"] * 1e-3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "f64 (vector) / int8 (matrix cores)", "data": "synthetic",
+            "config": {"workload": "standalone base conversion, vector kernel vs int8 matrix-core kernel"}, "shapes": rows,
+            "roofline": {"bound": "hbm", "kernel": "bconv_kernel", "achieved": big["vector_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": round(big["vector_GBs"] / HBM_PEAK_GBS, 4), "traffic": None}}
+
+
 def bench_copy(args, torch):
     """A plain device copy of known size: the yardstick the HBM counters of the profiling runs are scaled by."""
     n = 1 << 27  # 1 GiB of int64
@@ -550,11 +596,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--sets", type=int, default=6, help="disjoint buffer sets rotated through (cold-cache figure)")
     ap.add_argument("--no-batched", action="store_true", help="skip the batched key-switch measurement (counter runs)")
-    ap.add_argument("--workload", default="keyswitch", choices=["keyswitch", "keyswitch_u32", "ntt", "rotate", "rotate_mac", "bsgs", "hmult", "hmult_merged", "copy"])
+    ap.add_argument("--workload", default="keyswitch", choices=["keyswitch", "keyswitch_u32", "ntt", "rotate", "rotate_mac", "bsgs", "hmult", "hmult_merged", "bconv", "copy"])
     ap.add_argument("--word-size", type=int, default=64, choices=[64, 32],
                     help="32: the rotate / rotate_mac / hmult / hmult_merged / ntt workloads with 28-bit primes in 32-bit words")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--repeats", type=int, default=5, help="timed runs of the headline workload (the median is reported)")
+    ap.add_argument("--min-calls", type=int, default=200,
+                    help="calls per timed repeat are max(steps, this); counter-collection runs lower it to keep them short")
     ap.add_argument("--no-extras", action="store_true", help="skip configurations 3, 4 and 5 (profiling runs)")
     ap.add_argument("--opt", action="append", help="context tuning option ID=VALUE (ks_ctx_set_option), repeatable")
     args = ap.parse_args()
@@ -572,6 +620,8 @@ def main():
     torch.cuda.set_device(0)
     if args.workload == "copy":
         result = bench_copy(args, torch)
+    elif args.workload == "bconv":
+        result = bench_bconv(args, torch, K, ks_inputs)
     elif args.workload == "ntt":
         result = bench_ntt(args, torch, K, ks_inputs)
     elif args.workload == "keyswitch_u32":

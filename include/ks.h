@@ -71,8 +71,9 @@ int ks_ctx_create(ks_ctx** out, uint32_t logN, uint32_t L, uint32_t K, uint32_t 
 int ks_ctx_destroy(ks_ctx* ctx);
 
 /* Tuning options of a context (results never depend on them).
- *   KS_OPT_BCONV_KERNEL   which fused base-conversion kernel the pipelines use: 1 = vector fp64 accumulation,
- *                         2 = int8 matrix cores; 0 (default) = chosen from the launch size.
+ *   KS_OPT_BCONV_KERNEL   which base-conversion kernel the pipelines (fused with the column transform) and bconv use:
+ *                         1 = vector fp64 accumulation, 2 = int8 matrix cores; 0 (default) = chosen from the launch
+ *                         size (the matrix cores for launches too small to fill the chip).
  *   KS_OPT_BCONV_TARGETS  target limbs per workgroup (vector kernel, 1..4) or per lane half (matrix-core kernel, 1 or 3) of
  *                         the fused conversion kernel; 0 (default) = chosen from the launch size.
  * Not thread-safe against calls in flight on the same context from other host threads.  KS_EINVAL for an unknown

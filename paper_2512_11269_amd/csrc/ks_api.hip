@@ -234,9 +234,13 @@ static int bconv_impl(const ks_ctx* c, const void* in, const uint32_t* src_ids, 
         const uint32_t nb = std::min(batch - b0, 32768u);
         const char* ip = static_cast<const char*>(in) + (uint64_t)b0 * n_src * N * word;
         char* op = static_cast<char*>(out) + (uint64_t)b0 * n_dst * N * word;
-        // the vector kernel unless the matrix-core one is asked for (it measured no faster: both move the same bytes
-        // and the conversion alone is bandwidth-bound); 32-bit words always take the vector kernel
-        if (!words32 && c->opt[KS_OPT_BCONV_KERNEL] == 2)
+        // Which kernel (KS_OPT_BCONV_KERNEL overrides): launches of a few polynomials run about twice as fast on the
+        // matrix-core kernel (twice the workgroups, targets walked six at a time: 10.9 against 20.9 us for one polynomial,
+        // 8 -> 24 moduli at N = 2^16); once the chip is full both are bandwidth-bound and the vector kernel is 9-12 %
+        // ahead.  32-bit words always take the vector kernel.
+        const bool few = (uint64_t)nb * (N / 256) < 1024;
+        const int kernel = c->opt[KS_OPT_BCONV_KERNEL] ? c->opt[KS_OPT_BCONV_KERNEL] : (few ? 2 : 1);
+        if (!words32 && kernel == 2)
             launch_bconv_mfma(c, set, n_src + n_dst, reinterpret_cast<const uint64_t*>(ip), (uint64_t)n_src * N,
                               reinterpret_cast<uint64_t*>(op), (uint64_t)n_dst * N, nb, s);
         else
