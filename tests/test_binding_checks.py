@@ -17,6 +17,10 @@ def _t(*shape, dtype=torch.int64):
     return torch.zeros(shape, dtype=dtype)
 
 
+def _i(*shape):
+    return _t(*shape, dtype=torch.int32)
+
+
 CTX = _Ctx()
 N = CTX.N
 KEY = (2, 2, 6, N)
@@ -42,6 +46,14 @@ KEY = (2, 2, 6, N)
     lambda: K.ntt_fwd(CTX, _t(3, N - 8), [0, 1, 2]),
     lambda: K.ntt_inv(CTX, _t(2, N), [0, 1, 2]),
     lambda: K.bconv(CTX, _t(1, 2, N), [0, 1], _t(1, 3, N), [2, 3, 4, 5]),                          # output for three targets, four asked
+    # the 32-bit-word forms check the same element counts
+    lambda: K.ks_rotate_hoisted_u32(CTX, _i(2, 2, 4, N), 4, [5, 25], [_i(*KEY), _i(*KEY)], _i(2, 1, 2, 4, N), _t(10)),
+    lambda: K.ks_rotate_mac_hoisted_u32(CTX, _i(1, 2, 4, N), 4, [5], [_i(*KEY)], [_i(5, N)], _i(1, 2, 4, N), _t(10)),
+    lambda: K.hmult_relin_rescale_u32(CTX, _i(1, 2, 4, N), _i(1, 2, 4, N), 4, _i(*KEY), _i(1, 2, 4, N), _t(10)),
+    lambda: K.hmult_relin_rescale_merged_u32(CTX, _i(2, 2, 4, N), _i(1, 2, 4, N), 4, _i(*KEY), _i(2, 2, 3, N), _t(10)),
+    lambda: K.ntt_fwd_u32(CTX, _i(3, N - 8), [0, 1, 2]),
+    lambda: K.ntt_inv_u32(CTX, _i(2, N), [0, 1, 2]),
+    lambda: K.bconv_u32(CTX, _i(1, 2, N), [0, 1], _i(1, 3, N), [2, 3, 4, 5]),
 ])
 def test_wrong_sizes_are_refused(call):
     with pytest.raises(K.KsError):
