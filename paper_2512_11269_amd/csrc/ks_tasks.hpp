@@ -237,7 +237,10 @@ __device__ __forceinline__ void task_bconv_mfma_cols(const double* __restrict__ 
 // One wavefront: four rows (group rg) of limb position pos of one batch item.  d_b / lifted_b / acc_b: that batch item's
 // d [ell][N], raised digits [ndig][E][N] and accumulators [2][E][N].  lds_wave: 4 * kRowPitch doubles, lds_ta_wave: 64.
 // WD / WK: word types of d and of the key (64-bit, or 32-bit for moduli below 2^32).
-template <int LOG_R, typename WD, typename WK>
+// PREFETCH (64-bit words only): loads are requested in the order x(0), key(0), x(1), key(1), ... and return in that order.
+// While digit j is transformed, key(j) and x(j + 1) are in flight; every key slot is refilled with the next digit's as soon
+// as its product is done, so key(j + 1) has the whole transform of digit j + 1 to arrive.
+template <int LOG_R, typename WD, typename WK, bool PREFETCH = false>
 __device__ __forceinline__ void task_rows_inner_product(const TwTables& tw, const TwTables& twi, const Mod* __restrict__ mods,
                                                         const DigitRanges& dg, uint32_t ell, uint32_t E, uint32_t L, uint32_t M,
                                                         const WD* __restrict__ d_b, const uint64_t* __restrict__ lifted_b,
@@ -258,6 +261,56 @@ __device__ __forceinline__ void task_rows_inner_product(const TwTables& tw, cons
     load_row_twiddles_b(tb, tw, mid, N, R + row, j0, m);
     __syncthreads();
 
+    if constexpr (PREFETCH && sizeof(WD) == 8 && sizeof(WK) == 8) {
+        const uint64_t* keys = reinterpret_cast<const uint64_t*>(evk) + (uint64_t)mid * N + off;
+        const uint64_t comp = (uint64_t)M * N;
+        auto source = [&](uint32_t j) {
+            const bool own = pos >= dg.lo[j] && pos < dg.hi[j];  // uniform
+            return own ? reinterpret_cast<const uint64_t*>(d_b) + (uint64_t)pos * N + off : lifted_b + ((uint64_t)j * E + pos) * N + off;
+        };
+        uint64_t xn[16], kc0[16], kc1[16];
+        {
+            const uint64_t* src = source(0);
+#pragma unroll
+            for (int k = 0; k < 16; ++k) xn[k] = src[16 * k];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                kc0[k] = keys[16 * k];
+                kc1[k] = keys[comp + 16 * k];
+            }
+        }
+        auto digit = [&](uint32_t j, auto next) {
+            constexpr bool NEXT = decltype(next)::value;
+            const bool own = pos >= dg.lo[j] && pos < dg.hi[j];  // uniform
+            double x[16];
+            if (own) {
+#pragma unroll
+                for (int k = 0; k < 16; ++k) x[k] = u64_to_f64(xn[k]);
+            } else {
+#pragma unroll
+                for (int k = 0; k < 16; ++k) x[k] = __longlong_as_double((long long)xn[k]);
+            }
+            const uint64_t* kp = keys + (uint64_t)(j + 1) * 2 * comp;
+            if constexpr (NEXT) {
+                const uint64_t* src = source(j + 1);
+#pragma unroll
+                for (int k = 0; k < 16; ++k) xn[k] = src[16 * k];
+            }
+            if (!own) row_fwd_core_lds(x, lds_ta_wave + rr * 16, tb, j0, lds_wave + rr * kRowPitch, m);
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                a0[k] += mulmod_lazy(x[k], u64_to_f64(kc0[k]), m);
+                a1[k] += mulmod_lazy(x[k], u64_to_f64(kc1[k]), m);
+                if constexpr (NEXT) {
+                    kc0[k] = kp[16 * k];
+                    kc1[k] = kp[comp + 16 * k];
+                }
+            }
+        };
+#pragma unroll 1
+        for (uint32_t j = 0; j + 1 < dg.ndig; ++j) digit(j, std::true_type{});
+        digit(dg.ndig - 1, std::false_type{});
+    } else {
 #pragma unroll 1
     for (uint32_t j = 0; j < dg.ndig; ++j) {
         const bool own = pos >= dg.lo[j] && pos < dg.hi[j];  // uniform
@@ -311,6 +364,7 @@ __device__ __forceinline__ void task_rows_inner_product(const TwTables& tw, cons
             a0[k] += mulmod_lazy(x[k], k0[k], m);
             a1[k] += mulmod_lazy(x[k], k1[k], m);
         }
+    }
     }
     uint64_t* o0 = acc_b + ((uint64_t)0 * E + pos) * N + off;
     uint64_t* o1 = acc_b + ((uint64_t)1 * E + pos) * N + off;
