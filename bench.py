@@ -432,7 +432,8 @@ def bench_rotate_mac(args, torch, K, ks_inputs):
 def bench_bsgs(args, torch, K, ks_inputs):
     """Baby-step giant-step linear transform with configuration 3's parameters: 64 ciphertexts, 16 x 16 = 256 plaintext
     diagonals per ciphertext (rotation 0 of either level is the identity and needs no key)."""
-    cfg = ks_inputs.CONFIGS[3]
+    cfg, dtype, narrow, tag = _words(args, torch, ks_inputs.CONFIGS[3])
+    w32 = args.word_size == 32
     q, p = ks_inputs.moduli(cfg)
     logN, L, B, dnum = cfg["logN"], cfg["L"], cfg["batch"], cfg["dnum"]
     n1 = n2 = 16
@@ -441,21 +442,23 @@ def bench_bsgs(args, torch, K, ks_inputs):
     _apply_options(ctx, args)
     gal = ks_inputs.galois_elements(logN, n1 + n2)
     baby, giant = [1] + gal[:n1 - 1], [1] + gal[n1:n1 + n2 - 1]
-    key = lambda tid, g: None if g == 1 else ks_inputs.uniform_residues(cfg["seed"], tid, (dnum, 2), q + p, N, device="cuda")
+    key = lambda tid, g: None if g == 1 else narrow(ks_inputs.uniform_residues(cfg["seed"], tid, (dnum, 2), q + p, N, device="cuda"))
     bkeys = [key(10 + i, g) for i, g in enumerate(baby)]
     gkeys = [key(40 + i, g) for i, g in enumerate(giant)]
-    pts = [[ks_inputs.uniform_residues(cfg["seed"], 100 + g * n1 + b, (), q + p, N, device="cuda") for b in range(n1)] for g in range(n2)]
-    ct = ks_inputs.uniform_residues(cfg["seed"], 1, (B, 2), q, N, device="cuda")
-    out = torch.empty((B, 2, L, N), dtype=torch.int64, device="cuda")
-    ws = torch.empty(K.ks_workspace_bytes(ctx, K.KS_OP_BSGS, L, B) // 8, dtype=torch.int64, device="cuda")
-    fn = lambda: K.ks_bsgs_linear_transform(ctx, ct, L, baby, bkeys, giant, gkeys, pts, out, ws)
+    pts = [[narrow(ks_inputs.uniform_residues(cfg["seed"], 100 + g * n1 + b, (), q + p, N, device="cuda")) for b in range(n1)]
+           for g in range(n2)]
+    ct = narrow(ks_inputs.uniform_residues(cfg["seed"], 1, (B, 2), q, N, device="cuda"))
+    out = torch.empty((B, 2, L, N), dtype=dtype, device="cuda")
+    ws = torch.empty(K.ks_workspace_bytes(ctx, K.KS_OP_BSGS_U32 if w32 else K.KS_OP_BSGS, L, B) // 8, dtype=torch.int64, device="cuda")
+    entry = K.ks_bsgs_linear_transform_u32 if w32 else K.ks_bsgs_linear_transform
+    fn = lambda: entry(ctx, ct, L, baby, bkeys, giant, gkeys, pts, out, ws)
     reps = max(2, args.steps // 100)
     ms = _time_calls(torch, fn, reps)
     kernels = _kernel_breakdown(K, torch, fn, B * n1 * n2)
     return {"metric": "bsgs_diagonal_terms_per_sec", "value": round(B * n1 * n2 / (ms * 1e-3), 1), "unit": "rotated-and-multiplied term/s",
             "n_gpus": 1, "steps": reps, "warmup": 1, "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak",
             "vs_baseline": None, "dtype": "f64", "data": "synthetic", "transforms_per_sec": round(B / (ms * 1e-3), 1),
-            "config": {"workload": "bsgs linear transform N=2^16 L=24 K=8 dnum=3, 64 ciphertexts x (16 baby x 16 giant) diagonals per call"},
+            "config": {"workload": "bsgs linear transform N=2^16 L=24 K=8 dnum=3, 64 ciphertexts x (16 baby x 16 giant) diagonals per call" + tag},
             "roofline": _dominant_roofline(kernels), "kernels": kernels}
 
 
@@ -598,7 +601,7 @@ def main():
     ap.add_argument("--no-batched", action="store_true", help="skip the batched key-switch measurement (counter runs)")
     ap.add_argument("--workload", default="keyswitch", choices=["keyswitch", "keyswitch_u32", "ntt", "rotate", "rotate_mac", "bsgs", "hmult", "hmult_merged", "bconv", "copy"])
     ap.add_argument("--word-size", type=int, default=64, choices=[64, 32],
-                    help="32: the rotate / rotate_mac / hmult / hmult_merged / ntt workloads with 28-bit primes in 32-bit words")
+                    help="32: the rotate / rotate_mac / bsgs / hmult / hmult_merged / ntt workloads with 28-bit primes in 32-bit words")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--repeats", type=int, default=5, help="timed runs of the headline workload (the median is reported)")
     ap.add_argument("--min-calls", type=int, default=200,

@@ -54,7 +54,8 @@ enum { /* operations for ks_workspace_bytes */
     KS_OP_ROTATE_HOISTED = 2,
     KS_OP_HMULT_RELIN_RESCALE = 3,
     KS_OP_BSGS = 4,
-    KS_OP_ROTATE_HOISTED_U32 = 5 /* ks_rotate_hoisted_u32 and ks_rotate_mac_hoisted_u32 */
+    KS_OP_ROTATE_HOISTED_U32 = 5, /* ks_rotate_hoisted_u32 and ks_rotate_mac_hoisted_u32 */
+    KS_OP_BSGS_U32 = 6            /* ks_bsgs_linear_transform_u32 */
 };
 
 /* Build the tables for one parameter set on GPU `device`.
@@ -217,7 +218,8 @@ int hmult_relin_rescale_merged(const ks_ctx* ctx, const uint64_t* cta, const uin
  * residue per uint32_t in the same layout.  Arithmetic and results are identical; the traffic of those tensors
  * halves.  Intermediate values in the workspace stay 8 bytes wide.  Every call returns KS_EINVAL unless every modulus
  * of the context is below 2^32.  Workspace: the operation code of the 64-bit call, except that the two rotation calls
- * take KS_OP_ROTATE_HOISTED_U32 (the ciphertexts of a chunk are widened once into the workspace).
+ * take KS_OP_ROTATE_HOISTED_U32 and the BSGS transform KS_OP_BSGS_U32 (the ciphertexts of a chunk are widened once into
+ * the workspace).
  *   ntt_fwd_u32 / ntt_inv_u32 : in place on [batch][nlimbs][N] uint32_t.
  *   bconv_u32                 : pairs registered with bconv_prepare serve both word sizes. */
 int ntt_fwd_u32(const ks_ctx* ctx, uint32_t* data, const uint32_t* mod_ids, uint32_t nlimbs, uint32_t batch, void* stream);
@@ -230,6 +232,10 @@ int ks_rotate_hoisted_u32(const ks_ctx* ctx, const uint32_t* ct, uint32_t ell, c
 int ks_rotate_mac_hoisted_u32(const ks_ctx* ctx, const uint32_t* ct, uint32_t ell, const uint32_t* galois,
                               const uint32_t* const* rot_keys, const uint32_t* const* pts, uint32_t n_rot,
                               uint32_t* out, uint32_t batch, void* ws, size_t ws_bytes, void* stream);
+int ks_bsgs_linear_transform_u32(const ks_ctx* ctx, const uint32_t* ct, uint32_t ell, const uint32_t* baby_galois,
+                                 const uint32_t* const* baby_keys, uint32_t n1, const uint32_t* giant_galois,
+                                 const uint32_t* const* giant_keys, uint32_t n2, const uint32_t* const* pts, uint32_t* out,
+                                 uint32_t batch, void* ws, size_t ws_bytes, void* stream);
 int hmult_relin_rescale_u32(const ks_ctx* ctx, const uint32_t* cta, const uint32_t* ctb, uint32_t ell,
                             const uint32_t* rlk, uint32_t* out, uint32_t batch, void* ws, size_t ws_bytes,
                             void* stream);

@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("KS_MI355X_LIB") or os.path.join(_HERE, "libks_mi355x.so")
 _lib = None
 
-KS_OP_KEYSWITCH, KS_OP_ROTATE_HOISTED, KS_OP_HMULT_RELIN_RESCALE, KS_OP_BSGS, KS_OP_ROTATE_HOISTED_U32 = 1, 2, 3, 4, 5
+KS_OP_KEYSWITCH, KS_OP_ROTATE_HOISTED, KS_OP_HMULT_RELIN_RESCALE, KS_OP_BSGS, KS_OP_ROTATE_HOISTED_U32, KS_OP_BSGS_U32 = 1, 2, 3, 4, 5, 6
 KS_OPT_BCONV_TARGETS, KS_OPT_BCONV_KERNEL = 0, 1
 
 _u64p = ctypes.POINTER(ctypes.c_uint64)
@@ -70,8 +70,8 @@ def load_library():
                                              ctypes.c_size_t, _vp]
     lib.hmult_relin_rescale.argtypes = [_vp, _vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
     lib.hmult_relin_rescale_merged.argtypes = [_vp, _vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint32, _vp, ctypes.c_size_t, _vp]
-    for name in ("ntt_fwd", "ntt_inv", "bconv", "ks_rotate_hoisted", "ks_rotate_mac_hoisted", "hmult_relin_rescale",
-                 "hmult_relin_rescale_merged"):
+    for name in ("ntt_fwd", "ntt_inv", "bconv", "ks_rotate_hoisted", "ks_rotate_mac_hoisted", "ks_bsgs_linear_transform",
+                 "hmult_relin_rescale", "hmult_relin_rescale_merged"):
         getattr(lib, name + "_u32").argtypes = getattr(lib, name).argtypes
     lib.ks_profile_enable.argtypes = [ctypes.c_int]
     lib.ks_profile_report.argtypes = [ctypes.c_char_p, ctypes.c_size_t]
@@ -369,22 +369,34 @@ def ks_rotate_mac_hoisted_u32(ctx: Context, ct: torch.Tensor, ell: int, galois, 
     _rotate_mac("ks_rotate_mac_hoisted_u32", torch.int32, KS_OP_ROTATE_HOISTED_U32, ctx, ct, ell, galois, rot_keys, pts, out, ws)
 
 
+def _bsgs(name, dtype, op, ctx, ct, ell, baby_galois, baby_keys, giant_galois, giant_keys, pts, out, ws) -> None:
+    batch = _rotation_args(ctx, ct, ell, baby_galois, baby_keys, f"{name} (baby steps)")
+    _rotation_args(ctx, ct, ell, giant_galois, giant_keys, f"{name} (giant steps)")
+    if len(pts) != len(giant_keys) or any(len(row) != len(baby_keys) for row in pts):
+        raise KsError(f"{name}: plaintexts must form n2 rows of n1 entries")
+    flat = [w for row in pts for w in row]
+    _plaintexts_ok(ctx, flat)
+    _need(out, batch * 2 * ell * ctx.N, f"{name} out")
+    _workspace_ok(ctx, ws, op, ell, batch)
+    _on_device(ctx, ct, out, ws, *baby_keys, *giant_keys, *flat)
+    _check(getattr(load_library(), name)(ctx.handle, _dev_ptr(ct, dtype), ell, _u32_array(baby_galois), _ptr_array(baby_keys, dtype),
+                                         len(baby_keys), _u32_array(giant_galois), _ptr_array(giant_keys, dtype), len(giant_keys),
+                                         _ptr_array(flat, dtype), _dev_ptr(out, dtype), batch, _dev_ptr(ws), ws.numel() * 8, _stream()),
+           name)
+
+
 def ks_bsgs_linear_transform(ctx: Context, ct: torch.Tensor, ell: int, baby_galois, baby_keys, giant_galois, giant_keys, pts,
                              out: torch.Tensor, ws: torch.Tensor) -> None:
     """pts: n2 rows of n1 plaintext tensors (or None)."""
-    batch = _rotation_args(ctx, ct, ell, baby_galois, baby_keys, "ks_bsgs_linear_transform (baby steps)")
-    _rotation_args(ctx, ct, ell, giant_galois, giant_keys, "ks_bsgs_linear_transform (giant steps)")
-    if len(pts) != len(giant_keys) or any(len(row) != len(baby_keys) for row in pts):
-        raise KsError("ks_bsgs_linear_transform: plaintexts must form n2 rows of n1 entries")
-    flat = [w for row in pts for w in row]
-    _plaintexts_ok(ctx, flat)
-    _need(out, batch * 2 * ell * ctx.N, "ks_bsgs_linear_transform out")
-    _workspace_ok(ctx, ws, KS_OP_BSGS, ell, batch)
-    _on_device(ctx, ct, out, ws, *baby_keys, *giant_keys, *flat)
-    _check(load_library().ks_bsgs_linear_transform(ctx.handle, _dev_ptr(ct), ell, _u32_array(baby_galois), _ptr_array(baby_keys),
-                                                   len(baby_keys), _u32_array(giant_galois), _ptr_array(giant_keys), len(giant_keys),
-                                                   _ptr_array(flat), _dev_ptr(out), batch, _dev_ptr(ws), ws.numel() * 8, _stream()),
-           "ks_bsgs_linear_transform")
+    _bsgs("ks_bsgs_linear_transform", torch.int64, KS_OP_BSGS, ctx, ct, ell, baby_galois, baby_keys, giant_galois, giant_keys, pts,
+          out, ws)
+
+
+def ks_bsgs_linear_transform_u32(ctx: Context, ct: torch.Tensor, ell: int, baby_galois, baby_keys, giant_galois, giant_keys, pts,
+                                 out: torch.Tensor, ws: torch.Tensor) -> None:
+    """ct, keys, plaintexts, out: int32 tensors, one residue (< 2^32) per word; ws: int64, sized for KS_OP_BSGS_U32."""
+    _bsgs("ks_bsgs_linear_transform_u32", torch.int32, KS_OP_BSGS_U32, ctx, ct, ell, baby_galois, baby_keys, giant_galois,
+          giant_keys, pts, out, ws)
 
 
 def ks_keyswitch_u32(ctx: Context, d: torch.Tensor, ell: int, evk: torch.Tensor, out: torch.Tensor, ws: torch.Tensor) -> None:

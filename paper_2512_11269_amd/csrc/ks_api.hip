@@ -96,10 +96,12 @@ extern "C" size_t ks_workspace_bytes(const ks_ctx* c, int op, uint32_t ell, uint
             // the chunk's ciphertexts widened to 64-bit words
             if (op == KS_OP_ROTATE_HOISTED_U32) words += (uint64_t)bc * 2 * ell * N;
             break;
-        case KS_OP_BSGS: {
+        case KS_OP_BSGS:
+        case KS_OP_BSGS_U32: {
             // second set of raised digits and accumulators (outer level), inner result [bc][2][ell]
             const KsWorkspace w = ks_ws_words(c, lv, bc);
             words += w.lifted + w.acc + (uint64_t)bc * 2 * ell * N;
+            if (op == KS_OP_BSGS_U32) words += (uint64_t)bc * 2 * ell * N;  // the chunk's ciphertexts widened to 64-bit words
             break;
         }
         case KS_OP_HMULT_RELIN_RESCALE:
@@ -455,44 +457,61 @@ extern "C" int ks_rotate_mac_hoisted_u32(const ks_ctx* c, const uint32_t* ct, ui
                            reinterpret_cast<const void* const*>(pts), n_rot, out, batch, ws, ws_bytes, stream, true);
 }
 
-extern "C" int ks_bsgs_linear_transform(const ks_ctx* c, const uint64_t* ct, uint32_t ell, const uint32_t* baby_galois,
-                                        const uint64_t* const* baby_keys, uint32_t n1, const uint32_t* giant_galois,
-                                        const uint64_t* const* giant_keys, uint32_t n2, const uint64_t* const* pts, uint64_t* out,
-                                        uint32_t batch, void* ws, size_t ws_bytes, void* stream) {
+// ct, keys, plaintexts and out in 64-bit words, or all in 32-bit words (words32).
+static int bsgs_impl(const ks_ctx* c, const void* ct, uint32_t ell, const uint32_t* baby_galois, const void* const* bkeys, uint32_t n1,
+                     const uint32_t* giant_galois, const void* const* gkeys, uint32_t n2, const void* const* ptv, void* out,
+                     uint32_t batch, void* ws, size_t ws_bytes, void* stream, bool words32) {
     int rc = check_pipeline_args(c, ell, 1, ct, ct, out, ws);
     if (rc != KS_OK) return rc;
-    const void* const* bkeys = reinterpret_cast<const void* const*>(baby_keys);
-    const void* const* gkeys = reinterpret_cast<const void* const*>(giant_keys);
-    const void* const* ptv = reinterpret_cast<const void* const*>(pts);
-    if (!pts || check_mac_rotations(c, giant_galois, gkeys, nullptr, n2) != KS_OK) return KS_EINVAL;
+    if (!ptv || check_mac_rotations(c, giant_galois, gkeys, nullptr, n2) != KS_OK) return KS_EINVAL;
     for (uint32_t g = 0; g < n2; ++g)
         if (check_mac_rotations(c, baby_galois, bkeys, ptv + (size_t)g * n1, n1) != KS_OK) return KS_EINVAL;
+    if (words32 && !moduli_fit_u32(c)) return KS_EINVAL;
     if (batch == 0) return KS_OK;
-    if (ws_bytes < ks_workspace_bytes(c, KS_OP_BSGS, ell, batch, 0)) return KS_EWORKSPACE;
+    if (ws_bytes < ks_workspace_bytes(c, words32 ? KS_OP_BSGS_U32 : KS_OP_BSGS, ell, batch, 0)) return KS_EWORKSPACE;
     const Level& lv = c->levels[ell - 1];
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const uint64_t N = c->N, ct_bs = 2ull * ell * N;
+    const uint64_t N = c->N, ct_bs = 2ull * ell * N, word = words32 ? 4 : 8;
     for (uint32_t b0 = 0; b0 < batch; b0 += kChunk) {
         const uint32_t bc = std::min(batch - b0, kChunk);
         const KsWorkspace w = ks_ws_words(c, lv, bc);
-        uint64_t* coeff = static_cast<uint64_t*>(ws);
+        uint64_t* coeff;
+        const uint64_t* c0 = chunk_ct(c, ct, b0, bc, ct_bs, words32, ws, &coeff, s);
         uint64_t* lifted = coeff + w.coeff;          // raised digits of c1, shared by every baby step of every giant step
         uint64_t* acc = lifted + w.lifted;           // inner sum of the current giant step
         uint64_t* conv = acc + w.acc;
         uint64_t* lifted_v = conv + w.conv;          // raised digits of the current inner result
         uint64_t* acc_outer = lifted_v + w.lifted;   // outer sum over the giant steps
-        uint64_t* v = acc_outer + w.acc;             // [bc][2][ell][N] inner result of the current giant step
-        const uint64_t* c0 = ct + (uint64_t)b0 * ct_bs;
+        uint64_t* v = acc_outer + w.acc;             // [bc][2][ell][N] inner result of the current giant step (64-bit words)
         mod_up(c, lv, c0 + (uint64_t)ell * N, ct_bs, coeff, lifted, bc, true, s);
         for (uint32_t g = 0; g < n2; ++g) {
-            rotate_mac_all(c, lv, c0, ct_bs, lifted, baby_galois, bkeys, ptv + (size_t)g * n1, n1, acc, bc, false, s);
+            rotate_mac_all(c, lv, c0, ct_bs, lifted, baby_galois, bkeys, ptv + (size_t)g * n1, n1, acc, bc, false, s, words32);
             mod_down(c, lv, acc, conv, v, ct_bs, nullptr, 0, 0, 1, bc, false, s);
             if (giant_galois[g] != 1) mod_up(c, lv, v + (uint64_t)ell * N, ct_bs, coeff, lifted_v, bc, true, s);
-            rotate_mac_all(c, lv, v, ct_bs, lifted_v, giant_galois + g, gkeys + g, nullptr, 1, acc_outer, bc, g != 0, s);
+            rotate_mac_all(c, lv, v, ct_bs, lifted_v, giant_galois + g, gkeys + g, nullptr, 1, acc_outer, bc, g != 0, s, words32);
         }
-        mod_down(c, lv, acc_outer, conv, out + (uint64_t)b0 * ct_bs, ct_bs, nullptr, 0, 0, 1, bc, false, s);
+        mod_down(c, lv, acc_outer, conv, static_cast<char*>(out) + (uint64_t)b0 * ct_bs * word, ct_bs, nullptr, 0, 0, 1, bc, false, s,
+                 words32);
     }
-    return finish("ks_bsgs_linear_transform");
+    return finish(words32 ? "ks_bsgs_linear_transform_u32" : "ks_bsgs_linear_transform");
+}
+
+extern "C" int ks_bsgs_linear_transform(const ks_ctx* c, const uint64_t* ct, uint32_t ell, const uint32_t* baby_galois,
+                                        const uint64_t* const* baby_keys, uint32_t n1, const uint32_t* giant_galois,
+                                        const uint64_t* const* giant_keys, uint32_t n2, const uint64_t* const* pts, uint64_t* out,
+                                        uint32_t batch, void* ws, size_t ws_bytes, void* stream) {
+    return bsgs_impl(c, ct, ell, baby_galois, reinterpret_cast<const void* const*>(baby_keys), n1, giant_galois,
+                     reinterpret_cast<const void* const*>(giant_keys), n2, reinterpret_cast<const void* const*>(pts), out, batch, ws,
+                     ws_bytes, stream, false);
+}
+
+extern "C" int ks_bsgs_linear_transform_u32(const ks_ctx* c, const uint32_t* ct, uint32_t ell, const uint32_t* baby_galois,
+                                            const uint32_t* const* baby_keys, uint32_t n1, const uint32_t* giant_galois,
+                                            const uint32_t* const* giant_keys, uint32_t n2, const uint32_t* const* pts, uint32_t* out,
+                                            uint32_t batch, void* ws, size_t ws_bytes, void* stream) {
+    return bsgs_impl(c, ct, ell, baby_galois, reinterpret_cast<const void* const*>(baby_keys), n1, giant_galois,
+                     reinterpret_cast<const void* const*>(giant_keys), n2, reinterpret_cast<const void* const*>(pts), out, batch, ws,
+                     ws_bytes, stream, true);
 }
 
 // Division by P q_{ell-1} of acc + P addend in one conversion (ModDown merged with the rescale that would follow):

@@ -49,6 +49,7 @@ KEY = (2, 2, 6, N)
     # the 32-bit-word forms check the same element counts
     lambda: K.ks_rotate_hoisted_u32(CTX, _i(2, 2, 4, N), 4, [5, 25], [_i(*KEY), _i(*KEY)], _i(2, 1, 2, 4, N), _t(10)),
     lambda: K.ks_rotate_mac_hoisted_u32(CTX, _i(1, 2, 4, N), 4, [5], [_i(*KEY)], [_i(5, N)], _i(1, 2, 4, N), _t(10)),
+    lambda: K.ks_bsgs_linear_transform_u32(CTX, _i(1, 2, 4, N), 4, [1, 5], [None, _i(*KEY)], [1], [None], [[None]], _i(1, 2, 4, N), _t(10)),
     lambda: K.hmult_relin_rescale_u32(CTX, _i(1, 2, 4, N), _i(1, 2, 4, N), 4, _i(*KEY), _i(1, 2, 4, N), _t(10)),
     lambda: K.hmult_relin_rescale_merged_u32(CTX, _i(2, 2, 4, N), _i(1, 2, 4, N), 4, _i(*KEY), _i(2, 2, 3, N), _t(10)),
     lambda: K.ntt_fwd_u32(CTX, _i(3, N - 8), [0, 1, 2]),

@@ -194,3 +194,26 @@ def test_two_piece_conversion_extreme_residues(small28):
         out = torch.empty((1, 2, ell, small28.N), dtype=torch.int64, device="cuda")
         K.ks_keyswitch(small28.ctx, d, ell, evk, out, workspace(small28.ctx, K.KS_OP_KEYSWITCH, ell, 1))
         assert_equal(out, small28.ref.keyswitch(host(d), host(evk), ell))
+
+
+@pytest.mark.parametrize("which,ell,batch,n1,n2", [("small28", 4, 2, 3, 2), ("small32", 3, 9, 2, 3), ("boot28", 24, 2, 3, 2)])
+def test_bsgs_linear_transform(which, ell, batch, n1, n2, request):
+    """Both hoisting levels with keys, plaintexts, ciphertexts and result in 32-bit words; the identity element (no key)
+    and a unit plaintext included."""
+    st = request.getfixturevalue(which)
+    gal = ks_inputs.galois_elements(st.logN, n1 + n2)
+    baby, giant = [1] + gal[:n1 - 1], [1] + gal[n1:n1 + n2 - 1]
+    all_ids = list(range(st.L + st.K))
+    key = lambda tid, g: None if g == 1 else st.uniform(2009, tid, (st.ctx.dnum, 2), all_ids)
+    bkeys = [key(10 + i, g) for i, g in enumerate(baby)]
+    gkeys = [key(40 + i, g) for i, g in enumerate(giant)]
+    pts = [[st.uniform(2009, 100 + g * n1 + b, (), all_ids) for b in range(n1)] for g in range(n2)]
+    pts[-1][0] = None
+    ct = st.uniform(2009, 1, (batch, 2), list(range(ell)))
+    out = torch.empty((batch, 2, ell, st.N), dtype=torch.int32, device="cuda")
+    K.ks_bsgs_linear_transform_u32(st.ctx, narrow(ct), ell, baby, [narrow(k) for k in bkeys], giant, [narrow(k) for k in gkeys],
+                                   [[narrow(w) for w in row] for row in pts], out, workspace(st.ctx, K.KS_OP_BSGS_U32, ell, batch))
+    hostify = lambda t: None if t is None else host(t)
+    want = st.ref.bsgs_linear_transform(host(ct), baby, [hostify(k) for k in bkeys], giant, [hostify(k) for k in gkeys],
+                                        [[hostify(w) for w in row] for row in pts], ell)
+    assert_equal(widen(out), want)
