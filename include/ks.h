@@ -83,8 +83,9 @@ enum { KS_OPT_BCONV_TARGETS = 0, KS_OPT_BCONV_KERNEL = 1, KS_OPT_COUNT_ = 2 };
 int ks_ctx_set_option(ks_ctx* ctx, int option, int value);
 
 /* Bytes of device workspace the given operation needs for `batch` ciphertexts at level `ell`
- * (n_rot is only read for KS_OP_ROTATE_HOISTED, which also serves ks_rotate_mac_hoisted; KS_OP_HMULT_RELIN_RESCALE
- * serves both multiplication entry points).  Returns 0 for invalid arguments.  Large batches are processed in
+ * (n_rot is only read for KS_OP_ROTATE_HOISTED and KS_OP_ROTATE_HOISTED_U32, which also serve the rotate-multiply-
+ * accumulate calls; KS_OP_HMULT_RELIN_RESCALE serves all four multiplication entry points, KS_OP_KEYSWITCH both
+ * key-switch word sizes).  Returns 0 for invalid arguments.  Large batches are processed in
  * internal chunks, so the result stops growing beyond a chunk. */
 size_t ks_workspace_bytes(const ks_ctx* ctx, int op, uint32_t ell, uint32_t batch, uint32_t n_rot);
 
