@@ -249,7 +249,7 @@ __global__ __launch_bounds__(64, PREFETCH ? 2 : 0) void rows_inner_product(TwTab
                                                          uint32_t ell, uint32_t E, uint32_t L, uint32_t M,
                                                          const WD* __restrict__ d, uint64_t d_ps,
                                                          const uint64_t* __restrict__ lifted, const WK* __restrict__ evk,
-                                                         uint64_t* __restrict__ acc, uint32_t batch) {
+                                                         uint64_t* __restrict__ acc, uint32_t batch, uint32_t special_first) {
     constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R;
     __shared__ double lds[4 * kRowPitch];
     __shared__ double lds_ta[4 * 16];
@@ -259,7 +259,13 @@ __global__ __launch_bounds__(64, PREFETCH ? 2 : 0) void rows_inner_product(TwTab
     // fetched into that L2 once and reused by the whole batch.
     const uint32_t slot = blockIdx.x >> 3, b = slot % batch, tile = (slot / batch) * 8 + (blockIdx.x & 7);
     if (tile >= (R / 4) * E) return;  // uniform: padding workgroups when the tile count is not a multiple of 8
-    const uint32_t rg = tile % (R / 4), pos = tile / (R / 4);
+    // special_first (launches whose wavefronts are all resident at once, i.e. a single ciphertext): the special limbs take
+    // the first workgroup ids.  Their wavefronts have the most arithmetic after their last load (one more transform and the
+    // two inverse row passes) and the memory system serves the earliest requests first, so started last they are the tail
+    // of the launch (59 k cycles per special wavefront against 37 k for the others; 40.2 -> 37.1 us per launch).  Batched
+    // launches keep them last: the next kernel reads exactly these limbs and finds them cached (0.5-2 % per call).
+    const uint32_t rg = tile % (R / 4), slot_pos = tile / (R / 4), n_special = E - ell;
+    const uint32_t pos = !special_first ? slot_pos : slot_pos < n_special ? ell + slot_pos : slot_pos - n_special;
     task_rows_inner_product<LOG_R, WD, WK, PREFETCH>(tw, twi, mods, dg, ell, E, L, M, d + (uint64_t)b * d_ps, lifted + (uint64_t)b * dg.ndig * E * N, evk,
                                       acc + (uint64_t)b * 2 * E * N, pos, rg, threadIdx.x, lds, lds_ta);
 }
@@ -286,7 +292,7 @@ void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const void* d, 
     const bool prefetch = grid.x > 2048;
 #define KS_LAUNCH_IP(LOGR, WDT, WKT, PF)                                                                                           \
     hipLaunchKernelGGL((rows_inner_product<LOGR, WDT, WKT, PF>), grid, block, 0, s, c->tw_fwd, c->tw_inv, c->d_mod, dg, lv.ell, lv.E, c->L, \
-                       c->M, static_cast<const WDT*>(d), d_ps, lifted, static_cast<const WKT*>(evk), acc, batch)
+                       c->M, static_cast<const WDT*>(d), d_ps, lifted, static_cast<const WKT*>(evk), acc, batch, prefetch ? 0u : 1u)
 #define KS_LAUNCH(LOGR)                                                          \
     if (d_words32 && key_words32) KS_LAUNCH_IP(LOGR, uint32_t, uint32_t, false); \
     else if (key_words32) KS_LAUNCH_IP(LOGR, uint64_t, uint32_t, false);         \
