@@ -96,7 +96,7 @@ def test_keyswitch_small(small, ell, batch):
     assert_equal(out, small.ref.keyswitch(host(d), host(evk), ell))
 
 
-@pytest.mark.parametrize("ell,batch", [(24, 1), (17, 2)])
+@pytest.mark.parametrize("ell,batch", [(24, 1), (17, 2), (17, 1), (24, 9)])   # one ciphertext and several: different tile orders and load schedules; 9 = a chunk and one
 def test_keyswitch_bootstrap_shape(boot, ell, batch):
     d, evk, out = _run_keyswitch(boot, ks_inputs.CONFIGS[2]["seed"], ell, batch)
     assert_equal(out, boot.ref.keyswitch(host(d), host(evk), ell))
