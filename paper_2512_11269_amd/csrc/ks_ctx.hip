@@ -108,9 +108,9 @@ void fill_bconv_plan(const ks_ctx* c, BConvPlan* plan, const uint32_t* src_ids, 
             uint64_t prod = 1 % mt;
             for (uint32_t k = 0; k < n_src; ++k)
                 if (k != i) prod = h_mulmod(prod, c->mod[src_ids[k]] % mt, mt);
-            // factors against the pieces of a source residue: cut at 12 and 24 bits, or at 14 bits when every modulus is
-            // below 2^28 (split3 / split2)
-            const int cut = c->pieces == 2 ? 14 : 12;
+            // factors against the pieces of a source residue: cut at 12 and 24 bits, or at 16 bits when every modulus is
+            // below 2^32 (split3 / split2)
+            const int cut = c->pieces == 2 ? 16 : 12;
             for (int k = 0; k < 3; ++k) {
                 const uint64_t f = h_mulmod(prod, (1ull << (cut * k)) % mt, mt);
                 const double centred = f > mt / 2 ? -(double)(mt - f) : (double)f;
@@ -265,7 +265,7 @@ extern "C" int ks_ctx_create(ks_ctx** out, uint32_t logN, uint32_t L, uint32_t K
     }
     c->pieces = 2;
     for (uint64_t v : c->mod)
-        if (v >> 28) c->pieces = 3;
+        if (v >> 32) c->pieces = 3;
     {
         CK(hipSetDevice(device));
         CK(bind_static_scratch(device));

@@ -82,13 +82,14 @@ KS_HD void split3(double y, double& y2, double& y1, double& y0) {
     y0 = rem - y1;
 }
 
-// The same for 0 <= y < 2^28 (contexts whose moduli are all below 2^28, the paper's word size): y = y1 + y0 with y1 a
-// multiple of 2^14 and |y0| <= 2^13.  With f_k = centred([f * 2^(14 k)]_t) * 2^(-14 k), |f_k| * 2^(14 k) <= 2^27, the sum
-// y1 f_1 + y0 f_0 is an integer congruent to y f modulo t and below 2^42 in magnitude: sixteen accumulate exactly, at
-// two FMAs per source and target and three additions per split.
+// The same for 0 <= y < 2^32 (contexts whose moduli are all below 2^32, i.e. every context the 32-bit-word entry points
+// accept, the paper's 28-bit primes included): y = y1 + y0 with y1 a multiple of 2^16 and |y0| <= 2^15.  With
+// f_k = centred([f * 2^(16 k)]_t) * 2^(-16 k), |f_k| * 2^(16 k) <= 2^31, the sum y1 f_1 + y0 f_0 is an integer congruent to
+// y f modulo t and below 1.5 * 2^47 in magnitude: sixteen accumulate exactly (below 2^53), at two FMAs per source and
+// target and three additions per split.
 KS_HD void split2(double y, double& y1, double& y0) {
-    constexpr double kRound14 = 0x1.8p66;
-    y1 = (y + kRound14) - kRound14;
+    constexpr double kRound16 = 0x1.8p68;
+    y1 = (y + kRound16) - kRound16;
     y0 = y - y1;
 }
 

@@ -17,7 +17,7 @@
 namespace ks {
 
 // One source of a conversion: acc[t][k] += y[k] * f[t] as exact integers -- each source point is split once (split3, or
-// split2 when every modulus is below 2^28), every target adds PIECES products against its shifted, centred factors.
+// split2 when every modulus is below 2^32), every target adds PIECES products against its shifted, centred factors.
 // REFILL: once y[k] has been consumed, the same registers receive point k of the next source (byte offset next_off in
 // the buffer), which then has a whole source's worth of arithmetic to arrive.
 // The factors of the next source (fnext: uniform, scalar loads) are requested after the first point, together with
@@ -67,8 +67,8 @@ __device__ __forceinline__ void bconv_accumulate(double (&acc)[TS][16], double (
 // column stages of the forward transform modulo t and stores raw doubles.  The sources are re-read by the workgroups of
 // the other target subsets; those reads are served by L2 / the last-level cache.
 // ------------------------------------------------------------------------------------------------
-// PIECES: 3 in general (moduli below 2^36); 2 when every modulus of the context is below 2^28 (the plan's factors are
-// then cut at 14 bits: two products per source and target instead of three).
+// PIECES: 3 in general (moduli below 2^36); 2 when every modulus of the context is below 2^32 (the plan's factors are
+// then cut at 16 bits: two products per source and target instead of three).
 template <int LOG_R, int TS, bool TWO_SETS, int PIECES>
 __global__ __launch_bounds__(256) void bconv_ntt_cols(const double* __restrict__ tw, const BConvPlan* __restrict__ plans,
                                                       const uint64_t* __restrict__ y, uint64_t y_ps, uint64_t* __restrict__ out,

@@ -120,7 +120,7 @@ struct ks_ctx {
     ks::TwTables tw_fwd{}, tw_inv{};      // the three tables of each direction bundled for the row kernels
     std::vector<ks::Level> levels;        // index ell-1
     int opt[KS_OPT_COUNT_] = {};          // ks_ctx_set_option values, index = option id
-    int pieces = 3;                       // pieces a source residue is cut into by the fused conversion: 2 iff every modulus < 2^28
+    int pieces = 3;                       // pieces a source residue is cut into by the fused conversion: 2 iff every modulus < 2^32
     mutable std::mutex mu;
     mutable std::map<std::vector<uint32_t>, ks::PlanSet> bconv_cache;  // key: n_src, src ids, dst ids
 };

@@ -97,29 +97,29 @@ static void check_prime(uint64_t p) {
         const double r = reduce_lazy(acc, m);
         CHECK(fabs(r) <= lim && mod_i128((i128)(int64_t)r, p) == mod_i128(exact, p), "split3 conversion sum");
     }
-    // split2 (contexts whose moduli are all below 2^28): the two pieces add up, have the stated granularity and magnitude;
-    // with the centred factors cut at 14 bits, sixteen sources accumulate exactly and reduce to sum y_i f_i mod p
-    if (p < (1ull << 28)) {
+    // split2 (contexts whose moduli are all below 2^32): the two pieces add up, have the stated granularity and magnitude;
+    // with the centred factors cut at 16 bits, sixteen sources accumulate exactly and reduce to sum y_i f_i mod p
+    if (p < (1ull << 32)) {
         for (int rep = 0; rep < 20000; ++rep) {
             double acc = 0.0;
             i128 exact = 0;
             for (int i = 0; i < 16; ++i) {
-                uint64_t y = rnd() >> 36;  // below 2^28: a residue of some other modulus of such a context
-                if (rep % 9 == 0) y = (uint64_t[]){0, (1ull << 28) - 1, (1ull << 14) - 1, 1ull << 13, (1ull << 13) + 1, p - 1, 0xFFFE000ull, 0x2000ull}[(rep / 9 + i) % 8];
+                uint64_t y = rnd() >> 32;  // below 2^32: a residue of some other modulus of such a context
+                if (rep % 9 == 0) y = (uint64_t[]){0, (1ull << 32) - 1, (1ull << 16) - 1, 1ull << 15, (1ull << 15) + 1, p - 1, 0xFFFF8000ull, 0x8000ull}[(rep / 9 + i) % 8];
                 uint64_t f = rnd() % p;
                 if (rep % 5 == 0) f = (i & 1) ? p / 2 : p / 2 + 1;  // largest centred magnitudes
                 double y1, y0;
                 split2((double)y, y1, y0);
                 CHECK(y1 + y0 == (double)y, "split2 sum %llu", (unsigned long long)y);
-                CHECK(fmod(y1, 16384.0) == 0 && y1 >= 0 && y1 <= 268435456.0, "split2 y1 %llu", (unsigned long long)y);
-                CHECK(fabs(y0) <= 8192.0 && y0 == floor(y0), "split2 y0 %llu", (unsigned long long)y);
+                CHECK(fmod(y1, 65536.0) == 0 && y1 >= 0 && y1 <= 4294967296.0, "split2 y1 %llu", (unsigned long long)y);
+                CHECK(fabs(y0) <= 32768.0 && y0 == floor(y0), "split2 y0 %llu", (unsigned long long)y);
                 double fk[2];
                 for (int k = 0; k < 2; ++k) {
-                    const uint64_t s = (uint64_t)(((i128)f << (14 * k)) % p);
-                    fk[k] = ldexp(s > p / 2 ? -(double)(p - s) : (double)s, -14 * k);
+                    const uint64_t s = (uint64_t)(((i128)f << (16 * k)) % p);
+                    fk[k] = ldexp(s > p / 2 ? -(double)(p - s) : (double)s, -16 * k);
                 }
                 acc = __builtin_fma(y1, fk[1], __builtin_fma(y0, fk[0], acc));
-                CHECK(acc == floor(acc) && fabs(acc) < 70368744177664.0 /* 2^46 */, "split2 accumulator not an exact integer below 2^46");
+                CHECK(acc == floor(acc) && fabs(acc) < 9007199254740992.0, "split2 accumulator not an exact integer below 2^53");
                 exact += (i128)y * f;
             }
             const double r = reduce_lazy(acc, m);

@@ -169,7 +169,7 @@ def test_wide_moduli_are_refused():
 
 @pytest.mark.parametrize("targets,batch", [(0, 1), (1, 1), (2, 2), (3, 1), (4, 1), (0, 9)])
 def test_two_piece_conversion_at_the_benchmarked_shape(boot28, targets, batch):
-    """With every modulus below 2^28 the vector conversion kernel cuts a source residue into two pieces instead of
+    """With every modulus below 2^32 the vector conversion kernel cuts a source residue into two pieces instead of
     three.  All of its launch shapes (targets per workgroup; 0 = the library's choice) at the configuration 2 shape."""
     ell = 24
     d = boot28.uniform(2007, 1, (batch,), list(range(ell)))
@@ -185,15 +185,18 @@ def test_two_piece_conversion_at_the_benchmarked_shape(boot28, targets, batch):
     assert_equal(out, boot28.ref.keyswitch(host(d), host(evk), ell))
 
 
-def test_two_piece_conversion_extreme_residues(small28):
-    """Every source residue at modulus - 1 (the largest pieces) and at 0, through the vector conversion kernel."""
-    ell = 4
-    q = torch.tensor(small28.q, dtype=torch.int64, device="cuda").view(1, ell, 1)
-    evk = small28.uniform(2008, 2, (2, 2), list(range(6)))
-    for d in ((q - 1).expand(1, ell, small28.N).contiguous(), torch.zeros((1, ell, small28.N), dtype=torch.int64, device="cuda")):
-        out = torch.empty((1, 2, ell, small28.N), dtype=torch.int64, device="cuda")
-        K.ks_keyswitch(small28.ctx, d, ell, evk, out, workspace(small28.ctx, K.KS_OP_KEYSWITCH, ell, 1))
-        assert_equal(out, small28.ref.keyswitch(host(d), host(evk), ell))
+@pytest.mark.parametrize("which", ["small28", "small32"])
+def test_two_piece_conversion_extreme_residues(which, request):
+    """Every source residue at modulus - 1 (the largest pieces) and at 0, through the vector conversion kernel; with
+    32-bit moduli the exact sums come closest to the 2^53 they must stay below."""
+    st = request.getfixturevalue(which)
+    ell = st.L
+    q = torch.tensor(st.q, dtype=torch.int64, device="cuda").view(1, ell, 1)
+    evk = st.uniform(2008, 2, (st.ctx.dnum, 2), list(range(st.L + st.K)))
+    for d in ((q - 1).expand(1, ell, st.N).contiguous(), torch.zeros((1, ell, st.N), dtype=torch.int64, device="cuda")):
+        out = torch.empty((1, 2, ell, st.N), dtype=torch.int64, device="cuda")
+        K.ks_keyswitch(st.ctx, d, ell, evk, out, workspace(st.ctx, K.KS_OP_KEYSWITCH, ell, 1))
+        assert_equal(out, st.ref.keyswitch(host(d), host(evk), ell))
 
 
 @pytest.mark.parametrize("which,ell,batch,n1,n2", [("small28", 4, 2, 3, 2), ("small32", 3, 9, 2, 3), ("boot28", 24, 2, 3, 2)])
