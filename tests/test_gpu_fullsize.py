@@ -161,3 +161,87 @@ def test_cfg3_bsgs_full_size():
         want = st.ref.bsgs_linear_transform(host(ct[b])[None], baby, hb, giant, hg, hp, ell)
         assert_equal(out[b], want[0])
     assert _in_range(out[63].reshape(-1, ell, st.N), st.q)
+
+
+# ---- the same workloads with the paper's word size (28-bit primes, residues in 32-bit words), as `bench.py --word-size 32`
+# runs them.  Sampled items are recomputed by the reference; every other output is compared with what the 64-bit entry
+# point of the library gives on the same residues (itself checked against the reference above and in the other files).
+
+def _narrow(t):
+    return None if t is None else t.to(torch.int32)
+
+
+def _widen(t):
+    return t.to(torch.int64) & 0xFFFFFFFF
+
+
+def test_cfg4_batched_ntt_full_size_32bit_words():
+    cfg = dict(ks_inputs.CONFIGS[4], bits=28)
+    st = Setup(cfg["logN"], cfg["L"], 0, 1, bits=28)
+    ids = list(range(cfg["L"]))
+    x = st.uniform(cfg["seed"], 1, (cfg["batch"],), ids)
+    y = _narrow(x)
+    K.ntt_fwd_u32(st.ctx, y, ids)
+    for b in (0, cfg["batch"] - 1):              # every modulus, two whole polynomials
+        assert_equal(_widen(y[b]), st.ref.ntt_fwd(host(x[b])[None], ids)[0])
+    y64 = x.clone()
+    K.ntt_fwd(st.ctx, y64, ids)
+    assert torch.equal(_widen(y), y64)
+    K.ntt_inv_u32(st.ctx, y, ids)
+    assert torch.equal(_widen(y), x)
+
+
+def test_cfg3_rotations_full_size_32bit_words():
+    cfg = ks_inputs.CONFIGS[3]
+    st = Setup(cfg["logN"], cfg["L"], cfg["K"], cfg["dnum"], bits=28)
+    ell, B, n_rot, seed = cfg["L"], cfg["batch"], cfg["n_rot"], cfg["seed"]
+    ct = st.uniform(seed, 1, (B, 2), list(range(ell)))
+    keys = [st.uniform(seed, 10 + r, (cfg["dnum"], 2), list(range(ell + cfg["K"]))) for r in range(n_rot)]
+    pts = [st.uniform(seed, 100 + r, (), list(range(ell + cfg["K"]))) for r in range(n_rot)]
+    galois = ks_inputs.galois_elements(cfg["logN"], n_rot)
+    ct32, keys32, pts32 = _narrow(ct), [_narrow(k) for k in keys], [_narrow(w) for w in pts]
+    ws = workspace(st.ctx, K.KS_OP_ROTATE_HOISTED_U32, ell, B, n_rot)
+    # hoisted rotations: 12 GiB of results in 32-bit words
+    out32 = torch.empty((B, n_rot, 2, ell, st.N), dtype=torch.int32, device="cuda")
+    K.ks_rotate_hoisted_u32(st.ctx, ct32, ell, galois, keys32, out32, ws)
+    for b, r in [(0, 0), (17, 5), (63, 15)]:
+        want = st.ref.rotate_hoisted(host(ct[b])[None], [galois[r]], [host(keys[r])], ell)
+        assert_equal(_widen(out32[b, r]), want[0, 0])
+    out64 = torch.empty((8, n_rot, 2, ell, st.N), dtype=torch.int64, device="cuda")
+    for b0 in range(0, B, 8):                     # the 64-bit entry point on the same residues, a chunk at a time
+        K.ks_rotate_hoisted(st.ctx, ct[b0:b0 + 8], ell, galois, keys, out64, ws)
+        assert torch.equal(_widen(out32[b0:b0 + 8]), out64), b0
+    del out32, out64
+    # rotate-multiply-accumulate
+    mac32 = torch.empty((B, 2, ell, st.N), dtype=torch.int32, device="cuda")
+    K.ks_rotate_mac_hoisted_u32(st.ctx, ct32, ell, galois, keys32, pts32, mac32, ws)
+    hk, hp = [host(k) for k in keys], [host(w) for w in pts]
+    for b in (0, 63):
+        assert_equal(_widen(mac32[b]), st.ref.rotate_mac_hoisted(host(ct[b])[None], galois, hk, hp, ell)[0])
+    mac64 = torch.empty((B, 2, ell, st.N), dtype=torch.int64, device="cuda")
+    K.ks_rotate_mac_hoisted(st.ctx, ct, ell, galois, keys, pts, mac64, ws)
+    assert torch.equal(_widen(mac32), mac64)
+
+
+@pytest.mark.parametrize("merged", [False, True])
+def test_cfg5_hmult_full_size_32bit_words(merged):
+    cfg = ks_inputs.CONFIGS[5]
+    st = Setup(cfg["logN"], cfg["L"], cfg["K"], cfg["dnum"], bits=28)
+    ell, B, seed = cfg["L"], cfg["batch"], cfg["seed"]
+    cta = st.uniform(seed, 1, (B, 2), list(range(ell)))
+    ctb = st.uniform(seed, 2, (B, 2), list(range(ell)))
+    rlk = st.uniform(seed, 3, (cfg["dnum"], 2), list(range(ell + cfg["K"])))
+    ws = workspace(st.ctx, K.KS_OP_HMULT_RELIN_RESCALE, ell, B)
+    out32 = torch.empty((B, 2, ell - 1, st.N), dtype=torch.int32, device="cuda")
+    out64 = torch.empty((B, 2, ell - 1, st.N), dtype=torch.int64, device="cuda")
+    if merged:
+        K.hmult_relin_rescale_merged_u32(st.ctx, _narrow(cta), _narrow(ctb), ell, _narrow(rlk), out32, ws)
+        K.hmult_relin_rescale_merged(st.ctx, cta, ctb, ell, rlk, out64, ws)
+        ref = st.ref.hmult_relin_rescale_merged
+    else:
+        K.hmult_relin_rescale_u32(st.ctx, _narrow(cta), _narrow(ctb), ell, _narrow(rlk), out32, ws)
+        K.hmult_relin_rescale(st.ctx, cta, ctb, ell, rlk, out64, ws)
+        ref = st.ref.hmult_relin_rescale
+    for b in (0, 16, 255):
+        assert_equal(_widen(out32[b]), ref(host(cta[b])[None], host(ctb[b])[None], host(rlk), ell)[0])
+    assert torch.equal(_widen(out32), out64)
