@@ -41,8 +41,9 @@ KsWorkspace ks_ws_words(const ks_ctx* c, const Level& lv, uint32_t bc) {
 // Decompose and raise: d (evaluation domain, `bc` polynomials d_ps words apart) -> lifted [bc][ndig][E][N].
 // With finish_rows the raised limbs end as canonical evaluation-domain residues; without it they stop after the
 // column half of the forward transform (raw doubles) and the row half is left to the fused inner product.
+// lifted32 (with finish_rows): the finished digits go there as 32-bit words instead (same element layout).
 void mod_up(const ks_ctx* c, const Level& lv, const void* d, uint64_t d_ps, uint64_t* coeff, uint64_t* lifted, uint32_t bc,
-            bool finish_rows, hipStream_t s, bool d_words32 = false) {
+            bool finish_rows, hipStream_t s, bool d_words32 = false, uint32_t* lifted32 = nullptr) {
     const uint64_t N = c->N, coeff_ps = (uint64_t)lv.ell * N, lifted_ps = (uint64_t)lv.ndig * lv.E * N;
     launch_ntt_inv_rows(c, lv.q_map, XformIO{d, coeff, d_ps, coeff_ps, bc}, s, d_words32);
     // the column half also multiplies by N^-1 (D_j/q_i)^-1 and leaves canonical doubles for the conversion
@@ -57,7 +58,8 @@ void mod_up(const ks_ctx* c, const Level& lv, const void* d, uint64_t d_ps, uint
     }
     ops += lv.n_new * (3.0 + 4.0 * (c->logN - 8));
     launch_bconv_ntt_cols(c, lv.modup, lv.ell + lv.n_new, coeff, coeff_ps, lifted, lifted_ps, bc, s, ops);
-    if (finish_rows) launch_ntt_fwd_rows(c, lv.lifted_map, lifted, lifted_ps, bc, s);
+    if (finish_rows && lifted32) launch_ntt_fwd_rows_to(c, lv.lifted_map, lifted, lifted_ps, lifted32, lifted_ps, bc, s, true);
+    else if (finish_rows) launch_ntt_fwd_rows(c, lv.lifted_map, lifted, lifted_ps, bc, s);
 }
 
 // algorithmic fp64 work per coefficient of the ModDown conversion + column half (see mod_up)
@@ -93,15 +95,15 @@ extern "C" size_t ks_workspace_bytes(const ks_ctx* c, int op, uint32_t ell, uint
             if (n_rot == 0) return 0;
             // accumulators and converted limbs for a whole group of rotations
             words += (uint64_t)(std::min(n_rot, kRotGroup) - 1) * bc * (2 * lv.E + 2 * ell) * N;
-            // the chunk's ciphertexts widened to 64-bit words
-            if (op == KS_OP_ROTATE_HOISTED_U32) words += (uint64_t)bc * 2 * ell * N;
+            // the chunk's ciphertexts widened to 64-bit words, and the finished raised digits as 32-bit words
+            if (op == KS_OP_ROTATE_HOISTED_U32) words += (uint64_t)bc * 2 * ell * N + (ks_ws_words(c, lv, bc).lifted + 1) / 2;
             break;
         case KS_OP_BSGS:
         case KS_OP_BSGS_U32: {
             // second set of raised digits and accumulators (outer level), inner result [bc][2][ell]
             const KsWorkspace w = ks_ws_words(c, lv, bc);
             words += w.lifted + w.acc + (uint64_t)bc * 2 * ell * N;
-            if (op == KS_OP_BSGS_U32) words += (uint64_t)bc * 2 * ell * N;  // the chunk's ciphertexts widened to 64-bit words
+            if (op == KS_OP_BSGS_U32) words += (w.lifted + 1) / 2;  // the finished raised digits of the input as 32-bit words
             break;
         }
         case KS_OP_HMULT_RELIN_RESCALE:
@@ -305,20 +307,6 @@ extern "C" int ks_keyswitch_u32(const ks_ctx* c, const uint32_t* d, uint32_t ell
     return keyswitch_impl(c, d, ell, evk, out, batch, ws, ws_bytes, stream, true);
 }
 
-// Start of a chunk's ciphertexts as 64-bit words: the caller's own, or (words32) a widened copy at the head of the
-// workspace, whose remaining part starts at *rest.
-static const uint64_t* chunk_ct(const ks_ctx* c, const void* ct, uint32_t b0, uint32_t bc, uint64_t ct_bs, bool words32, void* ws,
-                                uint64_t** rest, hipStream_t s) {
-    if (!words32) {
-        *rest = static_cast<uint64_t*>(ws);
-        return static_cast<const uint64_t*>(ct) + (uint64_t)b0 * ct_bs;
-    }
-    uint64_t* wide = static_cast<uint64_t*>(ws);
-    launch_widen_u32(static_cast<const uint32_t*>(ct) + (uint64_t)b0 * ct_bs, wide, (uint64_t)bc * ct_bs, s);
-    *rest = wide + (uint64_t)bc * ct_bs;
-    return wide;
-}
-
 // ct, keys and out in 64-bit words, or all in 32-bit words (words32).
 static int rotate_hoisted_impl(const ks_ctx* c, const void* ct, uint32_t ell, const uint32_t* galois, const void* const* rot_keys,
                                uint32_t n_rot, void* out, uint32_t batch, void* ws, size_t ws_bytes, void* stream, bool words32) {
@@ -339,12 +327,25 @@ static int rotate_hoisted_impl(const ks_ctx* c, const void* ct, uint32_t ell, co
     for (uint32_t b0 = 0; b0 < batch; b0 += kChunk) {
         const uint32_t bc = std::min(batch - b0, kChunk);
         const KsWorkspace w = ks_ws_words(c, lv, bc);
-        uint64_t* coeff;
-        const uint64_t* c0 = chunk_ct(c, ct, b0, bc, ct_bs, words32, ws, &coeff, s);
+        // 32-bit words: the gather kernels read c1 and the finished raised digits as 32-bit words (half the gather traffic,
+        // which bounds them); only the last kernel's addend c0 is wanted in 64-bit words and comes from a widened copy
+        uint64_t* coeff = static_cast<uint64_t*>(ws);
+        const uint64_t* c0 = static_cast<const uint64_t*>(ct) + (uint64_t)b0 * ct_bs;
+        const void* c1 = c0 + (uint64_t)ell * N;
+        uint32_t* lifted32 = nullptr;
+        if (words32) {
+            const uint32_t* ct32 = static_cast<const uint32_t*>(ct) + (uint64_t)b0 * ct_bs;
+            uint64_t* wide = coeff;
+            launch_widen_u32(ct32, wide, (uint64_t)bc * ct_bs, s);
+            lifted32 = reinterpret_cast<uint32_t*>(wide + (uint64_t)bc * ct_bs);
+            coeff = wide + (uint64_t)bc * ct_bs + (w.lifted + 1) / 2;
+            c0 = wide;
+            c1 = ct32 + (uint64_t)ell * N;
+        }
         uint64_t* lifted = coeff + w.coeff;
         uint64_t* acc = lifted + w.lifted;
-        const uint64_t* c1 = c0 + (uint64_t)ell * N;
-        mod_up(c, lv, c1, ct_bs, coeff, lifted, bc, true, s);   // finished once, shared by every rotation
+        mod_up(c, lv, c1, ct_bs, coeff, lifted, bc, true, s, words32, lifted32);   // finished once, shared by every rotation
+        const void* digits = words32 ? static_cast<const void*>(lifted32) : static_cast<const void*>(lifted);
         // Rotations go in groups: one gather launch forms the accumulators of the whole group (the raised digits then come
         // from memory once per group), the inverse transform and the conversion run over the group as one batch, and only
         // the last kernel, which adds sigma_g(c0) through a rotation's own permutation, runs per rotation.
@@ -359,7 +360,7 @@ static int rotate_hoisted_impl(const ks_ctx* c, const void* ct, uint32_t ell, co
                 rot.key[r] = rot_keys[r0 + r];
                 rot.pt[r] = nullptr;
             }
-            launch_inner_product(c, lv, c1, ct_bs, lifted, rot, acc, bc, s, words32);
+            launch_inner_product(c, lv, c1, ct_bs, digits, rot, acc, bc, s, words32, words32);
             const uint32_t polys = 2 * rot.n * bc;
             launch_ntt_inv_rows(c, lv.special_map, XformIO{acc, acc, acc_ps, acc_ps, polys}, s);
             launch_ntt_inv_cols(c, lv.special_map, acc, acc_ps, polys, c->d_moddown_scale, true, true, s);
@@ -400,9 +401,9 @@ static int check_mac_rotations(const ks_ctx* c, const uint32_t* galois, const vo
 }
 
 // u (+)= sum_r pt_r * rot_{g_r}(ct) for all n rotations, in launches of kMacRotations
-static void rotate_mac_all(const ks_ctx* c, const Level& lv, const uint64_t* ct, uint64_t ct_bs, const uint64_t* lifted,
+static void rotate_mac_all(const ks_ctx* c, const Level& lv, const void* ct, uint64_t ct_bs, const void* lifted,
                            const uint32_t* galois, const void* const* keys, const void* const* pts, uint32_t n, uint64_t* u,
-                           uint32_t bc, bool accumulate, hipStream_t s, bool key_words32 = false) {
+                           uint32_t bc, bool accumulate, hipStream_t s, bool key_words32 = false, bool src_words32 = false) {
     for (uint32_t r0 = 0; r0 < n; r0 += kMacRotations) {
         MacRotations rot;
         rot.n = std::min<uint32_t>(n - r0, kMacRotations);
@@ -411,7 +412,7 @@ static void rotate_mac_all(const ks_ctx* c, const Level& lv, const uint64_t* ct,
             rot.key[r] = keys[r0 + r];
             rot.pt[r] = pts ? pts[r0 + r] : nullptr;
         }
-        launch_rotate_mac(c, lv, ct, ct_bs, lifted, rot, u, bc, accumulate || r0 != 0, s, key_words32);
+        launch_rotate_mac(c, lv, ct, ct_bs, lifted, rot, u, bc, accumulate || r0 != 0, s, key_words32, src_words32);
     }
 }
 
@@ -431,13 +432,16 @@ static int rotate_mac_impl(const ks_ctx* c, const void* ct, uint32_t ell, const 
     for (uint32_t b0 = 0; b0 < batch; b0 += kChunk) {
         const uint32_t bc = std::min(batch - b0, kChunk);
         const KsWorkspace w = ks_ws_words(c, lv, bc);
-        uint64_t* coeff;
-        const uint64_t* c0 = chunk_ct(c, ct, b0, bc, ct_bs, words32, ws, &coeff, s);
+        // 32-bit words: the ciphertext and the finished raised digits are gathered as 32-bit words
+        const char* c0 = static_cast<const char*>(ct) + (uint64_t)b0 * ct_bs * word;
+        uint32_t* lifted32 = words32 ? static_cast<uint32_t*>(ws) : nullptr;
+        uint64_t* coeff = static_cast<uint64_t*>(ws) + (words32 ? (w.lifted + 1) / 2 : 0);
         uint64_t* lifted = coeff + w.coeff;
         uint64_t* acc = lifted + w.lifted;
         uint64_t* conv = acc + w.acc;
-        mod_up(c, lv, c0 + (uint64_t)ell * N, ct_bs, coeff, lifted, bc, true, s);   // finished once, shared by every rotation
-        rotate_mac_all(c, lv, c0, ct_bs, lifted, galois, rot_keys, pts, n_rot, acc, bc, false, s, words32);
+        mod_up(c, lv, c0 + (uint64_t)ell * N * word, ct_bs, coeff, lifted, bc, true, s, words32, lifted32);   // finished once, shared by every rotation
+        rotate_mac_all(c, lv, c0, ct_bs, words32 ? static_cast<const void*>(lifted32) : lifted, galois, rot_keys, pts, n_rot, acc, bc,
+                       false, s, words32, words32);
         mod_down(c, lv, acc, conv, static_cast<char*>(out) + (uint64_t)b0 * ct_bs * word, ct_bs, nullptr, 0, 0, 1, bc, false, s, words32);
     }
     return finish(words32 ? "ks_rotate_mac_hoisted_u32" : "ks_rotate_mac_hoisted");
@@ -475,17 +479,21 @@ static int bsgs_impl(const ks_ctx* c, const void* ct, uint32_t ell, const uint32
     for (uint32_t b0 = 0; b0 < batch; b0 += kChunk) {
         const uint32_t bc = std::min(batch - b0, kChunk);
         const KsWorkspace w = ks_ws_words(c, lv, bc);
-        uint64_t* coeff;
-        const uint64_t* c0 = chunk_ct(c, ct, b0, bc, ct_bs, words32, ws, &coeff, s);
+        // 32-bit words: the input ciphertext and its finished raised digits are gathered as 32-bit words at the inner level;
+        // the inner results and their raised digits stay 64-bit
+        const char* c0 = static_cast<const char*>(ct) + (uint64_t)b0 * ct_bs * word;
+        uint32_t* lifted32 = words32 ? static_cast<uint32_t*>(ws) : nullptr;
+        uint64_t* coeff = static_cast<uint64_t*>(ws) + (words32 ? (w.lifted + 1) / 2 : 0);
         uint64_t* lifted = coeff + w.coeff;          // raised digits of c1, shared by every baby step of every giant step
         uint64_t* acc = lifted + w.lifted;           // inner sum of the current giant step
         uint64_t* conv = acc + w.acc;
         uint64_t* lifted_v = conv + w.conv;          // raised digits of the current inner result
         uint64_t* acc_outer = lifted_v + w.lifted;   // outer sum over the giant steps
         uint64_t* v = acc_outer + w.acc;             // [bc][2][ell][N] inner result of the current giant step (64-bit words)
-        mod_up(c, lv, c0 + (uint64_t)ell * N, ct_bs, coeff, lifted, bc, true, s);
+        mod_up(c, lv, c0 + (uint64_t)ell * N * word, ct_bs, coeff, lifted, bc, true, s, words32, lifted32);
+        const void* digits = words32 ? static_cast<const void*>(lifted32) : static_cast<const void*>(lifted);
         for (uint32_t g = 0; g < n2; ++g) {
-            rotate_mac_all(c, lv, c0, ct_bs, lifted, baby_galois, bkeys, ptv + (size_t)g * n1, n1, acc, bc, false, s, words32);
+            rotate_mac_all(c, lv, c0, ct_bs, digits, baby_galois, bkeys, ptv + (size_t)g * n1, n1, acc, bc, false, s, words32, words32);
             mod_down(c, lv, acc, conv, v, ct_bs, nullptr, 0, 0, 1, bc, false, s);
             if (giant_galois[g] != 1) mod_up(c, lv, v + (uint64_t)ell * N, ct_bs, coeff, lifted_v, bc, true, s);
             rotate_mac_all(c, lv, v, ct_bs, lifted_v, giant_galois + g, gkeys + g, nullptr, 1, acc_outer, bc, g != 0, s, words32);

@@ -13,10 +13,12 @@ constexpr int kBatchGroup = 8;  // batch items sharing one read of the key slots
 // the launch, so the raised digits it gathers from are read from memory once per launch and from cache afterwards.
 // Branch-free like rotate_mac_kernel below: the digit count is a template parameter and a short last group recomputes
 // its last ciphertext, so every load of a rotation is issued before the first product.
-template <int NDIG, typename WK>
+// WK: word type of the keys; WS: word type of the gathered sources d and lifted (32-bit words halve the gather traffic,
+// which is what bounds these kernels: every rotation re-reads all raised digits of the chunk).
+template <int NDIG, typename WK, typename WS>
 __global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restrict__ mods, DigitRanges dg, uint32_t ell, uint32_t E,
-                                                            uint32_t L, uint32_t M, uint32_t logN, const uint64_t* __restrict__ d,
-                                                            uint64_t d_ps, const uint64_t* __restrict__ lifted, MacRotations rot,
+                                                            uint32_t L, uint32_t M, uint32_t logN, const WS* __restrict__ d,
+                                                            uint64_t d_ps, const WS* __restrict__ lifted, MacRotations rot,
                                                             uint64_t* __restrict__ acc, uint32_t batch) {
     const uint32_t N = 1u << logN;
     const uint32_t pos = blockIdx.y;
@@ -24,7 +26,7 @@ __global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restric
     const Mod m = mods[mid];
     const uint32_t n = blockIdx.x * 256 + threadIdx.x;
     const uint32_t b_lo = blockIdx.z * kBatchGroup;
-    const uint64_t* srcp[kBatchGroup][NDIG];
+    const WS* srcp[kBatchGroup][NDIG];
 #pragma unroll
     for (int bi = 0; bi < kBatchGroup; ++bi) {
         const uint32_t b = min(b_lo + bi, batch - 1);
@@ -39,7 +41,7 @@ __global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restric
         const uint32_t sn = galois_source_slot(n, rot.galois[r], logN);
         const WK* key = static_cast<const WK*>(rot.key[r]) + (uint64_t)mid * N + n;
         WK kraw[NDIG][2];
-        uint64_t xraw[kBatchGroup][NDIG];
+        WS xraw[kBatchGroup][NDIG];
 #pragma unroll
         for (int j = 0; j < NDIG; ++j) {
             kraw[j][0] = key[(uint64_t)(j * 2 + 0) * M * N];
@@ -56,7 +58,7 @@ __global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restric
             double a0 = 0.0, a1 = 0.0;
 #pragma unroll
             for (int j = 0; j < NDIG; ++j) {
-                const double x = u64_to_f64(xraw[bi][j]);
+                const double x = word_to_f64<WS>(xraw[bi][j]);
                 a0 += mulmod_lazy(x, word_to_f64<WK>(kraw[j][0]), m);
                 a1 += mulmod_lazy(x, word_to_f64<WK>(kraw[j][1]), m);
             }
@@ -66,8 +68,8 @@ __global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restric
     }
 }
 
-void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, const uint64_t* lifted,
-                          const MacRotations& rot, uint64_t* acc, uint32_t batch, hipStream_t s, bool key_words32) {
+void launch_inner_product(const ks_ctx* c, const Level& lv, const void* d, uint64_t d_ps, const void* lifted,
+                          const MacRotations& rot, uint64_t* acc, uint32_t batch, hipStream_t s, bool key_words32, bool src_words32) {
     if (batch == 0 || rot.n == 0) return;
     DigitRanges dg;
     dg.ndig = lv.ndig;
@@ -79,16 +81,16 @@ void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, u
     const dim3 grid(c->N / 256, lv.E, groups), block(256);
     // reads: every raised digit limb per ciphertext once per launch, each rotation's key once per group; writes: both
     // accumulators of every rotation
-    const double wk = key_words32 ? 0.5 : 1.0;
+    const double wk = key_words32 ? 0.5 : 1.0, wsrc = src_words32 ? 0.5 : 1.0;
     ProfScope ps("inner_product",
-                 ((double)batch * lv.ndig * lv.E + (double)rot.n * (wk * 2.0 * lv.ndig * lv.E * groups + 2.0 * lv.E * batch)) * c->N * 8.0, s);
-#define KS_LAUNCH_IP(ND)                                                                                                                  \
-    if (key_words32)                                                                                                                      \
-        hipLaunchKernelGGL((inner_product_kernel<ND, uint32_t>), grid, block, 0, s, c->d_mod, dg, lv.ell, lv.E, c->L, c->M, c->logN, d, d_ps, \
-                           lifted, rot, acc, batch);                                                                                     \
-    else                                                                                                                                  \
-        hipLaunchKernelGGL((inner_product_kernel<ND, uint64_t>), grid, block, 0, s, c->d_mod, dg, lv.ell, lv.E, c->L, c->M, c->logN, d, d_ps, \
-                           lifted, rot, acc, batch)
+                 (wsrc * batch * lv.ndig * lv.E + (double)rot.n * (wk * 2.0 * lv.ndig * lv.E * groups + 2.0 * lv.E * batch)) * c->N * 8.0, s);
+#define KS_LAUNCH_IP_W(ND, WKT, WST)                                                                                               \
+    hipLaunchKernelGGL((inner_product_kernel<ND, WKT, WST>), grid, block, 0, s, c->d_mod, dg, lv.ell, lv.E, c->L, c->M, c->logN,   \
+                       static_cast<const WST*>(d), d_ps, static_cast<const WST*>(lifted), rot, acc, batch)
+#define KS_LAUNCH_IP(ND)                                                        \
+    if (key_words32 && src_words32) KS_LAUNCH_IP_W(ND, uint32_t, uint32_t);     \
+    else if (key_words32) KS_LAUNCH_IP_W(ND, uint32_t, uint64_t);               \
+    else KS_LAUNCH_IP_W(ND, uint64_t, uint64_t)
     switch (lv.ndig) {
         case 1: KS_LAUNCH_IP(1); break;
         case 2: KS_LAUNCH_IP(2); break;
@@ -100,6 +102,7 @@ void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, u
         default: KS_LAUNCH_IP(8); break;
     }
 #undef KS_LAUNCH_IP
+#undef KS_LAUNCH_IP_W
 }
 
 // Rotate-multiply-accumulate on the extended basis (inner sum of a baby-step giant-step transform with the division by P
@@ -109,11 +112,11 @@ void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, u
 // Branch-free within a rotation on purpose (digit count as a template parameter, a short last group recomputes its last
 // ciphertext, special limbs read a c0 limb they multiply by zero): every load of a rotation is then issued before the
 // first product.  Galois element 1 is the unrotated ciphertext (P (c0, c1), no key read).
-template <int NDIG, typename WK>
+template <int NDIG, typename WK, typename WS>
 __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__ mods, const double* __restrict__ Pmod, DigitRanges dg,
                                                          uint32_t ell, uint32_t E, uint32_t L, uint32_t M, uint32_t logN,
-                                                         const uint64_t* __restrict__ ct, uint64_t ct_bs,
-                                                         const uint64_t* __restrict__ lifted, MacRotations rot,
+                                                         const WS* __restrict__ ct, uint64_t ct_bs,
+                                                         const WS* __restrict__ lifted, MacRotations rot,
                                                          const uint64_t* __restrict__ one, uint64_t* __restrict__ u, uint32_t batch,
                                                          int accumulate) {
     const uint32_t N = 1u << logN;
@@ -125,13 +128,13 @@ __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__
     const uint32_t n = blockIdx.x * 256 + threadIdx.x;
     const uint32_t b_lo = blockIdx.z * kBatchGroup;
     // per ciphertext of the group: where its c0 limb and its NDIG source limbs of this position start
-    const uint64_t* c0p[kBatchGroup];
-    const uint64_t* srcp[kBatchGroup][NDIG];
+    const WS* c0p[kBatchGroup];
+    const WS* srcp[kBatchGroup][NDIG];
     uint64_t* up[kBatchGroup];
 #pragma unroll
     for (int bi = 0; bi < kBatchGroup; ++bi) {
         const uint32_t b = min(b_lo + bi, batch - 1);
-        const uint64_t* cb = ct + (uint64_t)b * ct_bs;
+        const WS* cb = ct + (uint64_t)b * ct_bs;
         c0p[bi] = cb + (uint64_t)c0_limb * N;
 #pragma unroll
         for (int j = 0; j < NDIG; ++j) {
@@ -153,7 +156,7 @@ __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__
         // (the table holds the 64-bit word 1, whose low half is the 32-bit word 1)
         const WK* wp = rot.pt[r] ? static_cast<const WK*>(rot.pt[r]) + (uint64_t)mid * N + n : reinterpret_cast<const WK*>(one);
         if (rot.galois[r] == 1) {  // uniform: the unrotated ciphertext, P (c0, c1), no key
-            uint64_t c0raw[kBatchGroup], c1raw[kBatchGroup];
+            WS c0raw[kBatchGroup], c1raw[kBatchGroup];
             const WK wraw = *wp;
 #pragma unroll
             for (int bi = 0; bi < kBatchGroup; ++bi) {
@@ -163,15 +166,15 @@ __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__
             const double w = word_to_f64<WK>(wraw);
 #pragma unroll
             for (int bi = 0; bi < kBatchGroup; ++bi) {
-                u0[bi] += mulmod_lazy(mulmod_lazy(u64_to_f64(c0raw[bi]), pm, m), w, m);
-                u1[bi] += mulmod_lazy(mulmod_lazy(u64_to_f64(c1raw[bi]), pm, m), w, m);
+                u0[bi] += mulmod_lazy(mulmod_lazy(word_to_f64<WS>(c0raw[bi]), pm, m), w, m);
+                u1[bi] += mulmod_lazy(mulmod_lazy(word_to_f64<WS>(c1raw[bi]), pm, m), w, m);
             }
             continue;
         }
         const uint32_t sn = galois_source_slot(n, rot.galois[r], logN);
         const WK* key = static_cast<const WK*>(rot.key[r]) + (uint64_t)mid * N + n;
         WK kraw[NDIG][2];
-        uint64_t xraw[kBatchGroup][NDIG], craw[kBatchGroup];
+        WS xraw[kBatchGroup][NDIG], craw[kBatchGroup];
 #pragma unroll
         for (int j = 0; j < NDIG; ++j) {
             kraw[j][0] = key[(uint64_t)(j * 2 + 0) * M * N];
@@ -187,10 +190,10 @@ __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__
         const double w = word_to_f64<WK>(wraw);
 #pragma unroll
         for (int bi = 0; bi < kBatchGroup; ++bi) {
-            double t0 = mulmod_lazy(u64_to_f64(craw[bi]), pm, m), t1 = 0.0;
+            double t0 = mulmod_lazy(word_to_f64<WS>(craw[bi]), pm, m), t1 = 0.0;
 #pragma unroll
             for (int j = 0; j < NDIG; ++j) {
-                const double x = u64_to_f64(xraw[bi][j]);
+                const double x = word_to_f64<WS>(xraw[bi][j]);
                 t0 += mulmod_lazy(x, word_to_f64<WK>(kraw[j][0]), m);
                 t1 += mulmod_lazy(x, word_to_f64<WK>(kraw[j][1]), m);
             }
@@ -206,8 +209,9 @@ __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__
     }
 }
 
-void launch_rotate_mac(const ks_ctx* c, const Level& lv, const uint64_t* ct, uint64_t ct_bs, const uint64_t* lifted,
-                       const MacRotations& rot, uint64_t* u, uint32_t batch, bool accumulate, hipStream_t s, bool key_words32) {
+void launch_rotate_mac(const ks_ctx* c, const Level& lv, const void* ct, uint64_t ct_bs, const void* lifted,
+                       const MacRotations& rot, uint64_t* u, uint32_t batch, bool accumulate, hipStream_t s, bool key_words32,
+                       bool src_words32) {
     if (batch == 0 || rot.n == 0) return;
     DigitRanges dg;
     dg.ndig = lv.ndig;
@@ -220,17 +224,17 @@ void launch_rotate_mac(const ks_ctx* c, const Level& lv, const uint64_t* ct, uin
     // Algorithmic traffic: the raised digits and c0 of a ciphertext once (the rotations of a launch re-read them through
     // the gather; those re-reads are meant to come from cache), key and plaintext of every rotation once per group, both
     // sums written once.  Algorithmic work per slot, ciphertext and rotation: 2 NDIG + 3 modular products.
-    const double reads = (double)batch * (lv.ndig * lv.E + lv.ell) +
+    const double reads = (src_words32 ? 0.5 : 1.0) * batch * (lv.ndig * lv.E + lv.ell) +
                          (key_words32 ? 0.5 : 1.0) * (double)rot.n * groups * (2.0 * lv.ndig + 1.0) * lv.E;
     ProfScope ps("rotate_mac", (reads + (double)batch * 2 * lv.E * (accumulate ? 2 : 1)) * c->N * 8.0, s,
                  (double)rot.n * batch * lv.E * c->N * (7.0 * (2 * lv.ndig + 3)));
-#define KS_LAUNCH_MAC(ND)                                                                                                                  \
-    if (key_words32)                                                                                                                       \
-        hipLaunchKernelGGL((rotate_mac_kernel<ND, uint32_t>), grid, block, 0, s, c->d_mod, c->d_Pmod, dg, lv.ell, lv.E, c->L, c->M, c->logN, ct, \
-                           ct_bs, lifted, rot, c->d_one, u, batch, accumulate ? 1 : 0);                                                   \
-    else                                                                                                                                   \
-        hipLaunchKernelGGL((rotate_mac_kernel<ND, uint64_t>), grid, block, 0, s, c->d_mod, c->d_Pmod, dg, lv.ell, lv.E, c->L, c->M, c->logN, ct, \
-                           ct_bs, lifted, rot, c->d_one, u, batch, accumulate ? 1 : 0)
+#define KS_LAUNCH_MAC_W(ND, WKT, WST)                                                                                                  \
+    hipLaunchKernelGGL((rotate_mac_kernel<ND, WKT, WST>), grid, block, 0, s, c->d_mod, c->d_Pmod, dg, lv.ell, lv.E, c->L, c->M, c->logN, \
+                       static_cast<const WST*>(ct), ct_bs, static_cast<const WST*>(lifted), rot, c->d_one, u, batch, accumulate ? 1 : 0)
+#define KS_LAUNCH_MAC(ND)                                                       \
+    if (key_words32 && src_words32) KS_LAUNCH_MAC_W(ND, uint32_t, uint32_t);    \
+    else if (key_words32) KS_LAUNCH_MAC_W(ND, uint32_t, uint64_t);              \
+    else KS_LAUNCH_MAC_W(ND, uint64_t, uint64_t)
     switch (lv.ndig) {
         case 1: KS_LAUNCH_MAC(1); break;
         case 2: KS_LAUNCH_MAC(2); break;
@@ -242,6 +246,7 @@ void launch_rotate_mac(const ks_ctx* c, const Level& lv, const uint64_t* ct, uin
         default: KS_LAUNCH_MAC(8); break;
     }
 #undef KS_LAUNCH_MAC
+#undef KS_LAUNCH_MAC_W
 }
 
 // (b1, a1) x (b2, a2) -> d0 = b1 b2, d1 = a1 b2 + a2 b1, d2 = a1 a2

@@ -178,6 +178,9 @@ void launch_ntt_u32(const ks_ctx* c, const LimbMap& map, uint32_t* data, uint64_
 // The two halves of each transform on their own (the fused pipeline replaces some halves by fused kernels).
 void launch_ntt_fwd_cols(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipStream_t s);
 void launch_ntt_fwd_rows(const ks_ctx* c, const LimbMap& map, uint64_t* data, uint64_t ps_words, uint32_t n_polys, hipStream_t s);
+// the same out of place, the canonical residues written as 64- or 32-bit words (strides in words)
+void launch_ntt_fwd_rows_to(const ks_ctx* c, const LimbMap& map, const uint64_t* in, uint64_t in_ps, void* out, uint64_t out_ps,
+                            uint32_t n_polys, hipStream_t s, bool out_words32);
 // in_words32: io.in holds 32-bit words (strides still count elements)
 void launch_ntt_inv_rows(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipStream_t s, bool in_words32 = false);
 // scale_tab: multiplier applied with the final reduction, indexed by the limb's position in `map` (scale_by_idx)
@@ -237,15 +240,18 @@ struct MacRotations {
 };
 // acc[r][b][c][pos] = sum_j sigma_{g_r}(src_j)[pos] * key_r[j][c][ext_id(pos)] for every rotation r of `rot` (pt unused);
 // src_j[pos] = d[b][pos] when pos lies in digit j, otherwise lifted[b][j][pos].
-// key_words32: keys (and plaintexts) hold one residue per 32-bit word; d, ct and the raised digits are always 64-bit.
-void launch_inner_product(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_poly_stride, const uint64_t* lifted,
-                          const MacRotations& rot, uint64_t* acc, uint32_t batch, hipStream_t s, bool key_words32 = false);
+// key_words32: keys (and plaintexts) hold one residue per 32-bit word; src_words32: so do d / ct and the raised digits
+// (strides in words either way; src_words32 implies key_words32).
+void launch_inner_product(const ks_ctx* c, const Level& lv, const void* d, uint64_t d_poly_stride, const void* lifted,
+                          const MacRotations& rot, uint64_t* acc, uint32_t batch, hipStream_t s, bool key_words32 = false,
+                          bool src_words32 = false);
 
 // u[b][c][pos] (+)= sum_r pt_r[pos] * (sum_j sigma_r(src_j)[pos] key_r[j][c][pos] + [c = 0][pos < ell] P sigma_r(c0)[pos]);
 // ct: [b][2][ell][N] (c0, c1), lifted: finished raised digits of c1.  accumulate: add to what u already holds.
 // galois[r] == 1: the term is P (c0, c1) and key[r] is not read; pt[r] == nullptr: the constant 1.
-void launch_rotate_mac(const ks_ctx* c, const Level& lv, const uint64_t* ct, uint64_t ct_bs, const uint64_t* lifted,
-                       const MacRotations& rot, uint64_t* u, uint32_t batch, bool accumulate, hipStream_t s, bool key_words32 = false);
+void launch_rotate_mac(const ks_ctx* c, const Level& lv, const void* ct, uint64_t ct_bs, const void* lifted,
+                       const MacRotations& rot, uint64_t* u, uint32_t batch, bool accumulate, hipStream_t s, bool key_words32 = false,
+                       bool src_words32 = false);
 
 // The key-switch chain behind ks_keyswitch / ks_keyswitch_u32 (argument checks included); ws is any device buffer of
 // at least ks_workspace_bytes(KS_OP_KEYSWITCH) bytes, whose contents need no initialisation.

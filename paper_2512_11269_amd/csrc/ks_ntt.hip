@@ -48,26 +48,28 @@ __global__ __launch_bounds__((TC << LOG_R) / 16) void ntt_fwd_cols(const double*
     for (int k = 0; k < 16; ++k) store_f64(L.out + col_row_grouped<LOG_R>(r0, k) * 256 + col, v[k]);
 }
 
-// forward, rows: raw doubles in, canonical u64 out, in place.  One wavefront = four rows.
-template <int LOG_R>
+// forward, rows: raw doubles in, canonical residues out (64- or 32-bit words), in place or not.  One wavefront = four rows.
+template <int LOG_R, typename WO>
 __global__ __launch_bounds__(64) void ntt_fwd_rows(TwTables tw, const Mod* __restrict__ mods, LimbMap map,
-                                                   uint64_t* data, uint64_t ps) {
+                                                   const uint64_t* in, WO* out, uint64_t in_ps, uint64_t out_ps) {
     constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R, GROUPS = R / 4;
     __shared__ double lds[4 * kRowPitch];
     const uint32_t tid = threadIdx.x;
     const uint32_t li = blockIdx.x / GROUPS, rg = blockIdx.x - li * GROUPS;
-    const LimbRef L = locate(map, li, data, data, ps, ps, N);
-    const Mod m = mods[L.mod_id];
+    const uint32_t poly = li / map.n, idx = li - poly * map.n, mod_id = map.mod[idx];
+    const uint64_t off = (uint64_t)map.off[idx] * N;
+    const Mod m = mods[mod_id];
     const uint32_t j0 = tid & 15, rr = tid >> 4, row = rg * 4 + rr;
-    uint64_t* p = L.out + row * 256;
+    const uint64_t* ip = in + poly * in_ps + off + row * 256;
+    WO* op = out + poly * out_ps + off + row * 256;
     double v[16];
     PassTwiddles t;
 #pragma unroll
-    for (int k = 0; k < 16; ++k) v[k] = load_f64(p + j0 + 16 * k);
-    load_row_twiddles(t, tw, L.mod_id, N, R + row, j0, m);
+    for (int k = 0; k < 16; ++k) v[k] = load_f64(ip + j0 + 16 * k);
+    load_row_twiddles(t, tw, mod_id, N, R + row, j0, m);
     row_fwd_core(v, t, j0, lds + rr * kRowPitch, m);
 #pragma unroll
-    for (int k = 0; k < 16; ++k) p[j0 + 16 * k] = f64_to_u64(canon(reduce_lazy(v[k], m), m));
+    for (int k = 0; k < 16; ++k) op[j0 + 16 * k] = f64_to_word<WO>(canon(reduce_lazy(v[k], m), m));
 }
 
 // inverse, rows first: canonical residues in (64- or 32-bit words), raw doubles out (|x| <= 0.501 p).
@@ -196,14 +198,24 @@ void launch_ntt_fwd_cols(const ks_ctx* c, const LimbMap& map, const XformIO& io,
 #undef KS_LAUNCH
 }
 
-void launch_ntt_fwd_rows(const ks_ctx* c, const LimbMap& map, uint64_t* data, uint64_t ps_words, uint32_t n_polys, hipStream_t s) {
+void launch_ntt_fwd_rows_to(const ks_ctx* c, const LimbMap& map, const uint64_t* in, uint64_t in_ps, void* out, uint64_t out_ps,
+                            uint32_t n_polys, hipStream_t s, bool out_words32) {
     const uint32_t limbs = map.n * n_polys;
     if (limbs == 0) return;
-    ProfScope ps("ntt_fwd_rows", 2.0 * limbs * c->N * 8.0, s);
-#define KS_LAUNCH(LOGR) \
-    hipLaunchKernelGGL(ntt_fwd_rows<LOGR>, dim3(limbs << (LOGR - 2)), dim3(64), 0, s, c->tw_fwd, c->d_mod, map, data, ps_words)
+    ProfScope ps("ntt_fwd_rows", (out_words32 ? 1.5 : 2.0) * limbs * c->N * 8.0, s);
+#define KS_LAUNCH(LOGR)                                                                                                              \
+    if (out_words32)                                                                                                                 \
+        hipLaunchKernelGGL((ntt_fwd_rows<LOGR, uint32_t>), dim3(limbs << (LOGR - 2)), dim3(64), 0, s, c->tw_fwd, c->d_mod, map, in,  \
+                           static_cast<uint32_t*>(out), in_ps, out_ps);                                                              \
+    else                                                                                                                             \
+        hipLaunchKernelGGL((ntt_fwd_rows<LOGR, uint64_t>), dim3(limbs << (LOGR - 2)), dim3(64), 0, s, c->tw_fwd, c->d_mod, map, in,  \
+                           static_cast<uint64_t*>(out), in_ps, out_ps)
     KS_FOR_LOG_R(c->logN, KS_LAUNCH)
 #undef KS_LAUNCH
+}
+
+void launch_ntt_fwd_rows(const ks_ctx* c, const LimbMap& map, uint64_t* data, uint64_t ps_words, uint32_t n_polys, hipStream_t s) {
+    launch_ntt_fwd_rows_to(c, map, data, ps_words, data, ps_words, n_polys, s, false);
 }
 
 // Polynomials per launch pair of a two-pass transform: the second pass of a group should find what the first pass wrote
