@@ -39,7 +39,7 @@ MEASURED_TRAFFIC_BYTES: dict = {
     ("keyswitch", "rows_inner_product"): 187897144,
     ("keyswitch", "rows_moddown_finish"): 77505428,
     ("keyswitch", "bconv_mfma_ntt_cols"): 53444702,  # mean of the ModUp and the ModDown launch
-    ("keyswitch", "ntt_inv_rows"): 27075285,
+    ("keyswitch", "ntt_inv_rows"): 27089621,
     ("keyswitch", "ntt_inv_cols"): 21380728,         # mean of the 24-limb and the 16-limb launch
 }
 

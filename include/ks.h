@@ -218,7 +218,8 @@ int hmult_relin_rescale_merged(const ks_ctx* ctx, const uint64_t* cta, const uin
  * ciphertexts, keys, plaintexts, results; for the transforms and the conversion the data itself -- holding one
  * residue per uint32_t in the same layout.  Arithmetic and results are identical; the traffic of those tensors
  * halves.  Intermediate values in the workspace stay 8 bytes wide, except that the rotation calls also keep the finished
- * raised digits as 32-bit words (their kernels are bound by re-reading them).  Every call returns KS_EINVAL unless every modulus
+ * raised digits as 32-bit words (their kernels are bound by re-reading them; the 64-bit rotation calls keep them as a
+ * 32-bit word plus a byte).  Every call returns KS_EINVAL unless every modulus
  * of the context is below 2^32.  Workspace: the operation code of the 64-bit call, except that the two rotation calls
  * take KS_OP_ROTATE_HOISTED_U32 and the BSGS transform KS_OP_BSGS_U32 (room for the 32-bit raised digits and, for
  * ks_rotate_hoisted_u32, a widened copy of a chunk's ciphertexts).

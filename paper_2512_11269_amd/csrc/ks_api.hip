@@ -39,11 +39,10 @@ KsWorkspace ks_ws_words(const ks_ctx* c, const Level& lv, uint32_t bc) {
 }
 
 // Decompose and raise: d (evaluation domain, `bc` polynomials d_ps words apart) -> lifted [bc][ndig][E][N].
-// With finish_rows the raised limbs end as canonical evaluation-domain residues; without it they stop after the
-// column half of the forward transform (raw doubles) and the row half is left to the fused inner product.
-// lifted32 (with finish_rows): the finished digits go there as 32-bit words instead (same element layout).
+// The raised limbs stop after the column half of the forward transform (raw doubles); the row half is left to the
+// fused inner product, or to mod_up_for_gather below.
 void mod_up(const ks_ctx* c, const Level& lv, const void* d, uint64_t d_ps, uint64_t* coeff, uint64_t* lifted, uint32_t bc,
-            bool finish_rows, hipStream_t s, bool d_words32 = false, uint32_t* lifted32 = nullptr) {
+            hipStream_t s, bool d_words32 = false) {
     const uint64_t N = c->N, coeff_ps = (uint64_t)lv.ell * N, lifted_ps = (uint64_t)lv.ndig * lv.E * N;
     launch_ntt_inv_rows(c, lv.q_map, XformIO{d, coeff, d_ps, coeff_ps, bc}, s, d_words32);
     // the column half also multiplies by N^-1 (D_j/q_i)^-1 and leaves canonical doubles for the conversion
@@ -58,8 +57,27 @@ void mod_up(const ks_ctx* c, const Level& lv, const void* d, uint64_t d_ps, uint
     }
     ops += lv.n_new * (3.0 + 4.0 * (c->logN - 8));
     launch_bconv_ntt_cols(c, lv.modup, lv.ell + lv.n_new, coeff, coeff_ps, lifted, lifted_ps, bc, s, ops);
-    if (finish_rows && lifted32) launch_ntt_fwd_rows_to(c, lv.lifted_map, lifted, lifted_ps, lifted32, lifted_ps, bc, s, true);
-    else if (finish_rows) launch_ntt_fwd_rows(c, lv.lifted_map, lifted, lifted_ps, bc, s);
+}
+
+// Words of workspace the gathers' sources of a chunk take: the finished raised digits as 32-bit words (words32), or as
+// 32-bit low words plus high bytes, own limbs included (64-bit operands).
+static uint64_t gather_words(const KsWorkspace& w, bool words32) { return (w.lifted + 1) / 2 + (words32 ? 0 : (w.lifted + 7) / 8); }
+
+// mod_up finished for the rotation gathers: the raised digits end as canonical evaluation-domain residues in `region`
+// (gather_words() words), in the form the gathers read.  `lifted` is only scratch here.
+static GatherSources mod_up_for_gather(const ks_ctx* c, const Level& lv, const void* d, uint64_t d_ps, uint64_t* coeff,
+                                       uint64_t* lifted, uint64_t* region, uint32_t bc, hipStream_t s, bool words32) {
+    mod_up(c, lv, d, d_ps, coeff, lifted, bc, s, words32);
+    const uint64_t lifted_ps = (uint64_t)lv.ndig * lv.E * c->N, lifted_words = (uint64_t)bc * lifted_ps;
+    uint32_t* lo = reinterpret_cast<uint32_t*>(region);
+    if (words32) {
+        launch_ntt_fwd_rows_to(c, lv.lifted_map, lifted, lifted_ps, lo, lifted_ps, bc, s, true);
+        return GatherSources{lo, nullptr, static_cast<const uint32_t*>(d), d_ps};
+    }
+    const PackedDigits pk{lo, reinterpret_cast<uint8_t*>(region + (lifted_words + 1) / 2)};
+    launch_ntt_fwd_rows_packed(c, lv.lifted_map, lifted, lifted_ps, pk, bc, s);
+    launch_pack_own_limbs(c, lv, static_cast<const uint64_t*>(d), d_ps, pk, bc, s);
+    return GatherSources{pk.lo, pk.hi, nullptr, 0};
 }
 
 // algorithmic fp64 work per coefficient of the ModDown conversion + column half (see mod_up)
@@ -95,15 +113,16 @@ extern "C" size_t ks_workspace_bytes(const ks_ctx* c, int op, uint32_t ell, uint
             if (n_rot == 0) return 0;
             // accumulators and converted limbs for a whole group of rotations
             words += (uint64_t)(std::min(n_rot, kRotGroup) - 1) * bc * (2 * lv.E + 2 * ell) * N;
-            // the chunk's ciphertexts widened to 64-bit words, and the finished raised digits as 32-bit words
-            if (op == KS_OP_ROTATE_HOISTED_U32) words += (uint64_t)bc * 2 * ell * N + (ks_ws_words(c, lv, bc).lifted + 1) / 2;
+            // the gathers' sources; 32-bit words: also the chunk's ciphertexts widened to 64-bit words
+            words += gather_words(ks_ws_words(c, lv, bc), op == KS_OP_ROTATE_HOISTED_U32);
+            if (op == KS_OP_ROTATE_HOISTED_U32) words += (uint64_t)bc * 2 * ell * N;
             break;
         case KS_OP_BSGS:
         case KS_OP_BSGS_U32: {
-            // second set of raised digits and accumulators (outer level), inner result [bc][2][ell]
+            // accumulators of the outer level, inner result [bc][2][ell], the gathers' sources of both levels (the
+            // inner results are 64-bit words either way)
             const KsWorkspace w = ks_ws_words(c, lv, bc);
-            words += w.lifted + w.acc + (uint64_t)bc * 2 * ell * N;
-            if (op == KS_OP_BSGS_U32) words += (w.lifted + 1) / 2;  // the finished raised digits of the input as 32-bit words
+            words += w.acc + (uint64_t)bc * 2 * ell * N + gather_words(w, op == KS_OP_BSGS_U32) + gather_words(w, false);
             break;
         }
         case KS_OP_HMULT_RELIN_RESCALE:
@@ -290,7 +309,7 @@ int ks::keyswitch_impl(const ks_ctx* c, const void* d, uint32_t ell, const void*
         uint64_t* acc = lifted + w.lifted;
         uint64_t* conv = acc + w.acc;
         const char* dc = static_cast<const char*>(d) + (uint64_t)b0 * d_ps * word;
-        mod_up(c, lv, dc, d_ps, coeff, lifted, bc, false, s, words32);
+        mod_up(c, lv, dc, d_ps, coeff, lifted, bc, s, words32);
         launch_rows_inner_product(c, lv, dc, d_ps, lifted, evk, acc, bc, s, words32, words32);
         mod_down(c, lv, acc, conv, static_cast<char*>(out) + (uint64_t)b0 * out_bs * word, out_bs, nullptr, 0, 0, 1, bc, true, s, words32);
     }
@@ -327,25 +346,25 @@ static int rotate_hoisted_impl(const ks_ctx* c, const void* ct, uint32_t ell, co
     for (uint32_t b0 = 0; b0 < batch; b0 += kChunk) {
         const uint32_t bc = std::min(batch - b0, kChunk);
         const KsWorkspace w = ks_ws_words(c, lv, bc);
-        // 32-bit words: the gather kernels read c1 and the finished raised digits as 32-bit words (half the gather traffic,
-        // which bounds them); only the last kernel's addend c0 is wanted in 64-bit words and comes from a widened copy
-        uint64_t* coeff = static_cast<uint64_t*>(ws);
+        // The gathers read c1 and its finished raised digits in a compact form (32-bit words, or 32-bit low words plus
+        // high bytes for 64-bit operands: their traffic bounds the gather kernels); with 32-bit words the last kernel's
+        // addend c0 is wanted in 64-bit words and comes from a widened copy.
+        uint64_t* region = static_cast<uint64_t*>(ws);
+        uint64_t* coeff = region + gather_words(w, words32);
         const uint64_t* c0 = static_cast<const uint64_t*>(ct) + (uint64_t)b0 * ct_bs;
         const void* c1 = c0 + (uint64_t)ell * N;
-        uint32_t* lifted32 = nullptr;
         if (words32) {
             const uint32_t* ct32 = static_cast<const uint32_t*>(ct) + (uint64_t)b0 * ct_bs;
             uint64_t* wide = coeff;
             launch_widen_u32(ct32, wide, (uint64_t)bc * ct_bs, s);
-            lifted32 = reinterpret_cast<uint32_t*>(wide + (uint64_t)bc * ct_bs);
-            coeff = wide + (uint64_t)bc * ct_bs + (w.lifted + 1) / 2;
+            coeff = wide + (uint64_t)bc * ct_bs;
             c0 = wide;
             c1 = ct32 + (uint64_t)ell * N;
         }
         uint64_t* lifted = coeff + w.coeff;
         uint64_t* acc = lifted + w.lifted;
-        mod_up(c, lv, c1, ct_bs, coeff, lifted, bc, true, s, words32, lifted32);   // finished once, shared by every rotation
-        const void* digits = words32 ? static_cast<const void*>(lifted32) : static_cast<const void*>(lifted);
+        // finished once, shared by every rotation
+        const GatherSources digits = mod_up_for_gather(c, lv, c1, ct_bs, coeff, lifted, region, bc, s, words32);
         // Rotations go in groups: one gather launch forms the accumulators of the whole group (the raised digits then come
         // from memory once per group), the inverse transform and the conversion run over the group as one batch, and only
         // the last kernel, which adds sigma_g(c0) through a rotation's own permutation, runs per rotation.
@@ -360,7 +379,7 @@ static int rotate_hoisted_impl(const ks_ctx* c, const void* ct, uint32_t ell, co
                 rot.key[r] = rot_keys[r0 + r];
                 rot.pt[r] = nullptr;
             }
-            launch_inner_product(c, lv, c1, ct_bs, digits, rot, acc, bc, s, words32, words32);
+            launch_inner_product(c, lv, digits, rot, acc, bc, s, words32);
             const uint32_t polys = 2 * rot.n * bc;
             launch_ntt_inv_rows(c, lv.special_map, XformIO{acc, acc, acc_ps, acc_ps, polys}, s);
             launch_ntt_inv_cols(c, lv.special_map, acc, acc_ps, polys, c->d_moddown_scale, true, true, s);
@@ -401,9 +420,9 @@ static int check_mac_rotations(const ks_ctx* c, const uint32_t* galois, const vo
 }
 
 // u (+)= sum_r pt_r * rot_{g_r}(ct) for all n rotations, in launches of kMacRotations
-static void rotate_mac_all(const ks_ctx* c, const Level& lv, const void* ct, uint64_t ct_bs, const void* lifted,
+static void rotate_mac_all(const ks_ctx* c, const Level& lv, const void* ct, uint64_t ct_bs, const GatherSources& src,
                            const uint32_t* galois, const void* const* keys, const void* const* pts, uint32_t n, uint64_t* u,
-                           uint32_t bc, bool accumulate, hipStream_t s, bool key_words32 = false, bool src_words32 = false) {
+                           uint32_t bc, bool accumulate, hipStream_t s, bool key_words32 = false) {
     for (uint32_t r0 = 0; r0 < n; r0 += kMacRotations) {
         MacRotations rot;
         rot.n = std::min<uint32_t>(n - r0, kMacRotations);
@@ -412,7 +431,7 @@ static void rotate_mac_all(const ks_ctx* c, const Level& lv, const void* ct, uin
             rot.key[r] = keys[r0 + r];
             rot.pt[r] = pts ? pts[r0 + r] : nullptr;
         }
-        launch_rotate_mac(c, lv, ct, ct_bs, lifted, rot, u, bc, accumulate || r0 != 0, s, key_words32, src_words32);
+        launch_rotate_mac(c, lv, ct, ct_bs, src, rot, u, bc, accumulate || r0 != 0, s, key_words32);
     }
 }
 
@@ -432,16 +451,16 @@ static int rotate_mac_impl(const ks_ctx* c, const void* ct, uint32_t ell, const 
     for (uint32_t b0 = 0; b0 < batch; b0 += kChunk) {
         const uint32_t bc = std::min(batch - b0, kChunk);
         const KsWorkspace w = ks_ws_words(c, lv, bc);
-        // 32-bit words: the ciphertext and the finished raised digits are gathered as 32-bit words
+        // the gathers read c1 and its finished raised digits in a compact form (see rotate_hoisted_impl)
         const char* c0 = static_cast<const char*>(ct) + (uint64_t)b0 * ct_bs * word;
-        uint32_t* lifted32 = words32 ? static_cast<uint32_t*>(ws) : nullptr;
-        uint64_t* coeff = static_cast<uint64_t*>(ws) + (words32 ? (w.lifted + 1) / 2 : 0);
+        uint64_t* region = static_cast<uint64_t*>(ws);
+        uint64_t* coeff = region + gather_words(w, words32);
         uint64_t* lifted = coeff + w.coeff;
         uint64_t* acc = lifted + w.lifted;
         uint64_t* conv = acc + w.acc;
-        mod_up(c, lv, c0 + (uint64_t)ell * N * word, ct_bs, coeff, lifted, bc, true, s, words32, lifted32);   // finished once, shared by every rotation
-        rotate_mac_all(c, lv, c0, ct_bs, words32 ? static_cast<const void*>(lifted32) : lifted, galois, rot_keys, pts, n_rot, acc, bc,
-                       false, s, words32, words32);
+        // finished once, shared by every rotation
+        const GatherSources digits = mod_up_for_gather(c, lv, c0 + (uint64_t)ell * N * word, ct_bs, coeff, lifted, region, bc, s, words32);
+        rotate_mac_all(c, lv, c0, ct_bs, digits, galois, rot_keys, pts, n_rot, acc, bc, false, s, words32);
         mod_down(c, lv, acc, conv, static_cast<char*>(out) + (uint64_t)b0 * ct_bs * word, ct_bs, nullptr, 0, 0, 1, bc, false, s, words32);
     }
     return finish(words32 ? "ks_rotate_mac_hoisted_u32" : "ks_rotate_mac_hoisted");
@@ -479,24 +498,26 @@ static int bsgs_impl(const ks_ctx* c, const void* ct, uint32_t ell, const uint32
     for (uint32_t b0 = 0; b0 < batch; b0 += kChunk) {
         const uint32_t bc = std::min(batch - b0, kChunk);
         const KsWorkspace w = ks_ws_words(c, lv, bc);
-        // 32-bit words: the input ciphertext and its finished raised digits are gathered as 32-bit words at the inner level;
-        // the inner results and their raised digits stay 64-bit
+        // The gathers of the inner level read the input ciphertext and its finished raised digits in a compact form (see
+        // rotate_hoisted_impl); the inner results are 64-bit words either way, so the outer level reads the packed form.
         const char* c0 = static_cast<const char*>(ct) + (uint64_t)b0 * ct_bs * word;
-        uint32_t* lifted32 = words32 ? static_cast<uint32_t*>(ws) : nullptr;
-        uint64_t* coeff = static_cast<uint64_t*>(ws) + (words32 ? (w.lifted + 1) / 2 : 0);
-        uint64_t* lifted = coeff + w.coeff;          // raised digits of c1, shared by every baby step of every giant step
+        uint64_t* region = static_cast<uint64_t*>(ws);   // sources of the inner level, shared by every baby step of every giant step
+        uint64_t* region_v = region + gather_words(w, words32);   // sources of the outer level: the current inner result
+        uint64_t* coeff = region_v + gather_words(w, false);
+        uint64_t* lifted = coeff + w.coeff;          // scratch of a ModUp
         uint64_t* acc = lifted + w.lifted;           // inner sum of the current giant step
         uint64_t* conv = acc + w.acc;
-        uint64_t* lifted_v = conv + w.conv;          // raised digits of the current inner result
-        uint64_t* acc_outer = lifted_v + w.lifted;   // outer sum over the giant steps
+        uint64_t* acc_outer = conv + w.conv;         // outer sum over the giant steps
         uint64_t* v = acc_outer + w.acc;             // [bc][2][ell][N] inner result of the current giant step (64-bit words)
-        mod_up(c, lv, c0 + (uint64_t)ell * N * word, ct_bs, coeff, lifted, bc, true, s, words32, lifted32);
-        const void* digits = words32 ? static_cast<const void*>(lifted32) : static_cast<const void*>(lifted);
+        const GatherSources digits = mod_up_for_gather(c, lv, c0 + (uint64_t)ell * N * word, ct_bs, coeff, lifted, region, bc, s, words32);
+        GatherSources digits_v{};
         for (uint32_t g = 0; g < n2; ++g) {
-            rotate_mac_all(c, lv, c0, ct_bs, digits, baby_galois, bkeys, ptv + (size_t)g * n1, n1, acc, bc, false, s, words32, words32);
+            rotate_mac_all(c, lv, c0, ct_bs, digits, baby_galois, bkeys, ptv + (size_t)g * n1, n1, acc, bc, false, s, words32);
             mod_down(c, lv, acc, conv, v, ct_bs, nullptr, 0, 0, 1, bc, false, s);
-            if (giant_galois[g] != 1) mod_up(c, lv, v + (uint64_t)ell * N, ct_bs, coeff, lifted_v, bc, true, s);
-            rotate_mac_all(c, lv, v, ct_bs, lifted_v, giant_galois + g, gkeys + g, nullptr, 1, acc_outer, bc, g != 0, s, words32);
+            if (giant_galois[g] != 1) digits_v = mod_up_for_gather(c, lv, v + (uint64_t)ell * N, ct_bs, coeff, lifted, region_v, bc, s, false);
+            // Galois element 1 gathers nothing; the packed form still says that v holds 64-bit words
+            else digits_v = GatherSources{reinterpret_cast<const uint32_t*>(region_v), reinterpret_cast<const uint8_t*>(region_v), nullptr, 0};
+            rotate_mac_all(c, lv, v, ct_bs, digits_v, giant_galois + g, gkeys + g, nullptr, 1, acc_outer, bc, g != 0, s, words32);
         }
         mod_down(c, lv, acc_outer, conv, static_cast<char*>(out) + (uint64_t)b0 * ct_bs * word, ct_bs, nullptr, 0, 0, 1, bc, false, s,
                  words32);
@@ -571,7 +592,7 @@ static int hmult_impl(const ks_ctx* c, const void* cta, const void* ctb, uint32_
         launch_tensor_product(c, static_cast<const char*>(cta) + (uint64_t)b0 * ct_bs * word,
                               static_cast<const char*>(ctb) + (uint64_t)b0 * ct_bs * word, td, ell, bc, s, words32);
         const uint64_t* d2 = td + 2ull * ell * N;
-        mod_up(c, lv, d2, td_bs, coeff, lifted, bc, false, s);
+        mod_up(c, lv, d2, td_bs, coeff, lifted, bc, s);
         launch_rows_inner_product(c, lv, d2, td_bs, lifted, rlk, acc, bc, s, false, words32);
         if (merged) {
             mod_down_merged(c, lv, acc, conv, oc, out_bs, td, td_bs, bc, s, words32);

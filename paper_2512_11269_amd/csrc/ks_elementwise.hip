@@ -8,17 +8,52 @@ namespace ks {
 
 constexpr int kBatchGroup = 8;  // batch items sharing one read of the key slots
 
+// What a gather reads for one (ciphertext, digit) at this limb position.  PACKED: bits 0..31 of the residue from a 32-bit
+// word array and the bits above from a byte array (5 bytes a residue); otherwise one 32-bit word.  These kernels are
+// bound by the gather traffic (every rotation re-reads all raised digits of the chunk), so the bytes per residue are
+// what sets their speed.
+template <bool PACKED>
+struct SrcPtr {
+    const uint32_t* lo;
+    const uint8_t* hi;
+};
+template <bool PACKED>
+struct SrcRaw {
+    uint32_t lo, hi;
+};
+template <bool PACKED>
+__device__ __forceinline__ SrcRaw<PACKED> src_load(const SrcPtr<PACKED>& p, uint32_t sn) {
+    SrcRaw<PACKED> r;
+    r.lo = p.lo[sn];
+    r.hi = PACKED ? p.hi[sn] : 0u;
+    return r;
+}
+template <bool PACKED>
+__device__ __forceinline__ double src_f64(const SrcRaw<PACKED>& r) {
+    return PACKED ? u64_to_f64((uint64_t)r.hi << 32 | r.lo) : (double)r.lo;
+}
+// Start of the sources of (ciphertext b, digit j) at limb position pos.  Packed bundles hold every (digit, position)
+// slot; with 32-bit words the digit's own limbs are read from the polynomial itself.
+template <bool PACKED>
+__device__ __forceinline__ SrcPtr<PACKED> src_ptr(const GatherSources& g, const DigitRanges& dg, uint32_t ndig, uint32_t E, uint32_t N,
+                                                  uint32_t b, uint32_t j, uint32_t pos) {
+    const uint64_t e = (((uint64_t)b * ndig + j) * E + pos) * N;
+    const bool own = !PACKED && pos >= dg.lo[j] && pos < dg.hi[j];  // uniform
+    SrcPtr<PACKED> p;
+    p.lo = own ? g.own + (uint64_t)b * g.own_ps + (uint64_t)pos * N : g.lo + e;
+    p.hi = PACKED ? g.hi + e : nullptr;
+    return p;
+}
+
 // Inner products through the sigma_g gather for a group of hoisted rotations: acc[r][b][c][pos] = sum_j sigma_{g_r}(src_j)[pos]
 // key_r[j][c][pos].  One thread owns one slot of one limb position for a group of ciphertexts and walks the rotations of
 // the launch, so the raised digits it gathers from are read from memory once per launch and from cache afterwards.
 // Branch-free like rotate_mac_kernel below: the digit count is a template parameter and a short last group recomputes
 // its last ciphertext, so every load of a rotation is issued before the first product.
-// WK: word type of the keys; WS: word type of the gathered sources d and lifted (32-bit words halve the gather traffic,
-// which is what bounds these kernels: every rotation re-reads all raised digits of the chunk).
-template <int NDIG, typename WK, typename WS>
+// WK: word type of the keys; PACKED: format of the gathered sources (see SrcPtr).
+template <int NDIG, typename WK, bool PACKED>
 __global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restrict__ mods, DigitRanges dg, uint32_t ell, uint32_t E,
-                                                            uint32_t L, uint32_t M, uint32_t logN, const WS* __restrict__ d,
-                                                            uint64_t d_ps, const WS* __restrict__ lifted, MacRotations rot,
+                                                            uint32_t L, uint32_t M, uint32_t logN, GatherSources src, MacRotations rot,
                                                             uint64_t* __restrict__ acc, uint32_t batch) {
     const uint32_t N = 1u << logN;
     const uint32_t pos = blockIdx.y;
@@ -26,22 +61,19 @@ __global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restric
     const Mod m = mods[mid];
     const uint32_t n = blockIdx.x * 256 + threadIdx.x;
     const uint32_t b_lo = blockIdx.z * kBatchGroup;
-    const WS* srcp[kBatchGroup][NDIG];
+    SrcPtr<PACKED> srcp[kBatchGroup][NDIG];
 #pragma unroll
     for (int bi = 0; bi < kBatchGroup; ++bi) {
         const uint32_t b = min(b_lo + bi, batch - 1);
 #pragma unroll
-        for (int j = 0; j < NDIG; ++j) {
-            const bool own = pos >= dg.lo[j] && pos < dg.hi[j];  // uniform
-            srcp[bi][j] = own ? d + (uint64_t)b * d_ps + (uint64_t)pos * N : lifted + (((uint64_t)b * NDIG + j) * E + pos) * N;
-        }
+        for (int j = 0; j < NDIG; ++j) srcp[bi][j] = src_ptr<PACKED>(src, dg, NDIG, E, N, b, j, pos);
     }
 #pragma unroll 1
     for (uint32_t r = 0; r < rot.n; ++r) {
         const uint32_t sn = galois_source_slot(n, rot.galois[r], logN);
         const WK* key = static_cast<const WK*>(rot.key[r]) + (uint64_t)mid * N + n;
         WK kraw[NDIG][2];
-        WS xraw[kBatchGroup][NDIG];
+        SrcRaw<PACKED> xraw[kBatchGroup][NDIG];
 #pragma unroll
         for (int j = 0; j < NDIG; ++j) {
             kraw[j][0] = key[(uint64_t)(j * 2 + 0) * M * N];
@@ -50,7 +82,7 @@ __global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restric
 #pragma unroll
         for (int bi = 0; bi < kBatchGroup; ++bi)
 #pragma unroll
-            for (int j = 0; j < NDIG; ++j) xraw[bi][j] = srcp[bi][j][sn];
+            for (int j = 0; j < NDIG; ++j) xraw[bi][j] = src_load<PACKED>(srcp[bi][j], sn);
         uint64_t* ar = acc + (uint64_t)r * batch * 2 * E * N;
 #pragma unroll
         for (int bi = 0; bi < kBatchGroup; ++bi) {
@@ -58,7 +90,7 @@ __global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restric
             double a0 = 0.0, a1 = 0.0;
 #pragma unroll
             for (int j = 0; j < NDIG; ++j) {
-                const double x = word_to_f64<WS>(xraw[bi][j]);
+                const double x = src_f64<PACKED>(xraw[bi][j]);
                 a0 += mulmod_lazy(x, word_to_f64<WK>(kraw[j][0]), m);
                 a1 += mulmod_lazy(x, word_to_f64<WK>(kraw[j][1]), m);
             }
@@ -68,29 +100,38 @@ __global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restric
     }
 }
 
-void launch_inner_product(const ks_ctx* c, const Level& lv, const void* d, uint64_t d_ps, const void* lifted,
-                          const MacRotations& rot, uint64_t* acc, uint32_t batch, hipStream_t s, bool key_words32, bool src_words32) {
-    if (batch == 0 || rot.n == 0) return;
+static DigitRanges digit_ranges(const Level& lv) {
     DigitRanges dg;
     dg.ndig = lv.ndig;
     for (uint32_t j = 0; j < kMaxDigits; ++j) {
         dg.lo[j] = j < lv.ndig ? lv.digit_lo[j] : 0;
         dg.hi[j] = j < lv.ndig ? lv.digit_hi[j] : 0;
     }
+    return dg;
+}
+
+// bytes a gathered source residue takes
+static double src_bytes(const GatherSources& g) { return g.hi ? 5.0 : 4.0; }
+
+void launch_inner_product(const ks_ctx* c, const Level& lv, const GatherSources& src, const MacRotations& rot, uint64_t* acc,
+                          uint32_t batch, hipStream_t s, bool key_words32) {
+    if (batch == 0 || rot.n == 0) return;
+    const DigitRanges dg = digit_ranges(lv);
     const uint32_t groups = (batch + kBatchGroup - 1) / kBatchGroup;
     const dim3 grid(c->N / 256, lv.E, groups), block(256);
     // reads: every raised digit limb per ciphertext once per launch, each rotation's key once per group; writes: both
     // accumulators of every rotation
-    const double wk = key_words32 ? 0.5 : 1.0, wsrc = src_words32 ? 0.5 : 1.0;
+    const double wk = key_words32 ? 4.0 : 8.0;
     ProfScope ps("inner_product",
-                 (wsrc * batch * lv.ndig * lv.E + (double)rot.n * (wk * 2.0 * lv.ndig * lv.E * groups + 2.0 * lv.E * batch)) * c->N * 8.0, s);
-#define KS_LAUNCH_IP_W(ND, WKT, WST)                                                                                               \
-    hipLaunchKernelGGL((inner_product_kernel<ND, WKT, WST>), grid, block, 0, s, c->d_mod, dg, lv.ell, lv.E, c->L, c->M, c->logN,   \
-                       static_cast<const WST*>(d), d_ps, static_cast<const WST*>(lifted), rot, acc, batch)
-#define KS_LAUNCH_IP(ND)                                                        \
-    if (key_words32 && src_words32) KS_LAUNCH_IP_W(ND, uint32_t, uint32_t);     \
-    else if (key_words32) KS_LAUNCH_IP_W(ND, uint32_t, uint64_t);               \
-    else KS_LAUNCH_IP_W(ND, uint64_t, uint64_t)
+                 (src_bytes(src) * batch * lv.ndig * lv.E + (double)rot.n * (wk * 2.0 * lv.ndig * lv.E * groups + 16.0 * lv.E * batch)) * c->N,
+                 s);
+#define KS_LAUNCH_IP_W(ND, WKT, PK)                                                                                                \
+    hipLaunchKernelGGL((inner_product_kernel<ND, WKT, PK>), grid, block, 0, s, c->d_mod, dg, lv.ell, lv.E, c->L, c->M, c->logN, src, \
+                       rot, acc, batch)
+#define KS_LAUNCH_IP(ND)                                                \
+    if (!src.hi) KS_LAUNCH_IP_W(ND, uint32_t, false);                   \
+    else if (key_words32) KS_LAUNCH_IP_W(ND, uint32_t, true);           \
+    else KS_LAUNCH_IP_W(ND, uint64_t, true)
     switch (lv.ndig) {
         case 1: KS_LAUNCH_IP(1); break;
         case 2: KS_LAUNCH_IP(2); break;
@@ -112,13 +153,15 @@ void launch_inner_product(const ks_ctx* c, const Level& lv, const void* d, uint6
 // Branch-free within a rotation on purpose (digit count as a template parameter, a short last group recomputes its last
 // ciphertext, special limbs read a c0 limb they multiply by zero): every load of a rotation is then issued before the
 // first product.  Galois element 1 is the unrotated ciphertext (P (c0, c1), no key read).
-template <int NDIG, typename WK, typename WS>
+// WC: word type of the ciphertext ct (64-bit with packed sources, 32-bit with 32-bit sources).
+template <int NDIG, typename WK, bool PACKED>
 __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__ mods, const double* __restrict__ Pmod, DigitRanges dg,
                                                          uint32_t ell, uint32_t E, uint32_t L, uint32_t M, uint32_t logN,
-                                                         const WS* __restrict__ ct, uint64_t ct_bs,
-                                                         const WS* __restrict__ lifted, MacRotations rot,
-                                                         const uint64_t* __restrict__ one, uint64_t* __restrict__ u, uint32_t batch,
-                                                         int accumulate) {
+                                                         const void* __restrict__ ct_, uint64_t ct_bs, GatherSources src,
+                                                         MacRotations rot, const uint64_t* __restrict__ one,
+                                                         uint64_t* __restrict__ u, uint32_t batch, int accumulate) {
+    using WC = std::conditional_t<PACKED, uint64_t, uint32_t>;
+    const WC* ct = static_cast<const WC*>(ct_);
     const uint32_t N = 1u << logN;
     const uint32_t pos = blockIdx.y;
     const uint32_t mid = pos < ell ? pos : L + (pos - ell);
@@ -128,19 +171,15 @@ __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__
     const uint32_t n = blockIdx.x * 256 + threadIdx.x;
     const uint32_t b_lo = blockIdx.z * kBatchGroup;
     // per ciphertext of the group: where its c0 limb and its NDIG source limbs of this position start
-    const WS* c0p[kBatchGroup];
-    const WS* srcp[kBatchGroup][NDIG];
+    const WC* c0p[kBatchGroup];
+    SrcPtr<PACKED> srcp[kBatchGroup][NDIG];
     uint64_t* up[kBatchGroup];
 #pragma unroll
     for (int bi = 0; bi < kBatchGroup; ++bi) {
         const uint32_t b = min(b_lo + bi, batch - 1);
-        const WS* cb = ct + (uint64_t)b * ct_bs;
-        c0p[bi] = cb + (uint64_t)c0_limb * N;
+        c0p[bi] = ct + (uint64_t)b * ct_bs + (uint64_t)c0_limb * N;
 #pragma unroll
-        for (int j = 0; j < NDIG; ++j) {
-            const bool own = pos >= dg.lo[j] && pos < dg.hi[j];  // uniform
-            srcp[bi][j] = own ? cb + ((uint64_t)ell + pos) * N : lifted + (((uint64_t)b * NDIG + j) * E + pos) * N;
-        }
+        for (int j = 0; j < NDIG; ++j) srcp[bi][j] = src_ptr<PACKED>(src, dg, NDIG, E, N, b, j, pos);
         up[bi] = u + (((uint64_t)b * 2) * E + pos) * N + n;
     }
     double u0[kBatchGroup], u1[kBatchGroup];
@@ -156,25 +195,26 @@ __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__
         // (the table holds the 64-bit word 1, whose low half is the 32-bit word 1)
         const WK* wp = rot.pt[r] ? static_cast<const WK*>(rot.pt[r]) + (uint64_t)mid * N + n : reinterpret_cast<const WK*>(one);
         if (rot.galois[r] == 1) {  // uniform: the unrotated ciphertext, P (c0, c1), no key
-            WS c0raw[kBatchGroup], c1raw[kBatchGroup];
+            WC c0raw[kBatchGroup], c1raw[kBatchGroup];
             const WK wraw = *wp;
 #pragma unroll
             for (int bi = 0; bi < kBatchGroup; ++bi) {
                 c0raw[bi] = c0p[bi][n];
                 c1raw[bi] = c0p[bi][(uint64_t)ell * N + n];
             }
-            const double w = word_to_f64<WK>(wraw);
+            const double pw = mulmod_lazy(pm, word_to_f64<WK>(wraw), m);
 #pragma unroll
             for (int bi = 0; bi < kBatchGroup; ++bi) {
-                u0[bi] += mulmod_lazy(mulmod_lazy(word_to_f64<WS>(c0raw[bi]), pm, m), w, m);
-                u1[bi] += mulmod_lazy(mulmod_lazy(word_to_f64<WS>(c1raw[bi]), pm, m), w, m);
+                u0[bi] += mulmod_lazy(word_to_f64<WC>(c0raw[bi]), pw, m);
+                u1[bi] += mulmod_lazy(word_to_f64<WC>(c1raw[bi]), pw, m);
             }
             continue;
         }
         const uint32_t sn = galois_source_slot(n, rot.galois[r], logN);
         const WK* key = static_cast<const WK*>(rot.key[r]) + (uint64_t)mid * N + n;
         WK kraw[NDIG][2];
-        WS xraw[kBatchGroup][NDIG], craw[kBatchGroup];
+        SrcRaw<PACKED> xraw[kBatchGroup][NDIG];
+        WC craw[kBatchGroup];
 #pragma unroll
         for (int j = 0; j < NDIG; ++j) {
             kraw[j][0] = key[(uint64_t)(j * 2 + 0) * M * N];
@@ -184,22 +224,29 @@ __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__
 #pragma unroll
         for (int bi = 0; bi < kBatchGroup; ++bi) {
 #pragma unroll
-            for (int j = 0; j < NDIG; ++j) xraw[bi][j] = srcp[bi][j][sn];
+            for (int j = 0; j < NDIG; ++j) xraw[bi][j] = src_load<PACKED>(srcp[bi][j], sn);
             craw[bi] = c0p[bi][sn];
         }
-        const double w = word_to_f64<WK>(wraw);
+        // the plaintext slot is folded into the key slots and into P once per rotation, not multiplied per ciphertext
+        const double w = word_to_f64<WK>(wraw), pw = mulmod_lazy(pm, w, m);
+        double kw[NDIG][2];
+#pragma unroll
+        for (int j = 0; j < NDIG; ++j) {
+            kw[j][0] = mulmod_lazy(word_to_f64<WK>(kraw[j][0]), w, m);
+            kw[j][1] = mulmod_lazy(word_to_f64<WK>(kraw[j][1]), w, m);
+        }
 #pragma unroll
         for (int bi = 0; bi < kBatchGroup; ++bi) {
-            double t0 = mulmod_lazy(word_to_f64<WS>(craw[bi]), pm, m), t1 = 0.0;
+            double t0 = mulmod_lazy(word_to_f64<WC>(craw[bi]), pw, m), t1 = 0.0;
 #pragma unroll
             for (int j = 0; j < NDIG; ++j) {
-                const double x = word_to_f64<WS>(xraw[bi][j]);
-                t0 += mulmod_lazy(x, word_to_f64<WK>(kraw[j][0]), m);
-                t1 += mulmod_lazy(x, word_to_f64<WK>(kraw[j][1]), m);
+                const double x = src_f64<PACKED>(xraw[bi][j]);
+                t0 += mulmod_lazy(x, kw[j][0], m);
+                t1 += mulmod_lazy(x, kw[j][1], m);
             }
-            // |t| <= (digits + 1) * 0.51 p, far inside the range of a lazy product; the sums grow by 0.51 p a rotation
-            u0[bi] += mulmod_lazy(t0, w, m);
-            u1[bi] += mulmod_lazy(t1, w, m);
+            // the sums grow by at most (digits + 1) * 0.51 p a rotation: below 2^43 after the 16 rotations of a launch
+            u0[bi] += t0;
+            u1[bi] += t1;
         }
     }
 #pragma unroll
@@ -209,32 +256,26 @@ __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__
     }
 }
 
-void launch_rotate_mac(const ks_ctx* c, const Level& lv, const void* ct, uint64_t ct_bs, const void* lifted,
-                       const MacRotations& rot, uint64_t* u, uint32_t batch, bool accumulate, hipStream_t s, bool key_words32,
-                       bool src_words32) {
+void launch_rotate_mac(const ks_ctx* c, const Level& lv, const void* ct, uint64_t ct_bs, const GatherSources& src,
+                       const MacRotations& rot, uint64_t* u, uint32_t batch, bool accumulate, hipStream_t s, bool key_words32) {
     if (batch == 0 || rot.n == 0) return;
-    DigitRanges dg;
-    dg.ndig = lv.ndig;
-    for (uint32_t j = 0; j < kMaxDigits; ++j) {
-        dg.lo[j] = j < lv.ndig ? lv.digit_lo[j] : 0;
-        dg.hi[j] = j < lv.ndig ? lv.digit_hi[j] : 0;
-    }
+    const DigitRanges dg = digit_ranges(lv);
     const uint32_t groups = (batch + kBatchGroup - 1) / kBatchGroup;
     const dim3 grid(c->N / 256, lv.E, groups), block(256);
     // Algorithmic traffic: the raised digits and c0 of a ciphertext once (the rotations of a launch re-read them through
     // the gather; those re-reads are meant to come from cache), key and plaintext of every rotation once per group, both
     // sums written once.  Algorithmic work per slot, ciphertext and rotation: 2 NDIG + 3 modular products.
-    const double reads = (src_words32 ? 0.5 : 1.0) * batch * (lv.ndig * lv.E + lv.ell) +
-                         (key_words32 ? 0.5 : 1.0) * (double)rot.n * groups * (2.0 * lv.ndig + 1.0) * lv.E;
-    ProfScope ps("rotate_mac", (reads + (double)batch * 2 * lv.E * (accumulate ? 2 : 1)) * c->N * 8.0, s,
+    const double reads = batch * (src_bytes(src) * lv.ndig * lv.E + (src.hi ? 8.0 : 4.0) * lv.ell) +
+                         (key_words32 ? 4.0 : 8.0) * (double)rot.n * groups * (2.0 * lv.ndig + 1.0) * lv.E;
+    ProfScope ps("rotate_mac", (reads + (double)batch * 16 * lv.E * (accumulate ? 2 : 1)) * c->N, s,
                  (double)rot.n * batch * lv.E * c->N * (7.0 * (2 * lv.ndig + 3)));
-#define KS_LAUNCH_MAC_W(ND, WKT, WST)                                                                                                  \
-    hipLaunchKernelGGL((rotate_mac_kernel<ND, WKT, WST>), grid, block, 0, s, c->d_mod, c->d_Pmod, dg, lv.ell, lv.E, c->L, c->M, c->logN, \
-                       static_cast<const WST*>(ct), ct_bs, static_cast<const WST*>(lifted), rot, c->d_one, u, batch, accumulate ? 1 : 0)
-#define KS_LAUNCH_MAC(ND)                                                       \
-    if (key_words32 && src_words32) KS_LAUNCH_MAC_W(ND, uint32_t, uint32_t);    \
-    else if (key_words32) KS_LAUNCH_MAC_W(ND, uint32_t, uint64_t);              \
-    else KS_LAUNCH_MAC_W(ND, uint64_t, uint64_t)
+#define KS_LAUNCH_MAC_W(ND, WKT, PK)                                                                                                  \
+    hipLaunchKernelGGL((rotate_mac_kernel<ND, WKT, PK>), grid, block, 0, s, c->d_mod, c->d_Pmod, dg, lv.ell, lv.E, c->L, c->M, c->logN, \
+                       ct, ct_bs, src, rot, c->d_one, u, batch, accumulate ? 1 : 0)
+#define KS_LAUNCH_MAC(ND)                                               \
+    if (!src.hi) KS_LAUNCH_MAC_W(ND, uint32_t, false);                  \
+    else if (key_words32) KS_LAUNCH_MAC_W(ND, uint32_t, true);          \
+    else KS_LAUNCH_MAC_W(ND, uint64_t, true)
     switch (lv.ndig) {
         case 1: KS_LAUNCH_MAC(1); break;
         case 2: KS_LAUNCH_MAC(2); break;
@@ -247,6 +288,28 @@ void launch_rotate_mac(const ks_ctx* c, const Level& lv, const void* ct, uint64_
     }
 #undef KS_LAUNCH_MAC
 #undef KS_LAUNCH_MAC_W
+}
+
+// A polynomial's own limbs into the packed bundle of its raised digits (32-bit low words plus high bytes, see SrcPtr):
+// limb pos of polynomial b goes to slot (b, digit of pos, pos).
+__global__ __launch_bounds__(256) void pack_own_limbs_kernel(DigitRanges dg, uint32_t E, uint32_t N, const uint64_t* __restrict__ d,
+                                                             uint64_t d_ps, uint32_t* __restrict__ lo, uint8_t* __restrict__ hi) {
+    const uint32_t pos = blockIdx.y, b = blockIdx.z;
+    uint32_t j = 0;
+    while (j + 1 < dg.ndig && pos >= dg.hi[j]) ++j;  // uniform
+    const uint32_t n = blockIdx.x * 256 + threadIdx.x;
+    const uint64_t u = d[(uint64_t)b * d_ps + (uint64_t)pos * N + n];
+    const uint64_t e = (((uint64_t)b * dg.ndig + j) * E + pos) * N + n;
+    lo[e] = (uint32_t)u;
+    hi[e] = (uint8_t)(u >> 32);
+}
+
+void launch_pack_own_limbs(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, const PackedDigits& out, uint32_t bc,
+                           hipStream_t s) {
+    if (bc == 0) return;
+    const DigitRanges dg = digit_ranges(lv);
+    ProfScope prof("pack_own_limbs", 13.0 * bc * lv.ell * c->N, s);
+    hipLaunchKernelGGL(pack_own_limbs_kernel, dim3(c->N / 256, lv.ell, bc), dim3(256), 0, s, dg, lv.E, c->N, d, d_ps, out.lo, out.hi);
 }
 
 // (b1, a1) x (b2, a2) -> d0 = b1 b2, d1 = a1 b2 + a2 b1, d2 = a1 a2

@@ -238,20 +238,40 @@ struct MacRotations {
     const void* key[kMacRotations];  // [dnum][2][L+K][N], 64- or 32-bit words
     const void* pt[kMacRotations];   // [L+K][N], same word size as the keys
 };
+// Finished raised digits in the packed form the rotation gathers read: bits 0..31 of a canonical residue in lo, the bits
+// above (moduli are below 2^36) in hi, both indexed like the [b][ndig][E][N] bundle; 5 bytes a residue instead of 8.
+struct PackedDigits {
+    uint32_t* lo;
+    uint8_t* hi;
+};
+// What the sigma_g gathers of a rotation read.  hi != nullptr: packed bundle (lo, hi) holding every (digit, position)
+// slot, the digits' own limbs included.  hi == nullptr: lo holds the raised digits as 32-bit words and a digit's own
+// limbs come from the polynomial itself (own, 32-bit words, own_ps words between polynomials).
+struct GatherSources {
+    const uint32_t* lo;
+    const uint8_t* hi;
+    const uint32_t* own;
+    uint64_t own_ps;
+};
+// forward rows, out of place, into a packed bundle (ps: elements between polynomials, the same on both sides)
+void launch_ntt_fwd_rows_packed(const ks_ctx* c, const LimbMap& map, const uint64_t* in, uint64_t ps, const PackedDigits& out,
+                                uint32_t n_polys, hipStream_t s);
+// d[b][pos] (64-bit words, d_ps apart) into slot (b, digit of pos, pos) of a packed bundle
+void launch_pack_own_limbs(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, const PackedDigits& out, uint32_t bc,
+                           hipStream_t s);
+
 // acc[r][b][c][pos] = sum_j sigma_{g_r}(src_j)[pos] * key_r[j][c][ext_id(pos)] for every rotation r of `rot` (pt unused);
-// src_j[pos] = d[b][pos] when pos lies in digit j, otherwise lifted[b][j][pos].
-// key_words32: keys (and plaintexts) hold one residue per 32-bit word; src_words32: so do d / ct and the raised digits
-// (strides in words either way; src_words32 implies key_words32).
-void launch_inner_product(const ks_ctx* c, const Level& lv, const void* d, uint64_t d_poly_stride, const void* lifted,
-                          const MacRotations& rot, uint64_t* acc, uint32_t batch, hipStream_t s, bool key_words32 = false,
-                          bool src_words32 = false);
+// src_j[pos] = d[b][pos] when pos lies in digit j, otherwise lifted[b][j][pos], both read through `src`.
+// key_words32: keys (and plaintexts) hold one residue per 32-bit word; 32-bit sources imply 32-bit keys.
+void launch_inner_product(const ks_ctx* c, const Level& lv, const GatherSources& src, const MacRotations& rot, uint64_t* acc,
+                          uint32_t batch, hipStream_t s, bool key_words32 = false);
 
 // u[b][c][pos] (+)= sum_r pt_r[pos] * (sum_j sigma_r(src_j)[pos] key_r[j][c][pos] + [c = 0][pos < ell] P sigma_r(c0)[pos]);
-// ct: [b][2][ell][N] (c0, c1), lifted: finished raised digits of c1.  accumulate: add to what u already holds.
+// ct: [b][2][ell][N] (c0, c1) in 64-bit words with packed sources, in 32-bit words with 32-bit sources (ct_bs in words);
+// src: c1 and its finished raised digits.  accumulate: add to what u already holds.
 // galois[r] == 1: the term is P (c0, c1) and key[r] is not read; pt[r] == nullptr: the constant 1.
-void launch_rotate_mac(const ks_ctx* c, const Level& lv, const void* ct, uint64_t ct_bs, const void* lifted,
-                       const MacRotations& rot, uint64_t* u, uint32_t batch, bool accumulate, hipStream_t s, bool key_words32 = false,
-                       bool src_words32 = false);
+void launch_rotate_mac(const ks_ctx* c, const Level& lv, const void* ct, uint64_t ct_bs, const GatherSources& src,
+                       const MacRotations& rot, uint64_t* u, uint32_t batch, bool accumulate, hipStream_t s, bool key_words32 = false);
 
 // The key-switch chain behind ks_keyswitch / ks_keyswitch_u32 (argument checks included); ws is any device buffer of
 // at least ks_workspace_bytes(KS_OP_KEYSWITCH) bytes, whose contents need no initialisation.

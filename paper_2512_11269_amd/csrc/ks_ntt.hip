@@ -72,6 +72,42 @@ __global__ __launch_bounds__(64) void ntt_fwd_rows(TwTables tw, const Mod* __res
     for (int k = 0; k < 16; ++k) op[j0 + 16 * k] = f64_to_word<WO>(canon(reduce_lazy(v[k], m), m));
 }
 
+// forward, rows, out of place into the packed form the rotation gathers read: bits 0..31 of a canonical residue in a
+// 32-bit word array and the bits above (moduli are below 2^36) in a byte array with the same element index, 5 bytes a
+// residue instead of 8.  A thread ends with sixteen consecutive points and stores them as four 16-byte words plus one
+// 16-byte word of high bytes, so the row needs no last exchange through LDS.
+template <int LOG_R>
+__global__ __launch_bounds__(64) void ntt_fwd_rows_packed(TwTables tw, const Mod* __restrict__ mods, LimbMap map, const uint64_t* in,
+                                                          uint32_t* __restrict__ lo, uint8_t* __restrict__ hi, uint64_t ps) {
+    constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R, GROUPS = R / 4;
+    __shared__ double lds[4 * kRowPitch];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t li = blockIdx.x / GROUPS, rg = blockIdx.x - li * GROUPS;
+    const uint32_t poly = li / map.n, idx = li - poly * map.n, mod_id = map.mod[idx];
+    const uint64_t off = poly * ps + (uint64_t)map.off[idx] * N;
+    const Mod m = mods[mod_id];
+    const uint32_t j0 = tid & 15, rr = tid >> 4, row = rg * 4 + rr;
+    const uint64_t* ip = in + off + row * 256;
+    double v[16];
+    PassTwiddles t;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = load_f64(ip + j0 + 16 * k);
+    load_row_twiddles(t, tw, mod_id, N, R + row, j0, m);
+    row_fwd_core_consecutive(v, t, j0, lds + rr * kRowPitch, m);
+    uint32_t l[16], h[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const uint64_t u = f64_to_u64(canon(reduce_lazy(v[k], m), m));
+        l[k] = (uint32_t)u;
+        h[k >> 2] |= (uint32_t)(u >> 32) << (8 * (k & 3));
+    }
+    const uint64_t e = off + row * 256 + 16 * j0;
+    uint4* lp = reinterpret_cast<uint4*>(lo + e);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) lp[q] = make_uint4(l[4 * q], l[4 * q + 1], l[4 * q + 2], l[4 * q + 3]);
+    *reinterpret_cast<uint4*>(hi + e) = make_uint4(h[0], h[1], h[2], h[3]);
+}
+
 // inverse, rows first: canonical residues in (64- or 32-bit words), raw doubles out (|x| <= 0.501 p).
 template <int LOG_R, typename W>
 __global__ __launch_bounds__(64) void ntt_inv_rows(TwTables twi, const Mod* __restrict__ mods, LimbMap map,
@@ -210,6 +246,18 @@ void launch_ntt_fwd_rows_to(const ks_ctx* c, const LimbMap& map, const uint64_t*
     else                                                                                                                             \
         hipLaunchKernelGGL((ntt_fwd_rows<LOGR, uint64_t>), dim3(limbs << (LOGR - 2)), dim3(64), 0, s, c->tw_fwd, c->d_mod, map, in,  \
                            static_cast<uint64_t*>(out), in_ps, out_ps)
+    KS_FOR_LOG_R(c->logN, KS_LAUNCH)
+#undef KS_LAUNCH
+}
+
+void launch_ntt_fwd_rows_packed(const ks_ctx* c, const LimbMap& map, const uint64_t* in, uint64_t ps, const PackedDigits& out,
+                                uint32_t n_polys, hipStream_t s) {
+    const uint32_t limbs = map.n * n_polys;
+    if (limbs == 0) return;
+    ProfScope prof("ntt_fwd_rows", 13.0 * limbs * c->N, s);
+#define KS_LAUNCH(LOGR)                                                                                                         \
+    hipLaunchKernelGGL((ntt_fwd_rows_packed<LOGR>), dim3(limbs << (LOGR - 2)), dim3(64), 0, s, c->tw_fwd, c->d_mod, map, in, out.lo, \
+                       out.hi, ps)
     KS_FOR_LOG_R(c->logN, KS_LAUNCH)
 #undef KS_LAUNCH
 }

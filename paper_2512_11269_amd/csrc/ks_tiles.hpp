@@ -117,6 +117,17 @@ __device__ __forceinline__ void row_fwd_core(double (&v)[16], const PassTwiddles
     for (int k = 0; k < 16; ++k) v[k] = lrow[j0 + 17 * k];
 }
 
+// The same without the last exchange: out v[k] = point 16 j0 + k (sixteen consecutive points per thread).
+__device__ __forceinline__ void row_fwd_core_consecutive(double (&v)[16], const PassTwiddles& t, uint32_t j0, double* lrow, Mod m) {
+    radix16_fwd(v, t.a, m);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) lrow[j0 + 17 * k] = v[k];
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = lrow[17 * j0 + k];
+    radix16_fwd(v, t.b, m);
+}
+
 // The same with the first-pass twiddles read from LDS (ta: 16 doubles of this row) and the second-pass ones in registers.
 __device__ __forceinline__ void row_fwd_core_lds(double (&v)[16], const double* ta, const double (&tb)[16], uint32_t j0, double* lrow,
                                                  Mod m) {
