@@ -69,6 +69,12 @@ def _keyswitch_bytes(L, K, dnum, N, batch=1):
     return compulsory, fused
 
 
+def _keyswitch_bytes_moved(L, K, dnum, N, batch=1):
+    """What the library's chain moves per key-switch: the fused-plan model with the ciphertext limbs of both
+    accumulators written and read back as 5-byte packed residues instead of 8-byte words (2 * 2 * L limbs at 3/8 less)."""
+    return _keyswitch_bytes(L, K, dnum, N, batch)[1] - 2 * 2 * L * N * 3.0
+
+
 def _apply_options(ctx, args):
     """--opt ID=VALUE pairs: tuning options of the context (see ks_ctx_set_option)."""
     for item in args.opt or []:
@@ -193,6 +199,9 @@ def bench_keyswitch(args, torch, K, ks_inputs):
     path = {"fused_plan_MiB": fused / MIB, "compulsory_MiB": compulsory / MIB,
             "fused_plan_GBs": round(fused / (ms * 1e-3) / 1e9, 1), "fused_plan_frac_of_peak": frac(fused, ms),
             "target_frac_of_peak": 0.60,
+            # the same with the packed accumulator limbs counted at their 5 bytes: the bytes the chain really moves
+            "moved_MiB": round(_keyswitch_bytes_moved(L, Kk, dnum, N) / MIB, 1),
+            "moved_frac_of_peak": frac(_keyswitch_bytes_moved(L, Kk, dnum, N), ms),
             "compulsory_GBs": round(compulsory / (ms * 1e-3) / 1e9, 1),
             "sum_kernel_ms_per_step": round(sum(k["ms_per_step"] for k in kernels), 4),
             # algorithmic traffic per ciphertext of a batched call, the key charged once per chunk of 8 (part of this

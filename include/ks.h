@@ -141,7 +141,7 @@ int ks_keyswitch_u32(const ks_ctx* ctx, const uint32_t* d, uint32_t ell, const u
  * The call allocates nothing and does not synchronise.  All calls on one GPU share the one array: calls whose
  * execution may overlap on a GPU (different streams, different host threads) race on it and must be serialised
  * by the caller; calls on one stream are safe.  Nothing in the array needs clearing between calls. */
-#define KS_STATIC_WORKSPACE_BYTES ((size_t)232 * 65536 * 8)
+#define KS_STATIC_WORKSPACE_BYTES ((size_t)262 * 65536 * 8)
 size_t ks_static_workspace_bytes(void);
 int ks_keyswitch_static(const ks_ctx* ctx, const uint64_t* d, uint32_t ell, const uint64_t* evk, uint64_t* out,
                         uint32_t batch, void* stream);

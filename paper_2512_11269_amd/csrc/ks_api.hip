@@ -25,8 +25,17 @@ int finish(const char* where) {
 
 struct KsWorkspace {  // element counts (uint64 words) for a chunk of `bc` ciphertexts
     uint64_t coeff, lifted, acc, conv;
-    uint64_t total() const { return coeff + lifted + acc + conv; }
+    uint64_t accq;  // ciphertext limbs of the accumulators in packed form, [bc][2][ell][N] residues
+    uint64_t total() const { return coeff + lifted + acc + conv + accq; }
 };
+
+// 64-bit words that n residues take in packed form (32-bit low words, then the bytes above; each part 8-byte aligned)
+static uint64_t packed_words(uint64_t n) { return (n + 1) / 2 + (n + 7) / 8; }
+
+// the packed tensor of n residues that starts at `words`
+static PackedDigits packed_at(uint64_t* words, uint64_t n) {
+    return PackedDigits{reinterpret_cast<uint32_t*>(words), reinterpret_cast<uint8_t*>(words + (n + 1) / 2)};
+}
 
 KsWorkspace ks_ws_words(const ks_ctx* c, const Level& lv, uint32_t bc) {
     const uint64_t N = c->N;
@@ -35,6 +44,7 @@ KsWorkspace ks_ws_words(const ks_ctx* c, const Level& lv, uint32_t bc) {
     w.lifted = (uint64_t)bc * lv.ndig * lv.E * N;
     w.acc = (uint64_t)bc * 2 * lv.E * N;
     w.conv = (uint64_t)bc * 2 * lv.ell * N;
+    w.accq = packed_words(w.conv);
     return w;
 }
 
@@ -87,15 +97,16 @@ static double moddown_ops(const ks_ctx* c, const Level& lv) {
 
 // Division by P of both accumulators, optional addend: INTT of the special limbs (in place), fused base
 // conversion + column half, fused row half + (acc - conv) P^-1.
+// accq: the ciphertext limbs of the accumulators are there, packed, instead of in acc.
 void mod_down(const ks_ctx* c, const Level& lv, uint64_t* acc, uint64_t* conv, void* out, uint64_t out_bs,
               const uint64_t* addend, uint64_t addend_bs, uint32_t addend_comps, uint32_t galois, uint32_t bc,
-              bool special_rows_done, hipStream_t s, bool out_words32 = false) {
+              bool special_rows_done, hipStream_t s, bool out_words32 = false, const PackedDigits* accq = nullptr) {
     const uint64_t N = c->N, acc_ps = (uint64_t)lv.E * N, conv_ps = (uint64_t)lv.ell * N;
     // the fused inner product already ran the row half of the inverse transform on the special limbs
     if (!special_rows_done) launch_ntt_inv_rows(c, lv.special_map, XformIO{acc, acc, acc_ps, acc_ps, 2 * bc}, s);
     launch_ntt_inv_cols(c, lv.special_map, acc, acc_ps, 2 * bc, c->d_moddown_scale, true, true, s);
     launch_bconv_ntt_cols(c, lv.moddown, c->K + lv.ell, acc, acc_ps, conv, conv_ps, 2 * bc, s, moddown_ops(c, lv));
-    launch_rows_moddown_finish(c, lv, acc, conv, out, out_bs, addend, addend_bs, addend_comps, galois, bc, s, nullptr, out_words32);
+    launch_rows_moddown_finish(c, lv, acc, conv, out, out_bs, addend, addend_bs, addend_comps, galois, bc, s, nullptr, out_words32, accq);
 }
 
 }  // namespace
@@ -113,8 +124,10 @@ extern "C" size_t ks_workspace_bytes(const ks_ctx* c, int op, uint32_t ell, uint
             if (n_rot == 0) return 0;
             // accumulators and converted limbs for a whole group of rotations
             words += (uint64_t)(std::min(n_rot, kRotGroup) - 1) * bc * (2 * lv.E + 2 * ell) * N;
-            // the gathers' sources; 32-bit words: also the chunk's ciphertexts widened to 64-bit words
+            // the gathers' sources; the ciphertext limbs of a group's accumulators, packed; 32-bit words: also the chunk's
+            // ciphertexts widened to 64-bit words
             words += gather_words(ks_ws_words(c, lv, bc), op == KS_OP_ROTATE_HOISTED_U32);
+            words += (uint64_t)(std::min(n_rot, kRotGroup) - 1) * ks_ws_words(c, lv, bc).accq;
             if (op == KS_OP_ROTATE_HOISTED_U32) words += (uint64_t)bc * 2 * ell * N;
             break;
         case KS_OP_BSGS:
@@ -308,10 +321,12 @@ int ks::keyswitch_impl(const ks_ctx* c, const void* d, uint32_t ell, const void*
         uint64_t* lifted = coeff + w.coeff;
         uint64_t* acc = lifted + w.lifted;
         uint64_t* conv = acc + w.acc;
+        const PackedDigits accq = packed_at(conv + w.conv, w.conv);
         const char* dc = static_cast<const char*>(d) + (uint64_t)b0 * d_ps * word;
         mod_up(c, lv, dc, d_ps, coeff, lifted, bc, s, words32);
-        launch_rows_inner_product(c, lv, dc, d_ps, lifted, evk, acc, bc, s, words32, words32);
-        mod_down(c, lv, acc, conv, static_cast<char*>(out) + (uint64_t)b0 * out_bs * word, out_bs, nullptr, 0, 0, 1, bc, true, s, words32);
+        launch_rows_inner_product(c, lv, dc, d_ps, lifted, evk, acc, bc, s, words32, words32, &accq, ell);
+        mod_down(c, lv, acc, conv, static_cast<char*>(out) + (uint64_t)b0 * out_bs * word, out_bs, nullptr, 0, 0, 1, bc, true, s, words32,
+                 &accq);
     }
     return finish(words32 ? "ks_keyswitch_u32" : "ks_keyswitch");
 }
@@ -370,6 +385,9 @@ static int rotate_hoisted_impl(const ks_ctx* c, const void* ct, uint32_t ell, co
         // the last kernel, which adds sigma_g(c0) through a rotation's own permutation, runs per rotation.
         const uint32_t group = std::min(n_rot, kRotGroup);
         uint64_t* conv = acc + (uint64_t)group * w.acc;
+        // ciphertext limbs of the group's accumulators, packed: [group][bc][2][ell][N]
+        const uint64_t accq_n = w.conv;
+        const PackedDigits accq = packed_at(conv + (uint64_t)group * w.conv, (uint64_t)group * accq_n);
         const uint64_t acc_ps = (uint64_t)lv.E * N, conv_ps = (uint64_t)ell * N;
         for (uint32_t r0 = 0; r0 < n_rot; r0 += group) {
             MacRotations rot;
@@ -379,15 +397,17 @@ static int rotate_hoisted_impl(const ks_ctx* c, const void* ct, uint32_t ell, co
                 rot.key[r] = rot_keys[r0 + r];
                 rot.pt[r] = nullptr;
             }
-            launch_inner_product(c, lv, digits, rot, acc, bc, s, words32);
+            launch_inner_product(c, lv, digits, rot, acc, accq, bc, s, words32);
             const uint32_t polys = 2 * rot.n * bc;
             launch_ntt_inv_rows(c, lv.special_map, XformIO{acc, acc, acc_ps, acc_ps, polys}, s);
             launch_ntt_inv_cols(c, lv.special_map, acc, acc_ps, polys, c->d_moddown_scale, true, true, s);
             launch_bconv_ntt_cols(c, lv.moddown, c->K + lv.ell, acc, acc_ps, conv, conv_ps, polys, s, moddown_ops(c, lv));
-            for (uint32_t r = 0; r < rot.n; ++r)
-                launch_rows_moddown_finish(c, lv, acc + (uint64_t)r * w.acc, conv + (uint64_t)r * w.conv,
+            for (uint32_t r = 0; r < rot.n; ++r) {
+                const PackedDigits accq_r{accq.lo + (uint64_t)r * accq_n, accq.hi + (uint64_t)r * accq_n};
+                launch_rows_moddown_finish(c, lv, nullptr, conv + (uint64_t)r * w.conv,
                                            static_cast<char*>(out) + ((uint64_t)b0 * out_bs + (uint64_t)(r0 + r) * 2 * ell * N) * word,
-                                           out_bs, c0, ct_bs, 1, galois[r0 + r], bc, s, nullptr, words32);
+                                           out_bs, c0, ct_bs, 1, galois[r0 + r], bc, s, nullptr, words32, &accq_r);
+            }
         }
     }
     return finish(words32 ? "ks_rotate_hoisted_u32" : "ks_rotate_hoisted");
@@ -546,8 +566,10 @@ extern "C" int ks_bsgs_linear_transform_u32(const ks_ctx* c, const uint32_t* ct,
 // Division by P q_{ell-1} of acc + P addend in one conversion (ModDown merged with the rescale that would follow):
 // limb ell-1 joins the special limbs as a source, the targets are q_0..q_{ell-2}.  The fused inner product has already
 // run the row half of the inverse transform on the special limbs.
+// accq: the ciphertext limbs below ell-1 of the accumulators, packed (limb ell-1 is a conversion source and stays in acc).
 static void mod_down_merged(const ks_ctx* c, const Level& lv, uint64_t* acc, uint64_t* conv, void* out, uint64_t out_bs,
-                            const uint64_t* addend, uint64_t addend_bs, uint32_t bc, hipStream_t s, bool out_words32) {
+                            const uint64_t* addend, uint64_t addend_bs, uint32_t bc, hipStream_t s, bool out_words32,
+                            const PackedDigits* accq) {
     const uint64_t N = c->N, acc_ps = (uint64_t)lv.E * N, conv_ps = (uint64_t)lv.ell * N;
     launch_add_scaled_limb(c, acc, acc_ps, addend, addend_bs, (uint64_t)lv.ell * N, lv.ell - 1, lv.Pmod_last, bc, s);
     launch_ntt_inv_rows(c, lv.last_map, XformIO{acc, acc, acc_ps, acc_ps, 2 * bc}, s);
@@ -556,7 +578,7 @@ static void mod_down_merged(const ks_ctx* c, const Level& lv, uint64_t* acc, uin
     const double ops = (double)n_src * n_dst * 4.5 + n_dst * (3.0 + 4.0 * (c->logN - 8));
     launch_bconv_ntt_cols(c, lv.merged, n_src + n_dst, acc, acc_ps, conv, conv_ps, 2 * bc, s, ops);
     const FinishScale fs{lv.d_Dinv, lv.d_qlinv, n_dst};
-    launch_rows_moddown_finish(c, lv, acc, conv, out, out_bs, addend, addend_bs, 2, 1, bc, s, &fs, out_words32);
+    launch_rows_moddown_finish(c, lv, acc, conv, out, out_bs, addend, addend_bs, 2, 1, bc, s, &fs, out_words32, accq);
 }
 
 // cta, ctb, rlk and out in 64-bit words, or all four in 32-bit words (words32); the tensor product and everything after it
@@ -584,7 +606,8 @@ static int hmult_impl(const ks_ctx* c, const void* cta, const void* ctb, uint32_
         uint64_t* lifted = coeff + w.coeff;
         uint64_t* acc = lifted + w.lifted;
         uint64_t* conv = acc + w.acc;
-        uint64_t* td = conv + w.conv;                           // [bc][3][ell][N]
+        const PackedDigits accq = packed_at(conv + w.conv, w.conv);
+        uint64_t* td = conv + w.conv + w.accq;                  // [bc][3][ell][N]
         uint64_t* sum = td + (uint64_t)bc * td_bs;              // [bc][2][ell][N]
         uint64_t* last = sum + (uint64_t)bc * ct_bs;            // [2 bc][N]
         uint64_t* spread = last + (uint64_t)bc * 2 * N;         // [2 bc][ell-1][N]
@@ -593,12 +616,12 @@ static int hmult_impl(const ks_ctx* c, const void* cta, const void* ctb, uint32_
                               static_cast<const char*>(ctb) + (uint64_t)b0 * ct_bs * word, td, ell, bc, s, words32);
         const uint64_t* d2 = td + 2ull * ell * N;
         mod_up(c, lv, d2, td_bs, coeff, lifted, bc, s);
-        launch_rows_inner_product(c, lv, d2, td_bs, lifted, rlk, acc, bc, s, false, words32);
+        launch_rows_inner_product(c, lv, d2, td_bs, lifted, rlk, acc, bc, s, false, words32, &accq, merged ? ell - 1 : ell);
         if (merged) {
-            mod_down_merged(c, lv, acc, conv, oc, out_bs, td, td_bs, bc, s, words32);
+            mod_down_merged(c, lv, acc, conv, oc, out_bs, td, td_bs, bc, s, words32, &accq);
             continue;
         }
-        mod_down(c, lv, acc, conv, sum, ct_bs, td, td_bs, 2, 1, bc, true, s);
+        mod_down(c, lv, acc, conv, sum, ct_bs, td, td_bs, 2, 1, bc, true, s, false, &accq);
         // rescale both components: inverse transform of the last limb, centred remainder to every q_i, forward
         // transform, subtract and divide
         launch_ntt_inv_rows(c, one, XformIO{sum + (uint64_t)(ell - 1) * N, last, (uint64_t)ell * N, N, 2 * bc}, s);

@@ -51,10 +51,14 @@ __device__ __forceinline__ SrcPtr<PACKED> src_ptr(const GatherSources& g, const 
 // Branch-free like rotate_mac_kernel below: the digit count is a template parameter and a short last group recomputes
 // its last ciphertext, so every load of a rotation is issued before the first product.
 // WK: word type of the keys; PACKED: format of the gathered sources (see SrcPtr).
+// The special limbs of the result go to acc ([r][b][2][E][N] 64-bit words, the inverse transform reads them next), the
+// ciphertext limbs to (accq_lo, accq_hi) as [r][b][2][ell][N] packed residues: they are only read back by the last
+// kernel of the rotation, and written and read once per rotation they are a fifth of these two kernels' traffic.
 template <int NDIG, typename WK, bool PACKED>
 __global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restrict__ mods, DigitRanges dg, uint32_t ell, uint32_t E,
                                                             uint32_t L, uint32_t M, uint32_t logN, GatherSources src, MacRotations rot,
-                                                            uint64_t* __restrict__ acc, uint32_t batch) {
+                                                            uint64_t* __restrict__ acc, uint32_t* __restrict__ accq_lo,
+                                                            uint8_t* __restrict__ accq_hi, uint32_t batch) {
     const uint32_t N = 1u << logN;
     const uint32_t pos = blockIdx.y;
     const uint32_t mid = pos < ell ? pos : L + (pos - ell);
@@ -84,6 +88,7 @@ __global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restric
 #pragma unroll
             for (int j = 0; j < NDIG; ++j) xraw[bi][j] = src_load<PACKED>(srcp[bi][j], sn);
         uint64_t* ar = acc + (uint64_t)r * batch * 2 * E * N;
+        const uint64_t rq = (uint64_t)r * batch * 2 * ell * N;
 #pragma unroll
         for (int bi = 0; bi < kBatchGroup; ++bi) {
             const uint32_t b = min(b_lo + bi, batch - 1);
@@ -94,8 +99,17 @@ __global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restric
                 a0 += mulmod_lazy(x, word_to_f64<WK>(kraw[j][0]), m);
                 a1 += mulmod_lazy(x, word_to_f64<WK>(kraw[j][1]), m);
             }
-            ar[(((uint64_t)b * 2 + 0) * E + pos) * N + n] = f64_to_u64(canon(reduce_lazy(a0, m), m));
-            ar[(((uint64_t)b * 2 + 1) * E + pos) * N + n] = f64_to_u64(canon(reduce_lazy(a1, m), m));
+            const uint64_t u0 = f64_to_u64(canon(reduce_lazy(a0, m), m)), u1 = f64_to_u64(canon(reduce_lazy(a1, m), m));
+            if (pos < ell) {  // uniform: ciphertext limbs go out packed, 5 bytes a residue
+                const uint64_t e0 = rq + (((uint64_t)b * 2 + 0) * ell + pos) * N + n, e1 = e0 + (uint64_t)ell * N;
+                accq_lo[e0] = (uint32_t)u0;
+                accq_hi[e0] = (uint8_t)(u0 >> 32);
+                accq_lo[e1] = (uint32_t)u1;
+                accq_hi[e1] = (uint8_t)(u1 >> 32);
+            } else {
+                ar[(((uint64_t)b * 2 + 0) * E + pos) * N + n] = u0;
+                ar[(((uint64_t)b * 2 + 1) * E + pos) * N + n] = u1;
+            }
         }
     }
 }
@@ -114,7 +128,7 @@ static DigitRanges digit_ranges(const Level& lv) {
 static double src_bytes(const GatherSources& g) { return g.hi ? 5.0 : 4.0; }
 
 void launch_inner_product(const ks_ctx* c, const Level& lv, const GatherSources& src, const MacRotations& rot, uint64_t* acc,
-                          uint32_t batch, hipStream_t s, bool key_words32) {
+                          const PackedDigits& accq, uint32_t batch, hipStream_t s, bool key_words32) {
     if (batch == 0 || rot.n == 0) return;
     const DigitRanges dg = digit_ranges(lv);
     const uint32_t groups = (batch + kBatchGroup - 1) / kBatchGroup;
@@ -123,11 +137,11 @@ void launch_inner_product(const ks_ctx* c, const Level& lv, const GatherSources&
     // accumulators of every rotation
     const double wk = key_words32 ? 4.0 : 8.0;
     ProfScope ps("inner_product",
-                 (src_bytes(src) * batch * lv.ndig * lv.E + (double)rot.n * (wk * 2.0 * lv.ndig * lv.E * groups + 16.0 * lv.E * batch)) * c->N,
+                 (src_bytes(src) * batch * lv.ndig * lv.E + (double)rot.n * (wk * 2.0 * lv.ndig * lv.E * groups + (16.0 * (lv.E - lv.ell) + 10.0 * lv.ell) * batch)) * c->N,
                  s);
 #define KS_LAUNCH_IP_W(ND, WKT, PK)                                                                                                \
     hipLaunchKernelGGL((inner_product_kernel<ND, WKT, PK>), grid, block, 0, s, c->d_mod, dg, lv.ell, lv.E, c->L, c->M, c->logN, src, \
-                       rot, acc, batch)
+                       rot, acc, accq.lo, accq.hi, batch)
 #define KS_LAUNCH_IP(ND)                                                \
     if (!src.hi) KS_LAUNCH_IP_W(ND, uint32_t, false);                   \
     else if (key_words32) KS_LAUNCH_IP_W(ND, uint32_t, true);           \

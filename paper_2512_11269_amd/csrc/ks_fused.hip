@@ -249,7 +249,9 @@ __global__ __launch_bounds__(64, PREFETCH ? 2 : 0) void rows_inner_product(TwTab
                                                          uint32_t ell, uint32_t E, uint32_t L, uint32_t M,
                                                          const WD* __restrict__ d, uint64_t d_ps,
                                                          const uint64_t* __restrict__ lifted, const WK* __restrict__ evk,
-                                                         uint64_t* __restrict__ acc, uint32_t batch, uint32_t special_first) {
+                                                         uint64_t* __restrict__ acc, uint32_t* __restrict__ accq_lo,
+                                                         uint8_t* __restrict__ accq_hi, uint32_t packed_limbs, uint32_t batch,
+                                                         uint32_t special_first) {
     constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R;
     __shared__ double lds[4 * kRowPitch];
     __shared__ double lds_ta[4 * 16];
@@ -267,12 +269,17 @@ __global__ __launch_bounds__(64, PREFETCH ? 2 : 0) void rows_inner_product(TwTab
     const uint32_t rg = tile % (R / 4), slot_pos = tile / (R / 4), n_special = E - ell;
     const uint32_t pos = !special_first ? slot_pos : slot_pos < n_special ? ell + slot_pos : slot_pos - n_special;
     task_rows_inner_product<LOG_R, WD, WK, PREFETCH>(tw, twi, mods, dg, ell, E, L, M, d + (uint64_t)b * d_ps, lifted + (uint64_t)b * dg.ndig * E * N, evk,
-                                      acc + (uint64_t)b * 2 * E * N, pos, rg, threadIdx.x, lds, lds_ta);
+                                      acc + (uint64_t)b * 2 * E * N, accq_lo + (uint64_t)b * 2 * ell * N,
+                                      accq_hi + (uint64_t)b * 2 * ell * N, packed_limbs, pos, rg, threadIdx.x, lds, lds_ta);
 }
 
 void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const void* d, uint64_t d_ps, const uint64_t* lifted,
-                               const void* evk, uint64_t* acc, uint32_t batch, hipStream_t s, bool d_words32, bool key_words32) {
+                               const void* evk, uint64_t* acc, uint32_t batch, hipStream_t s, bool d_words32, bool key_words32,
+                               const PackedDigits* accq, uint32_t packed_limbs) {
     if (batch == 0) return;
+    if (!accq) packed_limbs = 0;
+    uint32_t* accq_lo = accq ? accq->lo : nullptr;
+    uint8_t* accq_hi = accq ? accq->hi : nullptr;
     DigitRanges dg;
     dg.ndig = lv.ndig;
     for (uint32_t j = 0; j < kMaxDigits; ++j) {
@@ -283,7 +290,9 @@ void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const void* d, 
     // d (ell limbs per ciphertext) and the key arrive in boundary words, the raised limbs and the sums in 8 bytes
     const double wd = d_words32 ? 0.5 : 1.0, wk = key_words32 ? 0.5 : 1.0;
     ProfScope ps("rows_inner_product",
-                 ((double)batch * ((lv.ndig * lv.E - lv.ell) + wd * lv.ell + 2.0 * lv.E) + wk * 2.0 * lv.ndig * lv.E) * c->N * 8.0, s);
+                 ((double)batch * ((lv.ndig * lv.E - lv.ell) + wd * lv.ell + 2.0 * lv.E - 0.75 * packed_limbs) + wk * 2.0 * lv.ndig * lv.E) *
+                     c->N * 8.0,
+                 s);
     const uint32_t tiles = (c->N / 1024) * lv.E;
     const dim3 grid(((tiles + 7) / 8) * 8 * batch), block(64);
     // launches with more than two wavefronts per SIMD (1024 SIMDs) to run take the variant that requests the next digit's
@@ -292,7 +301,8 @@ void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const void* d, 
     const bool prefetch = grid.x > 2048;
 #define KS_LAUNCH_IP(LOGR, WDT, WKT, PF)                                                                                           \
     hipLaunchKernelGGL((rows_inner_product<LOGR, WDT, WKT, PF>), grid, block, 0, s, c->tw_fwd, c->tw_inv, c->d_mod, dg, lv.ell, lv.E, c->L, \
-                       c->M, static_cast<const WDT*>(d), d_ps, lifted, static_cast<const WKT*>(evk), acc, batch, prefetch ? 0u : 1u)
+                       c->M, static_cast<const WDT*>(d), d_ps, lifted, static_cast<const WKT*>(evk), acc, accq_lo, accq_hi, packed_limbs, batch,   \
+                       prefetch ? 0u : 1u)
 #define KS_LAUNCH(LOGR)                                                          \
     if (d_words32 && key_words32) KS_LAUNCH_IP(LOGR, uint32_t, uint32_t, false); \
     else if (key_words32) KS_LAUNCH_IP(LOGR, uint64_t, uint32_t, false);         \
@@ -309,11 +319,14 @@ void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const void* d, 
 // ADDEND: 0 = none, 1 = added as it is, 2 = multiplied by addend_mul[i] first.  Compile-time so that the kernel has no
 // branch: behind a run-time test every addend load became its own load-wait-use round trip.  A launch covers the
 // components comp0 .. comp0 + n_comps - 1 of every batch item.
-template <int LOG_R, bool GATHER, int ADDEND, typename W = uint64_t>
+// ACCP: the ciphertext limbs of the accumulator come packed (acc: [b][2][ell][N] 32-bit low words, acc_hi: the bytes
+// above) instead of as the first ell limbs of [b][2][E][N] 64-bit words.
+template <int LOG_R, bool GATHER, int ADDEND, typename W = uint64_t, bool ACCP = false>
 __global__ __launch_bounds__(64) void rows_moddown_finish(TwTables tw, const Mod* __restrict__ mods,
                                                           const double* __restrict__ Pinv, const double* __restrict__ addend_mul,
                                                           uint32_t ell, uint32_t E, uint32_t out_limbs,
-                                                          const uint64_t* __restrict__ acc, const uint64_t* __restrict__ conv,
+                                                          const void* __restrict__ acc, const uint8_t* __restrict__ acc_hi,
+                                                          const uint64_t* __restrict__ conv,
                                                           W* __restrict__ out, uint64_t out_bs,
                                                           const uint64_t* __restrict__ addend, uint64_t addend_bs,
                                                           uint32_t comp0, uint32_t n_comps, uint32_t galois) {
@@ -328,38 +341,55 @@ __global__ __launch_bounds__(64) void rows_moddown_finish(TwTables tw, const Mod
     double admul = 0.0;
     if constexpr (ADDEND != 0) adp = addend + (uint64_t)b * addend_bs + ((uint64_t)comp * ell + i) * N;
     if constexpr (ADDEND == 2) admul = addend_mul[i];
-    task_rows_finish<LOG_R, GATHER, ADDEND, W>(tw, mods[i], i, Pinv[i], admul, conv + (((uint64_t)b * 2 + comp) * ell + i) * N,
-                                               acc + (((uint64_t)b * 2 + comp) * E + i) * N,
-                                               out + (uint64_t)b * out_bs + ((uint64_t)comp * out_limbs + i) * N, adp, galois, rg,
-                                               threadIdx.x, lds);
+    const uint64_t conv_off = (((uint64_t)b * 2 + comp) * ell + i) * N;
+    const void* ap;
+    const uint8_t* ap_hi = nullptr;
+    if constexpr (ACCP) {
+        ap = static_cast<const uint32_t*>(acc) + conv_off;
+        ap_hi = acc_hi + conv_off;
+    } else {
+        ap = static_cast<const uint64_t*>(acc) + (((uint64_t)b * 2 + comp) * E + i) * N;
+    }
+    task_rows_finish<LOG_R, GATHER, ADDEND, W, ACCP>(tw, mods[i], i, Pinv[i], admul, conv + conv_off, ap, ap_hi,
+                                                     out + (uint64_t)b * out_bs + ((uint64_t)comp * out_limbs + i) * N, adp, galois, rg,
+                                                     threadIdx.x, lds);
 }
 
 void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t* acc, const uint64_t* conv, void* out_words,
                                 uint64_t out_bs, const uint64_t* addend, uint64_t addend_bs, uint32_t addend_comps,
-                                uint32_t galois, uint32_t batch, hipStream_t s, const FinishScale* fs, bool out_words32) {
+                                uint32_t galois, uint32_t batch, hipStream_t s, const FinishScale* fs, bool out_words32,
+                                const PackedDigits* acc_packed) {
     if (batch == 0) return;
     const double* mul = fs ? fs->mul : c->d_Pinv;
     const double* admul = fs ? fs->addend_mul : nullptr;
     const uint32_t out_limbs = fs ? fs->out_limbs : lv.ell;
     if (out_limbs == 0) return;
     if (!addend) addend_comps = 0;
-    ProfScope ps("rows_moddown_finish", (double)batch * out_limbs * (4 + (out_words32 ? 1 : 2) + addend_comps) * c->N * 8.0, s);
+    ProfScope ps("rows_moddown_finish",
+                 (double)batch * out_limbs * (2 * 8 + 2 * (acc_packed ? 5 : 8) + (out_words32 ? 1 : 2) * 8 + addend_comps * 8) * c->N, s);
     const dim3 block(64);
     const uint32_t row_groups = c->N / 1024;
+    const void* accp = acc_packed ? static_cast<const void*>(acc_packed->lo) : static_cast<const void*>(acc);
+    const uint8_t* acch = acc_packed ? acc_packed->hi : nullptr;
     // one launch for the components that take the addend, one for those that do not
     for (int pass = 0; pass < 2; ++pass) {
         const uint32_t comp0 = pass == 0 ? 0 : addend_comps, n_comps = pass == 0 ? addend_comps : 2 - addend_comps;
         if (n_comps == 0) continue;
         const int mode = pass == 1 ? 0 : (admul ? 2 : 1);
         const dim3 grid(row_groups, out_limbs, batch * n_comps);
-#define KS_LAUNCH_FINISH(LOGR, GATHER, MODE, WT)                                                                                   \
-    hipLaunchKernelGGL((rows_moddown_finish<LOGR, GATHER, MODE, WT>), grid, block, 0, s, c->tw_fwd, c->d_mod, mul, admul, lv.ell, lv.E, \
-                       out_limbs, acc, conv, static_cast<WT*>(out_words), out_bs, addend, addend_bs, comp0, n_comps, galois)
-#define KS_LAUNCH_MODES(LOGR, WT)                                  \
-    if (mode == 0) KS_LAUNCH_FINISH(LOGR, false, 0, WT);           \
-    else if (mode == 2) KS_LAUNCH_FINISH(LOGR, false, 2, WT);      \
-    else if (galois == 1) KS_LAUNCH_FINISH(LOGR, false, 1, WT);    \
-    else KS_LAUNCH_FINISH(LOGR, true, 1, WT)
+#define KS_LAUNCH_FINISH(LOGR, GATHER, MODE, WT, ACCP)                                                                             \
+    hipLaunchKernelGGL((rows_moddown_finish<LOGR, GATHER, MODE, WT, ACCP>), grid, block, 0, s, c->tw_fwd, c->d_mod, mul, admul, lv.ell, \
+                       lv.E, out_limbs, accp, acch, conv, static_cast<WT*>(out_words), out_bs, addend, addend_bs, comp0, n_comps, galois)
+#define KS_LAUNCH_MODES(LOGR, WT)                                                        \
+    if (acc_packed) {                                                                    \
+        if (mode == 0) KS_LAUNCH_FINISH(LOGR, false, 0, WT, true);                       \
+        else if (mode == 2) KS_LAUNCH_FINISH(LOGR, false, 2, WT, true);                  \
+        else if (galois == 1) KS_LAUNCH_FINISH(LOGR, false, 1, WT, true);                \
+        else KS_LAUNCH_FINISH(LOGR, true, 1, WT, true);                                  \
+    } else if (mode == 0) KS_LAUNCH_FINISH(LOGR, false, 0, WT, false);                   \
+    else if (mode == 2) KS_LAUNCH_FINISH(LOGR, false, 2, WT, false);                     \
+    else if (galois == 1) KS_LAUNCH_FINISH(LOGR, false, 1, WT, false);                   \
+    else KS_LAUNCH_FINISH(LOGR, true, 1, WT, false)
 #define KS_LAUNCH(LOGR)                                     \
     if (out_words32) { KS_LAUNCH_MODES(LOGR, uint32_t); }   \
     else { KS_LAUNCH_MODES(LOGR, uint64_t); }

@@ -197,14 +197,23 @@ void launch_bconv_mfma_ntt_cols(const ks_ctx* c, const PlanSet& plans, const uin
                                 uint64_t out_ps, uint32_t n_polys, int tl, hipStream_t s);
 // Upload host plans as a PlanSet (allocates; ks_ctx_create and bconv plan registration only).  Returns a HIP error code.
 hipError_t upload_plans(const BConvPlan* host_plans, uint32_t n_plans, uint32_t shape_src, PlanSet* out);
+// Canonical residues in packed form: bits 0..31 in lo, the bits above (moduli are below 2^36) in hi, both with the
+// element index of the tensor they stand for; 5 bytes a residue instead of 8.  The hoisted rotations keep the finished
+// raised digits ([b][ndig][E][N], what their gathers read) and the ciphertext limbs of their accumulators this way.
+struct PackedDigits {
+    uint32_t* lo;
+    uint8_t* hi;
+};
 // Fused row half of the forward transform of the raised digits + inner product with the key.
 // d_words32 / key_words32: d / the key hold one residue per 32-bit word (d_words32 implies key_words32)
+// accq != nullptr: the first packed_limbs ciphertext limbs of the sums go to accq ([b][2][ell][N], packed) instead of acc.
 void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const void* d, uint64_t d_ps, const uint64_t* lifted,
                                const void* evk, uint64_t* acc, uint32_t batch, hipStream_t s, bool d_words32 = false,
-                               bool key_words32 = false);
+                               bool key_words32 = false, const PackedDigits* accq = nullptr, uint32_t packed_limbs = 0);
 // Fused row half of the forward transform of the converted limbs + (acc - conv) P^-1 (+ addend).
 // fs == nullptr: multiply by P^-1, addend unscaled, ell output limbs.  Otherwise (merged ModDown + rescale): multiply by
 // fs->mul[i], scale the addend by fs->addend_mul[i], and write only the first fs->out_limbs limbs per component.
+// acc_packed: the ciphertext limbs of the accumulator are read from there ([b][2][ell][N]) instead of from acc.
 struct FinishScale {
     const double* mul;
     const double* addend_mul;
@@ -213,7 +222,7 @@ struct FinishScale {
 void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t* acc, const uint64_t* conv, void* out,
                                 uint64_t out_batch_stride, const uint64_t* addend, uint64_t addend_batch_stride,
                                 uint32_t addend_comps, uint32_t galois, uint32_t batch, hipStream_t s,
-                                const FinishScale* fs = nullptr, bool out_words32 = false);
+                                const FinishScale* fs = nullptr, bool out_words32 = false, const PackedDigits* acc_packed = nullptr);
 // acc[b][comp][limb] += mul * addend[b][comp][limb] for one ciphertext limb of both components (canonical in, canonical out)
 void launch_add_scaled_limb(const ks_ctx* c, uint64_t* acc, uint64_t acc_ps, const uint64_t* addend, uint64_t addend_bs,
                             uint64_t addend_comp_stride, uint32_t limb, double mul, uint32_t batch, hipStream_t s);
@@ -238,12 +247,6 @@ struct MacRotations {
     const void* key[kMacRotations];  // [dnum][2][L+K][N], 64- or 32-bit words
     const void* pt[kMacRotations];   // [L+K][N], same word size as the keys
 };
-// Finished raised digits in the packed form the rotation gathers read: bits 0..31 of a canonical residue in lo, the bits
-// above (moduli are below 2^36) in hi, both indexed like the [b][ndig][E][N] bundle; 5 bytes a residue instead of 8.
-struct PackedDigits {
-    uint32_t* lo;
-    uint8_t* hi;
-};
 // What the sigma_g gathers of a rotation read.  hi != nullptr: packed bundle (lo, hi) holding every (digit, position)
 // slot, the digits' own limbs included.  hi == nullptr: lo holds the raised digits as 32-bit words and a digit's own
 // limbs come from the polynomial itself (own, 32-bit words, own_ps words between polynomials).
@@ -263,8 +266,10 @@ void launch_pack_own_limbs(const ks_ctx* c, const Level& lv, const uint64_t* d, 
 // acc[r][b][c][pos] = sum_j sigma_{g_r}(src_j)[pos] * key_r[j][c][ext_id(pos)] for every rotation r of `rot` (pt unused);
 // src_j[pos] = d[b][pos] when pos lies in digit j, otherwise lifted[b][j][pos], both read through `src`.
 // key_words32: keys (and plaintexts) hold one residue per 32-bit word; 32-bit sources imply 32-bit keys.
+// The special limbs of the result go to acc ([r][b][2][E][N], ciphertext limbs left untouched), the ciphertext limbs to
+// accq ([r][b][2][ell][N], packed).
 void launch_inner_product(const ks_ctx* c, const Level& lv, const GatherSources& src, const MacRotations& rot, uint64_t* acc,
-                          uint32_t batch, hipStream_t s, bool key_words32 = false);
+                          const PackedDigits& accq, uint32_t batch, hipStream_t s, bool key_words32 = false);
 
 // u[b][c][pos] (+)= sum_r pt_r[pos] * (sum_j sigma_r(src_j)[pos] key_r[j][c][pos] + [c = 0][pos < ell] P sigma_r(c0)[pos]);
 // ct: [b][2][ell][N] (c0, c1) in 64-bit words with packed sources, in 32-bit words with 32-bit sources (ct_bs in words);

@@ -10,7 +10,7 @@
 namespace {
 
 // One bootstrapping-level ciphertext (N = 2^16, L = 24, K = 8, dnum = 3: coefficient copy 24 limbs, raised digits 96,
-// accumulators 64, converted limbs 48 = 232 limbs of 512 KiB).
+// accumulators 64, converted limbs 48, packed ciphertext limbs of the accumulators 30 = 262 limbs of 512 KiB).
 constexpr size_t kStaticScratchBytes = KS_STATIC_WORKSPACE_BYTES;
 constexpr int kMaxDevices = 64;
 

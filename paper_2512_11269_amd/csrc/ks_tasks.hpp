@@ -236,6 +236,8 @@ __device__ __forceinline__ void task_bconv_mfma_cols(const double* __restrict__ 
 // ---- row half of the forward transform of the raised limbs + inner product with the key (see ks_fused.hip) ----------
 // One wavefront: four rows (group rg) of limb position pos of one batch item.  d_b / lifted_b / acc_b: that batch item's
 // d [ell][N], raised digits [ndig][E][N] and accumulators [2][E][N].  lds_wave: 4 * kRowPitch doubles, lds_ta_wave: 64.
+// accq_lo_b / accq_hi_b, packed_limbs: the first packed_limbs ciphertext limbs of the sums go to that batch item's packed
+// [2][ell][N] accumulator instead of acc_b.
 // WD / WK: word types of d and of the key (64-bit, or 32-bit for moduli below 2^32).
 // PREFETCH (64-bit words only): loads are requested in the order x(0), key(0), x(1), key(1), ... and return in that order.
 // While digit j is transformed, key(j) and x(j + 1) are in flight; every key slot is refilled with the next digit's as soon
@@ -244,7 +246,9 @@ template <int LOG_R, typename WD, typename WK, bool PREFETCH = false>
 __device__ __forceinline__ void task_rows_inner_product(const TwTables& tw, const TwTables& twi, const Mod* __restrict__ mods,
                                                         const DigitRanges& dg, uint32_t ell, uint32_t E, uint32_t L, uint32_t M,
                                                         const WD* __restrict__ d_b, const uint64_t* __restrict__ lifted_b,
-                                                        const WK* __restrict__ evk, uint64_t* __restrict__ acc_b, uint32_t pos,
+                                                        const WK* __restrict__ evk, uint64_t* __restrict__ acc_b,
+                                                        uint32_t* __restrict__ accq_lo_b, uint8_t* __restrict__ accq_hi_b,
+                                                        uint32_t packed_limbs, uint32_t pos,
                                                         uint32_t rg, uint32_t lane, double* lds_wave, double* lds_ta_wave) {
     constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R;
     const uint32_t mid = pos < ell ? pos : L + (pos - ell);
@@ -373,7 +377,19 @@ __device__ __forceinline__ void task_rows_inner_product(const TwTables& tw, cons
         a0[k] = reduce_lazy(a0[k], m);
         a1[k] = reduce_lazy(a1[k], m);
     }
-    if (pos < ell) {  // uniform: ciphertext limbs are kept in evaluation domain for the final subtract-and-scale
+    if (pos < packed_limbs) {
+        // uniform: ciphertext limbs are kept in evaluation domain for the final subtract-and-scale, which is their only
+        // reader: they go out packed, bits 0..31 as a 32-bit word and the bits above as a byte, [2][ell][N] per batch item
+        const uint64_t e0 = (uint64_t)pos * N + off, e1 = e0 + (uint64_t)ell * N;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const uint64_t u0 = f64_to_u64(canon(a0[k], m)), u1 = f64_to_u64(canon(a1[k], m));
+            accq_lo_b[e0 + 16 * k] = (uint32_t)u0;
+            accq_lo_b[e1 + 16 * k] = (uint32_t)u1;
+            accq_hi_b[e0 + 16 * k] = (uint8_t)(u0 >> 32);
+            accq_hi_b[e1 + 16 * k] = (uint8_t)(u1 >> 32);
+        }
+    } else if (pos < ell) {  // uniform: a ciphertext limb that another kernel reads as a 64-bit word
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
             o0[16 * k] = f64_to_u64(canon(a0[k], m));
@@ -397,9 +413,11 @@ __device__ __forceinline__ void task_rows_inner_product(const TwTables& tw, cons
 // ---- row half of the forward transform of the converted limbs + (acc - conv) * mul (+ addend) ------------------------
 // One wavefront: four rows (group rg) of limb i.  src / ap / op: that limb of conv, of the accumulator and of the output;
 // adp: that limb of the addend (ADDEND != 0).  ADDEND: 0 = none, 1 = added as it is, 2 = multiplied by admul first.
-template <int LOG_R, bool GATHER, int ADDEND, typename W>
+// ACCP: the accumulator limb is packed, bits 0..31 as 32-bit words at ap and the bits above as bytes at ap_hi.
+template <int LOG_R, bool GATHER, int ADDEND, typename W, bool ACCP = false>
 __device__ __forceinline__ void task_rows_finish(const TwTables& tw, Mod m, uint32_t mod_id, double mul, double admul,
-                                                 const uint64_t* __restrict__ src, const uint64_t* __restrict__ ap, W* __restrict__ op,
+                                                 const uint64_t* __restrict__ src, const void* __restrict__ ap,
+                                                 const uint8_t* __restrict__ ap_hi, W* __restrict__ op,
                                                  const uint64_t* __restrict__ adp, uint32_t galois, uint32_t rg, uint32_t lane,
                                                  double* lds_wave) {
     constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R, LOGN = LOG_R + 8;
@@ -409,8 +427,18 @@ __device__ __forceinline__ void task_rows_finish(const TwTables& tw, Mod m, uint
     double w[16], a[16], ad[16];
 #pragma unroll
     for (int k = 0; k < 16; ++k) w[k] = load_f64(src + off + 16 * k);
+    if constexpr (ACCP) {
+        uint32_t alo[16], ahi[16];
 #pragma unroll
-    for (int k = 0; k < 16; ++k) a[k] = u64_to_f64(ap[off + 16 * k]);
+        for (int k = 0; k < 16; ++k) alo[k] = static_cast<const uint32_t*>(ap)[off + 16 * k];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) ahi[k] = ap_hi[off + 16 * k];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) a[k] = u64_to_f64((uint64_t)ahi[k] << 32 | alo[k]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) a[k] = u64_to_f64(static_cast<const uint64_t*>(ap)[off + 16 * k]);
+    }
     if constexpr (ADDEND != 0) {
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
