@@ -98,15 +98,18 @@ static double moddown_ops(const ks_ctx* c, const Level& lv) {
 // Division by P of both accumulators, optional addend: INTT of the special limbs (in place), fused base
 // conversion + column half, fused row half + (acc - conv) P^-1.
 // accq: the ciphertext limbs of the accumulators are there, packed, instead of in acc.
+// addend_packed (with accq): the addend is there, [b][2][ell][N] packed (addend_bs in elements), instead of at addend.
 void mod_down(const ks_ctx* c, const Level& lv, uint64_t* acc, uint64_t* conv, void* out, uint64_t out_bs,
               const uint64_t* addend, uint64_t addend_bs, uint32_t addend_comps, uint32_t galois, uint32_t bc,
-              bool special_rows_done, hipStream_t s, bool out_words32 = false, const PackedDigits* accq = nullptr) {
+              bool special_rows_done, hipStream_t s, bool out_words32 = false, const PackedDigits* accq = nullptr,
+              const PackedDigits* addend_packed = nullptr) {
     const uint64_t N = c->N, acc_ps = (uint64_t)lv.E * N, conv_ps = (uint64_t)lv.ell * N;
     // the fused inner product already ran the row half of the inverse transform on the special limbs
     if (!special_rows_done) launch_ntt_inv_rows(c, lv.special_map, XformIO{acc, acc, acc_ps, acc_ps, 2 * bc}, s);
     launch_ntt_inv_cols(c, lv.special_map, acc, acc_ps, 2 * bc, c->d_moddown_scale, true, true, s);
     launch_bconv_ntt_cols(c, lv.moddown, c->K + lv.ell, acc, acc_ps, conv, conv_ps, 2 * bc, s, moddown_ops(c, lv));
-    launch_rows_moddown_finish(c, lv, acc, conv, out, out_bs, addend, addend_bs, addend_comps, galois, bc, s, nullptr, out_words32, accq);
+    launch_rows_moddown_finish(c, lv, acc, conv, out, out_bs, addend, addend_bs, addend_comps, galois, bc, s, nullptr, out_words32, accq,
+                               addend_packed);
 }
 
 }  // namespace
@@ -140,8 +143,8 @@ extern "C" size_t ks_workspace_bytes(const ks_ctx* c, int op, uint32_t ell, uint
         }
         case KS_OP_HMULT_RELIN_RESCALE:
             if (ell < 2) return 0;
-            // tensor product [bc][3][ell], sum [bc][2][ell], last limb [2 bc], spread [2 bc][ell-1]
-            words += (uint64_t)bc * (3 * ell + 2 * ell + 2 + 2 * (ell - 1)) * N;
+            // d2 [bc][ell], (d0, d1) packed like the accumulator limbs, sum [bc][2][ell], last limb [2 bc], spread [2 bc][ell-1]
+            words += (uint64_t)bc * (ell + 2 * ell + 2 + 2 * (ell - 1)) * N + ks_ws_words(c, lv, bc).accq;
             break;
         default: return 0;
     }
@@ -567,18 +570,18 @@ extern "C" int ks_bsgs_linear_transform_u32(const ks_ctx* c, const uint32_t* ct,
 // limb ell-1 joins the special limbs as a source, the targets are q_0..q_{ell-2}.  The fused inner product has already
 // run the row half of the inverse transform on the special limbs.
 // accq: the ciphertext limbs below ell-1 of the accumulators, packed (limb ell-1 is a conversion source and stays in acc).
+// addend: [b][2][ell][N] packed.
 static void mod_down_merged(const ks_ctx* c, const Level& lv, uint64_t* acc, uint64_t* conv, void* out, uint64_t out_bs,
-                            const uint64_t* addend, uint64_t addend_bs, uint32_t bc, hipStream_t s, bool out_words32,
-                            const PackedDigits* accq) {
+                            const PackedDigits& addend, uint32_t bc, hipStream_t s, bool out_words32, const PackedDigits* accq) {
     const uint64_t N = c->N, acc_ps = (uint64_t)lv.E * N, conv_ps = (uint64_t)lv.ell * N;
-    launch_add_scaled_limb(c, acc, acc_ps, addend, addend_bs, (uint64_t)lv.ell * N, lv.ell - 1, lv.Pmod_last, bc, s);
+    launch_add_scaled_limb(c, acc, acc_ps, addend, lv.ell, lv.ell - 1, lv.Pmod_last, bc, s);
     launch_ntt_inv_rows(c, lv.last_map, XformIO{acc, acc, acc_ps, acc_ps, 2 * bc}, s);
     launch_ntt_inv_cols(c, lv.merged_map, acc, acc_ps, 2 * bc, lv.d_merged_scale, true, true, s);
     const uint32_t n_src = c->K + 1, n_dst = lv.ell - 1;
     const double ops = (double)n_src * n_dst * 4.5 + n_dst * (3.0 + 4.0 * (c->logN - 8));
     launch_bconv_ntt_cols(c, lv.merged, n_src + n_dst, acc, acc_ps, conv, conv_ps, 2 * bc, s, ops);
     const FinishScale fs{lv.d_Dinv, lv.d_qlinv, n_dst};
-    launch_rows_moddown_finish(c, lv, acc, conv, out, out_bs, addend, addend_bs, 2, 1, bc, s, &fs, out_words32, accq);
+    launch_rows_moddown_finish(c, lv, acc, conv, out, out_bs, nullptr, 2ull * lv.ell * N, 2, 1, bc, s, &fs, out_words32, accq, &addend);
 }
 
 // cta, ctb, rlk and out in 64-bit words, or all four in 32-bit words (words32); the tensor product and everything after it
@@ -594,7 +597,7 @@ static int hmult_impl(const ks_ctx* c, const void* cta, const void* ctb, uint32_
     const Level& lv = c->levels[ell - 1];
     if (merged && !lv.merged.d_plans) return KS_EINVAL;  // K + 1 sources exceed what one conversion takes
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const uint64_t N = c->N, ct_bs = 2ull * ell * N, td_bs = 3ull * ell * N, out_bs = 2ull * (ell - 1) * N, word = words32 ? 4 : 8;
+    const uint64_t N = c->N, ct_bs = 2ull * ell * N, out_bs = 2ull * (ell - 1) * N, word = words32 ? 4 : 8;
     LimbMap one;
     one.n = 1;
     one.off[0] = 0;
@@ -607,21 +610,22 @@ static int hmult_impl(const ks_ctx* c, const void* cta, const void* ctb, uint32_
         uint64_t* acc = lifted + w.lifted;
         uint64_t* conv = acc + w.acc;
         const PackedDigits accq = packed_at(conv + w.conv, w.conv);
-        uint64_t* td = conv + w.conv + w.accq;                  // [bc][3][ell][N]
-        uint64_t* sum = td + (uint64_t)bc * td_bs;              // [bc][2][ell][N]
+        uint64_t* d2 = conv + w.conv + w.accq;                  // [bc][ell][N], the polynomial that is key-switched
+        const uint64_t d2_ps = (uint64_t)ell * N;
+        const PackedDigits dq = packed_at(d2 + (uint64_t)bc * d2_ps, w.conv);   // (d0, d1): [bc][2][ell][N] packed
+        uint64_t* sum = d2 + (uint64_t)bc * d2_ps + w.accq;     // [bc][2][ell][N]
         uint64_t* last = sum + (uint64_t)bc * ct_bs;            // [2 bc][N]
         uint64_t* spread = last + (uint64_t)bc * 2 * N;         // [2 bc][ell-1][N]
         char* oc = static_cast<char*>(out) + (uint64_t)b0 * out_bs * word;
         launch_tensor_product(c, static_cast<const char*>(cta) + (uint64_t)b0 * ct_bs * word,
-                              static_cast<const char*>(ctb) + (uint64_t)b0 * ct_bs * word, td, ell, bc, s, words32);
-        const uint64_t* d2 = td + 2ull * ell * N;
-        mod_up(c, lv, d2, td_bs, coeff, lifted, bc, s);
-        launch_rows_inner_product(c, lv, d2, td_bs, lifted, rlk, acc, bc, s, false, words32, &accq, merged ? ell - 1 : ell);
+                              static_cast<const char*>(ctb) + (uint64_t)b0 * ct_bs * word, d2, dq, ell, bc, s, words32);
+        mod_up(c, lv, d2, d2_ps, coeff, lifted, bc, s);
+        launch_rows_inner_product(c, lv, d2, d2_ps, lifted, rlk, acc, bc, s, false, words32, &accq, merged ? ell - 1 : ell);
         if (merged) {
-            mod_down_merged(c, lv, acc, conv, oc, out_bs, td, td_bs, bc, s, words32, &accq);
+            mod_down_merged(c, lv, acc, conv, oc, out_bs, dq, bc, s, words32, &accq);
             continue;
         }
-        mod_down(c, lv, acc, conv, sum, ct_bs, td, td_bs, 2, 1, bc, true, s, false, &accq);
+        mod_down(c, lv, acc, conv, sum, ct_bs, nullptr, ct_bs, 2, 1, bc, true, s, false, &accq, &dq);
         // rescale both components: inverse transform of the last limb, centred remainder to every q_i, forward
         // transform, subtract and divide
         launch_ntt_inv_rows(c, one, XformIO{sum + (uint64_t)(ell - 1) * N, last, (uint64_t)ell * N, N, 2 * bc}, s);

@@ -326,33 +326,39 @@ void launch_pack_own_limbs(const ks_ctx* c, const Level& lv, const uint64_t* d, 
     hipLaunchKernelGGL(pack_own_limbs_kernel, dim3(c->N / 256, lv.ell, bc), dim3(256), 0, s, dg, lv.E, c->N, d, d_ps, out.lo, out.hi);
 }
 
-// (b1, a1) x (b2, a2) -> d0 = b1 b2, d1 = a1 b2 + a2 b1, d2 = a1 a2
+// (b1, a1) x (b2, a2) -> d0 = b1 b2, d1 = a1 b2 + a2 b1, d2 = a1 a2.  d2, the polynomial that is key-switched, goes out as
+// 64-bit words ([b][ell][N]); d0 and d1 are only added back by the last kernel of the chain and go out packed
+// ([b][2][ell][N]: bits 0..31 in dq_lo, the bits above in dq_hi).
 template <typename W>
 __global__ __launch_bounds__(256) void tensor_product_kernel(const Mod* __restrict__ mods, uint32_t ell, uint32_t N,
                                                              const W* __restrict__ cta, const W* __restrict__ ctb,
-                                                             uint64_t* __restrict__ td) {
+                                                             uint64_t* __restrict__ d2, uint32_t* __restrict__ dq_lo,
+                                                             uint8_t* __restrict__ dq_hi) {
     const uint32_t i = blockIdx.y, b = blockIdx.z;
     const Mod m = mods[i];
     const uint64_t n = blockIdx.x * 256 + threadIdx.x;
     const uint64_t ct_off = ((uint64_t)b * 2 * ell + i) * N + n, comp = (uint64_t)ell * N;
     const double b1 = word_to_f64<W>(cta[ct_off]), a1 = word_to_f64<W>(cta[ct_off + comp]);
     const double b2 = word_to_f64<W>(ctb[ct_off]), a2 = word_to_f64<W>(ctb[ct_off + comp]);
-    const uint64_t o = ((uint64_t)b * 3 * ell + i) * N + n;
-    td[o] = f64_to_u64(canon(mulmod_lazy(b1, b2, m), m));
-    td[o + comp] = f64_to_u64(canon(reduce_lazy(mulmod_lazy(a1, b2, m) + mulmod_lazy(a2, b1, m), m), m));
-    td[o + 2 * comp] = f64_to_u64(canon(mulmod_lazy(a1, a2, m), m));
+    const uint64_t u0 = f64_to_u64(canon(mulmod_lazy(b1, b2, m), m));
+    const uint64_t u1 = f64_to_u64(canon(reduce_lazy(mulmod_lazy(a1, b2, m) + mulmod_lazy(a2, b1, m), m), m));
+    dq_lo[ct_off] = (uint32_t)u0;
+    dq_hi[ct_off] = (uint8_t)(u0 >> 32);
+    dq_lo[ct_off + comp] = (uint32_t)u1;
+    dq_hi[ct_off + comp] = (uint8_t)(u1 >> 32);
+    d2[((uint64_t)b * ell + i) * N + n] = f64_to_u64(canon(mulmod_lazy(a1, a2, m), m));
 }
 
-void launch_tensor_product(const ks_ctx* c, const void* cta, const void* ctb, uint64_t* td, uint32_t ell, uint32_t batch,
-                           hipStream_t s, bool in_words32) {
+void launch_tensor_product(const ks_ctx* c, const void* cta, const void* ctb, uint64_t* d2, const PackedDigits& dq, uint32_t ell,
+                           uint32_t batch, hipStream_t s, bool in_words32) {
     if (batch == 0) return;
-    ProfScope ps("tensor_product", (double)batch * ell * (in_words32 ? 5 : 7) * c->N * 8.0, s);
+    ProfScope ps("tensor_product", (double)batch * ell * ((in_words32 ? 16 : 32) + 8 + 10) * c->N, s);
     if (in_words32)
         hipLaunchKernelGGL(tensor_product_kernel<uint32_t>, dim3(c->N / 256, ell, batch), dim3(256), 0, s, c->d_mod, ell, c->N,
-                           static_cast<const uint32_t*>(cta), static_cast<const uint32_t*>(ctb), td);
+                           static_cast<const uint32_t*>(cta), static_cast<const uint32_t*>(ctb), d2, dq.lo, dq.hi);
     else
         hipLaunchKernelGGL(tensor_product_kernel<uint64_t>, dim3(c->N / 256, ell, batch), dim3(256), 0, s, c->d_mod, ell, c->N,
-                           static_cast<const uint64_t*>(cta), static_cast<const uint64_t*>(ctb), td);
+                           static_cast<const uint64_t*>(cta), static_cast<const uint64_t*>(ctb), d2, dq.lo, dq.hi);
 }
 
 __global__ __launch_bounds__(256) void widen_u32_kernel(const uint32_t* __restrict__ in, uint64_t* __restrict__ out, uint64_t n) {
@@ -367,25 +373,25 @@ void launch_widen_u32(const uint32_t* in, uint64_t* out, uint64_t n, hipStream_t
 }
 
 // acc[b][comp][limb] = (acc + mul * addend[b][comp][limb]) mod q_limb, canonical: the one ciphertext limb that joins the
-// special limbs as a conversion source when ModDown and rescale are merged.
-__global__ __launch_bounds__(256) void add_scaled_limb_kernel(const Mod* __restrict__ mods, uint32_t limb, double mul, uint32_t N,
-                                                              uint64_t* __restrict__ acc, uint64_t acc_ps,
-                                                              const uint64_t* __restrict__ addend, uint64_t addend_bs,
-                                                              uint64_t addend_cs) {
+// special limbs as a conversion source when ModDown and rescale are merged.  The addend is packed ([b][2][ell][N]).
+__global__ __launch_bounds__(256) void add_scaled_limb_kernel(const Mod* __restrict__ mods, uint32_t limb, double mul, uint32_t ell,
+                                                              uint32_t N, uint64_t* __restrict__ acc, uint64_t acc_ps,
+                                                              const uint32_t* __restrict__ addend_lo,
+                                                              const uint8_t* __restrict__ addend_hi) {
     const Mod m = mods[limb];
-    const uint32_t b = blockIdx.z >> 1, comp = blockIdx.z & 1;
     const uint64_t n = blockIdx.x * 256 + threadIdx.x;
     uint64_t* a = acc + (uint64_t)blockIdx.z * acc_ps + (uint64_t)limb * N + n;
-    const double d = u64_to_f64(addend[(uint64_t)b * addend_bs + comp * addend_cs + (uint64_t)limb * N + n]);
+    const uint64_t e = ((uint64_t)blockIdx.z * ell + limb) * N + n;   // blockIdx.z = 2 b + comp
+    const double d = u64_to_f64((uint64_t)addend_hi[e] << 32 | addend_lo[e]);
     *a = f64_to_u64(canon(reduce_lazy(u64_to_f64(*a) + mulmod_lazy(d, mul, m), m), m));
 }
 
-void launch_add_scaled_limb(const ks_ctx* c, uint64_t* acc, uint64_t acc_ps, const uint64_t* addend, uint64_t addend_bs,
-                            uint64_t addend_comp_stride, uint32_t limb, double mul, uint32_t batch, hipStream_t s) {
+void launch_add_scaled_limb(const ks_ctx* c, uint64_t* acc, uint64_t acc_ps, const PackedDigits& addend, uint32_t ell, uint32_t limb,
+                            double mul, uint32_t batch, hipStream_t s) {
     if (batch == 0) return;
-    ProfScope ps("add_scaled_limb", (double)batch * 2 * 3 * c->N * 8.0, s);
-    hipLaunchKernelGGL(add_scaled_limb_kernel, dim3(c->N / 256, 1, batch * 2), dim3(256), 0, s, c->d_mod, limb, mul, c->N, acc, acc_ps,
-                       addend, addend_bs, addend_comp_stride);
+    ProfScope ps("add_scaled_limb", (double)batch * 2 * (16 + 5) * c->N, s);
+    hipLaunchKernelGGL(add_scaled_limb_kernel, dim3(c->N / 256, 1, batch * 2), dim3(256), 0, s, c->d_mod, limb, mul, ell, c->N, acc,
+                       acc_ps, addend.lo, addend.hi);
 }
 
 }  // namespace ks

@@ -214,6 +214,8 @@ void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const void* d, 
 // fs == nullptr: multiply by P^-1, addend unscaled, ell output limbs.  Otherwise (merged ModDown + rescale): multiply by
 // fs->mul[i], scale the addend by fs->addend_mul[i], and write only the first fs->out_limbs limbs per component.
 // acc_packed: the ciphertext limbs of the accumulator are read from there ([b][2][ell][N]) instead of from acc.
+// addend_packed (with acc_packed, galois == 1): the addend is read from there ([b][2][ell][N], addend_batch_stride in
+// elements) instead of from addend.
 struct FinishScale {
     const double* mul;
     const double* addend_mul;
@@ -222,10 +224,12 @@ struct FinishScale {
 void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t* acc, const uint64_t* conv, void* out,
                                 uint64_t out_batch_stride, const uint64_t* addend, uint64_t addend_batch_stride,
                                 uint32_t addend_comps, uint32_t galois, uint32_t batch, hipStream_t s,
-                                const FinishScale* fs = nullptr, bool out_words32 = false, const PackedDigits* acc_packed = nullptr);
-// acc[b][comp][limb] += mul * addend[b][comp][limb] for one ciphertext limb of both components (canonical in, canonical out)
-void launch_add_scaled_limb(const ks_ctx* c, uint64_t* acc, uint64_t acc_ps, const uint64_t* addend, uint64_t addend_bs,
-                            uint64_t addend_comp_stride, uint32_t limb, double mul, uint32_t batch, hipStream_t s);
+                                const FinishScale* fs = nullptr, bool out_words32 = false, const PackedDigits* acc_packed = nullptr,
+                                const PackedDigits* addend_packed = nullptr);
+// acc[b][comp][limb] += mul * addend[b][comp][limb] for one ciphertext limb of both components (canonical in, canonical
+// out); addend: [b][2][ell][N] packed
+void launch_add_scaled_limb(const ks_ctx* c, uint64_t* acc, uint64_t acc_ps, const PackedDigits& addend, uint32_t ell, uint32_t limb,
+                            double mul, uint32_t batch, hipStream_t s);
 
 // Fused rescale: last = coefficient-domain dropped limb as canonical doubles [polys][N]; spread = scratch
 // [polys][ell-1][N]; out[p][i] = (x[p][i] - NTT(centred last mod q_i)) * q_{ell-1}^-1.
@@ -287,9 +291,9 @@ int keyswitch_impl(const ks_ctx* c, const void* d, uint32_t ell, const void* evk
 // the device current.  Returns a HIP error code.
 hipError_t bind_static_scratch(int device);
 
-// d0 = b1 b2, d1 = a1 b2 + a2 b1, d2 = a1 a2 ; td: [batch][3][ell][N]
-void launch_tensor_product(const ks_ctx* c, const void* cta, const void* ctb, uint64_t* td, uint32_t ell, uint32_t batch,
-                           hipStream_t s, bool in_words32 = false);
+// d0 = b1 b2, d1 = a1 b2 + a2 b1 -> dq [batch][2][ell][N] packed; d2 = a1 a2 -> d2 [batch][ell][N] 64-bit words
+void launch_tensor_product(const ks_ctx* c, const void* cta, const void* ctb, uint64_t* d2, const PackedDigits& dq, uint32_t ell,
+                           uint32_t batch, hipStream_t s, bool in_words32 = false);
 // out[i] = in[i] for n 32-bit words -> 64-bit words (ciphertexts handed over in 32-bit words are widened once per chunk;
 // the large tensors of those calls -- keys, plaintexts, results -- are read and written in 32 bits by the kernels)
 void launch_widen_u32(const uint32_t* in, uint64_t* out, uint64_t n, hipStream_t s);

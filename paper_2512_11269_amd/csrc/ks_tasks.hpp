@@ -414,12 +414,13 @@ __device__ __forceinline__ void task_rows_inner_product(const TwTables& tw, cons
 // One wavefront: four rows (group rg) of limb i.  src / ap / op: that limb of conv, of the accumulator and of the output;
 // adp: that limb of the addend (ADDEND != 0).  ADDEND: 0 = none, 1 = added as it is, 2 = multiplied by admul first.
 // ACCP: the accumulator limb is packed, bits 0..31 as 32-bit words at ap and the bits above as bytes at ap_hi.
-template <int LOG_R, bool GATHER, int ADDEND, typename W, bool ACCP = false>
+// ADP: the same for the addend limb (adp, adp_hi).
+template <int LOG_R, bool GATHER, int ADDEND, typename W, bool ACCP = false, bool ADP = false>
 __device__ __forceinline__ void task_rows_finish(const TwTables& tw, Mod m, uint32_t mod_id, double mul, double admul,
                                                  const uint64_t* __restrict__ src, const void* __restrict__ ap,
                                                  const uint8_t* __restrict__ ap_hi, W* __restrict__ op,
-                                                 const uint64_t* __restrict__ adp, uint32_t galois, uint32_t rg, uint32_t lane,
-                                                 double* lds_wave) {
+                                                 const void* __restrict__ adp, const uint8_t* __restrict__ adp_hi,
+                                                 uint32_t galois, uint32_t rg, uint32_t lane, double* lds_wave) {
     constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R, LOGN = LOG_R + 8;
     const uint32_t j0 = lane & 15, rr = lane >> 4, row = rg * 4 + rr;
     const uint32_t off = row * 256 + j0;
@@ -439,11 +440,20 @@ __device__ __forceinline__ void task_rows_finish(const TwTables& tw, Mod m, uint
 #pragma unroll
         for (int k = 0; k < 16; ++k) a[k] = u64_to_f64(static_cast<const uint64_t*>(ap)[off + 16 * k]);
     }
-    if constexpr (ADDEND != 0) {
+    if constexpr (ADDEND != 0 && ADP) {
+        static_assert(!GATHER || !ADP, "a packed addend is read in place");
+        uint32_t dlo[16], dhi[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) dlo[k] = static_cast<const uint32_t*>(adp)[off + 16 * k];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) dhi[k] = adp_hi[off + 16 * k];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) ad[k] = u64_to_f64((uint64_t)dhi[k] << 32 | dlo[k]);
+    } else if constexpr (ADDEND != 0) {
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
             const uint32_t n = off + 16 * k;
-            ad[k] = u64_to_f64(adp[GATHER ? galois_source_slot(n, galois, LOGN) : n]);
+            ad[k] = u64_to_f64(static_cast<const uint64_t*>(adp)[GATHER ? galois_source_slot(n, galois, LOGN) : n]);
         }
     }
     PassTwiddles t;
