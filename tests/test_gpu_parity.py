@@ -335,6 +335,50 @@ def test_hmult_llm_shape():
     assert_equal(out, st.ref.hmult_relin_rescale(host(cta), host(ctb), host(rlk), 35))
 
 
+def _boundary_residues(st, seed, lead, ids):
+    """Residues drawn from the values around the cut of the packed 32 + 8 bit form (and the ends of the range):
+    0, 1, 2^32 - 1, 2^32, 2^32 + 1, m - 2, m - 1 of each limb's modulus m."""
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    mods = torch.tensor([st.moduli[i] for i in ids], dtype=torch.int64)
+    table = torch.stack([torch.zeros_like(mods), torch.ones_like(mods), torch.full_like(mods, 2**32 - 1), torch.full_like(mods, 2**32),
+                         torch.full_like(mods, 2**32 + 1), mods - 2, mods - 1])          # [7][limbs]
+    pick = torch.randint(0, 7, (*lead, len(ids), st.N), generator=g)
+    limb = torch.arange(len(ids)).view(*([1] * len(lead)), len(ids), 1).expand_as(pick)
+    return table[pick, limb].contiguous().cuda()
+
+
+def test_pipelines_with_residues_at_the_packed_word_boundaries(small):
+    """Intermediate tensors cross memory as a 32-bit word plus a byte per residue: inputs made of the values on both sides
+    of that cut, through every pipeline that uses the packed form."""
+    st, ell, batch = small, 4, 3
+    assert min(st.moduli) > 2**32 + 1
+    all_ids, ct_ids = list(range(st.L + st.K)), list(range(ell))
+    d = _boundary_residues(st, 1, (batch,), ct_ids)
+    evk = _boundary_residues(st, 2, (st.ctx.dnum, 2), all_ids)
+    out = torch.empty((batch, 2, ell, st.N), dtype=torch.int64, device="cuda")
+    K.ks_keyswitch(st.ctx, d, ell, evk, out, workspace(st.ctx, K.KS_OP_KEYSWITCH, ell, batch))
+    assert_equal(out, st.ref.keyswitch(host(d), host(evk), ell))
+
+    cta, ctb = _boundary_residues(st, 3, (batch, 2), ct_ids), _boundary_residues(st, 4, (batch, 2), ct_ids)
+    for merged in (False, True):
+        got = torch.empty((batch, 2, ell - 1, st.N), dtype=torch.int64, device="cuda")
+        (K.hmult_relin_rescale_merged if merged else K.hmult_relin_rescale)(st.ctx, cta, ctb, ell, evk, got,
+                                                                            workspace(st.ctx, K.KS_OP_HMULT_RELIN_RESCALE, ell, batch))
+        ref = st.ref.hmult_relin_rescale_merged if merged else st.ref.hmult_relin_rescale
+        assert_equal(got, ref(host(cta), host(ctb), host(evk), ell))
+
+    n_rot = 3
+    galois = ks_inputs.galois_elements(st.logN, n_rot)
+    keys = [_boundary_residues(st, 10 + r, (st.ctx.dnum, 2), all_ids) for r in range(n_rot)]
+    pts = [_boundary_residues(st, 20 + r, (), all_ids) for r in range(n_rot)]
+    rot = torch.empty((batch, n_rot, 2, ell, st.N), dtype=torch.int64, device="cuda")
+    K.ks_rotate_hoisted(st.ctx, cta, ell, galois, keys, rot, workspace(st.ctx, K.KS_OP_ROTATE_HOISTED, ell, batch, n_rot))
+    assert_equal(rot, st.ref.rotate_hoisted(host(cta), galois, [host(k) for k in keys], ell))
+    mac = torch.empty((batch, 2, ell, st.N), dtype=torch.int64, device="cuda")
+    K.ks_rotate_mac_hoisted(st.ctx, cta, ell, galois, keys, pts, mac, workspace(st.ctx, K.KS_OP_ROTATE_HOISTED, ell, batch, n_rot))
+    assert_equal(mac, st.ref.rotate_mac_hoisted(host(cta), galois, [host(k) for k in keys], [host(w) for w in pts], ell))
+
+
 def test_error_paths_return_codes(small):
     lib = K.load_library()
     ell = 4
