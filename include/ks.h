@@ -221,8 +221,7 @@ int hmult_relin_rescale_merged(const ks_ctx* ctx, const uint64_t* cta, const uin
  * raised digits as 32-bit words (their kernels are bound by re-reading them; the 64-bit rotation calls keep them as a
  * 32-bit word plus a byte).  Every call returns KS_EINVAL unless every modulus
  * of the context is below 2^32.  Workspace: the operation code of the 64-bit call, except that the two rotation calls
- * take KS_OP_ROTATE_HOISTED_U32 and the BSGS transform KS_OP_BSGS_U32 (room for the 32-bit raised digits and, for
- * ks_rotate_hoisted_u32, a widened copy of a chunk's ciphertexts).
+ * take KS_OP_ROTATE_HOISTED_U32 and the BSGS transform KS_OP_BSGS_U32 (the room their 32-bit raised digits take).
  *   ntt_fwd_u32 / ntt_inv_u32 : in place on [batch][nlimbs][N] uint32_t.
  *   bconv_u32                 : pairs registered with bconv_prepare serve both word sizes. */
 int ntt_fwd_u32(const ks_ctx* ctx, uint32_t* data, const uint32_t* mod_ids, uint32_t nlimbs, uint32_t batch, void* stream);

@@ -127,11 +127,9 @@ extern "C" size_t ks_workspace_bytes(const ks_ctx* c, int op, uint32_t ell, uint
             if (n_rot == 0) return 0;
             // accumulators and converted limbs for a whole group of rotations
             words += (uint64_t)(std::min(n_rot, kRotGroup) - 1) * bc * (2 * lv.E + 2 * ell) * N;
-            // the gathers' sources; the ciphertext limbs of a group's accumulators, packed; 32-bit words: also the chunk's
-            // ciphertexts widened to 64-bit words
+            // the gathers' sources; the ciphertext limbs of a group's accumulators, packed
             words += gather_words(ks_ws_words(c, lv, bc), op == KS_OP_ROTATE_HOISTED_U32);
             words += (uint64_t)(std::min(n_rot, kRotGroup) - 1) * ks_ws_words(c, lv, bc).accq;
-            if (op == KS_OP_ROTATE_HOISTED_U32) words += (uint64_t)bc * 2 * ell * N;
             break;
         case KS_OP_BSGS:
         case KS_OP_BSGS_U32: {
@@ -365,20 +363,12 @@ static int rotate_hoisted_impl(const ks_ctx* c, const void* ct, uint32_t ell, co
         const uint32_t bc = std::min(batch - b0, kChunk);
         const KsWorkspace w = ks_ws_words(c, lv, bc);
         // The gathers read c1 and its finished raised digits in a compact form (32-bit words, or 32-bit low words plus
-        // high bytes for 64-bit operands: their traffic bounds the gather kernels); with 32-bit words the last kernel's
-        // addend c0 is wanted in 64-bit words and comes from a widened copy.
+        // high bytes for 64-bit operands: their traffic bounds the gather kernels); the last kernel's addend c0 is gathered
+        // from the ciphertext in its own word size.
         uint64_t* region = static_cast<uint64_t*>(ws);
         uint64_t* coeff = region + gather_words(w, words32);
-        const uint64_t* c0 = static_cast<const uint64_t*>(ct) + (uint64_t)b0 * ct_bs;
-        const void* c1 = c0 + (uint64_t)ell * N;
-        if (words32) {
-            const uint32_t* ct32 = static_cast<const uint32_t*>(ct) + (uint64_t)b0 * ct_bs;
-            uint64_t* wide = coeff;
-            launch_widen_u32(ct32, wide, (uint64_t)bc * ct_bs, s);
-            coeff = wide + (uint64_t)bc * ct_bs;
-            c0 = wide;
-            c1 = ct32 + (uint64_t)ell * N;
-        }
+        const char* c0 = static_cast<const char*>(ct) + (uint64_t)b0 * ct_bs * word;
+        const void* c1 = c0 + (uint64_t)ell * N * word;
         uint64_t* lifted = coeff + w.coeff;
         uint64_t* acc = lifted + w.lifted;
         // finished once, shared by every rotation
@@ -409,7 +399,7 @@ static int rotate_hoisted_impl(const ks_ctx* c, const void* ct, uint32_t ell, co
                 const PackedDigits accq_r{accq.lo + (uint64_t)r * accq_n, accq.hi + (uint64_t)r * accq_n};
                 launch_rows_moddown_finish(c, lv, nullptr, conv + (uint64_t)r * w.conv,
                                            static_cast<char*>(out) + ((uint64_t)b0 * out_bs + (uint64_t)(r0 + r) * 2 * ell * N) * word,
-                                           out_bs, c0, ct_bs, 1, galois[r0 + r], bc, s, nullptr, words32, &accq_r);
+                                           out_bs, c0, ct_bs, 1, galois[r0 + r], bc, s, nullptr, words32, &accq_r, nullptr, words32);
             }
         }
     }

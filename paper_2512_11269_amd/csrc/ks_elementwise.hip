@@ -361,17 +361,6 @@ void launch_tensor_product(const ks_ctx* c, const void* cta, const void* ctb, ui
                            static_cast<const uint64_t*>(cta), static_cast<const uint64_t*>(ctb), d2, dq.lo, dq.hi);
 }
 
-__global__ __launch_bounds__(256) void widen_u32_kernel(const uint32_t* __restrict__ in, uint64_t* __restrict__ out, uint64_t n) {
-    const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < n) out[i] = in[i];
-}
-
-void launch_widen_u32(const uint32_t* in, uint64_t* out, uint64_t n, hipStream_t s) {
-    if (n == 0) return;
-    ProfScope ps("widen_u32", (double)n * 12.0, s);
-    hipLaunchKernelGGL(widen_u32_kernel, dim3((uint32_t)((n + 255) / 256)), dim3(256), 0, s, in, out, n);
-}
-
 // acc[b][comp][limb] = (acc + mul * addend[b][comp][limb]) mod q_limb, canonical: the one ciphertext limb that joins the
 // special limbs as a conversion source when ModDown and rescale are merged.  The addend is packed ([b][2][ell][N]).
 __global__ __launch_bounds__(256) void add_scaled_limb_kernel(const Mod* __restrict__ mods, uint32_t limb, double mul, uint32_t ell,

@@ -321,8 +321,9 @@ void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const void* d, 
 // components comp0 .. comp0 + n_comps - 1 of every batch item.
 // ACCP: the ciphertext limbs of the accumulator come packed (acc: [b][2][ell][N] 32-bit low words, acc_hi: the bytes
 // above) instead of as the first ell limbs of [b][2][E][N] 64-bit words.
-// ADP: the addend comes packed the same way (addend: [b][2][ell][N] low words, addend_hi: the bytes above).
-template <int LOG_R, bool GATHER, int ADDEND, typename W = uint64_t, bool ACCP = false, bool ADP = false>
+// ADF: format of the addend: 0 = 64-bit words; 1 = packed the same way (addend: [b][2][ell][N] low words, addend_hi: the
+// bytes above); 2 = 32-bit words.
+template <int LOG_R, bool GATHER, int ADDEND, typename W = uint64_t, bool ACCP = false, int ADF = 0>
 __global__ __launch_bounds__(64) void rows_moddown_finish(TwTables tw, const Mod* __restrict__ mods,
                                                           const double* __restrict__ Pinv, const double* __restrict__ addend_mul,
                                                           uint32_t ell, uint32_t E, uint32_t out_limbs,
@@ -343,9 +344,11 @@ __global__ __launch_bounds__(64) void rows_moddown_finish(TwTables tw, const Mod
     double admul = 0.0;
     if constexpr (ADDEND != 0) {
         const uint64_t ad_off = (uint64_t)b * addend_bs + ((uint64_t)comp * ell + i) * N;
-        if constexpr (ADP) {
+        if constexpr (ADF == 1) {
             adp = static_cast<const uint32_t*>(addend) + ad_off;
             adp_hi = addend_hi + ad_off;
+        } else if constexpr (ADF == 2) {
+            adp = static_cast<const uint32_t*>(addend) + ad_off;
         } else {
             adp = static_cast<const uint64_t*>(addend) + ad_off;
         }
@@ -360,17 +363,17 @@ __global__ __launch_bounds__(64) void rows_moddown_finish(TwTables tw, const Mod
     } else {
         ap = static_cast<const uint64_t*>(acc) + (((uint64_t)b * 2 + comp) * E + i) * N;
     }
-    task_rows_finish<LOG_R, GATHER, ADDEND, W, ACCP, ADP>(tw, mods[i], i, Pinv[i], admul, conv + conv_off, ap, ap_hi,
+    task_rows_finish<LOG_R, GATHER, ADDEND, W, ACCP, ADF>(tw, mods[i], i, Pinv[i], admul, conv + conv_off, ap, ap_hi,
                                                           out + (uint64_t)b * out_bs + ((uint64_t)comp * out_limbs + i) * N, adp,
                                                           adp_hi, galois, rg, threadIdx.x, lds);
 }
 
 void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t* acc, const uint64_t* conv, void* out_words,
-                                uint64_t out_bs, const uint64_t* addend, uint64_t addend_bs, uint32_t addend_comps,
+                                uint64_t out_bs, const void* addend, uint64_t addend_bs, uint32_t addend_comps,
                                 uint32_t galois, uint32_t batch, hipStream_t s, const FinishScale* fs, bool out_words32,
-                                const PackedDigits* acc_packed, const PackedDigits* addend_packed) {
+                                const PackedDigits* acc_packed, const PackedDigits* addend_packed, bool addend_words32) {
     if (batch == 0) return;
-    const void* addend_p = addend_packed ? static_cast<const void*>(addend_packed->lo) : static_cast<const void*>(addend);
+    const void* addend_p = addend_packed ? static_cast<const void*>(addend_packed->lo) : addend;
     const uint8_t* addend_h = addend_packed ? addend_packed->hi : nullptr;
     const double* mul = fs ? fs->mul : c->d_Pinv;
     const double* admul = fs ? fs->addend_mul : nullptr;
@@ -379,7 +382,7 @@ void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t
     if (!addend_p) addend_comps = 0;
     ProfScope ps("rows_moddown_finish",
                  (double)batch * out_limbs *
-                     (2 * 8 + 2 * (acc_packed ? 5 : 8) + (out_words32 ? 1 : 2) * 8 + addend_comps * (addend_packed ? 5 : 8)) * c->N,
+                     (2 * 8 + 2 * (acc_packed ? 5 : 8) + (out_words32 ? 1 : 2) * 8 + addend_comps * (addend_packed ? 5 : addend_words32 ? 4 : 8)) * c->N,
                  s);
     const dim3 block(64);
     const uint32_t row_groups = c->N / 1024;
@@ -391,15 +394,20 @@ void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t
         if (n_comps == 0) continue;
         const int mode = pass == 1 ? 0 : (admul ? 2 : 1);
         const dim3 grid(row_groups, out_limbs, batch * n_comps);
-#define KS_LAUNCH_FINISH_P(LOGR, GATHER, MODE, WT, ACCP, ADP)                                                                      \
-    hipLaunchKernelGGL((rows_moddown_finish<LOGR, GATHER, MODE, WT, ACCP, ADP>), grid, block, 0, s, c->tw_fwd, c->d_mod, mul, admul, \
+#define KS_LAUNCH_FINISH_P(LOGR, GATHER, MODE, WT, ACCP, ADF)                                                                      \
+    hipLaunchKernelGGL((rows_moddown_finish<LOGR, GATHER, MODE, WT, ACCP, ADF>), grid, block, 0, s, c->tw_fwd, c->d_mod, mul, admul, \
                        lv.ell, lv.E, out_limbs, accp, acch, conv, static_cast<WT*>(out_words), out_bs, addend_p, addend_h, addend_bs, \
                        comp0, n_comps, galois)
-#define KS_LAUNCH_FINISH(LOGR, GATHER, MODE, WT, ACCP) KS_LAUNCH_FINISH_P(LOGR, GATHER, MODE, WT, ACCP, false)
+#define KS_LAUNCH_FINISH(LOGR, GATHER, MODE, WT, ACCP) KS_LAUNCH_FINISH_P(LOGR, GATHER, MODE, WT, ACCP, 0)
+    // a packed addend comes with a packed accumulator (multiplications); an addend in 32-bit words with a packed accumulator
+    // and 32-bit output (hoisted rotations in 32-bit words)
 #define KS_LAUNCH_MODES(LOGR, WT)                                                        \
     if (addend_packed && mode != 0) {                                                    \
-        if (mode == 2) KS_LAUNCH_FINISH_P(LOGR, false, 2, WT, true, true);               \
-        else KS_LAUNCH_FINISH_P(LOGR, false, 1, WT, true, true);                         \
+        if (mode == 2) KS_LAUNCH_FINISH_P(LOGR, false, 2, WT, true, 1);                  \
+        else KS_LAUNCH_FINISH_P(LOGR, false, 1, WT, true, 1);                            \
+    } else if (addend_words32 && mode != 0) {                                            \
+        if (galois == 1) KS_LAUNCH_FINISH_P(LOGR, false, 1, uint32_t, true, 2);          \
+        else KS_LAUNCH_FINISH_P(LOGR, true, 1, uint32_t, true, 2);                       \
     } else if (acc_packed) {                                                             \
         if (mode == 0) KS_LAUNCH_FINISH(LOGR, false, 0, WT, true);                       \
         else if (mode == 2) KS_LAUNCH_FINISH(LOGR, false, 2, WT, true);                  \

@@ -215,17 +215,17 @@ void launch_rows_inner_product(const ks_ctx* c, const Level& lv, const void* d, 
 // fs->mul[i], scale the addend by fs->addend_mul[i], and write only the first fs->out_limbs limbs per component.
 // acc_packed: the ciphertext limbs of the accumulator are read from there ([b][2][ell][N]) instead of from acc.
 // addend_packed (with acc_packed, galois == 1): the addend is read from there ([b][2][ell][N], addend_batch_stride in
-// elements) instead of from addend.
+// elements) instead of from addend.  addend_words32 (with acc_packed and out_words32): addend holds 32-bit words.
 struct FinishScale {
     const double* mul;
     const double* addend_mul;
     uint32_t out_limbs;
 };
 void launch_rows_moddown_finish(const ks_ctx* c, const Level& lv, const uint64_t* acc, const uint64_t* conv, void* out,
-                                uint64_t out_batch_stride, const uint64_t* addend, uint64_t addend_batch_stride,
+                                uint64_t out_batch_stride, const void* addend, uint64_t addend_batch_stride,
                                 uint32_t addend_comps, uint32_t galois, uint32_t batch, hipStream_t s,
                                 const FinishScale* fs = nullptr, bool out_words32 = false, const PackedDigits* acc_packed = nullptr,
-                                const PackedDigits* addend_packed = nullptr);
+                                const PackedDigits* addend_packed = nullptr, bool addend_words32 = false);
 // acc[b][comp][limb] += mul * addend[b][comp][limb] for one ciphertext limb of both components (canonical in, canonical
 // out); addend: [b][2][ell][N] packed
 void launch_add_scaled_limb(const ks_ctx* c, uint64_t* acc, uint64_t acc_ps, const PackedDigits& addend, uint32_t ell, uint32_t limb,
@@ -294,8 +294,4 @@ hipError_t bind_static_scratch(int device);
 // d0 = b1 b2, d1 = a1 b2 + a2 b1 -> dq [batch][2][ell][N] packed; d2 = a1 a2 -> d2 [batch][ell][N] 64-bit words
 void launch_tensor_product(const ks_ctx* c, const void* cta, const void* ctb, uint64_t* d2, const PackedDigits& dq, uint32_t ell,
                            uint32_t batch, hipStream_t s, bool in_words32 = false);
-// out[i] = in[i] for n 32-bit words -> 64-bit words (ciphertexts handed over in 32-bit words are widened once per chunk;
-// the large tensors of those calls -- keys, plaintexts, results -- are read and written in 32 bits by the kernels)
-void launch_widen_u32(const uint32_t* in, uint64_t* out, uint64_t n, hipStream_t s);
-
 }  // namespace ks

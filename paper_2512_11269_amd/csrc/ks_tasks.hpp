@@ -414,8 +414,9 @@ __device__ __forceinline__ void task_rows_inner_product(const TwTables& tw, cons
 // One wavefront: four rows (group rg) of limb i.  src / ap / op: that limb of conv, of the accumulator and of the output;
 // adp: that limb of the addend (ADDEND != 0).  ADDEND: 0 = none, 1 = added as it is, 2 = multiplied by admul first.
 // ACCP: the accumulator limb is packed, bits 0..31 as 32-bit words at ap and the bits above as bytes at ap_hi.
-// ADP: the same for the addend limb (adp, adp_hi).
-template <int LOG_R, bool GATHER, int ADDEND, typename W, bool ACCP = false, bool ADP = false>
+// ADF: format of the addend limb: 0 = 64-bit words, 1 = packed like the accumulator (adp, adp_hi; read in place only),
+// 2 = 32-bit words.
+template <int LOG_R, bool GATHER, int ADDEND, typename W, bool ACCP = false, int ADF = 0>
 __device__ __forceinline__ void task_rows_finish(const TwTables& tw, Mod m, uint32_t mod_id, double mul, double admul,
                                                  const uint64_t* __restrict__ src, const void* __restrict__ ap,
                                                  const uint8_t* __restrict__ ap_hi, W* __restrict__ op,
@@ -440,8 +441,8 @@ __device__ __forceinline__ void task_rows_finish(const TwTables& tw, Mod m, uint
 #pragma unroll
         for (int k = 0; k < 16; ++k) a[k] = u64_to_f64(static_cast<const uint64_t*>(ap)[off + 16 * k]);
     }
-    if constexpr (ADDEND != 0 && ADP) {
-        static_assert(!GATHER || !ADP, "a packed addend is read in place");
+    if constexpr (ADDEND != 0 && ADF == 1) {
+        static_assert(!GATHER || ADF != 1, "a packed addend is read in place");
         uint32_t dlo[16], dhi[16];
 #pragma unroll
         for (int k = 0; k < 16; ++k) dlo[k] = static_cast<const uint32_t*>(adp)[off + 16 * k];
@@ -453,7 +454,9 @@ __device__ __forceinline__ void task_rows_finish(const TwTables& tw, Mod m, uint
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
             const uint32_t n = off + 16 * k;
-            ad[k] = u64_to_f64(static_cast<const uint64_t*>(adp)[GATHER ? galois_source_slot(n, galois, LOGN) : n]);
+            const uint32_t sn = GATHER ? galois_source_slot(n, galois, LOGN) : n;
+            if constexpr (ADF == 2) ad[k] = (double)static_cast<const uint32_t*>(adp)[sn];
+            else ad[k] = u64_to_f64(static_cast<const uint64_t*>(adp)[sn]);
         }
     }
     PassTwiddles t;

@@ -200,7 +200,9 @@ def test_cfg3_rotations_full_size_32bit_words():
     pts = [st.uniform(seed, 100 + r, (), list(range(ell + cfg["K"]))) for r in range(n_rot)]
     galois = ks_inputs.galois_elements(cfg["logN"], n_rot)
     ct32, keys32, pts32 = _narrow(ct), [_narrow(k) for k in keys], [_narrow(w) for w in pts]
-    ws = workspace(st.ctx, K.KS_OP_ROTATE_HOISTED_U32, ell, B, n_rot)
+    # one workspace for the 32-bit and the 64-bit entry points: the larger of the two
+    op = max((K.KS_OP_ROTATE_HOISTED_U32, K.KS_OP_ROTATE_HOISTED), key=lambda o: K.ks_workspace_bytes(st.ctx, o, ell, B, n_rot))
+    ws = workspace(st.ctx, op, ell, B, n_rot)
     # hoisted rotations: 12 GiB of results in 32-bit words
     out32 = torch.empty((B, n_rot, 2, ell, st.N), dtype=torch.int32, device="cuda")
     K.ks_rotate_hoisted_u32(st.ctx, ct32, ell, galois, keys32, out32, ws)
