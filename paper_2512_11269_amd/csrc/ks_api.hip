@@ -73,21 +73,17 @@ void mod_up(const ks_ctx* c, const Level& lv, const void* d, uint64_t d_ps, uint
 // 32-bit low words plus high bytes, own limbs included (64-bit operands).
 static uint64_t gather_words(const KsWorkspace& w, bool words32) { return (w.lifted + 1) / 2 + (words32 ? 0 : (w.lifted + 7) / 8); }
 
-// mod_up finished for the rotation gathers: the raised digits end as canonical evaluation-domain residues in `region`
-// (gather_words() words), in the form the gathers read.  `lifted` is only scratch here.
+// mod_up finished for the rotation gathers: `region` (gather_words() words) ends as the bundle the gathers read, the
+// raised digits as canonical evaluation-domain residues and d's own limbs in their digits' slots, 32-bit words (words32)
+// or packed.  `lifted` is only scratch here.
 static GatherSources mod_up_for_gather(const ks_ctx* c, const Level& lv, const void* d, uint64_t d_ps, uint64_t* coeff,
                                        uint64_t* lifted, uint64_t* region, uint32_t bc, hipStream_t s, bool words32) {
     mod_up(c, lv, d, d_ps, coeff, lifted, bc, s, words32);
-    const uint64_t lifted_ps = (uint64_t)lv.ndig * lv.E * c->N, lifted_words = (uint64_t)bc * lifted_ps;
-    uint32_t* lo = reinterpret_cast<uint32_t*>(region);
-    if (words32) {
-        launch_ntt_fwd_rows_to(c, lv.lifted_map, lifted, lifted_ps, lo, lifted_ps, bc, s, true);
-        return GatherSources{lo, nullptr, static_cast<const uint32_t*>(d), d_ps};
-    }
-    const PackedDigits pk{lo, reinterpret_cast<uint8_t*>(region + (lifted_words + 1) / 2)};
-    launch_ntt_fwd_rows_packed(c, lv.lifted_map, lifted, lifted_ps, pk, bc, s);
-    launch_pack_own_limbs(c, lv, static_cast<const uint64_t*>(d), d_ps, pk, bc, s);
-    return GatherSources{pk.lo, pk.hi, nullptr, 0};
+    const uint64_t lifted_words = (uint64_t)bc * lv.ndig * lv.E * c->N;
+    const PackedDigits bundle{reinterpret_cast<uint32_t*>(region),
+                              words32 ? nullptr : reinterpret_cast<uint8_t*>(region + (lifted_words + 1) / 2)};
+    launch_gather_bundle_rows(c, lv, lifted, d, d_ps, words32, bundle, bc, s);
+    return GatherSources{bundle.lo, bundle.hi};
 }
 
 // algorithmic fp64 work per coefficient of the ModDown conversion + column half (see mod_up)
@@ -529,7 +525,7 @@ static int bsgs_impl(const ks_ctx* c, const void* ct, uint32_t ell, const uint32
             mod_down(c, lv, acc, conv, v, ct_bs, nullptr, 0, 0, 1, bc, false, s);
             if (giant_galois[g] != 1) digits_v = mod_up_for_gather(c, lv, v + (uint64_t)ell * N, ct_bs, coeff, lifted, region_v, bc, s, false);
             // Galois element 1 gathers nothing; the packed form still says that v holds 64-bit words
-            else digits_v = GatherSources{reinterpret_cast<const uint32_t*>(region_v), reinterpret_cast<const uint8_t*>(region_v), nullptr, 0};
+            else digits_v = GatherSources{reinterpret_cast<const uint32_t*>(region_v), reinterpret_cast<const uint8_t*>(region_v)};
             rotate_mac_all(c, lv, v, ct_bs, digits_v, giant_galois + g, gkeys + g, nullptr, 1, acc_outer, bc, g != 0, s, words32);
         }
         mod_down(c, lv, acc_outer, conv, static_cast<char*>(out) + (uint64_t)b0 * ct_bs * word, ct_bs, nullptr, 0, 0, 1, bc, false, s,

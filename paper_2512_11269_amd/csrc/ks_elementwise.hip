@@ -8,41 +8,46 @@ namespace ks {
 
 constexpr int kBatchGroup = 8;  // batch items sharing one read of the key slots
 
-// What a gather reads for one (ciphertext, digit) at this limb position.  PACKED: bits 0..31 of the residue from a 32-bit
-// word array and the bits above from a byte array (5 bytes a residue); otherwise one 32-bit word.  These kernels are
-// bound by the gather traffic (every rotation re-reads all raised digits of the chunk), so the bytes per residue are
-// what sets their speed.
-template <bool PACKED>
-struct SrcPtr {
-    const uint32_t* lo;
+// What a gather reads for one (ciphertext, digit) at this limb position: a slot of the bundle [b][ndig][E][N] that holds
+// the finished raised digits and, in the slots of a digit's own positions, the limbs of the polynomial itself.  PACKED:
+// bits 0..31 of the residue from a 32-bit word array and the bits above from a byte array (5 bytes a residue); otherwise
+// one 32-bit word.  These kernels are bound by the gather traffic (every rotation re-reads all raised digits of the
+// chunk), so the bytes per residue are what sets their speed.
+// A thread keeps one source per (ciphertext of its group, digit).  As pointers they would be one or two 64-bit scalars
+// each, up to 48 pairs for three digits: more than the scalar register file holds beside everything else, and the spills
+// made rotate_mac 201 vector registers wide.  So there is ONE pair of base pointers (the bundle slice of the thread's
+// ciphertext group) and a 32-bit element offset per source; a load's address is base + 32-bit offset.
+struct SrcBases {
+    const char* lo;
     const uint8_t* hi;
 };
 template <bool PACKED>
 struct SrcRaw {
     uint32_t lo, hi;
 };
+// e: element offset from the group's bases; below 2^30 (8 ciphertexts x 8 digits x 255 limbs x 2^16)
 template <bool PACKED>
-__device__ __forceinline__ SrcRaw<PACKED> src_load(const SrcPtr<PACKED>& p, uint32_t sn) {
+__device__ __forceinline__ SrcRaw<PACKED> src_load(const SrcBases& g, uint32_t e, uint32_t sn) {
+    const uint32_t i = e + sn;
     SrcRaw<PACKED> r;
-    r.lo = p.lo[sn];
-    r.hi = PACKED ? p.hi[sn] : 0u;
+    r.lo = *reinterpret_cast<const uint32_t*>(g.lo + (i << 2));
+    r.hi = PACKED ? g.hi[i] : 0u;
     return r;
 }
 template <bool PACKED>
 __device__ __forceinline__ double src_f64(const SrcRaw<PACKED>& r) {
     return PACKED ? u64_to_f64((uint64_t)r.hi << 32 | r.lo) : (double)r.lo;
 }
-// Start of the sources of (ciphertext b, digit j) at limb position pos.  Packed bundles hold every (digit, position)
-// slot; with 32-bit words the digit's own limbs are read from the polynomial itself.
+// The bundle slice of the ciphertext group that starts at batch item b_lo.
 template <bool PACKED>
-__device__ __forceinline__ SrcPtr<PACKED> src_ptr(const GatherSources& g, const DigitRanges& dg, uint32_t ndig, uint32_t E, uint32_t N,
-                                                  uint32_t b, uint32_t j, uint32_t pos) {
-    const uint64_t e = (((uint64_t)b * ndig + j) * E + pos) * N;
-    const bool own = !PACKED && pos >= dg.lo[j] && pos < dg.hi[j];  // uniform
-    SrcPtr<PACKED> p;
-    p.lo = own ? g.own + (uint64_t)b * g.own_ps + (uint64_t)pos * N : g.lo + e;
-    p.hi = PACKED ? g.hi + e : nullptr;
-    return p;
+__device__ __forceinline__ SrcBases src_bases(const GatherSources& g, uint32_t ndig, uint32_t E, uint32_t N, uint32_t b_lo) {
+    const uint64_t e = (uint64_t)b_lo * ndig * E * N;
+    return SrcBases{reinterpret_cast<const char*>(g.lo + e), PACKED ? g.hi + e : nullptr};
+}
+// Offset of the sources of (ciphertext b of the group starting at b_lo, digit j) at limb position pos.
+__device__ __forceinline__ uint32_t src_offset(uint32_t ndig, uint32_t E, uint32_t N, uint32_t b_lo, uint32_t b, uint32_t j,
+                                               uint32_t pos) {
+    return (((b - b_lo) * ndig + j) * E + pos) * N;
 }
 
 // Inner products through the sigma_g gather for a group of hoisted rotations: acc[r][b][c][pos] = sum_j sigma_{g_r}(src_j)[pos]
@@ -55,7 +60,7 @@ __device__ __forceinline__ SrcPtr<PACKED> src_ptr(const GatherSources& g, const 
 // ciphertext limbs to (accq_lo, accq_hi) as [r][b][2][ell][N] packed residues: they are only read back by the last
 // kernel of the rotation, and written and read once per rotation they are a fifth of these two kernels' traffic.
 template <int NDIG, typename WK, bool PACKED>
-__global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restrict__ mods, DigitRanges dg, uint32_t ell, uint32_t E,
+__global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restrict__ mods, uint32_t ell, uint32_t E,
                                                             uint32_t L, uint32_t M, uint32_t logN, GatherSources src, MacRotations rot,
                                                             uint64_t* __restrict__ acc, uint32_t* __restrict__ accq_lo,
                                                             uint8_t* __restrict__ accq_hi, uint32_t batch) {
@@ -65,12 +70,13 @@ __global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restric
     const Mod m = mods[mid];
     const uint32_t n = blockIdx.x * 256 + threadIdx.x;
     const uint32_t b_lo = blockIdx.z * kBatchGroup;
-    SrcPtr<PACKED> srcp[kBatchGroup][NDIG];
+    const SrcBases bases = src_bases<PACKED>(src, NDIG, E, N, b_lo);
+    uint32_t srce[kBatchGroup][NDIG];
 #pragma unroll
     for (int bi = 0; bi < kBatchGroup; ++bi) {
         const uint32_t b = min(b_lo + bi, batch - 1);
 #pragma unroll
-        for (int j = 0; j < NDIG; ++j) srcp[bi][j] = src_ptr<PACKED>(src, dg, NDIG, E, N, b, j, pos);
+        for (int j = 0; j < NDIG; ++j) srce[bi][j] = src_offset(NDIG, E, N, b_lo, b, j, pos);
     }
 #pragma unroll 1
     for (uint32_t r = 0; r < rot.n; ++r) {
@@ -86,7 +92,7 @@ __global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restric
 #pragma unroll
         for (int bi = 0; bi < kBatchGroup; ++bi)
 #pragma unroll
-            for (int j = 0; j < NDIG; ++j) xraw[bi][j] = src_load<PACKED>(srcp[bi][j], sn);
+            for (int j = 0; j < NDIG; ++j) xraw[bi][j] = src_load<PACKED>(bases, srce[bi][j], sn);
         uint64_t* ar = acc + (uint64_t)r * batch * 2 * E * N;
         const uint64_t rq = (uint64_t)r * batch * 2 * ell * N;
 #pragma unroll
@@ -114,23 +120,12 @@ __global__ __launch_bounds__(256) void inner_product_kernel(const Mod* __restric
     }
 }
 
-static DigitRanges digit_ranges(const Level& lv) {
-    DigitRanges dg;
-    dg.ndig = lv.ndig;
-    for (uint32_t j = 0; j < kMaxDigits; ++j) {
-        dg.lo[j] = j < lv.ndig ? lv.digit_lo[j] : 0;
-        dg.hi[j] = j < lv.ndig ? lv.digit_hi[j] : 0;
-    }
-    return dg;
-}
-
 // bytes a gathered source residue takes
 static double src_bytes(const GatherSources& g) { return g.hi ? 5.0 : 4.0; }
 
 void launch_inner_product(const ks_ctx* c, const Level& lv, const GatherSources& src, const MacRotations& rot, uint64_t* acc,
                           const PackedDigits& accq, uint32_t batch, hipStream_t s, bool key_words32) {
     if (batch == 0 || rot.n == 0) return;
-    const DigitRanges dg = digit_ranges(lv);
     const uint32_t groups = (batch + kBatchGroup - 1) / kBatchGroup;
     const dim3 grid(c->N / 256, lv.E, groups), block(256);
     // reads: every raised digit limb per ciphertext once per launch, each rotation's key once per group; writes: both
@@ -140,7 +135,7 @@ void launch_inner_product(const ks_ctx* c, const Level& lv, const GatherSources&
                  (src_bytes(src) * batch * lv.ndig * lv.E + (double)rot.n * (wk * 2.0 * lv.ndig * lv.E * groups + (16.0 * (lv.E - lv.ell) + 10.0 * lv.ell) * batch)) * c->N,
                  s);
 #define KS_LAUNCH_IP_W(ND, WKT, PK)                                                                                                \
-    hipLaunchKernelGGL((inner_product_kernel<ND, WKT, PK>), grid, block, 0, s, c->d_mod, dg, lv.ell, lv.E, c->L, c->M, c->logN, src, \
+    hipLaunchKernelGGL((inner_product_kernel<ND, WKT, PK>), grid, block, 0, s, c->d_mod, lv.ell, lv.E, c->L, c->M, c->logN, src, \
                        rot, acc, accq.lo, accq.hi, batch)
 #define KS_LAUNCH_IP(ND)                                                \
     if (!src.hi) KS_LAUNCH_IP_W(ND, uint32_t, false);                   \
@@ -169,7 +164,7 @@ void launch_inner_product(const ks_ctx* c, const Level& lv, const GatherSources&
 // first product.  Galois element 1 is the unrotated ciphertext (P (c0, c1), no key read).
 // WC: word type of the ciphertext ct (64-bit with packed sources, 32-bit with 32-bit sources).
 template <int NDIG, typename WK, bool PACKED>
-__global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__ mods, const double* __restrict__ Pmod, DigitRanges dg,
+__global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__ mods, const double* __restrict__ Pmod,
                                                          uint32_t ell, uint32_t E, uint32_t L, uint32_t M, uint32_t logN,
                                                          const void* __restrict__ ct_, uint64_t ct_bs, GatherSources src,
                                                          MacRotations rot, const uint64_t* __restrict__ one,
@@ -184,16 +179,17 @@ __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__
     const double pm = pos < ell ? Pmod[c0_limb] : 0.0;
     const uint32_t n = blockIdx.x * 256 + threadIdx.x;
     const uint32_t b_lo = blockIdx.z * kBatchGroup;
+    const SrcBases bases = src_bases<PACKED>(src, NDIG, E, N, b_lo);
     // per ciphertext of the group: where its c0 limb and its NDIG source limbs of this position start
     const WC* c0p[kBatchGroup];
-    SrcPtr<PACKED> srcp[kBatchGroup][NDIG];
+    uint32_t srce[kBatchGroup][NDIG];
     uint64_t* up[kBatchGroup];
 #pragma unroll
     for (int bi = 0; bi < kBatchGroup; ++bi) {
         const uint32_t b = min(b_lo + bi, batch - 1);
         c0p[bi] = ct + (uint64_t)b * ct_bs + (uint64_t)c0_limb * N;
 #pragma unroll
-        for (int j = 0; j < NDIG; ++j) srcp[bi][j] = src_ptr<PACKED>(src, dg, NDIG, E, N, b, j, pos);
+        for (int j = 0; j < NDIG; ++j) srce[bi][j] = src_offset(NDIG, E, N, b_lo, b, j, pos);
         up[bi] = u + (((uint64_t)b * 2) * E + pos) * N + n;
     }
     double u0[kBatchGroup], u1[kBatchGroup];
@@ -238,7 +234,7 @@ __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__
 #pragma unroll
         for (int bi = 0; bi < kBatchGroup; ++bi) {
 #pragma unroll
-            for (int j = 0; j < NDIG; ++j) xraw[bi][j] = src_load<PACKED>(srcp[bi][j], sn);
+            for (int j = 0; j < NDIG; ++j) xraw[bi][j] = src_load<PACKED>(bases, srce[bi][j], sn);
             craw[bi] = c0p[bi][sn];
         }
         // the plaintext slot is folded into the key slots and into P once per rotation, not multiplied per ciphertext
@@ -273,18 +269,17 @@ __global__ __launch_bounds__(256) void rotate_mac_kernel(const Mod* __restrict__
 void launch_rotate_mac(const ks_ctx* c, const Level& lv, const void* ct, uint64_t ct_bs, const GatherSources& src,
                        const MacRotations& rot, uint64_t* u, uint32_t batch, bool accumulate, hipStream_t s, bool key_words32) {
     if (batch == 0 || rot.n == 0) return;
-    const DigitRanges dg = digit_ranges(lv);
     const uint32_t groups = (batch + kBatchGroup - 1) / kBatchGroup;
     const dim3 grid(c->N / 256, lv.E, groups), block(256);
     // Algorithmic traffic: the raised digits and c0 of a ciphertext once (the rotations of a launch re-read them through
     // the gather; those re-reads are meant to come from cache), key and plaintext of every rotation once per group, both
-    // sums written once.  Algorithmic work per slot, ciphertext and rotation: 2 NDIG + 3 modular products.
+    // sums written once.  Algorithmic work per slot, ciphertext and rotation: 2 NDIG + 1 modular products (+ 2 NDIG + 1 per group).
     const double reads = batch * (src_bytes(src) * lv.ndig * lv.E + (src.hi ? 8.0 : 4.0) * lv.ell) +
                          (key_words32 ? 4.0 : 8.0) * (double)rot.n * groups * (2.0 * lv.ndig + 1.0) * lv.E;
     ProfScope ps("rotate_mac", (reads + (double)batch * 16 * lv.E * (accumulate ? 2 : 1)) * c->N, s,
-                 (double)rot.n * batch * lv.E * c->N * (7.0 * (2 * lv.ndig + 3)));
+                 (double)rot.n * batch * lv.E * c->N * (7.0 * (2 * lv.ndig + 1)));
 #define KS_LAUNCH_MAC_W(ND, WKT, PK)                                                                                                  \
-    hipLaunchKernelGGL((rotate_mac_kernel<ND, WKT, PK>), grid, block, 0, s, c->d_mod, c->d_Pmod, dg, lv.ell, lv.E, c->L, c->M, c->logN, \
+    hipLaunchKernelGGL((rotate_mac_kernel<ND, WKT, PK>), grid, block, 0, s, c->d_mod, c->d_Pmod, lv.ell, lv.E, c->L, c->M, c->logN, \
                        ct, ct_bs, src, rot, c->d_one, u, batch, accumulate ? 1 : 0)
 #define KS_LAUNCH_MAC(ND)                                               \
     if (!src.hi) KS_LAUNCH_MAC_W(ND, uint32_t, false);                  \
@@ -302,28 +297,6 @@ void launch_rotate_mac(const ks_ctx* c, const Level& lv, const void* ct, uint64_
     }
 #undef KS_LAUNCH_MAC
 #undef KS_LAUNCH_MAC_W
-}
-
-// A polynomial's own limbs into the packed bundle of its raised digits (32-bit low words plus high bytes, see SrcPtr):
-// limb pos of polynomial b goes to slot (b, digit of pos, pos).
-__global__ __launch_bounds__(256) void pack_own_limbs_kernel(DigitRanges dg, uint32_t E, uint32_t N, const uint64_t* __restrict__ d,
-                                                             uint64_t d_ps, uint32_t* __restrict__ lo, uint8_t* __restrict__ hi) {
-    const uint32_t pos = blockIdx.y, b = blockIdx.z;
-    uint32_t j = 0;
-    while (j + 1 < dg.ndig && pos >= dg.hi[j]) ++j;  // uniform
-    const uint32_t n = blockIdx.x * 256 + threadIdx.x;
-    const uint64_t u = d[(uint64_t)b * d_ps + (uint64_t)pos * N + n];
-    const uint64_t e = (((uint64_t)b * dg.ndig + j) * E + pos) * N + n;
-    lo[e] = (uint32_t)u;
-    hi[e] = (uint8_t)(u >> 32);
-}
-
-void launch_pack_own_limbs(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, const PackedDigits& out, uint32_t bc,
-                           hipStream_t s) {
-    if (bc == 0) return;
-    const DigitRanges dg = digit_ranges(lv);
-    ProfScope prof("pack_own_limbs", 13.0 * bc * lv.ell * c->N, s);
-    hipLaunchKernelGGL(pack_own_limbs_kernel, dim3(c->N / 256, lv.ell, bc), dim3(256), 0, s, dg, lv.E, c->N, d, d_ps, out.lo, out.hi);
 }
 
 // (b1, a1) x (b2, a2) -> d0 = b1 b2, d1 = a1 b2 + a2 b1, d2 = a1 a2.  d2, the polynomial that is key-switched, goes out as

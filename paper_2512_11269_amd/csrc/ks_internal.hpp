@@ -178,9 +178,6 @@ void launch_ntt_u32(const ks_ctx* c, const LimbMap& map, uint32_t* data, uint64_
 // The two halves of each transform on their own (the fused pipeline replaces some halves by fused kernels).
 void launch_ntt_fwd_cols(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipStream_t s);
 void launch_ntt_fwd_rows(const ks_ctx* c, const LimbMap& map, uint64_t* data, uint64_t ps_words, uint32_t n_polys, hipStream_t s);
-// the same out of place, the canonical residues written as 64- or 32-bit words (strides in words)
-void launch_ntt_fwd_rows_to(const ks_ctx* c, const LimbMap& map, const uint64_t* in, uint64_t in_ps, void* out, uint64_t out_ps,
-                            uint32_t n_polys, hipStream_t s, bool out_words32);
 // in_words32: io.in holds 32-bit words (strides still count elements)
 void launch_ntt_inv_rows(const ks_ctx* c, const LimbMap& map, const XformIO& io, hipStream_t s, bool in_words32 = false);
 // scale_tab: multiplier applied with the final reduction, indexed by the limb's position in `map` (scale_by_idx)
@@ -251,24 +248,22 @@ struct MacRotations {
     const void* key[kMacRotations];  // [dnum][2][L+K][N], 64- or 32-bit words
     const void* pt[kMacRotations];   // [L+K][N], same word size as the keys
 };
-// What the sigma_g gathers of a rotation read.  hi != nullptr: packed bundle (lo, hi) holding every (digit, position)
-// slot, the digits' own limbs included.  hi == nullptr: lo holds the raised digits as 32-bit words and a digit's own
-// limbs come from the polynomial itself (own, 32-bit words, own_ps words between polynomials).
+// What the sigma_g gathers of a rotation read: the bundle [b][ndig][E][N] of the finished raised digits with, in the slots
+// of a digit's own positions, the limbs of the polynomial itself.  hi != nullptr: packed residues (lo, hi); hi == nullptr:
+// 32-bit words in lo (moduli below 2^32).
 struct GatherSources {
     const uint32_t* lo;
     const uint8_t* hi;
-    const uint32_t* own;
-    uint64_t own_ps;
 };
-// forward rows, out of place, into a packed bundle (ps: elements between polynomials, the same on both sides)
-void launch_ntt_fwd_rows_packed(const ks_ctx* c, const LimbMap& map, const uint64_t* in, uint64_t ps, const PackedDigits& out,
-                                uint32_t n_polys, hipStream_t s);
-// d[b][pos] (64-bit words, d_ps apart) into slot (b, digit of pos, pos) of a packed bundle
-void launch_pack_own_limbs(const ks_ctx* c, const Level& lv, const uint64_t* d, uint64_t d_ps, const PackedDigits& out, uint32_t bc,
-                           hipStream_t s);
+// Finish the bundle in one launch: the row half of the forward transform of the raised limbs (`lifted`, the bundle's
+// element layout, raw doubles after the column half) and a copy of the polynomials' own limbs d[b][pos] (64-bit words with
+// a packed bundle, 32-bit words with a 32-bit one; d_ps words apart) into the slots (b, digit of pos, pos).
+// out.hi == nullptr: a bundle of 32-bit words.
+void launch_gather_bundle_rows(const ks_ctx* c, const Level& lv, const uint64_t* lifted, const void* d, uint64_t d_ps, bool d_words32,
+                               const PackedDigits& out, uint32_t n_polys, hipStream_t s);
 
 // acc[r][b][c][pos] = sum_j sigma_{g_r}(src_j)[pos] * key_r[j][c][ext_id(pos)] for every rotation r of `rot` (pt unused);
-// src_j[pos] = d[b][pos] when pos lies in digit j, otherwise lifted[b][j][pos], both read through `src`.
+// src_j[pos] = d[b][pos] when pos lies in digit j, otherwise lifted[b][j][pos]: slot (b, j, pos) of the bundle `src`.
 // key_words32: keys (and plaintexts) hold one residue per 32-bit word; 32-bit sources imply 32-bit keys.
 // The special limbs of the result go to acc ([r][b][2][E][N], ciphertext limbs left untouched), the ciphertext limbs to
 // accq ([r][b][2][ell][N], packed).

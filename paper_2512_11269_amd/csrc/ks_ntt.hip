@@ -48,64 +48,92 @@ __global__ __launch_bounds__((TC << LOG_R) / 16) void ntt_fwd_cols(const double*
     for (int k = 0; k < 16; ++k) store_f64(L.out + col_row_grouped<LOG_R>(r0, k) * 256 + col, v[k]);
 }
 
-// forward, rows: raw doubles in, canonical residues out (64- or 32-bit words), in place or not.  One wavefront = four rows.
-template <int LOG_R, typename WO>
-__global__ __launch_bounds__(64) void ntt_fwd_rows(TwTables tw, const Mod* __restrict__ mods, LimbMap map,
-                                                   const uint64_t* in, WO* out, uint64_t in_ps, uint64_t out_ps) {
+// forward, rows, in place: raw doubles in, canonical residues out.  One wavefront = four rows.
+template <int LOG_R>
+__global__ __launch_bounds__(64) void ntt_fwd_rows(TwTables tw, const Mod* __restrict__ mods, LimbMap map, uint64_t* data, uint64_t ps) {
     constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R, GROUPS = R / 4;
     __shared__ double lds[4 * kRowPitch];
     const uint32_t tid = threadIdx.x;
     const uint32_t li = blockIdx.x / GROUPS, rg = blockIdx.x - li * GROUPS;
     const uint32_t poly = li / map.n, idx = li - poly * map.n, mod_id = map.mod[idx];
-    const uint64_t off = (uint64_t)map.off[idx] * N;
     const Mod m = mods[mod_id];
     const uint32_t j0 = tid & 15, rr = tid >> 4, row = rg * 4 + rr;
-    const uint64_t* ip = in + poly * in_ps + off + row * 256;
-    WO* op = out + poly * out_ps + off + row * 256;
+    uint64_t* p = data + poly * ps + (uint64_t)map.off[idx] * N + row * 256;
     double v[16];
     PassTwiddles t;
 #pragma unroll
-    for (int k = 0; k < 16; ++k) v[k] = load_f64(ip + j0 + 16 * k);
+    for (int k = 0; k < 16; ++k) v[k] = load_f64(p + j0 + 16 * k);
     load_row_twiddles(t, tw, mod_id, N, R + row, j0, m);
     row_fwd_core(v, t, j0, lds + rr * kRowPitch, m);
 #pragma unroll
-    for (int k = 0; k < 16; ++k) op[j0 + 16 * k] = f64_to_word<WO>(canon(reduce_lazy(v[k], m), m));
+    for (int k = 0; k < 16; ++k) p[j0 + 16 * k] = f64_to_u64(canon(reduce_lazy(v[k], m), m));
 }
 
-// forward, rows, out of place into the packed form the rotation gathers read: bits 0..31 of a canonical residue in a
-// 32-bit word array and the bits above (moduli are below 2^36) in a byte array with the same element index, 5 bytes a
-// residue instead of 8.  A thread ends with sixteen consecutive points and stores them as four 16-byte words plus one
-// 16-byte word of high bytes, so the row needs no last exchange through LDS.
-template <int LOG_R>
-__global__ __launch_bounds__(64) void ntt_fwd_rows_packed(TwTables tw, const Mod* __restrict__ mods, LimbMap map, const uint64_t* in,
-                                                          uint32_t* __restrict__ lo, uint8_t* __restrict__ hi, uint64_t ps) {
+// The bundle [b][ndig][E][N] the rotation gathers read, finished in one launch.  The first n_new_blocks workgroups run the
+// row half of the forward transform on the raised limbs (`lifted`, the same element layout, raw doubles after the column
+// half) and write canonical residues; the others copy the polynomial's own limbs d[b][pos] (WD words, d_ps apart) into
+// the slots (b, digit of pos, pos), so that every slot of the bundle is filled and a gather needs no own / raised
+// distinction.  PACKED: bits 0..31 of a residue go to the 32-bit word array lo and the bits above (moduli are below 2^36)
+// to the byte array hi with the same element index, 5 bytes a residue instead of 8; a transforming thread then ends with
+// sixteen consecutive points and stores them as four 16-byte words plus one 16-byte word of high bytes, so the row needs
+// no last exchange through LDS.  Otherwise (moduli below 2^32) lo alone holds 32-bit words.
+template <int LOG_R, bool PACKED, typename WD>
+__global__ __launch_bounds__(64) void gather_bundle_rows(TwTables tw, const Mod* __restrict__ mods, LimbMap map, DigitRanges dg,
+                                                         uint32_t ell, uint32_t E, const uint64_t* __restrict__ lifted,
+                                                         const WD* __restrict__ d, uint64_t d_ps, uint32_t n_new_blocks,
+                                                         uint32_t* __restrict__ lo, uint8_t* __restrict__ hi) {
     constexpr uint32_t N = 256u << LOG_R, R = 1u << LOG_R, GROUPS = R / 4;
     __shared__ double lds[4 * kRowPitch];
-    const uint32_t tid = threadIdx.x;
+    const uint32_t tid = threadIdx.x, j0 = tid & 15, rr = tid >> 4;
+    const uint64_t ps = (uint64_t)dg.ndig * E * N;
+    if (blockIdx.x >= n_new_blocks) {  // uniform: copy four rows of an own limb
+        const uint32_t t = blockIdx.x - n_new_blocks, li = t / GROUPS, row = (t - li * GROUPS) * 4 + rr;
+        const uint32_t poly = li / ell, pos = li - poly * ell;
+        uint32_t j = 0;
+        while (j + 1 < dg.ndig && pos >= dg.hi[j]) ++j;  // uniform
+        const WD* src = d + poly * d_ps + (uint64_t)pos * N + row * 256 + j0;
+        const uint64_t e = poly * ps + ((uint64_t)j * E + pos) * N + row * 256 + j0;
+        WD u[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) u[k] = src[16 * k];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            lo[e + 16 * k] = (uint32_t)u[k];
+            if constexpr (PACKED) hi[e + 16 * k] = (uint8_t)((uint64_t)u[k] >> 32);
+        }
+        return;
+    }
     const uint32_t li = blockIdx.x / GROUPS, rg = blockIdx.x - li * GROUPS;
     const uint32_t poly = li / map.n, idx = li - poly * map.n, mod_id = map.mod[idx];
     const uint64_t off = poly * ps + (uint64_t)map.off[idx] * N;
     const Mod m = mods[mod_id];
-    const uint32_t j0 = tid & 15, rr = tid >> 4, row = rg * 4 + rr;
-    const uint64_t* ip = in + off + row * 256;
+    const uint32_t row = rg * 4 + rr;
+    const uint64_t* ip = lifted + off + row * 256;
     double v[16];
     PassTwiddles t;
 #pragma unroll
     for (int k = 0; k < 16; ++k) v[k] = load_f64(ip + j0 + 16 * k);
     load_row_twiddles(t, tw, mod_id, N, R + row, j0, m);
-    row_fwd_core_consecutive(v, t, j0, lds + rr * kRowPitch, m);
-    uint32_t l[16], h[4] = {0, 0, 0, 0};
+    if constexpr (PACKED) {
+        row_fwd_core_consecutive(v, t, j0, lds + rr * kRowPitch, m);
+        uint32_t l[16], h[4] = {0, 0, 0, 0};
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
-        const uint64_t u = f64_to_u64(canon(reduce_lazy(v[k], m), m));
-        l[k] = (uint32_t)u;
-        h[k >> 2] |= (uint32_t)(u >> 32) << (8 * (k & 3));
+        for (int k = 0; k < 16; ++k) {
+            const uint64_t u = f64_to_u64(canon(reduce_lazy(v[k], m), m));
+            l[k] = (uint32_t)u;
+            h[k >> 2] |= (uint32_t)(u >> 32) << (8 * (k & 3));
+        }
+        const uint64_t e = off + row * 256 + 16 * j0;
+        uint4* lp = reinterpret_cast<uint4*>(lo + e);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) lp[q] = make_uint4(l[4 * q], l[4 * q + 1], l[4 * q + 2], l[4 * q + 3]);
+        *reinterpret_cast<uint4*>(hi + e) = make_uint4(h[0], h[1], h[2], h[3]);
+    } else {
+        row_fwd_core(v, t, j0, lds + rr * kRowPitch, m);
+        uint32_t* op = lo + off + row * 256 + j0;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) op[16 * k] = (uint32_t)canon(reduce_lazy(v[k], m), m);
     }
-    const uint64_t e = off + row * 256 + 16 * j0;
-    uint4* lp = reinterpret_cast<uint4*>(lo + e);
-#pragma unroll
-    for (int q = 0; q < 4; ++q) lp[q] = make_uint4(l[4 * q], l[4 * q + 1], l[4 * q + 2], l[4 * q + 3]);
-    *reinterpret_cast<uint4*>(hi + e) = make_uint4(h[0], h[1], h[2], h[3]);
 }
 
 // inverse, rows first: canonical residues in (64- or 32-bit words), raw doubles out (|x| <= 0.501 p).
@@ -234,36 +262,39 @@ void launch_ntt_fwd_cols(const ks_ctx* c, const LimbMap& map, const XformIO& io,
 #undef KS_LAUNCH
 }
 
-void launch_ntt_fwd_rows_to(const ks_ctx* c, const LimbMap& map, const uint64_t* in, uint64_t in_ps, void* out, uint64_t out_ps,
-                            uint32_t n_polys, hipStream_t s, bool out_words32) {
-    const uint32_t limbs = map.n * n_polys;
-    if (limbs == 0) return;
-    ProfScope ps("ntt_fwd_rows", (out_words32 ? 1.5 : 2.0) * limbs * c->N * 8.0, s);
-#define KS_LAUNCH(LOGR)                                                                                                              \
-    if (out_words32)                                                                                                                 \
-        hipLaunchKernelGGL((ntt_fwd_rows<LOGR, uint32_t>), dim3(limbs << (LOGR - 2)), dim3(64), 0, s, c->tw_fwd, c->d_mod, map, in,  \
-                           static_cast<uint32_t*>(out), in_ps, out_ps);                                                              \
-    else                                                                                                                             \
-        hipLaunchKernelGGL((ntt_fwd_rows<LOGR, uint64_t>), dim3(limbs << (LOGR - 2)), dim3(64), 0, s, c->tw_fwd, c->d_mod, map, in,  \
-                           static_cast<uint64_t*>(out), in_ps, out_ps)
-    KS_FOR_LOG_R(c->logN, KS_LAUNCH)
-#undef KS_LAUNCH
-}
-
-void launch_ntt_fwd_rows_packed(const ks_ctx* c, const LimbMap& map, const uint64_t* in, uint64_t ps, const PackedDigits& out,
-                                uint32_t n_polys, hipStream_t s) {
-    const uint32_t limbs = map.n * n_polys;
-    if (limbs == 0) return;
-    ProfScope prof("ntt_fwd_rows", 13.0 * limbs * c->N, s);
-#define KS_LAUNCH(LOGR)                                                                                                         \
-    hipLaunchKernelGGL((ntt_fwd_rows_packed<LOGR>), dim3(limbs << (LOGR - 2)), dim3(64), 0, s, c->tw_fwd, c->d_mod, map, in, out.lo, \
-                       out.hi, ps)
-    KS_FOR_LOG_R(c->logN, KS_LAUNCH)
-#undef KS_LAUNCH
-}
-
 void launch_ntt_fwd_rows(const ks_ctx* c, const LimbMap& map, uint64_t* data, uint64_t ps_words, uint32_t n_polys, hipStream_t s) {
-    launch_ntt_fwd_rows_to(c, map, data, ps_words, data, ps_words, n_polys, s, false);
+    const uint32_t limbs = map.n * n_polys;
+    if (limbs == 0) return;
+    ProfScope ps("ntt_fwd_rows", 2.0 * limbs * c->N * 8.0, s);
+#define KS_LAUNCH(LOGR) \
+    hipLaunchKernelGGL((ntt_fwd_rows<LOGR>), dim3(limbs << (LOGR - 2)), dim3(64), 0, s, c->tw_fwd, c->d_mod, map, data, ps_words)
+    KS_FOR_LOG_R(c->logN, KS_LAUNCH)
+#undef KS_LAUNCH
+}
+
+void launch_gather_bundle_rows(const ks_ctx* c, const Level& lv, const uint64_t* lifted, const void* d, uint64_t d_ps, bool d_words32,
+                               const PackedDigits& out, uint32_t n_polys, hipStream_t s) {
+    if (n_polys == 0) return;
+    const uint32_t n_new = lv.lifted_map.n * n_polys, n_own = lv.ell * n_polys;
+    DigitRanges dg;
+    dg.ndig = lv.ndig;
+    for (uint32_t j = 0; j < kMaxDigits; ++j) {
+        dg.lo[j] = j < lv.ndig ? lv.digit_lo[j] : 0;
+        dg.hi[j] = j < lv.ndig ? lv.digit_hi[j] : 0;
+    }
+    const double wb = out.hi ? 5.0 : 4.0;
+    ProfScope ps("gather_bundle_rows", ((8.0 + wb) * n_new + ((d_words32 ? 4.0 : 8.0) + wb) * n_own) * c->N, s);
+#define KS_LAUNCH(LOGR)                                                                                                              \
+    if (out.hi)                                                                                                                      \
+        hipLaunchKernelGGL((gather_bundle_rows<LOGR, true, uint64_t>), dim3((n_new + n_own) << (LOGR - 2)), dim3(64), 0, s, c->tw_fwd, \
+                           c->d_mod, lv.lifted_map, dg, lv.ell, lv.E, lifted, static_cast<const uint64_t*>(d), d_ps,                 \
+                           n_new << (LOGR - 2), out.lo, out.hi);                                                                     \
+    else                                                                                                                             \
+        hipLaunchKernelGGL((gather_bundle_rows<LOGR, false, uint32_t>), dim3((n_new + n_own) << (LOGR - 2)), dim3(64), 0, s, c->tw_fwd, \
+                           c->d_mod, lv.lifted_map, dg, lv.ell, lv.E, lifted, static_cast<const uint32_t*>(d), d_ps,                 \
+                           n_new << (LOGR - 2), out.lo, out.hi)
+    KS_FOR_LOG_R(c->logN, KS_LAUNCH)
+#undef KS_LAUNCH
 }
 
 // Polynomials per launch pair of a two-pass transform: the second pass of a group should find what the first pass wrote
